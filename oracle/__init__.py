@@ -1,0 +1,223 @@
+"""ctypes front end of the CPU oracle (kb_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: tests, the smoke check and the benchmark's CPU
+baseline leg load this; the product path never does.  Nothing here imports the
+GPU package, and the GPU package imports nothing from here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from types import SimpleNamespace
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "kb_oracle.c")
+_LIB = os.path.join(_HERE, "libkb_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile kb_oracle.c with gcc (no fast-math, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-ffp-contract=off", "-fopenmp", "-shared",
+               "-fPIC", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.kbo_max_threads.restype = ctypes.c_int32
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def max_threads() -> int:
+    return int(_load().kbo_max_threads())
+
+
+def prune(seg_off, flops, bytes_, peak_flops, peak_bw, incumbent):
+    lib = _load()
+    seg_off = _c(seg_off, np.int32)
+    G = len(seg_off) - 1
+    N = int(seg_off[-1])
+    flops = _c(flops, np.float32)
+    bytes_ = _c(bytes_, np.float32)
+    incumbent = _c(incumbent, np.float32)
+    bound = np.empty(N, dtype=np.float32)
+    alive = np.empty(N, dtype=np.uint8)
+    lib.kbo_prune(ctypes.c_int32(G), _p(seg_off), _p(flops), _p(bytes_),
+                  ctypes.c_float(peak_flops), ctypes.c_float(peak_bw),
+                  _p(incumbent), _p(bound), _p(alive))
+    return bound, alive
+
+
+def assign(seg_off, koff, X, cent):
+    lib = _load()
+    seg_off = _c(seg_off, np.int32)
+    koff = _c(koff, np.int32)
+    X = _c(X, np.float32)
+    cent = _c(cent, np.float32)
+    G = len(seg_off) - 1
+    N, D = X.shape
+    a = np.empty(N, dtype=np.int32)
+    mind2 = np.empty(N, dtype=np.float64)
+    flag = np.empty(N, dtype=np.uint8)
+    lib.kbo_assign(ctypes.c_int32(G), ctypes.c_int32(D), _p(seg_off), _p(koff),
+                   _p(X), _p(cent), _p(a), _p(mind2), _p(flag))
+    return a, mind2, flag
+
+
+def update(seg_off, koff, X, cent_in, assign_):
+    lib = _load()
+    seg_off = _c(seg_off, np.int32)
+    koff = _c(koff, np.int32)
+    X = _c(X, np.float32)
+    cent_in = _c(cent_in, np.float32)
+    assign_ = _c(assign_, np.int32)
+    G = len(seg_off) - 1
+    N, D = X.shape
+    Ksum = int(koff[-1])
+    cent_out = np.empty((Ksum, D), dtype=np.float32)
+    counts = np.empty(Ksum, dtype=np.int32)
+    lib.kbo_update(ctypes.c_int32(G), ctypes.c_int32(D), _p(seg_off), _p(koff),
+                   _p(X), _p(cent_in), _p(assign_), _p(cent_out), _p(counts))
+    return cent_out, counts
+
+
+def objective(seg_off, mind2):
+    lib = _load()
+    seg_off = _c(seg_off, np.int32)
+    mind2 = _c(mind2, np.float64)
+    G = len(seg_off) - 1
+    J = np.empty(G, dtype=np.float64)
+    lib.kbo_objective(ctypes.c_int32(G), _p(seg_off), _p(mind2), _p(J))
+    return J
+
+
+def cluster_step(seg_off, koff, X, cent_in):
+    """One Lloyd step.  Returns a namespace with assign, cent, counts,
+    objective (fp64), flag (near-tie per candidate) and mind2."""
+    lib = _load()
+    seg_off = _c(seg_off, np.int32)
+    koff = _c(koff, np.int32)
+    X = _c(X, np.float32)
+    cent_in = _c(cent_in, np.float32)
+    G = len(seg_off) - 1
+    N, D = X.shape
+    Ksum = int(koff[-1])
+    a = np.empty(N, dtype=np.int32)
+    cent_out = np.empty((Ksum, D), dtype=np.float32)
+    counts = np.empty(Ksum, dtype=np.int32)
+    J = np.empty(G, dtype=np.float64)
+    mind2 = np.empty(N, dtype=np.float64)
+    flag = np.empty(N, dtype=np.uint8)
+    lib.kbo_cluster_step(ctypes.c_int32(G), ctypes.c_int32(D), _p(seg_off),
+                         _p(koff), _p(X), _p(cent_in), _p(a), _p(cent_out),
+                         _p(counts), _p(J), _p(mind2), _p(flag))
+    return SimpleNamespace(assign=a, cent=cent_out, counts=counts, objective=J,
+                           flag=flag, mind2=mind2)
+
+
+def cluster(seg_off, koff, X, iters, cent_init=None):
+    """iters Lloyd steps from cent_init (default: first K_g rows)."""
+    lib = _load()
+    seg_off = _c(seg_off, np.int32)
+    koff = _c(koff, np.int32)
+    X = _c(X, np.float32)
+    if cent_init is not None:
+        cent_init = _c(cent_init, np.float32)
+    G = len(seg_off) - 1
+    N, D = X.shape
+    Ksum = int(koff[-1])
+    a = np.full(N, -1, dtype=np.int32)
+    cent = np.empty((Ksum, D), dtype=np.float32)
+    counts = np.full(Ksum, -1, dtype=np.int32)
+    J = np.full(G, np.nan, dtype=np.float64)
+    dirty = np.zeros(G, dtype=np.uint8)
+    lib.kbo_cluster(ctypes.c_int32(G), ctypes.c_int32(D), _p(seg_off), _p(koff),
+                    _p(X), _p(cent_init), ctypes.c_int32(iters), _p(a), _p(cent),
+                    _p(counts), _p(J), _p(dirty))
+    return SimpleNamespace(assign=a, cent=cent, counts=counts, objective=J,
+                           dirty=dirty)
+
+
+def ucb_select(seg_off, koff, S, assign_, alive, bound, visits, rsum, t, c,
+               prior_n=0.0, prior_mu=0.5):
+    lib = _load()
+    seg_off = _c(seg_off, np.int32)
+    koff = _c(koff, np.int32)
+    assign_ = _c(assign_, np.int32)
+    alive = _c(alive, np.uint8)
+    bound = _c(bound, np.float32)
+    visits = _c(visits, np.int32)
+    rsum = _c(rsum, np.float32)
+    t = _c(t, np.int64)
+    G = len(seg_off) - 1
+    Ksum = int(koff[-1])
+    Ncs = np.empty((Ksum, S), dtype=np.int64)
+    mu = np.empty((Ksum, S), dtype=np.float64)
+    ucb = np.empty((Ksum, S), dtype=np.float64)
+    sel = np.empty((G, 3), dtype=np.int32)
+    near = np.empty(G, dtype=np.uint8)
+    lib.kbo_ucb_select(ctypes.c_int32(G), ctypes.c_int32(S), _p(seg_off), _p(koff),
+                       _p(assign_), _p(alive), _p(bound), _p(visits), _p(rsum),
+                       _p(t), ctypes.c_double(c), ctypes.c_double(prior_n),
+                       ctypes.c_double(prior_mu), _p(Ncs), _p(mu), _p(ucb),
+                       _p(sel), _p(near))
+    return SimpleNamespace(Ncs=Ncs, mu=mu, ucb=ucb, sel=sel, near=near)
+
+
+def round_(b, iters=None):
+    """Full round on a synth.Batch-like object (duck-typed: only attributes are
+    read)."""
+    lib = _load()
+    iters = b.iters if iters is None else iters
+    seg_off = _c(b.seg_off, np.int32)
+    koff = _c(b.koff, np.int32)
+    X = _c(b.X, np.float32)
+    G = len(seg_off) - 1
+    N, D = X.shape
+    S = int(b.S)
+    Ksum = int(koff[-1])
+    flops = _c(b.flops, np.float32)
+    bytes_ = _c(b.bytes_, np.float32)
+    inc = _c(b.incumbent, np.float32)
+    visits = _c(b.visits, np.int32)
+    rsum = _c(b.rsum, np.float32)
+    t = _c(b.t, np.int64)
+    out = SimpleNamespace(
+        bound=np.empty(N, dtype=np.float32), alive=np.empty(N, dtype=np.uint8),
+        assign=np.full(N, -1, dtype=np.int32),
+        cent=np.empty((Ksum, D), dtype=np.float32),
+        counts=np.full(Ksum, -1, dtype=np.int32),
+        objective=np.full(G, np.nan, dtype=np.float64),
+        Ncs=np.empty((Ksum, S), dtype=np.int64),
+        mu=np.empty((Ksum, S), dtype=np.float64),
+        ucb=np.empty((Ksum, S), dtype=np.float64),
+        sel=np.empty((G, 3), dtype=np.int32),
+        dirty=np.zeros(G, dtype=np.uint8), near=np.zeros(G, dtype=np.uint8))
+    lib.kbo_round(ctypes.c_int32(G), ctypes.c_int32(D), ctypes.c_int32(S),
+                  _p(seg_off), _p(koff), _p(X), _p(flops), _p(bytes_), _p(inc),
+                  _p(visits), _p(rsum), _p(t), ctypes.c_float(b.peak_flops),
+                  ctypes.c_float(b.peak_bw), ctypes.c_double(b.c),
+                  ctypes.c_double(b.prior_n), ctypes.c_double(b.prior_mu),
+                  ctypes.c_int32(iters), _p(out.bound), _p(out.alive),
+                  _p(out.assign), _p(out.cent), _p(out.counts), _p(out.objective),
+                  _p(out.Ncs), _p(out.mu), _p(out.ucb), _p(out.sel), _p(out.dirty),
+                  _p(out.near))
+    return out

@@ -1,0 +1,348 @@
+/*
+ * CPU oracle for the arm-scoring pass of a KernelBand search round.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition the GPU
+ * library is checked against.  It shares no code with the GPU path and the
+ * product never calls it; only tests, the smoke check and the benchmark's CPU
+ * baseline leg may load it.
+ *
+ * What it computes, with the passage of the paper each part follows:
+ *
+ *   kbo_prune        hardware-aware gain bound made concrete as a roofline
+ *                    lower-bound runtime per candidate, and the binary mask of
+ *                    arms that can still beat the incumbent
+ *                    (Assumption 1 / Eq. 2; mask Eq. 5 with strict '<').
+ *   kbo_assign,      one K-Means (Lloyd) step on the behavioural features phi(k)
+ *   kbo_update,      under the L2 norm of Assumption 2 / Eq. 3: nearest centroid,
+ *   kbo_cluster_step then centroid = mean of members (Sec. 3.3 "Periodic
+ *                    re-clustering"; Alg. 1 "KMeans" and "Update centroids").
+ *   kbo_cluster      a fixed number of such steps from the first K rows.
+ *   kbo_ucb_select   per-cluster visit counts N_{i,s} and mean rewards mu_{i,s},
+ *                    the masked UCB index mu + c sqrt(ln t / N) and its argmax
+ *                    over valid cluster arms (Eq. 6), then the member of the
+ *                    chosen cluster with the most headroom (Sec. 3.4, zero-
+ *                    temperature limit of the softmax over V_hw).
+ *   kbo_round        the three in sequence.
+ *
+ * Arithmetic: fp64 everywhere, straight loops in index order, no blocking, no
+ * reordering - except the roofline bound, which is computed in fp32 on purpose:
+ * the incumbent is one of the candidates' own bounds, so the equality case of
+ * the strict compare must round the same way on every implementation (IEEE
+ * single-precision division, round to nearest even).
+ *
+ * Build: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC (no fast-math).
+ * The only parallelism is an OpenMP loop over independent searches.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define KBO_NEAR_TIE_REL 1e-6
+#define KBO_TINY 1e-30
+
+/* ------------------------------------------------------------------ prune */
+
+/* bound[k] = max(flops[k]/peak_flops, bytes[k]/peak_bw) in seconds (fp32);
+ * alive[k] = bound[k] < incumbent[g(k)].  A pruned candidate therefore has
+ * bound >= incumbent: even at the hardware limit it cannot beat the best
+ * runtime already found.  bound may be NULL. */
+void kbo_prune(int32_t G, const int32_t *seg_off, const float *flops,
+               const float *bytes, float peak_flops, float peak_bw,
+               const float *incumbent, float *bound, uint8_t *alive)
+{
+    for (int32_t g = 0; g < G; ++g) {
+        const float inc = incumbent[g];
+        for (int32_t k = seg_off[g]; k < seg_off[g + 1]; ++k) {
+            volatile float t_compute = flops[k] / peak_flops;
+            volatile float t_memory = bytes[k] / peak_bw;
+            float b = t_compute > t_memory ? t_compute : t_memory;
+            if (bound) bound[k] = b;
+            alive[k] = (uint8_t)(b < inc);
+        }
+    }
+}
+
+/* ---------------------------------------------------------------- cluster */
+
+static double sqdist(const float *x, const float *c, int32_t D)
+{
+    double acc = 0.0;
+    for (int32_t d = 0; d < D; ++d) {
+        double diff = (double)x[d] - (double)c[d];
+        acc += diff * diff;
+    }
+    return acc;
+}
+
+/* Nearest centroid of every candidate under squared L2 distance in fp64.
+ * assign[k]  = lowest cluster index (local to the search) attaining the min;
+ * mind2[k]   = that minimal squared distance;
+ * flag[k]    = 1 if the runner-up is within 1e-6 (relative) of the winner, i.e.
+ *              d2nd - d1st <= 1e-6 * max(d2nd, 1e-30); a search with one
+ *              cluster never flags.  flag and mind2 may be NULL. */
+void kbo_assign(int32_t G, int32_t D, const int32_t *seg_off,
+                const int32_t *koff, const float *X, const float *cent,
+                int32_t *assign, double *mind2, uint8_t *flag)
+{
+#pragma omp parallel for schedule(dynamic, 1) if (G > 1)
+    for (int32_t g = 0; g < G; ++g) {
+        const int32_t K = koff[g + 1] - koff[g];
+        const float *cg = cent + (size_t)koff[g] * D;
+        for (int32_t k = seg_off[g]; k < seg_off[g + 1]; ++k) {
+            const float *x = X + (size_t)k * D;
+            double best = INFINITY, second = INFINITY;
+            int32_t arg = -1;
+            for (int32_t j = 0; j < K; ++j) {
+                double dj = sqdist(x, cg + (size_t)j * D, D);
+                if (dj < best) {
+                    second = best;
+                    best = dj;
+                    arg = j;
+                } else if (dj < second) {
+                    second = dj;
+                }
+            }
+            assign[k] = arg;
+            if (mind2) mind2[k] = best;
+            if (flag) {
+                uint8_t f = 0;
+                if (K > 1) {
+                    double scale = second > KBO_TINY ? second : KBO_TINY;
+                    f = (uint8_t)((second - best) <= KBO_NEAR_TIE_REL * scale);
+                }
+                flag[k] = f;
+            }
+        }
+    }
+}
+
+/* Centroid update for a given assignment: the mean of each cluster's members,
+ * summed in fp64 in candidate order and rounded once to fp32; an empty cluster
+ * keeps its previous centroid. */
+void kbo_update(int32_t G, int32_t D, const int32_t *seg_off,
+                const int32_t *koff, const float *X, const float *cent_in,
+                const int32_t *assign, float *cent_out, int32_t *counts)
+{
+#pragma omp parallel for schedule(dynamic, 1) if (G > 1)
+    for (int32_t g = 0; g < G; ++g) {
+        const int32_t K = koff[g + 1] - koff[g];
+        if (K <= 0) continue;
+        double *sum = (double *)calloc((size_t)K * D, sizeof(double));
+        int32_t *cnt = counts + koff[g];
+        for (int32_t j = 0; j < K; ++j) cnt[j] = 0;
+        for (int32_t k = seg_off[g]; k < seg_off[g + 1]; ++k) {
+            const int32_t j = assign[k];
+            const float *x = X + (size_t)k * D;
+            for (int32_t d = 0; d < D; ++d) sum[(size_t)j * D + d] += (double)x[d];
+            cnt[j] += 1;
+        }
+        for (int32_t j = 0; j < K; ++j) {
+            const size_t row = ((size_t)koff[g] + j) * D;
+            for (int32_t d = 0; d < D; ++d) {
+                if (cnt[j] > 0)
+                    cent_out[row + d] = (float)(sum[(size_t)j * D + d] / (double)cnt[j]);
+                else
+                    cent_out[row + d] = cent_in[row + d];
+            }
+        }
+        free(sum);
+    }
+}
+
+/* J_g = sum over the search's candidates of their minimal squared distance. */
+void kbo_objective(int32_t G, const int32_t *seg_off, const double *mind2,
+                   double *objective)
+{
+    for (int32_t g = 0; g < G; ++g) {
+        double J = 0.0;
+        for (int32_t k = seg_off[g]; k < seg_off[g + 1]; ++k) J += mind2[k];
+        objective[g] = J;
+    }
+}
+
+/* One Lloyd step from cent_in: assign, objective, update.  mind2 is scratch of
+ * N doubles supplied by the caller; flag may be NULL. */
+void kbo_cluster_step(int32_t G, int32_t D, const int32_t *seg_off,
+                      const int32_t *koff, const float *X, const float *cent_in,
+                      int32_t *assign, float *cent_out, int32_t *counts,
+                      double *objective, double *mind2, uint8_t *flag)
+{
+    kbo_assign(G, D, seg_off, koff, X, cent_in, assign, mind2, flag);
+    kbo_objective(G, seg_off, mind2, objective);
+    kbo_update(G, D, seg_off, koff, X, cent_in, assign, cent_out, counts);
+}
+
+/* iters Lloyd steps.  Initial centroids: cent_init if given, else the first K_g
+ * rows of each search.  Outputs are those of the last step (assign, counts and
+ * objective refer to the centroids entering it; cent is its updated centroids).
+ * iters == 0 only writes cent = initial centroids.  dirty[g] (may be NULL) is
+ * set when any candidate of the search was a flagged near-tie in any step. */
+void kbo_cluster(int32_t G, int32_t D, const int32_t *seg_off,
+                 const int32_t *koff, const float *X, const float *cent_init,
+                 int32_t iters, int32_t *assign, float *cent, int32_t *counts,
+                 double *objective, uint8_t *dirty)
+{
+    const int64_t N = seg_off[G];
+    const int64_t Ksum = koff[G];
+    float *cur = (float *)malloc(sizeof(float) * (size_t)(Ksum > 0 ? Ksum : 1) * D);
+    double *mind2 = (double *)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+    uint8_t *flag = (uint8_t *)malloc((size_t)(N > 0 ? N : 1));
+    for (int32_t g = 0; g < G; ++g) {
+        const int32_t K = koff[g + 1] - koff[g];
+        for (int32_t j = 0; j < K; ++j) {
+            const float *src = cent_init
+                ? cent_init + ((size_t)koff[g] + j) * D
+                : X + ((size_t)seg_off[g] + j) * D;
+            memcpy(cur + ((size_t)koff[g] + j) * D, src, sizeof(float) * D);
+        }
+        if (dirty) dirty[g] = 0;
+    }
+    for (int32_t it = 0; it < iters; ++it) {
+        kbo_cluster_step(G, D, seg_off, koff, X, cur, assign, cent, counts,
+                         objective, mind2, flag);
+        memcpy(cur, cent, sizeof(float) * (size_t)Ksum * D);
+        if (dirty)
+            for (int32_t g = 0; g < G; ++g)
+                for (int32_t k = seg_off[g]; k < seg_off[g + 1]; ++k)
+                    if (flag[k]) dirty[g] = 1;
+    }
+    if (iters == 0) memcpy(cent, cur, sizeof(float) * (size_t)Ksum * D);
+    free(cur);
+    free(mind2);
+    free(flag);
+}
+
+/* -------------------------------------------------------------------- UCB */
+
+/* Cluster-arm statistics, masked UCB index and arm selection for every search.
+ *
+ *   Ncs[i,s] = sum of visits[k,s] over alive members k of cluster i
+ *   R[i,s]   = sum of rsum[k,s] over the same members
+ *   Ntilde   = Ncs + prior_n ; Rtilde = R + prior_n*prior_mu ; mu = Rtilde/Ntilde
+ *   a cluster is valid iff it has an alive member
+ *   ucb = mu + c*sqrt(ln t_g / Ntilde)  (valid, Ntilde > 0)
+ *       = +inf                          (valid, Ntilde == 0: untried arm first)
+ *       = -inf                          (not valid: masked)
+ *   (I, S*) = lowest flat index i*S+s attaining the max over valid arms
+ *   k*      = alive member of cluster I with the smallest bound, lowest k on ties
+ *   sel[g]  = (I, S*, k*) with k* a global candidate index, or (-1,-1,-1).
+ *
+ * near[g] (may be NULL) = 1 if the best score is finite and the largest score
+ * that is not equal to it is finite and within 1e-6*max(|best|,1e-30) of it.
+ * mu is written as NaN where Ntilde == 0.
+ */
+void kbo_ucb_select(int32_t G, int32_t S, const int32_t *seg_off,
+                    const int32_t *koff, const int32_t *assign,
+                    const uint8_t *alive, const float *bound,
+                    const int32_t *visits, const float *rsum, const int64_t *t,
+                    double c, double prior_n, double prior_mu, int64_t *Ncs,
+                    double *mu, double *ucb, int32_t *sel, uint8_t *near)
+{
+#pragma omp parallel for schedule(dynamic, 1) if (G > 1)
+    for (int32_t g = 0; g < G; ++g) {
+        const int32_t K = koff[g + 1] - koff[g];
+        const size_t base = (size_t)koff[g] * S;
+        int32_t *nalive = (int32_t *)calloc((size_t)(K > 0 ? K : 1), sizeof(int32_t));
+        double *R = (double *)calloc((size_t)(K > 0 ? K : 1) * S, sizeof(double));
+        for (size_t a = 0; a < (size_t)K * S; ++a) Ncs[base + a] = 0;
+        for (int32_t k = seg_off[g]; k < seg_off[g + 1]; ++k) {
+            if (!alive[k]) continue;
+            const int32_t i = assign[k];
+            nalive[i] += 1;
+            for (int32_t s = 0; s < S; ++s) {
+                Ncs[base + (size_t)i * S + s] += (int64_t)visits[(size_t)k * S + s];
+                R[(size_t)i * S + s] += (double)rsum[(size_t)k * S + s];
+            }
+        }
+        const double lnt = log((double)t[g]);
+        double best = -INFINITY;
+        int32_t best_flat = -1;
+        for (int32_t i = 0; i < K; ++i) {
+            for (int32_t s = 0; s < S; ++s) {
+                const size_t a = (size_t)i * S + s;
+                const double nt = (double)Ncs[base + a] + prior_n;
+                const double rt = R[a] + prior_n * prior_mu;
+                double m = nt > 0.0 ? rt / nt : NAN;
+                double u;
+                if (nalive[i] == 0) u = -INFINITY;
+                else if (nt > 0.0) u = m + c * sqrt(lnt / nt);
+                else u = INFINITY;
+                mu[base + a] = m;
+                ucb[base + a] = u;
+                if (nalive[i] > 0 && (best_flat < 0 || u > best)) {
+                    best = u;
+                    best_flat = (int32_t)a;
+                }
+            }
+        }
+        int32_t I = -1, Sstar = -1, kstar = -1;
+        if (best_flat >= 0) {
+            I = best_flat / S;
+            Sstar = best_flat % S;
+            float bmin = 0.0f;
+            for (int32_t k = seg_off[g]; k < seg_off[g + 1]; ++k) {
+                if (!alive[k] || assign[k] != I) continue;
+                if (kstar < 0 || bound[k] < bmin) {
+                    bmin = bound[k];
+                    kstar = k;
+                }
+            }
+        }
+        sel[3 * (size_t)g + 0] = I;
+        sel[3 * (size_t)g + 1] = Sstar;
+        sel[3 * (size_t)g + 2] = kstar;
+        if (near) {
+            uint8_t f = 0;
+            if (best_flat >= 0 && isfinite(best)) {
+                double runner = -INFINITY;
+                for (int32_t i = 0; i < K; ++i) {
+                    if (nalive[i] == 0) continue;
+                    for (int32_t s = 0; s < S; ++s) {
+                        double u = ucb[base + (size_t)i * S + s];
+                        if (u != best && u > runner) runner = u;
+                    }
+                }
+                if (isfinite(runner)) {
+                    double scale = fabs(best) > KBO_TINY ? fabs(best) : KBO_TINY;
+                    f = (uint8_t)((best - runner) <= KBO_NEAR_TIE_REL * scale);
+                }
+            }
+            near[g] = f;
+        }
+        free(nalive);
+        free(R);
+    }
+}
+
+/* ------------------------------------------------------------------ round */
+
+/* One scoring round: prune every candidate, cluster ALL candidates (pruned ones
+ * included - the frontier is clustered first and masked afterwards, Alg. 1),
+ * then statistics, UCB and selection over the alive members. */
+void kbo_round(int32_t G, int32_t D, int32_t S, const int32_t *seg_off,
+               const int32_t *koff, const float *X, const float *flops,
+               const float *bytes, const float *incumbent,
+               const int32_t *visits, const float *rsum, const int64_t *t,
+               float peak_flops, float peak_bw, double c, double prior_n,
+               double prior_mu, int32_t iters, float *bound, uint8_t *alive,
+               int32_t *assign, float *cent, int32_t *counts, double *objective,
+               int64_t *Ncs, double *mu, double *ucb, int32_t *sel,
+               uint8_t *dirty, uint8_t *near)
+{
+    kbo_prune(G, seg_off, flops, bytes, peak_flops, peak_bw, incumbent, bound, alive);
+    kbo_cluster(G, D, seg_off, koff, X, NULL, iters, assign, cent, counts,
+                objective, dirty);
+    kbo_ucb_select(G, S, seg_off, koff, assign, alive, bound, visits, rsum, t, c,
+                   prior_n, prior_mu, Ncs, mu, ucb, sel, near);
+}
+
+int32_t kbo_max_threads(void)
+{
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return (int32_t)omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
