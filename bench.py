@@ -1,0 +1,143 @@
+"""Benchmark of the arm-scoring round (prune -> cluster -> UCB select).
+
+A step is one kb_round over one batch of synthetic traces, inputs resident in
+HBM.  Prints ONE JSON line: whole-job candidate traces scored per second, the
+roofline of the dominant kernel (the fused Lloyd kernel) measured with HIP
+events, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def lloyd_algorithmic_bytes(b, iters):
+    """Streaming byte model of `iters` Lloyd steps: every step reads each
+    candidate's D features and writes its 4-byte assignment, and reads and writes
+    each search's centroids (2 * 4*K*D) and writes its counts (4*K)."""
+    import numpy as np
+    per_step = b.N * (4 * b.D + 4) + int(np.sum(np.diff(b.koff))) * (8 * b.D + 4)
+    return iters * per_step
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, help="workload: BASELINE config 1..5")
+    ap.add_argument("--searches", type=int, default=0, help="override the number of searches (config 3/5)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=0, help="searches in the CPU baseline sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2511_18868_amd import binding as kb, synth
+
+    kb.lib()   # fail loudly if the HIP library is missing
+    kw = {}
+    if args.searches and args.config in (3, 5):
+        kw["G"] = args.searches
+    t0 = time.time()
+    b = synth.make(args.config, **kw)
+    gen_s = time.time() - t0
+    d = kb.DeviceBatch(b, device="cuda:0")
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        d.round()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        d.round()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    value = b.N / (dt / args.steps)
+
+    # per-stage times with HIP events on the stream the kernels run on
+    def timed(fn, reps):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(reps)]
+        for s, e in ev:
+            s.record()
+            fn()
+            e.record()
+        torch.cuda.synchronize()
+        ts = sorted(s.elapsed_time(e) for s, e in ev)
+        return float(np.mean(ts)), float(ts[len(ts) // 2])
+
+    reps = max(3, min(args.steps, 20))
+    d.round()
+    torch.cuda.synchronize()
+    cl_mean, cl_med = timed(d.cluster, reps)
+    pr_mean, _ = timed(d.prune, reps)
+    uc_mean, _ = timed(d.ucb_select, reps)
+    d.cent2.copy_(d.cent)
+    step_mean, _ = timed(lambda: d.cluster_step(d.cent2), reps)
+
+    lloyd_bytes = lloyd_algorithmic_bytes(b, b.iters)
+    achieved = lloyd_bytes / (cl_mean * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "kernel": "cluster_fused_kernel", "ms": round(cl_mean, 4),
+                "algorithmic_bytes": lloyd_bytes}
+
+    out = {
+        "metric": "candidate traces scored/sec per round",
+        "value": round(value, 1), "unit": "traces/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config{args.config} full kb_round", "G": b.G, "N": b.N,
+                   "D": b.D, "S": b.S, "Ksum": b.Ksum, "Kmax": b.Kmax, "iters": b.iters},
+        "stages_ms": {"prune": round(pr_mean, 4), "cluster": round(cl_mean, 4),
+                      "ucb_select": round(uc_mean, 4), "one_lloyd_step": round(step_mean, 4)},
+        "lloyd_step_GBs": round(lloyd_algorithmic_bytes(b, 1) / (step_mean * 1e-3) / 1e9, 1),
+        "round_streaming_GBs": round(
+            (lloyd_bytes + b.N * 13 + b.N * (8 * b.S + 9)) / (ms_per_step * 1e-3) / 1e9, 1),
+        "roofline": roofline,
+        "input_generation_s": round(gen_s, 1),
+    }
+
+    if not args.no_cpu_baseline:
+        import copy
+        import oracle
+        # bounded sample: the first `gs` searches of the same batch
+        gs = args.cpu_sample or max(1, min(b.G, {1: 1, 2: 1, 3: 1024, 4: 1, 5: 768}[args.config]))
+        sb = copy.copy(b)
+        sb.G = gs
+        sb.seg_off = b.seg_off[:gs + 1]
+        sb.koff = b.koff[:gs + 1]
+        n, ks = int(sb.seg_off[-1]), int(sb.koff[-1])
+        sb.X, sb.flops, sb.bytes_ = b.X[:n], b.flops[:n], b.bytes_[:n]
+        sb.visits, sb.rsum = b.visits[:n], b.rsum[:n]
+        sb.incumbent, sb.t = b.incumbent[:gs], b.t[:gs]
+        iters = b.iters
+        if args.config == 4:
+            iters = 1     # one Lloyd step of the single large search, see `sample`
+        t0 = time.perf_counter()
+        oracle.round_(sb, iters=iters)
+        cdt = time.perf_counter() - t0
+        scale = b.iters / iters
+        out["cpu_baseline"] = {
+            "value": round(n / (cdt * scale), 1), "unit": "traces/s",
+            "cores": oracle.max_threads() if gs > 1 else 1, "kind": "oracle",
+            "sample": f"first {gs} of {b.G} searches ({n} of {b.N} candidates), full round"
+                      + (f", {iters} of {b.iters} Lloyd steps timed and scaled" if scale != 1 else ""),
+            "seconds": round(cdt, 2)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

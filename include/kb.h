@@ -1,0 +1,194 @@
+/*
+ * kb.h - C ABI of the MI355X arm-scoring library (libkernelband.so).
+ *
+ * One call scores the arms of a batch of G independent KernelBand searches
+ * (Alg. 1, the steps between "compute phi(k)" and "sample k_t"):
+ *
+ *   kb_prune         hardware-aware pruning: a roofline lower bound on the
+ *                    runtime reachable from each candidate and the binary mask
+ *                    of candidates whose bound still beats the incumbent
+ *                    (Assumption 1 / Eq. 2; mask of Eq. 5, strict '<').
+ *   kb_cluster_step  one K-Means (Lloyd) step on the behavioural feature
+ *                    vectors phi(k) under the L2 norm (Sec. 3.3; Assumption 2 /
+ *                    Eq. 3): nearest centroid, then centroid = mean of members.
+ *   kb_cluster       a fixed number of Lloyd steps starting from the first K
+ *                    rows of each search (or caller-supplied centroids).
+ *   kb_ucb_select    per-cluster arm statistics N_{i,s}, mu_{i,s}, the masked
+ *                    UCB index mu + c*sqrt(ln t / N) and its argmax (Eq. 6),
+ *                    then the member of the chosen cluster with the largest
+ *                    headroom (Sec. 3.4, zero-temperature limit of the softmax
+ *                    over V_hw).
+ *   kb_round         the three in sequence on one stream.
+ *
+ * Data model.  Search g owns the candidates seg_off[g] .. seg_off[g+1]-1 (its
+ * frontier P_t) and the clusters koff[g] .. koff[g+1]-1.  N = seg_off[G] is the
+ * total number of candidates, Ksum = koff[G] the total number of clusters.
+ * A search with no candidates is legal.  Every search with candidates needs
+ * 1 <= K_g <= N_g.
+ *
+ * Pointers.  Unless a comment says "host", every pointer is a DEVICE pointer to
+ * memory the caller allocated and keeps owning.  The library allocates nothing,
+ * keeps no state between calls and is re-entrant; all scratch comes from the
+ * caller's workspace `ws` (device, >= kb_workspace_bytes(), 256-byte aligned).
+ * Arrays are dense, row-major, with no padding.  X, cent*, flops, bytes, bound,
+ * visits and rsum must be 16-byte aligned.
+ *
+ * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default
+ * stream).  Every call only enqueues work on it and returns without waiting.
+ *
+ * Errors.  Only the return code.  Host-visible arguments are validated before
+ * anything is enqueued; contents of device memory cannot be (that would need a
+ * synchronisation), so these are preconditions: offsets non-decreasing and
+ * starting at 0, 1 <= K_g <= N_g, t_g >= 1, 0 <= rsum[k,s] <= visits[k,s],
+ * visits >= 0 with per-cluster totals below 2^31, finite inputs.  Offsets are
+ * only ever used after clamping to [0, N] / [0, Ksum], so a violated
+ * precondition gives wrong numbers but no out-of-bounds access.
+ *
+ * Limits of the compiled kernels (KB_EUNSUPPORTED beyond):
+ *   1 <= D <= 64, 1 <= S, Kmax <= 256, Kmax*S <= 8192, N < 2^31,
+ *   and G <= 1048576.
+ */
+#ifndef KB_H_
+#define KB_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KB_OK = 0,
+    KB_EINVAL = 1,       /* NULL/misaligned required pointer, non-positive size, bad parameter */
+    KB_EUNSUPPORTED = 2, /* shape beyond the compiled kernel limits */
+    KB_EWORKSPACE = 3,   /* ws is NULL, misaligned or smaller than kb_workspace_bytes() */
+    KB_EDEVICE = 4       /* a HIP call or kernel launch reported an error */
+} kb_status;
+
+#define KB_MAX_D 64
+#define KB_MAX_K 256
+#define KB_MAX_KS 8192
+#define KB_MAX_G 1048576
+
+/* Shape of a batch.  The scalars are HOST copies used for grid sizing and
+ * validation; they must agree with the device arrays. */
+typedef struct {
+    int32_t G;              /* number of searches, >= 1 */
+    int32_t D;              /* features per candidate (dimension of phi) */
+    int32_t S;              /* strategies |S| per candidate */
+    int64_t N;              /* total candidates = seg_off[G] */
+    int32_t Kmax;           /* max over searches of K_g */
+    int32_t Ksum;           /* koff[G] */
+    int32_t Nmax;           /* max over searches of N_g */
+    const int32_t *seg_off; /* device [G+1] */
+    const int32_t *koff;    /* device [G+1] */
+} kb_batch;
+
+typedef struct {
+    float peak_flops; /* flop/s of the target hardware, > 0 */
+    float peak_bw;    /* B/s of the target hardware, > 0 */
+    float c;          /* UCB exploration constant (the paper uses 2.0) */
+    float prior_n;    /* pseudo-visits added to every cluster arm (Alg. 1 starts at 1), >= 0 */
+    float prior_mu;   /* mean reward of the pseudo-visits (Alg. 1 starts at 0.5) */
+    int32_t iters;    /* Lloyd steps for kb_cluster / kb_round, >= 0 (>= 1 for kb_round) */
+} kb_params;
+
+/* Inputs and outputs of kb_round: the union of the arguments of the three
+ * stages, with the same meaning and layout as in their own entry points. */
+typedef struct {
+    const float *X;          /* [N, D]  feature vectors phi(k) */
+    const float *flops;      /* [N]     floating-point operations of candidate k */
+    const float *bytes;      /* [N]     bytes moved by candidate k */
+    const float *incumbent;  /* [G]     best runtime found so far in search g, seconds */
+    const int32_t *visits;   /* [N, S]  times strategy s was applied to candidate k */
+    const float *rsum;       /* [N, S]  sum of the rewards of those applications */
+    const int64_t *t;        /* [G]     iteration counter of search g, >= 1 */
+    float *bound;            /* [N]     out: roofline lower-bound runtime */
+    uint8_t *alive;          /* [N]     out: 1 = bound < incumbent */
+    int32_t *assign;         /* [N]     out: cluster of k, local to its search */
+    float *cent;             /* [Ksum, D] out: centroids after the last step */
+    int32_t *counts;         /* [Ksum]  out: cluster sizes */
+    float *objective;        /* [G]     out: sum of squared distances, last step */
+    int32_t *Ncs;            /* [Ksum, S] out */
+    float *mu;               /* [Ksum, S] out */
+    float *ucb;              /* [Ksum, S] out */
+    int32_t *sel;            /* [G, 3]  out: (I, S*, k*) */
+} kb_round_io;
+
+/* Bytes of device workspace any entry point needs for this batch.  Pure host
+ * function; returns 0 for a NULL or invalid batch. */
+size_t kb_workspace_bytes(const kb_batch *batch, const kb_params *params);
+
+/* Pruning (Assumption 1, Eq. 5).
+ *   bound[k] = max(flops[k]/peak_flops, bytes[k]/peak_bw)   seconds, IEEE fp32
+ *   alive[k] = bound[k] < incumbent[g(k)]                    (equality => pruned)
+ * A pruned candidate cannot beat the incumbent even at the hardware limit; all
+ * |S| arms of it are masked.  incumbent = +inf keeps everything ("no pruning
+ * initially", Alg. 1).  bound may be NULL.  Needs no workspace. */
+kb_status kb_prune(const kb_batch *batch, const kb_params *params,
+                   const float *flops, const float *bytes,
+                   const float *incumbent, float *bound, uint8_t *alive,
+                   void *stream);
+
+/* One Lloyd step from cent_in (Sec. 3.3).
+ *   assign[k]   = lowest j minimising ||x_k - cent_in[j]||^2 within k's search
+ *   objective[g]= sum over the search of that minimal squared distance
+ *   counts[j]   = members of cluster j
+ *   cent_out[j] = mean of the members; an empty cluster keeps cent_in[j]
+ * cent_in and cent_out must not overlap.  A search with no candidates gets
+ * objective 0 and nothing else written. */
+kb_status kb_cluster_step(const kb_batch *batch, const float *X,
+                          const float *cent_in, int32_t *assign,
+                          float *cent_out, int32_t *counts, float *objective,
+                          void *ws, size_t ws_bytes, void *stream);
+
+/* params->iters Lloyd steps.  Initial centroids are cent_init ([Ksum, D]) or,
+ * when it is NULL, the first K_g rows of each search.  Outputs are those of the
+ * last step: assign, counts and objective refer to the centroids entering it,
+ * cent is its updated centroids; identical to iterating kb_cluster_step.
+ * iters == 0 only writes cent = the initial centroids.  cent_init and cent must
+ * not overlap. */
+kb_status kb_cluster(const kb_batch *batch, const kb_params *params,
+                     const float *X, const float *cent_init, int32_t *assign,
+                     float *cent, int32_t *counts, float *objective, void *ws,
+                     size_t ws_bytes, void *stream);
+
+/* Cluster-arm statistics, masked UCB and selection (Eq. 6, Sec. 3.4).
+ *   Ncs[i,s] = sum of visits[k,s] over alive members k of cluster i
+ *   mu[i,s]  = (sum of rsum[k,s] + prior_n*prior_mu) / (Ncs[i,s] + prior_n)
+ *              (NaN when the denominator is 0)
+ *   ucb[i,s] = mu + c*sqrt(ln t_g / (Ncs+prior_n))  if cluster i has an alive member
+ *            = +inf  if it has one and the denominator is 0 (untried arm first)
+ *            = -inf  if it has none (masked)
+ *   sel[g]   = (I, S*, k*): (I, S*) = lowest flat index I*S+S* attaining the
+ *              maximal ucb among clusters with an alive member (scores are
+ *              compared in fp64 before rounding to fp32); k* = the alive member
+ *              of cluster I with the smallest bound, lowest index on ties, as
+ *              a GLOBAL candidate index; (-1,-1,-1) if no candidate is alive.
+ * assign must hold values in [0, K_g). */
+kb_status kb_ucb_select(const kb_batch *batch, const kb_params *params,
+                        const int32_t *assign, const uint8_t *alive,
+                        const float *bound, const int32_t *visits,
+                        const float *rsum, const int64_t *t, int32_t *Ncs,
+                        float *mu, float *ucb, int32_t *sel, void *ws,
+                        size_t ws_bytes, void *stream);
+
+/* kb_prune, then kb_cluster on ALL candidates (pruned ones are clustered too:
+ * the frontier is partitioned first and masked afterwards, Alg. 1), then
+ * kb_ucb_select with the mask, bounds and assignment just computed.
+ * Requires params->iters >= 1. */
+kb_status kb_round(const kb_batch *batch, const kb_params *params,
+                   const kb_round_io *io, void *ws, size_t ws_bytes,
+                   void *stream);
+
+/* Static, never NULL. */
+const char *kb_status_str(kb_status status);
+
+/* Library version, "major.minor". Static. */
+const char *kb_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KB_H_ */

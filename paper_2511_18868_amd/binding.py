@@ -1,0 +1,225 @@
+"""Thin ctypes binding of libkernelband.so: same names as include/kb.h,
+argument marshalling only.  torch supplies device memory and the stream; every
+step of the path runs in the library's HIP kernels.  There is no CPU fallback:
+a missing library raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkernelband.so")
+
+KB_OK, KB_EINVAL, KB_EUNSUPPORTED, KB_EWORKSPACE, KB_EDEVICE = range(5)
+
+
+class KBError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().kb_status_str(status).decode()
+        super().__init__(f"{where}: {msg}")
+
+
+class kb_batch(ctypes.Structure):
+    _fields_ = [("G", ctypes.c_int32), ("D", ctypes.c_int32), ("S", ctypes.c_int32),
+                ("N", ctypes.c_int64), ("Kmax", ctypes.c_int32), ("Ksum", ctypes.c_int32),
+                ("Nmax", ctypes.c_int32), ("seg_off", ctypes.c_void_p),
+                ("koff", ctypes.c_void_p)]
+
+
+class kb_params(ctypes.Structure):
+    _fields_ = [("peak_flops", ctypes.c_float), ("peak_bw", ctypes.c_float),
+                ("c", ctypes.c_float), ("prior_n", ctypes.c_float),
+                ("prior_mu", ctypes.c_float), ("iters", ctypes.c_int32)]
+
+
+class kb_round_io(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in (
+        "X", "flops", "bytes", "incumbent", "visits", "rsum", "t", "bound", "alive",
+        "assign", "cent", "counts", "objective", "Ncs", "mu", "ucb", "sel")]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libkernelband.so (built by paper_2511_18868_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with "
+                "`python -m paper_2511_18868_amd.build` (there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        pb, pp = ctypes.POINTER(kb_batch), ctypes.POINTER(kb_params)
+        L.kb_workspace_bytes.restype = sz
+        L.kb_workspace_bytes.argtypes = [pb, pp]
+        L.kb_prune.restype = ctypes.c_int
+        L.kb_prune.argtypes = [pb, pp, vp, vp, vp, vp, vp, vp]
+        L.kb_cluster_step.restype = ctypes.c_int
+        L.kb_cluster_step.argtypes = [pb, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.kb_cluster.restype = ctypes.c_int
+        L.kb_cluster.argtypes = [pb, pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.kb_ucb_select.restype = ctypes.c_int
+        L.kb_ucb_select.argtypes = [pb, pp] + [vp] * 10 + [vp, sz, vp]
+        L.kb_round.restype = ctypes.c_int
+        L.kb_round.argtypes = [pb, pp, ctypes.POINTER(kb_round_io), vp, sz, vp]
+        L.kb_status_str.restype = ctypes.c_char_p
+        L.kb_status_str.argtypes = [ctypes.c_int]
+        L.kb_version.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (or host) address of a torch tensor, an int, or None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(status: int, where: str, raise_on_error: bool) -> int:
+    if status != KB_OK and raise_on_error:
+        raise KBError(status, where)
+    return status
+
+
+def make_batch(G, D, S, N, Kmax, Ksum, Nmax, seg_off, koff) -> kb_batch:
+    return kb_batch(G, D, S, N, Kmax, Ksum, Nmax, _ptr(seg_off), _ptr(koff))
+
+
+def make_params(peak_flops=2.5e15, peak_bw=8e12, c=2.0, prior_n=0.0, prior_mu=0.5,
+                iters=1) -> kb_params:
+    return kb_params(peak_flops, peak_bw, c, prior_n, prior_mu, iters)
+
+
+def kb_workspace_bytes(batch: kb_batch, params: Optional[kb_params] = None) -> int:
+    return int(lib().kb_workspace_bytes(ctypes.byref(batch),
+                                        ctypes.byref(params) if params is not None else None))
+
+
+def kb_prune(batch, params, flops, bytes_, incumbent, bound, alive, stream=None, check=True):
+    s = lib().kb_prune(ctypes.byref(batch), ctypes.byref(params), _ptr(flops), _ptr(bytes_),
+                       _ptr(incumbent), _ptr(bound), _ptr(alive), _stream(stream))
+    return _check(s, "kb_prune", check)
+
+
+def kb_cluster_step(batch, X, cent_in, assign, cent_out, counts, objective, ws, ws_bytes,
+                    stream=None, check=True):
+    s = lib().kb_cluster_step(ctypes.byref(batch), _ptr(X), _ptr(cent_in), _ptr(assign),
+                              _ptr(cent_out), _ptr(counts), _ptr(objective), _ptr(ws),
+                              ws_bytes, _stream(stream))
+    return _check(s, "kb_cluster_step", check)
+
+
+def kb_cluster(batch, params, X, cent_init, assign, cent, counts, objective, ws, ws_bytes,
+               stream=None, check=True):
+    s = lib().kb_cluster(ctypes.byref(batch), ctypes.byref(params), _ptr(X), _ptr(cent_init),
+                         _ptr(assign), _ptr(cent), _ptr(counts), _ptr(objective), _ptr(ws),
+                         ws_bytes, _stream(stream))
+    return _check(s, "kb_cluster", check)
+
+
+def kb_ucb_select(batch, params, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel,
+                  ws, ws_bytes, stream=None, check=True):
+    s = lib().kb_ucb_select(ctypes.byref(batch), ctypes.byref(params), _ptr(assign), _ptr(alive),
+                            _ptr(bound), _ptr(visits), _ptr(rsum), _ptr(t), _ptr(Ncs), _ptr(mu),
+                            _ptr(ucb), _ptr(sel), _ptr(ws), ws_bytes, _stream(stream))
+    return _check(s, "kb_ucb_select", check)
+
+
+def kb_round(batch, params, io: kb_round_io, ws, ws_bytes, stream=None, check=True):
+    s = lib().kb_round(ctypes.byref(batch), ctypes.byref(params), ctypes.byref(io), _ptr(ws),
+                       ws_bytes, _stream(stream))
+    return _check(s, "kb_round", check)
+
+
+def kb_version() -> str:
+    return lib().kb_version().decode()
+
+
+# ---------------------------------------------------------------------------
+# Convenience: device buffers for one batch.  Allocation and copies only.
+
+class DeviceBatch:
+    """Uploads the arrays of a synth.Batch-like object (numpy attributes) to the
+    GPU and allocates every output and the workspace.  Holds the kb_batch /
+    kb_params / kb_round_io structs that point into those tensors."""
+
+    def __init__(self, b, device="cuda:0", iters=None):
+        import numpy as np
+        import torch
+        self.torch = torch
+        dev = torch.device(device)
+        self.device = dev
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        self.seg_off = up(b.seg_off.astype(np.int32))
+        self.koff = up(b.koff.astype(np.int32))
+        self.X = up(b.X)
+        self.flops = up(b.flops)
+        self.bytes_ = up(b.bytes_)
+        self.incumbent = up(b.incumbent)
+        self.visits = up(b.visits)
+        self.rsum = up(b.rsum)
+        self.t = up(b.t.astype(np.int64))
+        G, D, S, N, Ksum = b.G, b.D, b.S, b.N, b.Ksum
+        self.G, self.D, self.S, self.N, self.Ksum = G, D, S, N, Ksum
+        z = lambda shape, dt: torch.zeros(shape, dtype=dt, device=dev)
+        self.bound = z((N,), torch.float32)
+        self.alive = z((N,), torch.uint8)
+        self.assign = z((N,), torch.int32)
+        self.cent = z((Ksum, D), torch.float32)
+        self.cent2 = z((Ksum, D), torch.float32)
+        self.counts = z((Ksum,), torch.int32)
+        self.objective = z((G,), torch.float32)
+        self.Ncs = z((Ksum, S), torch.int32)
+        self.mu = z((Ksum, S), torch.float32)
+        self.ucb = z((Ksum, S), torch.float32)
+        self.sel = z((G, 3), torch.int32)
+        self.batch = make_batch(G, D, S, N, b.Kmax, Ksum, b.Nmax, self.seg_off, self.koff)
+        self.params = make_params(b.peak_flops, b.peak_bw, b.c, b.prior_n, b.prior_mu,
+                                  b.iters if iters is None else iters)
+        self.ws_bytes = kb_workspace_bytes(self.batch, self.params)
+        self.ws = z((max(self.ws_bytes, 256),), torch.uint8)
+        self.io = kb_round_io(*[_ptr(x) for x in (
+            self.X, self.flops, self.bytes_, self.incumbent, self.visits, self.rsum, self.t,
+            self.bound, self.alive, self.assign, self.cent, self.counts, self.objective,
+            self.Ncs, self.mu, self.ucb, self.sel)])
+
+    # the calls, on the buffers held here
+    def prune(self, **kw):
+        return kb_prune(self.batch, self.params, self.flops, self.bytes_, self.incumbent,
+                        self.bound, self.alive, **kw)
+
+    def cluster_step(self, cent_in, cent_out=None, **kw):
+        return kb_cluster_step(self.batch, self.X, cent_in,
+                               self.assign, self.cent if cent_out is None else cent_out,
+                               self.counts, self.objective, self.ws, self.ws_bytes, **kw)
+
+    def cluster(self, cent_init=None, **kw):
+        return kb_cluster(self.batch, self.params, self.X, cent_init, self.assign, self.cent,
+                          self.counts, self.objective, self.ws, self.ws_bytes, **kw)
+
+    def ucb_select(self, **kw):
+        return kb_ucb_select(self.batch, self.params, self.assign, self.alive, self.bound,
+                             self.visits, self.rsum, self.t, self.Ncs, self.mu, self.ucb,
+                             self.sel, self.ws, self.ws_bytes, **kw)
+
+    def round(self, **kw):
+        return kb_round(self.batch, self.params, self.io, self.ws, self.ws_bytes, **kw)
+
+    def host(self, name):
+        return getattr(self, name).cpu().numpy()

@@ -1,0 +1,229 @@
+// C-ABI entry points: host-side validation, workspace layout and dispatch.
+// Nothing here synchronises with the device or allocates memory.
+#include "kb_internal.h"
+
+namespace kb {
+
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+WsLayout ws_layout(const kb_batch& b) {
+    WsLayout w;
+    size_t off = 0;
+    w.a_new = off;  off += align256(sizeof(int32_t) * (size_t)(b.N > 0 ? b.N : 1));
+    w.order = off;  off += align256(sizeof(int32_t) * (size_t)b.G);
+    w.misc = off;   off += align256(sizeof(int32_t) * 128);
+    w.total = off;
+    return w;
+}
+
+static bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+static kb_status check_batch(const kb_batch* b) {
+    if (!b) return KB_EINVAL;
+    if (b->G <= 0 || b->D <= 0 || b->S <= 0) return KB_EINVAL;
+    if (b->N < 0 || b->Ksum < 0 || b->Kmax < 0 || b->Nmax < 0) return KB_EINVAL;
+    if (!b->seg_off || !b->koff) return KB_EINVAL;
+    if (b->Kmax > b->Nmax) return KB_EINVAL;
+    if ((int64_t)b->Nmax > b->N || b->Kmax > b->Ksum) return KB_EINVAL;
+    if (b->N > 0 && (b->Nmax == 0)) return KB_EINVAL;
+    if (b->N >= ((int64_t)1 << 31)) return KB_EUNSUPPORTED;
+    if (b->G > KB_MAX_G) return KB_EUNSUPPORTED;
+    return KB_OK;
+}
+
+static kb_status check_cluster_shape(const kb_batch* b) {
+    if (b->D > KB_MAX_D || b->Kmax > KB_MAX_K) return KB_EUNSUPPORTED;
+    if (!cluster_supported(*b)) return KB_EUNSUPPORTED;
+    return KB_OK;
+}
+
+static kb_status check_ws(const kb_batch* b, void* ws, size_t ws_bytes) {
+    if (!ws || !aligned(ws, 256)) return KB_EWORKSPACE;
+    if (ws_bytes < ws_layout(*b).total) return KB_EWORKSPACE;
+    return KB_OK;
+}
+
+static kb_status dev(hipError_t e) { return e == hipSuccess ? KB_OK : KB_EDEVICE; }
+
+static kb_status check_prune(const kb_params* p, const float* flops, const float* bytes,
+                             const float* inc, const float* bound, const uint8_t* alive) {
+    if (!p || !flops || !bytes || !inc || !alive) return KB_EINVAL;
+    if (!(p->peak_flops > 0.0f) || !(p->peak_bw > 0.0f)) return KB_EINVAL;
+    if (!aligned(flops, 16) || !aligned(bytes, 16) || (bound && !aligned(bound, 16)))
+        return KB_EINVAL;
+    return KB_OK;
+}
+
+static kb_status do_prune(const kb_batch* b, const kb_params* p, const float* flops,
+                          const float* bytes, const float* inc, float* bound,
+                          uint8_t* alive, hipStream_t st) {
+    kb_status s = check_prune(p, flops, bytes, inc, bound, alive);
+    if (s != KB_OK) return s;
+    if (b->N == 0) return KB_OK;
+    return dev(launch_prune(*b, p->peak_flops, p->peak_bw, flops, bytes, inc, bound, alive, st));
+}
+
+static kb_status check_cluster(const kb_batch* b, const float* X, const float* cent_init,
+                               int32_t iters, const int32_t* assign, const float* cent,
+                               const int32_t* counts, const float* objective) {
+    if (!X || !cent) return KB_EINVAL;
+    if (iters < 0) return KB_EINVAL;
+    if (iters > 0 && (!assign || !counts || !objective)) return KB_EINVAL;
+    if (!aligned(X, 16) || !aligned(cent, 16) || (cent_init && !aligned(cent_init, 16)))
+        return KB_EINVAL;
+    if (cent_init) {
+        // the two centroid arrays must not overlap
+        const char* a = (const char*)cent_init;
+        const char* c = (const char*)cent;
+        size_t bytes = sizeof(float) * (size_t)b->Ksum * b->D;
+        if (a < c + bytes && c < a + bytes) return KB_EINVAL;
+    }
+    return check_cluster_shape(b);
+}
+
+static kb_status do_cluster(const kb_batch* b, const float* X, const float* cent_init,
+                            int32_t iters, int32_t* assign, float* cent, int32_t* counts,
+                            float* objective, void* ws, hipStream_t st) {
+    kb_status s = check_cluster(b, X, cent_init, iters, assign, cent, counts, objective);
+    if (s != KB_OK) return s;
+    WsLayout w = ws_layout(*b);
+    char* base = (char*)ws;
+    int32_t* order = (int32_t*)(base + w.order);
+    hipError_t e = launch_order(*b, order, (int32_t*)(base + w.misc), st);
+    if (e != hipSuccess) return KB_EDEVICE;
+    ClusterCall c;
+    c.X = X; c.cent_init = cent_init; c.iters = iters; c.assign = assign;
+    c.cent_out = cent; c.counts = counts; c.objective = objective;
+    c.a_new = (int32_t*)(base + w.a_new); c.order = order;
+    return dev(launch_cluster(*b, c, st));
+}
+
+static kb_status check_ucb(const kb_batch* b, const kb_params* p, const int32_t* assign,
+                           const uint8_t* alive, const float* bound, const int32_t* visits,
+                           const float* rsum, const int64_t* t, const int32_t* Ncs,
+                           const float* mu, const float* ucb, const int32_t* sel) {
+    if (!p || !assign || !alive || !bound || !visits || !rsum || !t || !Ncs || !mu || !ucb || !sel)
+        return KB_EINVAL;
+    if (!(p->prior_n >= 0.0f) || !(p->c == p->c) || !(p->prior_mu == p->prior_mu)) return KB_EINVAL;
+    if (!aligned(visits, 16) || !aligned(rsum, 16)) return KB_EINVAL;
+    if (b->Kmax > KB_MAX_K || (int64_t)b->Kmax * b->S > KB_MAX_KS) return KB_EUNSUPPORTED;
+    return KB_OK;
+}
+
+static kb_status do_ucb(const kb_batch* b, const kb_params* p, const int32_t* assign,
+                        const uint8_t* alive, const float* bound, const int32_t* visits,
+                        const float* rsum, const int64_t* t, int32_t* Ncs, float* mu,
+                        float* ucb, int32_t* sel, void* ws, bool have_order, hipStream_t st) {
+    kb_status s = check_ucb(b, p, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel);
+    if (s != KB_OK) return s;
+    WsLayout w = ws_layout(*b);
+    char* base = (char*)ws;
+    int32_t* order = (int32_t*)(base + w.order);
+    if (!have_order) {
+        hipError_t e = launch_order(*b, order, (int32_t*)(base + w.misc), st);
+        if (e != hipSuccess) return KB_EDEVICE;
+    }
+    UcbCall c;
+    c.assign = assign; c.alive = alive; c.bound = bound; c.visits = visits; c.rsum = rsum;
+    c.t = t; c.c = p->c; c.prior_n = p->prior_n; c.prior_mu = p->prior_mu;
+    c.Ncs = Ncs; c.mu = mu; c.ucb = ucb; c.sel = sel; c.order = order;
+    return dev(launch_ucb(*b, c, st));
+}
+
+}  // namespace kb
+
+using namespace kb;
+
+extern "C" {
+
+size_t kb_workspace_bytes(const kb_batch* batch, const kb_params* /*params*/) {
+    if (check_batch(batch) != KB_OK) return 0;
+    return ws_layout(*batch).total;
+}
+
+kb_status kb_prune(const kb_batch* batch, const kb_params* params, const float* flops,
+                   const float* bytes, const float* incumbent, float* bound, uint8_t* alive,
+                   void* stream) {
+    kb_status s = check_batch(batch);
+    if (s != KB_OK) return s;
+    return do_prune(batch, params, flops, bytes, incumbent, bound, alive, (hipStream_t)stream);
+}
+
+kb_status kb_cluster_step(const kb_batch* batch, const float* X, const float* cent_in,
+                          int32_t* assign, float* cent_out, int32_t* counts, float* objective,
+                          void* ws, size_t ws_bytes, void* stream) {
+    kb_status s = check_batch(batch);
+    if (s != KB_OK) return s;
+    if (!cent_in) return KB_EINVAL;
+    s = check_ws(batch, ws, ws_bytes);
+    if (s != KB_OK) return s;
+    return do_cluster(batch, X, cent_in, 1, assign, cent_out, counts, objective, ws,
+                      (hipStream_t)stream);
+}
+
+kb_status kb_cluster(const kb_batch* batch, const kb_params* params, const float* X,
+                     const float* cent_init, int32_t* assign, float* cent, int32_t* counts,
+                     float* objective, void* ws, size_t ws_bytes, void* stream) {
+    kb_status s = check_batch(batch);
+    if (s != KB_OK) return s;
+    if (!params) return KB_EINVAL;
+    s = check_ws(batch, ws, ws_bytes);
+    if (s != KB_OK) return s;
+    return do_cluster(batch, X, cent_init, params->iters, assign, cent, counts, objective, ws,
+                      (hipStream_t)stream);
+}
+
+kb_status kb_ucb_select(const kb_batch* batch, const kb_params* params, const int32_t* assign,
+                        const uint8_t* alive, const float* bound, const int32_t* visits,
+                        const float* rsum, const int64_t* t, int32_t* Ncs, float* mu, float* ucb,
+                        int32_t* sel, void* ws, size_t ws_bytes, void* stream) {
+    kb_status s = check_batch(batch);
+    if (s != KB_OK) return s;
+    s = check_ws(batch, ws, ws_bytes);
+    if (s != KB_OK) return s;
+    return do_ucb(batch, params, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel, ws,
+                  false, (hipStream_t)stream);
+}
+
+kb_status kb_round(const kb_batch* batch, const kb_params* params, const kb_round_io* io,
+                   void* ws, size_t ws_bytes, void* stream) {
+    kb_status s = check_batch(batch);
+    if (s != KB_OK) return s;
+    if (!params || !io) return KB_EINVAL;
+    if (params->iters < 1) return KB_EINVAL;
+    if (!io->bound) return KB_EINVAL;
+    s = check_ws(batch, ws, ws_bytes);
+    if (s != KB_OK) return s;
+    // validate every stage before enqueueing anything
+    s = check_prune(params, io->flops, io->bytes, io->incumbent, io->bound, io->alive);
+    if (s != KB_OK) return s;
+    s = check_cluster(batch, io->X, nullptr, params->iters, io->assign, io->cent, io->counts,
+                      io->objective);
+    if (s != KB_OK) return s;
+    s = check_ucb(batch, params, io->assign, io->alive, io->bound, io->visits, io->rsum, io->t,
+                  io->Ncs, io->mu, io->ucb, io->sel);
+    if (s != KB_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+    s = do_prune(batch, params, io->flops, io->bytes, io->incumbent, io->bound, io->alive, st);
+    if (s != KB_OK) return s;
+    s = do_cluster(batch, io->X, nullptr, params->iters, io->assign, io->cent, io->counts,
+                   io->objective, ws, st);
+    if (s != KB_OK) return s;
+    return do_ucb(batch, params, io->assign, io->alive, io->bound, io->visits, io->rsum, io->t,
+                  io->Ncs, io->mu, io->ucb, io->sel, ws, true, st);
+}
+
+const char* kb_status_str(kb_status status) {
+    switch (status) {
+        case KB_OK: return "KB_OK";
+        case KB_EINVAL: return "KB_EINVAL: invalid argument";
+        case KB_EUNSUPPORTED: return "KB_EUNSUPPORTED: shape beyond the compiled kernel limits";
+        case KB_EWORKSPACE: return "KB_EWORKSPACE: workspace missing, misaligned or too small";
+        case KB_EDEVICE: return "KB_EDEVICE: HIP reported an error";
+    }
+    return "KB_E?: unknown status";
+}
+
+const char* kb_version(void) { return "0.1"; }
+
+}  // extern "C"

@@ -1,0 +1,76 @@
+// Internal declarations shared by the translation units of libkernelband.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "kb.h"
+
+namespace kb {
+
+constexpr int kWave = 64;
+
+// ---- workspace layout (all offsets 256-byte aligned) ------------------------
+struct WsLayout {
+    size_t a_new;   // int32 [N]     proposed assignment of the current step (bit 31: needs exact re-evaluation)
+    size_t order;   // int32 [G]     searches sorted by decreasing work, for longest-first scheduling
+    size_t misc;    // int32 [128]   histogram / cursors of the ordering kernel
+    size_t total;
+};
+WsLayout ws_layout(const kb_batch& b);
+
+// ---- launchers (enqueue only; return hipGetLastError()) ---------------------
+hipError_t launch_prune(const kb_batch& b, float peak_flops, float peak_bw,
+                        const float* flops, const float* bytes,
+                        const float* incumbent, float* bound, uint8_t* alive,
+                        hipStream_t st);
+
+hipError_t launch_order(const kb_batch& b, int32_t* order, int32_t* misc, hipStream_t st);
+
+struct ClusterCall {
+    const float* X;
+    const float* cent_init;   // NULL: first K_g rows
+    int32_t iters;
+    int32_t* assign;
+    float* cent_out;
+    int32_t* counts;
+    float* objective;
+    int32_t* a_new;
+    const int32_t* order;
+};
+hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t st);
+bool cluster_supported(const kb_batch& b);   // shape fits the compiled clustering kernels
+
+struct UcbCall {
+    const int32_t* assign;
+    const uint8_t* alive;
+    const float* bound;
+    const int32_t* visits;
+    const float* rsum;
+    const int64_t* t;
+    float c, prior_n, prior_mu;
+    int32_t* Ncs;
+    float* mu;
+    float* ucb;
+    int32_t* sel;
+    const int32_t* order;
+};
+hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st);
+
+// ---- device helpers ----------------------------------------------------------
+__device__ __forceinline__ int clampi(int v, int lo, int hi) {
+    return v < lo ? lo : (v > hi ? hi : v);
+}
+
+// Bounds of search g, clamped so that a malformed offset array cannot index
+// outside [0, N] / [0, Ksum].
+__device__ __forceinline__ void search_bounds(const int32_t* seg_off, const int32_t* koff,
+                                              int g, int64_t N, int Ksum,
+                                              int& n0, int& ng, int& k0, int& K) {
+    int a = clampi(seg_off[g], 0, (int)N);
+    int b = clampi(seg_off[g + 1], a, (int)N);
+    int c = clampi(koff[g], 0, Ksum);
+    int d = clampi(koff[g + 1], c, Ksum);
+    n0 = a; ng = b - a; k0 = c; K = d - c;
+}
+
+}  // namespace kb

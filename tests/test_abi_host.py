@@ -1,0 +1,133 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol include/kb.h declares, and rejects bad arguments before touching
+the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2511_18868_amd import binding as kb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x1000   # non-NULL, 256-byte aligned; never dereferenced on these paths
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(kb.LIB_PATH):
+        from paper_2511_18868_amd import build
+        build.build()
+    return kb.lib()
+
+
+def test_exports_every_declared_symbol(L):
+    hdr = open(os.path.join(ROOT, "include", "kb.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(kb_[a-z_]+)\s*\(", hdr))
+    assert {"kb_prune", "kb_cluster_step", "kb_cluster", "kb_ucb_select", "kb_round",
+            "kb_workspace_bytes", "kb_status_str", "kb_version"} <= names
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(kb.kb_batch) == 56
+    assert ctypes.sizeof(kb.kb_params) == 24
+    assert ctypes.sizeof(kb.kb_round_io) == 17 * 8
+    assert kb.kb_batch.N.offset == 16 and kb.kb_batch.seg_off.offset == 40
+
+
+def _batch(G=2, D=8, S=4, N=100, Kmax=4, Ksum=8, Nmax=60, seg=FAKE, ko=FAKE):
+    return kb.make_batch(G, D, S, N, Kmax, Ksum, Nmax, seg, ko)
+
+
+def test_status_strings(L):
+    for s in range(5):
+        assert L.kb_status_str(s).decode().startswith("KB_")
+    assert "unknown" in L.kb_status_str(99).decode()
+    assert kb.kb_version()
+
+
+def test_workspace_bytes_is_pure_and_monotone(L):
+    p = kb.make_params()
+    a = kb.kb_workspace_bytes(_batch(N=100, Nmax=60), p)
+    b = kb.kb_workspace_bytes(_batch(N=100000, Nmax=60), p)
+    assert 0 < a < b and a % 256 == 0
+    assert kb.kb_workspace_bytes(_batch(G=0), p) == 0
+
+
+@pytest.mark.parametrize("bad", [
+    dict(G=0), dict(D=0), dict(S=0), dict(N=-1), dict(seg=None), dict(ko=None),
+    dict(Kmax=70, Nmax=60), dict(Nmax=200, N=100), dict(Kmax=9, Ksum=8),
+])
+def test_bad_batch_is_einval(L, bad):
+    p = kb.make_params()
+    s = kb.kb_prune(_batch(**bad), p, FAKE, FAKE, FAKE, FAKE, FAKE, stream=0, check=False)
+    assert s == kb.KB_EINVAL
+
+
+def test_prune_argument_errors(L):
+    b = _batch()
+    ok = kb.make_params()
+    assert kb.kb_prune(b, ok, None, FAKE, FAKE, FAKE, FAKE, stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_prune(b, ok, FAKE, FAKE, FAKE, FAKE, None, stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_prune(b, ok, FAKE + 4, FAKE, FAKE, FAKE, FAKE, stream=0, check=False) == kb.KB_EINVAL
+    for bad in (dict(peak_flops=0.0), dict(peak_bw=-1.0), dict(peak_flops=float("nan"))):
+        assert kb.kb_prune(b, kb.make_params(**bad), FAKE, FAKE, FAKE, FAKE, FAKE, stream=0,
+                           check=False) == kb.KB_EINVAL
+
+
+def test_cluster_argument_errors(L):
+    b = _batch()
+    p = kb.make_params(iters=3)
+    big = 1 << 20
+    # workspace missing / misaligned / too small
+    assert kb.kb_cluster(b, p, FAKE, None, FAKE, FAKE, FAKE, FAKE, None, big, stream=0,
+                         check=False) == kb.KB_EWORKSPACE
+    assert kb.kb_cluster(b, p, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE + 16, big, stream=0,
+                         check=False) == kb.KB_EWORKSPACE
+    assert kb.kb_cluster(b, p, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, 8, stream=0,
+                         check=False) == kb.KB_EWORKSPACE
+    # NULL X, negative iters, overlapping centroid arrays, missing cent_in for a step
+    assert kb.kb_cluster(b, p, None, None, FAKE, FAKE, FAKE, FAKE, FAKE, big, stream=0,
+                         check=False) == kb.KB_EINVAL
+    assert kb.kb_cluster(b, kb.make_params(iters=-1), FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE,
+                         big, stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_cluster(b, p, FAKE, 0x2000, FAKE, 0x2000 + 16, FAKE, FAKE, FAKE, big, stream=0,
+                         check=False) == kb.KB_EINVAL
+    assert kb.kb_cluster_step(b, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, big, stream=0,
+                              check=False) == kb.KB_EINVAL
+    # beyond the compiled limits
+    assert kb.kb_cluster(_batch(D=65), p, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, big, stream=0,
+                         check=False) == kb.KB_EUNSUPPORTED
+    assert kb.kb_cluster(_batch(Kmax=257, Ksum=300, Nmax=400, N=1000), p, FAKE, None, FAKE, FAKE,
+                         FAKE, FAKE, FAKE, big, stream=0, check=False) == kb.KB_EUNSUPPORTED
+
+
+def test_ucb_and_round_argument_errors(L):
+    b = _batch()
+    p = kb.make_params(iters=2)
+    big = 1 << 20
+    args = [FAKE] * 10
+    bad = list(args)
+    bad[3] = None
+    assert kb.kb_ucb_select(b, p, *bad, FAKE, big, stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_ucb_select(b, kb.make_params(prior_n=-1.0), *args, FAKE, big, stream=0,
+                            check=False) == kb.KB_EINVAL
+    assert kb.kb_ucb_select(_batch(S=4096, Kmax=4), p, *args, FAKE, big, stream=0,
+                            check=False) == kb.KB_EUNSUPPORTED
+    io = kb.kb_round_io(*([FAKE] * 17))
+    assert kb.kb_round(b, kb.make_params(iters=0), io, FAKE, big, stream=0,
+                       check=False) == kb.KB_EINVAL
+    io2 = kb.kb_round_io(*([FAKE] * 17))
+    io2.sel = None
+    assert kb.kb_round(b, p, io2, FAKE, big, stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_round(b, p, io, FAKE, 16, stream=0, check=False) == kb.KB_EWORKSPACE
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(kb, "_lib", None)
+    monkeypatch.setattr(kb, "LIB_PATH", "/nonexistent/libkernelband.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        kb.lib()

@@ -1,0 +1,345 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Integer / byte / index outputs bit-exact; floating
+point within the tolerances written in kbcheck.py."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2511_18868_amd import synth
+from kbcheck import (assert_cent_close, assert_rel_close, compare_step, search_of)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def kb():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2511_18868_amd import binding
+    binding.lib()      # raises when the HIP library is missing: no fallback
+    return binding
+
+
+def _sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+SMALL = {
+    "cfg1": lambda: synth.config1(),
+    "cfg2": lambda: synth.config2(),
+    "cfg3s": lambda: synth.config3(G=48),
+    "cfg5s": lambda: synth.config5(G=96),
+    "paper": lambda: synth.paper_shape(),
+    "ragged": lambda: synth.config5(G=17, nmin=64, nmax=700, D=20, S=6, seed=99),
+}
+
+
+@pytest.fixture(scope="module", params=list(SMALL))
+def case(request):
+    return request.param, SMALL[request.param]()
+
+
+# ------------------------------------------------------------------ prune
+
+def test_prune_bit_exact(kb, case):
+    name, b = case
+    d = kb.DeviceBatch(b)
+    d.prune()
+    _sync()
+    bound, alive = oracle.prune(b.seg_off, b.flops, b.bytes_, b.peak_flops, b.peak_bw, b.incumbent)
+    np.testing.assert_array_equal(d.host("bound").view(np.uint32), bound.view(np.uint32))
+    np.testing.assert_array_equal(d.host("alive"), alive)
+    assert (bound == b.incumbent[search_of(b.seg_off)]).any()     # equality branch exercised
+
+
+def test_prune_extremes_and_null_bound(kb):
+    import torch
+    b = synth.config5(G=9, nmin=64, nmax=131, seed=5)
+    b.incumbent[0] = np.inf
+    b.incumbent[1] = 0.0
+    d = kb.DeviceBatch(b)
+    kb.kb_prune(d.batch, d.params, d.flops, d.bytes_, d.incumbent, None, d.alive)
+    _sync()
+    _, alive = oracle.prune(b.seg_off, b.flops, b.bytes_, b.peak_flops, b.peak_bw, b.incumbent)
+    got = d.host("alive")
+    np.testing.assert_array_equal(got, alive)
+    assert got[b.seg_off[0]:b.seg_off[1]].all() and not got[b.seg_off[1]:b.seg_off[2]].any()
+    assert torch.count_nonzero(d.bound).item() == 0               # NULL bound: not written
+
+
+# ---------------------------------------------------------- cluster step
+
+def _gpu_step(d, cent_in_np):
+    import torch
+    cin = torch.from_numpy(np.ascontiguousarray(cent_in_np)).to(d.device)
+    d.cluster_step(cin)
+    _sync()
+    return {k: d.host(k) for k in ("assign", "cent", "counts", "objective")}
+
+
+def test_cluster_step_strict(kb, case):
+    name, b = case
+    d = kb.DeviceBatch(b)
+    cin = synth.random_centroids(b, 1)
+    got = _gpu_step(d, cin)
+    ora = oracle.cluster_step(b.seg_off, b.koff, b.X, cin)
+    ndiff = compare_step(b, got, ora, name)
+    assert ndiff == 0, f"{name}: {ndiff} flagged candidates resolved differently"
+    assert got["counts"].sum() == b.N
+
+
+def test_cluster_lockstep_trajectory(kb, case):
+    name, b = case
+    d = kb.DeviceBatch(b)
+    cur = np.concatenate([b.X[b.seg_off[g]:b.seg_off[g] + (b.koff[g + 1] - b.koff[g])]
+                          for g in range(b.G)])
+    prevJ = np.full(b.G, np.inf)
+    for it in range(min(b.iters, 12)):
+        got = _gpu_step(d, cur)
+        ora = oracle.cluster_step(b.seg_off, b.koff, b.X, cur)
+        compare_step(b, got, ora, f"{name} step {it}")
+        assert np.all(got["objective"] <= prevJ * (1 + 1e-5))     # non-increasing
+        prevJ = got["objective"].astype(np.float64)
+        cur = got["cent"]          # both continue from the GPU's centroids
+
+
+def test_cluster_fused_matches_oracle(kb, case):
+    name, b = case
+    d = kb.DeviceBatch(b)
+    d.cluster()
+    _sync()
+    ora = oracle.cluster(b.seg_off, b.koff, b.X, b.iters)
+    got = {k: d.host(k) for k in ("assign", "cent", "counts", "objective")}
+    sid = search_of(b.seg_off)
+    clean = ora.dirty == 0
+    assert clean.mean() > 0.8, f"{name}: only {clean.mean():.2%} searches free of near-ties"
+    cp = clean[sid]
+    np.testing.assert_array_equal(got["assign"][cp], ora.assign[cp])
+    ck = np.repeat(clean, np.diff(b.koff))
+    np.testing.assert_array_equal(got["counts"][ck], ora.counts[ck])
+    assert_cent_close(got["cent"][ck], ora.cent[ck], name)
+    assert_rel_close(got["objective"][clean], ora.objective[clean], what=name + " objective")
+    # every search, clean or not: sizes sum to N_g, centroid = mean of members
+    for g in range(b.G):
+        a = got["assign"][b.seg_off[g]:b.seg_off[g + 1]]
+        K = b.koff[g + 1] - b.koff[g]
+        cnt = got["counts"][b.koff[g]:b.koff[g + 1]]
+        np.testing.assert_array_equal(cnt, np.bincount(a, minlength=K))
+    upd, _ = oracle.update(b.seg_off, b.koff, b.X, got["cent"], got["assign"])
+    nz = got["counts"] > 0
+    assert_cent_close(got["cent"][nz], upd[nz], name + " centroid = mean of members")
+    print(f"[{name}] searches excluded as near-tie: {(~clean).sum()} of {b.G}; "
+          f"of those matching anyway: "
+          f"{sum(np.array_equal(got['assign'][sid == g], ora.assign[sid == g]) for g in np.where(~clean)[0])}")
+
+
+def test_cluster_fused_equals_iterated_steps_and_is_deterministic(kb):
+    import torch
+    b = synth.config5(G=40, seed=3)
+    d = kb.DeviceBatch(b, iters=6)
+    d.cluster()
+    _sync()
+    first = {k: d.host(k).copy() for k in ("assign", "cent", "counts", "objective")}
+    d.assign.fill_(-7); d.cent.zero_(); d.counts.zero_(); d.objective.zero_()
+    d.cluster()
+    _sync()
+    for k in first:
+        np.testing.assert_array_equal(d.host(k).view(np.uint32), first[k].view(np.uint32), err_msg=k)
+    cur = np.concatenate([b.X[b.seg_off[g]:b.seg_off[g] + (b.koff[g + 1] - b.koff[g])]
+                          for g in range(b.G)])
+    for it in range(6):
+        got = _gpu_step(d, cur)
+        cur = got["cent"]
+    for k in first:
+        np.testing.assert_array_equal(got[k].view(np.uint32), first[k].view(np.uint32), err_msg=k)
+
+
+def test_cluster_edge_cases(kb):
+    import torch
+    # iters = 0: only the initial centroids come out
+    b = synth.config1(N=64, D=4, K=4)
+    d = kb.DeviceBatch(b, iters=0)
+    d.assign.fill_(-5)
+    d.cluster()
+    _sync()
+    np.testing.assert_array_equal(d.host("cent"), b.X[:4])
+    assert (d.host("assign") == -5).all()
+    # K = N: identity, zero objective; K = 1: column means
+    b = synth.config1(N=40, D=6, K=40)
+    d = kb.DeviceBatch(b, iters=3)
+    d.cluster()
+    _sync()
+    np.testing.assert_array_equal(d.host("assign"), np.arange(40))
+    assert d.host("objective")[0] == 0.0
+    np.testing.assert_array_equal(d.host("cent"), b.X)
+    b = synth.config2(N=500, D=12, K=1)
+    d = kb.DeviceBatch(b, iters=2)
+    d.cluster()
+    _sync()
+    assert_cent_close(d.host("cent")[0], b.X.astype(np.float64).mean(0))
+    assert abs(d.host("objective")[0] - 500 * 12) < 500 * 12 * 1e-5
+    # duplicate first rows: cluster 1 is empty after the first step and keeps its centroid
+    b = synth.config1(N=64, D=4, K=4)
+    b.X[1] = b.X[0]
+    d = kb.DeviceBatch(b, iters=1)
+    d.cluster()
+    _sync()
+    ora = oracle.cluster(b.seg_off, b.koff, b.X, 1)
+    assert d.host("counts")[1] == 0
+    np.testing.assert_array_equal(d.host("cent")[1], b.X[0])
+    np.testing.assert_array_equal(d.host("assign"), ora.assign)
+    # exact integer ties between centroids go to the lowest index
+    b = synth.config1(N=64, D=2, K=3)
+    b.X[:] = np.random.default_rng(0).integers(-3, 4, size=(64, 2)).astype(np.float32)
+    cin = np.array([[0, 0], [2, 0], [0, 2]], np.float32)
+    d = kb.DeviceBatch(b)
+    got = _gpu_step(d, cin)
+    ora = oracle.cluster_step(b.seg_off, b.koff, b.X, cin)
+    assert ora.flag.sum() > 5
+    np.testing.assert_array_equal(got["assign"], ora.assign)
+    np.testing.assert_array_equal(got["counts"], ora.counts)
+
+
+def test_empty_searches(kb):
+    b = synth.config5(G=12, nmin=64, nmax=200, seed=8)
+    # splice in empty searches (N_g = 0, K_g = 0) at the front, middle and end
+    ng = np.diff(b.seg_off); kg = np.diff(b.koff)
+    ins = [0, 5, len(ng)]
+    ng2 = np.insert(ng, ins, 0); kg2 = np.insert(kg, ins, 0)
+    b.seg_off = np.concatenate([[0], np.cumsum(ng2)]).astype(np.int32)
+    b.koff = np.concatenate([[0], np.cumsum(kg2)]).astype(np.int32)
+    b.G = len(ng2)
+    b.incumbent = np.insert(b.incumbent, ins, 1.0).astype(np.float32)
+    b.t = np.insert(b.t, ins, 1).astype(np.int64)
+    d = kb.DeviceBatch(b)
+    d.objective.fill_(-1.0)
+    d.round()
+    _sync()
+    ora = oracle.round_(b)
+    np.testing.assert_array_equal(d.host("alive"), ora.alive)
+    clean = ora.dirty == 0
+    cp = clean[search_of(b.seg_off)]
+    np.testing.assert_array_equal(d.host("assign")[cp], ora.assign[cp])
+    sel = d.host("sel")
+    empty = np.diff(b.seg_off) == 0
+    assert (sel[empty] == -1).all() and (d.host("objective")[empty] == 0).all()
+    ok = clean & (ora.near == 0)
+    np.testing.assert_array_equal(sel[ok], ora.sel[ok])
+
+
+# -------------------------------------------------------------------- UCB
+
+def test_ucb_select(kb, case):
+    import torch
+    name, b = case
+    bound, alive = oracle.prune(b.seg_off, b.flops, b.bytes_, b.peak_flops, b.peak_bw, b.incumbent)
+    cl = oracle.cluster(b.seg_off, b.koff, b.X, 3)
+    d = kb.DeviceBatch(b)
+    d.assign.copy_(torch.from_numpy(cl.assign))
+    d.alive.copy_(torch.from_numpy(alive))
+    d.bound.copy_(torch.from_numpy(bound))
+    d.ucb_select()
+    _sync()
+    ora = oracle.ucb_select(b.seg_off, b.koff, b.S, cl.assign, alive, bound, b.visits, b.rsum,
+                            b.t, b.c, b.prior_n, b.prior_mu)
+    np.testing.assert_array_equal(d.host("Ncs"), ora.Ncs)
+    assert_rel_close(d.host("mu"), ora.mu, what=name + " mu")
+    assert_rel_close(d.host("ucb"), ora.ucb, what=name + " ucb")
+    ok = ora.near == 0
+    np.testing.assert_array_equal(d.host("sel")[ok], ora.sel[ok])
+    assert ok.mean() > 0.9
+
+
+def test_ucb_special_cases(kb):
+    import torch
+    # Alg. 1's initial state: N = 1, mu = 0.5, t = 1 -> all scores 0.5, pick (0, 0)
+    b = synth.paper_shape()
+    b.visits[:] = 0; b.rsum[:] = 0; b.t[:] = 1
+    cl = oracle.cluster(b.seg_off, b.koff, b.X, 2)
+    d = kb.DeviceBatch(b)
+    d.assign.copy_(torch.from_numpy(cl.assign))
+    d.alive.fill_(1)
+    d.bound.copy_(torch.from_numpy(np.linspace(2, 1, b.N).astype(np.float32)))
+    d.ucb_select()
+    _sync()
+    assert (d.host("ucb") == 0.5).all() and (d.host("mu") == 0.5).all()
+    sel = d.host("sel")[0]
+    assert tuple(sel[:2]) == (0, 0) and sel[2] == np.where(cl.assign == 0)[0].max()
+    # untried arm -> +inf, cluster without alive member -> -inf, nothing alive -> (-1,-1,-1)
+    b.prior_n = 0.0
+    alive = (cl.assign != 1).astype(np.uint8)
+    b.visits[:] = 1; b.visits[cl.assign == 2, 3] = 0; b.rsum[:] = 0; b.t[:] = 50
+    d = kb.DeviceBatch(b)
+    d.assign.copy_(torch.from_numpy(cl.assign)); d.alive.copy_(torch.from_numpy(alive))
+    d.ucb_select()
+    _sync()
+    ora = oracle.ucb_select(b.seg_off, b.koff, b.S, cl.assign, alive, d.host("bound"), b.visits,
+                            b.rsum, b.t, b.c, 0.0, 0.5)
+    u = d.host("ucb")
+    assert np.isneginf(u[1]).all() and np.isposinf(u[2, 3]) and np.isnan(d.host("mu")[2, 3])
+    np.testing.assert_array_equal(d.host("sel"), ora.sel)
+    assert tuple(d.host("sel")[0][:2]) == (2, 3)
+    d.alive.zero_()
+    d.ucb_select()
+    _sync()
+    assert (d.host("sel") == -1).all()
+
+
+def test_ucb_real_valued_rewards(kb):
+    import torch
+    b = synth.config5(G=10, nmin=64, nmax=300, S=8, seed=21)
+    rng = np.random.default_rng(4)
+    b.rsum = (b.visits * rng.random(b.visits.shape)).astype(np.float32)
+    bound, alive = oracle.prune(b.seg_off, b.flops, b.bytes_, b.peak_flops, b.peak_bw, b.incumbent)
+    cl = oracle.cluster(b.seg_off, b.koff, b.X, 3)
+    d = kb.DeviceBatch(b)
+    d.assign.copy_(torch.from_numpy(cl.assign)); d.alive.copy_(torch.from_numpy(alive))
+    d.bound.copy_(torch.from_numpy(bound))
+    d.ucb_select()
+    _sync()
+    ora = oracle.ucb_select(b.seg_off, b.koff, b.S, cl.assign, alive, bound, b.visits, b.rsum,
+                            b.t, b.c)
+    assert_rel_close(d.host("mu"), ora.mu, what="mu")
+    assert_rel_close(d.host("ucb"), ora.ucb, what="ucb")
+    ok = ora.near == 0
+    np.testing.assert_array_equal(d.host("sel")[ok], ora.sel[ok])
+
+
+# ------------------------------------------------------------------ round
+
+def test_round_matches_oracle_and_composition(kb, case):
+    name, b = case
+    d = kb.DeviceBatch(b)
+    d.round()
+    _sync()
+    keys = ("bound", "alive", "assign", "cent", "counts", "objective", "Ncs", "mu", "ucb", "sel")
+    got = {k: d.host(k).copy() for k in keys}
+    ora = oracle.round_(b)
+    np.testing.assert_array_equal(got["bound"].view(np.uint32), ora.bound.view(np.uint32))
+    np.testing.assert_array_equal(got["alive"], ora.alive)
+    clean = ora.dirty == 0
+    cp = clean[search_of(b.seg_off)]
+    ck = np.repeat(clean, np.diff(b.koff))
+    np.testing.assert_array_equal(got["assign"][cp], ora.assign[cp])
+    assert_cent_close(got["cent"][ck], ora.cent[ck], name)
+    np.testing.assert_array_equal(got["Ncs"][ck], ora.Ncs[ck])
+    assert_rel_close(got["mu"][ck], ora.mu[ck], what="mu")
+    assert_rel_close(got["ucb"][ck], ora.ucb[ck], what="ucb")
+    ok = clean & (ora.near == 0)
+    np.testing.assert_array_equal(got["sel"][ok], ora.sel[ok])
+    # selected candidate is alive, in the chosen cluster, with the smallest bound there
+    for g in np.where(got["sel"][:, 0] >= 0)[0]:
+        I, _, ks = got["sel"][g]
+        sl = slice(b.seg_off[g], b.seg_off[g + 1])
+        m = (got["assign"][sl] == I) & (got["alive"][sl] == 1)
+        assert m[ks - b.seg_off[g]]
+        assert got["bound"][ks] == got["bound"][sl][m].min()
+    # composition: the three calls made separately give the same bytes
+    d2 = kb.DeviceBatch(b)
+    d2.prune(); d2.cluster(); d2.ucb_select()
+    _sync()
+    for k in keys:
+        a, c = got[k], d2.host(k)
+        np.testing.assert_array_equal(a.view(np.uint8), c.view(np.uint8), err_msg=k)
