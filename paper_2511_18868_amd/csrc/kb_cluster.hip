@@ -363,7 +363,7 @@ size_t fused_lds_bytes(int Kmax, int D, int DP) {
 bool cluster_supported(const kb_batch& b) {
     const int kmax = b.Kmax > 0 ? b.Kmax : 1;
     const int dv4 = (b.D + 15) / 16 * 4;
-    return fused_lds_bytes(kmax, b.D, dv4 + 4) <= kMaxLds;
+    return fused_lds_bytes(kmax, b.D, 4 * dv4 + 4) <= kMaxLds;
 }
 
 hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t st) {
@@ -374,7 +374,7 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     a.counts = c.counts; a.objective = c.objective; a.a_new = c.a_new; a.order = c.order;
 
     const int dv4 = (b.D + 15) / 16 * 4;   // 4, 8, 12 or 16 float4 chunks
-    const size_t lds = fused_lds_bytes(a.Kmax, b.D, dv4 + 4);
+    const size_t lds = fused_lds_bytes(a.Kmax, b.D, 4 * dv4 + 4);
     if (lds > kMaxLds) return hipErrorInvalidValue;
     const dim3 grid((unsigned)b.G), block(kThreads);
 #define KB_LAUNCH(DV)                                                                          \
