@@ -35,6 +35,9 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="workload: BASELINE config 1..5")
     ap.add_argument("--searches", type=int, default=0, help="override the number of searches (config 3/5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-step", action="store_true",
+                    help="skip the single-Lloyd-step timing (so a kernel trace of this run holds "
+                         "only full kb_cluster launches of the fused kernel)")
     ap.add_argument("--cpu-sample", type=int, default=0, help="searches in the CPU baseline sample")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -84,8 +87,10 @@ def main():
     cl_mean, cl_med = timed(d.cluster, reps)
     pr_mean, _ = timed(d.prune, reps)
     uc_mean, _ = timed(d.ucb_select, reps)
-    d.cent2.copy_(d.cent)
-    step_mean, _ = timed(lambda: d.cluster_step(d.cent2), reps)
+    step_mean = float("nan")
+    if not args.no_step:
+        d.cent2.copy_(d.cent)
+        step_mean, _ = timed(lambda: d.cluster_step(d.cent2), reps)
 
     lloyd_bytes = lloyd_algorithmic_bytes(b, b.iters)
     achieved = lloyd_bytes / (cl_mean * 1e-3) / 1e9
@@ -102,8 +107,9 @@ def main():
         "config": {"workload": f"config{args.config} full kb_round", "G": b.G, "N": b.N,
                    "D": b.D, "S": b.S, "Ksum": b.Ksum, "Kmax": b.Kmax, "iters": b.iters},
         "stages_ms": {"prune": round(pr_mean, 4), "cluster": round(cl_mean, 4),
-                      "ucb_select": round(uc_mean, 4), "one_lloyd_step": round(step_mean, 4)},
-        "lloyd_step_GBs": round(lloyd_algorithmic_bytes(b, 1) / (step_mean * 1e-3) / 1e9, 1),
+                      "ucb_select": round(uc_mean, 4), "one_lloyd_step": None if args.no_step else round(step_mean, 4)},
+        "lloyd_step_GBs": None if args.no_step else round(
+            lloyd_algorithmic_bytes(b, 1) / (step_mean * 1e-3) / 1e9, 1),
         "round_streaming_GBs": round(
             (lloyd_bytes + b.N * 13 + b.N * (8 * b.S + 9)) / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roofline,
@@ -114,7 +120,7 @@ def main():
         import copy
         import oracle
         # bounded sample: the first `gs` searches of the same batch
-        gs = args.cpu_sample or max(1, min(b.G, {1: 1, 2: 1, 3: 1024, 4: 1, 5: 768}[args.config]))
+        gs = args.cpu_sample or max(1, min(b.G, {1: 1, 2: 1, 3: 1024, 4: 1, 5: 4096}[args.config]))
         sb = copy.copy(b)
         sb.G = gs
         sb.seg_off = b.seg_off[:gs + 1]
