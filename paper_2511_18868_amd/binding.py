@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.kb_status_str.restype = ctypes.c_char_p
         L.kb_status_str.argtypes = [ctypes.c_int]
         L.kb_version.restype = ctypes.c_char_p
+        L.kb_set_scorer.restype = ctypes.c_int
+        L.kb_set_scorer.argtypes = [ctypes.c_int]
         _lib = L
     return _lib
 
@@ -145,6 +147,10 @@ def kb_round(batch, params, io: kb_round_io, ws, ws_bytes, stream=None, check=Tr
     s = lib().kb_round(ctypes.byref(batch), ctypes.byref(params), ctypes.byref(io), _ptr(ws),
                        ws_bytes, _stream(stream))
     return _check(s, "kb_round", check)
+
+
+def kb_set_scorer(mode: int) -> int:
+    return int(lib().kb_set_scorer(int(mode)))
 
 
 def kb_version() -> str:

@@ -224,6 +224,12 @@ const char* kb_status_str(kb_status status) {
     return "KB_E?: unknown status";
 }
 
-const char* kb_version(void) { return "0.1"; }
+const char* kb_version(void) { return "0.2"; }
+
+int kb_set_scorer(int mode) {
+    if (mode != 0 && mode != 1) return KB_EINVAL;
+    set_scorer(mode);
+    return KB_OK;
+}
 
 }  // extern "C"

@@ -5,10 +5,12 @@
 //
 // One step is three phases separated by workgroup barriers:
 //
-//   A  score   fast fp32 scores s_j = |c_j|^2 - 2 x.c_j for every centroid, the
-//              best and second-best per candidate, and a proved error bound E.
+//   A  score   fast scores s_j = |c_j|^2 - 2 x.c_j for every centroid, the best
+//              and second-best per candidate, and a proved error bound E.
 //              If second - best > 2E the winner is certain; otherwise the
-//              candidate is marked for exact re-evaluation.
+//              candidate is marked for exact re-evaluation.  Two scorers:
+//              matrix cores (bf16 x 3 split products, fp32 accumulate) for
+//              K <= 64, a vector-ALU fp32 FMA chain otherwise.
 //   R  refine  marked candidates get their squared distances in fp64, direct
 //              difference form, summed over the features in index order with
 //              separate multiply and add - exactly the plain definition - and
@@ -18,7 +20,9 @@
 //              from the old to the new cluster with integer LDS atomics.
 //              Integer addition commutes, so the sums (and with them the new
 //              centroids) do not depend on the order the waves run in: results
-//              are bit-identical from run to run without any sorting.
+//              are bit-identical from run to run without any sorting.  The
+//              matrix-core scorer does this straight from its registers for
+//              the candidates it is certain about.
 //
 // New centroid = (fixed-point sum / 2^shift) / count in fp64, rounded once to
 // fp32; an empty cluster keeps its centroid.
@@ -27,6 +31,9 @@
 namespace kb {
 
 namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 struct ClusterArgs {
     int G, D, Ksum, Kmax;
@@ -48,6 +55,7 @@ struct ClusterArgs {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kFlagBit = (int)0x80000000u;
+constexpr float kBig = 1.0e30f;    // score of a centroid row that does not exist
 
 __device__ __forceinline__ float wave_max_f(float v) {
 #pragma unroll
@@ -95,6 +103,14 @@ __device__ __forceinline__ int block_or_i(int v, double* red) {
     for (int w = 0; w < kWaves; ++w) r |= reinterpret_cast<int*>(red)[w];
     __syncthreads();
     return r;
+}
+
+// Fixed-point image of one feature value.
+__device__ __forceinline__ long long to_fixed(float x, double scale) {
+    return __double2ll_rn((double)x * scale);
+}
+__device__ __forceinline__ void lds_add(long long* p, long long q) {
+    atomicAdd(reinterpret_cast<unsigned long long*>(p), (unsigned long long)q);
 }
 
 // ---- phase A, vector-ALU scorer ---------------------------------------------
@@ -153,6 +169,171 @@ __device__ __forceinline__ void score_valu(const ClusterArgs& a, const float* __
     }
 }
 
+// ---- phase A, matrix-core scorer --------------------------------------------
+// v_mfma_f32_32x32x16_bf16 computes a 32 x 32 tile of scores: rows = centroids,
+// columns = candidates, contraction over 16 features.  Lane l supplies, for row
+// or column l%32, the 8 features 8*(l/32) .. +7 of the K-step, and receives the
+// 16 scores of column l%32 in rows 8*(r/4) + 4*(l/32) + r%4.
+//
+// fp32 operands are split into bf16 pieces v = hi + mid + rest (hi = bf16(v),
+// mid = bf16(v - hi), both round-to-nearest-even, |rest| <= 2^-16 |v|) and the
+// three leading products hi*hi + hi*mid + mid*hi are accumulated in fp32 on top
+// of |c_j|^2, with the factor -2 folded into the centroid operand (exact).
+// Error of a score against the real s_j = |c_j|^2 - 2 x.c_j:
+//   dropped products  mid*mid, rest*x, c*rest   <= 3.05 * 2^-16 * 2 sum|c_d x_d|
+//   fp32 accumulation of 3*Dpad products + |c|^2 <= (3 Dpad + 4) 2^-23 * (|c|^2 + 2 sum|c_d x_d|)(1+2^-7)
+// and 2 sum|c_d x_d| <= |x|^2 + |c|^2, so
+//   |s' - s| <= [3.1 * 2^-16 + (3 Dpad + 4) 2^-22] (|x|^2 + max_j |c_j|^2) = E.
+// (One ulp, 2^-23, per accumulated term is assumed for the matrix core's
+// internal summation, twice what round-to-nearest would give.)
+//
+// The centroid operands and |c_j|^2 (in accumulator layout) live in registers
+// for the whole step; a wave walks over tiles of 32 candidates.  Candidates the
+// scorer is certain about and whose cluster changed are moved between the
+// fixed-point sums right here, from the registers that hold their features.
+__device__ __forceinline__ void split8(const float (&v)[8], bf16x8& hi, bf16x8& mid) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const __bf16 h = (__bf16)v[i];
+        hi[i] = h;
+        mid[i] = (__bf16)(v[i] - (float)h);
+    }
+}
+
+template <int DS, int MT>
+__device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __restrict__ Xg,
+                                          int n0, int ng, int K, int D, int DP, int SP,
+                                          const float* cent, const float* cn, float cnmax,
+                                          bool first, double scale, long long* sums, int* cnt) {
+    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    const int m = lane & 31, h = lane >> 5;
+    const int mtiles = (K + 31) >> 5;
+    const float kappa = 3.1f * 1.52587890625e-05f + (float)(3 * 16 * DS + 4) * 2.384185791015625e-07f;
+    const bool vec = (D & 3) == 0;
+
+    bf16x8 Ah[MT][DS], Am[MT][DS];
+    f32x16 cnC[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int row = mt * 32 + m;
+        const bool rowok = row < K;
+#pragma unroll
+        for (int s = 0; s < DS; ++s) {
+            float v[8];
+            const float* cr = cent + (size_t)(rowok ? row : 0) * DP + 16 * s + 8 * h;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = rowok ? -2.f * cr[i] : 0.f;
+            split8(v, Ah[mt][s], Am[mt][s]);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int j = mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+            cnC[mt][r] = j < K ? cn[j] : kBig;
+        }
+    }
+
+    int any = 0;
+    for (int tile = wid; tile * 32 < ng; tile += kWaves) {
+        const int p = tile * 32 + m;
+        const bool valid = p < ng;
+        const float* xr = Xg + (size_t)(valid ? p : 0) * D;
+        float x[DS][8];
+#pragma unroll
+        for (int s = 0; s < DS; ++s) {
+            const int d0 = 16 * s + 8 * h;
+            if (vec) {
+                float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
+                if (valid && d0 < D) v0 = *reinterpret_cast<const float4*>(xr + d0);
+                if (valid && d0 + 4 < D) v1 = *reinterpret_cast<const float4*>(xr + d0 + 4);
+                x[s][0] = v0.x; x[s][1] = v0.y; x[s][2] = v0.z; x[s][3] = v0.w;
+                x[s][4] = v1.x; x[s][5] = v1.y; x[s][6] = v1.z; x[s][7] = v1.w;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) x[s][i] = (valid && d0 + i < D) ? xr[d0 + i] : 0.f;
+            }
+        }
+        int old = -1;
+        if (valid && !first) old = a.assign[(size_t)n0 + p];
+        old = (old >= 0 && old < K) ? old : -1;
+
+        bf16x8 Bh[DS], Bm[DS];
+        float xn = 0.f;
+#pragma unroll
+        for (int s = 0; s < DS; ++s) {
+            split8(x[s], Bh[s], Bm[s]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) xn = fmaf(x[s][i], x[s][i], xn);
+        }
+
+        float best = kBig * 4.f, second = kBig * 4.f;
+        int bi = 0;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            if (mt < mtiles) {
+                f32x16 acc = cnC[mt];
+#pragma unroll
+                for (int s = 0; s < DS; ++s) {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[mt][s], Bh[s], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[mt][s], Bm[s], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Am[mt][s], Bh[s], acc, 0, 0, 0);
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int j = mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                    const float v = acc[r];
+                    const bool lt = v < best;
+                    second = __builtin_amdgcn_fmed3f(best, second, v);
+                    best = fminf(best, v);
+                    bi = lt ? j : bi;
+                }
+            }
+        }
+        // the two half-waves hold complementary centroid rows of the same candidate
+        {
+            const float ob = __shfl_xor(best, 32);
+            const float os = __shfl_xor(second, 32);
+            const int oi = __shfl_xor(bi, 32);
+            second = fminf(fmaxf(best, ob), fminf(second, os));
+            const bool take = ob < best || (ob == best && oi < bi);
+            bi = take ? oi : bi;
+            best = fminf(best, ob);
+            xn += __shfl_xor(xn, 32);
+        }
+        bi = bi < K ? bi : 0;
+        const float E = kappa * (xn + cnmax);
+        const bool certain = (K == 1) || ((second - best) > 2.f * E);
+        const bool chg = valid && certain && (bi != old);
+        if (__any(chg)) {
+            any = 1;
+            if (chg) {
+#pragma unroll
+                for (int s = 0; s < DS; ++s) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const int d = 16 * s + 8 * h + i;
+                        if (d < D) {
+                            const long long q = to_fixed(x[s][i], scale);
+                            lds_add(&sums[(size_t)bi * SP + d], q);
+                            if (old >= 0) lds_add(&sums[(size_t)old * SP + d], -q);
+                        }
+                    }
+                }
+                if (h == 0) {
+                    atomicAdd(&cnt[bi], 1);
+                    if (old >= 0) atomicSub(&cnt[old], 1);
+                    a.assign[(size_t)n0 + p] = bi;
+                }
+            }
+        }
+        if (valid && h == 0) {
+            a.a_new[(size_t)n0 + p] = certain ? bi : (bi | kFlagBit);
+            // a candidate left to the exact pass in the very first step has no cluster yet
+            if (first && !certain) a.assign[(size_t)n0 + p] = -1;
+        }
+    }
+    return any;
+}
+
 // ---- phase R -----------------------------------------------------------------
 // Exact nearest centroid of the marked candidates: lanes take centroids, each
 // lane sums (x_d - c_d)^2 over d in index order in fp64 with separate multiply
@@ -191,11 +372,12 @@ __device__ __forceinline__ void refine(const ClusterArgs& a, const float* __rest
 }
 
 // ---- phase B -----------------------------------------------------------------
-// Move every candidate whose cluster changed: lanes take features, one
-// candidate at a time, so the atomics of one instruction hit consecutive LDS
-// addresses.  Returns whether this thread's wave saw any change.
+// Move every candidate whose proposed cluster differs from its recorded one:
+// lanes take features, one candidate at a time, so the atomics of one
+// instruction hit consecutive LDS addresses.  Returns whether this thread's
+// wave saw any change.
 __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restrict__ Xg, int n0,
-                                      int ng, int K, int D, bool first, double scale,
+                                      int ng, int K, int D, int SP, bool first, double scale,
                                       long long* sums, int* cnt) {
     const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
     int any = 0;
@@ -207,7 +389,7 @@ __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restr
             na = a.a_new[(size_t)n0 + p];
             na = (na >= 0 && na < K) ? na : 0;
             oa = first ? -1 : a.assign[(size_t)n0 + p];
-            oa = oa < K ? oa : -1;
+            oa = (oa >= 0 && oa < K) ? oa : -1;
             chg = na != oa;
             if (chg) a.assign[(size_t)n0 + p] = na;
         }
@@ -220,12 +402,9 @@ __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restr
             const int ob = __shfl(oa, b);
             const float* xr = Xg + (size_t)(base + b) * D;
             for (int d = lane; d < D; d += kWave) {
-                const long long q = __double2ll_rn((double)xr[d] * scale);
-                atomicAdd(reinterpret_cast<unsigned long long*>(&sums[(size_t)nb * D + d]),
-                          (unsigned long long)q);
-                if (ob >= 0)
-                    atomicAdd(reinterpret_cast<unsigned long long*>(&sums[(size_t)ob * D + d]),
-                              (unsigned long long)(-q));
+                const long long q = to_fixed(xr[d], scale);
+                lds_add(&sums[(size_t)nb * SP + d], q);
+                if (ob >= 0) lds_add(&sums[(size_t)ob * SP + d], -q);
             }
             if (lane == 0) {
                 atomicAdd(&cnt[nb], 1);
@@ -236,28 +415,50 @@ __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restr
     return any;
 }
 
-template <int DV4>
+// LDS layout shared by the kernel and the host-side size computation.
+struct Lds {
+    size_t sums, cent, cn, cnt, total;
+};
+__host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP) {
+    const int SP = D | 1;   // odd row stride: clusters spread over the LDS banks
+    Lds l;
+    size_t off = 128;                                   // reduction scratch
+    l.sums = off; off += (size_t)Kmax * SP * 8;
+    off = (off + 15) & ~(size_t)15;
+    l.cent = off; off += (size_t)Kmax * DP * 4;
+    l.cn = off;   off += (size_t)Kmax * 4;
+    l.cnt = off;  off += (size_t)Kmax * 4;
+    l.total = off;
+    return l;
+}
+
+// DS = feature K-steps of 16 (D <= 16*DS); MT = centroid tiles of 32 held in
+// registers by the matrix-core scorer, MT = 0 selects the vector-ALU scorer.
+template <int DS, int MT>
 __global__ void __launch_bounds__(kThreads) cluster_fused_kernel(ClusterArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
     const int D = a.D;
-    const int DP = 4 * DV4 + 4;
+    constexpr int DP = 16 * DS + 4;
+    const int SP = D | 1;
 
     int g = a.order ? a.order[blockIdx.x] : (int)blockIdx.x;
     g = clampi(g, 0, a.G - 1);
     int n0, ng, k0, K;
     search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
     if (K > a.Kmax) K = a.Kmax;   // LDS is sized from the host copy of Kmax
+    if (MT > 0 && K > 32 * MT) K = 32 * MT;
     if (ng <= 0 || K <= 0) {
         if (tid == 0 && a.iters > 0 && a.objective) a.objective[g] = 0.f;
         return;
     }
 
-    double* red = reinterpret_cast<double*>(smem);                       // 16 doubles
-    long long* sums = reinterpret_cast<long long*>(smem + 128);          // [Kmax][D]
-    float* cent = reinterpret_cast<float*>(sums + (((size_t)a.Kmax * D + 1) & ~(size_t)1));  // [Kmax][DP], 16-byte aligned
-    float* cn = cent + (size_t)a.Kmax * DP;                              // [Kmax]
-    int* cnt = reinterpret_cast<int*>(cn + a.Kmax);                      // [Kmax]
+    const Lds L = lds_layout(a.Kmax, D, DP);
+    double* red = reinterpret_cast<double*>(smem);
+    long long* sums = reinterpret_cast<long long*>(smem + L.sums);   // [Kmax][SP]
+    float* cent = reinterpret_cast<float*>(smem + L.cent);           // [Kmax][DP]
+    float* cn = reinterpret_cast<float*>(smem + L.cn);               // [Kmax]
+    int* cnt = reinterpret_cast<int*>(smem + L.cnt);                 // [Kmax]
 
     const float* Xg = a.X + (size_t)n0 * D;
 
@@ -269,7 +470,7 @@ __global__ void __launch_bounds__(kThreads) cluster_fused_kernel(ClusterArgs a) 
                             : Xg[(size_t)(j < ng ? j : ng - 1) * D + d];
         cent[idx] = v;
     }
-    for (int idx = tid; idx < K * D; idx += kThreads) sums[idx] = 0;
+    for (int idx = tid; idx < K * SP; idx += kThreads) sums[idx] = 0;
     for (int j = tid; j < K; j += kThreads) cnt[j] = 0;
     __syncthreads();
 
@@ -285,7 +486,15 @@ __global__ void __launch_bounds__(kThreads) cluster_fused_kernel(ClusterArgs a) 
     float am = 0.f;
     {
         const size_t total = (size_t)ng * D;
-        for (size_t i = tid; i < total; i += kThreads) am = fmaxf(am, fabsf(Xg[i]));
+        if ((D & 3) == 0) {
+            const size_t quads = total >> 2;
+            for (size_t i = tid; i < quads; i += kThreads) {
+                const float4 v = reinterpret_cast<const float4*>(Xg)[i];
+                am = fmaxf(fmaxf(am, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+            }
+        } else {
+            for (size_t i = tid; i < total; i += kThreads) am = fmaxf(am, fabsf(Xg[i]));
+        }
     }
     am = block_max_f(am, red);
     int e = 0;
@@ -310,11 +519,19 @@ __global__ void __launch_bounds__(kThreads) cluster_fused_kernel(ClusterArgs a) 
         }
         cm = block_max_f(cm, red);
 
-        score_valu<DV4>(a, Xg, n0, ng, K, D, DP, cent, cn, cm);
+        int chg = 0;
+        if constexpr (MT > 0) {
+            chg = score_mfma<DS, MT>(a, Xg, n0, ng, K, D, DP, SP, cent, cn, cm, first, scale, sums, cnt);
+        } else {
+            score_valu<4 * DS>(a, Xg, n0, ng, K, D, DP, cent, cn, cm);
+        }
         __syncthreads();
         refine(a, Xg, n0, ng, K, D, DP, cent);
         __syncthreads();
-        const int changed = block_or_i(update(a, Xg, n0, ng, K, D, first, scale, sums, cnt), red);
+        // after the matrix-core scorer only refined candidates are left to move,
+        // and it has already recorded an assignment for every other candidate
+        chg |= update(a, Xg, n0, ng, K, D, SP, first && MT == 0, scale, sums, cnt);
+        const int changed = block_or_i(chg, red);
         first = false;
 
         const bool last = (it == a.iters - 1) || (a.early_exit && !changed);
@@ -339,7 +556,9 @@ __global__ void __launch_bounds__(kThreads) cluster_fused_kernel(ClusterArgs a) 
         for (int idx = tid; idx < K * D; idx += kThreads) {
             const int j = idx / D, d = idx - j * D;
             const int c = cnt[j];
-            if (c > 0) cent[(size_t)j * DP + d] = (float)(((double)sums[idx] * inv) / (double)c);
+            if (c > 0)
+                cent[(size_t)j * DP + d] =
+                    (float)(((double)sums[(size_t)j * SP + d] * inv) / (double)c);
         }
         __syncthreads();
         if (last) break;
@@ -354,16 +573,16 @@ __global__ void __launch_bounds__(kThreads) cluster_fused_kernel(ClusterArgs a) 
 
 constexpr size_t kMaxLds = 160 * 1024;
 
-size_t fused_lds_bytes(int Kmax, int D, int DP) {
-    return 128 + (((size_t)Kmax * D + 1) & ~(size_t)1) * 8 + (size_t)Kmax * DP * 4 + (size_t)Kmax * 8;
-}
+int g_scorer = 0;   // 0 = automatic, 1 = vector ALU, 2 = matrix cores where the shape allows
 
 }  // namespace
 
+void set_scorer(int mode) { g_scorer = mode; }
+
 bool cluster_supported(const kb_batch& b) {
     const int kmax = b.Kmax > 0 ? b.Kmax : 1;
-    const int dv4 = (b.D + 15) / 16 * 4;
-    return fused_lds_bytes(kmax, b.D, 4 * dv4 + 4) <= kMaxLds;
+    const int ds = (b.D + 15) / 16;
+    return lds_layout(kmax, b.D, 16 * ds + 4).total <= kMaxLds;
 }
 
 hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t st) {
@@ -373,23 +592,33 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     a.iters = c.iters; a.early_exit = 0; a.assign = c.assign; a.cent_out = c.cent_out;
     a.counts = c.counts; a.objective = c.objective; a.a_new = c.a_new; a.order = c.order;
 
-    const int dv4 = (b.D + 15) / 16 * 4;   // 4, 8, 12 or 16 float4 chunks
-    const size_t lds = fused_lds_bytes(a.Kmax, b.D, 4 * dv4 + 4);
+    const int ds = (b.D + 15) / 16;   // 1..4 K-steps of 16 features
+    const size_t lds = lds_layout(a.Kmax, b.D, 16 * ds + 4).total;
     if (lds > kMaxLds) return hipErrorInvalidValue;
+    int mt = a.Kmax <= 32 ? 1 : (a.Kmax <= 64 ? 2 : 0);
+    if (g_scorer == 1) mt = 0;
     const dim3 grid((unsigned)b.G), block(kThreads);
-#define KB_LAUNCH(DV)                                                                          \
-    do {                                                                                       \
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(cluster_fused_kernel<DV>), \
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-        if (e != hipSuccess) return e;                                                         \
-        hipLaunchKernelGGL(cluster_fused_kernel<DV>, grid, block, lds, st, a);                 \
+#define KB_LAUNCH(DS_, MT_)                                                                     \
+    do {                                                                                        \
+        hipError_t e = hipFuncSetAttribute(                                                     \
+            reinterpret_cast<const void*>(cluster_fused_kernel<DS_, MT_>),                      \
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                              \
+        if (e != hipSuccess) return e;                                                          \
+        hipLaunchKernelGGL((cluster_fused_kernel<DS_, MT_>), grid, block, lds, st, a);          \
     } while (0)
-    switch (dv4) {
-        case 4: KB_LAUNCH(4); break;
-        case 8: KB_LAUNCH(8); break;
-        case 12: KB_LAUNCH(12); break;
-        default: KB_LAUNCH(16); break;
+#define KB_LAUNCH_DS(DS_)                                                                       \
+    do {                                                                                        \
+        if (mt == 1) KB_LAUNCH(DS_, 1);                                                         \
+        else if (mt == 2) KB_LAUNCH(DS_, 2);                                                    \
+        else KB_LAUNCH(DS_, 0);                                                                 \
+    } while (0)
+    switch (ds) {
+        case 1: KB_LAUNCH_DS(1); break;
+        case 2: KB_LAUNCH_DS(2); break;
+        case 3: KB_LAUNCH_DS(3); break;
+        default: KB_LAUNCH_DS(4); break;
     }
+#undef KB_LAUNCH_DS
 #undef KB_LAUNCH
     return hipGetLastError();
 }

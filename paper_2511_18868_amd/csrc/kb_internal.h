@@ -38,7 +38,8 @@ struct ClusterCall {
     const int32_t* order;
 };
 hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t st);
-bool cluster_supported(const kb_batch& b);   // shape fits the compiled clustering kernels
+bool cluster_supported(const kb_batch& b);
+void set_scorer(int mode);                   // 0 automatic, 1 vector ALU only   // shape fits the compiled clustering kernels
 
 struct UcbCall {
     const int32_t* assign;

@@ -26,7 +26,7 @@ def test_exports_every_declared_symbol(L):
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(kb_[a-z_]+)\s*\(", hdr))
     assert {"kb_prune", "kb_cluster_step", "kb_cluster", "kb_ucb_select", "kb_round",
-            "kb_workspace_bytes", "kb_status_str", "kb_version"} <= names
+            "kb_workspace_bytes", "kb_status_str", "kb_version", "kb_set_scorer"} <= names
     for n in names:
         assert hasattr(L, n), n
 
@@ -124,6 +124,12 @@ def test_ucb_and_round_argument_errors(L):
     io2.sel = None
     assert kb.kb_round(b, p, io2, FAKE, big, stream=0, check=False) == kb.KB_EINVAL
     assert kb.kb_round(b, p, io, FAKE, 16, stream=0, check=False) == kb.KB_EWORKSPACE
+
+
+def test_scorer_switch(L):
+    assert kb.kb_set_scorer(1) == kb.KB_OK
+    assert kb.kb_set_scorer(0) == kb.KB_OK
+    assert kb.kb_set_scorer(7) == kb.KB_EINVAL
 
 
 def test_missing_library_fails_loudly(monkeypatch):

@@ -36,6 +36,14 @@ SMALL = {
 }
 
 
+@pytest.fixture(scope="module", params=[0, 1], ids=["matrixcore", "vectoralu"])
+def scorer(kb, request):
+    """Both distance scorers of the Lloyd step must give the same results."""
+    assert kb.kb_set_scorer(request.param) == 0
+    yield request.param
+    kb.kb_set_scorer(0)
+
+
 @pytest.fixture(scope="module", params=list(SMALL))
 def case(request):
     return request.param, SMALL[request.param]()
@@ -79,7 +87,7 @@ def _gpu_step(d, cent_in_np):
     return {k: d.host(k) for k in ("assign", "cent", "counts", "objective")}
 
 
-def test_cluster_step_strict(kb, case):
+def test_cluster_step_strict(kb, case, scorer):
     name, b = case
     d = kb.DeviceBatch(b)
     cin = synth.random_centroids(b, 1)
@@ -90,7 +98,7 @@ def test_cluster_step_strict(kb, case):
     assert got["counts"].sum() == b.N
 
 
-def test_cluster_lockstep_trajectory(kb, case):
+def test_cluster_lockstep_trajectory(kb, case, scorer):
     name, b = case
     d = kb.DeviceBatch(b)
     cur = np.concatenate([b.X[b.seg_off[g]:b.seg_off[g] + (b.koff[g + 1] - b.koff[g])]
@@ -105,7 +113,7 @@ def test_cluster_lockstep_trajectory(kb, case):
         cur = got["cent"]          # both continue from the GPU's centroids
 
 
-def test_cluster_fused_matches_oracle(kb, case):
+def test_cluster_fused_matches_oracle(kb, case, scorer):
     name, b = case
     d = kb.DeviceBatch(b)
     d.cluster()
@@ -135,7 +143,7 @@ def test_cluster_fused_matches_oracle(kb, case):
           f"{sum(np.array_equal(got['assign'][sid == g], ora.assign[sid == g]) for g in np.where(~clean)[0])}")
 
 
-def test_cluster_fused_equals_iterated_steps_and_is_deterministic(kb):
+def test_cluster_fused_equals_iterated_steps_and_is_deterministic(kb, scorer):
     import torch
     b = synth.config5(G=40, seed=3)
     d = kb.DeviceBatch(b, iters=6)
@@ -156,7 +164,7 @@ def test_cluster_fused_equals_iterated_steps_and_is_deterministic(kb):
         np.testing.assert_array_equal(got[k].view(np.uint32), first[k].view(np.uint32), err_msg=k)
 
 
-def test_cluster_edge_cases(kb):
+def test_cluster_edge_cases(kb, scorer):
     import torch
     # iters = 0: only the initial centroids come out
     b = synth.config1(N=64, D=4, K=4)
@@ -202,7 +210,7 @@ def test_cluster_edge_cases(kb):
     np.testing.assert_array_equal(got["counts"], ora.counts)
 
 
-def test_empty_searches(kb):
+def test_empty_searches(kb, scorer):
     b = synth.config5(G=12, nmin=64, nmax=200, seed=8)
     # splice in empty searches (N_g = 0, K_g = 0) at the front, middle and end
     ng = np.diff(b.seg_off); kg = np.diff(b.koff)
@@ -309,7 +317,7 @@ def test_ucb_real_valued_rewards(kb):
 
 # ------------------------------------------------------------------ round
 
-def test_round_matches_oracle_and_composition(kb, case):
+def test_round_matches_oracle_and_composition(kb, case, scorer):
     name, b = case
     d = kb.DeviceBatch(b)
     d.round()
