@@ -12,6 +12,12 @@ WsLayout ws_layout(const kb_batch& b) {
     w.a_new = off;  off += align256(sizeof(int32_t) * (size_t)(b.N > 0 ? b.N : 1));
     w.order = off;  off += align256(sizeof(int32_t) * (size_t)b.G);
     w.misc = off;   off += align256(sizeof(int32_t) * 128);
+    w.tile_off = off; off += align256(sizeof(int32_t) * ((size_t)b.G + 1));
+    w.xn = off;     off += align256(sizeof(float) * (size_t)(b.N > 0 ? b.N : 1));
+    // every search rounds its candidates up to whole tiles of 32
+    w.max_tiles = (size_t)(b.N / 32) + (size_t)b.G;
+    const size_t steps = (size_t)(b.D + 15) / 16;
+    w.split = off;  off += align256(w.max_tiles * steps * 2 * 64 * 16);
     w.total = off;
     return w;
 }
@@ -89,12 +95,14 @@ static kb_status do_cluster(const kb_batch* b, const float* X, const float* cent
     WsLayout w = ws_layout(*b);
     char* base = (char*)ws;
     int32_t* order = (int32_t*)(base + w.order);
-    hipError_t e = launch_order(*b, order, (int32_t*)(base + w.misc), st);
+    hipError_t e = launch_order(*b, order, (int32_t*)(base + w.tile_off), st);
     if (e != hipSuccess) return KB_EDEVICE;
     ClusterCall c;
     c.X = X; c.cent_init = cent_init; c.iters = iters; c.assign = assign;
     c.cent_out = cent; c.counts = counts; c.objective = objective;
     c.a_new = (int32_t*)(base + w.a_new); c.order = order;
+    c.tile_off = (const int32_t*)(base + w.tile_off); c.xn = (float*)(base + w.xn);
+    c.split = (void*)(base + w.split); c.max_tiles = (int64_t)w.max_tiles;
     return dev(launch_cluster(*b, c, st));
 }
 
@@ -120,7 +128,7 @@ static kb_status do_ucb(const kb_batch* b, const kb_params* p, const int32_t* as
     char* base = (char*)ws;
     int32_t* order = (int32_t*)(base + w.order);
     if (!have_order) {
-        hipError_t e = launch_order(*b, order, (int32_t*)(base + w.misc), st);
+        hipError_t e = launch_order(*b, order, (int32_t*)(base + w.tile_off), st);
         if (e != hipSuccess) return KB_EDEVICE;
     }
     UcbCall c;

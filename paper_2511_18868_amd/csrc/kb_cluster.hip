@@ -50,6 +50,10 @@ struct ClusterArgs {
     float* objective;
     int32_t* a_new;
     const int32_t* order;
+    const int32_t* tile_off;
+    float* xn;
+    bf16x8* split;
+    int64_t max_tiles;
 };
 
 constexpr int kThreads = 256;
@@ -68,40 +72,40 @@ __device__ __forceinline__ double wave_sum_d(double v) {
     return v;
 }
 
-// Block-wide reductions over kThreads threads.  `red` is LDS scratch of at
-// least kWaves doubles.  Both end with every thread holding the result and
-// with a barrier behind them, and combine the per-wave values in a fixed order.
-__device__ __forceinline__ float block_max_f(float v, double* red) {
+// Block-wide reductions over kThreads threads.  `red` is LDS scratch of
+// 2 * kWaves doubles used as two alternating slots (`phase` counts the calls,
+// identically in every thread), so one barrier per reduction is enough: a slot
+// is rewritten only after another reduction's barrier has passed.  Every thread
+// gets the result; per-wave values are combined in a fixed order.
+__device__ __forceinline__ float block_max_f(float v, double* red, int& phase) {
+    float* slot = reinterpret_cast<float*>(red + (phase++ & 1) * kWaves);
     v = wave_max_f(v);
+    if ((threadIdx.x & 63) == 0) slot[threadIdx.x >> 6] = v;
     __syncthreads();
-    if ((threadIdx.x & 63) == 0) reinterpret_cast<float*>(red)[threadIdx.x >> 6] = v;
-    __syncthreads();
-    float r = reinterpret_cast<float*>(red)[0];
+    float r = slot[0];
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) r = fmaxf(r, reinterpret_cast<float*>(red)[w]);
-    __syncthreads();
+    for (int w = 1; w < kWaves; ++w) r = fmaxf(r, slot[w]);
     return r;
 }
-__device__ __forceinline__ double block_sum_d(double v, double* red) {
+__device__ __forceinline__ double block_sum_d(double v, double* red, int& phase) {
+    double* slot = red + (phase++ & 1) * kWaves;
     v = wave_sum_d(v);
+    if ((threadIdx.x & 63) == 0) slot[threadIdx.x >> 6] = v;
     __syncthreads();
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-    __syncthreads();
-    double r = red[0];
+    double r = slot[0];
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) r += red[w];
-    __syncthreads();
+    for (int w = 1; w < kWaves; ++w) r += slot[w];
     return r;
 }
-__device__ __forceinline__ int block_or_i(int v, double* red) {
-    v = __any(v) ? 1 : 0;
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) reinterpret_cast<int*>(red)[threadIdx.x >> 6] = v;
+// bitwise OR of the two low bits of v over the block
+__device__ __forceinline__ int block_or_i(int v, double* red, int& phase) {
+    int* slot = reinterpret_cast<int*>(red + (phase++ & 1) * kWaves);
+    v = (__any(v & 1) ? 1 : 0) | (__any(v & 2) ? 2 : 0);
+    if ((threadIdx.x & 63) == 0) slot[threadIdx.x >> 6] = v;
     __syncthreads();
     int r = 0;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) r |= reinterpret_cast<int*>(red)[w];
-    __syncthreads();
+    for (int w = 0; w < kWaves; ++w) r |= slot[w];
     return r;
 }
 
@@ -200,8 +204,56 @@ __device__ __forceinline__ void split8(const float (&v)[8], bf16x8& hi, bf16x8& 
     }
 }
 
+// The feature rows are split once per call (presplit) into a workspace laid out
+// in operand order - [tile][K-step][hi|mid][lane] x 16 bytes - so a step streams
+// them back with fully coalesced 1 KB loads and no conversion work, and the next
+// tile's operands are requested before the current tile is scored.
+template <int DS>
+__device__ __forceinline__ float presplit(const ClusterArgs& a, const float* __restrict__ Xg,
+                                          int n0, int ng, int D, bf16x8* __restrict__ sp) {
+    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    const int m = lane & 31, h = lane >> 5;
+    const bool vec = (D & 3) == 0;
+    float am = 0.f;
+    for (int tile = wid; tile * 32 < ng; tile += kWaves) {
+        const int p = tile * 32 + m;
+        const bool valid = p < ng;
+        const float* xr = Xg + (size_t)(valid ? p : 0) * D;
+        float xnp = 0.f;
+        bf16x8* tp = sp + (size_t)tile * (DS * 2 * 64) + lane;
+#pragma unroll
+        for (int s = 0; s < DS; ++s) {
+            const int d0 = 16 * s + 8 * h;
+            float x[8];
+            if (vec) {
+                float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
+                if (valid && d0 < D) v0 = *reinterpret_cast<const float4*>(xr + d0);
+                if (valid && d0 + 4 < D) v1 = *reinterpret_cast<const float4*>(xr + d0 + 4);
+                x[0] = v0.x; x[1] = v0.y; x[2] = v0.z; x[3] = v0.w;
+                x[4] = v1.x; x[5] = v1.y; x[6] = v1.z; x[7] = v1.w;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) x[i] = (valid && d0 + i < D) ? xr[d0 + i] : 0.f;
+            }
+            bf16x8 hi, mid;
+            split8(x, hi, mid);
+            tp[(2 * s) * 64] = hi;
+            tp[(2 * s + 1) * 64] = mid;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                xnp = fmaf(x[i], x[i], xnp);
+                am = fmaxf(am, fabsf(x[i]));
+            }
+        }
+        xnp += __shfl_xor(xnp, 32);
+        if (valid && h == 0) a.xn[(size_t)n0 + p] = xnp;
+    }
+    return am;
+}
+
 template <int DS, int MT>
 __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __restrict__ Xg,
+                                          const bf16x8* __restrict__ sp,
                                           int n0, int ng, int K, int D, int DP, int SP,
                                           const float* cent, const float* cn, float cnmax,
                                           bool first, double scale, long long* sums, int* cnt) {
@@ -209,10 +261,9 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
     const int m = lane & 31, h = lane >> 5;
     const int mtiles = (K + 31) >> 5;
     const float kappa = 3.1f * 1.52587890625e-05f + (float)(3 * 16 * DS + 4) * 2.384185791015625e-07f;
-    const bool vec = (D & 3) == 0;
 
+    // centroid operands (-2 c, split) stay in registers for the whole step
     bf16x8 Ah[MT][DS], Am[MT][DS];
-    f32x16 cnC[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int row = mt * 32 + m;
@@ -225,94 +276,111 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
             for (int i = 0; i < 8; ++i) v[i] = rowok ? -2.f * cr[i] : 0.f;
             split8(v, Ah[mt][s], Am[mt][s]);
         }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int j = mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-            cnC[mt][r] = j < K ? cn[j] : kBig;
-        }
     }
 
+    auto load_tile = [&](int tile, bf16x8 (&bh)[DS], bf16x8 (&bm)[DS], float& xnv, int& oldv) {
+        const bf16x8* tp = sp + (size_t)tile * (DS * 2 * 64) + lane;
+#pragma unroll
+        for (int s = 0; s < DS; ++s) {
+            bh[s] = tp[(2 * s) * 64];
+            bm[s] = tp[(2 * s + 1) * 64];
+        }
+        const int p = tile * 32 + m;
+        xnv = 0.f;
+        oldv = -1;
+        if (p < ng) {
+            xnv = a.xn[(size_t)n0 + p];
+            if (!first) oldv = a.assign[(size_t)n0 + p];
+        }
+    };
+
     int any = 0;
+    bf16x8 Bh[DS], Bm[DS];
+    float xn = 0.f;
+    int old = -1;
+    if (wid * 32 < ng) load_tile(wid, Bh, Bm, xn, old);
     for (int tile = wid; tile * 32 < ng; tile += kWaves) {
         const int p = tile * 32 + m;
         const bool valid = p < ng;
-        const float* xr = Xg + (size_t)(valid ? p : 0) * D;
-        float x[DS][8];
-#pragma unroll
-        for (int s = 0; s < DS; ++s) {
-            const int d0 = 16 * s + 8 * h;
-            if (vec) {
-                float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
-                if (valid && d0 < D) v0 = *reinterpret_cast<const float4*>(xr + d0);
-                if (valid && d0 + 4 < D) v1 = *reinterpret_cast<const float4*>(xr + d0 + 4);
-                x[s][0] = v0.x; x[s][1] = v0.y; x[s][2] = v0.z; x[s][3] = v0.w;
-                x[s][4] = v1.x; x[s][5] = v1.y; x[s][6] = v1.z; x[s][7] = v1.w;
-            } else {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) x[s][i] = (valid && d0 + i < D) ? xr[d0 + i] : 0.f;
-            }
-        }
-        int old = -1;
-        if (valid && !first) old = a.assign[(size_t)n0 + p];
+        // request the next tile before scoring this one
+        bf16x8 Bh2[DS], Bm2[DS];
+        float xn2 = 0.f;
+        int old2 = -1;
+        const bool more = (tile + kWaves) * 32 < ng;
+        if (more) load_tile(tile + kWaves, Bh2, Bm2, xn2, old2);
         old = (old >= 0 && old < K) ? old : -1;
 
-        bf16x8 Bh[DS], Bm[DS];
-        float xn = 0.f;
+        // accumulators start at |c_j|^2 (padded with a huge value for rows >= K),
+        // read from LDS in accumulator layout
+        f32x16 acc[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            if (mt < mtiles) {
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const float4 c4 = *reinterpret_cast<const float4*>(cn + mt * 32 + 8 * g4 + 4 * h);
+                    acc[mt][4 * g4 + 0] = c4.x; acc[mt][4 * g4 + 1] = c4.y;
+                    acc[mt][4 * g4 + 2] = c4.z; acc[mt][4 * g4 + 3] = c4.w;
+                }
+            }
+        }
 #pragma unroll
         for (int s = 0; s < DS; ++s) {
-            split8(x[s], Bh[s], Bm[s]);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) xn = fmaf(x[s][i], x[s][i], xn);
+            for (int mt = 0; mt < MT; ++mt) {
+                if (mt < mtiles) {
+                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[mt][s], Bh[s], acc[mt], 0, 0, 0);
+                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[mt][s], Bm[s], acc[mt], 0, 0, 0);
+                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Am[mt][s], Bh[s], acc[mt], 0, 0, 0);
+                }
+            }
         }
-
+        // best, second best and the row of the best among this lane's 16*MT rows;
+        // the lane-dependent part of the row number (4h) is added afterwards
         float best = kBig * 4.f, second = kBig * 4.f;
         int bi = 0;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             if (mt < mtiles) {
-                f32x16 acc = cnC[mt];
-#pragma unroll
-                for (int s = 0; s < DS; ++s) {
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[mt][s], Bh[s], acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[mt][s], Bm[s], acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Am[mt][s], Bh[s], acc, 0, 0, 0);
-                }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int j = mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                    const float v = acc[r];
+                    const float v = acc[mt][r];
                     const bool lt = v < best;
                     second = __builtin_amdgcn_fmed3f(best, second, v);
-                    best = fminf(best, v);
-                    bi = lt ? j : bi;
+                    best = lt ? v : best;
+                    bi = lt ? (mt * 32 + 8 * (r >> 2) + (r & 3)) : bi;
                 }
             }
         }
+        bi += 4 * h;
         // the two half-waves hold complementary centroid rows of the same candidate
         {
             const float ob = __shfl_xor(best, 32);
             const float os = __shfl_xor(second, 32);
             const int oi = __shfl_xor(bi, 32);
-            second = fminf(fmaxf(best, ob), fminf(second, os));
+            const float lo = ob < best ? ob : best, hi2 = ob < best ? best : ob;
+            const float s2 = os < second ? os : second;
+            second = s2 < hi2 ? s2 : hi2;
             const bool take = ob < best || (ob == best && oi < bi);
             bi = take ? oi : bi;
-            best = fminf(best, ob);
-            xn += __shfl_xor(xn, 32);
+            best = lo;
         }
         bi = bi < K ? bi : 0;
         const float E = kappa * (xn + cnmax);
         const bool certain = (K == 1) || ((second - best) > 2.f * E);
         const bool chg = valid && certain && (bi != old);
         if (__any(chg)) {
-            any = 1;
+            any |= 1;
             if (chg) {
+                // the fp32 row is read again (rare after the first steps)
+                const float* xr = Xg + (size_t)p * D;
 #pragma unroll
                 for (int s = 0; s < DS; ++s) {
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
                         const int d = 16 * s + 8 * h + i;
                         if (d < D) {
-                            const long long q = to_fixed(x[s][i], scale);
+                            const long long q = to_fixed(xr[d], scale);
                             lds_add(&sums[(size_t)bi * SP + d], q);
                             if (old >= 0) lds_add(&sums[(size_t)old * SP + d], -q);
                         }
@@ -330,8 +398,15 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
             // a candidate left to the exact pass in the very first step has no cluster yet
             if (first && !certain) a.assign[(size_t)n0 + p] = -1;
         }
+        if (__any(valid && !certain)) any |= 2;
+        if (more) {
+#pragma unroll
+            for (int s = 0; s < DS; ++s) { Bh[s] = Bh2[s]; Bm[s] = Bm2[s]; }
+            xn = xn2;
+            old = old2;
+        }
     }
-    return any;
+    return any;   // bit 0: some candidate moved, bit 1: some candidate needs the exact pass
 }
 
 // ---- phase R -----------------------------------------------------------------
@@ -349,16 +424,19 @@ __device__ __forceinline__ void refine(const ClusterArgs& a, const float* __rest
             const int b = __ffsll((long long)mask) - 1;
             mask &= mask - 1;
             const float* xr = Xg + (size_t)(base + b) * D;
+            // D <= 64: lane d holds feature d, broadcast by lane index below
+            const float xv = lane < D ? xr[lane] : 0.f;
             double bd = INFINITY;
             int bj = 0x7fffffff;
-            for (int j = lane; j < K; j += kWave) {
-                const float* cr = cent + (size_t)j * DP;
+            for (int j0 = 0; j0 < K; j0 += kWave) {
+                const int j = j0 + lane;
+                const float* cr = cent + (size_t)(j < K ? j : 0) * DP;
                 double acc = 0.0;
                 for (int d = 0; d < D; ++d) {
-                    const double diff = __dsub_rn((double)xr[d], (double)cr[d]);
+                    const double diff = __dsub_rn((double)__shfl(xv, d), (double)cr[d]);
                     acc = __dadd_rn(acc, __dmul_rn(diff, diff));
                 }
-                if (acc < bd) { bd = acc; bj = j; }
+                if (j < K && acc < bd) { bd = acc; bj = j; }
             }
 #pragma unroll
             for (int o = 32; o > 0; o >>= 1) {
@@ -426,7 +504,7 @@ __host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP) {
     l.sums = off; off += (size_t)Kmax * SP * 8;
     off = (off + 15) & ~(size_t)15;
     l.cent = off; off += (size_t)Kmax * DP * 4;
-    l.cn = off;   off += (size_t)Kmax * 4;
+    l.cn = off;   off += (size_t)((Kmax + 31) & ~31) * 4;   // padded to whole centroid tiles
     l.cnt = off;  off += (size_t)Kmax * 4;
     l.total = off;
     return l;
@@ -435,7 +513,7 @@ __host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP) {
 // DS = feature K-steps of 16 (D <= 16*DS); MT = centroid tiles of 32 held in
 // registers by the matrix-core scorer, MT = 0 selects the vector-ALU scorer.
 template <int DS, int MT>
-__global__ void __launch_bounds__(kThreads) cluster_fused_kernel(ClusterArgs a) {
+__global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
     const int D = a.D;
@@ -472,6 +550,7 @@ __global__ void __launch_bounds__(kThreads) cluster_fused_kernel(ClusterArgs a) 
     }
     for (int idx = tid; idx < K * SP; idx += kThreads) sums[idx] = 0;
     for (int j = tid; j < K; j += kThreads) cnt[j] = 0;
+    for (int j = K + tid; j < ((a.Kmax + 31) & ~31); j += kThreads) cn[j] = kBig;
     __syncthreads();
 
     if (a.iters == 0) {
@@ -484,7 +563,15 @@ __global__ void __launch_bounds__(kThreads) cluster_fused_kernel(ClusterArgs a) 
 
     // fixed-point scale: |x| < 2^e, N_g < 2^bits  =>  |sum of q| < 2^62
     float am = 0.f;
-    {
+    const bf16x8* sp = nullptr;
+    if constexpr (MT > 0) {
+        const int ntiles = (ng + 31) >> 5;
+        const int64_t tb = a.tile_off[g];
+        if (tb < 0 || tb + ntiles > a.max_tiles) return;   // inconsistent offsets: touch nothing
+        bf16x8* spw = a.split + (size_t)tb * (DS * 2 * 64);
+        am = presplit<DS>(a, Xg, n0, ng, D, spw);
+        sp = spw;
+    } else {
         const size_t total = (size_t)ng * D;
         if ((D & 3) == 0) {
             const size_t quads = total >> 2;
@@ -496,7 +583,8 @@ __global__ void __launch_bounds__(kThreads) cluster_fused_kernel(ClusterArgs a) 
             for (size_t i = tid; i < total; i += kThreads) am = fmaxf(am, fabsf(Xg[i]));
         }
     }
-    am = block_max_f(am, red);
+    int phase = 0;
+    am = block_max_f(am, red, phase);
     int e = 0;
     if (am > 0.f) (void)frexpf(am, &e);
     e = clampi(e, -126, 129);
@@ -506,32 +594,43 @@ __global__ void __launch_bounds__(kThreads) cluster_fused_kernel(ClusterArgs a) 
 
     bool first = true;
     for (int it = 0; it < a.iters; ++it) {
+        // |c_j|^2 in fp64, four lanes per centroid, combined in a fixed order
         float cm = 0.f;
-        for (int j = tid; j < K; j += kThreads) {
+        for (int j0 = 0; j0 < K; j0 += kThreads / 4) {
+            const int j = j0 + (tid >> 2), q = tid & 3;
             double s = 0.0;
-            for (int d = 0; d < D; ++d) {
-                const double c = (double)cent[(size_t)j * DP + d];
-                s += c * c;
+            if (j < K)
+                for (int d = q; d < D; d += 4) {
+                    const double c = (double)cent[(size_t)j * DP + d];
+                    s += c * c;
+                }
+            s += __shfl_xor(s, 1);
+            s += __shfl_xor(s, 2);
+            if (j < K) {
+                const float f = (float)s;
+                if (q == 0) cn[j] = f;
+                cm = fmaxf(cm, f);
             }
-            const float f = (float)s;
-            cn[j] = f;
-            cm = fmaxf(cm, f);
         }
-        cm = block_max_f(cm, red);
+        cm = block_max_f(cm, red, phase);
 
-        int chg = 0;
+        int st;
         if constexpr (MT > 0) {
-            chg = score_mfma<DS, MT>(a, Xg, n0, ng, K, D, DP, SP, cent, cn, cm, first, scale, sums, cnt);
+            st = score_mfma<DS, MT>(a, Xg, sp, n0, ng, K, D, DP, SP, cent, cn, cm, first, scale, sums, cnt);
         } else {
             score_valu<4 * DS>(a, Xg, n0, ng, K, D, DP, cent, cn, cm);
+            st = 2;
         }
-        __syncthreads();
-        refine(a, Xg, n0, ng, K, D, DP, cent);
-        __syncthreads();
-        // after the matrix-core scorer only refined candidates are left to move,
-        // and it has already recorded an assignment for every other candidate
-        chg |= update(a, Xg, n0, ng, K, D, SP, first && MT == 0, scale, sums, cnt);
-        const int changed = block_or_i(chg, red);
+        st = block_or_i(st, red, phase);
+        if (st & 2) {
+            refine(a, Xg, n0, ng, K, D, DP, cent);
+            __syncthreads();
+            // after the matrix-core scorer only refined candidates are left to move,
+            // and it has already recorded an assignment for every other candidate
+            const int moved = update(a, Xg, n0, ng, K, D, SP, first && MT == 0, scale, sums, cnt);
+            st |= block_or_i(moved, red, phase);
+        }
+        const int changed = st & 1;
         first = false;
 
         const bool last = (it == a.iters - 1) || (a.early_exit && !changed);
@@ -550,7 +649,7 @@ __global__ void __launch_bounds__(kThreads) cluster_fused_kernel(ClusterArgs a) 
                 }
                 acc += s;
             }
-            acc = block_sum_d(acc, red);
+            acc = block_sum_d(acc, red, phase);
             if (tid == 0) a.objective[g] = (float)acc;
         }
         for (int idx = tid; idx < K * D; idx += kThreads) {
@@ -591,6 +690,8 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     a.seg_off = b.seg_off; a.koff = b.koff; a.X = c.X; a.cent_init = c.cent_init;
     a.iters = c.iters; a.early_exit = 0; a.assign = c.assign; a.cent_out = c.cent_out;
     a.counts = c.counts; a.objective = c.objective; a.a_new = c.a_new; a.order = c.order;
+    a.tile_off = c.tile_off; a.xn = c.xn; a.split = reinterpret_cast<bf16x8*>(c.split);
+    a.max_tiles = c.max_tiles;
 
     const int ds = (b.D + 15) / 16;   // 1..4 K-steps of 16 features
     const size_t lds = lds_layout(a.Kmax, b.D, 16 * ds + 4).total;

@@ -14,6 +14,11 @@ struct WsLayout {
     size_t a_new;   // int32 [N]     proposed assignment of the current step (bit 31: needs exact re-evaluation)
     size_t order;   // int32 [G]     searches sorted by decreasing work, for longest-first scheduling
     size_t misc;    // int32 [128]   histogram / cursors of the ordering kernel
+    size_t tile_off;// int32 [G+1]   prefix sum of ceil(N_g / 32): first 32-candidate tile of each search
+    size_t xn;      // float [N]     |x_k|^2 of every candidate
+    size_t split;   // bf16          feature rows split into bf16 (hi, mid) pieces, in matrix-core
+                    //               operand order: [tile][16-feature step][hi|mid][lane][8]
+    size_t max_tiles;   // capacity of `split` in tiles (not an offset)
     size_t total;
 };
 WsLayout ws_layout(const kb_batch& b);
@@ -24,7 +29,7 @@ hipError_t launch_prune(const kb_batch& b, float peak_flops, float peak_bw,
                         const float* incumbent, float* bound, uint8_t* alive,
                         hipStream_t st);
 
-hipError_t launch_order(const kb_batch& b, int32_t* order, int32_t* misc, hipStream_t st);
+hipError_t launch_order(const kb_batch& b, int32_t* order, int32_t* tile_off, hipStream_t st);
 
 struct ClusterCall {
     const float* X;
@@ -36,6 +41,10 @@ struct ClusterCall {
     float* objective;
     int32_t* a_new;
     const int32_t* order;
+    const int32_t* tile_off;
+    float* xn;
+    void* split;
+    int64_t max_tiles;
 };
 hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t st);
 bool cluster_supported(const kb_batch& b);

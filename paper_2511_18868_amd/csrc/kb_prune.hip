@@ -89,17 +89,50 @@ hipError_t launch_prune(const kb_batch& b, float peak_flops, float peak_bw, cons
     return hipGetLastError();
 }
 
-// Searches sorted by decreasing floor(log2(N_g * K_g)): a counting sort over 64
+// Per-search scheduling data, computed by one workgroup: the first tile of every
+// search in the split-feature workspace, and the
+// searches sorted by decreasing floor(log2(N_g * K_g)): a counting sort over 64
 // buckets done by one workgroup.  The per-search kernels map blockIdx -> order[]
 // so the hardware dispatcher starts the long searches first and fills the tail
 // with short ones.  The order inside a bucket depends on atomics and may differ
 // between runs; it only affects scheduling, never results.
 __global__ void __launch_bounds__(1024)
 order_kernel(int G, int64_t N, int Ksum, const int32_t* __restrict__ seg_off,
-             const int32_t* __restrict__ koff, int32_t* __restrict__ order) {
+             const int32_t* __restrict__ koff, int32_t* __restrict__ order,
+             int32_t* __restrict__ tile_off) {
     __shared__ int hist[64];
     __shared__ int start[64];
+    __shared__ int part[1024];
     const int tid = threadIdx.x;
+    // tile_off = exclusive prefix sum of ceil(N_g / 32): each thread owns a
+    // contiguous chunk of searches
+    {
+        const int chunk = (G + (int)blockDim.x - 1) / (int)blockDim.x;
+        const int lo = tid * chunk < G ? tid * chunk : G;
+        const int hi = lo + chunk < G ? lo + chunk : G;
+        int local = 0;
+        for (int g = lo; g < hi; ++g) {
+            int n0, ng, k0, K;
+            search_bounds(seg_off, koff, g, N, Ksum, n0, ng, k0, K);
+            local += (ng + 31) >> 5;
+        }
+        part[tid] = local;
+        __syncthreads();
+        if (tid == 0) {
+            int acc = 0;
+            for (int i = 0; i < (int)blockDim.x; ++i) { const int v = part[i]; part[i] = acc; acc += v; }
+        }
+        __syncthreads();
+        int acc = part[tid];
+        for (int g = lo; g < hi; ++g) {
+            int n0, ng, k0, K;
+            search_bounds(seg_off, koff, g, N, Ksum, n0, ng, k0, K);
+            tile_off[g] = acc;
+            acc += (ng + 31) >> 5;
+        }
+        if (hi == G && lo < G) tile_off[G] = acc;
+        if (G == 0 && tid == 0) tile_off[0] = 0;
+    }
     if (tid < 64) hist[tid] = 0;
     __syncthreads();
     for (int g = tid; g < G; g += blockDim.x) {
@@ -125,9 +158,9 @@ order_kernel(int G, int64_t N, int Ksum, const int32_t* __restrict__ seg_off,
     }
 }
 
-hipError_t launch_order(const kb_batch& b, int32_t* order, int32_t* /*misc*/, hipStream_t st) {
+hipError_t launch_order(const kb_batch& b, int32_t* order, int32_t* tile_off, hipStream_t st) {
     hipLaunchKernelGGL(order_kernel, dim3(1), dim3(1024), 0, st, b.G, b.N, b.Ksum, b.seg_off,
-                       b.koff, order);
+                       b.koff, order, tile_off);
     return hipGetLastError();
 }
 
