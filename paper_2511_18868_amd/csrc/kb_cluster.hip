@@ -59,6 +59,7 @@ struct ClusterArgs {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kFlagBit = (int)0x80000000u;
+constexpr int kFlagCap = 256;      // LDS list of candidates waiting for the exact pass
 constexpr float kBig = 1.0e30f;    // score of a centroid row that does not exist
 
 __device__ __forceinline__ float wave_max_f(float v) {
@@ -109,9 +110,18 @@ __device__ __forceinline__ int block_or_i(int v, double* red, int& phase) {
     return r;
 }
 
-// Fixed-point image of one feature value.
+// Fixed-point image of one feature value: floor(x * 2^sh) as a 64-bit integer.
+// x * scale is exact (power-of-two scale); it is cut into a high and a low
+// 32-bit half with exact fp64 operations, so only the final cut below one unit
+// of the fixed-point grid rounds (toward -inf, the same way every time a value
+// is added or taken away).
 __device__ __forceinline__ long long to_fixed(float x, double scale) {
-    return __double2ll_rn((double)x * scale);
+    const double d = (double)x * scale;
+    const double hi = floor(d * 2.3283064365386963e-10);          // d / 2^32
+    const double lo = fma(hi, -4294967296.0, d);                   // in [0, 2^32)
+    const int ihi = __double2int_rz(hi);
+    const unsigned ilo = __double2uint_rz(lo);
+    return (long long)(((unsigned long long)(unsigned)ihi << 32) | ilo);
 }
 __device__ __forceinline__ void lds_add(long long* p, long long q) {
     atomicAdd(reinterpret_cast<unsigned long long*>(p), (unsigned long long)q);
@@ -251,32 +261,40 @@ __device__ __forceinline__ float presplit(const ClusterArgs& a, const float* __r
     return am;
 }
 
+// Centroid operands for the matrix cores: -2 c_j split into bf16 (hi, mid),
+// stored in LDS in operand order [tile of 32 rows][K-step][hi|mid][lane] so the
+// scorer reads them with conflict-free 16-byte loads.  Rows >= K are zero.
+template <int DS>
+__device__ __forceinline__ void build_operands(const float* cent, int K, int DP, int mtiles,
+                                               bf16x8* aop) {
+    const int chunks = mtiles * 32 * DS * 2;      // (row, 8-feature chunk) pairs
+    for (int c = threadIdx.x; c < chunks; c += kThreads) {
+        const int row = c / (DS * 2), ch = c - row * (DS * 2);
+        const int s = ch >> 1, h = ch & 1;
+        float v[8];
+        const float* cr = cent + (size_t)(row < K ? row : 0) * DP + 8 * ch;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = row < K ? -2.f * cr[i] : 0.f;
+        bf16x8 hi, mid;
+        split8(v, hi, mid);
+        const int mt = row >> 5, lane = (row & 31) + 32 * h;
+        aop[((mt * DS + s) * 2 + 0) * 64 + lane] = hi;
+        aop[((mt * DS + s) * 2 + 1) * 64 + lane] = mid;
+    }
+}
+
 template <int DS, int MT>
 __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __restrict__ Xg,
                                           const bf16x8* __restrict__ sp,
                                           int n0, int ng, int K, int D, int DP, int SP,
                                           const float* cent, const float* cn, float cnmax,
-                                          bool first, double scale, long long* sums, int* cnt) {
+                                          bool first, double scale, long long* sums, int* cnt,
+                                          int* nflag, int* flist, const bf16x8* aop) {
     const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
     const int m = lane & 31, h = lane >> 5;
     const int mtiles = (K + 31) >> 5;
     const float kappa = 3.1f * 1.52587890625e-05f + (float)(3 * 16 * DS + 4) * 2.384185791015625e-07f;
-
-    // centroid operands (-2 c, split) stay in registers for the whole step
-    bf16x8 Ah[MT][DS], Am[MT][DS];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int row = mt * 32 + m;
-        const bool rowok = row < K;
-#pragma unroll
-        for (int s = 0; s < DS; ++s) {
-            float v[8];
-            const float* cr = cent + (size_t)(rowok ? row : 0) * DP + 16 * s + 8 * h;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = rowok ? -2.f * cr[i] : 0.f;
-            split8(v, Ah[mt][s], Am[mt][s]);
-        }
-    }
+    const bool vec = (D & 3) == 0;
 
     auto load_tile = [&](int tile, bf16x8 (&bh)[DS], bf16x8 (&bm)[DS], float& xnv, int& oldv) {
         const bf16x8* tp = sp + (size_t)tile * (DS * 2 * 64) + lane;
@@ -310,60 +328,109 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
         if (more) load_tile(tile + kWaves, Bh2, Bm2, xn2, old2);
         old = (old >= 0 && old < K) ? old : -1;
 
-        // accumulators start at |c_j|^2 (padded with a huge value for rows >= K),
-        // read from LDS in accumulator layout
-        f32x16 acc[MT];
+        // Accumulators start at |c_j|^2 (padded with a huge value for rows >= K),
+        // read from LDS in accumulator layout.  Two accumulators are always in
+        // flight so that consecutive matrix instructions never depend on each
+        // other: the two centroid tiles when there are two, otherwise the
+        // hi*mid products are summed apart and added at the end.
+        constexpr int NA = 2;
+        f32x16 acc[NA];
+        const bool two = MT == 2 && mtiles == 2;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            if (mt < mtiles) {
+        for (int g4 = 0; g4 < 4; ++g4) {
+            const float4 c4 = *reinterpret_cast<const float4*>(cn + 8 * g4 + 4 * h);
+            acc[0][4 * g4 + 0] = c4.x; acc[0][4 * g4 + 1] = c4.y;
+            acc[0][4 * g4 + 2] = c4.z; acc[0][4 * g4 + 3] = c4.w;
+        }
+        if (two) {
 #pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    const float4 c4 = *reinterpret_cast<const float4*>(cn + mt * 32 + 8 * g4 + 4 * h);
-                    acc[mt][4 * g4 + 0] = c4.x; acc[mt][4 * g4 + 1] = c4.y;
-                    acc[mt][4 * g4 + 2] = c4.z; acc[mt][4 * g4 + 3] = c4.w;
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const float4 c4 = *reinterpret_cast<const float4*>(cn + 32 + 8 * g4 + 4 * h);
+                acc[1][4 * g4 + 0] = c4.x; acc[1][4 * g4 + 1] = c4.y;
+                acc[1][4 * g4 + 2] = c4.z; acc[1][4 * g4 + 3] = c4.w;
+            }
+#pragma unroll
+            for (int s = 0; s < DS; ++s) {
+                // centroid operands of this K-step, straight from LDS (operand order)
+                const bf16x8 a0h = aop[((0 * DS + s) * 2 + 0) * 64 + lane];
+                const bf16x8 a0m = aop[((0 * DS + s) * 2 + 1) * 64 + lane];
+                const bf16x8 a1h = aop[((1 * DS + s) * 2 + 0) * 64 + lane];
+                const bf16x8 a1m = aop[((1 * DS + s) * 2 + 1) * 64 + lane];
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bh[s], acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, Bh[s], acc[1], 0, 0, 0);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bm[s], acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, Bm[s], acc[1], 0, 0, 0);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0m, Bh[s], acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1m, Bh[s], acc[1], 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[1][r] = 0.f;
+#pragma unroll
+            for (int s = 0; s < DS; ++s) {
+                const bf16x8 a0h = aop[((0 * DS + s) * 2 + 0) * 64 + lane];
+                const bf16x8 a0m = aop[((0 * DS + s) * 2 + 1) * 64 + lane];
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bh[s], acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bm[s], acc[1], 0, 0, 0);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0m, Bh[s], acc[0], 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[0][r] += acc[1][r];
+        }
+        // Best, second best and the row of the best among this lane's rows: four
+        // independent chains of 8 (or 4) values, merged pairwise.  The
+        // lane-dependent part of the row number (4h) is added afterwards.
+        float cb[4], cs[4];
+        int ci[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { cb[c] = kBig * 4.f; cs[c] = kBig * 4.f; ci[c] = 0; }
+        if (two) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const int c = 2 * t + (r >> 3);
+                    const float v = acc[t][r];
+                    const bool lt = v < cb[c];
+                    cs[c] = __builtin_amdgcn_fmed3f(cb[c], cs[c], v);
+                    cb[c] = lt ? v : cb[c];
+                    ci[c] = lt ? (t * 32 + 8 * (r >> 2) + (r & 3)) : ci[c];
                 }
             }
-        }
+        } else {
 #pragma unroll
-        for (int s = 0; s < DS; ++s) {
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                if (mt < mtiles) {
-                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[mt][s], Bh[s], acc[mt], 0, 0, 0);
-                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[mt][s], Bm[s], acc[mt], 0, 0, 0);
-                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Am[mt][s], Bh[s], acc[mt], 0, 0, 0);
-                }
+            for (int r = 0; r < 16; ++r) {
+                const int c = r >> 2;
+                const float v = acc[0][r];
+                const bool lt = v < cb[c];
+                cs[c] = __builtin_amdgcn_fmed3f(cb[c], cs[c], v);
+                cb[c] = lt ? v : cb[c];
+                ci[c] = lt ? (8 * (r >> 2) + (r & 3)) : ci[c];
             }
         }
-        // best, second best and the row of the best among this lane's 16*MT rows;
-        // the lane-dependent part of the row number (4h) is added afterwards
-        float best = kBig * 4.f, second = kBig * 4.f;
-        int bi = 0;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            if (mt < mtiles) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float v = acc[mt][r];
-                    const bool lt = v < best;
-                    second = __builtin_amdgcn_fmed3f(best, second, v);
-                    best = lt ? v : best;
-                    bi = lt ? (mt * 32 + 8 * (r >> 2) + (r & 3)) : bi;
-                }
-            }
-        }
-        bi += 4 * h;
-        // the two half-waves hold complementary centroid rows of the same candidate
+        auto merge = [](float& b1, float& s1, int& i1, float b2, float s2, int i2) {
+            const bool take = b2 < b1;
+            const float hi2 = take ? b1 : b2;        // the larger of the two bests
+            const float sm = s2 < s1 ? s2 : s1;
+            s1 = sm < hi2 ? sm : hi2;
+            i1 = take ? i2 : i1;
+            b1 = take ? b2 : b1;
+        };
+        merge(cb[0], cs[0], ci[0], cb[1], cs[1], ci[1]);
+        merge(cb[2], cs[2], ci[2], cb[3], cs[3], ci[3]);
+        merge(cb[0], cs[0], ci[0], cb[2], cs[2], ci[2]);
+        float best = cb[0], second = cs[0];
+        int bi = ci[0] + 4 * h;
+        // the two half-waves hold complementary centroid rows of the same
+        // candidate: one lane-swap per value hands both halves both results
         {
-            const float ob = __shfl_xor(best, 32);
-            const float os = __shfl_xor(second, 32);
-            const int oi = __shfl_xor(bi, 32);
-            const float lo = ob < best ? ob : best, hi2 = ob < best ? best : ob;
-            const float s2 = os < second ? os : second;
-            second = s2 < hi2 ? s2 : hi2;
-            const bool take = ob < best || (ob == best && oi < bi);
-            bi = take ? oi : bi;
-            best = lo;
+            const auto rb = __builtin_amdgcn_permlane32_swap(__float_as_uint(best), __float_as_uint(best), false, false);
+            const auto rs = __builtin_amdgcn_permlane32_swap(__float_as_uint(second), __float_as_uint(second), false, false);
+            const auto ri = __builtin_amdgcn_permlane32_swap((unsigned)bi, (unsigned)bi, false, false);
+            float b0 = __uint_as_float(rb[0]), s0 = __uint_as_float(rs[0]);
+            int i0 = (int)ri[0];
+            merge(b0, s0, i0, __uint_as_float(rb[1]), __uint_as_float(rs[1]), (int)ri[1]);
+            best = b0; second = s0; bi = i0;
         }
         bi = bi < K ? bi : 0;
         const float E = kappa * (xn + cnmax);
@@ -372,15 +439,31 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
         if (__any(chg)) {
             any |= 1;
             if (chg) {
-                // the fp32 row is read again (rare after the first steps)
+                // the fp32 row is read again (rare after the first steps): all loads
+                // first, then the atomics
                 const float* xr = Xg + (size_t)p * D;
+                float xv[DS][8];
+#pragma unroll
+                for (int s = 0; s < DS; ++s) {
+                    const int d0 = 16 * s + 8 * h;
+                    if (vec) {
+                        float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
+                        if (d0 < D) v0 = *reinterpret_cast<const float4*>(xr + d0);
+                        if (d0 + 4 < D) v1 = *reinterpret_cast<const float4*>(xr + d0 + 4);
+                        xv[s][0] = v0.x; xv[s][1] = v0.y; xv[s][2] = v0.z; xv[s][3] = v0.w;
+                        xv[s][4] = v1.x; xv[s][5] = v1.y; xv[s][6] = v1.z; xv[s][7] = v1.w;
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) xv[s][i] = (d0 + i < D) ? xr[d0 + i] : 0.f;
+                    }
+                }
 #pragma unroll
                 for (int s = 0; s < DS; ++s) {
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
                         const int d = 16 * s + 8 * h + i;
                         if (d < D) {
-                            const long long q = to_fixed(xr[d], scale);
+                            const long long q = to_fixed(xv[s][i], scale);
                             lds_add(&sums[(size_t)bi * SP + d], q);
                             if (old >= 0) lds_add(&sums[(size_t)old * SP + d], -q);
                         }
@@ -395,8 +478,12 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
         }
         if (valid && h == 0) {
             a.a_new[(size_t)n0 + p] = certain ? bi : (bi | kFlagBit);
-            // a candidate left to the exact pass in the very first step has no cluster yet
-            if (first && !certain) a.assign[(size_t)n0 + p] = -1;
+            if (!certain) {
+                // a candidate left to the exact pass in the very first step has no cluster yet
+                if (first) a.assign[(size_t)n0 + p] = -1;
+                const int pos = atomicAdd(nflag, 1);
+                if (pos < kFlagCap) flist[pos] = p;
+            }
         }
         if (__any(valid && !certain)) any |= 2;
         if (more) {
@@ -449,6 +536,57 @@ __device__ __forceinline__ void refine(const ClusterArgs& a, const float* __rest
     }
 }
 
+// ---- phases R + B over the list of marked candidates ----------------------------
+// One wave per listed candidate: exact nearest centroid as in refine(), then, if
+// that differs from the recorded cluster, the move between the running sums.
+__device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* __restrict__ Xg,
+                                             int n0, int n, const int* flist, int K, int D, int DP,
+                                             int SP, const float* cent, double scale,
+                                             long long* sums, int* cnt) {
+    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    int any = 0;
+    for (int i = wid; i < n; i += kWaves) {
+        const int p = flist[i];
+        const float* xr = Xg + (size_t)p * D;
+        const float xv = lane < D ? xr[lane] : 0.f;
+        int old = a.assign[(size_t)n0 + p];
+        double bd = INFINITY;
+        int bj = 0x7fffffff;
+        for (int j0 = 0; j0 < K; j0 += kWave) {
+            const int j = j0 + lane;
+            const float* cr = cent + (size_t)(j < K ? j : 0) * DP;
+            double acc = 0.0;
+            for (int d = 0; d < D; ++d) {
+                const double diff = __dsub_rn((double)__shfl(xv, d), (double)cr[d]);
+                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+            }
+            if (j < K && acc < bd) { bd = acc; bj = j; }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const double od = __shfl_xor(bd, o);
+            const int oj = __shfl_xor(bj, o);
+            if (od < bd || (od == bd && oj < bj)) { bd = od; bj = oj; }
+        }
+        bj = bj < K ? bj : 0;
+        old = (old >= 0 && old < K) ? old : -1;
+        if (bj != old) {
+            any = 1;
+            if (lane < D) {
+                const long long q = to_fixed(xv, scale);
+                lds_add(&sums[(size_t)bj * SP + lane], q);
+                if (old >= 0) lds_add(&sums[(size_t)old * SP + lane], -q);
+            }
+            if (lane == 0) {
+                atomicAdd(&cnt[bj], 1);
+                if (old >= 0) atomicSub(&cnt[old], 1);
+                a.assign[(size_t)n0 + p] = bj;
+            }
+        }
+    }
+    return any;
+}
+
 // ---- phase B -----------------------------------------------------------------
 // Move every candidate whose proposed cluster differs from its recorded one:
 // lanes take features, one candidate at a time, so the atomics of one
@@ -495,7 +633,7 @@ __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restr
 
 // LDS layout shared by the kernel and the host-side size computation.
 struct Lds {
-    size_t sums, cent, cn, cnt, total;
+    size_t sums, cent, cn, cnt, flist, aop, total;
 };
 __host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP) {
     const int SP = D | 1;   // odd row stride: clusters spread over the LDS banks
@@ -506,6 +644,10 @@ __host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP) {
     l.cent = off; off += (size_t)Kmax * DP * 4;
     l.cn = off;   off += (size_t)((Kmax + 31) & ~31) * 4;   // padded to whole centroid tiles
     l.cnt = off;  off += (size_t)Kmax * 4;
+    l.flist = off; off += (size_t)kFlagCap * 4;
+    off = (off + 15) & ~(size_t)15;
+    // centroid operands of the matrix-core scorer (only when Kmax <= 64)
+    l.aop = off;  if (Kmax <= 64) off += (size_t)((Kmax + 31) / 32) * ((DP - 4) / 16) * 2 * 64 * 16;
     l.total = off;
     return l;
 }
@@ -537,6 +679,9 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     float* cent = reinterpret_cast<float*>(smem + L.cent);           // [Kmax][DP]
     float* cn = reinterpret_cast<float*>(smem + L.cn);               // [Kmax]
     int* cnt = reinterpret_cast<int*>(smem + L.cnt);                 // [Kmax]
+    int* flist = reinterpret_cast<int*>(smem + L.flist);             // [kFlagCap]
+    int* nflag = reinterpret_cast<int*>(smem + 64);                  // behind the two reduction slots
+    bf16x8* aop = reinterpret_cast<bf16x8*>(smem + L.aop);
 
     const float* Xg = a.X + (size_t)n0 * D;
 
@@ -594,6 +739,8 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
 
     bool first = true;
     for (int it = 0; it < a.iters; ++it) {
+        if (tid == 0) *nflag = 0;
+        if constexpr (MT > 0) build_operands<DS>(cent, K, DP, (K + 31) >> 5, aop);
         // |c_j|^2 in fp64, four lanes per centroid, combined in a fixed order
         float cm = 0.f;
         for (int j0 = 0; j0 < K; j0 += kThreads / 4) {
@@ -616,18 +763,26 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
 
         int st;
         if constexpr (MT > 0) {
-            st = score_mfma<DS, MT>(a, Xg, sp, n0, ng, K, D, DP, SP, cent, cn, cm, first, scale, sums, cnt);
+            st = score_mfma<DS, MT>(a, Xg, sp, n0, ng, K, D, DP, SP, cent, cn, cm, first, scale, sums, cnt,
+                                    nflag, flist, aop);
         } else {
             score_valu<4 * DS>(a, Xg, n0, ng, K, D, DP, cent, cn, cm);
             st = 2;
         }
         st = block_or_i(st, red, phase);
         if (st & 2) {
-            refine(a, Xg, n0, ng, K, D, DP, cent);
-            __syncthreads();
-            // after the matrix-core scorer only refined candidates are left to move,
-            // and it has already recorded an assignment for every other candidate
-            const int moved = update(a, Xg, n0, ng, K, D, SP, first && MT == 0, scale, sums, cnt);
+            int moved;
+            const int nf = MT > 0 ? *nflag : kFlagCap + 1;
+            if (nf <= kFlagCap) {
+                moved = refine_listed(a, Xg, n0, nf, flist, K, D, DP, SP, cent, scale, sums, cnt);
+            } else {
+                // the list overflowed (or the vector-ALU scorer ran): scan every candidate
+                refine(a, Xg, n0, ng, K, D, DP, cent);
+                __syncthreads();
+                // after the matrix-core scorer only refined candidates are left to move,
+                // and it has already recorded an assignment for every other candidate
+                moved = update(a, Xg, n0, ng, K, D, SP, first && MT == 0, scale, sums, cnt);
+            }
             st |= block_or_i(moved, red, phase);
         }
         const int changed = st & 1;
@@ -652,12 +807,12 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
             acc = block_sum_d(acc, red, phase);
             if (tid == 0) a.objective[g] = (float)acc;
         }
-        for (int idx = tid; idx < K * D; idx += kThreads) {
-            const int j = idx / D, d = idx - j * D;
+        for (int j = tid >> 6; j < K; j += kWaves) {
             const int c = cnt[j];
             if (c > 0)
-                cent[(size_t)j * DP + d] =
-                    (float)(((double)sums[(size_t)j * SP + d] * inv) / (double)c);
+                for (int d = tid & 63; d < D; d += kWave)
+                    cent[(size_t)j * DP + d] =
+                        (float)(((double)sums[(size_t)j * SP + d] * inv) / (double)c);
         }
         __syncthreads();
         if (last) break;
