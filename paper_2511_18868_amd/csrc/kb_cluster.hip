@@ -266,10 +266,11 @@ __device__ __forceinline__ float presplit(const ClusterArgs& a, const float* __r
 // scorer reads them with conflict-free 16-byte loads.  Rows >= K are zero.
 template <int DS>
 __device__ __forceinline__ void build_operands(const float* cent, int K, int DP, int mtiles,
-                                               bf16x8* aop) {
+                                               bf16x8* aop, const int* changed, bool all) {
     const int chunks = mtiles * 32 * DS * 2;      // (row, 8-feature chunk) pairs
     for (int c = threadIdx.x; c < chunks; c += kThreads) {
         const int row = c / (DS * 2), ch = c - row * (DS * 2);
+        if (!all && !(row < K && changed[row])) continue;   // rows >= K were zeroed in the first step
         const int s = ch >> 1, h = ch & 1;
         float v[8];
         const float* cr = cent + (size_t)(row < K ? row : 0) * DP + 8 * ch;
@@ -289,7 +290,7 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
                                           int n0, int ng, int K, int D, int DP, int SP,
                                           const float* cent, const float* cn, float cnmax,
                                           bool first, double scale, long long* sums, int* cnt,
-                                          int* nflag, int* flist, const bf16x8* aop) {
+                                          int* nflag, int* flist, const bf16x8* aop, int* dirty) {
     const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
     const int m = lane & 31, h = lane >> 5;
     const int mtiles = (K + 31) >> 5;
@@ -471,7 +472,8 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
                 }
                 if (h == 0) {
                     atomicAdd(&cnt[bi], 1);
-                    if (old >= 0) atomicSub(&cnt[old], 1);
+                    dirty[bi] = 1;
+                    if (old >= 0) { atomicSub(&cnt[old], 1); dirty[old] = 1; }
                     a.assign[(size_t)n0 + p] = bi;
                 }
             }
@@ -518,9 +520,18 @@ __device__ __forceinline__ void refine(const ClusterArgs& a, const float* __rest
             for (int j0 = 0; j0 < K; j0 += kWave) {
                 const int j = j0 + lane;
                 const float* cr = cent + (size_t)(j < K ? j : 0) * DP;
+                // rows are zero-padded to a multiple of 4 features (and xv is 0 beyond
+                // D), so whole float4 chunks can be summed: the extra terms are +0.0
                 double acc = 0.0;
-                for (int d = 0; d < D; ++d) {
-                    const double diff = __dsub_rn((double)__shfl(xv, d), (double)cr[d]);
+                for (int d = 0; d < D; d += 4) {
+                    const float4 cv = *reinterpret_cast<const float4*>(cr + d);
+                    double diff = __dsub_rn((double)__shfl(xv, d), (double)cv.x);
+                    acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                    diff = __dsub_rn((double)__shfl(xv, d + 1), (double)cv.y);
+                    acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                    diff = __dsub_rn((double)__shfl(xv, d + 2), (double)cv.z);
+                    acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                    diff = __dsub_rn((double)__shfl(xv, d + 3), (double)cv.w);
                     acc = __dadd_rn(acc, __dmul_rn(diff, diff));
                 }
                 if (j < K && acc < bd) { bd = acc; bj = j; }
@@ -542,7 +553,7 @@ __device__ __forceinline__ void refine(const ClusterArgs& a, const float* __rest
 __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* __restrict__ Xg,
                                              int n0, int n, const int* flist, int K, int D, int DP,
                                              int SP, const float* cent, double scale,
-                                             long long* sums, int* cnt) {
+                                             long long* sums, int* cnt, int* dirty) {
     const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
     int any = 0;
     for (int i = wid; i < n; i += kWaves) {
@@ -579,7 +590,8 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
             }
             if (lane == 0) {
                 atomicAdd(&cnt[bj], 1);
-                if (old >= 0) atomicSub(&cnt[old], 1);
+                dirty[bj] = 1;
+                if (old >= 0) { atomicSub(&cnt[old], 1); dirty[old] = 1; }
                 a.assign[(size_t)n0 + p] = bj;
             }
         }
@@ -594,7 +606,7 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
 // wave saw any change.
 __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restrict__ Xg, int n0,
                                       int ng, int K, int D, int SP, bool first, double scale,
-                                      long long* sums, int* cnt) {
+                                      long long* sums, int* cnt, int* dirty) {
     const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
     int any = 0;
     for (int base = wid * kWave; base < ng; base += kThreads) {
@@ -624,7 +636,8 @@ __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restr
             }
             if (lane == 0) {
                 atomicAdd(&cnt[nb], 1);
-                if (ob >= 0) atomicSub(&cnt[ob], 1);
+                dirty[nb] = 1;
+                if (ob >= 0) { atomicSub(&cnt[ob], 1); dirty[ob] = 1; }
             }
         }
     }
@@ -633,7 +646,7 @@ __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restr
 
 // LDS layout shared by the kernel and the host-side size computation.
 struct Lds {
-    size_t sums, cent, cn, cnt, flist, aop, total;
+    size_t sums, cent, cn, cnt, dirty, flist, aop, total;
 };
 __host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP) {
     const int SP = D | 1;   // odd row stride: clusters spread over the LDS banks
@@ -644,6 +657,7 @@ __host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP) {
     l.cent = off; off += (size_t)Kmax * DP * 4;
     l.cn = off;   off += (size_t)((Kmax + 31) & ~31) * 4;   // padded to whole centroid tiles
     l.cnt = off;  off += (size_t)Kmax * 4;
+    l.dirty = off; off += (size_t)Kmax * 4 * 2;     // two generations of "row changed" flags
     l.flist = off; off += (size_t)kFlagCap * 4;
     off = (off + 15) & ~(size_t)15;
     // centroid operands of the matrix-core scorer (only when Kmax <= 64)
@@ -680,6 +694,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     float* cn = reinterpret_cast<float*>(smem + L.cn);               // [Kmax]
     int* cnt = reinterpret_cast<int*>(smem + L.cnt);                 // [Kmax]
     int* flist = reinterpret_cast<int*>(smem + L.flist);             // [kFlagCap]
+    int* dirty = reinterpret_cast<int*>(smem + L.dirty);             // [2][Kmax]
     int* nflag = reinterpret_cast<int*>(smem + 64);                  // behind the two reduction slots
     bf16x8* aop = reinterpret_cast<bf16x8*>(smem + L.aop);
 
@@ -740,13 +755,19 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     bool first = true;
     for (int it = 0; it < a.iters; ++it) {
         if (tid == 0) *nflag = 0;
-        if constexpr (MT > 0) build_operands<DS>(cent, K, DP, (K + 31) >> 5, aop);
+        // dr: rows whose centroid was renewed by the previous step (all rows in the
+        // first); dw: rows touched in this step, for the renewal at its end
+        const int* dr = dirty + ((it + 1) & 1) * a.Kmax;
+        int* dw = dirty + (it & 1) * a.Kmax;
+        for (int j = tid; j < K; j += kThreads) dw[j] = 0;
+        if constexpr (MT > 0) build_operands<DS>(cent, K, DP, (K + 31) >> 5, aop, dr, it == 0);
         // |c_j|^2 in fp64, four lanes per centroid, combined in a fixed order
         float cm = 0.f;
         for (int j0 = 0; j0 < K; j0 += kThreads / 4) {
             const int j = j0 + (tid >> 2), q = tid & 3;
+            const bool renew = j < K && (it == 0 || dr[j]);
             double s = 0.0;
-            if (j < K)
+            if (renew)
                 for (int d = q; d < D; d += 4) {
                     const double c = (double)cent[(size_t)j * DP + d];
                     s += c * c;
@@ -754,8 +775,9 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
             s += __shfl_xor(s, 1);
             s += __shfl_xor(s, 2);
             if (j < K) {
-                const float f = (float)s;
-                if (q == 0) cn[j] = f;
+                float f;
+                if (renew) { f = (float)s; if (q == 0) cn[j] = f; }
+                else f = cn[j];
                 cm = fmaxf(cm, f);
             }
         }
@@ -764,7 +786,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
         int st;
         if constexpr (MT > 0) {
             st = score_mfma<DS, MT>(a, Xg, sp, n0, ng, K, D, DP, SP, cent, cn, cm, first, scale, sums, cnt,
-                                    nflag, flist, aop);
+                                    nflag, flist, aop, dw);
         } else {
             score_valu<4 * DS>(a, Xg, n0, ng, K, D, DP, cent, cn, cm);
             st = 2;
@@ -774,14 +796,14 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
             int moved;
             const int nf = MT > 0 ? *nflag : kFlagCap + 1;
             if (nf <= kFlagCap) {
-                moved = refine_listed(a, Xg, n0, nf, flist, K, D, DP, SP, cent, scale, sums, cnt);
+                moved = refine_listed(a, Xg, n0, nf, flist, K, D, DP, SP, cent, scale, sums, cnt, dw);
             } else {
                 // the list overflowed (or the vector-ALU scorer ran): scan every candidate
                 refine(a, Xg, n0, ng, K, D, DP, cent);
                 __syncthreads();
                 // after the matrix-core scorer only refined candidates are left to move,
                 // and it has already recorded an assignment for every other candidate
-                moved = update(a, Xg, n0, ng, K, D, SP, first && MT == 0, scale, sums, cnt);
+                moved = update(a, Xg, n0, ng, K, D, SP, first && MT == 0, scale, sums, cnt, dw);
             }
             st |= block_or_i(moved, red, phase);
         }
@@ -790,26 +812,41 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
 
         const bool last = (it == a.iters - 1) || (a.early_exit && !changed);
         if (last) {
-            // objective relative to the centroids that entered this step
+            // objective relative to the centroids that entered this step: 16 lanes
+            // per candidate (4 features each), per-lane fp64 partial sums in a fixed
+            // candidate order, then a fixed-order reduction
             double acc = 0.0;
-            for (int p = tid; p < ng; p += kThreads) {
-                int j = a.assign[(size_t)n0 + p];
-                j = (j >= 0 && j < K) ? j : 0;
-                const float* xr = Xg + (size_t)p * D;
-                const float* cr = cent + (size_t)j * DP;
-                double s = 0.0;
-                for (int d = 0; d < D; ++d) {
-                    const double diff = (double)xr[d] - (double)cr[d];
-                    s += diff * diff;
+            {
+                const int sub = tid >> 4, l16 = tid & 15;
+                const bool vec4 = (D & 3) == 0;
+                for (int p = sub; p < ng; p += kThreads / 16) {
+                    int j = a.assign[(size_t)n0 + p];
+                    j = (j >= 0 && j < K) ? j : 0;
+                    const float* xr = Xg + (size_t)p * D;
+                    const float* cr = cent + (size_t)j * DP;
+                    float sq = 0.f;
+                    if (vec4) {
+                        if (4 * l16 < D) {
+                            const float4 xv = *reinterpret_cast<const float4*>(xr + 4 * l16);
+                            const float4 cv = *reinterpret_cast<const float4*>(cr + 4 * l16);
+                            const float e0 = xv.x - cv.x, e1 = xv.y - cv.y, e2 = xv.z - cv.z, e3 = xv.w - cv.w;
+                            sq = fmaf(e0, e0, fmaf(e1, e1, fmaf(e2, e2, e3 * e3)));
+                        }
+                    } else {
+                        for (int d = 4 * l16; d < 4 * l16 + 4 && d < D; ++d) {
+                            const float e0 = xr[d] - cr[d];
+                            sq = fmaf(e0, e0, sq);
+                        }
+                    }
+                    acc += (double)sq;
                 }
-                acc += s;
             }
             acc = block_sum_d(acc, red, phase);
             if (tid == 0) a.objective[g] = (float)acc;
         }
         for (int j = tid >> 6; j < K; j += kWaves) {
             const int c = cnt[j];
-            if (c > 0)
+            if (c > 0 && dw[j])
                 for (int d = tid & 63; d < D; d += kWave)
                     cent[(size_t)j * DP + d] =
                         (float)(((double)sums[(size_t)j * SP + d] * inv) / (double)c);
