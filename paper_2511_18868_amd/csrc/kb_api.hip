@@ -18,6 +18,8 @@ WsLayout ws_layout(const kb_batch& b) {
     w.max_tiles = (size_t)(b.N / 32) + (size_t)b.G;
     const size_t steps = (size_t)(b.D + 15) / 16;
     w.split = off;  off += align256(w.max_tiles * steps * 2 * 64 * 16);
+    w.use_big = cluster_uses_big(b);
+    if (w.use_big) { w.big = big_ws_layout(b, off); off = w.big.end; }
     w.total = off;
     return w;
 }
@@ -39,7 +41,7 @@ static kb_status check_batch(const kb_batch* b) {
 
 static kb_status check_cluster_shape(const kb_batch* b) {
     if (b->D > KB_MAX_D || b->Kmax > KB_MAX_K) return KB_EUNSUPPORTED;
-    if (!cluster_supported(*b)) return KB_EUNSUPPORTED;
+    if (!cluster_uses_big(*b) && !cluster_supported(*b)) return KB_EUNSUPPORTED;
     return KB_OK;
 }
 
@@ -95,7 +97,8 @@ static kb_status do_cluster(const kb_batch* b, const float* X, const float* cent
     WsLayout w = ws_layout(*b);
     char* base = (char*)ws;
     int32_t* order = (int32_t*)(base + w.order);
-    hipError_t e = launch_order(*b, order, (int32_t*)(base + w.tile_off), st);
+    hipError_t e = launch_order(*b, order, (int32_t*)(base + w.tile_off),
+                                w.use_big ? (int32_t*)(base + w.big.chunk_off) : nullptr, st);
     if (e != hipSuccess) return KB_EDEVICE;
     ClusterCall c;
     c.X = X; c.cent_init = cent_init; c.iters = iters; c.assign = assign;
@@ -103,6 +106,7 @@ static kb_status do_cluster(const kb_batch* b, const float* X, const float* cent
     c.a_new = (int32_t*)(base + w.a_new); c.order = order;
     c.tile_off = (const int32_t*)(base + w.tile_off); c.xn = (float*)(base + w.xn);
     c.split = (void*)(base + w.split); c.max_tiles = (int64_t)w.max_tiles;
+    if (w.use_big) return dev(launch_cluster_big(*b, c, w.big, base, st));
     return dev(launch_cluster(*b, c, st));
 }
 
@@ -128,7 +132,7 @@ static kb_status do_ucb(const kb_batch* b, const kb_params* p, const int32_t* as
     char* base = (char*)ws;
     int32_t* order = (int32_t*)(base + w.order);
     if (!have_order) {
-        hipError_t e = launch_order(*b, order, (int32_t*)(base + w.tile_off), st);
+        hipError_t e = launch_order(*b, order, (int32_t*)(base + w.tile_off), nullptr, st);
         if (e != hipSuccess) return KB_EDEVICE;
     }
     UcbCall c;

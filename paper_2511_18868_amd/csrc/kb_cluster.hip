@@ -26,14 +26,11 @@
 //
 // New centroid = (fixed-point sum / 2^shift) / count in fp64, rounded once to
 // fp32; an empty cluster keeps its centroid.
-#include "kb_internal.h"
+#include "kb_cluster_dev.h"
 
 namespace kb {
 
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 struct ClusterArgs {
     int G, D, Ksum, Kmax;
@@ -58,9 +55,7 @@ struct ClusterArgs {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
-constexpr int kFlagBit = (int)0x80000000u;
 constexpr int kFlagCap = 256;      // LDS list of candidates waiting for the exact pass
-constexpr float kBig = 1.0e30f;    // score of a centroid row that does not exist
 
 __device__ __forceinline__ float wave_max_f(float v) {
 #pragma unroll
@@ -110,19 +105,6 @@ __device__ __forceinline__ int block_or_i(int v, double* red, int& phase) {
     return r;
 }
 
-// Fixed-point image of one feature value: floor(x * 2^sh) as a 64-bit integer.
-// x * scale is exact (power-of-two scale); it is cut into a high and a low
-// 32-bit half with exact fp64 operations, so only the final cut below one unit
-// of the fixed-point grid rounds (toward -inf, the same way every time a value
-// is added or taken away).
-__device__ __forceinline__ long long to_fixed(float x, double scale) {
-    const double d = (double)x * scale;
-    const double hi = floor(d * 2.3283064365386963e-10);          // d / 2^32
-    const double lo = fma(hi, -4294967296.0, d);                   // in [0, 2^32)
-    const int ihi = __double2int_rz(hi);
-    const unsigned ilo = __double2uint_rz(lo);
-    return (long long)(((unsigned long long)(unsigned)ihi << 32) | ilo);
-}
 __device__ __forceinline__ void lds_add(long long* p, long long q) {
     atomicAdd(reinterpret_cast<unsigned long long*>(p), (unsigned long long)q);
 }
@@ -205,15 +187,6 @@ __device__ __forceinline__ void score_valu(const ClusterArgs& a, const float* __
 // for the whole step; a wave walks over tiles of 32 candidates.  Candidates the
 // scorer is certain about and whose cluster changed are moved between the
 // fixed-point sums right here, from the registers that hold their features.
-__device__ __forceinline__ void split8(const float (&v)[8], bf16x8& hi, bf16x8& mid) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const __bf16 h = (__bf16)v[i];
-        hi[i] = h;
-        mid[i] = (__bf16)(v[i] - (float)h);
-    }
-}
-
 // The feature rows are split once per call (presplit) into a workspace laid out
 // in operand order - [tile][K-step][hi|mid][lane] x 16 bytes - so a step streams
 // them back with fully coalesced 1 KB loads and no conversion work, and the next

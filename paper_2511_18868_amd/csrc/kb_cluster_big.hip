@@ -1,0 +1,614 @@
+// K-Means (Lloyd) clustering, multi-workgroup path: for searches too large for
+// one workgroup or with more than 64 clusters (Sec. 3.3; L2 norm of Eq. 3).
+//
+// Same three phases per step as the one-workgroup kernel - fast matrix-core
+// scores with a proved error bound, exact fp64 re-evaluation of the doubtful
+// candidates, and 64-bit fixed-point centroid sums moved by integer atomics
+// (order-independent, so results are bit-identical from run to run) - but every
+// phase is its own launch and the shared state lives in global memory:
+//
+//   init      centroids <- initial rows, sums/counts <- 0, assign <- -1
+//   presplit  feature rows -> bf16 (hi, mid) operand-ordered tiles, |x|^2, max|x|
+//   per step:
+//     renew   centroid = sum/count for clusters whose membership changed, then
+//             |c|^2 and the split centroid operands (-2c) of those clusters
+//     score   one workgroup per chunk of 32 tiles of one search: centroid
+//             operands staged in LDS, bf16x3 MFMA scores, running best/second
+//             over the centroid tiles, sums updated with global atomics for the
+//             candidates that are certain, the others appended to a list
+//     exact   fp64 direct-difference distances for the listed candidates
+//   objective (before the last renewal, so it refers to the centroids that
+//             entered the last step), then the last renewal.
+#include "kb_cluster_dev.h"
+
+namespace kb {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+
+struct BigArgs {
+    int G, D, Ksum, Kmax, Kpad, it, final_pass;
+    int64_t N, max_tiles;
+    const int32_t* seg_off;
+    const int32_t* koff;
+    const float* X;
+    const float* cent_init;
+    int32_t* assign;
+    float* cent;
+    int32_t* counts;
+    float* objective;
+    const int32_t* tile_off;
+    const int32_t* chunk_off;
+    float* xn;
+    bf16x8* split;
+    long long* sums;        // [Ksum][D]
+    float* cnpad;           // [G][Kpad]
+    bf16x8* aop;            // [G][Kpad/32][DS][2][64]
+    int* dirty;             // [Ksum]
+    unsigned* amax_bits;    // [G]
+    unsigned* cnmax_bits;   // [2][G]
+    int* nflag;             // [1]
+    int32_t* flist;         // [N] global candidate indices
+    double* partJ;          // [chunks]
+};
+
+// largest g with off[g] <= v (off non-decreasing, off[0] = 0, v < off[G])
+__device__ __forceinline__ int upper_search(const int32_t* off, int G, int64_t v) {
+    int lo = 0, hi = G;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if ((int64_t)off[mid] <= v) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ double wave_sum_d(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+__global__ void __launch_bounds__(kThreads) big_init(BigArgs a) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int D = a.D;
+    for (int64_t idx = t0; idx < (int64_t)a.Ksum * D; idx += stride) {
+        const int r = (int)(idx / D), d = (int)(idx - (int64_t)r * D);
+        float v;
+        if (a.cent_init) {
+            v = a.cent_init[idx];
+        } else {
+            const int g = upper_search(a.koff, a.G, r);
+            int n0, ng, k0, K;
+            search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+            const int j = r - k0;
+            v = ng > 0 ? a.X[(size_t)(n0 + (j < ng ? j : ng - 1)) * D + d] : 0.f;
+        }
+        a.cent[idx] = v;
+        a.sums[idx] = 0;
+    }
+    if (a.it < 0) return;   // iters == 0: only the initial centroids
+    for (int64_t r = t0; r < a.Ksum; r += stride) { a.counts[r] = 0; a.dirty[r] = 0; }
+    for (int64_t k = t0; k < a.N; k += stride) a.assign[k] = -1;
+    for (int64_t g = t0; g < a.G; g += stride) {
+        a.amax_bits[g] = 0u;
+        a.cnmax_bits[g] = 0u;
+        a.cnmax_bits[a.G + g] = 0u;
+    }
+    if (t0 == 0) *a.nflag = 0;
+}
+
+template <int DS>
+__global__ void __launch_bounds__(kThreads) big_presplit(BigArgs a) {
+    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    const int m = lane & 31, h = lane >> 5;
+    const int64_t gt = (int64_t)blockIdx.x * kWaves + wid;
+    if (gt >= a.tile_off[a.G] || gt >= a.max_tiles) return;
+    const int g = upper_search(a.tile_off, a.G, gt);
+    int n0, ng, k0, K;
+    search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+    const int tile = (int)(gt - a.tile_off[g]);
+    if (tile * 32 >= ng) return;
+    const int D = a.D;
+    const bool vec = (D & 3) == 0;
+    const int p = tile * 32 + m;
+    const bool valid = p < ng;
+    const float* xr = a.X + (size_t)(n0 + (valid ? p : 0)) * D;
+    bf16x8* tp = a.split + (size_t)gt * (DS * 2 * 64) + lane;
+    float xnp = 0.f, am = 0.f;
+#pragma unroll
+    for (int s = 0; s < DS; ++s) {
+        const int d0 = 16 * s + 8 * h;
+        float x[8];
+        if (vec) {
+            float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
+            if (valid && d0 < D) v0 = *reinterpret_cast<const float4*>(xr + d0);
+            if (valid && d0 + 4 < D) v1 = *reinterpret_cast<const float4*>(xr + d0 + 4);
+            x[0] = v0.x; x[1] = v0.y; x[2] = v0.z; x[3] = v0.w;
+            x[4] = v1.x; x[5] = v1.y; x[6] = v1.z; x[7] = v1.w;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x[i] = (valid && d0 + i < D) ? xr[d0 + i] : 0.f;
+        }
+        bf16x8 hi, mid;
+        split8(x, hi, mid);
+        tp[(2 * s) * 64] = hi;
+        tp[(2 * s + 1) * 64] = mid;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            xnp = fmaf(x[i], x[i], xnp);
+            am = fmaxf(am, fabsf(x[i]));
+        }
+    }
+    xnp += __shfl_xor(xnp, 32);
+    if (valid && h == 0) a.xn[(size_t)n0 + p] = xnp;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) am = fmaxf(am, __shfl_xor(am, o));
+    // non-negative floats order like their bit patterns
+    if (lane == 0) atomicMax(&a.amax_bits[g], __float_as_uint(am));
+}
+
+// One wave per (search, padded centroid row).
+template <int DS>
+__global__ void __launch_bounds__(kThreads) big_renew(BigArgs a) {
+    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    const int64_t r = (int64_t)blockIdx.x * kWaves + wid;
+    if (r >= (int64_t)a.G * a.Kpad) return;
+    const int g = (int)(r / a.Kpad), j = (int)(r - (int64_t)g * a.Kpad);
+    int n0, ng, k0, K;
+    search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+    if (K > a.Kpad) K = a.Kpad;
+    const int D = a.D;
+    const int mt = j >> 5, lane_row = j & 31;
+    __bf16* ap = reinterpret_cast<__bf16*>(a.aop + (size_t)g * (a.Kpad / 32) * (DS * 2 * 64));
+    auto store_operand = [&](float v) {
+        // feature `lane` of row j: K-step s, half h, element i of the 16-byte entry
+        if (lane < 16 * DS) {
+            const int s = lane >> 4, h = (lane >> 3) & 1, i = lane & 7;
+            const __bf16 hi = (__bf16)v;
+            const __bf16 mid = (__bf16)(v - (float)hi);
+            const size_t e = (((size_t)(mt * DS + s) * 2) * 64 + (lane_row + 32 * h)) * 8 + i;
+            ap[e] = hi;
+            ap[e + 64 * 8] = mid;
+        }
+    };
+    if (j >= K || ng <= 0) {
+        if (a.it == 0 && !a.final_pass) {
+            if (lane == 0) a.cnpad[r] = kBig;
+            store_operand(0.f);
+        }
+        return;
+    }
+    const int row = k0 + j;
+    const int was_dirty = a.dirty[row];
+    if ((a.it > 0 || a.final_pass) && was_dirty) {
+        const int c = a.counts[row];
+        if (c > 0 && lane < D) {
+            const int sh = fixed_shift(__uint_as_float(a.amax_bits[g]), ng);
+            const double inv = ldexp(1.0, -sh);
+            a.cent[(size_t)row * D + lane] =
+                (float)(((double)a.sums[(size_t)row * D + lane] * inv) / (double)c);
+        }
+    }
+    if (a.final_pass) return;
+    float f;
+    if (a.it == 0 || was_dirty) {
+        const float c = lane < D ? a.cent[(size_t)row * D + lane] : 0.f;
+        f = (float)wave_sum_d((double)c * (double)c);
+        if (lane == 0) a.cnpad[r] = f;
+        store_operand(-2.f * c);
+    } else {
+        f = a.cnpad[r];
+    }
+    if (lane == 0) {
+        a.dirty[row] = 0;
+        atomicMax(&a.cnmax_bits[(a.it & 1) * a.G + g], __float_as_uint(f));
+        if (j == 0) a.cnmax_bits[((a.it + 1) & 1) * a.G + g] = 0u;
+        if (r == 0) *a.nflag = 0;
+    }
+}
+
+// One workgroup per chunk of kTilesPerChunk tiles of one search.
+template <int DS>
+__global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+    const int m = lane & 31, h = lane >> 5;
+    const int c = blockIdx.x;
+    if (c >= a.chunk_off[a.G]) return;
+    const int g = upper_search(a.chunk_off, a.G, c);
+    int n0, ng, k0, K;
+    search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+    if (K > a.Kpad) K = a.Kpad;
+    if (ng <= 0 || K <= 0) return;
+    const int ntiles = (ng + 31) >> 5;
+    const int t0 = (c - a.chunk_off[g]) * kTilesPerChunk;
+    const int t1 = t0 + kTilesPerChunk < ntiles ? t0 + kTilesPerChunk : ntiles;
+    const int64_t tb = a.tile_off[g];
+    if (t0 >= t1 || tb + ntiles > a.max_tiles) return;
+    const int D = a.D;
+    const int mtiles = (K + 31) >> 5;
+    const bool first = a.it == 0;
+    const bool vec = (D & 3) == 0;
+
+    // stage this search's centroid operands and padded |c|^2 in LDS
+    bf16x8* aop = reinterpret_cast<bf16x8*>(smem);
+    float* cn = reinterpret_cast<float*>(smem + (size_t)(a.Kpad / 32) * DS * 2 * 64 * 16);
+    {
+        const bf16x8* src = a.aop + (size_t)g * (a.Kpad / 32) * (DS * 2 * 64);
+        for (int i = tid; i < mtiles * DS * 2 * 64; i += kThreads) aop[i] = src[i];
+        for (int i = tid; i < mtiles * 32; i += kThreads) cn[i] = a.cnpad[(size_t)g * a.Kpad + i];
+    }
+    __syncthreads();
+
+    const float cnmax = __uint_as_float(a.cnmax_bits[(a.it & 1) * a.G + g]);
+    const float kappa = mfma_kappa(DS);
+    const double scale = ldexp(1.0, fixed_shift(__uint_as_float(a.amax_bits[g]), ng));
+    const bf16x8* sp = a.split + (size_t)tb * (DS * 2 * 64);
+
+    auto load_tile = [&](int tile, bf16x8 (&bh)[DS], bf16x8 (&bm)[DS], float& xnv, int& oldv) {
+        const bf16x8* tp = sp + (size_t)tile * (DS * 2 * 64) + lane;
+#pragma unroll
+        for (int s = 0; s < DS; ++s) {
+            bh[s] = tp[(2 * s) * 64];
+            bm[s] = tp[(2 * s + 1) * 64];
+        }
+        const int p = tile * 32 + m;
+        xnv = 0.f;
+        oldv = -1;
+        if (p < ng) {
+            xnv = a.xn[(size_t)n0 + p];
+            if (!first) oldv = a.assign[(size_t)n0 + p];
+        }
+    };
+
+    bf16x8 Bh[DS], Bm[DS];
+    float xn = 0.f;
+    int old = -1;
+    if (t0 + wid < t1) load_tile(t0 + wid, Bh, Bm, xn, old);
+    for (int tile = t0 + wid; tile < t1; tile += kWaves) {
+        const int p = tile * 32 + m;
+        const bool valid = p < ng;
+        bf16x8 Bh2[DS], Bm2[DS];
+        float xn2 = 0.f;
+        int old2 = -1;
+        const bool more = tile + kWaves < t1;
+        if (more) load_tile(tile + kWaves, Bh2, Bm2, xn2, old2);
+        old = (old >= 0 && old < K) ? old : -1;
+
+        // running (best, second, row) over the centroid tiles, two tiles at a time
+        float best = kBig * 4.f, second = kBig * 4.f;
+        int bi = 0;
+        for (int mt = 0; mt < mtiles; mt += 2) {
+            const bool two = mt + 1 < mtiles;
+            f32x16 acc[2];
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const float4 c4 = *reinterpret_cast<const float4*>(cn + mt * 32 + 8 * g4 + 4 * h);
+                acc[0][4 * g4 + 0] = c4.x; acc[0][4 * g4 + 1] = c4.y;
+                acc[0][4 * g4 + 2] = c4.z; acc[0][4 * g4 + 3] = c4.w;
+            }
+            float cb[4], cs[4];
+            int ci[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) { cb[q] = kBig * 4.f; cs[q] = kBig * 4.f; ci[q] = 0; }
+            if (two) {
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const float4 c4 = *reinterpret_cast<const float4*>(cn + (mt + 1) * 32 + 8 * g4 + 4 * h);
+                    acc[1][4 * g4 + 0] = c4.x; acc[1][4 * g4 + 1] = c4.y;
+                    acc[1][4 * g4 + 2] = c4.z; acc[1][4 * g4 + 3] = c4.w;
+                }
+#pragma unroll
+                for (int s = 0; s < DS; ++s) {
+                    const bf16x8 a0h = aop[((mt * DS + s) * 2 + 0) * 64 + lane];
+                    const bf16x8 a0m = aop[((mt * DS + s) * 2 + 1) * 64 + lane];
+                    const bf16x8 a1h = aop[(((mt + 1) * DS + s) * 2 + 0) * 64 + lane];
+                    const bf16x8 a1m = aop[(((mt + 1) * DS + s) * 2 + 1) * 64 + lane];
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bh[s], acc[0], 0, 0, 0);
+                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, Bh[s], acc[1], 0, 0, 0);
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bm[s], acc[0], 0, 0, 0);
+                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, Bm[s], acc[1], 0, 0, 0);
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0m, Bh[s], acc[0], 0, 0, 0);
+                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1m, Bh[s], acc[1], 0, 0, 0);
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const int q = 2 * t + (r >> 3);
+                        const float v = acc[t][r];
+                        const bool lt = v < cb[q];
+                        cs[q] = __builtin_amdgcn_fmed3f(cb[q], cs[q], v);
+                        cb[q] = lt ? v : cb[q];
+                        ci[q] = lt ? (t * 32 + 8 * (r >> 2) + (r & 3)) : ci[q];
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[1][r] = 0.f;
+#pragma unroll
+                for (int s = 0; s < DS; ++s) {
+                    const bf16x8 a0h = aop[((mt * DS + s) * 2 + 0) * 64 + lane];
+                    const bf16x8 a0m = aop[((mt * DS + s) * 2 + 1) * 64 + lane];
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bh[s], acc[0], 0, 0, 0);
+                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bm[s], acc[1], 0, 0, 0);
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0m, Bh[s], acc[0], 0, 0, 0);
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int q = r >> 2;
+                    const float v = acc[0][r] + acc[1][r];
+                    const bool lt = v < cb[q];
+                    cs[q] = __builtin_amdgcn_fmed3f(cb[q], cs[q], v);
+                    cb[q] = lt ? v : cb[q];
+                    ci[q] = lt ? (8 * (r >> 2) + (r & 3)) : ci[q];
+                }
+            }
+            merge_best(cb[0], cs[0], ci[0], cb[1], cs[1], ci[1]);
+            merge_best(cb[2], cs[2], ci[2], cb[3], cs[3], ci[3]);
+            merge_best(cb[0], cs[0], ci[0], cb[2], cs[2], ci[2]);
+            merge_best(best, second, bi, cb[0], cs[0], ci[0] + mt * 32);
+        }
+        bi += 4 * h;
+        {
+            const auto rb = __builtin_amdgcn_permlane32_swap(__float_as_uint(best), __float_as_uint(best), false, false);
+            const auto rs = __builtin_amdgcn_permlane32_swap(__float_as_uint(second), __float_as_uint(second), false, false);
+            const auto ri = __builtin_amdgcn_permlane32_swap((unsigned)bi, (unsigned)bi, false, false);
+            float b0 = __uint_as_float(rb[0]), s0 = __uint_as_float(rs[0]);
+            int i0 = (int)ri[0];
+            merge_best(b0, s0, i0, __uint_as_float(rb[1]), __uint_as_float(rs[1]), (int)ri[1]);
+            best = b0; second = s0; bi = i0;
+        }
+        bi = bi < K ? bi : 0;
+        const float E = kappa * (xn + cnmax);
+        const bool certain = (K == 1) || ((second - best) > 2.f * E);
+        const bool chg = valid && certain && (bi != old);
+        if (chg) {
+            const float* xr = a.X + (size_t)(n0 + p) * D;
+            float xv[DS][8];
+#pragma unroll
+            for (int s = 0; s < DS; ++s) {
+                const int d0 = 16 * s + 8 * h;
+                if (vec) {
+                    float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
+                    if (d0 < D) v0 = *reinterpret_cast<const float4*>(xr + d0);
+                    if (d0 + 4 < D) v1 = *reinterpret_cast<const float4*>(xr + d0 + 4);
+                    xv[s][0] = v0.x; xv[s][1] = v0.y; xv[s][2] = v0.z; xv[s][3] = v0.w;
+                    xv[s][4] = v1.x; xv[s][5] = v1.y; xv[s][6] = v1.z; xv[s][7] = v1.w;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) xv[s][i] = (d0 + i < D) ? xr[d0 + i] : 0.f;
+                }
+            }
+            unsigned long long* sn = reinterpret_cast<unsigned long long*>(a.sums + (size_t)(k0 + bi) * D);
+            unsigned long long* so = reinterpret_cast<unsigned long long*>(a.sums + (size_t)(k0 + (old >= 0 ? old : 0)) * D);
+#pragma unroll
+            for (int s = 0; s < DS; ++s) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int d = 16 * s + 8 * h + i;
+                    if (d < D) {
+                        const long long q = to_fixed(xv[s][i], scale);
+                        atomicAdd(sn + d, (unsigned long long)q);
+                        if (old >= 0) atomicAdd(so + d, (unsigned long long)(-q));
+                    }
+                }
+            }
+            if (h == 0) {
+                atomicAdd(&a.counts[k0 + bi], 1);
+                a.dirty[k0 + bi] = 1;
+                if (old >= 0) { atomicSub(&a.counts[k0 + old], 1); a.dirty[k0 + old] = 1; }
+                a.assign[(size_t)n0 + p] = bi;
+            }
+        }
+        if (valid && h == 0 && !certain) {
+            if (first) a.assign[(size_t)n0 + p] = -1;
+            const int pos = atomicAdd(a.nflag, 1);
+            if ((int64_t)pos < a.N) a.flist[pos] = n0 + p;
+        }
+        if (more) {
+#pragma unroll
+            for (int s = 0; s < DS; ++s) { Bh[s] = Bh2[s]; Bm[s] = Bm2[s]; }
+            xn = xn2;
+            old = old2;
+        }
+    }
+}
+
+// Exact nearest centroid for the listed candidates, one wave per candidate:
+// fp64 direct differences summed over the features in index order with separate
+// multiply and add, lowest index on ties; then the move between the sums.
+__global__ void __launch_bounds__(kThreads) big_exact(BigArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * kWaves;
+    int64_t n = *a.nflag;
+    if (n > a.N) n = a.N;
+    const int D = a.D;
+    for (int64_t i = wave; i < n; i += nwaves) {
+        const int pg = a.flist[i];
+        if (pg < 0 || pg >= a.N) continue;
+        const int g = upper_search(a.seg_off, a.G, pg);
+        int n0, ng, k0, K;
+        search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+        if (K <= 0) continue;
+        const float* xr = a.X + (size_t)pg * D;
+        const float xv = lane < D ? xr[lane] : 0.f;
+        int old = a.assign[pg];
+        double bd = INFINITY;
+        int bj = 0x7fffffff;
+        for (int j0 = 0; j0 < K; j0 += kWave) {
+            const int j = j0 + lane;
+            const float* cr = a.cent + (size_t)(k0 + (j < K ? j : 0)) * D;
+            double acc = 0.0;
+            for (int d = 0; d < D; ++d) {
+                const double diff = __dsub_rn((double)__shfl(xv, d), (double)cr[d]);
+                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+            }
+            if (j < K && acc < bd) { bd = acc; bj = j; }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const double od = __shfl_xor(bd, o);
+            const int oj = __shfl_xor(bj, o);
+            if (od < bd || (od == bd && oj < bj)) { bd = od; bj = oj; }
+        }
+        bj = bj < K ? bj : 0;
+        old = (old >= 0 && old < K) ? old : -1;
+        if (bj != old) {
+            if (lane < D) {
+                const double scale = ldexp(1.0, fixed_shift(__uint_as_float(a.amax_bits[g]), ng));
+                const long long q = to_fixed(xv, scale);
+                atomicAdd(reinterpret_cast<unsigned long long*>(a.sums + (size_t)(k0 + bj) * D + lane),
+                          (unsigned long long)q);
+                if (old >= 0)
+                    atomicAdd(reinterpret_cast<unsigned long long*>(a.sums + (size_t)(k0 + old) * D + lane),
+                              (unsigned long long)(-q));
+            }
+            if (lane == 0) {
+                atomicAdd(&a.counts[k0 + bj], 1);
+                a.dirty[k0 + bj] = 1;
+                if (old >= 0) { atomicSub(&a.counts[k0 + old], 1); a.dirty[k0 + old] = 1; }
+                a.assign[pg] = bj;
+            }
+        }
+    }
+}
+
+// Per-chunk partial objective: 16 lanes per candidate, per-lane fp64 partial
+// sums in a fixed candidate order, fixed-order reduction.
+__global__ void __launch_bounds__(kThreads) big_objective(BigArgs a) {
+    __shared__ double red[kWaves];
+    const int tid = threadIdx.x;
+    const int c = blockIdx.x;
+    if (c >= a.chunk_off[a.G]) return;
+    const int g = upper_search(a.chunk_off, a.G, c);
+    int n0, ng, k0, K;
+    search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+    const int D = a.D;
+    const int p0 = (c - a.chunk_off[g]) * kTilesPerChunk * 32;
+    const int p1 = p0 + kTilesPerChunk * 32 < ng ? p0 + kTilesPerChunk * 32 : ng;
+    const int sub = tid >> 4, l16 = tid & 15;
+    double acc = 0.0;
+    if (K > 0)
+        for (int p = p0 + sub; p < p1; p += kThreads / 16) {
+            int j = a.assign[(size_t)n0 + p];
+            j = (j >= 0 && j < K) ? j : 0;
+            const float* xr = a.X + (size_t)(n0 + p) * D;
+            const float* cr = a.cent + (size_t)(k0 + j) * D;
+            float sq = 0.f;
+            for (int d = 4 * l16; d < 4 * l16 + 4 && d < D; ++d) {
+                const float e0 = xr[d] - cr[d];
+                sq = fmaf(e0, e0, sq);
+            }
+            acc += (double)sq;
+        }
+    acc = wave_sum_d(acc);
+    if ((tid & 63) == 0) red[tid >> 6] = acc;
+    __syncthreads();
+    if (tid == 0) {
+        double r = red[0];
+        for (int w = 1; w < kWaves; ++w) r += red[w];
+        a.partJ[c] = r;
+    }
+}
+
+__global__ void __launch_bounds__(kThreads) big_objsum(BigArgs a) {
+    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= a.G) return;
+    double J = 0.0;
+    for (int c = a.chunk_off[g]; c < a.chunk_off[g + 1]; ++c) J += a.partJ[c];
+    a.objective[g] = (float)J;
+}
+
+}  // namespace
+
+static size_t al256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+BigWs big_ws_layout(const kb_batch& b, size_t base) {
+    BigWs w;
+    const size_t kpad = (size_t)((b.Kmax > 0 ? b.Kmax : 1) + 31) / 32 * 32;
+    const size_t ds = (size_t)(b.D + 15) / 16;
+    size_t off = base;
+    w.kpad = (int)kpad;
+    w.max_chunks = (size_t)(b.N / 32 + b.G) / kTilesPerChunk + (size_t)b.G + 1;
+    w.chunk_off = off; off += al256(sizeof(int32_t) * ((size_t)b.G + 1));
+    w.sums = off;      off += al256(sizeof(long long) * (size_t)(b.Ksum > 0 ? b.Ksum : 1) * b.D);
+    w.cnpad = off;     off += al256(sizeof(float) * (size_t)b.G * kpad);
+    w.aop = off;       off += al256((size_t)b.G * (kpad / 32) * ds * 2 * 64 * 16);
+    w.dirty = off;     off += al256(sizeof(int) * (size_t)(b.Ksum > 0 ? b.Ksum : 1));
+    w.amax = off;      off += al256(sizeof(unsigned) * (size_t)b.G);
+    w.cnmax = off;     off += al256(sizeof(unsigned) * 2 * (size_t)b.G);
+    w.nflag = off;     off += 256;
+    w.partJ = off;     off += al256(sizeof(double) * w.max_chunks);
+    w.end = off;
+    return w;
+}
+
+hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const BigWs& w, char* ws,
+                              hipStream_t st) {
+    BigArgs a;
+    a.G = b.G; a.D = b.D; a.Ksum = b.Ksum; a.Kmax = b.Kmax > 0 ? b.Kmax : 1; a.Kpad = w.kpad;
+    a.it = 0; a.final_pass = 0; a.N = b.N; a.max_tiles = c.max_tiles;
+    a.seg_off = b.seg_off; a.koff = b.koff; a.X = c.X; a.cent_init = c.cent_init;
+    a.assign = c.assign; a.cent = c.cent_out; a.counts = c.counts; a.objective = c.objective;
+    a.tile_off = c.tile_off; a.chunk_off = reinterpret_cast<const int32_t*>(ws + w.chunk_off);
+    a.xn = c.xn; a.split = reinterpret_cast<bf16x8*>(c.split);
+    a.sums = reinterpret_cast<long long*>(ws + w.sums);
+    a.cnpad = reinterpret_cast<float*>(ws + w.cnpad);
+    a.aop = reinterpret_cast<bf16x8*>(ws + w.aop);
+    a.dirty = reinterpret_cast<int*>(ws + w.dirty);
+    a.amax_bits = reinterpret_cast<unsigned*>(ws + w.amax);
+    a.cnmax_bits = reinterpret_cast<unsigned*>(ws + w.cnmax);
+    a.nflag = reinterpret_cast<int*>(ws + w.nflag);
+    a.flist = c.a_new;
+    a.partJ = reinterpret_cast<double*>(ws + w.partJ);
+
+    const int ds = (b.D + 15) / 16;
+    const size_t init_items = (size_t)(b.N > (int64_t)b.Ksum * b.D ? b.N : (int64_t)b.Ksum * b.D);
+    unsigned init_blocks = (unsigned)((init_items + kThreads - 1) / kThreads);
+    if (init_blocks > 65536u) init_blocks = 65536u;
+    if (init_blocks == 0) init_blocks = 1;
+    if (c.iters == 0) a.it = -1;
+    hipLaunchKernelGGL(big_init, dim3(init_blocks), dim3(kThreads), 0, st, a);
+    if (c.iters == 0) return hipGetLastError();
+    a.it = 0;
+
+    const unsigned tile_blocks = (unsigned)((c.max_tiles + kWaves - 1) / kWaves);
+    const unsigned row_blocks = (unsigned)(((size_t)b.G * w.kpad + kWaves - 1) / kWaves);
+    const unsigned chunk_blocks = (unsigned)w.max_chunks;
+    const size_t lds = (size_t)(w.kpad / 32) * ds * 2 * 64 * 16 + (size_t)w.kpad * 4;
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
+
+#define KB_BIG(DS_)                                                                              \
+    do {                                                                                         \
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(big_score<DS_>),        \
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+        if (e != hipSuccess) return e;                                                           \
+        if (tile_blocks) hipLaunchKernelGGL(big_presplit<DS_>, dim3(tile_blocks), dim3(kThreads), 0, st, a); \
+        for (int it = 0; it < c.iters; ++it) {                                                   \
+            a.it = it;                                                                           \
+            hipLaunchKernelGGL(big_renew<DS_>, dim3(row_blocks), dim3(kThreads), 0, st, a);      \
+            hipLaunchKernelGGL(big_score<DS_>, dim3(chunk_blocks), dim3(kThreads), lds, st, a);  \
+            hipLaunchKernelGGL(big_exact, dim3(512), dim3(kThreads), 0, st, a);                  \
+        }                                                                                        \
+        hipLaunchKernelGGL(big_objective, dim3(chunk_blocks), dim3(kThreads), 0, st, a);         \
+        hipLaunchKernelGGL(big_objsum, dim3((unsigned)((b.G + kThreads - 1) / kThreads)),        \
+                           dim3(kThreads), 0, st, a);                                            \
+        a.final_pass = 1;                                                                        \
+        hipLaunchKernelGGL(big_renew<DS_>, dim3(row_blocks), dim3(kThreads), 0, st, a);          \
+    } while (0)
+    switch (ds) {
+        case 1: KB_BIG(1); break;
+        case 2: KB_BIG(2); break;
+        case 3: KB_BIG(3); break;
+        default: KB_BIG(4); break;
+    }
+#undef KB_BIG
+    return hipGetLastError();
+}
+
+}  // namespace kb

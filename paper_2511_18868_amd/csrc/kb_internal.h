@@ -8,8 +8,20 @@
 namespace kb {
 
 constexpr int kWave = 64;
+constexpr int kTilesPerChunk = 32;   // tiles of 32 candidates per workgroup of the multi-workgroup clustering path
 
 // ---- workspace layout (all offsets 256-byte aligned) ------------------------
+// extra buffers of the multi-workgroup clustering path
+struct BigWs {
+    int kpad;            // Kmax rounded up to whole centroid tiles of 32
+    size_t max_chunks;   // upper bound of the number of tile chunks (grid size)
+    size_t chunk_off, sums, cnpad, aop, dirty, amax, cnmax, nflag, partJ, end;
+};
+BigWs big_ws_layout(const kb_batch& b, size_t base);
+// searches with more than 64 clusters or more than 65536 candidates take the
+// multi-workgroup path
+inline bool cluster_uses_big(const kb_batch& b) { return b.Kmax > 64 || b.Nmax > 65536; }
+
 struct WsLayout {
     size_t a_new;   // int32 [N]     proposed assignment of the current step (bit 31: needs exact re-evaluation)
     size_t order;   // int32 [G]     searches sorted by decreasing work, for longest-first scheduling
@@ -19,6 +31,8 @@ struct WsLayout {
     size_t split;   // bf16          feature rows split into bf16 (hi, mid) pieces, in matrix-core
                     //               operand order: [tile][16-feature step][hi|mid][lane][8]
     size_t max_tiles;   // capacity of `split` in tiles (not an offset)
+    bool use_big;
+    BigWs big;
     size_t total;
 };
 WsLayout ws_layout(const kb_batch& b);
@@ -29,7 +43,8 @@ hipError_t launch_prune(const kb_batch& b, float peak_flops, float peak_bw,
                         const float* incumbent, float* bound, uint8_t* alive,
                         hipStream_t st);
 
-hipError_t launch_order(const kb_batch& b, int32_t* order, int32_t* tile_off, hipStream_t st);
+hipError_t launch_order(const kb_batch& b, int32_t* order, int32_t* tile_off, int32_t* chunk_off,
+                        hipStream_t st);
 
 struct ClusterCall {
     const float* X;
@@ -47,6 +62,8 @@ struct ClusterCall {
     int64_t max_tiles;
 };
 hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t st);
+hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const BigWs& w, char* ws,
+                              hipStream_t st);
 bool cluster_supported(const kb_batch& b);
 void set_scorer(int mode);                   // 0 automatic, 1 vector ALU only   // shape fits the compiled clustering kernels
 

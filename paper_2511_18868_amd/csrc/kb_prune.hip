@@ -99,10 +99,10 @@ hipError_t launch_prune(const kb_batch& b, float peak_flops, float peak_bw, cons
 __global__ void __launch_bounds__(1024)
 order_kernel(int G, int64_t N, int Ksum, const int32_t* __restrict__ seg_off,
              const int32_t* __restrict__ koff, int32_t* __restrict__ order,
-             int32_t* __restrict__ tile_off) {
+             int32_t* __restrict__ tile_off, int32_t* __restrict__ chunk_off) {
     __shared__ int hist[64];
     __shared__ int start[64];
-    __shared__ int part[1024];
+    __shared__ long long part[1024];
     const int tid = threadIdx.x;
     // tile_off = exclusive prefix sum of ceil(N_g / 32): each thread owns a
     // contiguous chunk of searches
@@ -110,27 +110,35 @@ order_kernel(int G, int64_t N, int Ksum, const int32_t* __restrict__ seg_off,
         const int chunk = (G + (int)blockDim.x - 1) / (int)blockDim.x;
         const int lo = tid * chunk < G ? tid * chunk : G;
         const int hi = lo + chunk < G ? lo + chunk : G;
-        int local = 0;
+        // two prefix sums at once: tiles of 32 candidates, and chunks of
+        // kTilesPerChunk tiles (packed as low / high 32 bits while scanning)
+        long long local = 0;
         for (int g = lo; g < hi; ++g) {
             int n0, ng, k0, K;
             search_bounds(seg_off, koff, g, N, Ksum, n0, ng, k0, K);
-            local += (ng + 31) >> 5;
+            const int tiles = (ng + 31) >> 5;
+            local += (long long)tiles + ((long long)((tiles + kTilesPerChunk - 1) / kTilesPerChunk) << 32);
         }
         part[tid] = local;
         __syncthreads();
         if (tid == 0) {
-            int acc = 0;
-            for (int i = 0; i < (int)blockDim.x; ++i) { const int v = part[i]; part[i] = acc; acc += v; }
+            long long acc = 0;
+            for (int i = 0; i < (int)blockDim.x; ++i) { const long long v = part[i]; part[i] = acc; acc += v; }
         }
         __syncthreads();
-        int acc = part[tid];
+        long long acc = part[tid];
         for (int g = lo; g < hi; ++g) {
             int n0, ng, k0, K;
             search_bounds(seg_off, koff, g, N, Ksum, n0, ng, k0, K);
-            tile_off[g] = acc;
-            acc += (ng + 31) >> 5;
+            const int tiles = (ng + 31) >> 5;
+            tile_off[g] = (int)(acc & 0xffffffffll);
+            if (chunk_off) chunk_off[g] = (int)(acc >> 32);
+            acc += (long long)tiles + ((long long)((tiles + kTilesPerChunk - 1) / kTilesPerChunk) << 32);
         }
-        if (hi == G && lo < G) tile_off[G] = acc;
+        if (hi == G && lo < G) {
+            tile_off[G] = (int)(acc & 0xffffffffll);
+            if (chunk_off) chunk_off[G] = (int)(acc >> 32);
+        }
         if (G == 0 && tid == 0) tile_off[0] = 0;
     }
     if (tid < 64) hist[tid] = 0;
@@ -158,9 +166,10 @@ order_kernel(int G, int64_t N, int Ksum, const int32_t* __restrict__ seg_off,
     }
 }
 
-hipError_t launch_order(const kb_batch& b, int32_t* order, int32_t* tile_off, hipStream_t st) {
+hipError_t launch_order(const kb_batch& b, int32_t* order, int32_t* tile_off, int32_t* chunk_off,
+                        hipStream_t st) {
     hipLaunchKernelGGL(order_kernel, dim3(1), dim3(1024), 0, st, b.G, b.N, b.Ksum, b.seg_off,
-                       b.koff, order, tile_off);
+                       b.koff, order, tile_off, chunk_off);
     return hipGetLastError();
 }
 

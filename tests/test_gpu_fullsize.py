@@ -1,0 +1,128 @@
+"""GPU parity at the full sizes of the five benchmark configurations, in the
+launch configuration bench.py times (kb_round on the whole batch).
+
+Configurations 1 and 2 are already full size in test_gpu_parity.py.  3 and 5
+are compared with the oracle element by element.  For 4 (one search of 2^20
+candidates, 256 clusters) the oracle is evaluated on sampled candidates and
+clusters, and properties that hold at any size are checked on everything."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2511_18868_amd import synth
+from kbcheck import assert_cent_close, assert_rel_close, search_of
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def kb():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2511_18868_amd import binding
+    binding.lib()
+    binding.kb_set_scorer(0)
+    return binding
+
+
+def _sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+def _full_round_vs_oracle(kb, b, name):
+    d = kb.DeviceBatch(b)
+    d.round()
+    _sync()
+    print(f"[{name}] GPU round done, running the oracle on {b.N} candidates", flush=True)
+    ora = oracle.round_(b)
+    np.testing.assert_array_equal(d.host("bound").view(np.uint32), ora.bound.view(np.uint32))
+    np.testing.assert_array_equal(d.host("alive"), ora.alive)
+    clean = ora.dirty == 0
+    cp = clean[search_of(b.seg_off)]
+    ck = np.repeat(clean, np.diff(b.koff))
+    np.testing.assert_array_equal(d.host("assign")[cp], ora.assign[cp])
+    np.testing.assert_array_equal(d.host("counts")[ck], ora.counts[ck])
+    assert_cent_close(d.host("cent")[ck], ora.cent[ck], name)
+    assert_rel_close(d.host("objective")[clean], ora.objective[clean], what=name + " objective")
+    np.testing.assert_array_equal(d.host("Ncs")[ck], ora.Ncs[ck])
+    assert_rel_close(d.host("mu")[ck], ora.mu[ck], what="mu")
+    assert_rel_close(d.host("ucb")[ck], ora.ucb[ck], what="ucb")
+    ok = clean & (ora.near == 0)
+    np.testing.assert_array_equal(d.host("sel")[ok], ora.sel[ok])
+    # searches the oracle saw a near-tie in: still a valid clustering state
+    a, cnt = d.host("assign"), d.host("counts")
+    for g in np.where(~clean)[0]:
+        K = b.koff[g + 1] - b.koff[g]
+        np.testing.assert_array_equal(cnt[b.koff[g]:b.koff[g + 1]],
+                                      np.bincount(a[b.seg_off[g]:b.seg_off[g + 1]], minlength=K))
+    same = sum(np.array_equal(a[b.seg_off[g]:b.seg_off[g + 1]], ora.assign[b.seg_off[g]:b.seg_off[g + 1]])
+               for g in np.where(~clean)[0])
+    print(f"[{name}] {b.G} searches: {int(clean.sum())} compared bit-exactly, {int((~clean).sum())} "
+          f"excluded as near-tie (of which {same} match anyway), {int((ora.near != 0).sum())} "
+          f"selections excluded as near-tie", flush=True)
+    assert clean.mean() > 0.9
+
+
+def test_config3_full(kb):
+    _full_round_vs_oracle(kb, synth.config3(), "config3")
+
+
+def test_config5_full(kb):
+    _full_round_vs_oracle(kb, synth.config5(), "config5")
+
+
+def test_config4_full(kb):
+    import torch
+    b = synth.config4()
+    d = kb.DeviceBatch(b)
+    X64 = None
+    rng = np.random.default_rng(0)
+    sample = np.sort(rng.choice(b.N, size=4096, replace=False))
+    sub_seg = np.array([0, len(sample)], np.int32)
+
+    def check_step(assign, cent_in, cent_out, counts, objective, what):
+        # sampled candidates: the oracle's nearest centroid
+        a_s, _, flag = oracle.assign(sub_seg, b.koff, b.X[sample], cent_in)
+        okm = flag == 0
+        np.testing.assert_array_equal(assign[sample][okm], a_s[okm], err_msg=what)
+        assert okm.mean() > 0.99
+        # everything: sizes, centroid = mean of members, objective by definition
+        np.testing.assert_array_equal(counts, np.bincount(assign, minlength=b.Ksum))
+        upd, cnt2 = oracle.update(b.seg_off, b.koff, b.X, cent_in, assign)
+        assert_cent_close(cent_out, upd, what)
+        diff = b.X.astype(np.float64) - cent_in.astype(np.float64)[assign]
+        J = float(np.einsum("ij,ij->", diff, diff))
+        assert_rel_close(objective, np.array([J]), what=what + " objective")
+
+    # one step from random centroids
+    cin = synth.random_centroids(b, 3)
+    d.cluster_step(torch.from_numpy(cin).to(d.device))
+    _sync()
+    check_step(d.host("assign"), cin, d.host("cent"), d.host("counts"), d.host("objective"),
+               "config4 step")
+    # the full round; its clustering is checked against the 9-step centroids
+    d9 = kb.DeviceBatch(b, iters=b.iters - 1)
+    d9.cluster()
+    d.round()
+    _sync()
+    bound, alive = oracle.prune(b.seg_off, b.flops, b.bytes_, b.peak_flops, b.peak_bw, b.incumbent)
+    np.testing.assert_array_equal(d.host("bound").view(np.uint32), bound.view(np.uint32))
+    np.testing.assert_array_equal(d.host("alive"), alive)
+    check_step(d.host("assign"), d9.host("cent"), d.host("cent"), d.host("counts"),
+               d.host("objective"), "config4 last step")
+    assert d.host("objective")[0] <= d9.host("objective")[0] * (1 + 1e-6)
+    u = oracle.ucb_select(b.seg_off, b.koff, b.S, d.host("assign"), alive, bound, b.visits, b.rsum,
+                          b.t, b.c)
+    np.testing.assert_array_equal(d.host("Ncs"), u.Ncs)
+    assert_rel_close(d.host("mu"), u.mu, what="mu")
+    assert_rel_close(d.host("ucb"), u.ucb, what="ucb")
+    if not u.near[0]:
+        np.testing.assert_array_equal(d.host("sel"), u.sel)
+    # determinism of the multi-workgroup path
+    first = {k: d.host(k).copy() for k in ("assign", "cent", "counts", "objective", "sel")}
+    d.round()
+    _sync()
+    for k, v in first.items():
+        np.testing.assert_array_equal(d.host(k).view(np.uint8), v.view(np.uint8), err_msg=k)

@@ -33,6 +33,11 @@ SMALL = {
     "cfg5s": lambda: synth.config5(G=96),
     "paper": lambda: synth.paper_shape(),
     "ragged": lambda: synth.config5(G=17, nmin=64, nmax=700, D=20, S=6, seed=99),
+    # shapes that take the multi-workgroup clustering path (more than 64 clusters,
+    # or a search of more than 65536 candidates)
+    "cfg4s": lambda: synth.config4(N=8192, K=256, ncentres=256),
+    "bigmulti": lambda: synth.config5(G=5, nmin=1500, nmax=5000, kcap=128, D=40, S=4, iters=8, seed=77),
+    "bigN": lambda: synth.config2(N=70001, D=16, K=8, S=4, iters=6, seed=5),
 }
 
 
