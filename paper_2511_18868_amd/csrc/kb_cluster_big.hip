@@ -51,6 +51,7 @@ struct BigArgs {
     unsigned* cnmax_bits;   // [2][G]
     int* nflag;             // [1]
     int32_t* flist;         // [N] global candidate indices
+    int32_t* prop;          // [N] proposed cluster of every candidate in this step
     double* partJ;          // [chunks]
 };
 
@@ -230,9 +231,6 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
     if (t0 >= t1 || tb + ntiles > a.max_tiles) return;
     const int D = a.D;
     const int mtiles = (K + 31) >> 5;
-    const bool first = a.it == 0;
-    const bool vec = (D & 3) == 0;
-
     // stage this search's centroid operands and padded |c|^2 in LDS
     bf16x8* aop = reinterpret_cast<bf16x8*>(smem);
     float* cn = reinterpret_cast<float*>(smem + (size_t)(a.Kpad / 32) * DS * 2 * 64 * 16);
@@ -245,7 +243,6 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
 
     const float cnmax = __uint_as_float(a.cnmax_bits[(a.it & 1) * a.G + g]);
     const float kappa = mfma_kappa(DS);
-    const double scale = ldexp(1.0, fixed_shift(__uint_as_float(a.amax_bits[g]), ng));
     const bf16x8* sp = a.split + (size_t)tb * (DS * 2 * 64);
 
     auto load_tile = [&](int tile, bf16x8 (&bh)[DS], bf16x8 (&bm)[DS], float& xnv, int& oldv) {
@@ -256,12 +253,8 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
             bm[s] = tp[(2 * s + 1) * 64];
         }
         const int p = tile * 32 + m;
-        xnv = 0.f;
+        xnv = p < ng ? a.xn[(size_t)n0 + p] : 0.f;
         oldv = -1;
-        if (p < ng) {
-            xnv = a.xn[(size_t)n0 + p];
-            if (!first) oldv = a.assign[(size_t)n0 + p];
-        }
     };
 
     bf16x8 Bh[DS], Bm[DS];
@@ -276,8 +269,6 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
         int old2 = -1;
         const bool more = tile + kWaves < t1;
         if (more) load_tile(tile + kWaves, Bh2, Bm2, xn2, old2);
-        old = (old >= 0 && old < K) ? old : -1;
-
         // running (best, second, row) over the centroid tiles, two tiles at a time
         float best = kBig * 4.f, second = kBig * 4.f;
         int bi = 0;
@@ -365,49 +356,14 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
         bi = bi < K ? bi : 0;
         const float E = kappa * (xn + cnmax);
         const bool certain = (K == 1) || ((second - best) > 2.f * E);
-        const bool chg = valid && certain && (bi != old);
-        if (chg) {
-            const float* xr = a.X + (size_t)(n0 + p) * D;
-            float xv[DS][8];
-#pragma unroll
-            for (int s = 0; s < DS; ++s) {
-                const int d0 = 16 * s + 8 * h;
-                if (vec) {
-                    float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
-                    if (d0 < D) v0 = *reinterpret_cast<const float4*>(xr + d0);
-                    if (d0 + 4 < D) v1 = *reinterpret_cast<const float4*>(xr + d0 + 4);
-                    xv[s][0] = v0.x; xv[s][1] = v0.y; xv[s][2] = v0.z; xv[s][3] = v0.w;
-                    xv[s][4] = v1.x; xv[s][5] = v1.y; xv[s][6] = v1.z; xv[s][7] = v1.w;
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) xv[s][i] = (d0 + i < D) ? xr[d0 + i] : 0.f;
-                }
+        // the proposal of every candidate goes to `prop`; the doubtful ones are
+        // listed for the exact pass, which overwrites their proposal
+        if (valid && h == 0) {
+            a.prop[(size_t)n0 + p] = bi;
+            if (!certain) {
+                const int pos = atomicAdd(a.nflag, 1);
+                if ((int64_t)pos < a.N) a.flist[pos] = n0 + p;
             }
-            unsigned long long* sn = reinterpret_cast<unsigned long long*>(a.sums + (size_t)(k0 + bi) * D);
-            unsigned long long* so = reinterpret_cast<unsigned long long*>(a.sums + (size_t)(k0 + (old >= 0 ? old : 0)) * D);
-#pragma unroll
-            for (int s = 0; s < DS; ++s) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int d = 16 * s + 8 * h + i;
-                    if (d < D) {
-                        const long long q = to_fixed(xv[s][i], scale);
-                        atomicAdd(sn + d, (unsigned long long)q);
-                        if (old >= 0) atomicAdd(so + d, (unsigned long long)(-q));
-                    }
-                }
-            }
-            if (h == 0) {
-                atomicAdd(&a.counts[k0 + bi], 1);
-                a.dirty[k0 + bi] = 1;
-                if (old >= 0) { atomicSub(&a.counts[k0 + old], 1); a.dirty[k0 + old] = 1; }
-                a.assign[(size_t)n0 + p] = bi;
-            }
-        }
-        if (valid && h == 0 && !certain) {
-            if (first) a.assign[(size_t)n0 + p] = -1;
-            const int pos = atomicAdd(a.nflag, 1);
-            if ((int64_t)pos < a.N) a.flist[pos] = n0 + p;
         }
         if (more) {
 #pragma unroll
@@ -437,16 +393,32 @@ __global__ void __launch_bounds__(kThreads) big_exact(BigArgs a) {
         if (K <= 0) continue;
         const float* xr = a.X + (size_t)pg * D;
         const float xv = lane < D ? xr[lane] : 0.f;
-        int old = a.assign[pg];
         double bd = INFINITY;
         int bj = 0x7fffffff;
         for (int j0 = 0; j0 < K; j0 += kWave) {
             const int j = j0 + lane;
             const float* cr = a.cent + (size_t)(k0 + (j < K ? j : 0)) * D;
+            // the lane's centroid row goes to registers first (independent loads)
+            float c[KB_MAX_D];
+            if ((D & 3) == 0) {
+#pragma unroll
+                for (int q = 0; q < KB_MAX_D / 4; ++q) {
+                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (4 * q < D) v = *reinterpret_cast<const float4*>(cr + 4 * q);
+                    c[4 * q] = v.x; c[4 * q + 1] = v.y; c[4 * q + 2] = v.z; c[4 * q + 3] = v.w;
+                }
+            } else {
+#pragma unroll
+                for (int d = 0; d < KB_MAX_D; ++d) c[d] = d < D ? cr[d] : 0.f;
+            }
+            // features beyond D are 0 on both sides: their terms add +0.0
             double acc = 0.0;
-            for (int d = 0; d < D; ++d) {
-                const double diff = __dsub_rn((double)__shfl(xv, d), (double)cr[d]);
-                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+#pragma unroll
+            for (int d = 0; d < KB_MAX_D; ++d) {
+                if (d < ((D + 3) & ~3)) {
+                    const double diff = __dsub_rn((double)__shfl(xv, d), (double)c[d]);
+                    acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                }
             }
             if (j < K && acc < bd) { bd = acc; bj = j; }
         }
@@ -456,26 +428,95 @@ __global__ void __launch_bounds__(kThreads) big_exact(BigArgs a) {
             const int oj = __shfl_xor(bj, o);
             if (od < bd || (od == bd && oj < bj)) { bd = od; bj = oj; }
         }
-        bj = bj < K ? bj : 0;
-        old = (old >= 0 && old < K) ? old : -1;
-        if (bj != old) {
-            if (lane < D) {
-                const double scale = ldexp(1.0, fixed_shift(__uint_as_float(a.amax_bits[g]), ng));
-                const long long q = to_fixed(xv, scale);
-                atomicAdd(reinterpret_cast<unsigned long long*>(a.sums + (size_t)(k0 + bj) * D + lane),
-                          (unsigned long long)q);
-                if (old >= 0)
-                    atomicAdd(reinterpret_cast<unsigned long long*>(a.sums + (size_t)(k0 + old) * D + lane),
-                              (unsigned long long)(-q));
+        if (lane == 0) a.prop[pg] = bj < K ? bj : 0;
+    }
+}
+
+// Move the candidates whose proposal differs from their recorded cluster.  A
+// workgroup owns a group of kRowsPerGroup clusters of one search and a range of
+// its candidates: it scans the (recorded, proposed) pairs of the range, adds or
+// subtracts the rows that concern its clusters in LDS (integer atomics), and
+// flushes its partial sums to the global fixed-point sums once.  The last
+// cluster group of a range also records the new assignment.
+constexpr int kRowsPerGroup = 16;
+constexpr int kUpdateRange = 16384;   // candidates per workgroup
+__global__ void __launch_bounds__(kThreads) big_update(BigArgs a) {
+    __shared__ long long lsum[kRowsPerGroup * KB_MAX_D];
+    __shared__ int lcnt[kRowsPerGroup];
+    __shared__ int ltouched[kRowsPerGroup];
+    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+    // blockIdx.x = (range chunk over all candidates), blockIdx.y = cluster group
+    const int64_t r0 = (int64_t)blockIdx.x * kUpdateRange;
+    if (r0 >= a.N) return;
+    const int64_t r1 = r0 + kUpdateRange < a.N ? r0 + kUpdateRange : a.N;
+    const int jg0 = blockIdx.y * kRowsPerGroup;
+    const int D = a.D;
+    const bool first = a.it == 0;
+    // a range may span several searches: handle them one after the other
+    int g = upper_search(a.seg_off, a.G, r0);
+    for (; g < a.G; ++g) {
+        int n0, ng, k0, K;
+        search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+        if (n0 >= r1) break;
+        if (jg0 >= K || ng <= 0) continue;
+        const int64_t q0 = r0 > n0 ? r0 : n0;
+        const int64_t q1 = r1 < (int64_t)n0 + ng ? r1 : (int64_t)n0 + ng;
+        if (q0 >= q1) continue;
+        const int rows = K - jg0 < kRowsPerGroup ? K - jg0 : kRowsPerGroup;
+        for (int i = tid; i < rows * D; i += kThreads) lsum[i] = 0;
+        if (tid < kRowsPerGroup) { lcnt[tid] = 0; ltouched[tid] = 0; }
+        __syncthreads();
+        const double scale = ldexp(1.0, fixed_shift(__uint_as_float(a.amax_bits[g]), ng));
+        for (int64_t base = q0 + wid * kWave; base < q1; base += kThreads) {
+            const int64_t k = base + lane;
+            int na = -1, oa = -1;
+            if (k < q1) {
+                na = a.prop[k];
+                na = (na >= 0 && na < K) ? na : 0;
+                oa = first ? -1 : a.assign[k];
+                oa = (oa >= 0 && oa < K) ? oa : -1;
             }
-            if (lane == 0) {
-                atomicAdd(&a.counts[k0 + bj], 1);
-                a.dirty[k0 + bj] = 1;
-                if (old >= 0) { atomicSub(&a.counts[k0 + old], 1); a.dirty[k0 + old] = 1; }
-                a.assign[pg] = bj;
+            const bool chg = k < q1 && na != oa;
+            const bool in_new = chg && na >= jg0 && na < jg0 + rows;
+            const bool in_old = chg && oa >= jg0 && oa < jg0 + rows;
+            unsigned long long mask = __ballot(in_new || in_old);
+            while (mask) {
+                const int b = __ffsll((long long)mask) - 1;
+                mask &= mask - 1;
+                const int nb = __shfl(in_new ? na - jg0 : -1, b);
+                const int ob = __shfl(in_old ? oa - jg0 : -1, b);
+                const float* xr = a.X + (size_t)(base + b) * D;
+                if (lane < D) {
+                    const long long q = to_fixed(xr[lane], scale);
+                    if (nb >= 0) atomicAdd(reinterpret_cast<unsigned long long*>(&lsum[nb * D + lane]), (unsigned long long)q);
+                    if (ob >= 0) atomicAdd(reinterpret_cast<unsigned long long*>(&lsum[ob * D + lane]), (unsigned long long)(-q));
+                }
+                if (lane == 0) {
+                    if (nb >= 0) { atomicAdd(&lcnt[nb], 1); ltouched[nb] = 1; }
+                    if (ob >= 0) { atomicSub(&lcnt[ob], 1); ltouched[ob] = 1; }
+                }
             }
         }
+        __syncthreads();
+        for (int i = tid; i < rows * D; i += kThreads) {
+            const int jr = i / D;
+            if (ltouched[jr])
+                atomicAdd(reinterpret_cast<unsigned long long*>(a.sums + (size_t)(k0 + jg0) * D + i),
+                          (unsigned long long)lsum[i]);
+        }
+        if (tid < rows && ltouched[tid]) {
+            atomicAdd(&a.counts[k0 + jg0 + tid], lcnt[tid]);
+            a.dirty[k0 + jg0 + tid] = 1;
+        }
+        __syncthreads();
     }
+}
+
+// assign <- proposal, after every cluster group has read the old assignment
+__global__ void __launch_bounds__(kThreads) big_commit(BigArgs a) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < a.N; k += stride)
+        a.assign[k] = a.prop[k];
 }
 
 // Per-chunk partial objective: 16 lanes per candidate, per-lane fp64 partial
@@ -544,6 +585,7 @@ BigWs big_ws_layout(const kb_batch& b, size_t base) {
     w.cnmax = off;     off += al256(sizeof(unsigned) * 2 * (size_t)b.G);
     w.nflag = off;     off += 256;
     w.partJ = off;     off += al256(sizeof(double) * w.max_chunks);
+    w.prop = off;      off += al256(sizeof(int32_t) * (size_t)(b.N > 0 ? b.N : 1));
     w.end = off;
     return w;
 }
@@ -565,6 +607,7 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
     a.cnmax_bits = reinterpret_cast<unsigned*>(ws + w.cnmax);
     a.nflag = reinterpret_cast<int*>(ws + w.nflag);
     a.flist = c.a_new;
+    a.prop = reinterpret_cast<int32_t*>(ws + w.prop);
     a.partJ = reinterpret_cast<double*>(ws + w.partJ);
 
     const int ds = (b.D + 15) / 16;
@@ -582,6 +625,8 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
     const unsigned chunk_blocks = (unsigned)w.max_chunks;
     const size_t lds = (size_t)(w.kpad / 32) * ds * 2 * 64 * 16 + (size_t)w.kpad * 4;
     if (lds > 160 * 1024) return hipErrorInvalidValue;
+    const dim3 upd_grid((unsigned)((b.N + kUpdateRange - 1) / kUpdateRange),
+                        (unsigned)((a.Kmax + kRowsPerGroup - 1) / kRowsPerGroup));
 
 #define KB_BIG(DS_)                                                                              \
     do {                                                                                         \
@@ -593,7 +638,9 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
             a.it = it;                                                                           \
             hipLaunchKernelGGL(big_renew<DS_>, dim3(row_blocks), dim3(kThreads), 0, st, a);      \
             hipLaunchKernelGGL(big_score<DS_>, dim3(chunk_blocks), dim3(kThreads), lds, st, a);  \
-            hipLaunchKernelGGL(big_exact, dim3(512), dim3(kThreads), 0, st, a);                  \
+            hipLaunchKernelGGL(big_exact, dim3(1024), dim3(kThreads), 0, st, a);                 \
+            hipLaunchKernelGGL(big_update, upd_grid, dim3(kThreads), 0, st, a);                  \
+            hipLaunchKernelGGL(big_commit, dim3(init_blocks), dim3(kThreads), 0, st, a);         \
         }                                                                                        \
         hipLaunchKernelGGL(big_objective, dim3(chunk_blocks), dim3(kThreads), 0, st, a);         \
         hipLaunchKernelGGL(big_objsum, dim3((unsigned)((b.G + kThreads - 1) / kThreads)),        \
