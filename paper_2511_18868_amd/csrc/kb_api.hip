@@ -20,6 +20,15 @@ WsLayout ws_layout(const kb_batch& b) {
     w.split = off;  off += align256(w.max_tiles * steps * 2 * 64 * 16);
     w.use_big = cluster_uses_big(b);
     if (w.use_big) { w.big = big_ws_layout(b, off); off = w.big.end; }
+    w.ucb_chunked = b.Nmax > 16384;
+    w.ucb_R = w.ucb_N = w.ucb_kmin = w.ucb_nalive = 0;
+    if (w.ucb_chunked) {
+        const size_t ks = (size_t)(b.Ksum > 0 ? b.Ksum : 1) * b.S, k = (size_t)(b.Ksum > 0 ? b.Ksum : 1);
+        w.ucb_R = off;      off += align256(8 * ks);
+        w.ucb_kmin = off;   off += align256(8 * k);
+        w.ucb_N = off;      off += align256(4 * ks);
+        w.ucb_nalive = off; off += align256(4 * k);
+    }
     w.total = off;
     return w;
 }
@@ -139,6 +148,11 @@ static kb_status do_ucb(const kb_batch* b, const kb_params* p, const int32_t* as
     c.assign = assign; c.alive = alive; c.bound = bound; c.visits = visits; c.rsum = rsum;
     c.t = t; c.c = p->c; c.prior_n = p->prior_n; c.prior_mu = p->prior_mu;
     c.Ncs = Ncs; c.mu = mu; c.ucb = ucb; c.sel = sel; c.order = order;
+    c.gN = nullptr; c.gR = nullptr; c.gnalive = nullptr; c.gkmin = nullptr;
+    if (w.ucb_chunked) {
+        c.gN = (unsigned*)(base + w.ucb_N); c.gR = (unsigned long long*)(base + w.ucb_R);
+        c.gnalive = (unsigned*)(base + w.ucb_nalive); c.gkmin = (unsigned long long*)(base + w.ucb_kmin);
+    }
     return dev(launch_ucb(*b, c, st));
 }
 

@@ -229,7 +229,6 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
     const int t1 = t0 + kTilesPerChunk < ntiles ? t0 + kTilesPerChunk : ntiles;
     const int64_t tb = a.tile_off[g];
     if (t0 >= t1 || tb + ntiles > a.max_tiles) return;
-    const int D = a.D;
     const int mtiles = (K + 31) >> 5;
     // stage this search's centroid operands and padded |c|^2 in LDS
     bf16x8* aop = reinterpret_cast<bf16x8*>(smem);

@@ -33,6 +33,8 @@ struct WsLayout {
     size_t max_tiles;   // capacity of `split` in tiles (not an offset)
     bool use_big;
     BigWs big;
+    bool ucb_chunked;   // searches longer than 16384 candidates: partial tables per candidate range
+    size_t ucb_R, ucb_N, ucb_kmin, ucb_nalive;
     size_t total;
 };
 WsLayout ws_layout(const kb_batch& b);
@@ -80,6 +82,11 @@ struct UcbCall {
     float* ucb;
     int32_t* sel;
     const int32_t* order;
+    // global tables of the chunked path (NULL: one workgroup per search)
+    unsigned* gN;
+    unsigned long long* gR;
+    unsigned* gnalive;
+    unsigned long long* gkmin;
 };
 hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st);
 

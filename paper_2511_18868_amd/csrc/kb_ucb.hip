@@ -32,6 +32,11 @@ struct UcbArgs {
     float* ucb;
     int32_t* sel;
     const int32_t* order;
+    unsigned* gN;               // [Ksum*S]  global tables of the chunked path
+    unsigned long long* gR;     // [Ksum*S]
+    unsigned* gnalive;          // [Ksum]
+    unsigned long long* gkmin;  // [Ksum]
+    int64_t Nll;
 };
 
 constexpr int kThreads = 256;
@@ -46,41 +51,22 @@ __device__ __forceinline__ unsigned ordered_bits(float f) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-__global__ void __launch_bounds__(kThreads) ucb_kernel(UcbArgs a) {
-    extern __shared__ __align__(16) unsigned char smem[];
+// Scatter the visits / reward sums of the alive candidates [q0, q1) of a search
+// (indices local to the search) into K x S tables keyed by cluster.
+__device__ __forceinline__ void ucb_accumulate(const UcbArgs& a, int n0, int K, int q0, int q1,
+                                               unsigned* Ncnt, unsigned long long* R,
+                                               unsigned* nalive, unsigned long long* kmin) {
     const int tid = threadIdx.x;
     const int S = a.S;
-
-    int g = a.order ? a.order[blockIdx.x] : (int)blockIdx.x;
-    g = clampi(g, 0, a.G - 1);
-    int n0, ng, k0, K;
-    search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
-    if (K > a.Kmax) K = a.Kmax;
-    if (ng <= 0 || K <= 0) {
-        if (tid < 3) a.sel[(size_t)g * 3 + tid] = -1;
-        return;
-    }
-    const int KS = K * S;
-
-    double* redv = reinterpret_cast<double*>(smem);                                      // [kWaves]
-    int* redi = reinterpret_cast<int*>(smem + 32);                                       // [kWaves]
-    unsigned long long* R = reinterpret_cast<unsigned long long*>(smem + 64);            // [Kmax*S]
-    unsigned long long* kmin = R + (size_t)a.Kmax * S;                                   // [Kmax]
-    unsigned* Ncnt = reinterpret_cast<unsigned*>(kmin + a.Kmax);                         // [Kmax*S]
-    unsigned* nalive = Ncnt + (size_t)a.Kmax * S;                                        // [Kmax]
-
-    for (int i = tid; i < KS; i += kThreads) { R[i] = 0ull; Ncnt[i] = 0u; }
-    for (int i = tid; i < K; i += kThreads) { kmin[i] = ~0ull; nalive[i] = 0u; }
-    __syncthreads();
-
-    const int32_t* vis = a.visits + (size_t)n0 * S;
-    const float* rs = a.rsum + (size_t)n0 * S;
+    const int ng = q1 - q0;
+    const int32_t* vis = a.visits + ((size_t)n0 + q0) * S;
+    const float* rs = a.rsum + ((size_t)n0 + q0) * S;
     if ((S & 3) == 0) {
         const int S4 = S >> 2;
         const size_t quads = (size_t)ng * S4;
         for (size_t q = tid; q < quads; q += kThreads) {
-            const int p = (int)(q / S4);
-            const int s0 = (int)(q - (size_t)p * S4) * 4;
+            const int pl = (int)(q / S4), p = q0 + pl;
+            const int s0 = (int)(q - (size_t)pl * S4) * 4;
             if (!a.alive[(size_t)n0 + p]) continue;
             int j = a.assign[(size_t)n0 + p];
             j = (j >= 0 && j < K) ? j : 0;
@@ -104,8 +90,8 @@ __global__ void __launch_bounds__(kThreads) ucb_kernel(UcbArgs a) {
     } else {
         const size_t total = (size_t)ng * S;
         for (size_t q = tid; q < total; q += kThreads) {
-            const int p = (int)(q / S);
-            const int s = (int)(q - (size_t)p * S);
+            const int pl = (int)(q / S), p = q0 + pl;
+            const int s = (int)(q - (size_t)pl * S);
             if (!a.alive[(size_t)n0 + p]) continue;
             int j = a.assign[(size_t)n0 + p];
             j = (j >= 0 && j < K) ? j : 0;
@@ -120,8 +106,17 @@ __global__ void __launch_bounds__(kThreads) ucb_kernel(UcbArgs a) {
             }
         }
     }
-    __syncthreads();
+}
 
+// Scores, outputs and selection of one search from its accumulated tables
+// (which may live in LDS or in global memory).  Called by a whole workgroup.
+__device__ __forceinline__ void ucb_finish(const UcbArgs& a, int g, int n0, int k0, int K,
+                                           const unsigned* Ncnt, const unsigned long long* R,
+                                           const unsigned* nalive, const unsigned long long* kmin,
+                                           double* redv, int* redi) {
+    const int tid = threadIdx.x;
+    const int S = a.S;
+    const int KS = K * S;
     long long tg = a.t[g];
     if (tg < 1) tg = 1;
     const double lnt = log((double)tg);
@@ -173,6 +168,112 @@ __global__ void __launch_bounds__(kThreads) ucb_kernel(UcbArgs a) {
     }
 }
 
+__global__ void __launch_bounds__(kThreads) ucb_kernel(UcbArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int S = a.S;
+
+    int g = a.order ? a.order[blockIdx.x] : (int)blockIdx.x;
+    g = clampi(g, 0, a.G - 1);
+    int n0, ng, k0, K;
+    search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+    if (K > a.Kmax) K = a.Kmax;
+    if (ng <= 0 || K <= 0) {
+        if (tid < 3) a.sel[(size_t)g * 3 + tid] = -1;
+        return;
+    }
+    const int KS = K * S;
+
+    double* redv = reinterpret_cast<double*>(smem);                                      // [kWaves]
+    int* redi = reinterpret_cast<int*>(smem + 32);                                       // [kWaves]
+    unsigned long long* R = reinterpret_cast<unsigned long long*>(smem + 64);            // [Kmax*S]
+    unsigned long long* kmin = R + (size_t)a.Kmax * S;                                   // [Kmax]
+    unsigned* Ncnt = reinterpret_cast<unsigned*>(kmin + a.Kmax);                         // [Kmax*S]
+    unsigned* nalive = Ncnt + (size_t)a.Kmax * S;                                        // [Kmax]
+
+    for (int i = tid; i < KS; i += kThreads) { R[i] = 0ull; Ncnt[i] = 0u; }
+    for (int i = tid; i < K; i += kThreads) { kmin[i] = ~0ull; nalive[i] = 0u; }
+    __syncthreads();
+
+    ucb_accumulate(a, n0, K, 0, ng, Ncnt, R, nalive, kmin);
+    __syncthreads();
+
+    ucb_finish(a, g, n0, k0, K, Ncnt, R, nalive, kmin, redv, redi);
+}
+
+
+// ---- searches too long for one workgroup: partial tables per candidate range,
+// ---- merged in global memory with integer atomics (still order-independent)
+constexpr int kUcbRange = 8192;
+
+__global__ void __launch_bounds__(kThreads) ucb_zero(UcbArgs a) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (int64_t i = t0; i < (int64_t)a.Ksum * a.S; i += stride) { a.gN[i] = 0u; a.gR[i] = 0ull; }
+    for (int64_t i = t0; i < a.Ksum; i += stride) { a.gnalive[i] = 0u; a.gkmin[i] = ~0ull; }
+}
+
+__global__ void __launch_bounds__(kThreads) ucb_partial(UcbArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int S = a.S;
+    const int64_t r0 = (int64_t)blockIdx.x * kUcbRange;
+    if (r0 >= a.N) return;
+    const int64_t r1 = r0 + kUcbRange < a.N ? r0 + kUcbRange : a.N;
+    unsigned long long* R = reinterpret_cast<unsigned long long*>(smem + 64);
+    unsigned long long* kmin = R + (size_t)a.Kmax * S;
+    unsigned* Ncnt = reinterpret_cast<unsigned*>(kmin + a.Kmax);
+    unsigned* nalive = Ncnt + (size_t)a.Kmax * S;
+    // largest g with seg_off[g] <= r0
+    int lo = 0, hi = a.G;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if ((int64_t)a.seg_off[mid] <= r0) lo = mid; else hi = mid;
+    }
+    for (int g = lo; g < a.G; ++g) {
+        int n0, ng, k0, K;
+        search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+        if (K > a.Kmax) K = a.Kmax;
+        if (n0 >= r1) break;
+        if (ng <= 0 || K <= 0) continue;
+        const int64_t q0 = r0 > n0 ? r0 : n0;
+        const int64_t q1 = r1 < (int64_t)n0 + ng ? r1 : (int64_t)n0 + ng;
+        if (q0 >= q1) continue;
+        const int KS = K * S;
+        for (int i = tid; i < KS; i += kThreads) { R[i] = 0ull; Ncnt[i] = 0u; }
+        for (int i = tid; i < K; i += kThreads) { kmin[i] = ~0ull; nalive[i] = 0u; }
+        __syncthreads();
+        ucb_accumulate(a, n0, K, (int)(q0 - n0), (int)(q1 - n0), Ncnt, R, nalive, kmin);
+        __syncthreads();
+        for (int i = tid; i < KS; i += kThreads) {
+            if (Ncnt[i]) atomicAdd(&a.gN[(size_t)k0 * S + i], Ncnt[i]);
+            if (R[i]) atomicAdd(&a.gR[(size_t)k0 * S + i], R[i]);
+        }
+        for (int i = tid; i < K; i += kThreads) {
+            if (nalive[i]) {
+                atomicAdd(&a.gnalive[k0 + i], nalive[i]);
+                atomicMin(&a.gkmin[k0 + i], kmin[i]);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+__global__ void __launch_bounds__(kThreads) ucb_final(UcbArgs a) {
+    __shared__ double redv[kWaves];
+    __shared__ int redi[kWaves];
+    const int g = blockIdx.x;
+    int n0, ng, k0, K;
+    search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+    if (K > a.Kmax) K = a.Kmax;
+    if (ng <= 0 || K <= 0) {
+        if (threadIdx.x < 3) a.sel[(size_t)g * 3 + threadIdx.x] = -1;
+        return;
+    }
+    ucb_finish(a, g, n0, k0, K, a.gN + (size_t)k0 * a.S, a.gR + (size_t)k0 * a.S, a.gnalive + k0,
+               a.gkmin + k0, redv, redi);
+}
+
 }  // namespace
 
 hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st) {
@@ -184,6 +285,22 @@ hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st) {
     a.sel = c.sel; a.order = c.order;
     const size_t lds = 64 + (size_t)a.Kmax * b.S * 12 + (size_t)a.Kmax * 12;
     if (lds > 160 * 1024) return hipErrorInvalidValue;
+    a.gN = c.gN; a.gR = c.gR; a.gnalive = c.gnalive; a.gkmin = c.gkmin; a.Nll = b.N;
+    if (c.gN) {
+        // long searches: candidate ranges -> partial tables -> global tables -> scores
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ucb_partial),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        const size_t items = (size_t)b.Ksum * b.S;
+        unsigned zb = (unsigned)((items + kThreads - 1) / kThreads);
+        if (zb > 4096u) zb = 4096u;
+        if (zb == 0) zb = 1;
+        hipLaunchKernelGGL(ucb_zero, dim3(zb), dim3(kThreads), 0, st, a);
+        const unsigned ranges = (unsigned)((b.N + kUcbRange - 1) / kUcbRange);
+        if (ranges) hipLaunchKernelGGL(ucb_partial, dim3(ranges), dim3(kThreads), lds, st, a);
+        hipLaunchKernelGGL(ucb_final, dim3((unsigned)b.G), dim3(kThreads), 0, st, a);
+        return hipGetLastError();
+    }
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ucb_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
