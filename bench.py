@@ -35,6 +35,9 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="workload: BASELINE config 1..5")
     ap.add_argument("--searches", type=int, default=0, help="override the number of searches (config 3/5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calib", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy three times (reference "
+                         "for scaling the FETCH_SIZE / WRITE_SIZE counters of a --pmc run)")
     ap.add_argument("--no-step", action="store_true",
                     help="skip the single-Lloyd-step timing (so a kernel trace of this run holds "
                          "only full kb_cluster launches of the fused kernel)")
@@ -57,6 +60,14 @@ def main():
     gen_s = time.time() - t0
     d = kb.DeviceBatch(b, device="cuda:0")
     torch.cuda.synchronize()
+
+    if args.copy_calib:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         d.round()

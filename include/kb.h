@@ -185,12 +185,17 @@ kb_status kb_round(const kb_batch *batch, const kb_params *params,
 /* Static, never NULL. */
 const char *kb_status_str(kb_status status);
 
-/* Benchmarking switch for the distance scores of the Lloyd step: 0 (default) =
- * matrix cores (bf16 x 3 split products) whenever Kmax <= 64, 1 = always the
- * fp32 vector-ALU path.  Both give identical assignments (doubtful candidates
- * are re-evaluated exactly either way); only speed differs.  This is the one
- * piece of process-wide state in the library; not thread-safe against
- * concurrent calls.  Returns KB_OK or KB_EINVAL. */
+/* Benchmarking switch for the Lloyd step.  All modes give identical results
+ * (doubtful candidates are re-evaluated exactly in every mode); only speed
+ * differs.
+ *   0 (default)  matrix cores (bf16 x 3 split products) whenever Kmax <= 64, plus
+ *                distance bounds: a tile of 32 candidates whose nearest centroid
+ *                provably cannot have changed since the last step (triangle
+ *                inequality on how far the centroids moved) is not scored again;
+ *   1            fp32 vector-ALU scores, every candidate scored in every step;
+ *   2            matrix cores, every candidate scored in every step.
+ * This is the one piece of process-wide state in the library; not thread-safe
+ * against concurrent calls.  Returns KB_OK or KB_EINVAL. */
 int kb_set_scorer(int mode);
 
 /* Library version, "major.minor". Static. */

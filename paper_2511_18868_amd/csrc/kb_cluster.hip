@@ -33,7 +33,7 @@ namespace kb {
 namespace {
 
 struct ClusterArgs {
-    int G, D, Ksum, Kmax;
+    int G, D, Ksum, Kmax, Nmax;
     int64_t N;
     const int32_t* seg_off;
     const int32_t* koff;
@@ -51,6 +51,8 @@ struct ClusterArgs {
     float* xn;
     bf16x8* split;
     int64_t max_tiles;
+    float2* bnd;       // [N] (upper bound on the distance to the own centroid, lower bound on all others)
+    int use_bounds;
 };
 
 constexpr int kThreads = 256;
@@ -257,13 +259,63 @@ __device__ __forceinline__ void build_operands(const float* cent, int K, int DP,
     }
 }
 
+// Distance bounds (Hamerly): every candidate carries u >= distance to its own
+// centroid and l <= distance to every other centroid.  When the centroids move
+// by delta_j, u + delta_own < l - max_other delta proves that the nearest
+// centroid is unchanged and strictly nearest, so a tile whose 32 candidates all
+// pass is not scored in this step.  All roundings go the safe way.  This pass
+// moves the bounds of every candidate of the search (coalesced, several loads in
+// flight) and leaves one flag per tile in LDS: 1 = must be scored.
+__device__ __forceinline__ void bounds_pass(const ClusterArgs& a, int n0, int ng, int K,
+                                            const float* delta, unsigned char* tact) {
+    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    const float dj = lane < K ? delta[lane] : 0.f;     // K <= 64 on this path
+    const float dmax1 = wave_max_f(dj);
+    const int jmax = __ffsll((long long)__ballot(dj == dmax1)) - 1;
+    const float dmax2 = wave_max_f(lane == jmax ? 0.f : dj);
+    float2* bnd = a.bnd + (size_t)n0;
+    const int32_t* asg = a.assign + (size_t)n0;
+    constexpr int U = 4;
+    for (int base = wid * 64; base < ng; base += kThreads * U) {
+        int aa[U];
+        float2 bb[U];
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            const int p = base + q * kThreads + lane;
+            aa[q] = p < ng ? asg[p] : -2;
+            bb[q] = p < ng ? bnd[p] : make_float2(0.f, 1.f);
+        }
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            const int p0 = base + q * kThreads;         // first candidate of this wave's 64
+            if (p0 < ng) {                               // uniform over the wave
+                bool pass = true;
+                if (aa[q] != -2) {
+                    const int j = (aa[q] >= 0 && aa[q] < K) ? aa[q] : 0;
+                    const float u2 = (bb[q].x + delta[j]) * 1.0000005f;
+                    float l2 = bb[q].y - (j == jmax ? dmax2 : dmax1);
+                    l2 = l2 > 0.f ? l2 * 0.9999995f : l2;
+                    pass = aa[q] >= 0 && u2 < l2;
+                    bnd[p0 + lane] = make_float2(u2, l2);
+                }
+                const unsigned long long ok = __ballot(pass);
+                if (lane == 0) {
+                    tact[p0 >> 5] = (unsigned)ok != 0xffffffffu;
+                    if (p0 + 32 < ng) tact[(p0 >> 5) + 1] = (unsigned)(ok >> 32) != 0xffffffffu;
+                }
+            }
+        }
+    }
+}
+
 template <int DS, int MT>
 __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __restrict__ Xg,
                                           const bf16x8* __restrict__ sp,
                                           int n0, int ng, int K, int D, int DP, int SP,
                                           const float* cent, const float* cn, float cnmax,
                                           bool first, double scale, long long* sums, int* cnt,
-                                          int* nflag, int* flist, const bf16x8* aop, int* dirty) {
+                                          int* nflag, int* flist, const bf16x8* aop, int* dirty,
+                                          const unsigned char* tact) {
     const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
     const int m = lane & 31, h = lane >> 5;
     const int mtiles = (K + 31) >> 5;
@@ -286,20 +338,44 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
         }
     };
 
+    const bool bounds = a.use_bounds && !first;
+    float2* bnd = a.bnd + (size_t)n0;
+    const int ntiles = (ng + 31) >> 5;
+    const int ntw = ntiles > wid ? (ntiles - wid + kWaves - 1) / kWaves : 0;   // tiles of this wave
+
     int any = 0;
-    bf16x8 Bh[DS], Bm[DS];
-    float xn = 0.f;
-    int old = -1;
-    if (wid * 32 < ng) load_tile(wid, Bh, Bm, xn, old);
-    for (int tile = wid; tile * 32 < ng; tile += kWaves) {
+    for (int i0 = 0; i0 < ntw; i0 += 64) {
+        const int nb = ntw - i0 < 64 ? ntw - i0 : 64;
+        unsigned long long act = nb == 64 ? ~0ull : ((1ull << nb) - 1ull);
+        if (bounds) {
+            // tiles the bound pass could not clear
+            const int ti = wid + kWaves * (i0 + lane);
+            act = __ballot(lane < nb && tact[ti] != 0);
+        }
+        bf16x8 Bh[DS], Bm[DS];
+        float xn = 0.f;
+        int old = -1;
+        int cur = -1;
+        if (act) {
+            cur = __ffsll((long long)act) - 1;
+            act &= act - 1;
+            load_tile(wid + kWaves * (i0 + cur), Bh, Bm, xn, old);
+        }
+        while (cur >= 0) {
+        const int tile = wid + kWaves * (i0 + cur);
         const int p = tile * 32 + m;
         const bool valid = p < ng;
         // request the next tile before scoring this one
         bf16x8 Bh2[DS], Bm2[DS];
         float xn2 = 0.f;
         int old2 = -1;
-        const bool more = (tile + kWaves) * 32 < ng;
-        if (more) load_tile(tile + kWaves, Bh2, Bm2, xn2, old2);
+        int nxt = -1;
+        if (act) {
+            nxt = __ffsll((long long)act) - 1;
+            act &= act - 1;
+            load_tile(wid + kWaves * (i0 + nxt), Bh2, Bm2, xn2, old2);
+        }
+        const bool more = nxt >= 0;
         old = (old >= 0 && old < K) ? old : -1;
 
         // Accumulators start at |c_j|^2 (padded with a huge value for rows >= K),
@@ -461,11 +537,22 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
             }
         }
         if (__any(valid && !certain)) any |= 2;
+        if (a.use_bounds && valid && h == 0) {
+            // d_best^2 <= best + |x|^2 + E and d_other^2 >= second + |x|^2 - E, with
+            // room for the rounding of |x|^2 and of the square roots; a doubtful
+            // candidate gets bounds that force the next step to score it again
+            const float Eb = E + 4.0e-6f * xn;
+            const float ub = sqrtf(fmaxf(best + xn + Eb, 0.f)) * 1.0000005f;
+            const float lb = sqrtf(fmaxf(second + xn - Eb, 0.f)) * 0.9999995f;
+            bnd[p] = certain ? make_float2(ub, lb) : make_float2(kBig, 0.f);
+        }
         if (more) {
 #pragma unroll
             for (int s = 0; s < DS; ++s) { Bh[s] = Bh2[s]; Bm[s] = Bm2[s]; }
             xn = xn2;
             old = old2;
+        }
+        cur = nxt;
         }
     }
     return any;   // bit 0: some candidate moved, bit 1: some candidate needs the exact pass
@@ -534,24 +621,44 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
         const float* xr = Xg + (size_t)p * D;
         const float xv = lane < D ? xr[lane] : 0.f;
         int old = a.assign[(size_t)n0 + p];
-        double bd = INFINITY;
+        double bd = INFINITY, sd = INFINITY;      // smallest and second smallest distance
         int bj = 0x7fffffff;
         for (int j0 = 0; j0 < K; j0 += kWave) {
             const int j = j0 + lane;
             const float* cr = cent + (size_t)(j < K ? j : 0) * DP;
+            // rows are zero-padded to a multiple of 4 features (and xv is 0 beyond
+            // D), so whole float4 chunks can be summed: the extra terms are +0.0
             double acc = 0.0;
-            for (int d = 0; d < D; ++d) {
-                const double diff = __dsub_rn((double)__shfl(xv, d), (double)cr[d]);
+            for (int d = 0; d < D; d += 4) {
+                const float4 cv = *reinterpret_cast<const float4*>(cr + d);
+                double diff = __dsub_rn((double)__shfl(xv, d), (double)cv.x);
+                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                diff = __dsub_rn((double)__shfl(xv, d + 1), (double)cv.y);
+                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                diff = __dsub_rn((double)__shfl(xv, d + 2), (double)cv.z);
+                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                diff = __dsub_rn((double)__shfl(xv, d + 3), (double)cv.w);
                 acc = __dadd_rn(acc, __dmul_rn(diff, diff));
             }
-            if (j < K && acc < bd) { bd = acc; bj = j; }
+            if (j < K) {
+                if (acc < bd) { sd = bd; bd = acc; bj = j; }
+                else if (acc < sd) sd = acc;
+            }
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
             const double od = __shfl_xor(bd, o);
+            const double os = __shfl_xor(sd, o);
             const int oj = __shfl_xor(bj, o);
-            if (od < bd || (od == bd && oj < bj)) { bd = od; bj = oj; }
+            const bool take = od < bd || (od == bd && oj < bj);
+            const double hi2 = take ? bd : od;        // the larger of the two bests
+            const double sm = os < sd ? os : sd;
+            sd = sm < hi2 ? sm : hi2;
+            if (take) { bd = od; bj = oj; }
         }
+        if (a.use_bounds && lane == 0)
+            a.bnd[(size_t)n0 + p] = make_float2((float)sqrt(bd) * 1.0000005f,
+                                                (float)sqrt(sd) * 0.9999995f);
         bj = bj < K ? bj : 0;
         old = (old >= 0 && old < K) ? old : -1;
         if (bj != old) {
@@ -619,9 +726,9 @@ __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restr
 
 // LDS layout shared by the kernel and the host-side size computation.
 struct Lds {
-    size_t sums, cent, cn, cnt, dirty, flist, aop, total;
+    size_t sums, cent, cn, cnt, dirty, delta, flist, aop, tact, total;
 };
-__host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP) {
+__host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP, int Nmax) {
     const int SP = D | 1;   // odd row stride: clusters spread over the LDS banks
     Lds l;
     size_t off = 128;                                   // reduction scratch
@@ -631,10 +738,13 @@ __host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP) {
     l.cn = off;   off += (size_t)((Kmax + 31) & ~31) * 4;   // padded to whole centroid tiles
     l.cnt = off;  off += (size_t)Kmax * 4;
     l.dirty = off; off += (size_t)Kmax * 4 * 2;     // two generations of "row changed" flags
+    l.delta = off; off += (size_t)Kmax * 4;         // how far each centroid moved in the last renewal
     l.flist = off; off += (size_t)kFlagCap * 4;
     off = (off + 15) & ~(size_t)15;
     // centroid operands of the matrix-core scorer (only when Kmax <= 64)
     l.aop = off;  if (Kmax <= 64) off += (size_t)((Kmax + 31) / 32) * ((DP - 4) / 16) * 2 * 64 * 16;
+    // one "must be scored" flag per tile of 32 candidates
+    l.tact = off; if (Kmax <= 64) off += (((size_t)Nmax + 31) / 32 + 15) & ~(size_t)15;
     l.total = off;
     return l;
 }
@@ -660,7 +770,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
         return;
     }
 
-    const Lds L = lds_layout(a.Kmax, D, DP);
+    const Lds L = lds_layout(a.Kmax, D, DP, a.Nmax);
     double* red = reinterpret_cast<double*>(smem);
     long long* sums = reinterpret_cast<long long*>(smem + L.sums);   // [Kmax][SP]
     float* cent = reinterpret_cast<float*>(smem + L.cent);           // [Kmax][DP]
@@ -668,6 +778,8 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     int* cnt = reinterpret_cast<int*>(smem + L.cnt);                 // [Kmax]
     int* flist = reinterpret_cast<int*>(smem + L.flist);             // [kFlagCap]
     int* dirty = reinterpret_cast<int*>(smem + L.dirty);             // [2][Kmax]
+    float* delta = reinterpret_cast<float*>(smem + L.delta);         // [Kmax]
+    unsigned char* tact = smem + L.tact;                             // [tiles]
     int* nflag = reinterpret_cast<int*>(smem + 64);                  // behind the two reduction slots
     bf16x8* aop = reinterpret_cast<bf16x8*>(smem + L.aop);
 
@@ -728,6 +840,9 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     bool first = true;
     for (int it = 0; it < a.iters; ++it) {
         if (tid == 0) *nflag = 0;
+        if constexpr (MT > 0) {
+            if (a.use_bounds && !first) bounds_pass(a, n0, ng, K, delta, tact);
+        }
         // dr: rows whose centroid was renewed by the previous step (all rows in the
         // first); dw: rows touched in this step, for the renewal at its end
         const int* dr = dirty + ((it + 1) & 1) * a.Kmax;
@@ -759,7 +874,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
         int st;
         if constexpr (MT > 0) {
             st = score_mfma<DS, MT>(a, Xg, sp, n0, ng, K, D, DP, SP, cent, cn, cm, first, scale, sums, cnt,
-                                    nflag, flist, aop, dw);
+                                    nflag, flist, aop, dw, tact);
         } else {
             score_valu<4 * DS>(a, Xg, n0, ng, K, D, DP, cent, cn, cm);
             st = 2;
@@ -819,10 +934,21 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
         }
         for (int j = tid >> 6; j < K; j += kWaves) {
             const int c = cnt[j];
-            if (c > 0 && dw[j])
-                for (int d = tid & 63; d < D; d += kWave)
-                    cent[(size_t)j * DP + d] =
-                        (float)(((double)sums[(size_t)j * SP + d] * inv) / (double)c);
+            if (c > 0 && dw[j]) {                 // uniform over the wave
+                double mv = 0.0;
+                for (int d = tid & 63; d < D; d += kWave) {
+                    const float cold = cent[(size_t)j * DP + d];
+                    const float cnew = (float)(((double)sums[(size_t)j * SP + d] * inv) / (double)c);
+                    cent[(size_t)j * DP + d] = cnew;
+                    const double df = (double)cnew - (double)cold;
+                    mv += df * df;
+                }
+                // Euclidean length of the move, rounded up
+                mv = wave_sum_d(mv);
+                if ((tid & 63) == 0) delta[j] = (float)sqrt(mv) * 1.0000005f;
+            } else if ((tid & 63) == 0) {
+                delta[j] = 0.f;
+            }
         }
         __syncthreads();
         if (last) break;
@@ -837,7 +963,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
 
 constexpr size_t kMaxLds = 160 * 1024;
 
-int g_scorer = 0;   // 0 = automatic, 1 = vector ALU, 2 = matrix cores where the shape allows
+int g_scorer = 0;   // 0 = matrix cores + distance bounds, 1 = vector ALU, 2 = matrix cores, every tile scored
 
 }  // namespace
 
@@ -846,7 +972,7 @@ void set_scorer(int mode) { g_scorer = mode; }
 bool cluster_supported(const kb_batch& b) {
     const int kmax = b.Kmax > 0 ? b.Kmax : 1;
     const int ds = (b.D + 15) / 16;
-    return lds_layout(kmax, b.D, 16 * ds + 4).total <= kMaxLds;
+    return lds_layout(kmax, b.D, 16 * ds + 4, b.Nmax).total <= kMaxLds;
 }
 
 hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t st) {
@@ -857,9 +983,11 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     a.counts = c.counts; a.objective = c.objective; a.a_new = c.a_new; a.order = c.order;
     a.tile_off = c.tile_off; a.xn = c.xn; a.split = reinterpret_cast<bf16x8*>(c.split);
     a.max_tiles = c.max_tiles;
+    a.bnd = reinterpret_cast<float2*>(c.bnd); a.use_bounds = g_scorer != 2;
 
     const int ds = (b.D + 15) / 16;   // 1..4 K-steps of 16 features
-    const size_t lds = lds_layout(a.Kmax, b.D, 16 * ds + 4).total;
+    a.Nmax = b.Nmax;
+    const size_t lds = lds_layout(a.Kmax, b.D, 16 * ds + 4, b.Nmax).total;
     if (lds > kMaxLds) return hipErrorInvalidValue;
     int mt = a.Kmax <= 32 ? 1 : (a.Kmax <= 64 ? 2 : 0);
     if (g_scorer == 1) mt = 0;

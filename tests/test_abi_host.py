@@ -128,6 +128,7 @@ def test_ucb_and_round_argument_errors(L):
 
 def test_scorer_switch(L):
     assert kb.kb_set_scorer(1) == kb.KB_OK
+    assert kb.kb_set_scorer(2) == kb.KB_OK
     assert kb.kb_set_scorer(0) == kb.KB_OK
     assert kb.kb_set_scorer(7) == kb.KB_EINVAL
 

@@ -41,9 +41,9 @@ SMALL = {
 }
 
 
-@pytest.fixture(scope="module", params=[0, 1], ids=["matrixcore", "vectoralu"])
+@pytest.fixture(scope="module", params=[0, 1, 2], ids=["bounds", "vectoralu", "matrixcore"])
 def scorer(kb, request):
-    """Both distance scorers of the Lloyd step must give the same results."""
+    """Every mode of the Lloyd step must give the same results."""
     assert kb.kb_set_scorer(request.param) == 0
     yield request.param
     kb.kb_set_scorer(0)
