@@ -315,7 +315,7 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
                                           const float* cent, const float* cn, float cnmax,
                                           bool first, double scale, long long* sums, int* cnt,
                                           int* nflag, int* flist, const bf16x8* aop, int* dirty,
-                                          const unsigned char* tact) {
+                                          const unsigned char* tact, bool bounds, int* nmoved) {
     const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
     const int m = lane & 31, h = lane >> 5;
     const int mtiles = (K + 31) >> 5;
@@ -338,7 +338,6 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
         }
     };
 
-    const bool bounds = a.use_bounds && !first;
     float2* bnd = a.bnd + (size_t)n0;
     const int ntiles = (ng + 31) >> 5;
     const int ntw = ntiles > wid ? (ntiles - wid + kWaves - 1) / kWaves : 0;   // tiles of this wave
@@ -486,8 +485,10 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
         const float E = kappa * (xn + cnmax);
         const bool certain = (K == 1) || ((second - best) > 2.f * E);
         const bool chg = valid && certain && (bi != old);
-        if (__any(chg)) {
+        const unsigned long long cmask = __ballot(chg && h == 0);
+        if (cmask) {
             any |= 1;
+            if (lane == 0) atomicAdd(nmoved, __popcll(cmask));
             if (chg) {
                 // the fp32 row is read again (rare after the first steps): all loads
                 // first, then the atomics
@@ -613,7 +614,7 @@ __device__ __forceinline__ void refine(const ClusterArgs& a, const float* __rest
 __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* __restrict__ Xg,
                                              int n0, int n, const int* flist, int K, int D, int DP,
                                              int SP, const float* cent, double scale,
-                                             long long* sums, int* cnt, int* dirty) {
+                                             long long* sums, int* cnt, int* dirty, int* nmoved) {
     const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
     int any = 0;
     for (int i = wid; i < n; i += kWaves) {
@@ -669,6 +670,7 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
                 if (old >= 0) lds_add(&sums[(size_t)old * SP + lane], -q);
             }
             if (lane == 0) {
+                atomicAdd(nmoved, 1);
                 atomicAdd(&cnt[bj], 1);
                 dirty[bj] = 1;
                 if (old >= 0) { atomicSub(&cnt[old], 1); dirty[old] = 1; }
@@ -781,6 +783,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     float* delta = reinterpret_cast<float*>(smem + L.delta);         // [Kmax]
     unsigned char* tact = smem + L.tact;                             // [tiles]
     int* nflag = reinterpret_cast<int*>(smem + 64);                  // behind the two reduction slots
+    int* nmoved = reinterpret_cast<int*>(smem + 68);                 // [2] candidates moved, by step parity
     bf16x8* aop = reinterpret_cast<bf16x8*>(smem + L.aop);
 
     const float* Xg = a.X + (size_t)n0 * D;
@@ -796,6 +799,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     for (int idx = tid; idx < K * SP; idx += kThreads) sums[idx] = 0;
     for (int j = tid; j < K; j += kThreads) cnt[j] = 0;
     for (int j = K + tid; j < ((a.Kmax + 31) & ~31); j += kThreads) cn[j] = kBig;
+    if (tid == 0) { nmoved[0] = 0; nmoved[1] = 0; }
     __syncthreads();
 
     if (a.iters == 0) {
@@ -839,9 +843,13 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
 
     bool first = true;
     for (int it = 0; it < a.iters; ++it) {
-        if (tid == 0) *nflag = 0;
+        // The bound pass pays off once few candidates still move; until then every
+        // tile is scored (and gets fresh bounds from the scorer).
+        const int moved_prev = first ? ng : nmoved[(it + 1) & 1];
+        const bool use_b = MT > 0 && a.use_bounds && !first && (long long)moved_prev * 128 <= ng;
+        if (tid == 0) { *nflag = 0; nmoved[it & 1] = 0; }
         if constexpr (MT > 0) {
-            if (a.use_bounds && !first) bounds_pass(a, n0, ng, K, delta, tact);
+            if (use_b) bounds_pass(a, n0, ng, K, delta, tact);
         }
         // dr: rows whose centroid was renewed by the previous step (all rows in the
         // first); dw: rows touched in this step, for the renewal at its end
@@ -874,7 +882,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
         int st;
         if constexpr (MT > 0) {
             st = score_mfma<DS, MT>(a, Xg, sp, n0, ng, K, D, DP, SP, cent, cn, cm, first, scale, sums, cnt,
-                                    nflag, flist, aop, dw, tact);
+                                    nflag, flist, aop, dw, tact, use_b, nmoved + (it & 1));
         } else {
             score_valu<4 * DS>(a, Xg, n0, ng, K, D, DP, cent, cn, cm);
             st = 2;
@@ -884,7 +892,8 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
             int moved;
             const int nf = MT > 0 ? *nflag : kFlagCap + 1;
             if (nf <= kFlagCap) {
-                moved = refine_listed(a, Xg, n0, nf, flist, K, D, DP, SP, cent, scale, sums, cnt, dw);
+                moved = refine_listed(a, Xg, n0, nf, flist, K, D, DP, SP, cent, scale, sums, cnt, dw,
+                                      nmoved + (it & 1));
             } else {
                 // the list overflowed (or the vector-ALU scorer ran): scan every candidate
                 refine(a, Xg, n0, ng, K, D, DP, cent);
@@ -907,48 +916,68 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
             {
                 const int sub = tid >> 4, l16 = tid & 15;
                 const bool vec4 = (D & 3) == 0;
-                for (int p = sub; p < ng; p += kThreads / 16) {
-                    int j = a.assign[(size_t)n0 + p];
-                    j = (j >= 0 && j < K) ? j : 0;
-                    const float* xr = Xg + (size_t)p * D;
-                    const float* cr = cent + (size_t)j * DP;
-                    float sq = 0.f;
-                    if (vec4) {
-                        if (4 * l16 < D) {
-                            const float4 xv = *reinterpret_cast<const float4*>(xr + 4 * l16);
-                            const float4 cv = *reinterpret_cast<const float4*>(cr + 4 * l16);
-                            const float e0 = xv.x - cv.x, e1 = xv.y - cv.y, e2 = xv.z - cv.z, e3 = xv.w - cv.w;
-                            sq = fmaf(e0, e0, fmaf(e1, e1, fmaf(e2, e2, e3 * e3)));
-                        }
-                    } else {
-                        for (int d = 4 * l16; d < 4 * l16 + 4 && d < D; ++d) {
-                            const float e0 = xr[d] - cr[d];
-                            sq = fmaf(e0, e0, sq);
+                constexpr int U = 4, GR = kThreads / 16;
+                for (int p0 = sub; p0 < ng; p0 += GR * U) {
+                    int jj[U];
+                    float4 xq[U];
+#pragma unroll
+                    for (int q = 0; q < U; ++q) {
+                        const int p = p0 + q * GR;
+                        jj[q] = p < ng ? a.assign[(size_t)n0 + p] : 0;
+                    }
+#pragma unroll
+                    for (int q = 0; q < U; ++q) {
+                        const int p = p0 + q * GR;
+                        xq[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (p < ng) {
+                            const float* xr = Xg + (size_t)p * D;
+                            if (vec4) {
+                                if (4 * l16 < D) xq[q] = *reinterpret_cast<const float4*>(xr + 4 * l16);
+                            } else {
+                                const int d = 4 * l16;
+                                if (d < D) xq[q].x = xr[d];
+                                if (d + 1 < D) xq[q].y = xr[d + 1];
+                                if (d + 2 < D) xq[q].z = xr[d + 2];
+                                if (d + 3 < D) xq[q].w = xr[d + 3];
+                            }
                         }
                     }
-                    acc += (double)sq;
+#pragma unroll
+                    for (int q = 0; q < U; ++q) {
+                        const int p = p0 + q * GR;
+                        if (p < ng && 4 * l16 < D) {
+                            const int j = (jj[q] >= 0 && jj[q] < K) ? jj[q] : 0;
+                            // centroid rows are zero-padded beyond D, like xq
+                            const float4 cv = *reinterpret_cast<const float4*>(cent + (size_t)j * DP + 4 * l16);
+                            const float e0 = xq[q].x - cv.x, e1 = xq[q].y - cv.y;
+                            const float e2 = xq[q].z - cv.z, e3 = xq[q].w - cv.w;
+                            acc += (double)fmaf(e0, e0, fmaf(e1, e1, fmaf(e2, e2, e3 * e3)));
+                        }
+                    }
                 }
             }
             acc = block_sum_d(acc, red, phase);
             if (tid == 0) a.objective[g] = (float)acc;
         }
-        for (int j = tid >> 6; j < K; j += kWaves) {
-            const int c = cnt[j];
-            if (c > 0 && dw[j]) {                 // uniform over the wave
-                double mv = 0.0;
-                for (int d = tid & 63; d < D; d += kWave) {
+        for (int j0 = 0; j0 < K; j0 += kThreads / 16) {
+            const int j = j0 + (tid >> 4), l16 = tid & 15;
+            const int c = j < K ? cnt[j] : 0;
+            const bool renew = c > 0 && dw[j];
+            double mv = 0.0;
+            if (renew)
+                for (int d = l16; d < D; d += 16) {
                     const float cold = cent[(size_t)j * DP + d];
                     const float cnew = (float)(((double)sums[(size_t)j * SP + d] * inv) / (double)c);
                     cent[(size_t)j * DP + d] = cnew;
                     const double df = (double)cnew - (double)cold;
                     mv += df * df;
                 }
-                // Euclidean length of the move, rounded up
-                mv = wave_sum_d(mv);
-                if ((tid & 63) == 0) delta[j] = (float)sqrt(mv) * 1.0000005f;
-            } else if ((tid & 63) == 0) {
-                delta[j] = 0.f;
-            }
+            // Euclidean length of the move (0 for an unchanged centroid), rounded up
+            mv += __shfl_xor(mv, 8);
+            mv += __shfl_xor(mv, 4);
+            mv += __shfl_xor(mv, 2);
+            mv += __shfl_xor(mv, 1);
+            if (j < K && l16 == 0) delta[j] = renew ? (float)sqrt(mv) * 1.0000005f : 0.f;
         }
         __syncthreads();
         if (last) break;
