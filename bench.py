@@ -27,6 +27,20 @@ def lloyd_algorithmic_bytes(b, iters):
     return iters * per_step
 
 
+def measured_traffic(config):
+    """HBM bytes per launch of the fused Lloyd kernel from the rocprofv3 --pmc runs
+    recorded in profiles/traffic_config5.json, or None when the kernel source has
+    changed since they were taken (or the workload is not config 5)."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "traffic_config5.json")
+    src = os.path.join(ROOT, "paper_2511_18868_amd", "csrc", "kb_cluster.hip")
+    if not os.path.exists(path) or config != 5:
+        return None
+    rec = json.load(open(path))
+    h = hashlib.sha256(open(src, "rb").read()).hexdigest()
+    return rec["bytes_per_launch"] if rec.get("kb_cluster_hip_sha256") == h else None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -99,16 +113,34 @@ def main():
     pr_mean, _ = timed(d.prune, reps)
     uc_mean, _ = timed(d.ucb_select, reps)
     step_mean = float("nan")
+    modes = {}
     if not args.no_step:
         d.cent2.copy_(d.cent)
         step_mean, _ = timed(lambda: d.cluster_step(d.cent2), reps)
+        # the same clustering with every tile scored in every step (no distance
+        # bounds), on the matrix cores and on the vector ALU
+        for name, mode in (("matrix_cores_every_tile", 2), ("vector_alu_every_tile", 1)):
+            kb.kb_set_scorer(mode)
+            d.cluster()
+            torch.cuda.synchronize()
+            modes[name] = round(timed(d.cluster, max(3, reps // 2))[0], 4)
+        kb.kb_set_scorer(0)
 
     lloyd_bytes = lloyd_algorithmic_bytes(b, b.iters)
     achieved = lloyd_bytes / (cl_mean * 1e-3) / 1e9
+    big = b.Kmax > 64 or b.Nmax > 65536
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "kernel": "cluster_fused_kernel", "ms": round(cl_mean, 4),
-                "algorithmic_bytes": lloyd_bytes}
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": measured_traffic(args.config),
+                "kernel": "kb_cluster launch sequence (multi-workgroup path)" if big
+                          else "cluster_fused_kernel",
+                "ms": round(cl_mean, 4), "algorithmic_bytes": lloyd_bytes}
+    # distance contraction: 2*N_g*K_g*D flops per step, 3 bf16 products issued per flop
+    nk = float(np.sum(np.diff(b.seg_off).astype(np.float64) * np.diff(b.koff)))
+    logical = 2.0 * nk * b.D * b.iters
+    mfma = {"logical_TFLOPs": round(logical / (cl_mean * 1e-3) / 1e12, 1),
+            "issued_bf16_TFLOPs_if_every_tile_scored": round(3 * logical / (cl_mean * 1e-3) / 1e12, 1),
+            "bf16_peak_TFLOPs": 2500.0}
 
     out = {
         "metric": "candidate traces scored/sec per round",
@@ -116,14 +148,19 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config{args.config} full kb_round", "G": b.G, "N": b.N,
-                   "D": b.D, "S": b.S, "Ksum": b.Ksum, "Kmax": b.Kmax, "iters": b.iters},
+                   "D": b.D, "S": b.S, "Ksum": b.Ksum, "Kmax": b.Kmax, "iters": b.iters,
+                   "lloyd_mode": "matrix cores + distance bounds (library default; results "
+                                 "identical to scoring every tile)"},
         "stages_ms": {"prune": round(pr_mean, 4), "cluster": round(cl_mean, 4),
-                      "ucb_select": round(uc_mean, 4), "one_lloyd_step": None if args.no_step else round(step_mean, 4)},
+                      "ucb_select": round(uc_mean, 4),
+                      "one_lloyd_step": None if args.no_step else round(step_mean, 4)},
+        "cluster_ms_other_modes": modes,
         "lloyd_step_GBs": None if args.no_step else round(
             lloyd_algorithmic_bytes(b, 1) / (step_mean * 1e-3) / 1e9, 1),
         "round_streaming_GBs": round(
             (lloyd_bytes + b.N * 13 + b.N * (8 * b.S + 9)) / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roofline,
+        "distance_contraction": mfma,
         "input_generation_s": round(gen_s, 1),
     }
 

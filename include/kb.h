@@ -27,9 +27,14 @@
  * 1 <= K_g <= N_g.
  *
  * Pointers.  Unless a comment says "host", every pointer is a DEVICE pointer to
- * memory the caller allocated and keeps owning.  The library allocates nothing,
- * keeps no state between calls and is re-entrant; all scratch comes from the
- * caller's workspace `ws` (device, >= kb_workspace_bytes(), 256-byte aligned).
+ * memory the caller allocated and keeps owning.  The library allocates nothing
+ * and keeps no state between calls (the benchmarking switch kb_set_scorer
+ * aside); all scratch comes from the caller's workspace `ws` (device,
+ * >= kb_workspace_bytes(), 256-byte aligned, contents undefined before and
+ * after a call).  The workspace holds, besides small tables, a bf16 copy of the
+ * features, |x|^2 and two distance bounds per candidate: about (4*Dpad + 16) * N
+ * bytes with Dpad = D rounded up to 16.  Two calls may run concurrently only on
+ * different workspaces.
  * Arrays are dense, row-major, with no padding.  X, cent*, flops, bytes, bound,
  * visits and rsum must be 16-byte aligned.
  *

@@ -3,15 +3,22 @@
 // of its Lloyd steps, so the search's rows stay in L2 / Infinity Cache between
 // steps and the centroids never leave LDS.
 //
-// One step is three phases separated by workgroup barriers:
+// Once per call the feature rows are split into bf16 (hi, mid) pieces in the
+// matrix cores' operand order (workspace), together with |x|^2.
 //
+// One step:
+//
+//   bounds     (default mode, once few candidates still move) every candidate
+//              carries an upper bound on the distance to its centroid and a
+//              lower bound on the distance to all others; a tile of 32
+//              candidates that provably keeps its clusters is not scored.
 //   A  score   fast scores s_j = |c_j|^2 - 2 x.c_j for every centroid, the best
 //              and second-best per candidate, and a proved error bound E.
 //              If second - best > 2E the winner is certain; otherwise the
-//              candidate is marked for exact re-evaluation.  Two scorers:
+//              candidate is listed for exact re-evaluation.  Two scorers:
 //              matrix cores (bf16 x 3 split products, fp32 accumulate) for
 //              K <= 64, a vector-ALU fp32 FMA chain otherwise.
-//   R  refine  marked candidates get their squared distances in fp64, direct
+//   R  refine  listed candidates get their squared distances in fp64, direct
 //              difference form, summed over the features in index order with
 //              separate multiply and add - exactly the plain definition - and
 //              the lowest index attaining the minimum wins.
@@ -21,8 +28,8 @@
 //              Integer addition commutes, so the sums (and with them the new
 //              centroids) do not depend on the order the waves run in: results
 //              are bit-identical from run to run without any sorting.  The
-//              matrix-core scorer does this straight from its registers for
-//              the candidates it is certain about.
+//              matrix-core scorer does this itself for the candidates it is
+//              certain about.
 //
 // New centroid = (fixed-point sum / 2^shift) / count in fp64, rounded once to
 // fp32; an empty cluster keeps its centroid.
@@ -185,10 +192,10 @@ __device__ __forceinline__ void score_valu(const ClusterArgs& a, const float* __
 // (One ulp, 2^-23, per accumulated term is assumed for the matrix core's
 // internal summation, twice what round-to-nearest would give.)
 //
-// The centroid operands and |c_j|^2 (in accumulator layout) live in registers
-// for the whole step; a wave walks over tiles of 32 candidates.  Candidates the
-// scorer is certain about and whose cluster changed are moved between the
-// fixed-point sums right here, from the registers that hold their features.
+// The centroid operands and |c_j|^2 (in accumulator layout) are read from LDS;
+// a wave walks over tiles of 32 candidates.  Candidates the scorer is certain
+// about and whose cluster changed are moved between the fixed-point sums right
+// here (their fp32 row is read again; rare after the first steps).
 // The feature rows are split once per call (presplit) into a workspace laid out
 // in operand order - [tile][K-step][hi|mid][lane] x 16 bytes - so a step streams
 // them back with fully coalesced 1 KB loads and no conversion work, and the next

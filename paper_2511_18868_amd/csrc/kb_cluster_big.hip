@@ -14,9 +14,14 @@
 //             |c|^2 and the split centroid operands (-2c) of those clusters
 //     score   one workgroup per chunk of 32 tiles of one search: centroid
 //             operands staged in LDS, bf16x3 MFMA scores, running best/second
-//             over the centroid tiles, sums updated with global atomics for the
-//             candidates that are certain, the others appended to a list
+//             over the centroid tiles; writes the proposed cluster of every
+//             candidate and appends the doubtful ones to a list
 //     exact   fp64 direct-difference distances for the listed candidates
+//             (centroid rows resident in registers), proposal overwritten
+//     update  candidates whose proposal differs from their cluster: partial
+//             fixed-point sums per (candidate range, cluster group) in LDS,
+//             flushed with 64-bit global integer atomics
+//     commit  assign <- proposal
 //   objective (before the last renewal, so it refers to the centroids that
 //             entered the last step), then the last renewal.
 #include "kb_cluster_dev.h"
