@@ -7,7 +7,7 @@
 // (order-independent, so results are bit-identical from run to run) - but every
 // phase is its own launch and the shared state lives in global memory:
 //
-//   init      centroids <- initial rows, sums/counts <- 0, assign <- -1
+//   init      centroids <- initial rows, sums/counts <- 0
 //   presplit  feature rows -> bf16 (hi, mid) operand-ordered tiles, |x|^2, max|x|
 //   per step:
 //     renew   centroid = sum/count for clusters whose membership changed, then
@@ -21,7 +21,8 @@
 //     update  candidates whose proposal differs from their cluster: partial
 //             fixed-point sums per (candidate range, cluster group) in LDS,
 //             flushed with 64-bit global integer atomics
-//     commit  assign <- proposal
+//             (the assignment is kept in two buffers that swap roles every
+//             step, chosen so that the last step writes the caller's array)
 //   objective (before the last renewal, so it refers to the centroids that
 //             entered the last step), then the last renewal.
 #include "kb_cluster_dev.h"
@@ -40,7 +41,9 @@ struct BigArgs {
     const int32_t* koff;
     const float* X;
     const float* cent_init;
-    int32_t* assign;
+    int32_t* assign;        // [N] the caller's output; holds the last step's assignment
+    const int32_t* prev;    // [N] assignment before this step (unused in the first step)
+    int32_t* next;          // [N] assignment proposed by this step
     float* cent;
     int32_t* counts;
     float* objective;
@@ -50,13 +53,13 @@ struct BigArgs {
     bf16x8* split;
     long long* sums;        // [Ksum][D]
     float* cnpad;           // [G][Kpad]
+    float* centT;           // [G][D][Kpad] centroids, feature-major (coalesced reads with lanes over centroids)
     bf16x8* aop;            // [G][Kpad/32][DS][2][64]
     int* dirty;             // [Ksum]
     unsigned* amax_bits;    // [G]
     unsigned* cnmax_bits;   // [2][G]
     int* nflag;             // [1]
     int32_t* flist;         // [N] global candidate indices
-    int32_t* prop;          // [N] proposed cluster of every candidate in this step
     double* partJ;          // [chunks]
 };
 
@@ -97,7 +100,6 @@ __global__ void __launch_bounds__(kThreads) big_init(BigArgs a) {
     }
     if (a.it < 0) return;   // iters == 0: only the initial centroids
     for (int64_t r = t0; r < a.Ksum; r += stride) { a.counts[r] = 0; a.dirty[r] = 0; }
-    for (int64_t k = t0; k < a.N; k += stride) a.assign[k] = -1;
     for (int64_t g = t0; g < a.G; g += stride) {
         a.amax_bits[g] = 0u;
         a.cnmax_bits[g] = 0u;
@@ -152,8 +154,13 @@ __global__ void __launch_bounds__(kThreads) big_presplit(BigArgs a) {
     if (valid && h == 0) a.xn[(size_t)n0 + p] = xnp;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) am = fmaxf(am, __shfl_xor(am, o));
-    // non-negative floats order like their bit patterns
-    if (lane == 0) atomicMax(&a.amax_bits[g], __float_as_uint(am));
+    // non-negative floats order like their bit patterns; most waves find a value
+    // at least as large already recorded and skip the atomic (the plain read may
+    // be stale, which only costs an unnecessary atomic)
+    if (lane == 0) {
+        const unsigned bits = __float_as_uint(am);
+        if (bits > *reinterpret_cast<volatile unsigned*>(&a.amax_bits[g])) atomicMax(&a.amax_bits[g], bits);
+    }
 }
 
 // One wave per (search, padded centroid row).
@@ -204,6 +211,7 @@ __global__ void __launch_bounds__(kThreads) big_renew(BigArgs a) {
         const float c = lane < D ? a.cent[(size_t)row * D + lane] : 0.f;
         f = (float)wave_sum_d((double)c * (double)c);
         if (lane == 0) a.cnpad[r] = f;
+        if (lane < D) a.centT[((size_t)g * D + lane) * a.Kpad + j] = c;
         store_operand(-2.f * c);
     } else {
         f = a.cnpad[r];
@@ -238,6 +246,10 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
     // stage this search's centroid operands and padded |c|^2 in LDS
     bf16x8* aop = reinterpret_cast<bf16x8*>(smem);
     float* cn = reinterpret_cast<float*>(smem + (size_t)(a.Kpad / 32) * DS * 2 * 64 * 16);
+    // doubtful candidates of this chunk, handed to the global list in one piece
+    int* lflag = reinterpret_cast<int*>(cn + a.Kpad);       // [kTilesPerChunk * 32]
+    int* lcount = lflag + kTilesPerChunk * 32;               // [2]: count, base in the global list
+    if (tid == 0) lcount[0] = 0;
     {
         const bf16x8* src = a.aop + (size_t)g * (a.Kpad / 32) * (DS * 2 * 64);
         for (int i = tid; i < mtiles * DS * 2 * 64; i += kThreads) aop[i] = src[i];
@@ -363,11 +375,8 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
         // the proposal of every candidate goes to `prop`; the doubtful ones are
         // listed for the exact pass, which overwrites their proposal
         if (valid && h == 0) {
-            a.prop[(size_t)n0 + p] = bi;
-            if (!certain) {
-                const int pos = atomicAdd(a.nflag, 1);
-                if ((int64_t)pos < a.N) a.flist[pos] = n0 + p;
-            }
+            a.next[(size_t)n0 + p] = bi;
+            if (!certain) lflag[atomicAdd(&lcount[0], 1)] = n0 + p;   // at most one entry per candidate of the chunk
         }
         if (more) {
 #pragma unroll
@@ -376,55 +385,91 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
             old = old2;
         }
     }
+    __syncthreads();
+    const int nl = lcount[0];
+    if (nl > 0) {
+        if (tid == 0) lcount[1] = atomicAdd(a.nflag, nl);
+        __syncthreads();
+        const int64_t pos0 = lcount[1];
+        for (int i = tid; i < nl; i += kThreads)
+            if (pos0 + i < a.N) a.flist[pos0 + i] = lflag[i];
+    }
 }
 
-// Exact nearest centroid for the listed candidates, one wave per candidate:
-// fp64 direct differences summed over the features in index order with separate
-// multiply and add, lowest index on ties; then the move between the sums.
+// Exact nearest centroid for the listed candidates: a workgroup takes one
+// candidate at a time, one wave per group of 64 centroids, lanes over centroids.
+// A lane keeps its centroid in registers from one candidate to the next (read
+// from the feature-major copy, so the loads are coalesced).  A first pass computes every squared
+// distance in fp32 (direct differences, a sum of non-negative terms, so its
+// relative error is at most (D + 2) 2^-24 < 5e-6); only groups that hold a
+// distance within a factor 1 + 3e-5 of the smallest - every true minimiser is
+// among them - are evaluated exactly: fp64 direct differences summed over the
+// features in index order with separate multiply and add, lowest index on ties.
 __global__ void __launch_bounds__(kThreads) big_exact(BigArgs a) {
-    const int lane = threadIdx.x & 63;
-    const int64_t wave = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
-    const int64_t nwaves = (int64_t)gridDim.x * kWaves;
+    static_assert(KB_MAX_K <= kThreads, "one lane per centroid");
+    __shared__ float redm[kWaves];
+    __shared__ double redd[kWaves];
+    __shared__ int redj[kWaves];
+    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
     int64_t n = *a.nflag;
     if (n > a.N) n = a.N;
     const int D = a.D;
-    for (int64_t i = wave; i < n; i += nwaves) {
+    const int D4 = (D + 3) & ~3;
+    float c[KB_MAX_D];          // this lane's centroid, kept while the search stays the same
+    int g_held = -1;
+    for (int64_t i = blockIdx.x; i < n; i += gridDim.x) {
+        // everything up to the barriers is uniform over the workgroup
         const int pg = a.flist[i];
         if (pg < 0 || pg >= a.N) continue;
         const int g = upper_search(a.seg_off, a.G, pg);
         int n0, ng, k0, K;
         search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
         if (K <= 0) continue;
+        if (K > a.Kpad) K = a.Kpad;
         const float* xr = a.X + (size_t)pg * D;
         const float xv = lane < D ? xr[lane] : 0.f;
+        const int j = tid;                      // this lane's centroid
+        const bool group = wid * kWave < K;     // uniform over the wave
+        if (g != g_held) {
+            g_held = g;
+            const float* ct = a.centT + (size_t)g * D * a.Kpad + (j < K ? j : 0);
+#pragma unroll
+            for (int d = 0; d < KB_MAX_D; ++d) c[d] = (group && d < D) ? ct[(size_t)d * a.Kpad] : 0.f;
+        }
+        float d32 = INFINITY;
+        if (group) {
+            float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll
+            for (int d = 0; d < KB_MAX_D; d += 2) {
+                if (d < D4) {
+                    const float e0 = __shfl(xv, d) - c[d];
+                    const float e1 = __shfl(xv, d + 1) - c[d + 1];
+                    acc0 = fmaf(e0, e0, acc0);
+                    acc1 = fmaf(e1, e1, acc1);
+                }
+            }
+            if (j < K) d32 = acc0 + acc1;
+        }
+        float m32 = d32;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) m32 = fminf(m32, __shfl_xor(m32, o));
+        if (lane == 0) redm[wid] = m32;
+        __syncthreads();
+        m32 = fminf(fminf(redm[0], redm[1]), fminf(redm[2], redm[3]));
+        const float thr = m32 * 1.00003f + 1.0e-35f;   // the constant covers sums that underflow
         double bd = INFINITY;
         int bj = 0x7fffffff;
-        for (int j0 = 0; j0 < K; j0 += kWave) {
-            const int j = j0 + lane;
-            const float* cr = a.cent + (size_t)(k0 + (j < K ? j : 0)) * D;
-            // the lane's centroid row goes to registers first (independent loads)
-            float c[KB_MAX_D];
-            if ((D & 3) == 0) {
-#pragma unroll
-                for (int q = 0; q < KB_MAX_D / 4; ++q) {
-                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (4 * q < D) v = *reinterpret_cast<const float4*>(cr + 4 * q);
-                    c[4 * q] = v.x; c[4 * q + 1] = v.y; c[4 * q + 2] = v.z; c[4 * q + 3] = v.w;
-                }
-            } else {
-#pragma unroll
-                for (int d = 0; d < KB_MAX_D; ++d) c[d] = d < D ? cr[d] : 0.f;
-            }
+        if (group && __any(d32 <= thr)) {
             // features beyond D are 0 on both sides: their terms add +0.0
             double acc = 0.0;
 #pragma unroll
             for (int d = 0; d < KB_MAX_D; ++d) {
-                if (d < ((D + 3) & ~3)) {
+                if (d < D4) {
                     const double diff = __dsub_rn((double)__shfl(xv, d), (double)c[d]);
                     acc = __dadd_rn(acc, __dmul_rn(diff, diff));
                 }
             }
-            if (j < K && acc < bd) { bd = acc; bj = j; }
+            if (j < K) { bd = acc; bj = j; }
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
@@ -432,23 +477,39 @@ __global__ void __launch_bounds__(kThreads) big_exact(BigArgs a) {
             const int oj = __shfl_xor(bj, o);
             if (od < bd || (od == bd && oj < bj)) { bd = od; bj = oj; }
         }
-        if (lane == 0) a.prop[pg] = bj < K ? bj : 0;
+        if (lane == 0) { redd[wid] = bd; redj[wid] = bj; }
+        __syncthreads();
+        if (tid == 0) {
+            // groups in ascending centroid order: a strict compare keeps the lowest index
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w)
+                if (redd[w] < bd) { bd = redd[w]; bj = redj[w]; }
+            a.next[pg] = bj < K ? bj : 0;
+        }
     }
 }
 
-// Move the candidates whose proposal differs from their recorded cluster.  A
+// Move the candidates whose proposal differs from their previous cluster.  A
 // workgroup owns a group of kRowsPerGroup clusters of one search and a range of
-// its candidates: it scans the (recorded, proposed) pairs of the range, adds or
-// subtracts the rows that concern its clusters in LDS (integer atomics), and
-// flushes its partial sums to the global fixed-point sums once.  The last
-// cluster group of a range also records the new assignment.
+// its candidates.  It works through the range in batches: the (previous,
+// proposed) pairs of a batch are scanned and the candidates that join or leave
+// one of its clusters are listed in LDS; then 16 lanes per listed row (features
+// l, l + 16, ...) convert it to fixed point and add or subtract it in LDS
+// (integer atomics), with the next row already requested.  The partial sums go
+// to the global fixed-point sums once, at the end.
 constexpr int kRowsPerGroup = 16;
 constexpr int kUpdateRange = 16384;   // candidates per workgroup
+constexpr int kUpdateBatch = 4096;    // candidates scanned per list
 __global__ void __launch_bounds__(kThreads) big_update(BigArgs a) {
     __shared__ long long lsum[kRowsPerGroup * KB_MAX_D];
     __shared__ int lcnt[kRowsPerGroup];
     __shared__ int ltouched[kRowsPerGroup];
-    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+    __shared__ int list[kUpdateBatch];     // offset in the batch | (row joined + 1) << 16 | (row left + 1) << 24
+    __shared__ int nlist;
+    const int tid = threadIdx.x;
+    const int grp = tid >> 4, l16 = tid & 15;
+    constexpr int kGroups = kThreads / 16, E = KB_MAX_D / 16;
+    static_assert(kRowsPerGroup < 255 && kUpdateBatch <= 65536, "list entry packing");
     // blockIdx.x = (range chunk over all candidates), blockIdx.y = cluster group
     const int64_t r0 = (int64_t)blockIdx.x * kUpdateRange;
     if (r0 >= a.N) return;
@@ -469,39 +530,73 @@ __global__ void __launch_bounds__(kThreads) big_update(BigArgs a) {
         const int rows = K - jg0 < kRowsPerGroup ? K - jg0 : kRowsPerGroup;
         for (int i = tid; i < rows * D; i += kThreads) lsum[i] = 0;
         if (tid < kRowsPerGroup) { lcnt[tid] = 0; ltouched[tid] = 0; }
-        __syncthreads();
         const double scale = ldexp(1.0, fixed_shift(__uint_as_float(a.amax_bits[g]), ng));
-        for (int64_t base = q0 + wid * kWave; base < q1; base += kThreads) {
-            const int64_t k = base + lane;
-            int na = -1, oa = -1;
-            if (k < q1) {
-                na = a.prop[k];
-                na = (na >= 0 && na < K) ? na : 0;
-                oa = first ? -1 : a.assign[k];
-                oa = (oa >= 0 && oa < K) ? oa : -1;
-            }
-            const bool chg = k < q1 && na != oa;
-            const bool in_new = chg && na >= jg0 && na < jg0 + rows;
-            const bool in_old = chg && oa >= jg0 && oa < jg0 + rows;
-            unsigned long long mask = __ballot(in_new || in_old);
-            while (mask) {
-                const int b = __ffsll((long long)mask) - 1;
-                mask &= mask - 1;
-                const int nb = __shfl(in_new ? na - jg0 : -1, b);
-                const int ob = __shfl(in_old ? oa - jg0 : -1, b);
-                const float* xr = a.X + (size_t)(base + b) * D;
-                if (lane < D) {
-                    const long long q = to_fixed(xr[lane], scale);
-                    if (nb >= 0) atomicAdd(reinterpret_cast<unsigned long long*>(&lsum[nb * D + lane]), (unsigned long long)q);
-                    if (ob >= 0) atomicAdd(reinterpret_cast<unsigned long long*>(&lsum[ob * D + lane]), (unsigned long long)(-q));
-                }
-                if (lane == 0) {
-                    if (nb >= 0) { atomicAdd(&lcnt[nb], 1); ltouched[nb] = 1; }
-                    if (ob >= 0) { atomicSub(&lcnt[ob], 1); ltouched[ob] = 1; }
+        for (int64_t b0 = q0; b0 < q1; b0 += kUpdateBatch) {
+            if (tid == 0) nlist = 0;
+            __syncthreads();
+            const int nb = (int)(q1 - b0 < kUpdateBatch ? q1 - b0 : kUpdateBatch);
+            // scan: every thread takes kUpdateBatch / kThreads candidates, loads first
+            constexpr int U = kUpdateBatch / kThreads;
+            int na[U], oa[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int o = u * kThreads + tid;
+                na[u] = -1; oa[u] = -1;
+                if (o < nb) {
+                    na[u] = a.next[b0 + o];
+                    if (!first) oa[u] = a.prev[b0 + o];
                 }
             }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int o = u * kThreads + tid;
+                const int nn = (na[u] >= 0 && na[u] < K) ? na[u] : 0;
+                const int oo = (oa[u] >= 0 && oa[u] < K) ? oa[u] : -1;
+                const bool chg = o < nb && nn != oo;
+                const int jn = (chg && nn >= jg0 && nn < jg0 + rows) ? nn - jg0 + 1 : 0;
+                const int jo = (chg && oo >= jg0 && oo < jg0 + rows) ? oo - jg0 + 1 : 0;
+                if (jn | jo) list[atomicAdd(&nlist, 1)] = o | (jn << 16) | (jo << 24);
+            }
+            __syncthreads();
+            const int n = nlist;
+            // process: group `grp` takes entries grp, grp + 16, ...; the order in the
+            // list varies from run to run, the integer sums do not depend on it
+            float xv[E], xw[E];
+            int ent = grp < n ? list[grp] : 0;
+            if (grp < n) {
+                const float* xr = a.X + (size_t)(b0 + (ent & 0xffff)) * D;
+#pragma unroll
+                for (int e = 0; e < E; ++e) xv[e] = (l16 + 16 * e) < D ? xr[l16 + 16 * e] : 0.f;
+            }
+            for (int i = grp; i < n; i += kGroups) {
+                const int inext = i + kGroups;
+                int ent2 = 0;
+                if (inext < n) {
+                    ent2 = list[inext];
+                    const float* xr = a.X + (size_t)(b0 + (ent2 & 0xffff)) * D;
+#pragma unroll
+                    for (int e = 0; e < E; ++e) xw[e] = (l16 + 16 * e) < D ? xr[l16 + 16 * e] : 0.f;
+                }
+                const int jn = ((ent >> 16) & 0xff) - 1, jo = ((ent >> 24) & 0xff) - 1;
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    const int d = l16 + 16 * e;
+                    if (d < D) {
+                        const long long q = to_fixed(xv[e], scale);
+                        if (jn >= 0) atomicAdd(reinterpret_cast<unsigned long long*>(&lsum[jn * D + d]), (unsigned long long)q);
+                        if (jo >= 0) atomicAdd(reinterpret_cast<unsigned long long*>(&lsum[jo * D + d]), (unsigned long long)(-q));
+                    }
+                }
+                if (l16 == 0) {
+                    if (jn >= 0) { atomicAdd(&lcnt[jn], 1); ltouched[jn] = 1; }
+                    if (jo >= 0) { atomicSub(&lcnt[jo], 1); ltouched[jo] = 1; }
+                }
+                ent = ent2;
+#pragma unroll
+                for (int e = 0; e < E; ++e) xv[e] = xw[e];
+            }
+            __syncthreads();   // the list is rebuilt by the next batch
         }
-        __syncthreads();
         for (int i = tid; i < rows * D; i += kThreads) {
             const int jr = i / D;
             if (ltouched[jr])
@@ -516,15 +611,9 @@ __global__ void __launch_bounds__(kThreads) big_update(BigArgs a) {
     }
 }
 
-// assign <- proposal, after every cluster group has read the old assignment
-__global__ void __launch_bounds__(kThreads) big_commit(BigArgs a) {
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < a.N; k += stride)
-        a.assign[k] = a.prop[k];
-}
-
-// Per-chunk partial objective: 16 lanes per candidate, per-lane fp64 partial
-// sums in a fixed candidate order, fixed-order reduction.
+// Per-chunk partial objective: 16 lanes per candidate (features l, l + 16, ...),
+// four candidates in flight per group, per-lane fp64 partial sums in a fixed
+// candidate order, fixed-order reduction.
 __global__ void __launch_bounds__(kThreads) big_objective(BigArgs a) {
     __shared__ double red[kWaves];
     const int tid = threadIdx.x;
@@ -537,19 +626,40 @@ __global__ void __launch_bounds__(kThreads) big_objective(BigArgs a) {
     const int p0 = (c - a.chunk_off[g]) * kTilesPerChunk * 32;
     const int p1 = p0 + kTilesPerChunk * 32 < ng ? p0 + kTilesPerChunk * 32 : ng;
     const int sub = tid >> 4, l16 = tid & 15;
+    constexpr int U = 4, GR = kThreads / 16, E = KB_MAX_D / 16;
     double acc = 0.0;
     if (K > 0)
-        for (int p = p0 + sub; p < p1; p += kThreads / 16) {
-            int j = a.assign[(size_t)n0 + p];
-            j = (j >= 0 && j < K) ? j : 0;
-            const float* xr = a.X + (size_t)(n0 + p) * D;
-            const float* cr = a.cent + (size_t)(k0 + j) * D;
-            float sq = 0.f;
-            for (int d = 4 * l16; d < 4 * l16 + 4 && d < D; ++d) {
-                const float e0 = xr[d] - cr[d];
-                sq = fmaf(e0, e0, sq);
+        for (int pb = p0 + sub; pb < p1; pb += GR * U) {
+            int jj[U];
+            float xv[U][E], cv[U][E];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int p = pb + u * GR;
+                jj[u] = p < p1 ? a.assign[(size_t)n0 + p] : 0;
             }
-            acc += (double)sq;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int p = pb + u * GR;
+                const int j = (jj[u] >= 0 && jj[u] < K) ? jj[u] : 0;
+                const float* xr = a.X + (size_t)(n0 + (p < p1 ? p : p0)) * D;
+                const float* cr = a.cent + (size_t)(k0 + j) * D;
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    const int d = l16 + 16 * e;
+                    xv[u][e] = (p < p1 && d < D) ? xr[d] : 0.f;
+                    cv[u][e] = (p < p1 && d < D) ? cr[d] : 0.f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float sq = 0.f;
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    const float e0 = xv[u][e] - cv[u][e];
+                    sq = fmaf(e0, e0, sq);
+                }
+                acc += (double)sq;
+            }
         }
     acc = wave_sum_d(acc);
     if ((tid & 63) == 0) red[tid >> 6] = acc;
@@ -561,12 +671,22 @@ __global__ void __launch_bounds__(kThreads) big_objective(BigArgs a) {
     }
 }
 
+// One workgroup per search: the chunk partials are summed in a fixed order
+// (thread t takes chunks t, t + 256, ...; then a fixed tree).
 __global__ void __launch_bounds__(kThreads) big_objsum(BigArgs a) {
-    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    __shared__ double red[kWaves];
+    const int g = blockIdx.x, tid = threadIdx.x;
     if (g >= a.G) return;
     double J = 0.0;
-    for (int c = a.chunk_off[g]; c < a.chunk_off[g + 1]; ++c) J += a.partJ[c];
-    a.objective[g] = (float)J;
+    for (int c = a.chunk_off[g] + tid; c < a.chunk_off[g + 1]; c += kThreads) J += a.partJ[c];
+    J = wave_sum_d(J);
+    if ((tid & 63) == 0) red[tid >> 6] = J;
+    __syncthreads();
+    if (tid == 0) {
+        double r = red[0];
+        for (int w = 1; w < kWaves; ++w) r += red[w];
+        a.objective[g] = (float)r;
+    }
 }
 
 }  // namespace
@@ -583,6 +703,7 @@ BigWs big_ws_layout(const kb_batch& b, size_t base) {
     w.chunk_off = off; off += al256(sizeof(int32_t) * ((size_t)b.G + 1));
     w.sums = off;      off += al256(sizeof(long long) * (size_t)(b.Ksum > 0 ? b.Ksum : 1) * b.D);
     w.cnpad = off;     off += al256(sizeof(float) * (size_t)b.G * kpad);
+    w.centT = off;     off += al256(sizeof(float) * (size_t)b.G * kpad * b.D);
     w.aop = off;       off += al256((size_t)b.G * (kpad / 32) * ds * 2 * 64 * 16);
     w.dirty = off;     off += al256(sizeof(int) * (size_t)(b.Ksum > 0 ? b.Ksum : 1));
     w.amax = off;      off += al256(sizeof(unsigned) * (size_t)b.G);
@@ -605,13 +726,15 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
     a.xn = c.xn; a.split = reinterpret_cast<bf16x8*>(c.split);
     a.sums = reinterpret_cast<long long*>(ws + w.sums);
     a.cnpad = reinterpret_cast<float*>(ws + w.cnpad);
+    a.centT = reinterpret_cast<float*>(ws + w.centT);
     a.aop = reinterpret_cast<bf16x8*>(ws + w.aop);
     a.dirty = reinterpret_cast<int*>(ws + w.dirty);
     a.amax_bits = reinterpret_cast<unsigned*>(ws + w.amax);
     a.cnmax_bits = reinterpret_cast<unsigned*>(ws + w.cnmax);
     a.nflag = reinterpret_cast<int*>(ws + w.nflag);
     a.flist = c.a_new;
-    a.prop = reinterpret_cast<int32_t*>(ws + w.prop);
+    int32_t* const other = reinterpret_cast<int32_t*>(ws + w.prop);
+    a.prev = other; a.next = c.assign;
     a.partJ = reinterpret_cast<double*>(ws + w.partJ);
 
     const int ds = (b.D + 15) / 16;
@@ -627,7 +750,8 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
     const unsigned tile_blocks = (unsigned)((c.max_tiles + kWaves - 1) / kWaves);
     const unsigned row_blocks = (unsigned)(((size_t)b.G * w.kpad + kWaves - 1) / kWaves);
     const unsigned chunk_blocks = (unsigned)w.max_chunks;
-    const size_t lds = (size_t)(w.kpad / 32) * ds * 2 * 64 * 16 + (size_t)w.kpad * 4;
+    const size_t lds = (size_t)(w.kpad / 32) * ds * 2 * 64 * 16 + (size_t)w.kpad * 4 +
+                       (size_t)kTilesPerChunk * 32 * 4 + 16;
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     const dim3 upd_grid((unsigned)((b.N + kUpdateRange - 1) / kUpdateRange),
                         (unsigned)((a.Kmax + kRowsPerGroup - 1) / kRowsPerGroup));
@@ -640,15 +764,17 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
         if (tile_blocks) hipLaunchKernelGGL(big_presplit<DS_>, dim3(tile_blocks), dim3(kThreads), 0, st, a); \
         for (int it = 0; it < c.iters; ++it) {                                                   \
             a.it = it;                                                                           \
+            /* the two assignment buffers swap roles; the last step writes the caller's */       \
+            const bool mine = ((c.iters - 1 - it) & 1) == 0;                                     \
+            a.next = mine ? c.assign : other;                                                    \
+            a.prev = mine ? other : c.assign;                                                    \
             hipLaunchKernelGGL(big_renew<DS_>, dim3(row_blocks), dim3(kThreads), 0, st, a);      \
             hipLaunchKernelGGL(big_score<DS_>, dim3(chunk_blocks), dim3(kThreads), lds, st, a);  \
             hipLaunchKernelGGL(big_exact, dim3(1024), dim3(kThreads), 0, st, a);                 \
             hipLaunchKernelGGL(big_update, upd_grid, dim3(kThreads), 0, st, a);                  \
-            hipLaunchKernelGGL(big_commit, dim3(init_blocks), dim3(kThreads), 0, st, a);         \
         }                                                                                        \
         hipLaunchKernelGGL(big_objective, dim3(chunk_blocks), dim3(kThreads), 0, st, a);         \
-        hipLaunchKernelGGL(big_objsum, dim3((unsigned)((b.G + kThreads - 1) / kThreads)),        \
-                           dim3(kThreads), 0, st, a);                                            \
+        hipLaunchKernelGGL(big_objsum, dim3((unsigned)b.G), dim3(kThreads), 0, st, a);           \
         a.final_pass = 1;                                                                        \
         hipLaunchKernelGGL(big_renew<DS_>, dim3(row_blocks), dim3(kThreads), 0, st, a);          \
     } while (0)
