@@ -14,7 +14,6 @@ WsLayout ws_layout(const kb_batch& b) {
     w.misc = off;   off += align256(sizeof(int32_t) * 128);
     w.tile_off = off; off += align256(sizeof(int32_t) * ((size_t)b.G + 1));
     w.xn = off;     off += align256(sizeof(float) * (size_t)(b.N > 0 ? b.N : 1));
-    w.bnd = off;    off += align256(2 * sizeof(float) * (size_t)(b.N > 0 ? b.N : 1));
     // every search rounds its candidates up to whole tiles of 32
     w.max_tiles = (size_t)(b.N / 32) + (size_t)b.G;
     const size_t steps = (size_t)(b.D + 15) / 16;
@@ -116,7 +115,6 @@ static kb_status do_cluster(const kb_batch* b, const float* X, const float* cent
     c.a_new = (int32_t*)(base + w.a_new); c.order = order;
     c.tile_off = (const int32_t*)(base + w.tile_off); c.xn = (float*)(base + w.xn);
     c.split = (void*)(base + w.split); c.max_tiles = (int64_t)w.max_tiles;
-    c.bnd = (void*)(base + w.bnd);
     if (w.use_big) return dev(launch_cluster_big(*b, c, w.big, base, st));
     return dev(launch_cluster(*b, c, st));
 }

@@ -58,7 +58,6 @@ struct ClusterArgs {
     float* xn;
     bf16x8* split;
     int64_t max_tiles;
-    float2* bnd;       // [N] (upper bound on the distance to the own centroid, lower bound on all others)
     int use_bounds;
 };
 
@@ -200,49 +199,6 @@ __device__ __forceinline__ void score_valu(const ClusterArgs& a, const float* __
 // in operand order - [tile][K-step][hi|mid][lane] x 16 bytes - so a step streams
 // them back with fully coalesced 1 KB loads and no conversion work, and the next
 // tile's operands are requested before the current tile is scored.
-template <int DS>
-__device__ __forceinline__ float presplit(const ClusterArgs& a, const float* __restrict__ Xg,
-                                          int n0, int ng, int D, bf16x8* __restrict__ sp) {
-    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
-    const int m = lane & 31, h = lane >> 5;
-    const bool vec = (D & 3) == 0;
-    float am = 0.f;
-    for (int tile = wid; tile * 32 < ng; tile += kWaves) {
-        const int p = tile * 32 + m;
-        const bool valid = p < ng;
-        const float* xr = Xg + (size_t)(valid ? p : 0) * D;
-        float xnp = 0.f;
-        bf16x8* tp = sp + (size_t)tile * (DS * 2 * 64) + lane;
-#pragma unroll
-        for (int s = 0; s < DS; ++s) {
-            const int d0 = 16 * s + 8 * h;
-            float x[8];
-            if (vec) {
-                float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
-                if (valid && d0 < D) v0 = *reinterpret_cast<const float4*>(xr + d0);
-                if (valid && d0 + 4 < D) v1 = *reinterpret_cast<const float4*>(xr + d0 + 4);
-                x[0] = v0.x; x[1] = v0.y; x[2] = v0.z; x[3] = v0.w;
-                x[4] = v1.x; x[5] = v1.y; x[6] = v1.z; x[7] = v1.w;
-            } else {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) x[i] = (valid && d0 + i < D) ? xr[d0 + i] : 0.f;
-            }
-            bf16x8 hi, mid;
-            split8(x, hi, mid);
-            tp[(2 * s) * 64] = hi;
-            tp[(2 * s + 1) * 64] = mid;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                xnp = fmaf(x[i], x[i], xnp);
-                am = fmaxf(am, fabsf(x[i]));
-            }
-        }
-        xnp += __shfl_xor(xnp, 32);
-        if (valid && h == 0) a.xn[(size_t)n0 + p] = xnp;
-    }
-    return am;
-}
-
 // Centroid operands for the matrix cores: -2 c_j split into bf16 (hi, mid),
 // stored in LDS in operand order [tile of 32 rows][K-step][hi|mid][lane] so the
 // scorer reads them with conflict-free 16-byte loads.  Rows >= K are zero.
@@ -266,52 +222,146 @@ __device__ __forceinline__ void build_operands(const float* cent, int K, int DP,
     }
 }
 
-// Distance bounds (Hamerly): every candidate carries u >= distance to its own
-// centroid and l <= distance to every other centroid.  When the centroids move
-// by delta_j, u + delta_own < l - max_other delta proves that the nearest
-// centroid is unchanged and strictly nearest, so a tile whose 32 candidates all
-// pass is not scored in this step.  All roundings go the safe way.  This pass
-// moves the bounds of every candidate of the search (coalesced, several loads in
-// flight) and leaves one flag per tile in LDS: 1 = must be scored.
-__device__ __forceinline__ void bounds_pass(const ClusterArgs& a, int n0, int ng, int K,
-                                            const float* delta, unsigned char* tact) {
-    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
-    const float dj = lane < K ? delta[lane] : 0.f;     // K <= 64 on this path
-    const float dmax1 = wave_max_f(dj);
-    const int jmax = __ffsll((long long)__ballot(dj == dmax1)) - 1;
-    const float dmax2 = wave_max_f(lane == jmax ? 0.f : dj);
-    float2* bnd = a.bnd + (size_t)n0;
-    const int32_t* asg = a.assign + (size_t)n0;
-    constexpr int U = 4;
-    for (int base = wid * 64; base < ng; base += kThreads * U) {
-        int aa[U];
-        float2 bb[U];
+// Distance bounds.  When a candidate is scored, ub >= distance to its nearest
+// centroid and lb <= distance to every other centroid are known; its slack is
+// lb - ub.  If afterwards the centroids move, the nearest centroid b gets at most
+// sum delta_b closer/farther and any other centroid j at most sum delta_j, and
+// delta_b + delta_j never exceeds the two largest moves of a step.  So while
+//     slack > sum over the steps since scoring of (largest + second largest move)
+// the candidate's nearest centroid is unchanged and strictly nearest.  A tile of
+// 32 candidates keeps one number in LDS: (cumulative drift when it was scored) +
+// (smallest slack in the tile), rounded down; the cumulative drift is rounded up
+// at every step.  A tile whose number still exceeds the drift is not scored, and
+// not even fetched.  No per-candidate bound is stored anywhere.
+__device__ __forceinline__ float slack_of(float best, float second, float xn, float E) {
+    // d_best^2 <= best + |x|^2 + E and d_other^2 >= second + |x|^2 - E, with room
+    // for the rounding of |x|^2, of the square roots and of the difference
+    const float Eb = E + 4.0e-6f * xn;
+    const float ub = sqrtf(fmaxf(best + xn + Eb, 0.f)) * 1.0000005f;
+    const float lb = sqrtf(fmaxf(second + xn - Eb, 0.f)) * 0.9999995f;
+    return fmaxf((lb - ub) * 0.9999995f, 0.f);
+}
+__device__ __forceinline__ float wave_min_f(float v) {
 #pragma unroll
-        for (int q = 0; q < U; ++q) {
-            const int p = base + q * kThreads + lane;
-            aa[q] = p < ng ? asg[p] : -2;
-            bb[q] = p < ng ? bnd[p] : make_float2(0.f, 1.f);
+    for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o));
+    return v;
+}
+// drift + slack, rounded down (both non-negative)
+__device__ __forceinline__ float tile_limit(float drift, float slack) {
+    return (drift + slack) * 0.9999995f;
+}
+
+// Scores of one tile of 32 candidates (operands Bh, Bm) against the K <= 64
+// centroids: best score, second best and the row of the best, the same in both
+// half-waves.
+template <int DS, int MT>
+__device__ __forceinline__ void tile_scores(const bf16x8 (&Bh)[DS], const bf16x8 (&Bm)[DS],
+                                            const float* cn, const bf16x8* aop, int mtiles,
+                                            int lane, float& best, float& second, int& bi) {
+    const int h = lane >> 5;
+    // Accumulators start at |c_j|^2 (padded with a huge value for rows >= K),
+    // read from LDS in accumulator layout.  Two accumulators are always in
+    // flight so that consecutive matrix instructions never depend on each
+    // other: the two centroid tiles when there are two, otherwise the
+    // hi*mid products are summed apart and added at the end.
+    constexpr int NA = 2;
+    f32x16 acc[NA];
+    const bool two = MT == 2 && mtiles == 2;
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+        const float4 c4 = *reinterpret_cast<const float4*>(cn + 8 * g4 + 4 * h);
+        acc[0][4 * g4 + 0] = c4.x; acc[0][4 * g4 + 1] = c4.y;
+        acc[0][4 * g4 + 2] = c4.z; acc[0][4 * g4 + 3] = c4.w;
+    }
+    if (two) {
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+            const float4 c4 = *reinterpret_cast<const float4*>(cn + 32 + 8 * g4 + 4 * h);
+            acc[1][4 * g4 + 0] = c4.x; acc[1][4 * g4 + 1] = c4.y;
+            acc[1][4 * g4 + 2] = c4.z; acc[1][4 * g4 + 3] = c4.w;
         }
 #pragma unroll
-        for (int q = 0; q < U; ++q) {
-            const int p0 = base + q * kThreads;         // first candidate of this wave's 64
-            if (p0 < ng) {                               // uniform over the wave
-                bool pass = true;
-                if (aa[q] != -2) {
-                    const int j = (aa[q] >= 0 && aa[q] < K) ? aa[q] : 0;
-                    const float u2 = (bb[q].x + delta[j]) * 1.0000005f;
-                    float l2 = bb[q].y - (j == jmax ? dmax2 : dmax1);
-                    l2 = l2 > 0.f ? l2 * 0.9999995f : l2;
-                    pass = aa[q] >= 0 && u2 < l2;
-                    bnd[p0 + lane] = make_float2(u2, l2);
-                }
-                const unsigned long long ok = __ballot(pass);
-                if (lane == 0) {
-                    tact[p0 >> 5] = (unsigned)ok != 0xffffffffu;
-                    if (p0 + 32 < ng) tact[(p0 >> 5) + 1] = (unsigned)(ok >> 32) != 0xffffffffu;
-                }
+        for (int s = 0; s < DS; ++s) {
+            // centroid operands of this K-step, straight from LDS (operand order)
+            const bf16x8 a0h = aop[((0 * DS + s) * 2 + 0) * 64 + lane];
+            const bf16x8 a0m = aop[((0 * DS + s) * 2 + 1) * 64 + lane];
+            const bf16x8 a1h = aop[((1 * DS + s) * 2 + 0) * 64 + lane];
+            const bf16x8 a1m = aop[((1 * DS + s) * 2 + 1) * 64 + lane];
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bh[s], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, Bh[s], acc[1], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bm[s], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, Bm[s], acc[1], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0m, Bh[s], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1m, Bh[s], acc[1], 0, 0, 0);
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[1][r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < DS; ++s) {
+            const bf16x8 a0h = aop[((0 * DS + s) * 2 + 0) * 64 + lane];
+            const bf16x8 a0m = aop[((0 * DS + s) * 2 + 1) * 64 + lane];
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bh[s], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bm[s], acc[1], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0m, Bh[s], acc[0], 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[0][r] += acc[1][r];
+    }
+    // Best, second best and the row of the best among this lane's rows: four
+    // independent chains of 8 (or 4) values, merged pairwise.  The
+    // lane-dependent part of the row number (4h) is added afterwards.
+    float cb[4], cs[4];
+    int ci[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) { cb[c] = kBig * 4.f; cs[c] = kBig * 4.f; ci[c] = 0; }
+    if (two) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int c = 2 * t + (r >> 3);
+                const float v = acc[t][r];
+                const bool lt = v < cb[c];
+                cs[c] = __builtin_amdgcn_fmed3f(cb[c], cs[c], v);
+                cb[c] = lt ? v : cb[c];
+                ci[c] = lt ? (t * 32 + 8 * (r >> 2) + (r & 3)) : ci[c];
             }
         }
+    } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int c = r >> 2;
+            const float v = acc[0][r];
+            const bool lt = v < cb[c];
+            cs[c] = __builtin_amdgcn_fmed3f(cb[c], cs[c], v);
+            cb[c] = lt ? v : cb[c];
+            ci[c] = lt ? (8 * (r >> 2) + (r & 3)) : ci[c];
+        }
+    }
+    auto merge = [](float& b1, float& s1, int& i1, float b2, float s2, int i2) {
+        const bool take = b2 < b1;
+        const float hi2 = take ? b1 : b2;        // the larger of the two bests
+        const float sm = s2 < s1 ? s2 : s1;
+        s1 = sm < hi2 ? sm : hi2;
+        i1 = take ? i2 : i1;
+        b1 = take ? b2 : b1;
+    };
+    merge(cb[0], cs[0], ci[0], cb[1], cs[1], ci[1]);
+    merge(cb[2], cs[2], ci[2], cb[3], cs[3], ci[3]);
+    merge(cb[0], cs[0], ci[0], cb[2], cs[2], ci[2]);
+    best = cb[0]; second = cs[0];
+    bi = ci[0] + 4 * h;
+    // the two half-waves hold complementary centroid rows of the same
+    // candidate: one lane-swap per value hands both halves both results
+    {
+        const auto rb = __builtin_amdgcn_permlane32_swap(__float_as_uint(best), __float_as_uint(best), false, false);
+        const auto rs = __builtin_amdgcn_permlane32_swap(__float_as_uint(second), __float_as_uint(second), false, false);
+        const auto ri = __builtin_amdgcn_permlane32_swap((unsigned)bi, (unsigned)bi, false, false);
+        float b0 = __uint_as_float(rb[0]), s0 = __uint_as_float(rs[0]);
+        int i0 = (int)ri[0];
+        merge(b0, s0, i0, __uint_as_float(rb[1]), __uint_as_float(rs[1]), (int)ri[1]);
+        best = b0; second = s0; bi = i0;
     }
 }
 
@@ -320,14 +370,13 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
                                           const bf16x8* __restrict__ sp,
                                           int n0, int ng, int K, int D, int DP, int SP,
                                           const float* cent, const float* cn, float cnmax,
-                                          bool first, double scale, long long* sums, int* cnt,
+                                          double scale, long long* sums, int* cnt,
                                           int* nflag, int* flist, const bf16x8* aop, int* dirty,
-                                          const unsigned char* tact, bool bounds, int* nmoved) {
+                                          float* thr, float drift) {
     const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
     const int m = lane & 31, h = lane >> 5;
     const int mtiles = (K + 31) >> 5;
-    const float kappa = 3.1f * 1.52587890625e-05f + (float)(3 * 16 * DS + 4) * 2.384185791015625e-07f;
-    const bool vec = (D & 3) == 0;
+    const float kappa = mfma_kappa(DS);
 
     auto load_tile = [&](int tile, bf16x8 (&bh)[DS], bf16x8 (&bm)[DS], float& xnv, int& oldv) {
         const bf16x8* tp = sp + (size_t)tile * (DS * 2 * 64) + lane;
@@ -336,16 +385,15 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
             bh[s] = tp[(2 * s) * 64];
             bm[s] = tp[(2 * s + 1) * 64];
         }
+        // no branch around any of these loads (rows past the end read the last row):
+        // the number of loads in flight is then known at compile time, and waiting
+        // for one tile does not also wait for the tile requested after it
         const int p = tile * 32 + m;
-        xnv = 0.f;
-        oldv = -1;
-        if (p < ng) {
-            xnv = a.xn[(size_t)n0 + p];
-            if (!first) oldv = a.assign[(size_t)n0 + p];
-        }
+        const int pc = p < ng ? p : ng - 1;
+        xnv = a.xn[(size_t)n0 + pc];
+        oldv = a.assign[(size_t)n0 + pc];
     };
 
-    float2* bnd = a.bnd + (size_t)n0;
     const int ntiles = (ng + 31) >> 5;
     const int ntw = ntiles > wid ? (ntiles - wid + kWaves - 1) / kWaves : 0;   // tiles of this wave
 
@@ -353,184 +401,211 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
     for (int i0 = 0; i0 < ntw; i0 += 64) {
         const int nb = ntw - i0 < 64 ? ntw - i0 : 64;
         unsigned long long act = nb == 64 ? ~0ull : ((1ull << nb) - 1ull);
-        if (bounds) {
-            // tiles the bound pass could not clear
+        if (a.use_bounds) {
+            // tiles whose slack the centroids' drift has not used up keep their clusters
             const int ti = wid + kWaves * (i0 + lane);
-            act = __ballot(lane < nb && tact[ti] != 0);
+            act = __ballot(lane < nb && !(thr[ti] > drift));
         }
         bf16x8 Bh[DS], Bm[DS];
-        float xn = 0.f;
-        int old = -1;
+        float xn;
+        int old;
         int cur = -1;
         if (act) {
             cur = __ffsll((long long)act) - 1;
             act &= act - 1;
-            load_tile(wid + kWaves * (i0 + cur), Bh, Bm, xn, old);
+        }
+        {
+            const int t0 = wid + kWaves * (i0 + (cur >= 0 ? cur : 0));
+            load_tile(t0 < ntiles ? t0 : ntiles - 1, Bh, Bm, xn, old);
         }
         while (cur >= 0) {
         const int tile = wid + kWaves * (i0 + cur);
         const int p = tile * 32 + m;
         const bool valid = p < ng;
-        // request the next tile before scoring this one
+        // request the next tile before scoring this one (the same tile again when
+        // there is no next one)
         bf16x8 Bh2[DS], Bm2[DS];
-        float xn2 = 0.f;
-        int old2 = -1;
+        float xn2;
+        int old2;
         int nxt = -1;
         if (act) {
             nxt = __ffsll((long long)act) - 1;
             act &= act - 1;
-            load_tile(wid + kWaves * (i0 + nxt), Bh2, Bm2, xn2, old2);
         }
-        const bool more = nxt >= 0;
-        old = (old >= 0 && old < K) ? old : -1;
+        load_tile(nxt >= 0 ? wid + kWaves * (i0 + nxt) : tile, Bh2, Bm2, xn2, old2);
+        old = (valid && old >= 0 && old < K) ? old : -1;
 
-        // Accumulators start at |c_j|^2 (padded with a huge value for rows >= K),
-        // read from LDS in accumulator layout.  Two accumulators are always in
-        // flight so that consecutive matrix instructions never depend on each
-        // other: the two centroid tiles when there are two, otherwise the
-        // hi*mid products are summed apart and added at the end.
-        constexpr int NA = 2;
-        f32x16 acc[NA];
-        const bool two = MT == 2 && mtiles == 2;
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-            const float4 c4 = *reinterpret_cast<const float4*>(cn + 8 * g4 + 4 * h);
-            acc[0][4 * g4 + 0] = c4.x; acc[0][4 * g4 + 1] = c4.y;
-            acc[0][4 * g4 + 2] = c4.z; acc[0][4 * g4 + 3] = c4.w;
-        }
-        if (two) {
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                const float4 c4 = *reinterpret_cast<const float4*>(cn + 32 + 8 * g4 + 4 * h);
-                acc[1][4 * g4 + 0] = c4.x; acc[1][4 * g4 + 1] = c4.y;
-                acc[1][4 * g4 + 2] = c4.z; acc[1][4 * g4 + 3] = c4.w;
-            }
-#pragma unroll
-            for (int s = 0; s < DS; ++s) {
-                // centroid operands of this K-step, straight from LDS (operand order)
-                const bf16x8 a0h = aop[((0 * DS + s) * 2 + 0) * 64 + lane];
-                const bf16x8 a0m = aop[((0 * DS + s) * 2 + 1) * 64 + lane];
-                const bf16x8 a1h = aop[((1 * DS + s) * 2 + 0) * 64 + lane];
-                const bf16x8 a1m = aop[((1 * DS + s) * 2 + 1) * 64 + lane];
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bh[s], acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, Bh[s], acc[1], 0, 0, 0);
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bm[s], acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, Bm[s], acc[1], 0, 0, 0);
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0m, Bh[s], acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1m, Bh[s], acc[1], 0, 0, 0);
-            }
-        } else {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[1][r] = 0.f;
-#pragma unroll
-            for (int s = 0; s < DS; ++s) {
-                const bf16x8 a0h = aop[((0 * DS + s) * 2 + 0) * 64 + lane];
-                const bf16x8 a0m = aop[((0 * DS + s) * 2 + 1) * 64 + lane];
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bh[s], acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bm[s], acc[1], 0, 0, 0);
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0m, Bh[s], acc[0], 0, 0, 0);
-            }
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[0][r] += acc[1][r];
-        }
-        // Best, second best and the row of the best among this lane's rows: four
-        // independent chains of 8 (or 4) values, merged pairwise.  The
-        // lane-dependent part of the row number (4h) is added afterwards.
-        float cb[4], cs[4];
-        int ci[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) { cb[c] = kBig * 4.f; cs[c] = kBig * 4.f; ci[c] = 0; }
-        if (two) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const int c = 2 * t + (r >> 3);
-                    const float v = acc[t][r];
-                    const bool lt = v < cb[c];
-                    cs[c] = __builtin_amdgcn_fmed3f(cb[c], cs[c], v);
-                    cb[c] = lt ? v : cb[c];
-                    ci[c] = lt ? (t * 32 + 8 * (r >> 2) + (r & 3)) : ci[c];
-                }
-            }
-        } else {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int c = r >> 2;
-                const float v = acc[0][r];
-                const bool lt = v < cb[c];
-                cs[c] = __builtin_amdgcn_fmed3f(cb[c], cs[c], v);
-                cb[c] = lt ? v : cb[c];
-                ci[c] = lt ? (8 * (r >> 2) + (r & 3)) : ci[c];
-            }
-        }
-        auto merge = [](float& b1, float& s1, int& i1, float b2, float s2, int i2) {
-            const bool take = b2 < b1;
-            const float hi2 = take ? b1 : b2;        // the larger of the two bests
-            const float sm = s2 < s1 ? s2 : s1;
-            s1 = sm < hi2 ? sm : hi2;
-            i1 = take ? i2 : i1;
-            b1 = take ? b2 : b1;
-        };
-        merge(cb[0], cs[0], ci[0], cb[1], cs[1], ci[1]);
-        merge(cb[2], cs[2], ci[2], cb[3], cs[3], ci[3]);
-        merge(cb[0], cs[0], ci[0], cb[2], cs[2], ci[2]);
-        float best = cb[0], second = cs[0];
-        int bi = ci[0] + 4 * h;
-        // the two half-waves hold complementary centroid rows of the same
-        // candidate: one lane-swap per value hands both halves both results
-        {
-            const auto rb = __builtin_amdgcn_permlane32_swap(__float_as_uint(best), __float_as_uint(best), false, false);
-            const auto rs = __builtin_amdgcn_permlane32_swap(__float_as_uint(second), __float_as_uint(second), false, false);
-            const auto ri = __builtin_amdgcn_permlane32_swap((unsigned)bi, (unsigned)bi, false, false);
-            float b0 = __uint_as_float(rb[0]), s0 = __uint_as_float(rs[0]);
-            int i0 = (int)ri[0];
-            merge(b0, s0, i0, __uint_as_float(rb[1]), __uint_as_float(rs[1]), (int)ri[1]);
-            best = b0; second = s0; bi = i0;
-        }
+        float best, second;
+        int bi;
+        tile_scores<DS, MT>(Bh, Bm, cn, aop, mtiles, lane, best, second, bi);
         bi = bi < K ? bi : 0;
         const float E = kappa * (xn + cnmax);
         const bool certain = (K == 1) || ((second - best) > 2.f * E);
         const bool chg = valid && certain && (bi != old);
+        // Candidates that change cluster: lanes 0..31 (one per candidate) fix counts
+        // and flags; then the wave takes the movers eight at a time, lanes over
+        // features: the fp32 rows are read again (all loads first), converted to
+        // fixed point and moved between the sums.
+        unsigned rem = (unsigned)__ballot(chg && h == 0);
+        if (rem) {
+            any |= 1;
+            if (chg && h == 0) {
+                atomicAdd(&cnt[bi], 1);
+                dirty[bi] = 1;
+                if (old >= 0) { atomicSub(&cnt[old], 1); dirty[old] = 1; }
+                a.assign[(size_t)n0 + p] = bi;
+            }
+            const int lc = lane < D ? lane : 0;
+            while (rem) {
+                constexpr int MV = 8;
+                int mb[MV];
+                float xq[MV];
+#pragma unroll
+                for (int q = 0; q < MV; ++q) {
+                    mb[q] = rem ? __ffs((int)rem) - 1 : -1;
+                    rem &= rem - 1;
+                }
+                // unconditional loads (an unused slot reads the first mover's row again)
+#pragma unroll
+                for (int q = 0; q < MV; ++q)
+                    xq[q] = Xg[(size_t)(tile * 32 + (mb[q] >= 0 ? mb[q] : mb[0])) * D + lc];
+#pragma unroll
+                for (int q = 0; q < MV; ++q) {
+                    if (mb[q] >= 0) {                       // uniform over the wave
+                        const int nb2 = __shfl(bi, mb[q]);
+                        const int ob2 = __shfl(old, mb[q]);
+                        if (lane < D) {
+                            const long long qf = to_fixed(xq[q], scale);
+                            lds_add(&sums[(size_t)nb2 * SP + lane], qf);
+                            if (ob2 >= 0) lds_add(&sums[(size_t)ob2 * SP + lane], -qf);
+                        }
+                    }
+                }
+            }
+        }
+        if (valid && h == 0) {
+            a.a_new[(size_t)n0 + p] = certain ? bi : (bi | kFlagBit);
+            if (!certain) {
+                const int pos = atomicAdd(nflag, 1);
+                if (pos < kFlagCap) flist[pos] = p;
+            }
+        }
+        if (__any(valid && !certain)) any |= 2;
+        if (a.use_bounds) {
+            // the exact pass lowers the limit for the candidates it decides
+            const float sl = wave_min_f((valid && certain) ? slack_of(best, second, xn, E) : INFINITY);
+            if (lane == 0) thr[tile] = tile_limit(drift, sl);
+        }
+#pragma unroll
+        for (int s = 0; s < DS; ++s) { Bh[s] = Bh2[s]; Bm[s] = Bm2[s]; }
+        xn = xn2;
+        old = old2;
+        cur = nxt;
+        }
+    }
+    return any;   // bit 0: some candidate moved, bit 1: some candidate needs the exact pass
+}
+
+// First step of a call on the matrix-core path.  One pass over the fp32 rows
+// does everything the later steps get from the workspace: the rows are split
+// into bf16 (hi, mid) operands (written to the workspace for the steps that
+// follow, with |x|^2), scored from the registers that hold them, and - every
+// candidate joins a cluster in the first step - added to the fixed-point sums
+// from the same registers.  Returns max |x| over the rows this thread saw in
+// `am_out`, which the caller checks against the estimate the scale was taken from.
+template <int DS, int MT>
+__device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __restrict__ Xg,
+                                           bf16x8* __restrict__ spw, int n0, int ng, int K, int D,
+                                           int SP, const float* cn, float cnmax, double scale,
+                                           long long* sums, int* cnt, int* nflag, int* flist,
+                                           const bf16x8* aop, int* dirty, float* thr,
+                                           float& am_out, double& sq_out) {
+    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    const int m = lane & 31, h = lane >> 5;
+    const int mtiles = (K + 31) >> 5;
+    const float kappa = mfma_kappa(DS);
+    const bool vec = (D & 3) == 0;
+    const int ntiles = (ng + 31) >> 5;
+
+    // this lane's 8 features of every 16-feature step of row `tile * 32 + m`
+    auto load_rows = [&](int tile, float4 (&r)[DS][2]) {
+        const int p = tile * 32 + m;
+        const bool valid = p < ng;
+        const float* xr = Xg + (size_t)(valid ? p : 0) * D;
+#pragma unroll
+        for (int s = 0; s < DS; ++s) {
+            const int d0 = 16 * s + 8 * h;
+            r[s][0] = make_float4(0.f, 0.f, 0.f, 0.f);
+            r[s][1] = r[s][0];
+            if (vec) {
+                if (valid && d0 < D) r[s][0] = *reinterpret_cast<const float4*>(xr + d0);
+                if (valid && d0 + 4 < D) r[s][1] = *reinterpret_cast<const float4*>(xr + d0 + 4);
+            } else if (valid) {
+                if (d0 + 0 < D) r[s][0].x = xr[d0 + 0];
+                if (d0 + 1 < D) r[s][0].y = xr[d0 + 1];
+                if (d0 + 2 < D) r[s][0].z = xr[d0 + 2];
+                if (d0 + 3 < D) r[s][0].w = xr[d0 + 3];
+                if (d0 + 4 < D) r[s][1].x = xr[d0 + 4];
+                if (d0 + 5 < D) r[s][1].y = xr[d0 + 5];
+                if (d0 + 6 < D) r[s][1].z = xr[d0 + 6];
+                if (d0 + 7 < D) r[s][1].w = xr[d0 + 7];
+            }
+        }
+    };
+
+    float am = 0.f;
+    double sq = 0.0;          // sum of x^2 over this lane's features, exact products
+    int any = 0;
+    float4 cur[DS][2], nxt[DS][2];
+    if (wid < ntiles) load_rows(wid, cur);
+    for (int tile = wid; tile < ntiles; tile += kWaves) {
+        const bool more = tile + kWaves < ntiles;
+        if (more) load_rows(tile + kWaves, nxt);
+        const int p = tile * 32 + m;
+        const bool valid = p < ng;
+        float xv[DS][8];
+        bf16x8 Bh[DS], Bm[DS];
+        float xn = 0.f;
+        bf16x8* tp = spw + (size_t)tile * (DS * 2 * 64) + lane;
+#pragma unroll
+        for (int s = 0; s < DS; ++s) {
+            xv[s][0] = cur[s][0].x; xv[s][1] = cur[s][0].y; xv[s][2] = cur[s][0].z; xv[s][3] = cur[s][0].w;
+            xv[s][4] = cur[s][1].x; xv[s][5] = cur[s][1].y; xv[s][6] = cur[s][1].z; xv[s][7] = cur[s][1].w;
+            split8(xv[s], Bh[s], Bm[s]);
+            tp[(2 * s) * 64] = Bh[s];
+            tp[(2 * s + 1) * 64] = Bm[s];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                xn = fmaf(xv[s][i], xv[s][i], xn);
+                am = fmaxf(am, fabsf(xv[s][i]));
+                sq = fma((double)xv[s][i], (double)xv[s][i], sq);
+            }
+        }
+        xn += __shfl_xor(xn, 32);
+        if (valid && h == 0) a.xn[(size_t)n0 + p] = xn;
+
+        float best, second;
+        int bi;
+        tile_scores<DS, MT>(Bh, Bm, cn, aop, mtiles, lane, best, second, bi);
+        bi = bi < K ? bi : 0;
+        const float E = kappa * (xn + cnmax);
+        const bool certain = (K == 1) || ((second - best) > 2.f * E);
+        const bool chg = valid && certain;
         const unsigned long long cmask = __ballot(chg && h == 0);
         if (cmask) {
             any |= 1;
-            if (lane == 0) atomicAdd(nmoved, __popcll(cmask));
             if (chg) {
-                // the fp32 row is read again (rare after the first steps): all loads
-                // first, then the atomics
-                const float* xr = Xg + (size_t)p * D;
-                float xv[DS][8];
-#pragma unroll
-                for (int s = 0; s < DS; ++s) {
-                    const int d0 = 16 * s + 8 * h;
-                    if (vec) {
-                        float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
-                        if (d0 < D) v0 = *reinterpret_cast<const float4*>(xr + d0);
-                        if (d0 + 4 < D) v1 = *reinterpret_cast<const float4*>(xr + d0 + 4);
-                        xv[s][0] = v0.x; xv[s][1] = v0.y; xv[s][2] = v0.z; xv[s][3] = v0.w;
-                        xv[s][4] = v1.x; xv[s][5] = v1.y; xv[s][6] = v1.z; xv[s][7] = v1.w;
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) xv[s][i] = (d0 + i < D) ? xr[d0 + i] : 0.f;
-                    }
-                }
 #pragma unroll
                 for (int s = 0; s < DS; ++s) {
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
                         const int d = 16 * s + 8 * h + i;
-                        if (d < D) {
-                            const long long q = to_fixed(xv[s][i], scale);
-                            lds_add(&sums[(size_t)bi * SP + d], q);
-                            if (old >= 0) lds_add(&sums[(size_t)old * SP + d], -q);
-                        }
+                        if (d < D) lds_add(&sums[(size_t)bi * SP + d], to_fixed(xv[s][i], scale));
                     }
                 }
                 if (h == 0) {
                     atomicAdd(&cnt[bi], 1);
                     dirty[bi] = 1;
-                    if (old >= 0) { atomicSub(&cnt[old], 1); dirty[old] = 1; }
                     a.assign[(size_t)n0 + p] = bi;
                 }
             }
@@ -538,32 +613,25 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
         if (valid && h == 0) {
             a.a_new[(size_t)n0 + p] = certain ? bi : (bi | kFlagBit);
             if (!certain) {
-                // a candidate left to the exact pass in the very first step has no cluster yet
-                if (first) a.assign[(size_t)n0 + p] = -1;
+                // left to the exact pass: no cluster yet
+                a.assign[(size_t)n0 + p] = -1;
                 const int pos = atomicAdd(nflag, 1);
                 if (pos < kFlagCap) flist[pos] = p;
             }
         }
         if (__any(valid && !certain)) any |= 2;
-        if (a.use_bounds && valid && h == 0) {
-            // d_best^2 <= best + |x|^2 + E and d_other^2 >= second + |x|^2 - E, with
-            // room for the rounding of |x|^2 and of the square roots; a doubtful
-            // candidate gets bounds that force the next step to score it again
-            const float Eb = E + 4.0e-6f * xn;
-            const float ub = sqrtf(fmaxf(best + xn + Eb, 0.f)) * 1.0000005f;
-            const float lb = sqrtf(fmaxf(second + xn - Eb, 0.f)) * 0.9999995f;
-            bnd[p] = certain ? make_float2(ub, lb) : make_float2(kBig, 0.f);
+        if (a.use_bounds) {
+            const float sl = wave_min_f((valid && certain) ? slack_of(best, second, xn, E) : INFINITY);
+            if (lane == 0) thr[tile] = tile_limit(0.f, sl);
         }
         if (more) {
 #pragma unroll
-            for (int s = 0; s < DS; ++s) { Bh[s] = Bh2[s]; Bm[s] = Bm2[s]; }
-            xn = xn2;
-            old = old2;
-        }
-        cur = nxt;
+            for (int s = 0; s < DS; ++s) { cur[s][0] = nxt[s][0]; cur[s][1] = nxt[s][1]; }
         }
     }
-    return any;   // bit 0: some candidate moved, bit 1: some candidate needs the exact pass
+    am_out = am;
+    sq_out = sq;
+    return any;
 }
 
 // ---- phase R -----------------------------------------------------------------
@@ -621,7 +689,8 @@ __device__ __forceinline__ void refine(const ClusterArgs& a, const float* __rest
 __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* __restrict__ Xg,
                                              int n0, int n, const int* flist, int K, int D, int DP,
                                              int SP, const float* cent, double scale,
-                                             long long* sums, int* cnt, int* dirty, int* nmoved) {
+                                             long long* sums, int* cnt, int* dirty, float* thr,
+                                             float drift) {
     const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
     int any = 0;
     for (int i = wid; i < n; i += kWaves) {
@@ -664,9 +733,12 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
             sd = sm < hi2 ? sm : hi2;
             if (take) { bd = od; bj = oj; }
         }
-        if (a.use_bounds && lane == 0)
-            a.bnd[(size_t)n0 + p] = make_float2((float)sqrt(bd) * 1.0000005f,
-                                                (float)sqrt(sd) * 0.9999995f);
+        if (a.use_bounds && lane == 0) {
+            // exact distances: the slack is their difference, rounded down; limits are
+            // non-negative floats, which order like their bit patterns
+            const float sl = fmaxf(((float)sqrt(sd) * 0.9999995f - (float)sqrt(bd) * 1.0000005f) * 0.9999995f, 0.f);
+            atomicMin(reinterpret_cast<unsigned*>(&thr[p >> 5]), __float_as_uint(tile_limit(drift, sl)));
+        }
         bj = bj < K ? bj : 0;
         old = (old >= 0 && old < K) ? old : -1;
         if (bj != old) {
@@ -677,7 +749,6 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
                 if (old >= 0) lds_add(&sums[(size_t)old * SP + lane], -q);
             }
             if (lane == 0) {
-                atomicAdd(nmoved, 1);
                 atomicAdd(&cnt[bj], 1);
                 dirty[bj] = 1;
                 if (old >= 0) { atomicSub(&cnt[old], 1); dirty[old] = 1; }
@@ -735,7 +806,7 @@ __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restr
 
 // LDS layout shared by the kernel and the host-side size computation.
 struct Lds {
-    size_t sums, cent, cn, cnt, dirty, delta, flist, aop, tact, total;
+    size_t sums, cent, cn, cnt, dirty, delta, flist, aop, thr, total;
 };
 __host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP, int Nmax) {
     const int SP = D | 1;   // odd row stride: clusters spread over the LDS banks
@@ -752,8 +823,8 @@ __host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP, int Nmax) {
     off = (off + 15) & ~(size_t)15;
     // centroid operands of the matrix-core scorer (only when Kmax <= 64)
     l.aop = off;  if (Kmax <= 64) off += (size_t)((Kmax + 31) / 32) * ((DP - 4) / 16) * 2 * 64 * 16;
-    // one "must be scored" flag per tile of 32 candidates
-    l.tact = off; if (Kmax <= 64) off += (((size_t)Nmax + 31) / 32 + 15) & ~(size_t)15;
+    // one drift limit per tile of 32 candidates
+    l.thr = off; if (Kmax <= 64) off += ((((size_t)Nmax + 31) / 32) * 4 + 15) & ~(size_t)15;
     l.total = off;
     return l;
 }
@@ -788,9 +859,8 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     int* flist = reinterpret_cast<int*>(smem + L.flist);             // [kFlagCap]
     int* dirty = reinterpret_cast<int*>(smem + L.dirty);             // [2][Kmax]
     float* delta = reinterpret_cast<float*>(smem + L.delta);         // [Kmax]
-    unsigned char* tact = smem + L.tact;                             // [tiles]
+    float* thr = reinterpret_cast<float*>(smem + L.thr);             // [tiles]
     int* nflag = reinterpret_cast<int*>(smem + 64);                  // behind the two reduction slots
-    int* nmoved = reinterpret_cast<int*>(smem + 68);                 // [2] candidates moved, by step parity
     bf16x8* aop = reinterpret_cast<bf16x8*>(smem + L.aop);
 
     const float* Xg = a.X + (size_t)n0 * D;
@@ -806,7 +876,6 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     for (int idx = tid; idx < K * SP; idx += kThreads) sums[idx] = 0;
     for (int j = tid; j < K; j += kThreads) cnt[j] = 0;
     for (int j = K + tid; j < ((a.Kmax + 31) & ~31); j += kThreads) cn[j] = kBig;
-    if (tid == 0) { nmoved[0] = 0; nmoved[1] = 0; }
     __syncthreads();
 
     if (a.iters == 0) {
@@ -817,16 +886,22 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
         return;
     }
 
-    // fixed-point scale: |x| < 2^e, N_g < 2^bits  =>  |sum of q| < 2^62
+    // Fixed-point scale of the sums, from max |x| of the search (fixed_shift rounds
+    // the exponent up to a multiple of 4).  The vector-ALU path reads all rows for
+    // it.  The matrix-core path estimates it from the first rows, since its first
+    // step reads, scores and sums the rows in a single pass; that pass also finds
+    // the true maximum, and in the rare case that the estimate's exponent class
+    // was too small the sums are rebuilt with the right scale.
     float am = 0.f;
-    const bf16x8* sp = nullptr;
+    double tsq = 0.0;           // sum of x^2 over the search (exact products, fp64 sums), for the objective
+    bf16x8* spw = nullptr;
     if constexpr (MT > 0) {
         const int ntiles = (ng + 31) >> 5;
         const int64_t tb = a.tile_off[g];
         if (tb < 0 || tb + ntiles > a.max_tiles) return;   // inconsistent offsets: touch nothing
-        bf16x8* spw = a.split + (size_t)tb * (DS * 2 * 64);
-        am = presplit<DS>(a, Xg, n0, ng, D, spw);
-        sp = spw;
+        spw = a.split + (size_t)tb * (DS * 2 * 64);
+        const size_t total = (size_t)(ng < kThreads ? ng : kThreads) * D;
+        for (size_t i = tid; i < total; i += kThreads) am = fmaxf(am, fabsf(Xg[i]));
     } else {
         const size_t total = (size_t)ng * D;
         if ((D & 3) == 0) {
@@ -834,29 +909,40 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
             for (size_t i = tid; i < quads; i += kThreads) {
                 const float4 v = reinterpret_cast<const float4*>(Xg)[i];
                 am = fmaxf(fmaxf(am, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+                tsq = fma((double)v.x, (double)v.x, tsq);
+                tsq = fma((double)v.y, (double)v.y, tsq);
+                tsq = fma((double)v.z, (double)v.z, tsq);
+                tsq = fma((double)v.w, (double)v.w, tsq);
             }
         } else {
-            for (size_t i = tid; i < total; i += kThreads) am = fmaxf(am, fabsf(Xg[i]));
+            for (size_t i = tid; i < total; i += kThreads) {
+                const float v = Xg[i];
+                am = fmaxf(am, fabsf(v));
+                tsq = fma((double)v, (double)v, tsq);
+            }
         }
     }
+    const bf16x8* sp = spw;
     int phase = 0;
     am = block_max_f(am, red, phase);
-    int e = 0;
-    if (am > 0.f) (void)frexpf(am, &e);
-    e = clampi(e, -126, 129);
-    const int sh = 62 - e - (32 - __clz(ng));
-    const double scale = ldexp(1.0, sh);
-    const double inv = ldexp(1.0, -sh);
+    if constexpr (MT == 0) tsq = block_sum_d(tsq, red, phase);
+    int sh = fixed_shift(am, ng);
+    double scale = ldexp(1.0, sh);
+    double inv = ldexp(1.0, -sh);
 
     bool first = true;
+    float drift = 0.f;          // cumulative (largest + second largest) centroid move, rounded up
     for (int it = 0; it < a.iters; ++it) {
-        // The bound pass pays off once few candidates still move; until then every
-        // tile is scored (and gets fresh bounds from the scorer).
-        const int moved_prev = first ? ng : nmoved[(it + 1) & 1];
-        const bool use_b = MT > 0 && a.use_bounds && !first && (long long)moved_prev * 128 <= ng;
-        if (tid == 0) { *nflag = 0; nmoved[it & 1] = 0; }
+        if (tid == 0) *nflag = 0;
         if constexpr (MT > 0) {
-            if (use_b) bounds_pass(a, n0, ng, K, delta, tact);
+            if (a.use_bounds && it > 0) {
+                const int lane = tid & 63;
+                const float dj = lane < K ? delta[lane] : 0.f;     // K <= 64 on this path
+                const float d1 = wave_max_f(dj);
+                const int jm = __ffsll((long long)__ballot(dj == d1)) - 1;
+                const float d2 = wave_max_f(lane == jm ? 0.f : dj);
+                drift = (drift + (d1 + d2) * 1.0000005f) * 1.0000005f;
+            }
         }
         // dr: rows whose centroid was renewed by the previous step (all rows in the
         // first); dw: rows touched in this step, for the renewal at its end
@@ -888,8 +974,36 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
 
         int st;
         if constexpr (MT > 0) {
-            st = score_mfma<DS, MT>(a, Xg, sp, n0, ng, K, D, DP, SP, cent, cn, cm, first, scale, sums, cnt,
-                                    nflag, flist, aop, dw, tact, use_b, nmoved + (it & 1));
+            if (first) {
+                float am_seen;
+                st = score_first<DS, MT>(a, Xg, spw, n0, ng, K, D, SP, cn, cm, scale, sums, cnt, nflag,
+                                         flist, aop, dw, thr, am_seen, tsq);
+                am_seen = block_max_f(am_seen, red, phase);
+                tsq = block_sum_d(tsq, red, phase);
+                const int sh_true = fixed_shift(am_seen, ng);
+                if (sh_true != sh) {
+                    // the rows beyond the estimate's sample were larger: rebuild the
+                    // sums of the candidates placed so far with the right scale
+                    sh = sh_true;
+                    scale = ldexp(1.0, sh);
+                    inv = ldexp(1.0, -sh);
+                    for (int idx = tid; idx < K * SP; idx += kThreads) sums[idx] = 0;
+                    for (int j = tid; j < K; j += kThreads) cnt[j] = 0;
+                    __syncthreads();
+                    const int lane = tid & 63;
+                    for (int p = tid >> 6; p < ng; p += kWaves) {
+                        int v = a.a_new[(size_t)n0 + p];      // uniform over the wave
+                        if (v < 0) continue;                    // waits for the exact pass
+                        v = v < K ? v : 0;
+                        for (int d = lane; d < D; d += kWave)
+                            lds_add(&sums[(size_t)v * SP + d], to_fixed(Xg[(size_t)p * D + d], scale));
+                        if (lane == 0) atomicAdd(&cnt[v], 1);
+                    }
+                    __syncthreads();
+                }
+            } else
+            st = score_mfma<DS, MT>(a, Xg, sp, n0, ng, K, D, DP, SP, cent, cn, cm, scale, sums, cnt,
+                                    nflag, flist, aop, dw, thr, drift);
         } else {
             score_valu<4 * DS>(a, Xg, n0, ng, K, D, DP, cent, cn, cm);
             st = 2;
@@ -900,9 +1014,12 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
             const int nf = MT > 0 ? *nflag : kFlagCap + 1;
             if (nf <= kFlagCap) {
                 moved = refine_listed(a, Xg, n0, nf, flist, K, D, DP, SP, cent, scale, sums, cnt, dw,
-                                      nmoved + (it & 1));
+                                      thr, drift);
             } else {
-                // the list overflowed (or the vector-ALU scorer ran): scan every candidate
+                // the list overflowed (or the vector-ALU scorer ran): scan every candidate;
+                // no slack is known for the refined ones, so every tile is scored next time
+                if (MT > 0 && a.use_bounds)
+                    for (int t = tid; t < ((ng + 31) >> 5); t += kThreads) thr[t] = 0.f;
                 refine(a, Xg, n0, ng, K, D, DP, cent);
                 __syncthreads();
                 // after the matrix-core scorer only refined candidates are left to move,
@@ -916,9 +1033,30 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
 
         const bool last = (it == a.iters - 1) || (a.early_exit && !changed);
         if (last) {
-            // objective relative to the centroids that entered this step: 16 lanes
-            // per candidate (4 features each), per-lane fp64 partial sums in a fixed
-            // candidate order, then a fixed-order reduction
+            // Objective relative to the centroids c_j that entered this step.  With
+            // S_j the (exact, fixed-point) sum and n_j the size of cluster j,
+            //   sum_k |x_k - c_a(k)|^2 = sum_k |x_k|^2 - sum_j c_j . (2 S_j - n_j c_j),
+            // everything in fp64.  The subtraction cancels; when less than 1e-7 of the
+            // first term is left the members are summed one by one instead.
+            double part = 0.0;
+            for (int j0 = 0; j0 < K; j0 += kThreads / 16) {
+                const int j = j0 + (tid >> 4), l16 = tid & 15;
+                if (j < K) {
+                    const double nj = (double)cnt[j];
+                    for (int d = l16; d < D; d += 16) {
+                        const double cj = (double)cent[(size_t)j * DP + d];
+                        const double Sj = (double)sums[(size_t)j * SP + d] * inv;
+                        part += cj * (2.0 * Sj - nj * cj);
+                    }
+                }
+            }
+            part = block_sum_d(part, red, phase);
+            const double Jfast = tsq - part;
+            if (Jfast >= 1.0e-7 * tsq) {
+                if (tid == 0) a.objective[g] = (float)Jfast;
+            } else {
+            // 16 lanes per candidate (4 features each), per-lane fp64 partial sums in a
+            // fixed candidate order, then a fixed-order reduction
             double acc = 0.0;
             {
                 const int sub = tid >> 4, l16 = tid & 15;
@@ -965,6 +1103,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
             }
             acc = block_sum_d(acc, red, phase);
             if (tid == 0) a.objective[g] = (float)acc;
+            }
         }
         for (int j0 = 0; j0 < K; j0 += kThreads / 16) {
             const int j = j0 + (tid >> 4), l16 = tid & 15;
@@ -1019,7 +1158,7 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     a.counts = c.counts; a.objective = c.objective; a.a_new = c.a_new; a.order = c.order;
     a.tile_off = c.tile_off; a.xn = c.xn; a.split = reinterpret_cast<bf16x8*>(c.split);
     a.max_tiles = c.max_tiles;
-    a.bnd = reinterpret_cast<float2*>(c.bnd); a.use_bounds = g_scorer != 2;
+    a.use_bounds = g_scorer != 2;
 
     const int ds = (b.D + 15) / 16;   // 1..4 K-steps of 16 features
     a.Nmax = b.Nmax;

@@ -268,15 +268,17 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
             bh[s] = tp[(2 * s) * 64];
             bm[s] = tp[(2 * s + 1) * 64];
         }
+        // no branch around these loads: their number in flight is then known at
+        // compile time and waiting for one tile does not wait for the next one too
         const int p = tile * 32 + m;
-        xnv = p < ng ? a.xn[(size_t)n0 + p] : 0.f;
+        xnv = a.xn[(size_t)n0 + (p < ng ? p : ng - 1)];
         oldv = -1;
     };
 
     bf16x8 Bh[DS], Bm[DS];
     float xn = 0.f;
     int old = -1;
-    if (t0 + wid < t1) load_tile(t0 + wid, Bh, Bm, xn, old);
+    load_tile(t0 + wid < t1 ? t0 + wid : t1 - 1, Bh, Bm, xn, old);
     for (int tile = t0 + wid; tile < t1; tile += kWaves) {
         const int p = tile * 32 + m;
         const bool valid = p < ng;
@@ -284,7 +286,7 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
         float xn2 = 0.f;
         int old2 = -1;
         const bool more = tile + kWaves < t1;
-        if (more) load_tile(tile + kWaves, Bh2, Bm2, xn2, old2);
+        load_tile(more ? tile + kWaves : tile, Bh2, Bm2, xn2, old2);
         // running (best, second, row) over the centroid tiles, two tiles at a time
         float best = kBig * 4.f, second = kBig * 4.f;
         int bi = 0;
@@ -378,12 +380,10 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
             a.next[(size_t)n0 + p] = bi;
             if (!certain) lflag[atomicAdd(&lcount[0], 1)] = n0 + p;   // at most one entry per candidate of the chunk
         }
-        if (more) {
 #pragma unroll
-            for (int s = 0; s < DS; ++s) { Bh[s] = Bh2[s]; Bm[s] = Bm2[s]; }
-            xn = xn2;
-            old = old2;
-        }
+        for (int s = 0; s < DS; ++s) { Bh[s] = Bh2[s]; Bm[s] = Bm2[s]; }
+        xn = xn2;
+        old = old2;
     }
     __syncthreads();
     const int nl = lcount[0];

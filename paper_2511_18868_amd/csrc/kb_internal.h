@@ -28,7 +28,6 @@ struct WsLayout {
     size_t misc;    // int32 [128]   histogram / cursors of the ordering kernel
     size_t tile_off;// int32 [G+1]   prefix sum of ceil(N_g / 32): first 32-candidate tile of each search
     size_t xn;      // float [N]     |x_k|^2 of every candidate
-    size_t bnd;     // float2 [N]    distance bounds of every candidate (upper to own, lower to others)
     size_t split;   // bf16          feature rows split into bf16 (hi, mid) pieces, in matrix-core
                     //               operand order: [tile][16-feature step][hi|mid][lane][8]
     size_t max_tiles;   // capacity of `split` in tiles (not an offset)
@@ -63,7 +62,6 @@ struct ClusterCall {
     float* xn;
     void* split;
     int64_t max_tiles;
-    void* bnd;
 };
 hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t st);
 hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const BigWs& w, char* ws,

@@ -26,6 +26,17 @@ def _sync():
     torch.cuda.synchronize()
 
 
+def _late_outliers():
+    """Searches whose largest feature values sit in late rows, far above anything in
+    the first few hundred rows: the fixed-point scale estimated from the leading
+    rows is too small and the kernel has to rebuild its sums."""
+    b = synth.config5(G=6, nmin=400, nmax=900, seed=123)
+    for g in range(b.G):
+        b.X[b.seg_off[g + 1] - 3] *= 300.0
+        b.X[b.seg_off[g] + 300] *= 40.0
+    return b
+
+
 SMALL = {
     "cfg1": lambda: synth.config1(),
     "cfg2": lambda: synth.config2(),
@@ -33,6 +44,7 @@ SMALL = {
     "cfg5s": lambda: synth.config5(G=96),
     "paper": lambda: synth.paper_shape(),
     "ragged": lambda: synth.config5(G=17, nmin=64, nmax=700, D=20, S=6, seed=99),
+    "lateoutliers": _late_outliers,
     # shapes that take the multi-workgroup clustering path (more than 64 clusters,
     # or a search of more than 65536 candidates)
     "cfg4s": lambda: synth.config4(N=8192, K=256, ncentres=256),
