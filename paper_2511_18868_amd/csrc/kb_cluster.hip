@@ -234,17 +234,30 @@ __device__ __forceinline__ void build_operands(const float* cent, int K, int DP,
 // at every step.  A tile whose number still exceeds the drift is not scored, and
 // not even fetched.  No per-candidate bound is stored anywhere.
 __device__ __forceinline__ float slack_of(float best, float second, float xn, float E) {
-    // d_best^2 <= best + |x|^2 + E and d_other^2 >= second + |x|^2 - E, with room
-    // for the rounding of |x|^2, of the square roots and of the difference
+    // A >= d_best^2 and B <= d_other^2 (room for the rounding of |x|^2 included), and
+    // sqrt(B) - sqrt(A) = (B - A) / (sqrt(B) + sqrt(A)) >= (B - A) / (2 sqrt(B)):
+    // one reciprocal square root (good to an ulp), the result rounded down
     const float Eb = E + 4.0e-6f * xn;
-    const float ub = sqrtf(fmaxf(best + xn + Eb, 0.f)) * 1.0000005f;
-    const float lb = sqrtf(fmaxf(second + xn - Eb, 0.f)) * 0.9999995f;
-    return fmaxf((lb - ub) * 0.9999995f, 0.f);
+    const float A = fmaxf(best + xn + Eb, 0.f);
+    const float B = second + xn - Eb;
+    const float sl = (B - A) * 0.5f * __builtin_amdgcn_rsqf(B) * 0.999999f;
+    return B > A ? sl : 0.f;
 }
-__device__ __forceinline__ float wave_min_f(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o));
-    return v;
+// minimum over lanes 0..31, delivered to every lane of the wave: four cross-lane
+// steps inside rows of 16 lanes, then the two rows
+template <int CTRL>
+__device__ __forceinline__ float dpp_min(float v) {
+    const int o = __builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, 0xf, 0xf, false);
+    return fminf(v, __int_as_float(o));
+}
+__device__ __forceinline__ float half_wave_min_f(float v) {
+    v = dpp_min<0xB1>(v);    // lanes 1,0,3,2 of every four
+    v = dpp_min<0x4E>(v);    // lanes 2,3,0,1 of every four
+    v = dpp_min<0x141>(v);   // mirror inside every eight
+    v = dpp_min<0x140>(v);   // mirror inside every sixteen
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    return fminf(r0, r1);
 }
 // drift + slack, rounded down (both non-negative)
 __device__ __forceinline__ float tile_limit(float drift, float slack) {
@@ -370,7 +383,7 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
                                           const bf16x8* __restrict__ sp,
                                           int n0, int ng, int K, int D, int DP, int SP,
                                           const float* cent, const float* cn, float cnmax,
-                                          double scale, long long* sums, int* cnt,
+                                          int fsh, long long* sums, int* cnt,
                                           int* nflag, int* flist, const bf16x8* aop, int* dirty,
                                           float* thr, float drift) {
     const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
@@ -475,7 +488,7 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
                         const int nb2 = __shfl(bi, mb[q]);
                         const int ob2 = __shfl(old, mb[q]);
                         if (lane < D) {
-                            const long long qf = to_fixed(xq[q], scale);
+                            const long long qf = to_fixed(xq[q], fsh);
                             lds_add(&sums[(size_t)nb2 * SP + lane], qf);
                             if (ob2 >= 0) lds_add(&sums[(size_t)ob2 * SP + lane], -qf);
                         }
@@ -493,7 +506,8 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
         if (__any(valid && !certain)) any |= 2;
         if (a.use_bounds) {
             // the exact pass lowers the limit for the candidates it decides
-            const float sl = wave_min_f((valid && certain) ? slack_of(best, second, xn, E) : INFINITY);
+            // both half-waves hold the same 32 candidates
+            const float sl = half_wave_min_f((valid && certain) ? slack_of(best, second, xn, E) : INFINITY);
             if (lane == 0) thr[tile] = tile_limit(drift, sl);
         }
 #pragma unroll
@@ -516,7 +530,7 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
 template <int DS, int MT>
 __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __restrict__ Xg,
                                            bf16x8* __restrict__ spw, int n0, int ng, int K, int D,
-                                           int SP, const float* cn, float cnmax, double scale,
+                                           int SP, const float* cn, float cnmax, int fsh,
                                            long long* sums, int* cnt, int* nflag, int* flist,
                                            const bf16x8* aop, int* dirty, float* thr,
                                            float& am_out, double& sq_out) {
@@ -600,7 +614,7 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
                         const int d = 16 * s + 8 * h + i;
-                        if (d < D) lds_add(&sums[(size_t)bi * SP + d], to_fixed(xv[s][i], scale));
+                        if (d < D) lds_add(&sums[(size_t)bi * SP + d], to_fixed(xv[s][i], fsh));
                     }
                 }
                 if (h == 0) {
@@ -621,7 +635,7 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
         }
         if (__any(valid && !certain)) any |= 2;
         if (a.use_bounds) {
-            const float sl = wave_min_f((valid && certain) ? slack_of(best, second, xn, E) : INFINITY);
+            const float sl = half_wave_min_f((valid && certain) ? slack_of(best, second, xn, E) : INFINITY);
             if (lane == 0) thr[tile] = tile_limit(0.f, sl);
         }
         if (more) {
@@ -688,7 +702,7 @@ __device__ __forceinline__ void refine(const ClusterArgs& a, const float* __rest
 // that differs from the recorded cluster, the move between the running sums.
 __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* __restrict__ Xg,
                                              int n0, int n, const int* flist, int K, int D, int DP,
-                                             int SP, const float* cent, double scale,
+                                             int SP, const float* cent, int fsh,
                                              long long* sums, int* cnt, int* dirty, float* thr,
                                              float drift) {
     const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
@@ -744,7 +758,7 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
         if (bj != old) {
             any = 1;
             if (lane < D) {
-                const long long q = to_fixed(xv, scale);
+                const long long q = to_fixed(xv, fsh);
                 lds_add(&sums[(size_t)bj * SP + lane], q);
                 if (old >= 0) lds_add(&sums[(size_t)old * SP + lane], -q);
             }
@@ -765,7 +779,7 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
 // instruction hit consecutive LDS addresses.  Returns whether this thread's
 // wave saw any change.
 __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restrict__ Xg, int n0,
-                                      int ng, int K, int D, int SP, bool first, double scale,
+                                      int ng, int K, int D, int SP, bool first, int fsh,
                                       long long* sums, int* cnt, int* dirty) {
     const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
     int any = 0;
@@ -790,7 +804,7 @@ __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restr
             const int ob = __shfl(oa, b);
             const float* xr = Xg + (size_t)(base + b) * D;
             for (int d = lane; d < D; d += kWave) {
-                const long long q = to_fixed(xr[d], scale);
+                const long long q = to_fixed(xr[d], fsh);
                 lds_add(&sums[(size_t)nb * SP + d], q);
                 if (ob >= 0) lds_add(&sums[(size_t)ob * SP + d], -q);
             }
@@ -927,7 +941,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     am = block_max_f(am, red, phase);
     if constexpr (MT == 0) tsq = block_sum_d(tsq, red, phase);
     int sh = fixed_shift(am, ng);
-    double scale = ldexp(1.0, sh);
+    int fsh = sh - 32;          // what to_fixed takes
     double inv = ldexp(1.0, -sh);
 
     bool first = true;
@@ -976,7 +990,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
         if constexpr (MT > 0) {
             if (first) {
                 float am_seen;
-                st = score_first<DS, MT>(a, Xg, spw, n0, ng, K, D, SP, cn, cm, scale, sums, cnt, nflag,
+                st = score_first<DS, MT>(a, Xg, spw, n0, ng, K, D, SP, cn, cm, fsh, sums, cnt, nflag,
                                          flist, aop, dw, thr, am_seen, tsq);
                 am_seen = block_max_f(am_seen, red, phase);
                 tsq = block_sum_d(tsq, red, phase);
@@ -985,7 +999,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
                     // the rows beyond the estimate's sample were larger: rebuild the
                     // sums of the candidates placed so far with the right scale
                     sh = sh_true;
-                    scale = ldexp(1.0, sh);
+                    fsh = sh - 32;
                     inv = ldexp(1.0, -sh);
                     for (int idx = tid; idx < K * SP; idx += kThreads) sums[idx] = 0;
                     for (int j = tid; j < K; j += kThreads) cnt[j] = 0;
@@ -996,13 +1010,13 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
                         if (v < 0) continue;                    // waits for the exact pass
                         v = v < K ? v : 0;
                         for (int d = lane; d < D; d += kWave)
-                            lds_add(&sums[(size_t)v * SP + d], to_fixed(Xg[(size_t)p * D + d], scale));
+                            lds_add(&sums[(size_t)v * SP + d], to_fixed(Xg[(size_t)p * D + d], fsh));
                         if (lane == 0) atomicAdd(&cnt[v], 1);
                     }
                     __syncthreads();
                 }
             } else
-            st = score_mfma<DS, MT>(a, Xg, sp, n0, ng, K, D, DP, SP, cent, cn, cm, scale, sums, cnt,
+            st = score_mfma<DS, MT>(a, Xg, sp, n0, ng, K, D, DP, SP, cent, cn, cm, fsh, sums, cnt,
                                     nflag, flist, aop, dw, thr, drift);
         } else {
             score_valu<4 * DS>(a, Xg, n0, ng, K, D, DP, cent, cn, cm);
@@ -1013,7 +1027,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
             int moved;
             const int nf = MT > 0 ? *nflag : kFlagCap + 1;
             if (nf <= kFlagCap) {
-                moved = refine_listed(a, Xg, n0, nf, flist, K, D, DP, SP, cent, scale, sums, cnt, dw,
+                moved = refine_listed(a, Xg, n0, nf, flist, K, D, DP, SP, cent, fsh, sums, cnt, dw,
                                       thr, drift);
             } else {
                 // the list overflowed (or the vector-ALU scorer ran): scan every candidate;
@@ -1024,7 +1038,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
                 __syncthreads();
                 // after the matrix-core scorer only refined candidates are left to move,
                 // and it has already recorded an assignment for every other candidate
-                moved = update(a, Xg, n0, ng, K, D, SP, first && MT == 0, scale, sums, cnt, dw);
+                moved = update(a, Xg, n0, ng, K, D, SP, first && MT == 0, fsh, sums, cnt, dw);
             }
             st |= block_or_i(moved, red, phase);
         }

@@ -530,7 +530,7 @@ __global__ void __launch_bounds__(kThreads) big_update(BigArgs a) {
         const int rows = K - jg0 < kRowsPerGroup ? K - jg0 : kRowsPerGroup;
         for (int i = tid; i < rows * D; i += kThreads) lsum[i] = 0;
         if (tid < kRowsPerGroup) { lcnt[tid] = 0; ltouched[tid] = 0; }
-        const double scale = ldexp(1.0, fixed_shift(__uint_as_float(a.amax_bits[g]), ng));
+        const int fsh = fixed_shift(__uint_as_float(a.amax_bits[g]), ng) - 32;
         for (int64_t b0 = q0; b0 < q1; b0 += kUpdateBatch) {
             if (tid == 0) nlist = 0;
             __syncthreads();
@@ -582,7 +582,7 @@ __global__ void __launch_bounds__(kThreads) big_update(BigArgs a) {
                 for (int e = 0; e < E; ++e) {
                     const int d = l16 + 16 * e;
                     if (d < D) {
-                        const long long q = to_fixed(xv[e], scale);
+                        const long long q = to_fixed(xv[e], fsh);
                         if (jn >= 0) atomicAdd(reinterpret_cast<unsigned long long*>(&lsum[jn * D + d]), (unsigned long long)q);
                         if (jo >= 0) atomicAdd(reinterpret_cast<unsigned long long*>(&lsum[jo * D + d]), (unsigned long long)(-q));
                     }

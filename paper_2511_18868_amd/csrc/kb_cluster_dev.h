@@ -10,18 +10,20 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kFlagBit = (int)0x80000000u;
 constexpr float kBig = 1.0e30f;    // score of a centroid row that does not exist
 
-// Fixed-point image of one feature value: floor(x * 2^sh) as a 64-bit integer.
-// x * scale is exact (power-of-two scale); it is cut into a high and a low
-// 32-bit half with exact fp64 operations, so only the final cut below one unit
-// of the fixed-point grid rounds (toward -inf, the same way every time a value
-// is added or taken away).
-__device__ __forceinline__ long long to_fixed(float x, double scale) {
-    const double d = (double)x * scale;
-    const double hi = floor(d * 2.3283064365386963e-10);          // d / 2^32
-    const double lo = fma(hi, -4294967296.0, d);                   // in [0, 2^32)
-    const int ihi = __double2int_rz(hi);
-    const unsigned ilo = __double2uint_rz(lo);
-    return (long long)(((unsigned long long)(unsigned)ihi << 32) | ilo);
+// Fixed-point image of one feature value: x * 2^sh cut to a 64-bit integer
+// (toward zero, so the image of -x is minus the image of x), from fsh = sh - 32.
+// Only exact fp32 steps are used: |x| * 2^fsh (a power-of-two scaling; < 2^31 by
+// the choice of sh) is cut into its integer part, which becomes the high word,
+// and its fraction, whose first 32 bits become the low word.  The same value
+// results every time a feature is added to or taken out of a sum.
+__device__ __forceinline__ long long to_fixed(float x, int fsh) {
+    const float t = ldexpf(fabsf(x), fsh);
+    const float hi = floorf(t);
+    const float lo = ldexpf(t - hi, 32);          // t - hi is exact and in [0, 1)
+    const unsigned ihi = (unsigned)hi;
+    const unsigned ilo = (unsigned)lo;           // truncates
+    const long long mag = (long long)(((unsigned long long)ihi << 32) | ilo);
+    return x < 0.f ? -mag : mag;
 }
 
 // Shift of the fixed-point grid for a search: |x| < 2^e and N_g < 2^bits give

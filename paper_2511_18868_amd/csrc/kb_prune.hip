@@ -102,7 +102,7 @@ order_kernel(int G, int64_t N, int Ksum, const int32_t* __restrict__ seg_off,
              int32_t* __restrict__ tile_off, int32_t* __restrict__ chunk_off) {
     __shared__ int hist[64];
     __shared__ int start[64];
-    __shared__ long long part[1024];
+    __shared__ long long part[32];
     const int tid = threadIdx.x;
     // tile_off = exclusive prefix sum of ceil(N_g / 32): each thread owns a
     // contiguous chunk of searches
@@ -119,14 +119,29 @@ order_kernel(int G, int64_t N, int Ksum, const int32_t* __restrict__ seg_off,
             const int tiles = (ng + 31) >> 5;
             local += (long long)tiles + ((long long)((tiles + kTilesPerChunk - 1) / kTilesPerChunk) << 32);
         }
-        part[tid] = local;
+        // exclusive prefix sum over the 1024 threads: shuffles inside each wave, then
+        // the 16 wave totals
+        const int lane = tid & 63, wv = tid >> 6;
+        long long incl = local;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const long long t = __shfl_up(incl, o);
+            if (lane >= o) incl += t;
+        }
+        if (lane == 63) part[wv] = incl;
         __syncthreads();
-        if (tid == 0) {
-            long long acc = 0;
-            for (int i = 0; i < (int)blockDim.x; ++i) { const long long v = part[i]; part[i] = acc; acc += v; }
+        if (wv == 0) {
+            const long long tot = lane < 16 ? part[lane] : 0;
+            long long w = tot;
+#pragma unroll
+            for (int o = 1; o < 16; o <<= 1) {
+                const long long t = __shfl_up(w, o);
+                if (lane >= o) w += t;
+            }
+            if (lane < 16) part[16 + lane] = w - tot;
         }
         __syncthreads();
-        long long acc = part[tid];
+        long long acc = part[16 + wv] + incl - local;
         for (int g = lo; g < hi; ++g) {
             int n0, ng, k0, K;
             search_bounds(seg_off, koff, g, N, Ksum, n0, ng, k0, K);

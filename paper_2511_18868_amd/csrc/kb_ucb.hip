@@ -41,7 +41,6 @@ struct UcbArgs {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
-constexpr double kRewardScale = 1073741824.0;          // 2^30
 constexpr double kRewardInv = 1.0 / 1073741824.0;
 
 // Monotone map from float to uint32 (a < b  <=>  key(a) < key(b)), so an
@@ -49,6 +48,15 @@ constexpr double kRewardInv = 1.0 / 1073741824.0;
 __device__ __forceinline__ unsigned ordered_bits(float f) {
     const unsigned u = __float_as_uint(f);
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Reward sum in 2^-30 fixed point, rounded to nearest (ties to even), with exact
+// fp32 steps only: the integer part of r and its fraction are converted apart.
+// r is non-negative and below 2^31 (a reward sum never exceeds its visit count).
+__device__ __forceinline__ unsigned long long reward_fixed(float r) {
+    const float hi = floorf(r);
+    const float lo = rintf(ldexpf(r - hi, 30));       // r - hi is exact, in [0, 1)
+    return ((unsigned long long)(unsigned)hi << 30) + (unsigned)lo;
 }
 
 // Scatter the visits / reward sums of the alive candidates [q0, q1) of a search
@@ -61,30 +69,59 @@ __device__ __forceinline__ void ucb_accumulate(const UcbArgs& a, int n0, int K, 
     const int ng = q1 - q0;
     const int32_t* vis = a.visits + ((size_t)n0 + q0) * S;
     const float* rs = a.rsum + ((size_t)n0 + q0) * S;
-    if ((S & 3) == 0) {
+    if ((S & 3) == 0 && (kThreads % (S >> 2)) == 0) {
+        // S/4 threads per candidate, each owning one 16-byte piece of its two rows;
+        // the thread-to-piece mapping is fixed, so no index arithmetic per step.  Four
+        // candidates per thread are in flight: mask and cluster first, then the rows
+        // of the alive ones, then the atomics.
         const int S4 = S >> 2;
-        const size_t quads = (size_t)ng * S4;
-        for (size_t q = tid; q < quads; q += kThreads) {
-            const int pl = (int)(q / S4), p = q0 + pl;
-            const int s0 = (int)(q - (size_t)pl * S4) * 4;
-            if (!a.alive[(size_t)n0 + p]) continue;
-            int j = a.assign[(size_t)n0 + p];
-            j = (j >= 0 && j < K) ? j : 0;
-            const int4 v = reinterpret_cast<const int4*>(vis)[q];
-            const float4 r = reinterpret_cast<const float4*>(rs)[q];
-            unsigned* nc = Ncnt + (size_t)j * S + s0;
-            unsigned long long* rr = R + (size_t)j * S + s0;
-            atomicAdd(nc + 0, (unsigned)v.x); atomicAdd(nc + 1, (unsigned)v.y);
-            atomicAdd(nc + 2, (unsigned)v.z); atomicAdd(nc + 3, (unsigned)v.w);
-            atomicAdd(rr + 0, (unsigned long long)__double2ll_rn((double)r.x * kRewardScale));
-            atomicAdd(rr + 1, (unsigned long long)__double2ll_rn((double)r.y * kRewardScale));
-            atomicAdd(rr + 2, (unsigned long long)__double2ll_rn((double)r.z * kRewardScale));
-            atomicAdd(rr + 3, (unsigned long long)__double2ll_rn((double)r.w * kRewardScale));
-            if (s0 == 0) {
-                atomicAdd(&nalive[j], 1u);
-                const unsigned long long key =
-                    ((unsigned long long)ordered_bits(a.bound[(size_t)n0 + p]) << 32) | (unsigned)p;
-                atomicMin(&kmin[j], key);
+        const int rpp = kThreads / S4;            // candidates per pass of the workgroup
+        const int sq = tid % S4, row = tid / S4;
+        const int s0 = sq * 4;
+        constexpr int U = 4;
+        for (int pb = q0 + row; pb < q1; pb += rpp * U) {
+            bool al[U];
+            int jj[U];
+            float bd[U];
+            int4 v[U];
+            float4 r[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int p = pb + u * rpp;
+                const int pc = p < q1 ? p : q1 - 1;
+                al[u] = a.alive[(size_t)n0 + pc] != 0 && p < q1;
+                jj[u] = a.assign[(size_t)n0 + pc];
+                bd[u] = a.bound[(size_t)n0 + pc];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int p = pb + u * rpp;
+                v[u] = make_int4(0, 0, 0, 0);
+                r[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (al[u]) {
+                    v[u] = reinterpret_cast<const int4*>(a.visits)[((size_t)n0 + p) * S4 + sq];
+                    r[u] = reinterpret_cast<const float4*>(a.rsum)[((size_t)n0 + p) * S4 + sq];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (!al[u]) continue;
+                const int p = pb + u * rpp;
+                const int j = (jj[u] >= 0 && jj[u] < K) ? jj[u] : 0;
+                unsigned* nc = Ncnt + (size_t)j * S + s0;
+                unsigned long long* rr = R + (size_t)j * S + s0;
+                atomicAdd(nc + 0, (unsigned)v[u].x); atomicAdd(nc + 1, (unsigned)v[u].y);
+                atomicAdd(nc + 2, (unsigned)v[u].z); atomicAdd(nc + 3, (unsigned)v[u].w);
+                atomicAdd(rr + 0, reward_fixed(r[u].x));
+                atomicAdd(rr + 1, reward_fixed(r[u].y));
+                atomicAdd(rr + 2, reward_fixed(r[u].z));
+                atomicAdd(rr + 3, reward_fixed(r[u].w));
+                if (sq == 0) {
+                    atomicAdd(&nalive[j], 1u);
+                    const unsigned long long key =
+                        ((unsigned long long)ordered_bits(bd[u]) << 32) | (unsigned)p;
+                    atomicMin(&kmin[j], key);
+                }
             }
         }
     } else {
@@ -96,8 +133,7 @@ __device__ __forceinline__ void ucb_accumulate(const UcbArgs& a, int n0, int K, 
             int j = a.assign[(size_t)n0 + p];
             j = (j >= 0 && j < K) ? j : 0;
             atomicAdd(&Ncnt[(size_t)j * S + s], (unsigned)vis[q]);
-            atomicAdd(&R[(size_t)j * S + s],
-                      (unsigned long long)__double2ll_rn((double)rs[q] * kRewardScale));
+            atomicAdd(&R[(size_t)j * S + s], reward_fixed(rs[q]));
             if (s == 0) {
                 atomicAdd(&nalive[j], 1u);
                 const unsigned long long key =
