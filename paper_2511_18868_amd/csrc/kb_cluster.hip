@@ -65,15 +65,60 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kFlagCap = 256;      // LDS list of candidates waiting for the exact pass
 
-__device__ __forceinline__ float wave_max_f(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+// Cross-lane steps inside rows of 16 lanes (data-parallel primitives: no LDS
+// traffic): lanes 1,0,3,2 and 2,3,0,1 of every four, then mirrors inside every
+// eight and every sixteen.  After the four steps every lane of a row holds the
+// row's result; rows are combined through scalar registers.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_d(double v) {
+    const long long b = __double_as_longlong(v);
+    const int lo = (int)(unsigned)b, hi = (int)(b >> 32);
+    const unsigned lo2 = (unsigned)__builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xf, 0xf, false);
+    const unsigned hi2 = (unsigned)__builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xf, 0xf, false);
+    return __longlong_as_double((long long)(((unsigned long long)hi2 << 32) | lo2));
+}
+__device__ __forceinline__ float row_max_f(float v) {
+    v = fmaxf(v, dpp_f<0xB1>(v));
+    v = fmaxf(v, dpp_f<0x4E>(v));
+    v = fmaxf(v, dpp_f<0x141>(v));
+    v = fmaxf(v, dpp_f<0x140>(v));
     return v;
 }
-__device__ __forceinline__ double wave_sum_d(double v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+__device__ __forceinline__ float row_min_f(float v) {
+    v = fminf(v, dpp_f<0xB1>(v));
+    v = fminf(v, dpp_f<0x4E>(v));
+    v = fminf(v, dpp_f<0x141>(v));
+    v = fminf(v, dpp_f<0x140>(v));
     return v;
+}
+// sum over the 16 lanes of a row, in a fixed order, delivered to all 16
+__device__ __forceinline__ double row_sum_d(double v) {
+    v += dpp_d<0xB1>(v);
+    v += dpp_d<0x4E>(v);
+    v += dpp_d<0x141>(v);
+    v += dpp_d<0x140>(v);
+    return v;
+}
+__device__ __forceinline__ float lane_f(float v, int l) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
+}
+__device__ __forceinline__ double lane_d(double v, int l) {
+    const long long b = __double_as_longlong(v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, l);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(b >> 32), l);
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+__device__ __forceinline__ float wave_max_f(float v) {
+    v = row_max_f(v);
+    return fmaxf(fmaxf(lane_f(v, 0), lane_f(v, 16)), fmaxf(lane_f(v, 32), lane_f(v, 48)));
+}
+__device__ __forceinline__ double wave_sum_d(double v) {
+    v = row_sum_d(v);
+    return (lane_d(v, 0) + lane_d(v, 16)) + (lane_d(v, 32) + lane_d(v, 48));
 }
 
 // Block-wide reductions over kThreads threads.  `red` is LDS scratch of
@@ -199,27 +244,87 @@ __device__ __forceinline__ void score_valu(const ClusterArgs& a, const float* __
 // in operand order - [tile][K-step][hi|mid][lane] x 16 bytes - so a step streams
 // them back with fully coalesced 1 KB loads and no conversion work, and the next
 // tile's operands are requested before the current tile is scored.
-// Centroid operands for the matrix cores: -2 c_j split into bf16 (hi, mid),
-// stored in LDS in operand order [tile of 32 rows][K-step][hi|mid][lane] so the
-// scorer reads them with conflict-free 16-byte loads.  Rows >= K are zero.
-template <int DS>
-__device__ __forceinline__ void build_operands(const float* cent, int K, int DP, int mtiles,
-                                               bf16x8* aop, const int* changed, bool all) {
-    const int chunks = mtiles * 32 * DS * 2;      // (row, 8-feature chunk) pairs
-    for (int c = threadIdx.x; c < chunks; c += kThreads) {
-        const int row = c / (DS * 2), ch = c - row * (DS * 2);
-        if (!all && !(row < K && changed[row])) continue;   // rows >= K were zeroed in the first step
-        const int s = ch >> 1, h = ch & 1;
-        float v[8];
-        const float* cr = cent + (size_t)(row < K ? row : 0) * DP + 8 * ch;
+// Everything that follows a change of a centroid, 16 lanes per row (lane l owns
+// features 4l .. 4l+3): the new centroid (fixed-point sum / 2^shift) / count in
+// fp64, rounded once to fp32; how far it moved (rounded up); |c_j|^2 in fp64; and
+// the matrix cores' operands -2 c_j split into bf16 (hi, mid), stored in LDS in
+// operand order [tile of 32 rows][16-feature step][hi|mid][lane] x 16 bytes so the
+// scorer reads them with conflict-free 16-byte loads.  Only rows whose membership
+// changed are touched (`init`: every row, nothing renewed; rows >= K get zero
+// operands).  Returns this thread's view of max_j |c_j|^2.
+template <int DS, bool OPERANDS>
+__device__ __forceinline__ float renew_rows(float* cent, float* cn, bf16x8* aop, const long long* sums,
+                                            const int* cnt, int* dirty, float* delta, int K, int D,
+                                            int SP, double inv, bool init, bool need_scores) {
+    constexpr int DP = 16 * DS + 4;
+    const int tid = threadIdx.x, l16 = tid & 15, d0 = 4 * (tid & 15);
+    const bool infeat = d0 < 16 * DS;                 // this lane's features exist in the padded row
+    const int rows = init && OPERANDS ? ((K + 31) & ~31) : K;
+    float cm = 0.f;
+    for (int j0 = 0; j0 < rows; j0 += kThreads / 16) {
+        const int j = j0 + (tid >> 4);
+        const bool real = j < K;
+        const int c = real ? cnt[j] : 0;
+        const bool renew = !init && real && c > 0 && dirty[j] != 0;
+        const bool fresh = renew || (init && j < rows);
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (real && infeat) v = *reinterpret_cast<const float4*>(cent + (size_t)j * DP + d0);
+        double mv = 0.0;
+        if (renew && infeat) {
+            float* vp = &v.x;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = row < K ? -2.f * cr[i] : 0.f;
-        bf16x8 hi, mid;
-        split8(v, hi, mid);
-        const int mt = row >> 5, lane = (row & 31) + 32 * h;
-        aop[((mt * DS + s) * 2 + 0) * 64 + lane] = hi;
-        aop[((mt * DS + s) * 2 + 1) * 64 + lane] = mid;
+            for (int i = 0; i < 4; ++i) {
+                if (d0 + i < D) {
+                    const float cnew = (float)(((double)sums[(size_t)j * SP + d0 + i] * inv) / (double)c);
+                    const double df = (double)cnew - (double)vp[i];
+                    mv += df * df;
+                    vp[i] = cnew;
+                }
+            }
+            *reinterpret_cast<float4*>(cent + (size_t)j * DP + d0) = v;
+        }
+        // uniform over the 16 lanes of a row from here on
+        if (!init) {
+            mv = row_sum_d(mv);
+            if (real && l16 == 0) {
+                delta[j] = renew ? (float)sqrt(mv) * 1.0000005f : 0.f;
+                dirty[j] = 0;
+            }
+        }
+        float f = 0.f;
+        if (need_scores) {
+            if (fresh) {
+                double sq = (double)v.x * (double)v.x + (double)v.y * (double)v.y +
+                            (double)v.z * (double)v.z + (double)v.w * (double)v.w;
+                sq = row_sum_d(sq);
+                f = (float)sq;
+                if (real && l16 == 0) cn[j] = f;
+                if constexpr (OPERANDS) {
+                    if (infeat) {
+                        // features d0 .. d0+3 are half of the 8-feature piece d0 / 8
+                        typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+                        const float w[4] = {-2.f * v.x, -2.f * v.y, -2.f * v.z, -2.f * v.w};
+                        bf16x4 hi, mid;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const __bf16 hb = (__bf16)w[i];
+                            hi[i] = hb;
+                            mid[i] = (__bf16)(w[i] - (float)hb);
+                        }
+                        const int piece = l16 >> 1, st = piece >> 1, hh = piece & 1;
+                        const int mt = j >> 5, ln = (j & 31) + 32 * hh;
+                        bf16x4* e = reinterpret_cast<bf16x4*>(aop + ((mt * DS + st) * 2 + 0) * 64 + ln) + (l16 & 1);
+                        e[0] = hi;
+                        e[64 * 2] = mid;            // the mid block follows 64 entries of 16 bytes later
+                    }
+                }
+            } else if (real) {
+                f = cn[j];
+            }
+            if (real) cm = fmaxf(cm, f);
+        }
     }
+    return cm;
 }
 
 // Distance bounds.  When a candidate is scored, ub >= distance to its nearest
@@ -243,21 +348,10 @@ __device__ __forceinline__ float slack_of(float best, float second, float xn, fl
     const float sl = (B - A) * 0.5f * __builtin_amdgcn_rsqf(B) * 0.999999f;
     return B > A ? sl : 0.f;
 }
-// minimum over lanes 0..31, delivered to every lane of the wave: four cross-lane
-// steps inside rows of 16 lanes, then the two rows
-template <int CTRL>
-__device__ __forceinline__ float dpp_min(float v) {
-    const int o = __builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, 0xf, 0xf, false);
-    return fminf(v, __int_as_float(o));
-}
+// minimum over lanes 0..31, delivered to every lane of the wave
 __device__ __forceinline__ float half_wave_min_f(float v) {
-    v = dpp_min<0xB1>(v);    // lanes 1,0,3,2 of every four
-    v = dpp_min<0x4E>(v);    // lanes 2,3,0,1 of every four
-    v = dpp_min<0x141>(v);   // mirror inside every eight
-    v = dpp_min<0x140>(v);   // mirror inside every sixteen
-    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
-    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
-    return fminf(r0, r1);
+    v = row_min_f(v);
+    return fminf(lane_f(v, 0), lane_f(v, 16));
 }
 // drift + slack, rounded down (both non-negative)
 __device__ __forceinline__ float tile_limit(float drift, float slack) {
@@ -831,7 +925,7 @@ __host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP, int Nmax) {
     l.cent = off; off += (size_t)Kmax * DP * 4;
     l.cn = off;   off += (size_t)((Kmax + 31) & ~31) * 4;   // padded to whole centroid tiles
     l.cnt = off;  off += (size_t)Kmax * 4;
-    l.dirty = off; off += (size_t)Kmax * 4 * 2;     // two generations of "row changed" flags
+    l.dirty = off; off += (size_t)Kmax * 4;         // "membership changed" flags
     l.delta = off; off += (size_t)Kmax * 4;         // how far each centroid moved in the last renewal
     l.flist = off; off += (size_t)kFlagCap * 4;
     off = (off + 15) & ~(size_t)15;
@@ -871,7 +965,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     float* cn = reinterpret_cast<float*>(smem + L.cn);               // [Kmax]
     int* cnt = reinterpret_cast<int*>(smem + L.cnt);                 // [Kmax]
     int* flist = reinterpret_cast<int*>(smem + L.flist);             // [kFlagCap]
-    int* dirty = reinterpret_cast<int*>(smem + L.dirty);             // [2][Kmax]
+    int* dirty = reinterpret_cast<int*>(smem + L.dirty);             // [Kmax]
     float* delta = reinterpret_cast<float*>(smem + L.delta);         // [Kmax]
     float* thr = reinterpret_cast<float*>(smem + L.thr);             // [tiles]
     int* nflag = reinterpret_cast<int*>(smem + 64);                  // behind the two reduction slots
@@ -888,7 +982,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
         cent[idx] = v;
     }
     for (int idx = tid; idx < K * SP; idx += kThreads) sums[idx] = 0;
-    for (int j = tid; j < K; j += kThreads) cnt[j] = 0;
+    for (int j = tid; j < K; j += kThreads) { cnt[j] = 0; dirty[j] = 0; delta[j] = 0.f; }
     for (int j = K + tid; j < ((a.Kmax + 31) & ~31); j += kThreads) cn[j] = kBig;
     __syncthreads();
 
@@ -944,6 +1038,10 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     int fsh = sh - 32;          // what to_fixed takes
     double inv = ldexp(1.0, -sh);
 
+    // |c_j|^2, their maximum and the matrix-core operands of the initial centroids
+    float cm = renew_rows<DS, (MT > 0)>(cent, cn, aop, sums, cnt, dirty, delta, K, D, SP, inv, true, true);
+    cm = block_max_f(cm, red, phase);
+
     bool first = true;
     float drift = 0.f;          // cumulative (largest + second largest) centroid move, rounded up
     for (int it = 0; it < a.iters; ++it) {
@@ -958,33 +1056,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
                 drift = (drift + (d1 + d2) * 1.0000005f) * 1.0000005f;
             }
         }
-        // dr: rows whose centroid was renewed by the previous step (all rows in the
-        // first); dw: rows touched in this step, for the renewal at its end
-        const int* dr = dirty + ((it + 1) & 1) * a.Kmax;
-        int* dw = dirty + (it & 1) * a.Kmax;
-        for (int j = tid; j < K; j += kThreads) dw[j] = 0;
-        if constexpr (MT > 0) build_operands<DS>(cent, K, DP, (K + 31) >> 5, aop, dr, it == 0);
-        // |c_j|^2 in fp64, four lanes per centroid, combined in a fixed order
-        float cm = 0.f;
-        for (int j0 = 0; j0 < K; j0 += kThreads / 4) {
-            const int j = j0 + (tid >> 2), q = tid & 3;
-            const bool renew = j < K && (it == 0 || dr[j]);
-            double s = 0.0;
-            if (renew)
-                for (int d = q; d < D; d += 4) {
-                    const double c = (double)cent[(size_t)j * DP + d];
-                    s += c * c;
-                }
-            s += __shfl_xor(s, 1);
-            s += __shfl_xor(s, 2);
-            if (j < K) {
-                float f;
-                if (renew) { f = (float)s; if (q == 0) cn[j] = f; }
-                else f = cn[j];
-                cm = fmaxf(cm, f);
-            }
-        }
-        cm = block_max_f(cm, red, phase);
+        int* dw = dirty;        // rows touched in this step, for the renewal at its end
 
         int st;
         if constexpr (MT > 0) {
@@ -1119,27 +1191,9 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
             if (tid == 0) a.objective[g] = (float)acc;
             }
         }
-        for (int j0 = 0; j0 < K; j0 += kThreads / 16) {
-            const int j = j0 + (tid >> 4), l16 = tid & 15;
-            const int c = j < K ? cnt[j] : 0;
-            const bool renew = c > 0 && dw[j];
-            double mv = 0.0;
-            if (renew)
-                for (int d = l16; d < D; d += 16) {
-                    const float cold = cent[(size_t)j * DP + d];
-                    const float cnew = (float)(((double)sums[(size_t)j * SP + d] * inv) / (double)c);
-                    cent[(size_t)j * DP + d] = cnew;
-                    const double df = (double)cnew - (double)cold;
-                    mv += df * df;
-                }
-            // Euclidean length of the move (0 for an unchanged centroid), rounded up
-            mv += __shfl_xor(mv, 8);
-            mv += __shfl_xor(mv, 4);
-            mv += __shfl_xor(mv, 2);
-            mv += __shfl_xor(mv, 1);
-            if (j < K && l16 == 0) delta[j] = renew ? (float)sqrt(mv) * 1.0000005f : 0.f;
-        }
-        __syncthreads();
+        // new centroids, and what the next step needs from them
+        cm = renew_rows<DS, (MT > 0)>(cent, cn, aop, sums, cnt, dirty, delta, K, D, SP, inv, false, !last);
+        cm = block_max_f(cm, red, phase);
         if (last) break;
     }
 
