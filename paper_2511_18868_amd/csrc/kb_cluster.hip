@@ -116,6 +116,10 @@ __device__ __forceinline__ float wave_max_f(float v) {
     v = row_max_f(v);
     return fmaxf(fmaxf(lane_f(v, 0), lane_f(v, 16)), fmaxf(lane_f(v, 32), lane_f(v, 48)));
 }
+__device__ __forceinline__ float wave_min_f(float v) {
+    v = row_min_f(v);
+    return fminf(fminf(lane_f(v, 0), lane_f(v, 16)), fminf(lane_f(v, 32), lane_f(v, 48)));
+}
 __device__ __forceinline__ double wave_sum_d(double v) {
     v = row_sum_d(v);
     return (lane_d(v, 0) + lane_d(v, 16)) + (lane_d(v, 32) + lane_d(v, 48));
@@ -792,59 +796,111 @@ __device__ __forceinline__ void refine(const ClusterArgs& a, const float* __rest
 }
 
 // ---- phases R + B over the list of marked candidates ----------------------------
-// One wave per listed candidate: exact nearest centroid as in refine(), then, if
-// that differs from the recorded cluster, the move between the running sums.
+// One wave per listed candidate, lanes over centroids; the next candidate's row
+// is requested before the current one is worked on.  First every squared
+// distance in fp32, direct differences: a sum of non-negative terms, so its
+// relative error is at most (D + 2) 2^-24.  If the two smallest are further apart
+// than twice that bound allows, the smallest is the unique nearest centroid.
+// Otherwise the distances are formed exactly as the plain definition does - fp64,
+// summed over the features in index order with separate multiply and add - and the
+// lowest index attaining the minimum wins.  Then, if the nearest centroid differs
+// from the recorded cluster, the row moves between the running sums.
 __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* __restrict__ Xg,
                                              int n0, int n, const int* flist, int K, int D, int DP,
                                              int SP, const float* cent, int fsh,
                                              long long* sums, int* cnt, int* dirty, float* thr,
                                              float drift) {
     const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    const int lc = lane < D ? lane : 0;
+    const float eps = 2.f * (float)(D + 2) * 5.9604644775390625e-08f;
     int any = 0;
+    if (wid >= n) return 0;
+    int p_n = flist[wid];
+    float xv_n = Xg[(size_t)p_n * D + lc];
+    int old_n = a.assign[(size_t)n0 + p_n];
     for (int i = wid; i < n; i += kWaves) {
-        const int p = flist[i];
-        const float* xr = Xg + (size_t)p * D;
-        const float xv = lane < D ? xr[lane] : 0.f;
-        int old = a.assign[(size_t)n0 + p];
-        double bd = INFINITY, sd = INFINITY;      // smallest and second smallest distance
-        int bj = 0x7fffffff;
+        const int p = p_n;
+        const float xv = lane < D ? xv_n : 0.f;
+        int old = old_n;
+        {
+            // no branch around the loads (the last candidate requests its own row again)
+            const int i2 = i + kWaves < n ? i + kWaves : i;
+            p_n = flist[i2];
+            xv_n = Xg[(size_t)p_n * D + lc];
+            old_n = a.assign[(size_t)n0 + p_n];
+        }
+        // rows are zero-padded to a multiple of 4 features (and xv is 0 beyond D), so
+        // whole float4 chunks can be summed: the extra terms are +0.0
+        float lb = INFINITY, ls = INFINITY;       // this lane's smallest and second smallest
+        int lj = 0x7fffffff;
         for (int j0 = 0; j0 < K; j0 += kWave) {
             const int j = j0 + lane;
             const float* cr = cent + (size_t)(j < K ? j : 0) * DP;
-            // rows are zero-padded to a multiple of 4 features (and xv is 0 beyond
-            // D), so whole float4 chunks can be summed: the extra terms are +0.0
-            double acc = 0.0;
+            float acc0 = 0.f, acc1 = 0.f;
             for (int d = 0; d < D; d += 4) {
                 const float4 cv = *reinterpret_cast<const float4*>(cr + d);
-                double diff = __dsub_rn((double)__shfl(xv, d), (double)cv.x);
-                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
-                diff = __dsub_rn((double)__shfl(xv, d + 1), (double)cv.y);
-                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
-                diff = __dsub_rn((double)__shfl(xv, d + 2), (double)cv.z);
-                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
-                diff = __dsub_rn((double)__shfl(xv, d + 3), (double)cv.w);
-                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                const float e0 = __shfl(xv, d) - cv.x, e1 = __shfl(xv, d + 1) - cv.y;
+                const float e2 = __shfl(xv, d + 2) - cv.z, e3 = __shfl(xv, d + 3) - cv.w;
+                acc0 = fmaf(e0, e0, acc0);
+                acc1 = fmaf(e1, e1, acc1);
+                acc0 = fmaf(e2, e2, acc0);
+                acc1 = fmaf(e3, e3, acc1);
             }
+            const float acc = acc0 + acc1;
             if (j < K) {
-                if (acc < bd) { sd = bd; bd = acc; bj = j; }
-                else if (acc < sd) sd = acc;
+                if (acc < lb) { ls = lb; lb = acc; lj = j; }
+                else if (acc < ls) ls = acc;
             }
         }
+        const float b32 = wave_min_f(lb);
+        const int fl = __ffsll((long long)__ballot(lb == b32)) - 1;
+        const float s32 = wave_min_f(lane == fl ? ls : lb);
+        int bj = __shfl(lj, fl);
+        float ub, lbd;      // upper bound on the nearest distance, lower bound on all others
+        if (s32 * (1.f - eps) > b32 * (1.f + eps) + 1.0e-35f) {     // uniform over the wave
+            ub = sqrtf(b32 * (1.f + eps)) * 1.0000005f;
+            lbd = sqrtf(s32 * (1.f - eps)) * 0.9999995f;
+        } else {
+            double bd = INFINITY, sd = INFINITY;
+            bj = 0x7fffffff;
+            for (int j0 = 0; j0 < K; j0 += kWave) {
+                const int j = j0 + lane;
+                const float* cr = cent + (size_t)(j < K ? j : 0) * DP;
+                double acc = 0.0;
+                for (int d = 0; d < D; d += 4) {
+                    const float4 cv = *reinterpret_cast<const float4*>(cr + d);
+                    double diff = __dsub_rn((double)__shfl(xv, d), (double)cv.x);
+                    acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                    diff = __dsub_rn((double)__shfl(xv, d + 1), (double)cv.y);
+                    acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                    diff = __dsub_rn((double)__shfl(xv, d + 2), (double)cv.z);
+                    acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                    diff = __dsub_rn((double)__shfl(xv, d + 3), (double)cv.w);
+                    acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                }
+                if (j < K) {
+                    if (acc < bd) { sd = bd; bd = acc; bj = j; }
+                    else if (acc < sd) sd = acc;
+                }
+            }
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const double od = __shfl_xor(bd, o);
-            const double os = __shfl_xor(sd, o);
-            const int oj = __shfl_xor(bj, o);
-            const bool take = od < bd || (od == bd && oj < bj);
-            const double hi2 = take ? bd : od;        // the larger of the two bests
-            const double sm = os < sd ? os : sd;
-            sd = sm < hi2 ? sm : hi2;
-            if (take) { bd = od; bj = oj; }
+            for (int o = 32; o > 0; o >>= 1) {
+                const double od = __shfl_xor(bd, o);
+                const double os = __shfl_xor(sd, o);
+                const int oj = __shfl_xor(bj, o);
+                const bool take = od < bd || (od == bd && oj < bj);
+                const double hi2 = take ? bd : od;        // the larger of the two bests
+                const double sm = os < sd ? os : sd;
+                sd = sm < hi2 ? sm : hi2;
+                if (take) { bd = od; bj = oj; }
+            }
+            ub = (float)sqrt(bd) * 1.0000005f;
+            lbd = (float)sqrt(sd) * 0.9999995f;
         }
         if (a.use_bounds && lane == 0) {
-            // exact distances: the slack is their difference, rounded down; limits are
+            // the slack is the difference of the bounds, rounded down; limits are
             // non-negative floats, which order like their bit patterns
-            const float sl = fmaxf(((float)sqrt(sd) * 0.9999995f - (float)sqrt(bd) * 1.0000005f) * 0.9999995f, 0.f);
+            const float sl = fmaxf((lbd - ub) * 0.9999995f, 0.f);
             atomicMin(reinterpret_cast<unsigned*>(&thr[p >> 5]), __float_as_uint(tile_limit(drift, sl)));
         }
         bj = bj < K ? bj : 0;
