@@ -1029,6 +1029,24 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
 
     const float* Xg = a.X + (size_t)n0 * D;
 
+    // requested together with the initial centroids so that the latencies overlap:
+    // the search's place in the split workspace, and (matrix-core path) the largest
+    // |x| among the first rows, from which the fixed-point scale is estimated
+    int64_t tb = 0;
+    float am = 0.f;
+    if constexpr (MT > 0) {
+        tb = a.tile_off[g];
+        const int srows = ng < 64 ? ng : 64;
+        if ((D & 3) == 0) {
+            const int quads = srows * (D >> 2);
+            for (int i = tid; i < quads; i += kThreads) {
+                const float4 v = reinterpret_cast<const float4*>(Xg)[i];
+                am = fmaxf(fmaxf(am, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+            }
+        } else {
+            for (int i = tid; i < srows * D; i += kThreads) am = fmaxf(am, fabsf(Xg[i]));
+        }
+    }
     for (int idx = tid; idx < K * DP; idx += kThreads) {
         const int j = idx / DP, d = idx - j * DP;
         float v = 0.f;
@@ -1056,16 +1074,12 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     // step reads, scores and sums the rows in a single pass; that pass also finds
     // the true maximum, and in the rare case that the estimate's exponent class
     // was too small the sums are rebuilt with the right scale.
-    float am = 0.f;
     double tsq = 0.0;           // sum of x^2 over the search (exact products, fp64 sums), for the objective
     bf16x8* spw = nullptr;
     if constexpr (MT > 0) {
         const int ntiles = (ng + 31) >> 5;
-        const int64_t tb = a.tile_off[g];
         if (tb < 0 || tb + ntiles > a.max_tiles) return;   // inconsistent offsets: touch nothing
         spw = a.split + (size_t)tb * (DS * 2 * 64);
-        const size_t total = (size_t)(ng < kThreads ? ng : kThreads) * D;
-        for (size_t i = tid; i < total; i += kThreads) am = fmaxf(am, fabsf(Xg[i]));
     } else {
         const size_t total = (size_t)ng * D;
         if ((D & 3) == 0) {
