@@ -182,6 +182,41 @@ def ucb_select(seg_off, koff, S, assign_, alive, bound, visits, rsum, t, c,
     return SimpleNamespace(Ncs=Ncs, mu=mu, ucb=ucb, sel=sel, near=near)
 
 
+def philox4x32_10(ctr, key):
+    lib = _load()
+    c = (ctypes.c_uint32 * 4)(*[int(v) for v in ctr])
+    k = (ctypes.c_uint32 * 2)(*[int(v) for v in key])
+    out = (ctypes.c_uint32 * 4)()
+    lib.kbo_philox4x32_10(c, k, out)
+    return [int(v) for v in out]
+
+
+def uniform(seed, draw, k):
+    lib = _load()
+    lib.kbo_uniform.restype = ctypes.c_double
+    return float(lib.kbo_uniform(ctypes.c_uint64(seed), ctypes.c_uint64(draw), ctypes.c_int32(k)))
+
+
+def sample(seg_off, assign_, alive, bound, incumbent, sel, seed, draw, tau=1.0):
+    """Draw k_t in the chosen cluster of every search.  Returns a namespace with
+    ksel (global candidate index or -1) and near (near-tie of the two best keys)."""
+    lib = _load()
+    seg_off = _c(seg_off, np.int32)
+    assign_ = _c(assign_, np.int32)
+    if alive is not None:
+        alive = _c(alive, np.uint8)
+    bound = _c(bound, np.float32)
+    incumbent = _c(incumbent, np.float32)
+    sel = _c(sel, np.int32)
+    G = len(seg_off) - 1
+    ksel = np.empty(G, dtype=np.int32)
+    near = np.empty(G, dtype=np.uint8)
+    lib.kbo_sample(ctypes.c_int32(G), _p(seg_off), _p(assign_), _p(alive), _p(bound),
+                   _p(incumbent), _p(sel), ctypes.c_uint64(seed), ctypes.c_uint64(draw),
+                   ctypes.c_double(tau), _p(ksel), _p(near))
+    return SimpleNamespace(ksel=ksel, near=near)
+
+
 def round_(b, iters=None):
     """Full round on a synth.Batch-like object (duck-typed: only attributes are
     read)."""

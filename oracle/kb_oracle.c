@@ -23,6 +23,10 @@
  *                    chosen cluster with the most headroom (Sec. 3.4, zero-
  *                    temperature limit of the softmax over V_hw).
  *   kbo_round        the three in sequence.
+ *   kbo_sample       the draw of k_t inside the chosen cluster with probability
+ *                    proportional to exp(headroom) (Sec. 3.4; Alg. 1 "Sample
+ *                    k_t"), made reproducible by a counter-based generator and
+ *                    the Gumbel-max identity.
  *
  * Arithmetic: fp64 everywhere, straight loops in index order, no blocking, no
  * reordering - except the roofline bound, which is computed in fp32 on purpose:
@@ -312,6 +316,100 @@ void kbo_ucb_select(int32_t G, int32_t S, const int32_t *seg_off,
         }
         free(nalive);
         free(R);
+    }
+}
+
+/* --------------------------------------------------------------- sampling */
+
+/* Philox4x32 with 10 rounds: the counter-based generator of Salmon, Moraes,
+ * Dror and Shaw, "Parallel random numbers: as easy as 1, 2, 3" (SC'11), written
+ * from its published definition: each round multiplies counter words 0 and 2 by
+ * the two round constants, mixes the high halves with the other two words and
+ * the key, and the key is advanced by the Weyl constants between rounds. */
+void kbo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The uniform variate of candidate k (global index) in draw number `draw` under
+ * `seed`: counter = (k, 0, draw low, draw high), key = (seed low, seed high);
+ * the first two output words give 52 random bits m and u = (m + 1/2) 2^-52,
+ * which lies strictly inside (0, 1) and is exact in fp64. */
+double kbo_uniform(uint64_t seed, uint64_t draw, int32_t k)
+{
+    const uint32_t ctr[4] = {(uint32_t)k, 0u, (uint32_t)draw, (uint32_t)(draw >> 32)};
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t out[4];
+    kbo_philox4x32_10(ctr, key, out);
+    const uint64_t m = ((uint64_t)out[0] << 20) | (uint64_t)(out[1] >> 12);
+    return ((double)m + 0.5) * (1.0 / 4503599627370496.0);
+}
+
+/* Sampling of k_t inside the chosen cluster (Sec. 3.4, Alg. 1 "Sample k_t"):
+ * P(k) proportional to exp(V(k)/tau) over the alive members of cluster I_t,
+ * where V is the remaining headroom of candidate k.  With the roofline reading
+ * of the bound the headroom is the fraction of the incumbent's runtime the
+ * candidate could still gain, V(k) = 1 - bound[k]/incumbent[g]  (in (0, 1] for
+ * an alive candidate; incumbent = +inf gives V = 1 for all, a uniform draw).
+ *
+ * The draw is made reproducible by the Gumbel-max identity: with independent
+ * standard Gumbel variates g_k = -ln(-ln u_k), argmax_k (V(k)/tau + g_k) is
+ * distributed exactly as the softmax above.  Lowest index on exact ties.
+ *
+ *   sel[g]  = (I, S*, .) from the selection step; I < 0 gives ksel[g] = -1
+ *   ksel[g] = the sampled candidate, a global index
+ *   near[g] = 1 if the runner-up key is within 1e-6*max(|best|,1e-30) of the
+ *             best (the logarithms differ between libraries in the last bits)
+ * alive may be NULL (every candidate alive). */
+void kbo_sample(int32_t G, const int32_t *seg_off, const int32_t *assign,
+                const uint8_t *alive, const float *bound, const float *incumbent,
+                const int32_t *sel, uint64_t seed, uint64_t draw, double tau,
+                int32_t *ksel, uint8_t *near)
+{
+#pragma omp parallel for schedule(dynamic, 16) if (G > 64)
+    for (int32_t g = 0; g < G; ++g) {
+        const int32_t I = sel[3 * (size_t)g];
+        double best = -INFINITY, runner = -INFINITY;
+        int32_t arg = -1;
+        if (I >= 0) {
+            const double inc = (double)incumbent[g];
+            for (int32_t k = seg_off[g]; k < seg_off[g + 1]; ++k) {
+                if ((alive && !alive[k]) || assign[k] != I) continue;
+                const double V = 1.0 - (double)bound[k] / inc;
+                const double u = kbo_uniform(seed, draw, k);
+                const double gumbel = -log(-log(u));
+                const double key = V / tau + gumbel;
+                if (arg < 0 || key > best) {
+                    runner = best;
+                    best = key;
+                    arg = k;
+                } else if (key > runner) {
+                    runner = key;
+                }
+            }
+        }
+        ksel[g] = arg;
+        if (near) {
+            uint8_t f = 0;
+            if (arg >= 0 && runner > -INFINITY) {
+                double scale = fabs(best) > KBO_TINY ? fabs(best) : KBO_TINY;
+                f = (uint8_t)((best - runner) <= KBO_NEAR_TIE_REL * scale);
+            }
+            near[g] = f;
+        }
     }
 }
 
