@@ -19,6 +19,9 @@
  *                    headroom (Sec. 3.4, zero-temperature limit of the softmax
  *                    over V_hw).
  *   kb_round         the three in sequence on one stream.
+ *   kb_sample        the draw of k_t inside the chosen cluster with probability
+ *                    proportional to exp(headroom) (Sec. 3.4), reproducible from
+ *                    (seed, draw).
  *
  * Data model.  Search g owns the candidates seg_off[g] .. seg_off[g+1]-1 (its
  * frontier P_t) and the clusters koff[g] .. koff[g+1]-1.  N = seg_off[G] is the
@@ -186,6 +189,33 @@ kb_status kb_ucb_select(const kb_batch *batch, const kb_params *params,
 kb_status kb_round(const kb_batch *batch, const kb_params *params,
                    const kb_round_io *io, void *ws, size_t ws_bytes,
                    void *stream);
+
+/* Parameters of the in-cluster draw. */
+typedef struct {
+    uint64_t seed; /* key of the counter-based generator */
+    uint64_t draw; /* number of the draw (e.g. the round t); distinct draws are independent */
+    float tau;     /* softmax temperature, > 0 and finite (the paper's form is tau = 1) */
+} kb_sample_params;
+
+/* Draw of k_t inside the chosen cluster (Sec. 3.4; Alg. 1 "Sample k_t"):
+ *   P(k) proportional to exp(V(k)/tau) over the members k of cluster I = sel[g][0]
+ *   with alive[k] != 0, where V(k) = 1 - bound[k]/incumbent[g] is the fraction of
+ *   the incumbent's runtime candidate k could still gain (its headroom; +inf as
+ *   incumbent makes the draw uniform).
+ * The draw is reproducible: u_k = (m + 1/2) 2^-52 with m the first 52 bits of
+ * Philox4x32-10 (counter (k, 0, draw low, draw high), key (seed low, seed high),
+ * k the global candidate index), and
+ *   ksel[g] = argmax_k ( V(k)/tau - ln(-ln u_k) )       (Gumbel-max identity)
+ * evaluated in fp64, lowest k on exact ties; -1 when I < 0 or the cluster has
+ * no alive member.  tau -> 0 tends to the k* of kb_ucb_select.
+ * sel is the [G,3] output of kb_ucb_select (device); only its first column is
+ * read.  alive may be NULL (every candidate alive).  Keys must be finite:
+ * incumbent > 0, tau a normal positive number. */
+kb_status kb_sample(const kb_batch *batch, const kb_sample_params *sp,
+                    const int32_t *assign, const uint8_t *alive,
+                    const float *bound, const float *incumbent,
+                    const int32_t *sel, int32_t *ksel, void *ws,
+                    size_t ws_bytes, void *stream);
 
 /* Static, never NULL. */
 const char *kb_status_str(kb_status status);

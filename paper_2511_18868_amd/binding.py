@@ -40,6 +40,10 @@ class kb_round_io(ctypes.Structure):
         "assign", "cent", "counts", "objective", "Ncs", "mu", "ucb", "sel")]
 
 
+class kb_sample_params(ctypes.Structure):
+    _fields_ = [("seed", ctypes.c_uint64), ("draw", ctypes.c_uint64), ("tau", ctypes.c_float)]
+
+
 _lib = None
 
 
@@ -66,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.kb_ucb_select.argtypes = [pb, pp] + [vp] * 10 + [vp, sz, vp]
         L.kb_round.restype = ctypes.c_int
         L.kb_round.argtypes = [pb, pp, ctypes.POINTER(kb_round_io), vp, sz, vp]
+        L.kb_sample.restype = ctypes.c_int
+        L.kb_sample.argtypes = [pb, ctypes.POINTER(kb_sample_params)] + [vp] * 6 + [vp, sz, vp]
         L.kb_status_str.restype = ctypes.c_char_p
         L.kb_status_str.argtypes = [ctypes.c_int]
         L.kb_version.restype = ctypes.c_char_p
@@ -149,6 +155,14 @@ def kb_round(batch, params, io: kb_round_io, ws, ws_bytes, stream=None, check=Tr
     return _check(s, "kb_round", check)
 
 
+def kb_sample(batch, sp: kb_sample_params, assign, alive, bound, incumbent, sel, ksel, ws,
+              ws_bytes, stream=None, check=True):
+    s = lib().kb_sample(ctypes.byref(batch), ctypes.byref(sp), _ptr(assign), _ptr(alive),
+                        _ptr(bound), _ptr(incumbent), _ptr(sel), _ptr(ksel), _ptr(ws), ws_bytes,
+                        _stream(stream))
+    return _check(s, "kb_sample", check)
+
+
 def kb_set_scorer(mode: int) -> int:
     return int(lib().kb_set_scorer(int(mode)))
 
@@ -195,6 +209,7 @@ class DeviceBatch:
         self.mu = z((Ksum, S), torch.float32)
         self.ucb = z((Ksum, S), torch.float32)
         self.sel = z((G, 3), torch.int32)
+        self.ksel = z((G,), torch.int32)
         self.batch = make_batch(G, D, S, N, b.Kmax, Ksum, b.Nmax, self.seg_off, self.koff)
         self.params = make_params(b.peak_flops, b.peak_bw, b.c, b.prior_n, b.prior_mu,
                                   b.iters if iters is None else iters)
@@ -223,6 +238,11 @@ class DeviceBatch:
         return kb_ucb_select(self.batch, self.params, self.assign, self.alive, self.bound,
                              self.visits, self.rsum, self.t, self.Ncs, self.mu, self.ucb,
                              self.sel, self.ws, self.ws_bytes, **kw)
+
+    def sample(self, seed, draw, tau=1.0, alive=True, **kw):
+        return kb_sample(self.batch, kb_sample_params(seed, draw, tau), self.assign,
+                         self.alive if alive else None, self.bound, self.incumbent, self.sel,
+                         self.ksel, self.ws, self.ws_bytes, **kw)
 
     def round(self, **kw):
         return kb_round(self.batch, self.params, self.io, self.ws, self.ws_bytes, **kw)

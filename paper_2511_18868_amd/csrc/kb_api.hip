@@ -29,6 +29,11 @@ WsLayout ws_layout(const kb_batch& b) {
         w.ucb_N = off;      off += align256(4 * ks);
         w.ucb_nalive = off; off += align256(4 * k);
     }
+    {
+        const size_t ranges = (size_t)((b.N + kSampleRange - 1) / kSampleRange) + 1;
+        w.samp_key = off; off += align256(8 * 2 * ranges);
+        w.samp_idx = off; off += align256(4 * 2 * ranges);
+    }
     w.total = off;
     return w;
 }
@@ -209,6 +214,25 @@ kb_status kb_ucb_select(const kb_batch* batch, const kb_params* params, const in
     if (s != KB_OK) return s;
     return do_ucb(batch, params, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel, ws,
                   false, (hipStream_t)stream);
+}
+
+kb_status kb_sample(const kb_batch* batch, const kb_sample_params* sp, const int32_t* assign,
+                    const uint8_t* alive, const float* bound, const float* incumbent,
+                    const int32_t* sel, int32_t* ksel, void* ws, size_t ws_bytes, void* stream) {
+    kb_status s = check_batch(batch);
+    if (s != KB_OK) return s;
+    if (!sp || !assign || !bound || !incumbent || !sel || !ksel) return KB_EINVAL;
+    if (!(sp->tau > 0.0f) || !(sp->tau < INFINITY)) return KB_EINVAL;
+    s = check_ws(batch, ws, ws_bytes);
+    if (s != KB_OK) return s;
+    WsLayout w = ws_layout(*batch);
+    char* base = (char*)ws;
+    SampleCall c;
+    c.assign = assign; c.alive = alive; c.bound = bound; c.incumbent = incumbent; c.sel = sel;
+    c.h = nullptr; c.target = nullptr; c.R = 1; c.theta_sat = 0.0f;
+    c.seed = sp->seed; c.draw = sp->draw; c.tau = sp->tau; c.ksel = ksel;
+    c.slot_key = (double*)(base + w.samp_key); c.slot_idx = (int32_t*)(base + w.samp_idx);
+    return dev(launch_sample(*batch, c, (hipStream_t)stream));
 }
 
 kb_status kb_round(const kb_batch* batch, const kb_params* params, const kb_round_io* io,

@@ -8,6 +8,7 @@
 namespace kb {
 
 constexpr int kWave = 64;
+constexpr int kSampleRange = 4096;   // candidates per workgroup of the in-cluster draw
 constexpr int kTilesPerChunk = 32;   // tiles of 32 candidates per workgroup of the multi-workgroup clustering path
 
 // ---- workspace layout (all offsets 256-byte aligned) ------------------------
@@ -35,6 +36,8 @@ struct WsLayout {
     BigWs big;
     bool ucb_chunked;   // searches longer than 16384 candidates: partial tables per candidate range
     size_t ucb_R, ucb_N, ucb_kmin, ucb_nalive;
+    size_t samp_key;   // double [2*ranges]  partial best keys of searches that cross range borders
+    size_t samp_idx;   // int32  [2*ranges]  their candidates
     size_t total;
 };
 WsLayout ws_layout(const kb_batch& b);
@@ -89,6 +92,24 @@ struct UcbCall {
     unsigned long long* gkmin;
 };
 hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st);
+
+struct SampleCall {
+    const int32_t* assign;
+    const uint8_t* alive;      // NULL: every candidate alive
+    const float* bound;
+    const float* incumbent;
+    const int32_t* sel;
+    const float* h;            // non-NULL selects the signature form of the headroom
+    const int32_t* target;
+    int R;
+    float theta_sat;
+    uint64_t seed, draw;
+    float tau;
+    int32_t* ksel;
+    double* slot_key;
+    int32_t* slot_idx;
+};
+hipError_t launch_sample(const kb_batch& b, const SampleCall& c, hipStream_t st);
 
 // ---- device helpers ----------------------------------------------------------
 __device__ __forceinline__ int clampi(int v, int lo, int hi) {

@@ -26,7 +26,7 @@ def test_exports_every_declared_symbol(L):
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(kb_[a-z_]+)\s*\(", hdr))
     assert {"kb_prune", "kb_cluster_step", "kb_cluster", "kb_ucb_select", "kb_round",
-            "kb_workspace_bytes", "kb_status_str", "kb_version", "kb_set_scorer"} <= names
+            "kb_workspace_bytes", "kb_status_str", "kb_version", "kb_set_scorer", "kb_sample"} <= names
     for n in names:
         assert hasattr(L, n), n
 
@@ -124,6 +124,23 @@ def test_ucb_and_round_argument_errors(L):
     io2.sel = None
     assert kb.kb_round(b, p, io2, FAKE, big, stream=0, check=False) == kb.KB_EINVAL
     assert kb.kb_round(b, p, io, FAKE, 16, stream=0, check=False) == kb.KB_EWORKSPACE
+
+
+def test_sample_argument_errors(L):
+    b = _batch()
+    big = 1 << 20
+    ok = kb.kb_sample_params(1, 2, 1.0)
+    args = [FAKE] * 6      # assign, alive, bound, incumbent, sel, ksel
+    for i in (0, 2, 3, 4, 5):
+        bad = list(args)
+        bad[i] = None
+        assert kb.kb_sample(b, ok, *bad, FAKE, big, stream=0, check=False) == kb.KB_EINVAL
+    for tau in (0.0, -1.0, float("inf"), float("nan")):
+        assert kb.kb_sample(b, kb.kb_sample_params(1, 2, tau), *args, FAKE, big, stream=0,
+                            check=False) == kb.KB_EINVAL
+    assert kb.kb_sample(b, ok, *args, FAKE, 16, stream=0, check=False) == kb.KB_EWORKSPACE
+    assert kb.kb_sample(b, ok, *args, None, big, stream=0, check=False) == kb.KB_EWORKSPACE
+    assert ctypes.sizeof(kb.kb_sample_params) == 24
 
 
 def test_scorer_switch(L):
