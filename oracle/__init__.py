@@ -157,13 +157,14 @@ def cluster(seg_off, koff, X, iters, cent_init=None):
 
 
 def ucb_select(seg_off, koff, S, assign_, alive, bound, visits, rsum, t, c,
-               prior_n=0.0, prior_mu=0.5):
+               prior_n=0.0, prior_mu=0.5, M=None):
     lib = _load()
     seg_off = _c(seg_off, np.int32)
     koff = _c(koff, np.int32)
     assign_ = _c(assign_, np.int32)
-    alive = _c(alive, np.uint8)
-    bound = _c(bound, np.float32)
+    alive = None if alive is None else _c(alive, np.uint8)
+    bound = None if bound is None else _c(bound, np.float32)
+    M = None if M is None else _c(M, np.uint8)
     visits = _c(visits, np.int32)
     rsum = _c(rsum, np.float32)
     t = _c(t, np.int64)
@@ -177,7 +178,7 @@ def ucb_select(seg_off, koff, S, assign_, alive, bound, visits, rsum, t, c,
     lib.kbo_ucb_select(ctypes.c_int32(G), ctypes.c_int32(S), _p(seg_off), _p(koff),
                        _p(assign_), _p(alive), _p(bound), _p(visits), _p(rsum),
                        _p(t), ctypes.c_double(c), ctypes.c_double(prior_n),
-                       ctypes.c_double(prior_mu), _p(Ncs), _p(mu), _p(ucb),
+                       ctypes.c_double(prior_mu), _p(M), _p(Ncs), _p(mu), _p(ucb),
                        _p(sel), _p(near))
     return SimpleNamespace(Ncs=Ncs, mu=mu, ucb=ucb, sel=sel, near=near)
 
@@ -215,6 +216,83 @@ def sample(seg_off, assign_, alive, bound, incumbent, sel, seed, draw, tau=1.0):
                    _p(incumbent), _p(sel), ctypes.c_uint64(seed), ctypes.c_uint64(draw),
                    ctypes.c_double(tau), _p(ksel), _p(near))
     return SimpleNamespace(ksel=ksel, near=near)
+
+
+def cluster_geometry(seg_off, koff, X, cent, assign_):
+    """Representative (member nearest the centroid) and radius of every cluster,
+    and the squared distance of every candidate to its centroid."""
+    lib = _load()
+    seg_off = _c(seg_off, np.int32)
+    koff = _c(koff, np.int32)
+    X = _c(X, np.float32)
+    cent = _c(cent, np.float32)
+    assign_ = _c(assign_, np.int32)
+    G = len(seg_off) - 1
+    N, D = X.shape
+    Ksum = int(koff[-1])
+    rep = np.full(Ksum, -1, dtype=np.int32)
+    radius = np.zeros(Ksum, dtype=np.float64)
+    dist2 = np.zeros(N, dtype=np.float64)
+    lib.kbo_cluster_geometry(ctypes.c_int32(G), ctypes.c_int32(D), _p(seg_off), _p(koff),
+                             _p(X), _p(cent), _p(assign_), _p(rep), _p(radius), _p(dist2))
+    return SimpleNamespace(rep=rep, radius=radius, dist2=dist2)
+
+
+def strategy_mask(koff, S, h, target, rep, theta_sat):
+    lib = _load()
+    koff = _c(koff, np.int32)
+    h = _c(h, np.float32)
+    target = _c(target, np.int32)
+    rep = _c(rep, np.int32)
+    G = len(koff) - 1
+    Ksum = int(koff[-1])
+    R = h.shape[1]
+    M = np.zeros((Ksum, S), dtype=np.uint8)
+    nvalid = np.zeros(G, dtype=np.int32)
+    lib.kbo_strategy_mask(ctypes.c_int32(G), ctypes.c_int32(S), ctypes.c_int32(R), _p(koff),
+                          _p(h), _p(target), _p(rep), ctypes.c_float(theta_sat), _p(M),
+                          _p(nvalid))
+    return SimpleNamespace(M=M, nvalid=nvalid)
+
+
+def sample_signature(seg_off, assign_, alive, h, target, theta_sat, sel, seed, draw, tau=1.0):
+    lib = _load()
+    seg_off = _c(seg_off, np.int32)
+    assign_ = _c(assign_, np.int32)
+    if alive is not None:
+        alive = _c(alive, np.uint8)
+    h = _c(h, np.float32)
+    target = _c(target, np.int32)
+    sel = _c(sel, np.int32)
+    G = len(seg_off) - 1
+    ksel = np.empty(G, dtype=np.int32)
+    near = np.empty(G, dtype=np.uint8)
+    lib.kbo_sample_signature(ctypes.c_int32(G), ctypes.c_int32(h.shape[1]), _p(seg_off),
+                             _p(assign_), _p(alive), _p(h), _p(target),
+                             ctypes.c_float(theta_sat), _p(sel), ctypes.c_uint64(seed),
+                             ctypes.c_uint64(draw), ctypes.c_double(tau), _p(ksel), _p(near))
+    return SimpleNamespace(ksel=ksel, near=near)
+
+
+def update_stats(koff, S, sel, ksel, reward, ok, prior_n, visits, rsum, Ncs, mu, t):
+    """Applies the end-of-iteration update; returns updated COPIES of visits,
+    rsum, Ncs (int32), mu (fp32) and t."""
+    lib = _load()
+    koff = _c(koff, np.int32)
+    sel = _c(sel, np.int32)
+    ksel = _c(ksel, np.int32)
+    reward = _c(reward, np.float32)
+    ok = _c(ok, np.uint8)
+    visits = np.array(visits, dtype=np.int32, order="C", copy=True)
+    rsum = np.array(rsum, dtype=np.float32, order="C", copy=True)
+    Ncs = np.array(Ncs, dtype=np.int32, order="C", copy=True)
+    mu = np.array(mu, dtype=np.float32, order="C", copy=True)
+    t = np.array(t, dtype=np.int64, order="C", copy=True)
+    G = len(koff) - 1
+    lib.kbo_update_stats(ctypes.c_int32(G), ctypes.c_int32(S), _p(koff), _p(sel), _p(ksel),
+                         _p(reward), _p(ok), ctypes.c_double(prior_n), _p(visits), _p(rsum),
+                         _p(Ncs), _p(mu), _p(t))
+    return SimpleNamespace(visits=visits, rsum=rsum, Ncs=Ncs, mu=mu, t=t)
 
 
 def round_(b, iters=None):

@@ -23,6 +23,11 @@
  *                    chosen cluster with the most headroom (Sec. 3.4, zero-
  *                    temperature limit of the softmax over V_hw).
  *   kbo_round        the three in sequence.
+ *   kbo_cluster_geometry  the representative (centroid kernel) of each cluster
+ *                    and the cluster radius (Sec. 3.3; Theorem 1's covering term).
+ *   kbo_strategy_mask     the mask of Eq. 5 in the paper's own form, from the
+ *                    hardware signature of the representatives.
+ *   kbo_update_stats the statistics update that ends an iteration of Alg. 1.
  *   kbo_sample       the draw of k_t inside the chosen cluster with probability
  *                    proportional to exp(headroom) (Sec. 3.4; Alg. 1 "Sample
  *                    k_t"), made reproducible by a counter-based generator and
@@ -224,12 +229,15 @@ void kbo_cluster(int32_t G, int32_t D, const int32_t *seg_off,
  *   Ncs[i,s] = sum of visits[k,s] over alive members k of cluster i
  *   R[i,s]   = sum of rsum[k,s] over the same members
  *   Ntilde   = Ncs + prior_n ; Rtilde = R + prior_n*prior_mu ; mu = Rtilde/Ntilde
- *   a cluster is valid iff it has an alive member
+ *   a cluster is valid iff it has an alive member; with a strategy mask M
+ *   ([Ksum,S], may be NULL: the paper's own form of Eq. 5) arm (i,s) is valid
+ *   iff cluster i is and M[i,s] != 0
  *   ucb = mu + c*sqrt(ln t_g / Ntilde)  (valid, Ntilde > 0)
  *       = +inf                          (valid, Ntilde == 0: untried arm first)
  *       = -inf                          (not valid: masked)
  *   (I, S*) = lowest flat index i*S+s attaining the max over valid arms
  *   k*      = alive member of cluster I with the smallest bound, lowest k on ties
+ *             (alive == NULL: every candidate alive; bound == NULL: lowest k)
  *   sel[g]  = (I, S*, k*) with k* a global candidate index, or (-1,-1,-1).
  *
  * near[g] (may be NULL) = 1 if the best score is finite and the largest score
@@ -240,8 +248,8 @@ void kbo_ucb_select(int32_t G, int32_t S, const int32_t *seg_off,
                     const int32_t *koff, const int32_t *assign,
                     const uint8_t *alive, const float *bound,
                     const int32_t *visits, const float *rsum, const int64_t *t,
-                    double c, double prior_n, double prior_mu, int64_t *Ncs,
-                    double *mu, double *ucb, int32_t *sel, uint8_t *near)
+                    double c, double prior_n, double prior_mu, const uint8_t *M,
+                    int64_t *Ncs, double *mu, double *ucb, int32_t *sel, uint8_t *near)
 {
 #pragma omp parallel for schedule(dynamic, 1) if (G > 1)
     for (int32_t g = 0; g < G; ++g) {
@@ -251,7 +259,7 @@ void kbo_ucb_select(int32_t G, int32_t S, const int32_t *seg_off,
         double *R = (double *)calloc((size_t)(K > 0 ? K : 1) * S, sizeof(double));
         for (size_t a = 0; a < (size_t)K * S; ++a) Ncs[base + a] = 0;
         for (int32_t k = seg_off[g]; k < seg_off[g + 1]; ++k) {
-            if (!alive[k]) continue;
+            if (alive && !alive[k]) continue;
             const int32_t i = assign[k];
             nalive[i] += 1;
             for (int32_t s = 0; s < S; ++s) {
@@ -269,12 +277,13 @@ void kbo_ucb_select(int32_t G, int32_t S, const int32_t *seg_off,
                 const double rt = R[a] + prior_n * prior_mu;
                 double m = nt > 0.0 ? rt / nt : NAN;
                 double u;
-                if (nalive[i] == 0) u = -INFINITY;
+                const int valid = nalive[i] > 0 && (!M || M[base + a]);
+                if (!valid) u = -INFINITY;
                 else if (nt > 0.0) u = m + c * sqrt(lnt / nt);
                 else u = INFINITY;
                 mu[base + a] = m;
                 ucb[base + a] = u;
-                if (nalive[i] > 0 && (best_flat < 0 || u > best)) {
+                if (valid && (best_flat < 0 || u > best)) {
                     best = u;
                     best_flat = (int32_t)a;
                 }
@@ -286,9 +295,9 @@ void kbo_ucb_select(int32_t G, int32_t S, const int32_t *seg_off,
             Sstar = best_flat % S;
             float bmin = 0.0f;
             for (int32_t k = seg_off[g]; k < seg_off[g + 1]; ++k) {
-                if (!alive[k] || assign[k] != I) continue;
-                if (kstar < 0 || bound[k] < bmin) {
-                    bmin = bound[k];
+                if ((alive && !alive[k]) || assign[k] != I) continue;
+                if (kstar < 0 || (bound && bound[k] < bmin)) {
+                    bmin = bound ? bound[k] : 0.0f;
                     kstar = k;
                 }
             }
@@ -303,6 +312,7 @@ void kbo_ucb_select(int32_t G, int32_t S, const int32_t *seg_off,
                 for (int32_t i = 0; i < K; ++i) {
                     if (nalive[i] == 0) continue;
                     for (int32_t s = 0; s < S; ++s) {
+                        if (M && !M[base + (size_t)i * S + s]) continue;
                         double u = ucb[base + (size_t)i * S + s];
                         if (u != best && u > runner) runner = u;
                     }
@@ -413,6 +423,163 @@ void kbo_sample(int32_t G, const int32_t *seg_off, const int32_t *assign,
     }
 }
 
+/* ------------------------------------------------- cluster representatives */
+
+/* The centroid kernel k_c^(i) of every cluster - the member whose feature vector
+ * is nearest the centroid (Sec. 3.3 "Representative profiling"; Alg. 1 "Update
+ * centroids k_c") - and the cluster's radius, the largest distance from the
+ * centroid to a member.  The radius is the covering radius epsilon of the
+ * approximation term of Theorem 1 (Appendix "Bounding Approximation Regret"),
+ * and diam(C_i) <= 2 radius_i.
+ *
+ *   rep[j]    = global index of the member of cluster j with the smallest squared
+ *               distance to cent[j] (fp64, direct differences), lowest index on
+ *               ties; -1 for a cluster without members
+ *   radius[j] = sqrt(largest such squared distance); 0 for an empty cluster
+ *   dist2[k]  = squared distance of candidate k to its own centroid (may be NULL)
+ */
+void kbo_cluster_geometry(int32_t G, int32_t D, const int32_t *seg_off,
+                          const int32_t *koff, const float *X, const float *cent,
+                          const int32_t *assign, int32_t *rep, double *radius,
+                          double *dist2)
+{
+#pragma omp parallel for schedule(dynamic, 1) if (G > 1)
+    for (int32_t g = 0; g < G; ++g) {
+        const int32_t K = koff[g + 1] - koff[g];
+        if (K <= 0) continue;
+        double *dmin = (double *)malloc(sizeof(double) * (size_t)K);
+        double *dmax = (double *)malloc(sizeof(double) * (size_t)K);
+        int32_t *r = rep + koff[g];
+        for (int32_t j = 0; j < K; ++j) {
+            r[j] = -1;
+            dmin[j] = 0.0;
+            dmax[j] = 0.0;
+        }
+        for (int32_t k = seg_off[g]; k < seg_off[g + 1]; ++k) {
+            const int32_t j = assign[k];
+            const double d = sqdist(X + (size_t)k * D, cent + ((size_t)koff[g] + j) * D, D);
+            if (dist2) dist2[k] = d;
+            if (r[j] < 0 || d < dmin[j]) {
+                dmin[j] = d;
+                r[j] = k;
+            }
+            if (d > dmax[j]) dmax[j] = d;
+        }
+        for (int32_t j = 0; j < K; ++j) radius[koff[g] + j] = sqrt(dmax[j]);
+        free(dmin);
+        free(dmax);
+    }
+}
+
+/* ------------------------------------------------- paper-form strategy mask */
+
+/* The binary mask of Eq. 5 in the paper's own form: strategy s is valid for
+ * cluster i iff the resource it targets is not saturated on the cluster's
+ * representative,  M[i,s] = [ h(k_c^(i))[Target(s)] < theta_sat ].
+ *
+ *   h[N,R]      hardware signature of every candidate (throughput as a share of
+ *               peak for R resources; the paper uses DRAM, L2 and SM)
+ *   target[S]   the resource each strategy targets, in [0, R)
+ *   rep[Ksum]   representative of each cluster (-1: empty cluster, nothing valid)
+ *   M[Ksum,S]   out, 0/1
+ *   nvalid[G]   out: number of valid cluster arms of the search, K |S_valid| in
+ *               the estimation term of Theorem 1
+ * The comparison is made on the fp32 values as they are (strict '<'). */
+void kbo_strategy_mask(int32_t G, int32_t S, int32_t R, const int32_t *koff,
+                       const float *h, const int32_t *target, const int32_t *rep,
+                       float theta_sat, uint8_t *M, int32_t *nvalid)
+{
+    for (int32_t g = 0; g < G; ++g) {
+        int32_t n = 0;
+        for (int32_t i = koff[g]; i < koff[g + 1]; ++i) {
+            for (int32_t s = 0; s < S; ++s) {
+                uint8_t m = 0;
+                if (rep[i] >= 0) m = (uint8_t)(h[(size_t)rep[i] * R + target[s]] < theta_sat);
+                M[(size_t)i * S + s] = m;
+                n += m;
+            }
+        }
+        nvalid[g] = n;
+    }
+}
+
+/* Draw of k_t with the paper's own potential (Sec. 3.4):
+ * V_hw(k, S_t) = theta_sat - h(k)[Target(S_t)], P(k) proportional to
+ * exp(V_hw/tau) over the members of cluster I_t (alive may be NULL), by the same
+ * Gumbel-max construction and the same variates as kbo_sample. */
+void kbo_sample_signature(int32_t G, int32_t R, const int32_t *seg_off,
+                          const int32_t *assign, const uint8_t *alive, const float *h,
+                          const int32_t *target, float theta_sat, const int32_t *sel,
+                          uint64_t seed, uint64_t draw, double tau, int32_t *ksel,
+                          uint8_t *near)
+{
+#pragma omp parallel for schedule(dynamic, 16) if (G > 64)
+    for (int32_t g = 0; g < G; ++g) {
+        const int32_t I = sel[3 * (size_t)g];
+        double best = -INFINITY, runner = -INFINITY;
+        int32_t arg = -1;
+        if (I >= 0) {
+            const int32_t col = target[sel[3 * (size_t)g + 1]];
+            for (int32_t k = seg_off[g]; k < seg_off[g + 1]; ++k) {
+                if ((alive && !alive[k]) || assign[k] != I) continue;
+                const double V = (double)theta_sat - (double)h[(size_t)k * R + col];
+                const double u = kbo_uniform(seed, draw, k);
+                const double gumbel = -log(-log(u));
+                const double key = V / tau + gumbel;
+                if (arg < 0 || key > best) {
+                    runner = best;
+                    best = key;
+                    arg = k;
+                } else if (key > runner) {
+                    runner = key;
+                }
+            }
+        }
+        ksel[g] = arg;
+        if (near) {
+            uint8_t f = 0;
+            if (arg >= 0 && runner > -INFINITY) {
+                double scale = fabs(best) > KBO_TINY ? fabs(best) : KBO_TINY;
+                f = (uint8_t)((best - runner) <= KBO_NEAR_TIE_REL * scale);
+            }
+            near[g] = f;
+        }
+    }
+}
+
+/* ------------------------------------------------------- statistics update */
+
+/* The update at the end of an iteration of Alg. 1 for every search at once.
+ * For search g with the chosen arm (I, S*) = sel[g][0..1], the expanded
+ * candidate k = ksel[g] and the observed reward r = reward[g] in [0,1]:
+ *   t[g] <- t[g] + 1                                    (always)
+ * and, only if the new kernel was verified (ok[g] != 0) and an arm was chosen:
+ *   N_{I,S*}  <- N_{I,S*} + 1
+ *   mu_{I,S*} <- mu_{I,S*} + (r - mu_{I,S*}) / (N_{I,S*} + prior_n)
+ *   visits[k,S*] += 1 ; rsum[k,S*] += r                 (the per-candidate history
+ *                    from which the cluster statistics are rebuilt after a
+ *                    re-clustering)
+ * mu is read as fp32, updated in fp64 and rounded once; rsum likewise. */
+void kbo_update_stats(int32_t G, int32_t S, const int32_t *koff, const int32_t *sel,
+                      const int32_t *ksel, const float *reward, const uint8_t *ok,
+                      double prior_n, int32_t *visits, float *rsum, int32_t *Ncs,
+                      float *mu, int64_t *t)
+{
+    for (int32_t g = 0; g < G; ++g) {
+        t[g] += 1;
+        const int32_t I = sel[3 * (size_t)g], s = sel[3 * (size_t)g + 1];
+        const int32_t k = ksel[g];
+        if (!ok[g] || I < 0 || s < 0 || k < 0) continue;
+        const size_t arm = ((size_t)koff[g] + I) * S + s;
+        Ncs[arm] += 1;
+        const double n = (double)Ncs[arm] + prior_n;
+        const double m = (double)mu[arm];
+        mu[arm] = (float)(m + ((double)reward[g] - m) / n);
+        visits[(size_t)k * S + s] += 1;
+        rsum[(size_t)k * S + s] = (float)((double)rsum[(size_t)k * S + s] + (double)reward[g]);
+    }
+}
+
 /* ------------------------------------------------------------------ round */
 
 /* One scoring round: prune every candidate, cluster ALL candidates (pruned ones
@@ -432,7 +599,7 @@ void kbo_round(int32_t G, int32_t D, int32_t S, const int32_t *seg_off,
     kbo_cluster(G, D, seg_off, koff, X, NULL, iters, assign, cent, counts,
                 objective, dirty);
     kbo_ucb_select(G, S, seg_off, koff, assign, alive, bound, visits, rsum, t, c,
-                   prior_n, prior_mu, Ncs, mu, ucb, sel, near);
+                   prior_n, prior_mu, NULL, Ncs, mu, ucb, sel, near);
 }
 
 int32_t kbo_max_threads(void)
