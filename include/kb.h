@@ -19,6 +19,12 @@
  *                    headroom (Sec. 3.4, zero-temperature limit of the softmax
  *                    over V_hw).
  *   kb_round         the three in sequence on one stream.
+ *   kb_cluster_geometry, kb_strategy_mask, kb_ucb_select_masked,
+ *   kb_sample_signature, kb_update_stats
+ *                    the remaining device-side steps of an iteration of Alg. 1:
+ *                    cluster representatives, the mask in the paper's own form,
+ *                    selection under that mask, the draw with the paper's
+ *                    potential, and the statistics update.
  *   kb_sample        the draw of k_t inside the chosen cluster with probability
  *                    proportional to exp(headroom) (Sec. 3.4), reproducible from
  *                    (seed, draw).
@@ -35,8 +41,8 @@
  * aside); all scratch comes from the caller's workspace `ws` (device,
  * >= kb_workspace_bytes(), 256-byte aligned, contents undefined before and
  * after a call).  The workspace holds, besides small tables, a bf16 copy of the
- * features, |x|^2 and two distance bounds per candidate: about (4*Dpad + 16) * N
- * bytes with Dpad = D rounded up to 16.  Two calls may run concurrently only on
+ * features, |x|^2, a proposal and an fp64 distance per candidate: about
+ * (4*Dpad + 16) * N bytes with Dpad = D rounded up to 16.  Two calls may run concurrently only on
  * different workspaces.
  * Arrays are dense, row-major, with no padding.  X, cent*, flops, bytes, bound,
  * visits and rsum must be 16-byte aligned.
@@ -216,6 +222,68 @@ kb_status kb_sample(const kb_batch *batch, const kb_sample_params *sp,
                     const float *bound, const float *incumbent,
                     const int32_t *sel, int32_t *ksel, void *ws,
                     size_t ws_bytes, void *stream);
+
+/* The same draw with the paper's own potential (Sec. 3.4):
+ *   V_hw(k, S_t) = theta_sat - h[k, target[S_t]],  S_t = sel[g][1],
+ * h [N,R] being the hardware signature of every candidate (share of peak
+ * throughput of R resources) and target [S] the resource each strategy works on
+ * (values in [0,R)).  Same generator, same variates and same tie rule as
+ * kb_sample; alive may be NULL. */
+kb_status kb_sample_signature(const kb_batch *batch, const kb_sample_params *sp,
+                              const int32_t *assign, const uint8_t *alive,
+                              int32_t R, const float *h, const int32_t *target,
+                              float theta_sat, const int32_t *sel, int32_t *ksel,
+                              void *ws, size_t ws_bytes, void *stream);
+
+/* Representative and radius of every cluster (Sec. 3.3 "Representative
+ * profiling"; Alg. 1 "Update centroids k_c"; covering term of Theorem 1).
+ *   rep[j]    = GLOBAL index of the member of cluster j nearest cent[j] (squared
+ *               L2 distance in fp64 from direct differences, exactly as the
+ *               definition; lowest index on ties); -1 for an empty cluster
+ *   radius[j] = largest distance from cent[j] to a member, rounded to fp32
+ *               (0 for an empty cluster); diam(C_j) <= 2 radius[j]
+ * X [N,D], cent [Ksum,D] (16-byte aligned), assign [N] with values in [0,K_g). */
+kb_status kb_cluster_geometry(const kb_batch *batch, const float *X,
+                              const float *cent, const int32_t *assign,
+                              int32_t *rep, float *radius, void *ws,
+                              size_t ws_bytes, void *stream);
+
+/* The binary mask of Eq. 5 in the paper's own form,
+ *   M[i,s] = [ h[rep[i], target[s]] < theta_sat ]        (0 for rep[i] < 0),
+ * and nvalid[g] = the number of valid cluster arms of search g (K |S_valid| in
+ * Theorem 1).  h [N,R], target [S] in [0,R), rep [Ksum] as returned by
+ * kb_cluster_geometry, M [Ksum,S] out, nvalid [G] out.  Needs no workspace. */
+kb_status kb_strategy_mask(const kb_batch *batch, int32_t R, const float *h,
+                           const int32_t *target, const int32_t *rep,
+                           float theta_sat, uint8_t *M, int32_t *nvalid,
+                           void *stream);
+
+/* kb_ucb_select with the cluster-arm mask of Eq. 6: arm (i,s) takes part in the
+ * argmax iff cluster i has an alive member and M[i,s] != 0 (M == NULL: no
+ * mask); a masked arm gets ucb = -inf.  Here alive may be NULL (every candidate
+ * alive) and bound may be NULL (k* = the lowest-index alive member of I). */
+kb_status kb_ucb_select_masked(const kb_batch *batch, const kb_params *params,
+                               const int32_t *assign, const uint8_t *alive,
+                               const float *bound, const uint8_t *M,
+                               const int32_t *visits, const float *rsum,
+                               const int64_t *t, int32_t *Ncs, float *mu,
+                               float *ucb, int32_t *sel, void *ws,
+                               size_t ws_bytes, void *stream);
+
+/* The statistics update that ends an iteration of Alg. 1, for all searches at
+ * once and in place.  With (I, S*) = sel[g][0..1], k = ksel[g], r = reward[g]:
+ *   t[g] += 1                                              always
+ *   if ok[g] != 0 and an arm and a candidate were chosen:
+ *     Ncs[I,S*] += 1;  mu[I,S*] += (r - mu[I,S*]) / (Ncs[I,S*] + prior_n)
+ *     visits[k,S*] += 1;  rsum[k,S*] += r      (the per-candidate history the
+ *                       cluster statistics are rebuilt from after re-clustering)
+ * reward [G] in [0,1], ok [G] (1 = the generated kernel was verified).  Entries
+ * of sel / ksel outside their search are ignored. */
+kb_status kb_update_stats(const kb_batch *batch, const kb_params *params,
+                          const int32_t *sel, const int32_t *ksel,
+                          const float *reward, const uint8_t *ok,
+                          int32_t *visits, float *rsum, int32_t *Ncs, float *mu,
+                          int64_t *t, void *stream);
 
 /* Static, never NULL. */
 const char *kb_status_str(kb_status status);

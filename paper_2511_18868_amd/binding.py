@@ -72,6 +72,18 @@ def lib() -> ctypes.CDLL:
         L.kb_round.argtypes = [pb, pp, ctypes.POINTER(kb_round_io), vp, sz, vp]
         L.kb_sample.restype = ctypes.c_int
         L.kb_sample.argtypes = [pb, ctypes.POINTER(kb_sample_params)] + [vp] * 6 + [vp, sz, vp]
+        L.kb_sample_signature.restype = ctypes.c_int
+        L.kb_sample_signature.argtypes = [pb, ctypes.POINTER(kb_sample_params), vp, vp,
+                                          ctypes.c_int32, vp, vp, ctypes.c_float, vp, vp,
+                                          vp, sz, vp]
+        L.kb_cluster_geometry.restype = ctypes.c_int
+        L.kb_cluster_geometry.argtypes = [pb] + [vp] * 5 + [vp, sz, vp]
+        L.kb_strategy_mask.restype = ctypes.c_int
+        L.kb_strategy_mask.argtypes = [pb, ctypes.c_int32, vp, vp, vp, ctypes.c_float, vp, vp, vp]
+        L.kb_ucb_select_masked.restype = ctypes.c_int
+        L.kb_ucb_select_masked.argtypes = [pb, pp] + [vp] * 11 + [vp, sz, vp]
+        L.kb_update_stats.restype = ctypes.c_int
+        L.kb_update_stats.argtypes = [pb, pp] + [vp] * 9 + [vp]
         L.kb_status_str.restype = ctypes.c_char_p
         L.kb_status_str.argtypes = [ctypes.c_int]
         L.kb_version.restype = ctypes.c_char_p
@@ -163,6 +175,43 @@ def kb_sample(batch, sp: kb_sample_params, assign, alive, bound, incumbent, sel,
     return _check(s, "kb_sample", check)
 
 
+def kb_sample_signature(batch, sp: kb_sample_params, assign, alive, R, h, target, theta_sat, sel,
+                        ksel, ws, ws_bytes, stream=None, check=True):
+    s = lib().kb_sample_signature(ctypes.byref(batch), ctypes.byref(sp), _ptr(assign), _ptr(alive),
+                                  R, _ptr(h), _ptr(target), theta_sat, _ptr(sel), _ptr(ksel),
+                                  _ptr(ws), ws_bytes, _stream(stream))
+    return _check(s, "kb_sample_signature", check)
+
+
+def kb_cluster_geometry(batch, X, cent, assign, rep, radius, ws, ws_bytes, stream=None, check=True):
+    s = lib().kb_cluster_geometry(ctypes.byref(batch), _ptr(X), _ptr(cent), _ptr(assign), _ptr(rep),
+                                  _ptr(radius), _ptr(ws), ws_bytes, _stream(stream))
+    return _check(s, "kb_cluster_geometry", check)
+
+
+def kb_strategy_mask(batch, R, h, target, rep, theta_sat, M, nvalid, stream=None, check=True):
+    s = lib().kb_strategy_mask(ctypes.byref(batch), R, _ptr(h), _ptr(target), _ptr(rep), theta_sat,
+                               _ptr(M), _ptr(nvalid), _stream(stream))
+    return _check(s, "kb_strategy_mask", check)
+
+
+def kb_ucb_select_masked(batch, params, assign, alive, bound, M, visits, rsum, t, Ncs, mu, ucb, sel,
+                         ws, ws_bytes, stream=None, check=True):
+    s = lib().kb_ucb_select_masked(ctypes.byref(batch), ctypes.byref(params), _ptr(assign),
+                                   _ptr(alive), _ptr(bound), _ptr(M), _ptr(visits), _ptr(rsum),
+                                   _ptr(t), _ptr(Ncs), _ptr(mu), _ptr(ucb), _ptr(sel), _ptr(ws),
+                                   ws_bytes, _stream(stream))
+    return _check(s, "kb_ucb_select_masked", check)
+
+
+def kb_update_stats(batch, params, sel, ksel, reward, ok, visits, rsum, Ncs, mu, t, stream=None,
+                    check=True):
+    s = lib().kb_update_stats(ctypes.byref(batch), ctypes.byref(params), _ptr(sel), _ptr(ksel),
+                              _ptr(reward), _ptr(ok), _ptr(visits), _ptr(rsum), _ptr(Ncs), _ptr(mu),
+                              _ptr(t), _stream(stream))
+    return _check(s, "kb_update_stats", check)
+
+
 def kb_set_scorer(mode: int) -> int:
     return int(lib().kb_set_scorer(int(mode)))
 
@@ -210,6 +259,10 @@ class DeviceBatch:
         self.ucb = z((Ksum, S), torch.float32)
         self.sel = z((G, 3), torch.int32)
         self.ksel = z((G,), torch.int32)
+        self.rep = z((Ksum,), torch.int32)
+        self.radius = z((Ksum,), torch.float32)
+        self.M = z((Ksum, S), torch.uint8)
+        self.nvalid = z((G,), torch.int32)
         self.batch = make_batch(G, D, S, N, b.Kmax, Ksum, b.Nmax, self.seg_off, self.koff)
         self.params = make_params(b.peak_flops, b.peak_bw, b.c, b.prior_n, b.prior_mu,
                                   b.iters if iters is None else iters)
@@ -243,6 +296,10 @@ class DeviceBatch:
         return kb_sample(self.batch, kb_sample_params(seed, draw, tau), self.assign,
                          self.alive if alive else None, self.bound, self.incumbent, self.sel,
                          self.ksel, self.ws, self.ws_bytes, **kw)
+
+    def cluster_geometry(self, **kw):
+        return kb_cluster_geometry(self.batch, self.X, self.cent, self.assign, self.rep,
+                                   self.radius, self.ws, self.ws_bytes, **kw)
 
     def round(self, **kw):
         return kb_round(self.batch, self.params, self.io, self.ws, self.ws_bytes, **kw)

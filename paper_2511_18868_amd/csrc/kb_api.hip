@@ -30,6 +30,12 @@ WsLayout ws_layout(const kb_batch& b) {
         w.ucb_nalive = off; off += align256(4 * k);
     }
     {
+        const size_t k = (size_t)(b.Ksum > 0 ? b.Ksum : 1);
+        w.geo_d2 = off;  off += align256(8 * (size_t)(b.N > 0 ? b.N : 1));
+        w.geo_min = off; off += align256(8 * k);
+        w.geo_max = off; off += align256(8 * k);
+    }
+    {
         const size_t ranges = (size_t)((b.N + kSampleRange - 1) / kSampleRange) + 1;
         w.samp_key = off; off += align256(8 * 2 * ranges);
         w.samp_idx = off; off += align256(4 * 2 * ranges);
@@ -127,9 +133,10 @@ static kb_status do_cluster(const kb_batch* b, const float* X, const float* cent
 static kb_status check_ucb(const kb_batch* b, const kb_params* p, const int32_t* assign,
                            const uint8_t* alive, const float* bound, const int32_t* visits,
                            const float* rsum, const int64_t* t, const int32_t* Ncs,
-                           const float* mu, const float* ucb, const int32_t* sel) {
-    if (!p || !assign || !alive || !bound || !visits || !rsum || !t || !Ncs || !mu || !ucb || !sel)
-        return KB_EINVAL;
+                           const float* mu, const float* ucb, const int32_t* sel,
+                           bool optional_mask_inputs = false) {
+    if (!p || !assign || !visits || !rsum || !t || !Ncs || !mu || !ucb || !sel) return KB_EINVAL;
+    if (!optional_mask_inputs && (!alive || !bound)) return KB_EINVAL;
     if (!(p->prior_n >= 0.0f) || !(p->c == p->c) || !(p->prior_mu == p->prior_mu)) return KB_EINVAL;
     if (!aligned(visits, 16) || !aligned(rsum, 16)) return KB_EINVAL;
     if (b->Kmax > KB_MAX_K || (int64_t)b->Kmax * b->S > KB_MAX_KS) return KB_EUNSUPPORTED;
@@ -139,8 +146,10 @@ static kb_status check_ucb(const kb_batch* b, const kb_params* p, const int32_t*
 static kb_status do_ucb(const kb_batch* b, const kb_params* p, const int32_t* assign,
                         const uint8_t* alive, const float* bound, const int32_t* visits,
                         const float* rsum, const int64_t* t, int32_t* Ncs, float* mu,
-                        float* ucb, int32_t* sel, void* ws, bool have_order, hipStream_t st) {
-    kb_status s = check_ucb(b, p, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel);
+                        float* ucb, int32_t* sel, void* ws, bool have_order, hipStream_t st,
+                        const uint8_t* M = nullptr, bool optional_mask_inputs = false) {
+    kb_status s = check_ucb(b, p, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel,
+                            optional_mask_inputs);
     if (s != KB_OK) return s;
     WsLayout w = ws_layout(*b);
     char* base = (char*)ws;
@@ -150,7 +159,7 @@ static kb_status do_ucb(const kb_batch* b, const kb_params* p, const int32_t* as
         if (e != hipSuccess) return KB_EDEVICE;
     }
     UcbCall c;
-    c.assign = assign; c.alive = alive; c.bound = bound; c.visits = visits; c.rsum = rsum;
+    c.assign = assign; c.alive = alive; c.bound = bound; c.M = M; c.visits = visits; c.rsum = rsum;
     c.t = t; c.c = p->c; c.prior_n = p->prior_n; c.prior_mu = p->prior_mu;
     c.Ncs = Ncs; c.mu = mu; c.ucb = ucb; c.sel = sel; c.order = order;
     c.gN = nullptr; c.gR = nullptr; c.gnalive = nullptr; c.gkmin = nullptr;
@@ -216,6 +225,86 @@ kb_status kb_ucb_select(const kb_batch* batch, const kb_params* params, const in
                   false, (hipStream_t)stream);
 }
 
+kb_status kb_ucb_select_masked(const kb_batch* batch, const kb_params* params,
+                               const int32_t* assign, const uint8_t* alive, const float* bound,
+                               const uint8_t* M, const int32_t* visits, const float* rsum,
+                               const int64_t* t, int32_t* Ncs, float* mu, float* ucb, int32_t* sel,
+                               void* ws, size_t ws_bytes, void* stream) {
+    kb_status s = check_batch(batch);
+    if (s != KB_OK) return s;
+    s = check_ws(batch, ws, ws_bytes);
+    if (s != KB_OK) return s;
+    return do_ucb(batch, params, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel, ws,
+                  false, (hipStream_t)stream, M, true);
+}
+
+kb_status kb_cluster_geometry(const kb_batch* batch, const float* X, const float* cent,
+                              const int32_t* assign, int32_t* rep, float* radius, void* ws,
+                              size_t ws_bytes, void* stream) {
+    kb_status s = check_batch(batch);
+    if (s != KB_OK) return s;
+    if (!X || !cent || !assign || !rep || !radius) return KB_EINVAL;
+    if (!aligned(X, 16) || !aligned(cent, 16)) return KB_EINVAL;
+    if (batch->D > KB_MAX_D || batch->Kmax > KB_MAX_K) return KB_EUNSUPPORTED;
+    if (geometry_lds_bytes(batch->Kmax > 0 ? batch->Kmax : 1, batch->D) > 160 * 1024)
+        return KB_EUNSUPPORTED;
+    s = check_ws(batch, ws, ws_bytes);
+    if (s != KB_OK) return s;
+    WsLayout w = ws_layout(*batch);
+    char* base = (char*)ws;
+    GeoCall c;
+    c.X = X; c.cent = cent; c.assign = assign; c.rep = rep; c.radius = radius;
+    c.d2 = (double*)(base + w.geo_d2);
+    c.gmin = (unsigned long long*)(base + w.geo_min);
+    c.gmax = (unsigned long long*)(base + w.geo_max);
+    return dev(launch_geometry(*batch, c, (hipStream_t)stream));
+}
+
+kb_status kb_strategy_mask(const kb_batch* batch, int32_t R, const float* h, const int32_t* target,
+                           const int32_t* rep, float theta_sat, uint8_t* M, int32_t* nvalid,
+                           void* stream) {
+    kb_status s = check_batch(batch);
+    if (s != KB_OK) return s;
+    if (R <= 0 || !h || !target || !rep || !M || !nvalid) return KB_EINVAL;
+    if (!(theta_sat == theta_sat)) return KB_EINVAL;
+    return dev(launch_strategy_mask(*batch, R, h, target, rep, theta_sat, M, nvalid,
+                                    (hipStream_t)stream));
+}
+
+kb_status kb_update_stats(const kb_batch* batch, const kb_params* params, const int32_t* sel,
+                          const int32_t* ksel, const float* reward, const uint8_t* ok,
+                          int32_t* visits, float* rsum, int32_t* Ncs, float* mu, int64_t* t,
+                          void* stream) {
+    kb_status s = check_batch(batch);
+    if (s != KB_OK) return s;
+    if (!params || !sel || !ksel || !reward || !ok || !visits || !rsum || !Ncs || !mu || !t)
+        return KB_EINVAL;
+    if (!(params->prior_n >= 0.0f)) return KB_EINVAL;
+    return dev(launch_update_stats(*batch, params->prior_n, sel, ksel, reward, ok, visits, rsum,
+                                   Ncs, mu, t, (hipStream_t)stream));
+}
+
+kb_status kb_sample_signature(const kb_batch* batch, const kb_sample_params* sp,
+                              const int32_t* assign, const uint8_t* alive, int32_t R,
+                              const float* h, const int32_t* target, float theta_sat,
+                              const int32_t* sel, int32_t* ksel, void* ws, size_t ws_bytes,
+                              void* stream) {
+    kb_status s = check_batch(batch);
+    if (s != KB_OK) return s;
+    if (!sp || !assign || R <= 0 || !h || !target || !sel || !ksel) return KB_EINVAL;
+    if (!(sp->tau > 0.0f) || !(sp->tau < INFINITY) || !(theta_sat == theta_sat)) return KB_EINVAL;
+    s = check_ws(batch, ws, ws_bytes);
+    if (s != KB_OK) return s;
+    WsLayout w = ws_layout(*batch);
+    char* base = (char*)ws;
+    SampleCall c;
+    c.assign = assign; c.alive = alive; c.bound = nullptr; c.incumbent = nullptr; c.sel = sel;
+    c.h = h; c.target = target; c.R = R; c.theta_sat = theta_sat;
+    c.seed = sp->seed; c.draw = sp->draw; c.tau = sp->tau; c.ksel = ksel;
+    c.slot_key = (double*)(base + w.samp_key); c.slot_idx = (int32_t*)(base + w.samp_idx);
+    return dev(launch_sample(*batch, c, (hipStream_t)stream));
+}
+
 kb_status kb_sample(const kb_batch* batch, const kb_sample_params* sp, const int32_t* assign,
                     const uint8_t* alive, const float* bound, const float* incumbent,
                     const int32_t* sel, int32_t* ksel, void* ws, size_t ws_bytes, void* stream) {
@@ -274,7 +363,7 @@ const char* kb_status_str(kb_status status) {
     return "KB_E?: unknown status";
 }
 
-const char* kb_version(void) { return "0.2"; }
+const char* kb_version(void) { return "0.3"; }
 
 int kb_set_scorer(int mode) {
     if (mode < 0 || mode > 2) return KB_EINVAL;

@@ -8,6 +8,7 @@
 namespace kb {
 
 constexpr int kWave = 64;
+constexpr int kGeoRange = 2048;      // candidates per workgroup of the representative / radius pass
 constexpr int kSampleRange = 4096;   // candidates per workgroup of the in-cluster draw
 constexpr int kTilesPerChunk = 32;   // tiles of 32 candidates per workgroup of the multi-workgroup clustering path
 
@@ -36,6 +37,9 @@ struct WsLayout {
     BigWs big;
     bool ucb_chunked;   // searches longer than 16384 candidates: partial tables per candidate range
     size_t ucb_R, ucb_N, ucb_kmin, ucb_nalive;
+    size_t geo_d2;     // double [N]     squared distance of every candidate to its centroid
+    size_t geo_min;    // uint64 [Ksum]  bit pattern of the smallest such distance per cluster
+    size_t geo_max;    // uint64 [Ksum]  and of the largest
     size_t samp_key;   // double [2*ranges]  partial best keys of searches that cross range borders
     size_t samp_idx;   // int32  [2*ranges]  their candidates
     size_t total;
@@ -74,8 +78,9 @@ void set_scorer(int mode);                   // 0 default, 1 vector ALU only, 2 
 
 struct UcbCall {
     const int32_t* assign;
-    const uint8_t* alive;
-    const float* bound;
+    const uint8_t* alive;     // NULL: every candidate alive
+    const float* bound;       // NULL: k* = lowest-index member
+    const uint8_t* M;         // NULL or [Ksum,S] strategy mask
     const int32_t* visits;
     const float* rsum;
     const int64_t* t;
@@ -110,6 +115,27 @@ struct SampleCall {
     int32_t* slot_idx;
 };
 hipError_t launch_sample(const kb_batch& b, const SampleCall& c, hipStream_t st);
+
+struct GeoCall {
+    const float* X;
+    const float* cent;
+    const int32_t* assign;
+    int32_t* rep;
+    float* radius;
+    double* d2;
+    unsigned long long* gmin;
+    unsigned long long* gmax;
+};
+hipError_t launch_geometry(const kb_batch& b, const GeoCall& c, hipStream_t st);
+size_t geometry_lds_bytes(int Kmax, int D);
+
+hipError_t launch_strategy_mask(const kb_batch& b, int R, const float* h, const int32_t* target,
+                                const int32_t* rep, float theta_sat, uint8_t* M, int32_t* nvalid,
+                                hipStream_t st);
+hipError_t launch_update_stats(const kb_batch& b, float prior_n, const int32_t* sel,
+                               const int32_t* ksel, const float* reward, const uint8_t* ok,
+                               int32_t* visits, float* rsum, int32_t* Ncs, float* mu, int64_t* t,
+                               hipStream_t st);
 
 // ---- device helpers ----------------------------------------------------------
 __device__ __forceinline__ int clampi(int v, int lo, int hi) {

@@ -21,8 +21,9 @@ struct UcbArgs {
     const int32_t* seg_off;
     const int32_t* koff;
     const int32_t* assign;
-    const uint8_t* alive;
-    const float* bound;
+    const uint8_t* alive;       // NULL: every candidate alive
+    const float* bound;         // NULL: all bounds equal (k* = lowest-index member)
+    const uint8_t* M;           // NULL or [Ksum*S]: cluster arms allowed by the strategy mask
     const int32_t* visits;
     const float* rsum;
     const int64_t* t;
@@ -89,9 +90,9 @@ __device__ __forceinline__ void ucb_accumulate(const UcbArgs& a, int n0, int K, 
             for (int u = 0; u < U; ++u) {
                 const int p = pb + u * rpp;
                 const int pc = p < q1 ? p : q1 - 1;
-                al[u] = a.alive[(size_t)n0 + pc] != 0 && p < q1;
+                al[u] = (a.alive ? a.alive[(size_t)n0 + pc] != 0 : true) && p < q1;
                 jj[u] = a.assign[(size_t)n0 + pc];
-                bd[u] = a.bound[(size_t)n0 + pc];
+                bd[u] = a.bound ? a.bound[(size_t)n0 + pc] : 0.f;
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -129,7 +130,7 @@ __device__ __forceinline__ void ucb_accumulate(const UcbArgs& a, int n0, int K, 
         for (size_t q = tid; q < total; q += kThreads) {
             const int pl = (int)(q / S), p = q0 + pl;
             const int s = (int)(q - (size_t)pl * S);
-            if (!a.alive[(size_t)n0 + p]) continue;
+            if (a.alive && !a.alive[(size_t)n0 + p]) continue;
             int j = a.assign[(size_t)n0 + p];
             j = (j >= 0 && j < K) ? j : 0;
             atomicAdd(&Ncnt[(size_t)j * S + s], (unsigned)vis[q]);
@@ -137,7 +138,7 @@ __device__ __forceinline__ void ucb_accumulate(const UcbArgs& a, int n0, int K, 
             if (s == 0) {
                 atomicAdd(&nalive[j], 1u);
                 const unsigned long long key =
-                    ((unsigned long long)ordered_bits(a.bound[(size_t)n0 + p]) << 32) | (unsigned)p;
+                    ((unsigned long long)ordered_bits(a.bound ? a.bound[(size_t)n0 + p] : 0.f) << 32) | (unsigned)p;
                 atomicMin(&kmin[j], key);
             }
         }
@@ -167,7 +168,7 @@ __device__ __forceinline__ void ucb_finish(const UcbArgs& a, int g, int n0, int 
         const double rt = (double)(long long)R[i] * kRewardInv + pn * pm;
         const double m = nt > 0.0 ? rt / nt : NAN;
         double u;
-        const bool valid = nalive[cl] > 0u;
+        const bool valid = nalive[cl] > 0u && (!a.M || a.M[(size_t)k0 * S + i] != 0);
         if (!valid) u = -INFINITY;
         else if (nt > 0.0) u = m + cc * sqrt(lnt / nt);
         else u = INFINITY;
@@ -316,7 +317,7 @@ hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st) {
     UcbArgs a;
     a.G = b.G; a.S = b.S; a.Ksum = b.Ksum; a.Kmax = b.Kmax > 0 ? b.Kmax : 1; a.N = b.N;
     a.seg_off = b.seg_off; a.koff = b.koff; a.assign = c.assign; a.alive = c.alive;
-    a.bound = c.bound; a.visits = c.visits; a.rsum = c.rsum; a.t = c.t; a.c = c.c;
+    a.bound = c.bound; a.M = c.M; a.visits = c.visits; a.rsum = c.rsum; a.t = c.t; a.c = c.c;
     a.prior_n = c.prior_n; a.prior_mu = c.prior_mu; a.Ncs = c.Ncs; a.mu = c.mu; a.ucb = c.ucb;
     a.sel = c.sel; a.order = c.order;
     const size_t lds = 64 + (size_t)a.Kmax * b.S * 12 + (size_t)a.Kmax * 12;

@@ -246,3 +246,29 @@ def random_centroids(batch: Batch, seed: int = 0) -> np.ndarray:
             rows = rng.choice(b - a, size=k1 - k0, replace=False)
             out[k0:k1] = batch.X[a + rows]
     return out
+
+
+def signatures(batch: Batch, R: int = 3, seed: int = 0):
+    """Hardware signatures for the paper's own form of the mask (Sec. 3.2): for
+    every candidate the share of peak throughput of R resources (the paper uses
+    DRAM, L2 and SM), drawn from a Beta(2, 2) so that a 75 % threshold cuts off a
+    sizeable minority, a few of them set exactly to the threshold; and the resource
+    each strategy targets, round-robin over the resources.  Returns (h [N,R] fp32,
+    target [S] int32, theta_sat)."""
+    rng = np.random.default_rng(BASE_SEED + 1000 + seed)
+    h = rng.beta(2.0, 2.0, size=(batch.N, R)).astype(np.float32)
+    theta = float(np.float32(0.75))
+    exact = rng.random((batch.N, R)) < 0.02
+    h[exact] = np.float32(theta)
+    target = (np.arange(batch.S) % R).astype(np.int32)
+    return h, target, theta
+
+
+def feedback(batch: Batch, seed: int = 0):
+    """Outcome of one generation step per search: a reward in [0, 1] (Sec. 2.2) and
+    whether the generated kernel passed verification (about four in five do)."""
+    rng = np.random.default_rng(BASE_SEED + 2000 + seed)
+    reward = rng.uniform(0.0, 1.0, batch.G).astype(np.float32)
+    ok = (rng.random(batch.G) < 0.8).astype(np.uint8)
+    reward[ok == 0] = 0.0
+    return reward, ok

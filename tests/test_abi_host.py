@@ -143,6 +143,46 @@ def test_sample_argument_errors(L):
     assert ctypes.sizeof(kb.kb_sample_params) == 24
 
 
+def test_loop_entry_points_argument_errors(L):
+    b = _batch()
+    p = kb.make_params()
+    big = 1 << 20
+    sp = kb.kb_sample_params(1, 2, 1.0)
+    # geometry: X, cent, assign, rep, radius
+    g = [FAKE] * 5
+    for i in range(5):
+        bad = list(g); bad[i] = None
+        assert kb.kb_cluster_geometry(b, *bad, FAKE, big, stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_cluster_geometry(b, FAKE + 4, *g[1:], FAKE, big, stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_cluster_geometry(b, *g, FAKE, 16, stream=0, check=False) == kb.KB_EWORKSPACE
+    assert kb.kb_cluster_geometry(_batch(D=65), *g, FAKE, big, stream=0, check=False) == kb.KB_EUNSUPPORTED
+    # mask: R, h, target, rep, theta, M, nvalid
+    assert kb.kb_strategy_mask(b, 0, FAKE, FAKE, FAKE, 0.75, FAKE, FAKE, stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_strategy_mask(b, 3, None, FAKE, FAKE, 0.75, FAKE, FAKE, stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_strategy_mask(b, 3, FAKE, FAKE, FAKE, float("nan"), FAKE, FAKE, stream=0,
+                               check=False) == kb.KB_EINVAL
+    # masked selection: alive, bound and M may be NULL, the rest may not
+    args = [FAKE] * 11
+    bad = list(args); bad[0] = None
+    assert kb.kb_ucb_select_masked(b, p, *bad, FAKE, big, stream=0, check=False) == kb.KB_EINVAL
+    bad = list(args); bad[4] = None
+    assert kb.kb_ucb_select_masked(b, p, *bad, FAKE, big, stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_ucb_select_masked(b, p, *args, FAKE, 16, stream=0, check=False) == kb.KB_EWORKSPACE
+    # update: sel, ksel, reward, ok, visits, rsum, Ncs, mu, t
+    u = [FAKE] * 9
+    for i in range(9):
+        bad = list(u); bad[i] = None
+        assert kb.kb_update_stats(b, p, *bad, stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_update_stats(b, kb.make_params(prior_n=-1.0), *u, stream=0, check=False) == kb.KB_EINVAL
+    # signature draw
+    assert kb.kb_sample_signature(b, sp, FAKE, None, 0, FAKE, FAKE, 0.75, FAKE, FAKE, FAKE, big,
+                                  stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_sample_signature(b, sp, FAKE, None, 3, None, FAKE, 0.75, FAKE, FAKE, FAKE, big,
+                                  stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_sample_signature(b, kb.kb_sample_params(1, 2, 0.0), FAKE, None, 3, FAKE, FAKE, 0.75,
+                                  FAKE, FAKE, FAKE, big, stream=0, check=False) == kb.KB_EINVAL
+
+
 def test_scorer_switch(L):
     assert kb.kb_set_scorer(1) == kb.KB_OK
     assert kb.kb_set_scorer(2) == kb.KB_OK

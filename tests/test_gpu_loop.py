@@ -1,0 +1,203 @@
+"""GPU parity of the steps that close the loop of Alg. 1 around the scoring pass
+- cluster representatives and radii, the strategy mask in the paper's own form,
+selection under that mask, the draw with the paper's potential and the statistics
+update - against the CPU oracle, through the C ABI.  Indices, masks and counts
+are compared bit-exactly; the distances behind the representatives are formed in
+the same precision and order on both sides, so they need no exclusions."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2511_18868_amd import synth
+from kbcheck import assert_rel_close
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def kb():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2511_18868_amd import binding
+    binding.lib()
+    binding.kb_set_scorer(0)
+    return binding
+
+
+def _sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+def _up(d, a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to(d.device)
+
+
+def _with_empty_searches():
+    b = synth.config5(G=12, nmin=64, nmax=200, seed=8)
+    ng = np.diff(b.seg_off); kg = np.diff(b.koff)
+    ins = [0, 5, len(ng)]
+    ng2 = np.insert(ng, ins, 0); kg2 = np.insert(kg, ins, 0)
+    b.seg_off = np.concatenate([[0], np.cumsum(ng2)]).astype(np.int32)
+    b.koff = np.concatenate([[0], np.cumsum(kg2)]).astype(np.int32)
+    b.G = len(ng2)
+    b.incumbent = np.insert(b.incumbent, ins, 1.0).astype(np.float32)
+    b.t = np.insert(b.t, ins, 1).astype(np.int64)
+    return b
+
+
+CASES = {
+    "cfg1": lambda: synth.config1(),
+    "cfg2": lambda: synth.config2(),
+    "cfg3s": lambda: synth.config3(G=48),
+    "cfg5s": lambda: synth.config5(G=96),
+    "paper": lambda: synth.paper_shape(),                       # D = 5: the scalar row path
+    "ragged": lambda: synth.config5(G=17, nmin=64, nmax=700, D=20, S=6, seed=99),
+    "oddD": lambda: synth.config5(G=9, nmin=64, nmax=900, D=7, S=3, seed=4),
+    "empty": _with_empty_searches,
+    "cfg4s": lambda: synth.config4(N=8192, K=256, ncentres=256),  # largest LDS footprint
+    "bigN": lambda: synth.config2(N=70001, D=16, K=8, S=4, iters=2, seed=5),
+}
+
+
+@pytest.fixture(scope="module", params=list(CASES))
+def case(request):
+    b = CASES[request.param]()
+    c = oracle.cluster(b.seg_off, b.koff, b.X, min(b.iters, 3))
+    return request.param, b, c
+
+
+def test_cluster_geometry_exact(kb, case):
+    name, b, c = case
+    d = kb.DeviceBatch(b)
+    d.assign.copy_(_up(d, c.assign))
+    d.cent.copy_(_up(d, c.cent))
+    d.rep.fill_(-5)
+    d.radius.fill_(-1.0)
+    d.cluster_geometry()
+    _sync()
+    want = oracle.cluster_geometry(b.seg_off, b.koff, b.X, c.cent, c.assign)
+    np.testing.assert_array_equal(d.host("rep"), want.rep, err_msg=name)
+    np.testing.assert_array_equal(d.host("radius"), want.radius.astype(np.float32), err_msg=name)
+    # an empty cluster (when the case has one) reports -1 / 0
+    empty = c.counts == 0
+    assert (d.host("rep")[empty] == -1).all() and (d.host("radius")[empty] == 0).all()
+    # twice in a row on the same workspace: same bytes
+    d.cluster_geometry()
+    _sync()
+    np.testing.assert_array_equal(d.host("rep"), want.rep)
+
+
+def test_geometry_ties_and_duplicates(kb):
+    # duplicate rows at the minimum distance: the lowest index is the representative
+    b = synth.config5(G=4, nmin=100, nmax=300, seed=13)
+    c = oracle.cluster(b.seg_off, b.koff, b.X, 3)
+    g = oracle.cluster_geometry(b.seg_off, b.koff, b.X, c.cent, c.assign)
+    X = b.X.copy()
+    assign = c.assign.copy()
+    moved = 0
+    for s in range(b.G):
+        for j in range(b.koff[s], b.koff[s + 1]):
+            r = g.rep[j]
+            mem = np.where(assign[b.seg_off[s]:b.seg_off[s + 1]] == j - b.koff[s])[0] + b.seg_off[s]
+            later = mem[mem > r]
+            earlier = mem[mem < r]
+            if len(later) and len(earlier):
+                X[later[-1]] = X[r]          # a copy of the representative after it
+                X[earlier[0]] = X[r]         # and one before it: that one must win
+                moved += 1
+    assert moved > 10
+    b.X = X
+    d = kb.DeviceBatch(b)
+    d.assign.copy_(_up(d, assign))
+    d.cent.copy_(_up(d, c.cent))
+    d.cluster_geometry()
+    _sync()
+    want = oracle.cluster_geometry(b.seg_off, b.koff, X, c.cent, assign)
+    assert (want.rep != g.rep).sum() >= moved
+    np.testing.assert_array_equal(d.host("rep"), want.rep)
+    np.testing.assert_array_equal(d.host("radius"), want.radius.astype(np.float32))
+
+
+def test_mask_selection_draw_update_chain(kb, case):
+    """The paper-form iteration on identical inputs, step by step."""
+    import torch
+    name, b, c = case
+    R = 3
+    h, target, theta = synth.signatures(b, R)
+    g = oracle.cluster_geometry(b.seg_off, b.koff, b.X, c.cent, c.assign)
+    d = kb.DeviceBatch(b)
+    d.assign.copy_(_up(d, c.assign))
+    dh, dt, drep = _up(d, h), _up(d, target), _up(d, g.rep)
+    # mask
+    kb.kb_strategy_mask(d.batch, R, dh, dt, drep, theta, d.M, d.nvalid)
+    _sync()
+    m = oracle.strategy_mask(b.koff, b.S, h, target, g.rep, theta)
+    np.testing.assert_array_equal(d.host("M"), m.M)
+    np.testing.assert_array_equal(d.host("nvalid"), m.nvalid)
+    assert 0 < m.M.mean() < 1
+    # selection under the mask, every candidate alive, no bounds
+    kb.kb_ucb_select_masked(d.batch, d.params, d.assign, None, None, d.M, d.visits, d.rsum, d.t,
+                            d.Ncs, d.mu, d.ucb, d.sel, d.ws, d.ws_bytes)
+    _sync()
+    u = oracle.ucb_select(b.seg_off, b.koff, b.S, c.assign, None, None, b.visits, b.rsum, b.t, b.c,
+                          b.prior_n, b.prior_mu, M=m.M)
+    np.testing.assert_array_equal(d.host("Ncs"), u.Ncs)
+    assert_rel_close(d.host("mu"), u.mu, what="mu")
+    assert_rel_close(d.host("ucb"), u.ucb, what="ucb")
+    ok = u.near == 0
+    np.testing.assert_array_equal(d.host("sel")[ok], u.sel[ok])
+    assert np.isneginf(d.host("ucb")[m.M == 0]).all()
+    # the draw with V = theta - h[k, target[S*]] on the oracle's selection
+    d.sel.copy_(_up(d, u.sel))
+    sp = kb.kb_sample_params(11, 3, 0.1)
+    kb.kb_sample_signature(d.batch, sp, d.assign, None, R, dh, dt, theta, d.sel, d.ksel, d.ws,
+                           d.ws_bytes)
+    _sync()
+    s = oracle.sample_signature(b.seg_off, c.assign, None, h, target, theta, u.sel, 11, 3,
+                                float(np.float32(0.1)))
+    oks = s.near == 0
+    np.testing.assert_array_equal(d.host("ksel")[oks], s.ksel[oks])
+    # the update, in place, from the oracle's tables so that both start equal
+    reward, okv = synth.feedback(b)
+    Ncs0 = u.Ncs.astype(np.int32)
+    mu0 = np.nan_to_num(u.mu.astype(np.float32), nan=0.5)
+    d.Ncs.copy_(_up(d, Ncs0)); d.mu.copy_(_up(d, mu0)); d.ksel.copy_(_up(d, s.ksel))
+    kb.kb_update_stats(d.batch, d.params, d.sel, d.ksel, _up(d, reward), _up(d, okv), d.visits,
+                       d.rsum, d.Ncs, d.mu, d.t)
+    _sync()
+    w = oracle.update_stats(b.koff, b.S, u.sel, s.ksel, reward, okv, b.prior_n, b.visits, b.rsum,
+                            Ncs0, mu0, b.t)
+    np.testing.assert_array_equal(d.host("visits"), w.visits)
+    np.testing.assert_array_equal(d.host("Ncs"), w.Ncs)
+    np.testing.assert_array_equal(d.host("t"), w.t)
+    np.testing.assert_array_equal(d.host("rsum").view(np.uint32), w.rsum.view(np.uint32))
+    np.testing.assert_array_equal(d.host("mu").view(np.uint32), w.mu.view(np.uint32))
+    changed = (w.Ncs != Ncs0).sum()
+    assert changed == int(((okv != 0) & (u.sel[:, 0] >= 0) & (s.ksel >= 0)).sum())
+
+
+def test_masked_selection_reduces_to_plain_selection(kb):
+    b = synth.config5(G=40, nmin=64, nmax=2000, seed=3)
+    ora = oracle.round_(b, iters=2)
+    d = kb.DeviceBatch(b)
+    for n in ("assign", "alive", "bound"):
+        getattr(d, n).copy_(_up(d, getattr(ora, n)))
+    d.ucb_select()
+    _sync()
+    plain = {k: d.host(k).copy() for k in ("Ncs", "mu", "ucb", "sel")}
+    d.M.fill_(1)
+    for M in (None, d.M):
+        d.sel.fill_(-9)
+        kb.kb_ucb_select_masked(d.batch, d.params, d.assign, d.alive, d.bound, M, d.visits, d.rsum,
+                                d.t, d.Ncs, d.mu, d.ucb, d.sel, d.ws, d.ws_bytes)
+        _sync()
+        for k, v in plain.items():
+            np.testing.assert_array_equal(d.host(k).view(np.uint8), v.view(np.uint8), err_msg=k)
+    d.M.fill_(0)
+    kb.kb_ucb_select_masked(d.batch, d.params, d.assign, d.alive, d.bound, d.M, d.visits, d.rsum,
+                            d.t, d.Ncs, d.mu, d.ucb, d.sel, d.ws, d.ws_bytes)
+    _sync()
+    assert (d.host("sel") == -1).all()
