@@ -55,6 +55,9 @@ def main():
     ap.add_argument("--no-step", action="store_true",
                     help="skip the single-Lloyd-step timing (so a kernel trace of this run holds "
                          "only full kb_cluster launches of the fused kernel)")
+    ap.add_argument("--no-loop-steps", action="store_true",
+                    help="skip the timings of the steps outside the round (draw, representatives, "
+                         "paper-form mask, masked selection, statistics update)")
     ap.add_argument("--cpu-sample", type=int, default=0, help="searches in the CPU baseline sample")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -126,6 +129,37 @@ def main():
             modes[name] = round(timed(d.cluster, max(3, reps // 2))[0], 4)
         kb.kb_set_scorer(0)
 
+    # the remaining device-side steps of an iteration of Alg. 1 (not part of the
+    # timed round): in-cluster draw, cluster representatives, the paper-form mask,
+    # selection under it, the draw with the paper's potential, statistics update
+    loop = {}
+    if not args.no_loop_steps:
+        R = 3
+        h, target, theta = synth.signatures(b, R)
+        reward, okv = synth.feedback(b)
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(d.device)
+        dh, dtg, drw, dok = up(h), up(target), up(reward), up(okv)
+        d.round()
+        sp = kb.kb_sample_params(20251118, 1, 1.0)
+        loop["sample"] = timed(lambda: d.sample(20251118, 1, 1.0), reps)[0]
+        loop["cluster_geometry"] = timed(d.cluster_geometry, reps)[0]
+        loop["strategy_mask"] = timed(lambda: kb.kb_strategy_mask(
+            d.batch, R, dh, dtg, d.rep, theta, d.M, d.nvalid), reps)[0]
+        loop["ucb_select_masked"] = timed(lambda: kb.kb_ucb_select_masked(
+            d.batch, d.params, d.assign, None, None, d.M, d.visits, d.rsum, d.t, d.Ncs, d.mu, d.ucb,
+            d.sel, d.ws, d.ws_bytes), reps)[0]
+        loop["sample_signature"] = timed(lambda: kb.kb_sample_signature(
+            d.batch, sp, d.assign, None, R, dh, dtg, theta, d.sel, d.ksel, d.ws, d.ws_bytes), reps)[0]
+        loop["update_stats"] = timed(lambda: kb.kb_update_stats(
+            d.batch, d.params, d.sel, d.ksel, drw, dok, d.visits, d.rsum, d.Ncs, d.mu, d.t), reps)[0]
+        loop = {k: round(v, 4) for k, v in loop.items()}
+        # representatives: every feature row and assignment read once
+        loop["cluster_geometry_GBs"] = round(
+            b.N * (4 * b.D + 4) / (loop["cluster_geometry"] * 1e-3) / 1e9, 1)
+        # the draw reads the 4-byte assignment of every candidate (mask and bound only of
+        # the members of the chosen cluster)
+        loop["sample_GBs"] = round(b.N * 4 / (loop["sample"] * 1e-3) / 1e9, 1)
+
     lloyd_bytes = lloyd_algorithmic_bytes(b, b.iters)
     achieved = lloyd_bytes / (cl_mean * 1e-3) / 1e9
     big = b.Kmax > 64 or b.Nmax > 65536
@@ -155,6 +189,7 @@ def main():
                       "ucb_select": round(uc_mean, 4),
                       "one_lloyd_step": None if args.no_step else round(step_mean, 4)},
         "cluster_ms_other_modes": modes,
+        "iteration_steps_ms": loop,
         "lloyd_step_GBs": None if args.no_step else round(
             lloyd_algorithmic_bytes(b, 1) / (step_mean * 1e-3) / 1e9, 1),
         "round_streaming_GBs": round(

@@ -63,6 +63,35 @@ def _full_round_vs_oracle(kb, b, name):
           f"excluded as near-tie (of which {same} match anyway), {int((ora.near != 0).sum())} "
           f"selections excluded as near-tie", flush=True)
     assert clean.mean() > 0.9
+    _loop_steps_vs_oracle(kb, b, d, name, ora, ok)
+
+
+def _loop_steps_vs_oracle(kb, b, d, name, ora=None, ok=None):
+    """The in-cluster draw and the cluster representatives at full size, on the
+    state the round just left on the device."""
+    import torch
+    d.sample(20251118, 7, 1.0)
+    d.cluster_geometry()
+    _sync()
+    a, cent = d.host("assign"), d.host("cent")
+    alive, bound, sel = d.host("alive"), d.host("bound"), d.host("sel")
+    # the draw, given the device's own selection (exact inputs, index output)
+    want = oracle.sample(b.seg_off, a, alive, bound, b.incumbent, sel, 20251118, 7, 1.0)
+    fine = want.near == 0
+    np.testing.assert_array_equal(d.host("ksel")[fine], want.ksel[fine], err_msg=name + " ksel")
+    assert fine.mean() > 0.999
+    if ora is not None:
+        # and end to end against the oracle's own round where nothing was a near-tie
+        w2 = oracle.sample(b.seg_off, ora.assign, ora.alive, ora.bound, b.incumbent, ora.sel,
+                           20251118, 7, 1.0)
+        e2e = ok & (w2.near == 0)
+        np.testing.assert_array_equal(d.host("ksel")[e2e], w2.ksel[e2e], err_msg=name + " ksel e2e")
+    # representatives and radii of the final clustering: exact on every cluster
+    g = oracle.cluster_geometry(b.seg_off, b.koff, b.X, cent, a)
+    np.testing.assert_array_equal(d.host("rep"), g.rep, err_msg=name + " rep")
+    np.testing.assert_array_equal(d.host("radius"), g.radius.astype(np.float32), err_msg=name + " radius")
+    print(f"[{name}] draw compared on {int(fine.sum())} of {b.G} searches, representatives and "
+          f"radii exact on {b.Ksum} clusters", flush=True)
 
 
 def test_config3_full(kb):
@@ -126,3 +155,4 @@ def test_config4_full(kb):
     _sync()
     for k, v in first.items():
         np.testing.assert_array_equal(d.host(k).view(np.uint8), v.view(np.uint8), err_msg=k)
+    _loop_steps_vs_oracle(kb, b, d, "config4")
