@@ -225,6 +225,40 @@ __global__ void __launch_bounds__(kThreads) big_renew(BigArgs a) {
 }
 
 // One workgroup per chunk of kTilesPerChunk tiles of one search.
+//
+// The centroid operands stay in registers for the whole chunk: the centroids are
+// cut into groups of 64 (two matrix-core tiles) and every wave owns one group -
+// its bf16 (hi, mid) operands (16 * DS VGPRs) and, as the accumulator input of
+// the first product, its |c|^2.  The candidate tiles are what moves: four tiles
+// at a time are copied from global memory into LDS (the copy of the next four is
+// requested before the current four are scored) and every wave reads each tile's
+// operands from there, 2 * DS 16-byte LDS reads per 6 * DS matrix instructions.
+// With fewer than four centroid groups the waves that share a group split the
+// tiles among themselves.
+//
+// Best and second best of a lane's 32 scores are tracked with two vector
+// instructions per score (median-of-three, minimum) on scores whose 5 lowest
+// mantissa bits have been replaced by the score's position; the position of the
+// minimum is read back from those bits.  The replacement moves a score by less
+// than 2^-18 of its magnitude, which the error bound below accounts for.  The
+// per-group results of a tile meet in LDS and one wave per tile merges them,
+// decides whether the nearest centroid is certain, and writes the proposal.
+constexpr int kGroupTiles = 4;     // candidate tiles staged in LDS at a time
+
+// Plain v_min_f32 / v_max_f32.  (fminf would first quiet a signalling NaN with one
+// more instruction per operand, because the compiler cannot see that scores
+// with rewritten low bits are ordinary numbers.)
+__device__ __forceinline__ float vmin(float x, float y) {
+    float r;
+    asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
+    return r;
+}
+__device__ __forceinline__ float vmax(float x, float y) {
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
+    return r;
+}
+
 template <int DS>
 __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -243,147 +277,210 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
     const int64_t tb = a.tile_off[g];
     if (t0 >= t1 || tb + ntiles > a.max_tiles) return;
     const int mtiles = (K + 31) >> 5;
-    // stage this search's centroid operands and padded |c|^2 in LDS
-    bf16x8* aop = reinterpret_cast<bf16x8*>(smem);
-    float* cn = reinterpret_cast<float*>(smem + (size_t)(a.Kpad / 32) * DS * 2 * 64 * 16);
-    // doubtful candidates of this chunk, handed to the global list in one piece
-    int* lflag = reinterpret_cast<int*>(cn + a.Kpad);       // [kTilesPerChunk * 32]
-    int* lcount = lflag + kTilesPerChunk * 32;               // [2]: count, base in the global list
+    const int ngroups = (mtiles + 1) >> 1;          // centroid groups of 64: 1..4
+    const int nx = kWaves / ngroups;                // waves per centroid group
+    const int cgroup = wid % ngroups, xsub = wid / ngroups;
+    const bool active = xsub < nx;                  // with three groups the fourth wave only copies
+    const bool have1 = 2 * cgroup + 1 < mtiles;     // the group's second tile of 32 centroids exists
+
+    constexpr int kTileUnits = DS * 2 * 64;         // 16-byte units of one candidate tile
+    bf16x8* stage = reinterpret_cast<bf16x8*>(smem);                                  // [kGroupTiles][kTileUnits]
+    // per (centroid group, tile, lane): best and second best of the lane's 32 scores
+    float2* res = reinterpret_cast<float2*>(smem + (size_t)kGroupTiles * kTileUnits * 16);   // [4][kGroupTiles][64]
+    int* lflag = reinterpret_cast<int*>(res + 4 * kGroupTiles * 64);   // [kTilesPerChunk * 32] doubtful candidates of this chunk
+    int* lcount = lflag + kTilesPerChunk * 32;      // [2]: count, base in the global list
     if (tid == 0) lcount[0] = 0;
+
+    // this wave's centroid operands and |c|^2, resident for the whole chunk
+    bf16x8 Ah[2][DS], Am[2][DS];
+    f32x16 cnr[2];
     {
-        const bf16x8* src = a.aop + (size_t)g * (a.Kpad / 32) * (DS * 2 * 64);
-        for (int i = tid; i < mtiles * DS * 2 * 64; i += kThreads) aop[i] = src[i];
-        for (int i = tid; i < mtiles * 32; i += kThreads) cn[i] = a.cnpad[(size_t)g * a.Kpad + i];
-    }
-    __syncthreads();
-
-    const float cnmax = __uint_as_float(a.cnmax_bits[(a.it & 1) * a.G + g]);
-    const float kappa = mfma_kappa(DS);
-    const bf16x8* sp = a.split + (size_t)tb * (DS * 2 * 64);
-
-    auto load_tile = [&](int tile, bf16x8 (&bh)[DS], bf16x8 (&bm)[DS], float& xnv, int& oldv) {
-        const bf16x8* tp = sp + (size_t)tile * (DS * 2 * 64) + lane;
+        const bf16x8* src = a.aop + (size_t)g * (a.Kpad / 32) * kTileUnits;
+        const float* cnp = a.cnpad + (size_t)g * a.Kpad;
 #pragma unroll
-        for (int s = 0; s < DS; ++s) {
-            bh[s] = tp[(2 * s) * 64];
-            bm[s] = tp[(2 * s + 1) * 64];
-        }
-        // no branch around these loads: their number in flight is then known at
-        // compile time and waiting for one tile does not wait for the next one too
-        const int p = tile * 32 + m;
-        xnv = a.xn[(size_t)n0 + (p < ng ? p : ng - 1)];
-        oldv = -1;
-    };
-
-    bf16x8 Bh[DS], Bm[DS];
-    float xn = 0.f;
-    int old = -1;
-    load_tile(t0 + wid < t1 ? t0 + wid : t1 - 1, Bh, Bm, xn, old);
-    for (int tile = t0 + wid; tile < t1; tile += kWaves) {
-        const int p = tile * 32 + m;
-        const bool valid = p < ng;
-        bf16x8 Bh2[DS], Bm2[DS];
-        float xn2 = 0.f;
-        int old2 = -1;
-        const bool more = tile + kWaves < t1;
-        load_tile(more ? tile + kWaves : tile, Bh2, Bm2, xn2, old2);
-        // running (best, second, row) over the centroid tiles, two tiles at a time
-        float best = kBig * 4.f, second = kBig * 4.f;
-        int bi = 0;
-        for (int mt = 0; mt < mtiles; mt += 2) {
-            const bool two = mt + 1 < mtiles;
-            f32x16 acc[2];
+        for (int t = 0; t < 2; ++t) {
+            const int mt = (t == 0 || have1) ? 2 * cgroup + t : 2 * cgroup;
+#pragma unroll
+            for (int s = 0; s < DS; ++s) {
+                Ah[t][s] = src[((mt * DS + s) * 2 + 0) * 64 + lane];
+                Am[t][s] = src[((mt * DS + s) * 2 + 1) * 64 + lane];
+            }
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
-                const float4 c4 = *reinterpret_cast<const float4*>(cn + mt * 32 + 8 * g4 + 4 * h);
-                acc[0][4 * g4 + 0] = c4.x; acc[0][4 * g4 + 1] = c4.y;
-                acc[0][4 * g4 + 2] = c4.z; acc[0][4 * g4 + 3] = c4.w;
+                const float4 c4 = *reinterpret_cast<const float4*>(cnp + mt * 32 + 8 * g4 + 4 * h);
+                cnr[t][4 * g4 + 0] = c4.x; cnr[t][4 * g4 + 1] = c4.y;
+                cnr[t][4 * g4 + 2] = c4.z; cnr[t][4 * g4 + 3] = c4.w;
             }
-            float cb[4], cs[4];
-            int ci[4];
+        }
+    }
+    const float cnmax = __uint_as_float(a.cnmax_bits[(a.it & 1) * a.G + g]);
+    // error bound of a score: the matrix-core products, plus the position bits
+    // (|score| <= 2 (|x|^2 + max |c|^2), moved by less than 2^-18 of itself)
+    const float kappa = mfma_kappa(DS) + 7.62939453125e-06f;
+    const bf16x8* sp = a.split + (size_t)tb * kTileUnits;
+
+    // copy of a group of tiles: global -> registers (early) -> LDS (when the
+    // previous group has been scored)
+    constexpr int kPre = kGroupTiles * kTileUnits / kThreads;     // = 2 * DS units per thread
+    bf16x8 pre[kPre];
+    auto prefetch = [&](int gt0) {
+        const int cnt = t1 - gt0 < kGroupTiles ? t1 - gt0 : kGroupTiles;
+        const bf16x8* src = sp + (size_t)gt0 * kTileUnits;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) { cb[q] = kBig * 4.f; cs[q] = kBig * 4.f; ci[q] = 0; }
-            if (two) {
+        for (int i = 0; i < kPre; ++i) {
+            const int u = tid + i * kThreads;
+            // clamped, not skipped: the number of loads in flight is then fixed
+            pre[i] = src[u < cnt * kTileUnits ? u : 0];
+        }
+    };
+    prefetch(t0);
+    for (int gt0 = t0; gt0 < t1; gt0 += kGroupTiles) {
+        const int cnt = t1 - gt0 < kGroupTiles ? t1 - gt0 : kGroupTiles;
 #pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    const float4 c4 = *reinterpret_cast<const float4*>(cn + (mt + 1) * 32 + 8 * g4 + 4 * h);
-                    acc[1][4 * g4 + 0] = c4.x; acc[1][4 * g4 + 1] = c4.y;
-                    acc[1][4 * g4 + 2] = c4.z; acc[1][4 * g4 + 3] = c4.w;
+        for (int i = 0; i < kPre; ++i) stage[tid + i * kThreads] = pre[i];
+        __syncthreads();
+        if (gt0 + kGroupTiles < t1) prefetch(gt0 + kGroupTiles);
+
+        // |x|^2 of the tile this wave closes below, requested before the scoring
+        float xn_close = 0.f;
+        {
+            const int p = (gt0 + wid) * 32 + m;
+            if (wid < cnt && p < ng) xn_close = a.xn[(size_t)n0 + p];
+        }
+
+        // best and second best of the 16 scores of one accumulator, position
+        // (offset `base`) in the 5 lowest bits; three vector instructions per score
+        auto argmin16 = [&](const f32x16& acc, unsigned base, float& cb, float& cs) {
+            cb = kBig * 8.f; cs = kBig * 8.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float v = __uint_as_float((__float_as_uint(acc[r]) & 0xffffffe0u) | (base + (unsigned)r));
+                cs = __builtin_amdgcn_fmed3f(cb, cs, v);
+                cb = vmin(cb, v);
+            }
+        };
+        // union of the two accumulators' results: this lane's part of tile tt
+        auto close_tile = [&](int tt, float cb0, float cs0, float cb1, float cs1) {
+            const float lo = vmin(cb0, cb1);
+            const float hi = vmax(cb0, cb1);
+            const float second = vmin(vmin(cs0, cs1), hi);
+            res[(cgroup * kGroupTiles + tt) * 64 + lane] = make_float2(lo, second);
+        };
+
+        if (active && have1) {
+            // Two accumulators, one per tile of 32 centroids, used in turn: while the
+            // matrix cores fill one, the vector unit takes the minimum of the other
+            // (the previous half of the work), so neither waits for the other.
+            bf16x8 Bh[DS], Bm[DS];
+            {
+                const bf16x8* bt = stage + (xsub < cnt ? xsub : 0) * kTileUnits + lane;
+#pragma unroll
+                for (int s = 0; s < DS; ++s) { Bh[s] = bt[(2 * s) * 64]; Bm[s] = bt[(2 * s + 1) * 64]; }
+            }
+            f32x16 acc0, acc1;
+            float cb0, cs0, cb1, cs1;
+            auto chain0 = [&]() {
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[0][0], Bh[0], cnr[0], 0, 0, 0);
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[0][0], Bm[0], acc0, 0, 0, 0);
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Am[0][0], Bh[0], acc0, 0, 0, 0);
+#pragma unroll
+                for (int s = 1; s < DS; ++s) {
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[0][s], Bh[s], acc0, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[0][s], Bm[s], acc0, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Am[0][s], Bh[s], acc0, 0, 0, 0);
                 }
+            };
+            if (xsub < cnt) {
+                chain0();
+                for (int tt = xsub;;) {
+                    // second tile of centroids of candidate tile tt, while the vector
+                    // unit takes the minimum of the first; the candidate operands of a
+                    // step are replaced by the next tile's as soon as they are spent
+                    const int nt = tt + nx;
+                    const bf16x8* bt = stage + (nt < cnt ? nt : tt) * kTileUnits + lane;
+#pragma unroll
+                    for (int s = 0; s < DS; ++s) {
+                        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[1][s], Bh[s], s == 0 ? cnr[1] : acc1, 0, 0, 0);
+                        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[1][s], Bm[s], acc1, 0, 0, 0);
+                        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Am[1][s], Bh[s], acc1, 0, 0, 0);
+                        Bh[s] = bt[(2 * s) * 64];
+                        Bm[s] = bt[(2 * s + 1) * 64];
+                    }
+                    argmin16(acc0, 0u, cb0, cs0);
+#pragma unroll
+                    for (int r = 0; r < DS * 3; ++r) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 5, 1);
+                    }
+                    if (nt >= cnt) {
+                        argmin16(acc1, 16u, cb1, cs1);
+                        close_tile(tt, cb0, cs0, cb1, cs1);
+                        break;
+                    }
+                    // first tile of centroids of the next candidate tile, while the
+                    // vector unit finishes this one
+                    chain0();
+                    argmin16(acc1, 16u, cb1, cs1);
+                    close_tile(tt, cb0, cs0, cb1, cs1);
+#pragma unroll
+                    for (int r = 0; r < DS * 3; ++r) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+                    }
+                    tt = nt;
+                }
+            }
+        } else if (active) {
+            // one tile of 32 centroids in this group: the third product goes to a
+            // second accumulator so that two chains are in flight
+            for (int tt = xsub; tt < cnt; tt += nx) {
+                const bf16x8* bt = stage + tt * kTileUnits + lane;
+                f32x16 acc0 = cnr[0], acc1;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc1[r] = 0.f;
 #pragma unroll
                 for (int s = 0; s < DS; ++s) {
-                    const bf16x8 a0h = aop[((mt * DS + s) * 2 + 0) * 64 + lane];
-                    const bf16x8 a0m = aop[((mt * DS + s) * 2 + 1) * 64 + lane];
-                    const bf16x8 a1h = aop[(((mt + 1) * DS + s) * 2 + 0) * 64 + lane];
-                    const bf16x8 a1m = aop[(((mt + 1) * DS + s) * 2 + 1) * 64 + lane];
-                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bh[s], acc[0], 0, 0, 0);
-                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, Bh[s], acc[1], 0, 0, 0);
-                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bm[s], acc[0], 0, 0, 0);
-                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, Bm[s], acc[1], 0, 0, 0);
-                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0m, Bh[s], acc[0], 0, 0, 0);
-                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1m, Bh[s], acc[1], 0, 0, 0);
+                    const bf16x8 Bh = bt[(2 * s) * 64], Bm = bt[(2 * s + 1) * 64];
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[0][s], Bh, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[0][s], Bm, acc1, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Am[0][s], Bh, acc0, 0, 0, 0);
                 }
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
+                for (int r = 0; r < 16; ++r) acc0[r] += acc1[r];
+                float cb0, cs0;
+                argmin16(acc0, 0u, cb0, cs0);
+                close_tile(tt, cb0, cs0, kBig * 8.f, kBig * 8.f);
+            }
+        }
+        __syncthreads();
+        // wave w closes tile w of the group: merge the lanes' parts over the centroid
+        // groups and the two half-waves, read the position of the minimum back from
+        // its lowest bits, decide
+        if (wid < cnt && h == 0) {
+            const int tile = gt0 + wid;
+            const int p = tile * 32 + m;
+            if (p < ng) {
+                float best = kBig * 16.f, second = kBig * 16.f;
+                int slot = 0;           // 2 * centroid group + half-wave of the best so far
+                for (int cg = 0; cg < ngroups; ++cg) {
 #pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        const int q = 2 * t + (r >> 3);
-                        const float v = acc[t][r];
-                        const bool lt = v < cb[q];
-                        cs[q] = __builtin_amdgcn_fmed3f(cb[q], cs[q], v);
-                        cb[q] = lt ? v : cb[q];
-                        ci[q] = lt ? (t * 32 + 8 * (r >> 2) + (r & 3)) : ci[q];
+                    for (int hh = 0; hh < 2; ++hh) {
+                        const float2 r = res[(cg * kGroupTiles + wid) * 64 + hh * 32 + m];
+                        merge_best(best, second, slot, r.x, r.y, 2 * cg + hh);
                     }
                 }
-            } else {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[1][r] = 0.f;
-#pragma unroll
-                for (int s = 0; s < DS; ++s) {
-                    const bf16x8 a0h = aop[((mt * DS + s) * 2 + 0) * 64 + lane];
-                    const bf16x8 a0m = aop[((mt * DS + s) * 2 + 1) * 64 + lane];
-                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bh[s], acc[0], 0, 0, 0);
-                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bm[s], acc[1], 0, 0, 0);
-                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0m, Bh[s], acc[0], 0, 0, 0);
-                }
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int q = r >> 2;
-                    const float v = acc[0][r] + acc[1][r];
-                    const bool lt = v < cb[q];
-                    cs[q] = __builtin_amdgcn_fmed3f(cb[q], cs[q], v);
-                    cb[q] = lt ? v : cb[q];
-                    ci[q] = lt ? (8 * (r >> 2) + (r & 3)) : ci[q];
-                }
+                const int code = (int)(__float_as_uint(best) & 31u);
+                const int bi = (slot >> 1) * 64 + (code >> 4) * 32 + 8 * ((code & 15) >> 2) + (code & 3) +
+                               4 * (slot & 1);
+                const float E = kappa * (xn_close + cnmax);
+                // a best score next to zero may have lost its position bits to a
+                // flush of subnormal numbers: leave that candidate to the exact pass
+                const bool certain = (K == 1) ||
+                                     (((second - best) > 2.f * E) && fabsf(best) > 1.0e-30f && bi < K);
+                a.next[(size_t)n0 + p] = bi < K ? bi : 0;
+                if (!certain) lflag[atomicAdd(&lcount[0], 1)] = n0 + p;   // at most one entry per candidate of the chunk
             }
-            merge_best(cb[0], cs[0], ci[0], cb[1], cs[1], ci[1]);
-            merge_best(cb[2], cs[2], ci[2], cb[3], cs[3], ci[3]);
-            merge_best(cb[0], cs[0], ci[0], cb[2], cs[2], ci[2]);
-            merge_best(best, second, bi, cb[0], cs[0], ci[0] + mt * 32);
         }
-        bi += 4 * h;
-        {
-            const auto rb = __builtin_amdgcn_permlane32_swap(__float_as_uint(best), __float_as_uint(best), false, false);
-            const auto rs = __builtin_amdgcn_permlane32_swap(__float_as_uint(second), __float_as_uint(second), false, false);
-            const auto ri = __builtin_amdgcn_permlane32_swap((unsigned)bi, (unsigned)bi, false, false);
-            float b0 = __uint_as_float(rb[0]), s0 = __uint_as_float(rs[0]);
-            int i0 = (int)ri[0];
-            merge_best(b0, s0, i0, __uint_as_float(rb[1]), __uint_as_float(rs[1]), (int)ri[1]);
-            best = b0; second = s0; bi = i0;
-        }
-        bi = bi < K ? bi : 0;
-        const float E = kappa * (xn + cnmax);
-        const bool certain = (K == 1) || ((second - best) > 2.f * E);
-        // the proposal of every candidate goes to `prop`; the doubtful ones are
-        // listed for the exact pass, which overwrites their proposal
-        if (valid && h == 0) {
-            a.next[(size_t)n0 + p] = bi;
-            if (!certain) lflag[atomicAdd(&lcount[0], 1)] = n0 + p;   // at most one entry per candidate of the chunk
-        }
-#pragma unroll
-        for (int s = 0; s < DS; ++s) { Bh[s] = Bh2[s]; Bm[s] = Bm2[s]; }
-        xn = xn2;
-        old = old2;
     }
     __syncthreads();
     const int nl = lcount[0];
@@ -417,17 +514,29 @@ __global__ void __launch_bounds__(kThreads) big_exact(BigArgs a) {
     const int D4 = (D + 3) & ~3;
     float c[KB_MAX_D];          // this lane's centroid, kept while the search stays the same
     int g_held = -1;
+    // two requests ahead: the index of the candidate after next, and the row of the
+    // next one (whose index has arrived by then)
+    auto index_at = [&](int64_t i) {
+        const int v = i < n ? a.flist[i] : -1;
+        return (v >= 0 && v < a.N) ? v : -1;
+    };
+    auto row_at = [&](int pgv) { return (pgv >= 0 && lane < D) ? a.X[(size_t)pgv * D + lane] : 0.f; };
+    int pg_cur = index_at(blockIdx.x);
+    int pg_nxt = index_at((int64_t)blockIdx.x + gridDim.x);
+    float xv_cur = row_at(pg_cur);
     for (int64_t i = blockIdx.x; i < n; i += gridDim.x) {
         // everything up to the barriers is uniform over the workgroup
-        const int pg = a.flist[i];
-        if (pg < 0 || pg >= a.N) continue;
+        const int pg = pg_cur;
+        const float xv = xv_cur;
+        pg_cur = pg_nxt;
+        pg_nxt = index_at(i + 2 * (int64_t)gridDim.x);
+        xv_cur = row_at(pg_cur);
+        if (pg < 0) continue;
         const int g = upper_search(a.seg_off, a.G, pg);
         int n0, ng, k0, K;
         search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
         if (K <= 0) continue;
         if (K > a.Kpad) K = a.Kpad;
-        const float* xr = a.X + (size_t)pg * D;
-        const float xv = lane < D ? xr[lane] : 0.f;
         const int j = tid;                      // this lane's centroid
         const bool group = wid * kWave < K;     // uniform over the wave
         if (g != g_held) {
@@ -750,7 +859,7 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
     const unsigned tile_blocks = (unsigned)((c.max_tiles + kWaves - 1) / kWaves);
     const unsigned row_blocks = (unsigned)(((size_t)b.G * w.kpad + kWaves - 1) / kWaves);
     const unsigned chunk_blocks = (unsigned)w.max_chunks;
-    const size_t lds = (size_t)(w.kpad / 32) * ds * 2 * 64 * 16 + (size_t)w.kpad * 4 +
+    const size_t lds = (size_t)kGroupTiles * ds * 2 * 64 * 16 + (size_t)4 * kGroupTiles * 64 * 8 +
                        (size_t)kTilesPerChunk * 32 * 4 + 16;
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     const dim3 upd_grid((unsigned)((b.N + kUpdateRange - 1) / kUpdateRange),
