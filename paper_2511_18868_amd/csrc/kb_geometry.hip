@@ -12,7 +12,7 @@
 //              intersect it.  Per search piece the centroids are staged in LDS;
 //              tiles of 256 rows are fetched with coalesced 16-byte loads (the
 //              next tile is requested before the current one is worked on),
-//              transposed through LDS (row stride D+1 words: conflict-free) so
+//              transposed through LDS (padded row stride: conflict-free) so
 //              that each thread owns one candidate, and the distances are reduced
 //              per cluster with 64-bit integer LDS atomics on their bit patterns
 //              (non-negative doubles order like unsigned integers), then merged
@@ -55,11 +55,14 @@ template <int VEC>
 __global__ void __launch_bounds__(kThreads) geo_dist(GeoArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
-    const int D = a.D, DP = D + 1;
+    // row stride of the transposed tile: D + 4 words keeps 16-byte pieces aligned and
+    // spreads consecutive rows over the banks (conflict-free 16-byte reads whenever
+    // D/4 is even); D + 1 for the scalar path
+    const int D = a.D, DP = VEC == 4 ? D + 4 : D + 1;
     unsigned long long* lmin = reinterpret_cast<unsigned long long*>(smem);          // [Kmax]
     unsigned long long* lmax = lmin + a.Kmax;                                         // [Kmax]
     float* lc = reinterpret_cast<float*>(lmax + a.Kmax);                              // [Kmax * D]
-    float* lx = lc + (size_t)a.Kmax * D;                                              // [256 * (D+1)]
+    float* lx = lc + (size_t)a.Kmax * D;                                              // [256 * DP]
 
     const int64_t r0 = (int64_t)blockIdx.x * kGeoRange;
     if (r0 >= a.N) return;
@@ -132,8 +135,11 @@ __global__ void __launch_bounds__(kThreads) geo_dist(GeoArgs a) {
                     const int idx = tid + i * kThreads;
                     if (i < npieces && idx < total) {
                         float* dst = lx + row * DP + col;
-#pragma unroll
-                        for (int e = 0; e < VEC; ++e) dst[e] = xr[i][e];
+                        if constexpr (VEC == 4) {
+                            *reinterpret_cast<float4*>(dst) = make_float4(xr[i][0], xr[i][1], xr[i][2], xr[i][3]);
+                        } else {
+                            dst[0] = xr[i][0];
+                        }
                     }
                     row += qd; col += rd;
                     if (col >= D) { col -= D; row += 1; }
@@ -148,9 +154,27 @@ __global__ void __launch_bounds__(kThreads) geo_dist(GeoArgs a) {
                 const float* xrow = lx + tid * DP;
                 const float* crow = lc + (size_t)j * D;
                 double acc = 0.0;
-                for (int d = 0; d < D; ++d) {
-                    const double diff = __dsub_rn((double)xrow[d], (double)crow[d]);
-                    acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                if constexpr (VEC == 4) {
+                    // 16-byte LDS reads, eight features in flight; the sum itself stays
+                    // in index order
+#pragma unroll 2
+                    for (int d = 0; d < D; d += 4) {
+                        const float4 xv = *reinterpret_cast<const float4*>(xrow + d);
+                        const float4 cv = *reinterpret_cast<const float4*>(crow + d);
+                        double diff = __dsub_rn((double)xv.x, (double)cv.x);
+                        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                        diff = __dsub_rn((double)xv.y, (double)cv.y);
+                        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                        diff = __dsub_rn((double)xv.z, (double)cv.z);
+                        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                        diff = __dsub_rn((double)xv.w, (double)cv.w);
+                        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                    }
+                } else {
+                    for (int d = 0; d < D; ++d) {
+                        const double diff = __dsub_rn((double)xrow[d], (double)crow[d]);
+                        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                    }
                 }
                 a.d2[p] = acc;
                 const unsigned long long bits = (unsigned long long)__double_as_longlong(acc);
@@ -206,7 +230,7 @@ __global__ void __launch_bounds__(kThreads) geo_final(GeoArgs a) {
 }  // namespace
 
 size_t geometry_lds_bytes(int Kmax, int D) {
-    return (size_t)16 * Kmax + (size_t)4 * Kmax * D + (size_t)4 * kThreads * (D + 1);
+    return (size_t)16 * Kmax + (size_t)4 * Kmax * D + (size_t)4 * kThreads * (D + 4);
 }
 
 hipError_t launch_geometry(const kb_batch& b, const GeoCall& c, hipStream_t st) {
