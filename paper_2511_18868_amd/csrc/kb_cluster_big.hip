@@ -58,8 +58,9 @@ struct BigArgs {
     int* dirty;             // [Ksum]
     unsigned* amax_bits;    // [G]
     unsigned* cnmax_bits;   // [2][G]
-    int* nflag;             // [1]
+    int* nflag;             // [2]: candidates listed for the full exact pass, records for the short one
     int32_t* flist;         // [N] global candidate indices
+    int4* few;              // [N] (candidate, count, contenders 0..3, contenders 4..7 as bytes)
     double* partJ;          // [chunks]
 };
 
@@ -105,7 +106,7 @@ __global__ void __launch_bounds__(kThreads) big_init(BigArgs a) {
         a.cnmax_bits[g] = 0u;
         a.cnmax_bits[a.G + g] = 0u;
     }
-    if (t0 == 0) *a.nflag = 0;
+    if (t0 == 0) { a.nflag[0] = 0; a.nflag[1] = 0; }
 }
 
 template <int DS>
@@ -220,7 +221,7 @@ __global__ void __launch_bounds__(kThreads) big_renew(BigArgs a) {
         a.dirty[row] = 0;
         atomicMax(&a.cnmax_bits[(a.it & 1) * a.G + g], __float_as_uint(f));
         if (j == 0) a.cnmax_bits[((a.it + 1) & 1) * a.G + g] = 0u;
-        if (r == 0) *a.nflag = 0;
+        if (r == 0) { a.nflag[0] = 0; a.nflag[1] = 0; }
     }
 }
 
@@ -287,9 +288,13 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
     bf16x8* stage = reinterpret_cast<bf16x8*>(smem);                                  // [kGroupTiles][kTileUnits]
     // per (centroid group, tile, lane): best and second best of the lane's 32 scores
     float2* res = reinterpret_cast<float2*>(smem + (size_t)kGroupTiles * kTileUnits * 16);   // [4][kGroupTiles][64]
-    int* lflag = reinterpret_cast<int*>(res + 4 * kGroupTiles * 64);   // [kTilesPerChunk * 32] doubtful candidates of this chunk
-    int* lcount = lflag + kTilesPerChunk * 32;      // [2]: count, base in the global list
-    if (tid == 0) lcount[0] = 0;
+    // doubtful candidates of this chunk: those with at most one possible nearest
+    // centroid per lane part go to `lfew` with the list of those centroids, the
+    // others to `lflag` for the full exact pass
+    int4* lfew = reinterpret_cast<int4*>(res + 4 * kGroupTiles * 64);   // [kTilesPerChunk * 32]
+    int* lflag = reinterpret_cast<int*>(lfew + kTilesPerChunk * 32);    // [kTilesPerChunk * 32]
+    int* lcount = lflag + kTilesPerChunk * 32;      // [4]: counts, bases in the global lists
+    if (tid < 2) lcount[tid] = 0;
 
     // this wave's centroid operands and |c|^2, resident for the whole chunk
     bf16x8 Ah[2][DS], Am[2][DS];
@@ -456,12 +461,13 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
         // wave w closes tile w of the group: merge the lanes' parts over the centroid
         // groups and the two half-waves, read the position of the minimum back from
         // its lowest bits, decide
-        if (wid < cnt && h == 0) {
+        if (wid < cnt) {
             const int tile = gt0 + wid;
             const int p = tile * 32 + m;
-            if (p < ng) {
-                float best = kBig * 16.f, second = kBig * 16.f;
-                int slot = 0;           // 2 * centroid group + half-wave of the best so far
+            const bool mine = h == 0 && p < ng;
+            float best = kBig * 16.f, second = kBig * 16.f;
+            int slot = 0;           // 2 * centroid group + half-wave of the best so far
+            if (mine) {
                 for (int cg = 0; cg < ngroups; ++cg) {
 #pragma unroll
                     for (int hh = 0; hh < 2; ++hh) {
@@ -469,27 +475,121 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
                         merge_best(best, second, slot, r.x, r.y, 2 * cg + hh);
                     }
                 }
-                const int code = (int)(__float_as_uint(best) & 31u);
-                const int bi = (slot >> 1) * 64 + (code >> 4) * 32 + 8 * ((code & 15) >> 2) + (code & 3) +
-                               4 * (slot & 1);
-                const float E = kappa * (xn_close + cnmax);
-                // a best score next to zero may have lost its position bits to a
-                // flush of subnormal numbers: leave that candidate to the exact pass
-                const bool certain = (K == 1) ||
-                                     (((second - best) > 2.f * E) && fabsf(best) > 1.0e-30f && bi < K);
-                a.next[(size_t)n0 + p] = bi < K ? bi : 0;
-                if (!certain) lflag[atomicAdd(&lcount[0], 1)] = n0 + p;   // at most one entry per candidate of the chunk
+            }
+            const int code = (int)(__float_as_uint(best) & 31u);
+            const int bi = (slot >> 1) * 64 + (code >> 4) * 32 + 8 * ((code & 15) >> 2) + (code & 3) +
+                           4 * (slot & 1);
+            const float E = kappa * (xn_close + cnmax);
+            // a best score next to zero may have lost its position bits to a flush of
+            // subnormal numbers: leave that candidate to the full exact pass
+            const bool sane = fabsf(best) > 1.0e-30f && bi < K;
+            const bool certain = (K == 1) || (((second - best) > 2.f * E) && sane);
+            if (mine) a.next[(size_t)n0 + p] = bi < K ? bi : 0;
+            // Doubtful candidates, one at a time with the whole wave.  Every centroid
+            // that can be the true nearest one has a score within 2E of the best.  Lane
+            // q looks at lane part q of the candidate: the part contributes its own
+            // best if that is within the threshold; if its second best is too, the
+            // part holds more such centroids than it can name and the candidate goes
+            // to the full exact pass.  Otherwise the named centroids (at most eight)
+            // are recorded for the short one.
+            const float thr = best + 2.f * E;
+            unsigned long long todo = __ballot(mine && !certain);
+            while (todo) {
+                const int bl = __ffsll((long long)todo) - 1;
+                todo &= todo - 1;
+                const float thr_b = __shfl(thr, bl);
+                const int sane_b = __shfl((int)sane, bl);
+                const int q = lane;
+                bool is = false, over = false;
+                int idx = 0;
+                if (q < 2 * ngroups) {
+                    const float2 r = res[((q >> 1) * kGroupTiles + wid) * 64 + (q & 1) * 32 + bl];
+                    const int cd = (int)(__float_as_uint(r.x) & 31u);
+                    idx = (q >> 1) * 64 + (cd >> 4) * 32 + 8 * ((cd & 15) >> 2) + (cd & 3) + 4 * (q & 1);
+                    is = r.x <= thr_b;
+                    over = r.y <= thr_b || (is && idx >= K);
+                }
+                const unsigned long long cm = __ballot(is), om = __ballot(over);
+                const int pcand = n0 + tile * 32 + bl;
+                // at most one entry per candidate of the chunk in either list
+                if (sane_b && om == 0ull && cm != 0ull) {
+                    int e = 0;
+                    if (lane == 0) e = atomicAdd(&lcount[1], 1);
+                    e = __shfl(e, 0);
+                    if (is) {
+                        const int rank = __popcll(cm & ((1ull << q) - 1ull));
+                        reinterpret_cast<unsigned char*>(lfew)[e * 16 + 8 + rank] = (unsigned char)idx;
+                    }
+                    if (lane == 0) {
+                        int* hdr = reinterpret_cast<int*>(lfew + e);
+                        hdr[0] = pcand;
+                        hdr[1] = __popcll(cm);
+                    }
+                } else if (lane == 0) {
+                    lflag[atomicAdd(&lcount[0], 1)] = pcand;
+                }
             }
         }
     }
     __syncthreads();
-    const int nl = lcount[0];
-    if (nl > 0) {
-        if (tid == 0) lcount[1] = atomicAdd(a.nflag, nl);
+    const int nl = lcount[0], nf = lcount[1];
+    if (nl > 0 || nf > 0) {
+        if (tid == 0 && nl > 0) lcount[2] = atomicAdd(&a.nflag[0], nl);
+        if (tid == 1 && nf > 0) lcount[3] = atomicAdd(&a.nflag[1], nf);
         __syncthreads();
-        const int64_t pos0 = lcount[1];
+        const int64_t pos0 = lcount[2], pos1 = lcount[3];
         for (int i = tid; i < nl; i += kThreads)
             if (pos0 + i < a.N) a.flist[pos0 + i] = lflag[i];
+        for (int i = tid; i < nf; i += kThreads)
+            if (pos1 + i < a.N) a.few[pos1 + i] = lfew[i];
+    }
+}
+
+// Short exact pass: a doubtful candidate whose possible nearest centroids are
+// all named (at most eight) needs the exact distance to those only.  Eight
+// threads per candidate, one per named centroid; each forms its squared distance
+// exactly as the plain definition does - fp64, direct differences, summed over the
+// features in index order with separate multiply and add - and the eight reduce
+// to the minimum, lowest centroid index on ties.
+__global__ void __launch_bounds__(kThreads) big_exact_few(BigArgs a) {
+    int64_t n = a.nflag[1];
+    if (n > a.N) n = a.N;
+    const int D = a.D;
+    const int64_t stride = (int64_t)gridDim.x * (kThreads / 8);
+    const int slot = threadIdx.x & 7;
+    for (int64_t i = (int64_t)blockIdx.x * (kThreads / 8) + (threadIdx.x >> 3); i < n; i += stride) {
+        const int4 rec = a.few[i];
+        const int pg = rec.x;
+        double dist = INFINITY;
+        int jj = 0x7fffffff;
+        int K = 0;
+        if (pg >= 0 && pg < a.N) {
+            const int g = upper_search(a.seg_off, a.G, pg);
+            int n0, ng, k0;
+            search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+            if (slot < rec.y && slot < 8) {
+                const unsigned packed = slot < 4 ? (unsigned)rec.z : (unsigned)rec.w;
+                const int j = (int)((packed >> (8 * (slot & 3))) & 0xffu);
+                if (j < K) {
+                    const float* xr = a.X + (size_t)pg * D;
+                    const float* cr = a.cent + (size_t)(k0 + j) * D;
+                    double acc = 0.0;
+                    for (int d = 0; d < D; ++d) {
+                        const double diff = __dsub_rn((double)xr[d], (double)cr[d]);
+                        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                    }
+                    dist = acc;
+                    jj = j;
+                }
+            }
+        }
+#pragma unroll
+        for (int o = 4; o > 0; o >>= 1) {
+            const double od = __shfl_xor(dist, o);
+            const int oj = __shfl_xor(jj, o);
+            if (od < dist || (od == dist && oj < jj)) { dist = od; jj = oj; }
+        }
+        if (slot == 0 && jj < K) a.next[pg] = jj;
     }
 }
 
@@ -818,6 +918,7 @@ BigWs big_ws_layout(const kb_batch& b, size_t base) {
     w.amax = off;      off += al256(sizeof(unsigned) * (size_t)b.G);
     w.cnmax = off;     off += al256(sizeof(unsigned) * 2 * (size_t)b.G);
     w.nflag = off;     off += 256;
+    w.few = off;       off += al256(sizeof(int4) * (size_t)(b.N > 0 ? b.N : 1));
     w.partJ = off;     off += al256(sizeof(double) * w.max_chunks);
     w.prop = off;      off += al256(sizeof(int32_t) * (size_t)(b.N > 0 ? b.N : 1));
     w.end = off;
@@ -842,6 +943,7 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
     a.cnmax_bits = reinterpret_cast<unsigned*>(ws + w.cnmax);
     a.nflag = reinterpret_cast<int*>(ws + w.nflag);
     a.flist = c.a_new;
+    a.few = reinterpret_cast<int4*>(ws + w.few);
     int32_t* const other = reinterpret_cast<int32_t*>(ws + w.prop);
     a.prev = other; a.next = c.assign;
     a.partJ = reinterpret_cast<double*>(ws + w.partJ);
@@ -860,7 +962,7 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
     const unsigned row_blocks = (unsigned)(((size_t)b.G * w.kpad + kWaves - 1) / kWaves);
     const unsigned chunk_blocks = (unsigned)w.max_chunks;
     const size_t lds = (size_t)kGroupTiles * ds * 2 * 64 * 16 + (size_t)4 * kGroupTiles * 64 * 8 +
-                       (size_t)kTilesPerChunk * 32 * 4 + 16;
+                       (size_t)kTilesPerChunk * 32 * (16 + 4) + 16;
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     const dim3 upd_grid((unsigned)((b.N + kUpdateRange - 1) / kUpdateRange),
                         (unsigned)((a.Kmax + kRowsPerGroup - 1) / kRowsPerGroup));
@@ -879,6 +981,7 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
             a.prev = mine ? other : c.assign;                                                    \
             hipLaunchKernelGGL(big_renew<DS_>, dim3(row_blocks), dim3(kThreads), 0, st, a);      \
             hipLaunchKernelGGL(big_score<DS_>, dim3(chunk_blocks), dim3(kThreads), lds, st, a);  \
+            hipLaunchKernelGGL(big_exact_few, dim3(512), dim3(kThreads), 0, st, a);              \
             hipLaunchKernelGGL(big_exact, dim3(1024), dim3(kThreads), 0, st, a);                 \
             hipLaunchKernelGGL(big_update, upd_grid, dim3(kThreads), 0, st, a);                  \
         }                                                                                        \
