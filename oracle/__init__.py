@@ -238,6 +238,23 @@ def cluster_geometry(seg_off, koff, X, cent, assign_):
     return SimpleNamespace(rep=rep, radius=radius, dist2=dist2)
 
 
+def seed_farthest(seg_off, koff, X):
+    """Farthest-point initial centroids.  Returns cent [Ksum, D] and pick [Ksum]
+    (global candidate index of every chosen row)."""
+    lib = _load()
+    seg_off = _c(seg_off, np.int32)
+    koff = _c(koff, np.int32)
+    X = _c(X, np.float32)
+    G = len(seg_off) - 1
+    N, D = X.shape
+    Ksum = int(koff[-1])
+    cent = np.zeros((Ksum, D), dtype=np.float32)
+    pick = np.full(Ksum, -1, dtype=np.int32)
+    lib.kbo_seed_farthest(ctypes.c_int32(G), ctypes.c_int32(D), _p(seg_off), _p(koff), _p(X),
+                          _p(cent), _p(pick))
+    return SimpleNamespace(cent=cent, pick=pick)
+
+
 def strategy_mask(koff, S, h, target, rep, theta_sat):
     lib = _load()
     koff = _c(koff, np.int32)

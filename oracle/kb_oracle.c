@@ -25,6 +25,8 @@
  *   kbo_round        the three in sequence.
  *   kbo_cluster_geometry  the representative (centroid kernel) of each cluster
  *                    and the cluster radius (Sec. 3.3; Theorem 1's covering term).
+ *   kbo_seed_farthest     farthest-point initial centroids (greedy cover; the
+ *                    covering radius of Theorem 1's approximation term).
  *   kbo_strategy_mask     the mask of Eq. 5 in the paper's own form, from the
  *                    hardware signature of the representatives.
  *   kbo_update_stats the statistics update that ends an iteration of Alg. 1.
@@ -468,6 +470,52 @@ void kbo_cluster_geometry(int32_t G, int32_t D, const int32_t *seg_off,
         for (int32_t j = 0; j < K; ++j) radius[koff[g] + j] = sqrt(dmax[j]);
         free(dmin);
         free(dmax);
+    }
+}
+
+/* ------------------------------------------------------ farthest-point seeding */
+
+/* Initial centroids that spread over the frontier (an option beside "the first
+ * K rows"): the first centroid is the search's first row, and every further one
+ * is the candidate farthest from the centroids chosen so far,
+ *     c_{j+1} = x_k  with  k = argmax_k min_{i <= j} ||x_k - c_i||^2 ,
+ * lowest k on ties (squared L2 distances in fp64, direct differences).  This is
+ * the greedy cover whose largest cluster radius is within a factor two of the
+ * smallest possible one - the covering radius epsilon that the approximation
+ * term of Theorem 1 (Appendix "Bounding Approximation Regret") is linear in.
+ *
+ *   cent[koff[g] + j, :] = the j-th chosen row of search g (an exact copy)
+ *   pick[koff[g] + j]    = its global candidate index (may be NULL)
+ * When all remaining candidates coincide with chosen centroids the farthest
+ * distance is 0 and the lowest-index candidate is taken again. */
+void kbo_seed_farthest(int32_t G, int32_t D, const int32_t *seg_off,
+                       const int32_t *koff, const float *X, float *cent, int32_t *pick)
+{
+#pragma omp parallel for schedule(dynamic, 1) if (G > 1)
+    for (int32_t g = 0; g < G; ++g) {
+        const int32_t n0 = seg_off[g], n = seg_off[g + 1] - seg_off[g];
+        const int32_t K = koff[g + 1] - koff[g];
+        if (n <= 0 || K <= 0) continue;
+        double *mind = (double *)malloc(sizeof(double) * (size_t)n);
+        for (int32_t k = 0; k < n; ++k) mind[k] = INFINITY;
+        int32_t chosen = 0;                 /* local index of the newest centroid */
+        for (int32_t j = 0; j < K; ++j) {
+            float *c = cent + ((size_t)koff[g] + j) * D;
+            memcpy(c, X + ((size_t)n0 + chosen) * D, sizeof(float) * D);
+            if (pick) pick[koff[g] + j] = n0 + chosen;
+            double far = -1.0;
+            int32_t arg = 0;
+            for (int32_t k = 0; k < n; ++k) {
+                const double d = sqdist(X + ((size_t)n0 + k) * D, c, D);
+                if (d < mind[k]) mind[k] = d;
+                if (mind[k] > far) {
+                    far = mind[k];
+                    arg = k;
+                }
+            }
+            chosen = arg;
+        }
+        free(mind);
     }
 }
 

@@ -274,3 +274,59 @@ def test_incremental_update_equals_reaggregation():
     np.testing.assert_array_equal(st["Ncs"], agg2.Ncs)
     np.testing.assert_allclose(st["mu"], agg2.mu, rtol=2e-5)
     np.testing.assert_array_equal(st["t"], b.t + 60)
+
+
+# ----------------------------------------------------------------- seeding
+
+def test_seed_farthest_hand_example():
+    rows = _rows("seed_farthest_hand.txt")
+    X = np.array([[float(r[0])] for r in rows], np.float32)
+    order = [int(r[1]) for r in rows]
+    K = max(order) + 1
+    want_pick = [order.index(j) for j in range(K)]
+    seg, koff = _one(len(rows), K)
+    s = oracle.seed_farthest(seg, koff, X)
+    np.testing.assert_array_equal(s.pick, want_pick)
+    np.testing.assert_array_equal(s.cent[:, 0], X[want_pick, 0])
+
+
+def test_seed_farthest_greedy_property_and_two_approximation():
+    # every pick maximises the distance to the picks before it (checked with numpy),
+    # and the greedy cover's radius is within a factor two of the best possible
+    # k-centre radius over all K-subsets of the rows (brute force)
+    import itertools
+    rng = np.random.default_rng(3)
+    for trial in range(6):
+        n, D, K = 11, 3, 3
+        X = rng.normal(size=(n, D)).astype(np.float32)
+        seg, koff = _one(n, K)
+        s = oracle.seed_farthest(seg, koff, X)
+        X64 = X.astype(np.float64)
+        d2 = ((X64[:, None, :] - X64[None, :, :]) ** 2).sum(-1)
+        assert s.pick[0] == 0
+        for j in range(1, K):
+            mind = d2[:, s.pick[:j]].min(1)
+            assert mind[s.pick[j]] >= mind.max() * (1 - 1e-12)
+        np.testing.assert_array_equal(s.cent, X[s.pick])
+        greedy_r = np.sqrt(d2[:, s.pick].min(1).max())
+        best_r = min(np.sqrt(d2[:, list(c)].min(1).max()) for c in itertools.combinations(range(n), K))
+        assert greedy_r <= 2 * best_r * (1 + 1e-9)
+
+
+def test_seed_farthest_segments_duplicates_and_radius_gain():
+    # global indices per search; with fewer distinct rows than clusters the first row
+    # is taken again once the farthest distance is zero
+    X = np.array([[0.0], [0.0], [5.0], [7.0], [7.0], [9.0]], np.float32)
+    seg = np.array([0, 3, 6], np.int32)
+    koff = np.array([0, 3, 5], np.int32)
+    s = oracle.seed_farthest(seg, koff, X)
+    np.testing.assert_array_equal(s.pick, [0, 2, 0, 3, 5])
+    # on blobs the greedy cover starts Lloyd from a smaller covering radius than the
+    # first K rows do
+    b = synth.config5(G=6, nmin=200, nmax=600, seed=40)
+    far = oracle.seed_farthest(b.seg_off, b.koff, b.X)
+    first = np.vstack([b.X[b.seg_off[g]:b.seg_off[g] + (b.koff[g + 1] - b.koff[g])] for g in range(b.G)])
+    def cover(cent):
+        a, mind2, _ = oracle.assign(b.seg_off, b.koff, b.X, cent)
+        return np.array([np.sqrt(mind2[b.seg_off[g]:b.seg_off[g + 1]].max()) for g in range(b.G)])
+    assert (cover(far.cent) < cover(first)).all()
