@@ -152,7 +152,11 @@ def main():
             d.batch, sp, d.assign, None, R, dh, dtg, theta, d.sel, d.ksel, d.ws, d.ws_bytes), reps)[0]
         loop["update_stats"] = timed(lambda: kb.kb_update_stats(
             d.batch, d.params, d.sel, d.ksel, drw, dok, d.visits, d.rsum, d.Ncs, d.mu, d.t), reps)[0]
+        # optional farthest-point seeding: K_g passes over the rows of every search
+        loop["seed_farthest"] = timed(d.seed_farthest, 3)[0]
         loop = {k: round(v, 4) for k, v in loop.items()}
+        nk_rows = float(np.sum(np.diff(b.seg_off).astype(np.float64) * np.diff(b.koff)))
+        loop["seed_farthest_GBs"] = round(nk_rows * (4 * b.D + 16) / (loop["seed_farthest"] * 1e-3) / 1e9, 1)
         # representatives: every feature row and assignment read once
         loop["cluster_geometry_GBs"] = round(
             b.N * (4 * b.D + 4) / (loop["cluster_geometry"] * 1e-3) / 1e9, 1)

@@ -20,7 +20,7 @@
  *                    over V_hw).
  *   kb_round         the three in sequence on one stream.
  *   kb_cluster_geometry, kb_strategy_mask, kb_ucb_select_masked,
- *   kb_sample_signature, kb_update_stats
+ *   kb_sample_signature, kb_update_stats, kb_seed_farthest
  *                    the remaining device-side steps of an iteration of Alg. 1:
  *                    cluster representatives, the mask in the paper's own form,
  *                    selection under that mask, the draw with the paper's
@@ -247,6 +247,19 @@ kb_status kb_cluster_geometry(const kb_batch *batch, const float *X,
                               const float *cent, const int32_t *assign,
                               int32_t *rep, float *radius, void *ws,
                               size_t ws_bytes, void *stream);
+
+/* Farthest-point initial centroids, an option beside "the first K rows" for the
+ * cent_init of kb_cluster: cent[koff[g]] = the first row of search g, and every
+ * further centroid is the row farthest from those chosen so far,
+ *   argmax_k min_i ||x_k - c_i||^2      (fp64 from direct differences, exactly as
+ * the definition; lowest k on ties).  The cover's largest radius is within a
+ * factor two of the smallest possible one (the covering radius of Theorem 1's
+ * approximation term).  cent [Ksum,D] out (exact copies of the chosen rows),
+ * pick [Ksum] out: their global candidate indices (may be NULL).  K_g passes over
+ * the rows of each search. */
+kb_status kb_seed_farthest(const kb_batch *batch, const float *X, float *cent,
+                           int32_t *pick, void *ws, size_t ws_bytes,
+                           void *stream);
 
 /* The binary mask of Eq. 5 in the paper's own form,
  *   M[i,s] = [ h[rep[i], target[s]] < theta_sat ]        (0 for rep[i] < 0),

@@ -84,6 +84,8 @@ def lib() -> ctypes.CDLL:
         L.kb_ucb_select_masked.argtypes = [pb, pp] + [vp] * 11 + [vp, sz, vp]
         L.kb_update_stats.restype = ctypes.c_int
         L.kb_update_stats.argtypes = [pb, pp] + [vp] * 9 + [vp]
+        L.kb_seed_farthest.restype = ctypes.c_int
+        L.kb_seed_farthest.argtypes = [pb, vp, vp, vp, vp, sz, vp]
         L.kb_status_str.restype = ctypes.c_char_p
         L.kb_status_str.argtypes = [ctypes.c_int]
         L.kb_version.restype = ctypes.c_char_p
@@ -212,6 +214,12 @@ def kb_update_stats(batch, params, sel, ksel, reward, ok, visits, rsum, Ncs, mu,
     return _check(s, "kb_update_stats", check)
 
 
+def kb_seed_farthest(batch, X, cent, pick, ws, ws_bytes, stream=None, check=True):
+    s = lib().kb_seed_farthest(ctypes.byref(batch), _ptr(X), _ptr(cent), _ptr(pick), _ptr(ws),
+                               ws_bytes, _stream(stream))
+    return _check(s, "kb_seed_farthest", check)
+
+
 def kb_set_scorer(mode: int) -> int:
     return int(lib().kb_set_scorer(int(mode)))
 
@@ -300,6 +308,10 @@ class DeviceBatch:
     def cluster_geometry(self, **kw):
         return kb_cluster_geometry(self.batch, self.X, self.cent, self.assign, self.rep,
                                    self.radius, self.ws, self.ws_bytes, **kw)
+
+    def seed_farthest(self, cent=None, pick=True, **kw):
+        return kb_seed_farthest(self.batch, self.X, self.cent2 if cent is None else cent,
+                                self.rep if pick else None, self.ws, self.ws_bytes, **kw)
 
     def round(self, **kw):
         return kb_round(self.batch, self.params, self.io, self.ws, self.ws_bytes, **kw)

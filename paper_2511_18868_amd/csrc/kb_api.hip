@@ -260,6 +260,24 @@ kb_status kb_cluster_geometry(const kb_batch* batch, const float* X, const float
     return dev(launch_geometry(*batch, c, (hipStream_t)stream));
 }
 
+kb_status kb_seed_farthest(const kb_batch* batch, const float* X, float* cent, int32_t* pick,
+                           void* ws, size_t ws_bytes, void* stream) {
+    kb_status s = check_batch(batch);
+    if (s != KB_OK) return s;
+    if (!X || !cent) return KB_EINVAL;
+    if (!aligned(X, 16) || !aligned(cent, 16)) return KB_EINVAL;
+    if (batch->D > KB_MAX_D) return KB_EUNSUPPORTED;
+    s = check_ws(batch, ws, ws_bytes);
+    if (s != KB_OK) return s;
+    WsLayout w = ws_layout(*batch);
+    char* base = (char*)ws;
+    int32_t* order = (int32_t*)(base + w.order);
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = launch_order(*batch, order, (int32_t*)(base + w.tile_off), nullptr, st);
+    if (e != hipSuccess) return KB_EDEVICE;
+    return dev(launch_seed_farthest(*batch, X, cent, pick, (double*)(base + w.geo_d2), order, st));
+}
+
 kb_status kb_strategy_mask(const kb_batch* batch, int32_t R, const float* h, const int32_t* target,
                            const int32_t* rep, float theta_sat, uint8_t* M, int32_t* nvalid,
                            void* stream) {

@@ -174,6 +174,13 @@ def test_loop_entry_points_argument_errors(L):
         bad = list(u); bad[i] = None
         assert kb.kb_update_stats(b, p, *bad, stream=0, check=False) == kb.KB_EINVAL
     assert kb.kb_update_stats(b, kb.make_params(prior_n=-1.0), *u, stream=0, check=False) == kb.KB_EINVAL
+    # farthest-point seeds: X, cent, pick (pick may be NULL)
+    assert kb.kb_seed_farthest(b, None, FAKE, FAKE, FAKE, big, stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_seed_farthest(b, FAKE, None, FAKE, FAKE, big, stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_seed_farthest(b, FAKE, FAKE + 8, None, FAKE, big, stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_seed_farthest(b, FAKE, FAKE, None, FAKE, 16, stream=0, check=False) == kb.KB_EWORKSPACE
+    assert kb.kb_seed_farthest(_batch(D=65), FAKE, FAKE, None, FAKE, big, stream=0,
+                               check=False) == kb.KB_EUNSUPPORTED
     # signature draw
     assert kb.kb_sample_signature(b, sp, FAKE, None, 0, FAKE, FAKE, 0.75, FAKE, FAKE, FAKE, big,
                                   stream=0, check=False) == kb.KB_EINVAL

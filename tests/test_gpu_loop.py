@@ -201,3 +201,44 @@ def test_masked_selection_reduces_to_plain_selection(kb):
                             d.t, d.Ncs, d.mu, d.ucb, d.sel, d.ws, d.ws_bytes)
     _sync()
     assert (d.host("sel") == -1).all()
+
+
+def test_seed_farthest_exact(kb, case):
+    name, b, _ = case
+    d = kb.DeviceBatch(b)
+    d.cent2.fill_(-3.0)
+    d.rep.fill_(-7)
+    d.seed_farthest()
+    _sync()
+    want = oracle.seed_farthest(b.seg_off, b.koff, b.X)
+    np.testing.assert_array_equal(d.host("rep"), want.pick, err_msg=name)
+    np.testing.assert_array_equal(d.host("cent2").view(np.uint32), want.cent.view(np.uint32), err_msg=name)
+    # pick may be NULL
+    d.cent2.fill_(-3.0)
+    d.seed_farthest(pick=False)
+    _sync()
+    np.testing.assert_array_equal(d.host("cent2").view(np.uint32), want.cent.view(np.uint32))
+
+
+def test_clustering_from_farthest_seeds(kb):
+    # the seeds feed kb_cluster as cent_init; the result is the oracle's from the same
+    # seeds, and its covering radius beats the one reached from the first K rows
+    b = synth.config5(G=24, nmin=64, nmax=1500, seed=61)
+    d = kb.DeviceBatch(b, iters=5)
+    d.seed_farthest()
+    d.cluster(cent_init=d.cent2)
+    d.cluster_geometry()
+    _sync()
+    seeds = oracle.seed_farthest(b.seg_off, b.koff, b.X)
+    ora = oracle.cluster(b.seg_off, b.koff, b.X, 5, cent_init=seeds.cent)
+    clean = ora.dirty == 0
+    cp = np.repeat(clean, np.diff(b.seg_off))
+    np.testing.assert_array_equal(d.host("assign")[cp], ora.assign[cp])
+    assert clean.mean() > 0.8
+    r_far = d.host("radius").copy()
+    d.cluster()
+    d.cluster_geometry()
+    _sync()
+    r_first = d.host("radius")
+    worst = lambda r: np.array([r[b.koff[g]:b.koff[g + 1]].max() for g in range(b.G)])
+    assert (worst(r_far) <= worst(r_first)).mean() > 0.7

@@ -321,6 +321,9 @@ def test_seed_farthest_segments_duplicates_and_radius_gain():
     koff = np.array([0, 3, 5], np.int32)
     s = oracle.seed_farthest(seg, koff, X)
     np.testing.assert_array_equal(s.pick, [0, 2, 0, 3, 5])
+    # scaling by a power of two scales every distance exactly: same picks at any scale
+    for e in (-12, 9):
+        np.testing.assert_array_equal(oracle.seed_farthest(seg, koff, X * np.float32(2.0 ** e)).pick, s.pick)
     # on blobs the greedy cover starts Lloyd from a smaller covering radius than the
     # first K rows do
     b = synth.config5(G=6, nmin=200, nmax=600, seed=40)
