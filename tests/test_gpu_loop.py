@@ -242,3 +242,39 @@ def test_clustering_from_farthest_seeds(kb):
     r_first = d.host("radius")
     worst = lambda r: np.array([r[b.koff[g]:b.koff[g + 1]].max() for g in range(b.G)])
     assert (worst(r_far) <= worst(r_first)).mean() > 0.7
+
+
+def test_batch_without_candidates(kb):
+    """Every search empty (N = 0): each entry point returns without touching memory it
+    does not own and reports 'nothing' where it reports at all."""
+    import torch
+    dev = torch.device("cuda:0")
+    G, D, S = 3, 8, 4
+    z = lambda n, dt: torch.zeros(max(n, 1), dtype=dt, device=dev)
+    seg = torch.zeros(G + 1, dtype=torch.int32, device=dev)
+    ko = torch.zeros(G + 1, dtype=torch.int32, device=dev)
+    batch = kb.make_batch(G, D, S, 0, 0, 0, 0, seg, ko)
+    params = kb.make_params(iters=3)
+    wsb = kb.kb_workspace_bytes(batch, params)
+    assert wsb > 0
+    ws = z(wsb, torch.uint8)
+    X, cent = z(4, torch.float32), z(4, torch.float32)
+    f32, i32, u8 = z(4, torch.float32), z(4, torch.int32), z(4, torch.uint8)
+    inc = torch.ones(G, dtype=torch.float32, device=dev)
+    t = torch.ones(G, dtype=torch.int64, device=dev)
+    sel = torch.full((G, 3), 5, dtype=torch.int32, device=dev)
+    ksel = torch.full((G,), 5, dtype=torch.int32, device=dev)
+    nvalid = torch.full((G,), 5, dtype=torch.int32, device=dev)
+    obj = torch.full((G,), -1.0, dtype=torch.float32, device=dev)
+    assert kb.kb_prune(batch, params, f32, f32, inc, f32, u8) == 0
+    assert kb.kb_cluster(batch, params, X, None, i32, cent, i32, obj, ws, wsb) == 0
+    assert kb.kb_ucb_select(batch, params, i32, u8, f32, i32, f32, t, i32, f32, f32, sel, ws, wsb) == 0
+    assert kb.kb_sample(batch, kb.kb_sample_params(1, 1, 1.0), i32, u8, f32, inc, sel, ksel, ws, wsb) == 0
+    assert kb.kb_cluster_geometry(batch, X, cent, i32, i32, f32, ws, wsb) == 0
+    assert kb.kb_seed_farthest(batch, X, cent, None, ws, wsb) == 0
+    assert kb.kb_strategy_mask(batch, 3, f32, i32, i32, 0.75, u8, nvalid) == 0
+    _sync()
+    assert (sel.cpu().numpy() == -1).all()
+    assert (ksel.cpu().numpy() == -1).all()
+    assert (nvalid.cpu().numpy() == 0).all()
+    assert (obj.cpu().numpy() == 0).all()
