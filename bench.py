@@ -46,7 +46,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=5, help="workload: BASELINE config 1..5")
+    ap.add_argument("--config", type=int, default=5, help="workload: benchmark configuration 1..5")
     ap.add_argument("--searches", type=int, default=0, help="override the number of searches (config 3/5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calib", action="store_true",
@@ -61,7 +61,7 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=0, help="searches in the CPU baseline sample")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus must be 1", file=sys.stderr)
+        print("bench.py: the library runs on one GPU; --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
