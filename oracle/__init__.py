@@ -255,6 +255,25 @@ def seed_farthest(seg_off, koff, X):
     return SimpleNamespace(cent=cent, pick=pick)
 
 
+def seed_dsquared(seg_off, koff, X, seed, draw0):
+    """k-means++-style initial centroids (D^2-weighted draws).  Returns cent, pick
+    and near (per search: some draw had its two best keys within 1e-6 relative)."""
+    lib = _load()
+    seg_off = _c(seg_off, np.int32)
+    koff = _c(koff, np.int32)
+    X = _c(X, np.float32)
+    G = len(seg_off) - 1
+    N, D = X.shape
+    Ksum = int(koff[-1])
+    cent = np.zeros((Ksum, D), dtype=np.float32)
+    pick = np.full(Ksum, -1, dtype=np.int32)
+    near = np.zeros(G, dtype=np.uint8)
+    lib.kbo_seed_dsquared(ctypes.c_int32(G), ctypes.c_int32(D), _p(seg_off), _p(koff), _p(X),
+                          ctypes.c_uint64(seed), ctypes.c_uint64(draw0), _p(cent), _p(pick),
+                          _p(near))
+    return SimpleNamespace(cent=cent, pick=pick, near=near)
+
+
 def strategy_mask(koff, S, h, target, rep, theta_sat):
     lib = _load()
     koff = _c(koff, np.int32)

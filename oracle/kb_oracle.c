@@ -27,6 +27,9 @@
  *                    and the cluster radius (Sec. 3.3; Theorem 1's covering term).
  *   kbo_seed_farthest     farthest-point initial centroids (greedy cover; the
  *                    covering radius of Theorem 1's approximation term).
+ *   kbo_seed_dsquared     randomised initial centroids drawn with probability
+ *                    proportional to the squared distance to the chosen ones
+ *                    (k-means++ seeding, the scikit-learn default of Sec. 3.6).
  *   kbo_strategy_mask     the mask of Eq. 5 in the paper's own form, from the
  *                    hardware signature of the representatives.
  *   kbo_update_stats the statistics update that ends an iteration of Alg. 1.
@@ -514,6 +517,70 @@ void kbo_seed_farthest(int32_t G, int32_t D, const int32_t *seg_off,
                 }
             }
             chosen = arg;
+        }
+        free(mind);
+    }
+}
+
+/* ------------------------------------------------- D^2-weighted seeding (++) */
+
+double kbo_uniform(uint64_t seed, uint64_t draw, int32_t k);
+
+/* Randomised initial centroids in the manner of k-means++ (the seeding behind
+ * the scikit-learn default the paper runs, Sec. 3.6): the first centroid is a
+ * uniformly drawn row of the search, every further one is drawn with
+ * probability proportional to its squared distance to the nearest centroid
+ * chosen so far,  P(k) = D_k^2 / sum D^2,  D_k^2 = min_i ||x_k - c_i||^2 (fp64,
+ * direct differences).  Every draw is made reproducible the same way as the
+ * draw of k_t: with independent Gumbel variates, argmax_k (ln D_k^2 - ln(-ln u_k))
+ * is distributed exactly as P, and u_k is the variate of candidate k (global
+ * index) in draw number draw0 + j under `seed`, j the position of the centroid
+ * in its search.  A row at distance 0 has weight 0 (key -inf) and is never
+ * drawn while a row at positive distance exists; lowest index on exact ties.
+ *
+ *   cent[koff[g] + j, :] = the j-th drawn row (an exact copy), pick = its index
+ *   near[g] = 1 if, in any of the K_g draws, the runner-up key was within
+ *             1e-6*max(|best|,1e-30) of the best (logarithms differ between
+ *             libraries in the last bits; the later draws then depend on it) */
+void kbo_seed_dsquared(int32_t G, int32_t D, const int32_t *seg_off, const int32_t *koff,
+                       const float *X, uint64_t seed, uint64_t draw0, float *cent,
+                       int32_t *pick, uint8_t *near)
+{
+#pragma omp parallel for schedule(dynamic, 1) if (G > 1)
+    for (int32_t g = 0; g < G; ++g) {
+        const int32_t n0 = seg_off[g], n = seg_off[g + 1] - seg_off[g];
+        const int32_t K = koff[g + 1] - koff[g];
+        if (near) near[g] = 0;
+        if (n <= 0 || K <= 0) continue;
+        double *mind = (double *)malloc(sizeof(double) * (size_t)n);
+        for (int32_t k = 0; k < n; ++k) mind[k] = INFINITY;
+        for (int32_t j = 0; j < K; ++j) {
+            /* draw with weights mind (all equal, i.e. uniform, for the first) */
+            double best = -INFINITY, runner = -INFINITY;
+            int32_t arg = -1;
+            for (int32_t k = 0; k < n; ++k) {
+                const double u = kbo_uniform(seed, draw0 + (uint64_t)j, n0 + k);
+                const double gumbel = -log(-log(u));
+                const double key = (j == 0 ? 0.0 : log(mind[k])) + gumbel;
+                if (arg < 0 || key > best) {
+                    runner = best;
+                    best = key;
+                    arg = k;
+                } else if (key > runner) {
+                    runner = key;
+                }
+            }
+            if (near && runner > -INFINITY) {
+                const double scale = fabs(best) > KBO_TINY ? fabs(best) : KBO_TINY;
+                if ((best - runner) <= KBO_NEAR_TIE_REL * scale) near[g] = 1;
+            }
+            float *c = cent + ((size_t)koff[g] + j) * D;
+            memcpy(c, X + ((size_t)n0 + arg) * D, sizeof(float) * D);
+            if (pick) pick[koff[g] + j] = n0 + arg;
+            for (int32_t k = 0; k < n; ++k) {
+                const double d = sqdist(X + ((size_t)n0 + k) * D, c, D);
+                if (d < mind[k]) mind[k] = d;
+            }
         }
         free(mind);
     }

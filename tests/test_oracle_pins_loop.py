@@ -333,3 +333,62 @@ def test_seed_farthest_segments_duplicates_and_radius_gain():
         a, mind2, _ = oracle.assign(b.seg_off, b.koff, b.X, cent)
         return np.array([np.sqrt(mind2[b.seg_off[g]:b.seg_off[g + 1]].max()) for g in range(b.G)])
     assert (cover(far.cent) < cover(first)).all()
+
+
+def test_seed_dsquared_first_two_draws_follow_their_laws():
+    # first centroid: uniform over the rows; second: P(k) = D_k^2 / sum D^2 given the first
+    n, D = 9, 2
+    rng = np.random.default_rng(12)
+    X = rng.normal(size=(n, D)).astype(np.float32)
+    seg, koff = _one(n, 2)
+    draws = 24000
+    first = np.zeros(n)
+    second = np.zeros((n, n))
+    for d in range(draws):
+        s = oracle.seed_dsquared(seg, koff, X, 2024, 1000 * d)
+        first[s.pick[0]] += 1
+        second[s.pick[0], s.pick[1]] += 1
+        assert s.pick[0] != s.pick[1]                      # a chosen row has weight zero
+    chi2 = ((first - draws / n) ** 2 / (draws / n)).sum()
+    assert stats.chi2.sf(chi2, n - 1) > 1e-3
+    X64 = X.astype(np.float64)
+    d2 = ((X64[:, None, :] - X64[None, :, :]) ** 2).sum(-1)
+    for a in range(n):
+        p = d2[a] / d2[a].sum()
+        m = first[a]
+        keep = p > 0
+        chi2 = ((second[a][keep] - m * p[keep]) ** 2 / (m * p[keep])).sum()
+        assert stats.chi2.sf(chi2, keep.sum() - 1) > 1e-4, (a, chi2)
+        # a uniform second draw would be rejected
+        chi2u = ((second[a][keep] - m / (n - 1)) ** 2 / (m / (n - 1))).sum()
+        assert stats.chi2.sf(chi2u, keep.sum() - 1) < 1e-6
+
+
+def test_seed_dsquared_structure():
+    b = synth.config5(G=5, nmin=64, nmax=300, seed=9)
+    s = oracle.seed_dsquared(b.seg_off, b.koff, b.X, 7, 3)
+    for g in range(b.G):
+        pk = s.pick[b.koff[g]:b.koff[g + 1]]
+        assert ((pk >= b.seg_off[g]) & (pk < b.seg_off[g + 1])).all()
+        assert len(set(pk.tolist())) == len(pk)            # distinct rows: no duplicates in this data
+    np.testing.assert_array_equal(s.cent, b.X[s.pick])
+    # reproducible; another seed or draw number gives other seeds
+    s2 = oracle.seed_dsquared(b.seg_off, b.koff, b.X, 7, 3)
+    np.testing.assert_array_equal(s.pick, s2.pick)
+    assert (oracle.seed_dsquared(b.seg_off, b.koff, b.X, 8, 3).pick != s.pick).any()
+    assert (oracle.seed_dsquared(b.seg_off, b.koff, b.X, 7, 4).pick != s.pick).any()
+    # identical rows: after the first pick every weight is zero and the draw falls back to
+    # the lowest index
+    X = np.ones((6, 3), np.float32)
+    seg, koff = _one(6, 3)
+    d = oracle.seed_dsquared(seg, koff, X, 1, 0)
+    assert d.pick[1] == 0 and d.pick[2] == 0
+    # mean D^2 cost of the seeds is below that of the first K rows on blobs (the point of ++)
+    far = []
+    for draw in range(5):
+        sd = oracle.seed_dsquared(b.seg_off, b.koff, b.X, 5, 100 * draw)
+        _, m2, _ = oracle.assign(b.seg_off, b.koff, b.X, sd.cent)
+        far.append(m2.sum())
+    first = np.vstack([b.X[b.seg_off[g]:b.seg_off[g] + (b.koff[g + 1] - b.koff[g])] for g in range(b.G)])
+    _, m1, _ = oracle.assign(b.seg_off, b.koff, b.X, first)
+    assert np.mean(far) < m1.sum()
