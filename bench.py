@@ -154,6 +154,7 @@ def main():
             d.batch, d.params, d.sel, d.ksel, drw, dok, d.visits, d.rsum, d.Ncs, d.mu, d.t), reps)[0]
         # optional farthest-point seeding: K_g passes over the rows of every search
         loop["seed_farthest"] = timed(d.seed_farthest, 3)[0]
+        loop["seed_dsquared"] = timed(lambda: d.seed_dsquared(20251118, 0), 3)[0]
         loop = {k: round(v, 4) for k, v in loop.items()}
         nk_rows = float(np.sum(np.diff(b.seg_off).astype(np.float64) * np.diff(b.koff)))
         loop["seed_farthest_GBs"] = round(nk_rows * (4 * b.D + 16) / (loop["seed_farthest"] * 1e-3) / 1e9, 1)

@@ -20,7 +20,8 @@
  *                    over V_hw).
  *   kb_round         the three in sequence on one stream.
  *   kb_cluster_geometry, kb_strategy_mask, kb_ucb_select_masked,
- *   kb_sample_signature, kb_update_stats, kb_seed_farthest
+ *   kb_sample_signature, kb_update_stats, kb_seed_farthest,
+ *   kb_seed_dsquared
  *                    the remaining device-side steps of an iteration of Alg. 1:
  *                    cluster representatives, the mask in the paper's own form,
  *                    selection under that mask, the draw with the paper's
@@ -260,6 +261,21 @@ kb_status kb_cluster_geometry(const kb_batch *batch, const float *X,
 kb_status kb_seed_farthest(const kb_batch *batch, const float *X, float *cent,
                            int32_t *pick, void *ws, size_t ws_bytes,
                            void *stream);
+
+/* Randomised initial centroids in the manner of k-means++, the seeding of the
+ * scikit-learn default the paper runs (Sec. 3.6): the first centroid of a search
+ * is a uniformly drawn row, every further one is drawn with probability
+ * proportional to its squared distance to the nearest centroid chosen so far.
+ * Reproducible like kb_sample: the j-th centroid of a search is
+ *   argmax_k ( ln D_k^2 - ln(-ln u_k) ),   D_k^2 = min_i ||x_k - c_i||^2  (fp64),
+ * with u_k the variate of candidate k (global index) in draw number draw0 + j
+ * under `seed` (ln D^2 replaced by 0 for j = 0), lowest k on exact ties; rows at
+ * distance 0 are never drawn while another row exists.  Outputs as
+ * kb_seed_farthest.  A batch that seeds again should move draw0 on by at least
+ * Kmax. */
+kb_status kb_seed_dsquared(const kb_batch *batch, const float *X, uint64_t seed,
+                           uint64_t draw0, float *cent, int32_t *pick, void *ws,
+                           size_t ws_bytes, void *stream);
 
 /* The binary mask of Eq. 5 in the paper's own form,
  *   M[i,s] = [ h[rep[i], target[s]] < theta_sat ]        (0 for rep[i] < 0),

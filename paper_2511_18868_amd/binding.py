@@ -86,6 +86,8 @@ def lib() -> ctypes.CDLL:
         L.kb_update_stats.argtypes = [pb, pp] + [vp] * 9 + [vp]
         L.kb_seed_farthest.restype = ctypes.c_int
         L.kb_seed_farthest.argtypes = [pb, vp, vp, vp, vp, sz, vp]
+        L.kb_seed_dsquared.restype = ctypes.c_int
+        L.kb_seed_dsquared.argtypes = [pb, vp, ctypes.c_uint64, ctypes.c_uint64, vp, vp, vp, sz, vp]
         L.kb_status_str.restype = ctypes.c_char_p
         L.kb_status_str.argtypes = [ctypes.c_int]
         L.kb_version.restype = ctypes.c_char_p
@@ -220,6 +222,12 @@ def kb_seed_farthest(batch, X, cent, pick, ws, ws_bytes, stream=None, check=True
     return _check(s, "kb_seed_farthest", check)
 
 
+def kb_seed_dsquared(batch, X, seed, draw0, cent, pick, ws, ws_bytes, stream=None, check=True):
+    s = lib().kb_seed_dsquared(ctypes.byref(batch), _ptr(X), seed, draw0, _ptr(cent), _ptr(pick),
+                               _ptr(ws), ws_bytes, _stream(stream))
+    return _check(s, "kb_seed_dsquared", check)
+
+
 def kb_set_scorer(mode: int) -> int:
     return int(lib().kb_set_scorer(int(mode)))
 
@@ -311,6 +319,11 @@ class DeviceBatch:
 
     def seed_farthest(self, cent=None, pick=True, **kw):
         return kb_seed_farthest(self.batch, self.X, self.cent2 if cent is None else cent,
+                                self.rep if pick else None, self.ws, self.ws_bytes, **kw)
+
+    def seed_dsquared(self, seed, draw0, cent=None, pick=True, **kw):
+        return kb_seed_dsquared(self.batch, self.X, seed, draw0,
+                                self.cent2 if cent is None else cent,
                                 self.rep if pick else None, self.ws, self.ws_bytes, **kw)
 
     def round(self, **kw):

@@ -260,8 +260,9 @@ kb_status kb_cluster_geometry(const kb_batch* batch, const float* X, const float
     return dev(launch_geometry(*batch, c, (hipStream_t)stream));
 }
 
-kb_status kb_seed_farthest(const kb_batch* batch, const float* X, float* cent, int32_t* pick,
-                           void* ws, size_t ws_bytes, void* stream) {
+static kb_status do_seed(const kb_batch* batch, const float* X, float* cent, int32_t* pick,
+                         void* ws, size_t ws_bytes, void* stream, int dsquared, uint64_t seed,
+                         uint64_t draw0) {
     kb_status s = check_batch(batch);
     if (s != KB_OK) return s;
     if (!X || !cent) return KB_EINVAL;
@@ -275,7 +276,18 @@ kb_status kb_seed_farthest(const kb_batch* batch, const float* X, float* cent, i
     hipStream_t st = (hipStream_t)stream;
     hipError_t e = launch_order(*batch, order, (int32_t*)(base + w.tile_off), nullptr, st);
     if (e != hipSuccess) return KB_EDEVICE;
-    return dev(launch_seed_farthest(*batch, X, cent, pick, (double*)(base + w.geo_d2), order, st));
+    return dev(launch_seed(*batch, X, cent, pick, (double*)(base + w.geo_d2), order, dsquared, seed,
+                           draw0, st));
+}
+
+kb_status kb_seed_farthest(const kb_batch* batch, const float* X, float* cent, int32_t* pick,
+                           void* ws, size_t ws_bytes, void* stream) {
+    return do_seed(batch, X, cent, pick, ws, ws_bytes, stream, 0, 0, 0);
+}
+
+kb_status kb_seed_dsquared(const kb_batch* batch, const float* X, uint64_t seed, uint64_t draw0,
+                           float* cent, int32_t* pick, void* ws, size_t ws_bytes, void* stream) {
+    return do_seed(batch, X, cent, pick, ws, ws_bytes, stream, 1, seed, draw0);
 }
 
 kb_status kb_strategy_mask(const kb_batch* batch, int32_t R, const float* h, const int32_t* target,

@@ -129,8 +129,9 @@ struct GeoCall {
 hipError_t launch_geometry(const kb_batch& b, const GeoCall& c, hipStream_t st);
 size_t geometry_lds_bytes(int Kmax, int D);
 
-hipError_t launch_seed_farthest(const kb_batch& b, const float* X, float* cent, int32_t* pick,
-                                double* mind, const int32_t* order, hipStream_t st);
+hipError_t launch_seed(const kb_batch& b, const float* X, float* cent, int32_t* pick, double* mind,
+                       const int32_t* order, int dsquared, uint64_t seed, uint64_t draw0,
+                       hipStream_t st);
 
 hipError_t launch_strategy_mask(const kb_batch& b, int R, const float* h, const int32_t* target,
                                 const int32_t* rep, float theta_sat, uint8_t* M, int32_t* nvalid,

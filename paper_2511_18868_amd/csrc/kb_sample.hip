@@ -16,6 +16,7 @@
 // each such search in index order.  Keys are fp64 and compared exactly, lowest
 // index on ties, so the result does not depend on the cutting.
 #include "kb_internal.h"
+#include "kb_rng_dev.h"
 
 namespace kb {
 
@@ -47,23 +48,6 @@ struct SampleArgs {
     int32_t* slot_idx;         // [2 * ranges]
 };
 
-__device__ __forceinline__ void philox4x32_10(unsigned c0, unsigned c1, unsigned c2, unsigned c3,
-                                              unsigned k0, unsigned k1, unsigned& o0, unsigned& o1) {
-#pragma unroll
-    for (int r = 0; r < 10; ++r) {
-        const unsigned h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
-        const unsigned h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
-        c0 = h1 ^ c1 ^ k0;
-        c1 = l1;
-        c2 = h0 ^ c3 ^ k1;
-        c3 = l0;
-        k0 += 0x9E3779B9u;
-        k1 += 0xBB67AE85u;
-    }
-    o0 = c0;
-    o1 = c1;
-}
-
 // (key, index) pairs ordered by larger key, then lower index; index kNone = empty
 __device__ __forceinline__ bool better(double ka, int ia, double kb_, int ib) {
     return ia != kNone && (ib == kNone || ka > kb_ || (ka == kb_ && ia < ib));
@@ -77,12 +61,7 @@ __device__ __forceinline__ double sample_key(const SampleArgs& a, int k, double 
     } else {
         V = (double)a.theta_sat - (double)a.h[(size_t)k * a.R + tcol];
     }
-    unsigned x0, x1;
-    philox4x32_10((unsigned)k, 0u, a.draw_lo, a.draw_hi, a.seed_lo, a.seed_hi, x0, x1);
-    const unsigned long long m = ((unsigned long long)x0 << 20) | (unsigned long long)(x1 >> 12);
-    const double u = ((double)m + 0.5) * (1.0 / 4503599627370496.0);
-    const double gumbel = -log(-log(u));
-    return V / a.tau + gumbel;
+    return V / a.tau + gumbel_variate(a.seed_lo, a.seed_hi, a.draw_lo, a.draw_hi, k);
 }
 
 __global__ void __launch_bounds__(kThreads) sample_range(SampleArgs a) {

@@ -12,6 +12,7 @@
 // its largest; the workgroup reduces to the maximum with the lowest index on
 // ties.  Distances are exact, so the choice needs no tolerance.
 #include "kb_internal.h"
+#include "kb_rng_dev.h"
 
 namespace kb {
 
@@ -30,6 +31,10 @@ struct SeedArgs {
     int32_t* pick;       // may be NULL
     double* mind;        // [N] running minimum of every candidate
     const int32_t* order;
+    // randomised (D^2-weighted) seeding instead of the farthest point
+    int dsquared;
+    unsigned seed_lo, seed_hi;
+    unsigned long long draw0;
 };
 
 __global__ void __launch_bounds__(kThreads) seed_farthest_kernel(SeedArgs a) {
@@ -47,8 +52,42 @@ __global__ void __launch_bounds__(kThreads) seed_farthest_kernel(SeedArgs a) {
     if (ng <= 0 || K <= 0) return;
     const float* Xg = a.X + (size_t)n0 * D;
     double* mind = a.mind + n0;
+    // largest (value, lowest index) of the workgroup; every thread returns the index
+    auto block_argmax = [&](double far, int arg) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const double of = __shfl_xor(far, o);
+            const int oa = __shfl_xor(arg, o);
+            if (of > far || (of == far && oa < arg)) { far = of; arg = oa; }
+        }
+        if ((tid & 63) == 0) { redv[tid >> 6] = far; redi[tid >> 6] = arg; }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w = 1; w < kWaves; ++w)
+                if (redv[w] > far || (redv[w] == far && redi[w] < arg)) { far = redv[w]; arg = redi[w]; }
+            chosen_s = (arg >= 0 && arg < ng) ? arg : 0;
+        }
+        __syncthreads();
+        return chosen_s;
+    };
     int chosen = 0;
+    if (a.dsquared) {
+        // first centroid: a uniform draw, i.e. the largest variate of draw number draw0
+        double far = -INFINITY;
+        int arg = 0x7fffffff;
+        for (int k = tid; k < ng; k += kThreads) {
+            const double key = gumbel_variate(a.seed_lo, a.seed_hi, (unsigned)a.draw0,
+                                              (unsigned)(a.draw0 >> 32), n0 + k);
+            if (key > far || (key == far && k < arg)) { far = key; arg = k; }
+        }
+        chosen = block_argmax(far, arg);
+    }
     for (int j = 0; j < K; ++j) {
+        // what the next centroid maximises: the running minimum itself (farthest
+        // point), or ln(minimum) plus the variate of draw number draw0 + j + 1 (a draw
+        // with probability proportional to the minimum)
+        const unsigned long long drawn = a.draw0 + (unsigned long long)j + 1ull;
+        const bool need_key = a.dsquared && j + 1 < K;
         if (tid < D) {
             const float v = Xg[(size_t)chosen * D + tid];
             c[tid] = v;
@@ -56,7 +95,7 @@ __global__ void __launch_bounds__(kThreads) seed_farthest_kernel(SeedArgs a) {
         }
         if (tid == 0 && a.pick) a.pick[k0 + j] = n0 + chosen;
         __syncthreads();
-        double far = -1.0;
+        double far = -INFINITY;
         int arg = 0x7fffffff;
         constexpr int U = 4;      // rows in flight per thread
         for (int kb = tid; kb < ng; kb += U * kThreads) {
@@ -116,34 +155,27 @@ __global__ void __launch_bounds__(kThreads) seed_farthest_kernel(SeedArgs a) {
                         mk = old < acc[u] ? old : acc[u];
                     }
                     mind[k] = mk;
-                    // rows are visited in increasing order: a strict compare keeps the lowest
-                    if (mk > far) { far = mk; arg = k; }
+                    double v = mk;
+                    if (a.dsquared)
+                        v = need_key ? log(mk) + gumbel_variate(a.seed_lo, a.seed_hi, (unsigned)drawn,
+                                                                (unsigned)(drawn >> 32), n0 + k)
+                                     : 0.0;
+                    if (v > far || (v == far && k < arg)) { far = v; arg = k; }
                 }
             }
         }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const double of = __shfl_xor(far, o);
-            const int oa = __shfl_xor(arg, o);
-            if (of > far || (of == far && oa < arg)) { far = of; arg = oa; }
-        }
-        if ((tid & 63) == 0) { redv[tid >> 6] = far; redi[tid >> 6] = arg; }
-        __syncthreads();
-        if (tid == 0) {
-            for (int w = 1; w < kWaves; ++w)
-                if (redv[w] > far || (redv[w] == far && redi[w] < arg)) { far = redv[w]; arg = redi[w]; }
-            chosen_s = (arg >= 0 && arg < ng) ? arg : 0;
-        }
-        __syncthreads();
-        chosen = chosen_s;
+        chosen = block_argmax(far, arg);
     }
 }
 
 }  // namespace
 
-hipError_t launch_seed_farthest(const kb_batch& b, const float* X, float* cent, int32_t* pick,
-                                double* mind, const int32_t* order, hipStream_t st) {
+hipError_t launch_seed(const kb_batch& b, const float* X, float* cent, int32_t* pick, double* mind,
+                       const int32_t* order, int dsquared, uint64_t seed, uint64_t draw0,
+                       hipStream_t st) {
     SeedArgs a;
+    a.dsquared = dsquared; a.seed_lo = (unsigned)seed; a.seed_hi = (unsigned)(seed >> 32);
+    a.draw0 = draw0;
     a.G = b.G; a.D = b.D; a.Ksum = b.Ksum; a.N = b.N; a.seg_off = b.seg_off; a.koff = b.koff;
     a.X = X; a.cent = cent; a.pick = pick; a.mind = mind; a.order = order;
     hipLaunchKernelGGL(seed_farthest_kernel, dim3((unsigned)b.G), dim3(kThreads), 0, st, a);

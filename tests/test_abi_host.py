@@ -181,6 +181,8 @@ def test_loop_entry_points_argument_errors(L):
     assert kb.kb_seed_farthest(b, FAKE, FAKE, None, FAKE, 16, stream=0, check=False) == kb.KB_EWORKSPACE
     assert kb.kb_seed_farthest(_batch(D=65), FAKE, FAKE, None, FAKE, big, stream=0,
                                check=False) == kb.KB_EUNSUPPORTED
+    assert kb.kb_seed_dsquared(b, None, 1, 2, FAKE, FAKE, FAKE, big, stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_seed_dsquared(b, FAKE, 1, 2, FAKE, None, FAKE, 16, stream=0, check=False) == kb.KB_EWORKSPACE
     # signature draw
     assert kb.kb_sample_signature(b, sp, FAKE, None, 0, FAKE, FAKE, 0.75, FAKE, FAKE, FAKE, big,
                                   stream=0, check=False) == kb.KB_EINVAL

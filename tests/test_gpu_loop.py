@@ -278,3 +278,22 @@ def test_batch_without_candidates(kb):
     assert (ksel.cpu().numpy() == -1).all()
     assert (nvalid.cpu().numpy() == 0).all()
     assert (obj.cpu().numpy() == 0).all()
+
+
+def test_seed_dsquared_matches_oracle(kb, case):
+    name, b, _ = case
+    d = kb.DeviceBatch(b)
+    for seed, draw0 in ((20251118, 0), (3, 2 ** 33 + 5)):
+        d.cent2.fill_(-3.0)
+        d.rep.fill_(-7)
+        d.seed_dsquared(seed, draw0)
+        _sync()
+        want = oracle.seed_dsquared(b.seg_off, b.koff, b.X, seed, draw0)
+        ok = np.repeat(want.near == 0, np.diff(b.koff))
+        np.testing.assert_array_equal(d.host("rep")[ok], want.pick[ok], err_msg=name)
+        np.testing.assert_array_equal(d.host("cent2")[ok].view(np.uint32), want.cent[ok].view(np.uint32))
+        assert ok.mean() > 0.95
+        # searches the oracle flagged: still rows of their own search
+        pk = d.host("rep")
+        sid = np.repeat(np.arange(b.G), np.diff(b.koff))
+        assert ((pk >= b.seg_off[sid]) & (pk < b.seg_off[sid + 1])).all()
