@@ -368,3 +368,32 @@ def test_round_matches_oracle_and_composition(kb, case, scorer):
     for k in keys:
         a, c = got[k], d2.host(k)
         np.testing.assert_array_equal(a.view(np.uint8), c.view(np.uint8), err_msg=k)
+
+
+@pytest.mark.parametrize("shape", ["K64xS128", "K256xS32"])
+def test_ucb_at_the_table_limit(kb, shape):
+    """Largest cluster-arm tables the kernels take (Kmax * S = 8192)."""
+    import torch
+    if shape == "K64xS128":
+        b = synth.config5(G=3, nmin=1024, nmax=2000, S=128, seed=71)
+    else:
+        b = synth.config4(N=8192, K=256, S=32, ncentres=256)
+    assert b.Kmax * b.S == 8192
+    bound, alive = oracle.prune(b.seg_off, b.flops, b.bytes_, b.peak_flops, b.peak_bw, b.incumbent)
+    cl = oracle.cluster(b.seg_off, b.koff, b.X, 2)
+    d = kb.DeviceBatch(b)
+    d.assign.copy_(torch.from_numpy(cl.assign)); d.alive.copy_(torch.from_numpy(alive))
+    d.bound.copy_(torch.from_numpy(bound))
+    d.ucb_select()
+    _sync()
+    ora = oracle.ucb_select(b.seg_off, b.koff, b.S, cl.assign, alive, bound, b.visits, b.rsum,
+                            b.t, b.c)
+    np.testing.assert_array_equal(d.host("Ncs"), ora.Ncs)
+    assert_rel_close(d.host("mu"), ora.mu, what="mu")
+    assert_rel_close(d.host("ucb"), ora.ucb, what="ucb")
+    ok = ora.near == 0
+    np.testing.assert_array_equal(d.host("sel")[ok], ora.sel[ok])
+    # one more strategy is beyond the limit
+    bad = kb.make_batch(b.G, b.D, b.S + 1, b.N, b.Kmax, b.Ksum, b.Nmax, d.seg_off, d.koff)
+    assert kb.kb_ucb_select(bad, d.params, d.assign, d.alive, d.bound, d.visits, d.rsum, d.t, d.Ncs,
+                            d.mu, d.ucb, d.sel, d.ws, d.ws_bytes, check=False) == kb.KB_EUNSUPPORTED
