@@ -397,3 +397,34 @@ def test_ucb_at_the_table_limit(kb, shape):
     bad = kb.make_batch(b.G, b.D, b.S + 1, b.N, b.Kmax, b.Ksum, b.Nmax, d.seg_off, d.koff)
     assert kb.kb_ucb_select(bad, d.params, d.assign, d.alive, d.bound, d.visits, d.rsum, d.t, d.Ncs,
                             d.mu, d.ucb, d.sel, d.ws, d.ws_bytes, check=False) == kb.KB_EUNSUPPORTED
+
+
+def test_many_tiny_searches(kb):
+    """Twenty thousand searches of 1 to 40 candidates (one or two clusters each):
+    the per-search kernels run with mostly idle workgroups, the flat-range kernels
+    with hundreds of search pieces per range."""
+    b = synth.config5(G=20000, nmin=1, nmax=40, D=8, S=4, iters=4, seed=15)
+    assert int(np.diff(b.seg_off).min()) == 1
+    d = kb.DeviceBatch(b)
+    d.round()
+    d.sample(9, 1, 1.0)
+    d.cluster_geometry()
+    _sync()
+    ora = oracle.round_(b)
+    np.testing.assert_array_equal(d.host("alive"), ora.alive)
+    clean = ora.dirty == 0
+    cp = clean[search_of(b.seg_off)]
+    ck = np.repeat(clean, np.diff(b.koff))
+    np.testing.assert_array_equal(d.host("assign")[cp], ora.assign[cp])
+    np.testing.assert_array_equal(d.host("counts")[ck], ora.counts[ck])
+    assert_cent_close(d.host("cent")[ck], ora.cent[ck], "tiny")
+    ok = clean & (ora.near == 0)
+    np.testing.assert_array_equal(d.host("sel")[ok], ora.sel[ok])
+    assert clean.mean() > 0.95
+    s = oracle.sample(b.seg_off, d.host("assign"), d.host("alive"), d.host("bound"), b.incumbent,
+                      d.host("sel"), 9, 1, 1.0)
+    fine = s.near == 0
+    np.testing.assert_array_equal(d.host("ksel")[fine], s.ksel[fine])
+    g = oracle.cluster_geometry(b.seg_off, b.koff, b.X, d.host("cent"), d.host("assign"))
+    np.testing.assert_array_equal(d.host("rep"), g.rep)
+    np.testing.assert_array_equal(d.host("radius"), g.radius.astype(np.float32))
