@@ -238,6 +238,21 @@ def cluster_geometry(seg_off, koff, X, cent, assign_):
     return SimpleNamespace(rep=rep, radius=radius, dist2=dist2)
 
 
+def cluster_diameter(seg_off, koff, X, assign_):
+    """diam(C_i) of every cluster: largest member-to-member distance (fp64)."""
+    lib = _load()
+    seg_off = _c(seg_off, np.int32)
+    koff = _c(koff, np.int32)
+    X = _c(X, np.float32)
+    assign_ = _c(assign_, np.int32)
+    G = len(seg_off) - 1
+    N, D = X.shape
+    diam = np.zeros(int(koff[-1]), dtype=np.float64)
+    lib.kbo_cluster_diameter(ctypes.c_int32(G), ctypes.c_int32(D), _p(seg_off), _p(koff), _p(X),
+                             _p(assign_), _p(diam))
+    return diam
+
+
 def seed_farthest(seg_off, koff, X):
     """Farthest-point initial centroids.  Returns cent [Ksum, D] and pick [Ksum]
     (global candidate index of every chosen row)."""

@@ -25,6 +25,8 @@
  *   kbo_round        the three in sequence.
  *   kbo_cluster_geometry  the representative (centroid kernel) of each cluster
  *                    and the cluster radius (Sec. 3.3; Theorem 1's covering term).
+ *   kbo_cluster_diameter  the largest distance between two members of a cluster
+ *                    (diam(C_i) of Theorem 1).
  *   kbo_seed_farthest     farthest-point initial centroids (greedy cover; the
  *                    covering radius of Theorem 1's approximation term).
  *   kbo_seed_dsquared     randomised initial centroids drawn with probability
@@ -473,6 +475,35 @@ void kbo_cluster_geometry(int32_t G, int32_t D, const int32_t *seg_off,
         for (int32_t j = 0; j < K; ++j) radius[koff[g] + j] = sqrt(dmax[j]);
         free(dmin);
         free(dmax);
+    }
+}
+
+/* ----------------------------------------------------------- cluster diameters */
+
+/* diam(C_i) = the largest distance between two members of cluster i, the
+ * quantity in the approximation term L * max_i diam(C_i) of Theorem 1.  Plain
+ * definition: every pair of members, squared L2 distance in fp64 from direct
+ * differences, square root of the largest.  0 for clusters with fewer than two
+ * members. */
+void kbo_cluster_diameter(int32_t G, int32_t D, const int32_t *seg_off,
+                          const int32_t *koff, const float *X, const int32_t *assign,
+                          double *diam)
+{
+#pragma omp parallel for schedule(dynamic, 1) if (G > 1)
+    for (int32_t g = 0; g < G; ++g) {
+        const int32_t K = koff[g + 1] - koff[g];
+        for (int32_t j = 0; j < K; ++j) diam[koff[g] + j] = 0.0;
+        for (int32_t a = seg_off[g]; a < seg_off[g + 1]; ++a) {
+            const int32_t j = assign[a];
+            double far = 0.0;
+            for (int32_t b = a + 1; b < seg_off[g + 1]; ++b) {
+                if (assign[b] != j) continue;
+                const double d = sqdist(X + (size_t)a * D, X + (size_t)b * D, D);
+                if (d > far) far = d;
+            }
+            far = sqrt(far);
+            if (far > diam[koff[g] + j]) diam[koff[g] + j] = far;
+        }
     }
 }
 

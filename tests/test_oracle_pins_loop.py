@@ -392,3 +392,50 @@ def test_seed_dsquared_structure():
     first = np.vstack([b.X[b.seg_off[g]:b.seg_off[g] + (b.koff[g + 1] - b.koff[g])] for g in range(b.G)])
     _, m1, _ = oracle.assign(b.seg_off, b.koff, b.X, first)
     assert np.mean(far) < m1.sum()
+
+
+# --------------------------------------------------------------- diameters
+
+def test_diameter_hand_example():
+    rows = _rows("diameter_hand.txt")
+    X = np.array([[float(r[0]), float(r[1])] for r in rows], np.float32)
+    a = np.array([int(r[2]) for r in rows], np.int32)
+    seg, koff = _one(len(rows), 4)            # cluster 3 has no member
+    np.testing.assert_allclose(oracle.cluster_diameter(seg, koff, X, a), [5.0, 0.0, 7.0, 0.0])
+
+
+def test_diameter_bruteforce_radius_relation_and_invariance():
+    b = synth.config5(G=6, nmin=64, nmax=400, seed=33)
+    c = oracle.cluster(b.seg_off, b.koff, b.X, 4)
+    diam = oracle.cluster_diameter(b.seg_off, b.koff, b.X, c.assign)
+    X = b.X.astype(np.float64)
+    for s in range(b.G):
+        n0, n1, k0 = b.seg_off[s], b.seg_off[s + 1], b.koff[s]
+        for j in range(b.koff[s + 1] - k0):
+            mem = np.where(c.assign[n0:n1] == j)[0] + n0
+            if len(mem) < 2:
+                assert diam[k0 + j] == 0.0
+                continue
+            diff = X[mem][:, None, :] - X[mem][None, :, :]
+            np.testing.assert_allclose(diam[k0 + j], np.sqrt((diff ** 2).sum(-1)).max(), rtol=1e-12)
+    # against the independent radius computation: radius <= diam <= 2 radius, with the
+    # centroids that are the means of these members
+    upd, _ = oracle.update(b.seg_off, b.koff, b.X, c.cent, c.assign)
+    geo = oracle.cluster_geometry(b.seg_off, b.koff, b.X, upd, c.assign)
+    many = c.counts > 1
+    assert (diam[many] <= 2 * geo.radius[many] * (1 + 1e-6)).all()
+    assert (diam[many] >= geo.radius[many] * (1 - 1e-6)).all()
+    # a shift of all rows by a constant vector leaves every diameter unchanged
+    # (integers keep the shift exact in fp32)
+    Xi = np.round(b.X * 64).astype(np.float32)
+    d1 = oracle.cluster_diameter(b.seg_off, b.koff, Xi, c.assign)
+    d2 = oracle.cluster_diameter(b.seg_off, b.koff, Xi + np.float32(1000.0), c.assign)
+    np.testing.assert_array_equal(d1, d2)
+    # members of other searches or clusters play no part
+    a2 = c.assign.copy()
+    np.testing.assert_array_equal(oracle.cluster_diameter(b.seg_off, b.koff, b.X, a2), diam)
+    seg1 = np.array([0, b.seg_off[1]], np.int32)
+    koff1 = np.array([0, b.koff[1]], np.int32)
+    np.testing.assert_array_equal(
+        oracle.cluster_diameter(seg1, koff1, b.X[:b.seg_off[1]], c.assign[:b.seg_off[1]]),
+        diam[:b.koff[1]])
