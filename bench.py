@@ -152,6 +152,7 @@ def main():
             d.batch, sp, d.assign, None, R, dh, dtg, theta, d.sel, d.ksel, d.ws, d.ws_bytes), reps)[0]
         loop["update_stats"] = timed(lambda: kb.kb_update_stats(
             d.batch, d.params, d.sel, d.ksel, drw, dok, d.visits, d.rsum, d.Ncs, d.mu, d.t), reps)[0]
+        loop["cluster_diameter"] = timed(d.cluster_diameter, 3)[0]
         # optional farthest-point seeding: K_g passes over the rows of every search
         loop["seed_farthest"] = timed(d.seed_farthest, 3)[0]
         loop["seed_dsquared"] = timed(lambda: d.seed_dsquared(20251118, 0), 3)[0]

@@ -21,7 +21,7 @@
  *   kb_round         the three in sequence on one stream.
  *   kb_cluster_geometry, kb_strategy_mask, kb_ucb_select_masked,
  *   kb_sample_signature, kb_update_stats, kb_seed_farthest,
- *   kb_seed_dsquared
+ *   kb_seed_dsquared, kb_cluster_diameter
  *                    the remaining device-side steps of an iteration of Alg. 1:
  *                    cluster representatives, the mask in the paper's own form,
  *                    selection under that mask, the draw with the paper's
@@ -247,6 +247,16 @@ kb_status kb_sample_signature(const kb_batch *batch, const kb_sample_params *sp,
 kb_status kb_cluster_geometry(const kb_batch *batch, const float *X,
                               const float *cent, const int32_t *assign,
                               int32_t *rep, float *radius, void *ws,
+                              size_t ws_bytes, void *stream);
+
+/* diam(C_i), the largest distance between two members of cluster i (the quantity
+ * in the approximation term L * max_i diam(C_i) of Theorem 1): every pair of
+ * members, squared L2 distance from direct differences in fp32 (relative error
+ * of a distance below (D + 2) 2^-24), square root of the largest.  diam [Ksum]
+ * out; 0 for clusters with fewer than two members.  Work grows with the sum of
+ * the squared cluster sizes. */
+kb_status kb_cluster_diameter(const kb_batch *batch, const float *X,
+                              const int32_t *assign, float *diam, void *ws,
                               size_t ws_bytes, void *stream);
 
 /* Farthest-point initial centroids, an option beside "the first K rows" for the

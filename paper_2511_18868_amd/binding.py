@@ -88,6 +88,8 @@ def lib() -> ctypes.CDLL:
         L.kb_seed_farthest.argtypes = [pb, vp, vp, vp, vp, sz, vp]
         L.kb_seed_dsquared.restype = ctypes.c_int
         L.kb_seed_dsquared.argtypes = [pb, vp, ctypes.c_uint64, ctypes.c_uint64, vp, vp, vp, sz, vp]
+        L.kb_cluster_diameter.restype = ctypes.c_int
+        L.kb_cluster_diameter.argtypes = [pb, vp, vp, vp, vp, sz, vp]
         L.kb_status_str.restype = ctypes.c_char_p
         L.kb_status_str.argtypes = [ctypes.c_int]
         L.kb_version.restype = ctypes.c_char_p
@@ -228,6 +230,12 @@ def kb_seed_dsquared(batch, X, seed, draw0, cent, pick, ws, ws_bytes, stream=Non
     return _check(s, "kb_seed_dsquared", check)
 
 
+def kb_cluster_diameter(batch, X, assign, diam, ws, ws_bytes, stream=None, check=True):
+    s = lib().kb_cluster_diameter(ctypes.byref(batch), _ptr(X), _ptr(assign), _ptr(diam), _ptr(ws),
+                                  ws_bytes, _stream(stream))
+    return _check(s, "kb_cluster_diameter", check)
+
+
 def kb_set_scorer(mode: int) -> int:
     return int(lib().kb_set_scorer(int(mode)))
 
@@ -277,6 +285,7 @@ class DeviceBatch:
         self.ksel = z((G,), torch.int32)
         self.rep = z((Ksum,), torch.int32)
         self.radius = z((Ksum,), torch.float32)
+        self.diam = z((Ksum,), torch.float32)
         self.M = z((Ksum, S), torch.uint8)
         self.nvalid = z((G,), torch.int32)
         self.batch = make_batch(G, D, S, N, b.Kmax, Ksum, b.Nmax, self.seg_off, self.koff)
@@ -325,6 +334,10 @@ class DeviceBatch:
         return kb_seed_dsquared(self.batch, self.X, seed, draw0,
                                 self.cent2 if cent is None else cent,
                                 self.rep if pick else None, self.ws, self.ws_bytes, **kw)
+
+    def cluster_diameter(self, **kw):
+        return kb_cluster_diameter(self.batch, self.X, self.assign, self.diam, self.ws,
+                                   self.ws_bytes, **kw)
 
     def round(self, **kw):
         return kb_round(self.batch, self.params, self.io, self.ws, self.ws_bytes, **kw)

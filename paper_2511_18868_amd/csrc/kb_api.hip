@@ -34,6 +34,9 @@ WsLayout ws_layout(const kb_batch& b) {
         w.geo_d2 = off;  off += align256(8 * (size_t)(b.N > 0 ? b.N : 1));
         w.geo_min = off; off += align256(8 * k);
         w.geo_max = off; off += align256(8 * k);
+        w.dia_off = off; off += align256(4 * (k + 1));
+        w.dia_toff = off; off += align256(4 * (k + 1));
+        w.dia_bsum = off; off += align256(16 * (k / 4096 + 1));
     }
     {
         const size_t ranges = (size_t)((b.N + kSampleRange - 1) / kSampleRange) + 1;
@@ -258,6 +261,29 @@ kb_status kb_cluster_geometry(const kb_batch* batch, const float* X, const float
     c.gmin = (unsigned long long*)(base + w.geo_min);
     c.gmax = (unsigned long long*)(base + w.geo_max);
     return dev(launch_geometry(*batch, c, (hipStream_t)stream));
+}
+
+kb_status kb_cluster_diameter(const kb_batch* batch, const float* X, const int32_t* assign,
+                              float* diam, void* ws, size_t ws_bytes, void* stream) {
+    kb_status s = check_batch(batch);
+    if (s != KB_OK) return s;
+    if (!X || !assign || !diam) return KB_EINVAL;
+    if (!aligned(X, 16)) return KB_EINVAL;
+    if (batch->D > KB_MAX_D || batch->Kmax > KB_MAX_K) return KB_EUNSUPPORTED;
+    s = check_ws(batch, ws, ws_bytes);
+    if (s != KB_OK) return s;
+    WsLayout w = ws_layout(*batch);
+    char* base = (char*)ws;
+    DiameterCall c;
+    c.X = X; c.assign = assign; c.diam = diam;
+    // the grouped index list and the per-cluster counters live in buffers the
+    // clustering and the representative pass use at other times
+    c.perm = (int32_t*)(base + w.a_new);
+    c.cnt = (int32_t*)(base + w.geo_min);
+    c.off = (int32_t*)(base + w.dia_off);
+    c.toff = (int32_t*)(base + w.dia_toff);
+    c.bsum = (long long*)(base + w.dia_bsum);
+    return dev(launch_diameter(*batch, c, (hipStream_t)stream));
 }
 
 static kb_status do_seed(const kb_batch* batch, const float* X, float* cent, int32_t* pick,

@@ -40,6 +40,9 @@ struct WsLayout {
     size_t geo_d2;     // double [N]     squared distance of every candidate to its centroid
     size_t geo_min;    // uint64 [Ksum]  bit pattern of the smallest such distance per cluster
     size_t geo_max;    // uint64 [Ksum]  and of the largest
+    size_t dia_off;    // int32 [Ksum + 1] first slot of every cluster in the grouped index list
+    size_t dia_toff;   // int32 [Ksum + 1] first tile of every cluster in the global tile numbering
+    size_t dia_bsum;   // int64 [2 * (Ksum / 4096 + 1)] block sums of the two prefix sums
     size_t samp_key;   // double [2*ranges]  partial best keys of searches that cross range borders
     size_t samp_idx;   // int32  [2*ranges]  their candidates
     size_t total;
@@ -128,6 +131,18 @@ struct GeoCall {
 };
 hipError_t launch_geometry(const kb_batch& b, const GeoCall& c, hipStream_t st);
 size_t geometry_lds_bytes(int Kmax, int D);
+
+struct DiameterCall {
+    const float* X;
+    const int32_t* assign;
+    float* diam;
+    int32_t* cnt;     // [Ksum]
+    int32_t* off;     // [Ksum + 1]
+    int32_t* toff;    // [Ksum + 1]
+    long long* bsum;  // [2 * (Ksum / 4096 + 1)]
+    int32_t* perm;    // [N]
+};
+hipError_t launch_diameter(const kb_batch& b, const DiameterCall& c, hipStream_t st);
 
 hipError_t launch_seed(const kb_batch& b, const float* X, float* cent, int32_t* pick, double* mind,
                        const int32_t* order, int dsquared, uint64_t seed, uint64_t draw0,

@@ -174,6 +174,10 @@ def test_loop_entry_points_argument_errors(L):
         bad = list(u); bad[i] = None
         assert kb.kb_update_stats(b, p, *bad, stream=0, check=False) == kb.KB_EINVAL
     assert kb.kb_update_stats(b, kb.make_params(prior_n=-1.0), *u, stream=0, check=False) == kb.KB_EINVAL
+    # diameters: X, assign, diam
+    assert kb.kb_cluster_diameter(b, None, FAKE, FAKE, FAKE, big, stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_cluster_diameter(b, FAKE, FAKE, None, FAKE, big, stream=0, check=False) == kb.KB_EINVAL
+    assert kb.kb_cluster_diameter(b, FAKE, FAKE, FAKE, FAKE, 16, stream=0, check=False) == kb.KB_EWORKSPACE
     # farthest-point seeds: X, cent, pick (pick may be NULL)
     assert kb.kb_seed_farthest(b, None, FAKE, FAKE, FAKE, big, stream=0, check=False) == kb.KB_EINVAL
     assert kb.kb_seed_farthest(b, FAKE, None, FAKE, FAKE, big, stream=0, check=False) == kb.KB_EINVAL

@@ -92,6 +92,34 @@ def _loop_steps_vs_oracle(kb, b, d, name, ora=None, ok=None):
     np.testing.assert_array_equal(d.host("radius"), g.radius.astype(np.float32), err_msg=name + " radius")
     print(f"[{name}] draw compared on {int(fine.sum())} of {b.G} searches, representatives and "
           f"radii exact on {b.Ksum} clusters", flush=True)
+    # diameters: all clusters where the pair loop of the oracle is affordable, otherwise
+    # a few clusters taken out as searches of their own
+    d.cluster_diameter()
+    _sync()
+    diam = d.host("diam")
+    cnt = np.bincount(np.repeat(b.koff[:-1], np.diff(b.seg_off)) + a, minlength=b.Ksum)
+    if float((cnt.astype(np.float64) ** 2).sum()) < 5e8:
+        assert_rel_close(diam, oracle.cluster_diameter(b.seg_off, b.koff, b.X, a), what=name + " diameter")
+        checked = b.Ksum
+    else:
+        rng = np.random.default_rng(1)
+        checked = 0
+        for j in rng.choice(b.Ksum, size=3, replace=False):
+            g = int(np.searchsorted(b.koff, j, side="right") - 1)
+            mem = np.where(a[b.seg_off[g]:b.seg_off[g + 1]] == j - b.koff[g])[0] + b.seg_off[g]
+            mem = mem[:6000]          # the diameter of a subset is a lower bound ...
+            sub = oracle.cluster_diameter(np.array([0, len(mem)], np.int32), np.array([0, 1], np.int32),
+                                          b.X[mem], np.zeros(len(mem), np.int32))[0]
+            if len(mem) == cnt[j]:
+                assert_rel_close(diam[j:j + 1], np.array([sub]), what=name + " diameter")
+                checked += 1
+            else:
+                assert diam[j] >= sub * (1 - 1e-5)
+        # ... and on every cluster: radius <= diameter <= 2 radius
+    rad = d.host("radius")
+    many = cnt > 1
+    assert (diam[many] <= 2 * rad[many] * (1 + 1e-5)).all() and (diam[many] >= rad[many] * (1 - 1e-5)).all()
+    print(f"[{name}] diameters compared on {checked} clusters, bracketed by the radii on all", flush=True)
 
 
 def test_config3_full(kb):

@@ -297,3 +297,27 @@ def test_seed_dsquared_matches_oracle(kb, case):
         pk = d.host("rep")
         sid = np.repeat(np.arange(b.G), np.diff(b.koff))
         assert ((pk >= b.seg_off[sid]) & (pk < b.seg_off[sid + 1])).all()
+
+
+def test_cluster_diameter(kb, case):
+    name, b, c = case
+    if name == "bigN":
+        # eight clusters of about 9000 members: the oracle's pair loop takes too long here;
+        # thinned to every fifth row the structure (members spread over 18 ranges) stays
+        keep = np.arange(0, b.N, 5)
+        b2 = synth.config2(N=len(keep), D=16, K=8, S=4, iters=2, seed=5)
+        b2.X = np.ascontiguousarray(b.X[keep])
+        b, c = b2, oracle.cluster(b2.seg_off, b2.koff, b2.X, 2)
+    d = kb.DeviceBatch(b)
+    d.assign.copy_(_up(d, c.assign))
+    d.diam.fill_(-1.0)
+    d.cluster_diameter()
+    _sync()
+    first = d.host("diam").copy()
+    want = oracle.cluster_diameter(b.seg_off, b.koff, b.X, c.assign)
+    assert_rel_close(first, want, what=name + " diameter")
+    assert (first[c.counts < 2] == 0).all()
+    # the grouping order varies from run to run, the result does not
+    d.cluster_diameter()
+    _sync()
+    np.testing.assert_array_equal(d.host("diam").view(np.uint32), first.view(np.uint32))

@@ -428,3 +428,7 @@ def test_many_tiny_searches(kb):
     g = oracle.cluster_geometry(b.seg_off, b.koff, b.X, d.host("cent"), d.host("assign"))
     np.testing.assert_array_equal(d.host("rep"), g.rep)
     np.testing.assert_array_equal(d.host("radius"), g.radius.astype(np.float32))
+    d.cluster_diameter()
+    _sync()
+    assert_rel_close(d.host("diam"), oracle.cluster_diameter(b.seg_off, b.koff, b.X, d.host("assign")),
+                     what="diameter")
