@@ -419,35 +419,30 @@ __device__ __forceinline__ void tile_scores(const bf16x8 (&Bh)[DS], const bf16x8
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[0][r] += acc[1][r];
     }
-    // Best, second best and the row of the best among this lane's rows: four
-    // independent chains of 8 (or 4) values, merged pairwise.  The
-    // lane-dependent part of the row number (4h) is added afterwards.
-    float cb[4], cs[4];
-    int ci[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) { cb[c] = kBig * 4.f; cs[c] = kBig * 4.f; ci[c] = 0; }
+    // Best and second best among this lane's rows with three vector instructions per
+    // score: the score's position replaces its 5 lowest mantissa bits (which moves
+    // it by less than 2^-18 of itself - part of the error bound), then a
+    // median-of-three and a minimum; the row of the best is read back from those
+    // bits.  Two independent chains; the lane-dependent part of the row number
+    // (4h) is added afterwards.
+    float cb[2] = {kBig * 8.f, kBig * 8.f}, cs[2] = {kBig * 8.f, kBig * 8.f};
     if (two) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
-                const int c = 2 * t + (r >> 3);
-                const float v = acc[t][r];
-                const bool lt = v < cb[c];
-                cs[c] = __builtin_amdgcn_fmed3f(cb[c], cs[c], v);
-                cb[c] = lt ? v : cb[c];
-                ci[c] = lt ? (t * 32 + 8 * (r >> 2) + (r & 3)) : ci[c];
+                const float v = __uint_as_float((__float_as_uint(acc[t][r]) & 0xffffffe0u) | (unsigned)(16 * t + r));
+                cs[t] = __builtin_amdgcn_fmed3f(cb[t], cs[t], v);
+                cb[t] = vmin(cb[t], v);
             }
         }
     } else {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int c = r >> 2;
-            const float v = acc[0][r];
-            const bool lt = v < cb[c];
+            const int c = r & 1;
+            const float v = __uint_as_float((__float_as_uint(acc[0][r]) & 0xffffffe0u) | (unsigned)r);
             cs[c] = __builtin_amdgcn_fmed3f(cb[c], cs[c], v);
-            cb[c] = lt ? v : cb[c];
-            ci[c] = lt ? (8 * (r >> 2) + (r & 3)) : ci[c];
+            cb[c] = vmin(cb[c], v);
         }
     }
     auto merge = [](float& b1, float& s1, int& i1, float b2, float s2, int i2) {
@@ -458,11 +453,12 @@ __device__ __forceinline__ void tile_scores(const bf16x8 (&Bh)[DS], const bf16x8
         i1 = take ? i2 : i1;
         b1 = take ? b2 : b1;
     };
-    merge(cb[0], cs[0], ci[0], cb[1], cs[1], ci[1]);
-    merge(cb[2], cs[2], ci[2], cb[3], cs[3], ci[3]);
-    merge(cb[0], cs[0], ci[0], cb[2], cs[2], ci[2]);
-    best = cb[0]; second = cs[0];
-    bi = ci[0] + 4 * h;
+    best = vmin(cb[0], cb[1]);
+    second = vmin(vmin(cs[0], cs[1]), vmax(cb[0], cb[1]));
+    {
+        const int code = (int)(__float_as_uint(best) & 31u);
+        bi = (code >> 4) * 32 + 8 * ((code & 15) >> 2) + (code & 3) + 4 * h;
+    }
     // the two half-waves hold complementary centroid rows of the same
     // candidate: one lane-swap per value hands both halves both results
     {
@@ -551,7 +547,9 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
         tile_scores<DS, MT>(Bh, Bm, cn, aop, mtiles, lane, best, second, bi);
         bi = bi < K ? bi : 0;
         const float E = kappa * (xn + cnmax);
-        const bool certain = (K == 1) || ((second - best) > 2.f * E);
+        // (a best score next to zero may have lost its position bits to a flush of
+        // subnormal numbers: that candidate goes to the exact pass)
+        const bool certain = (K == 1) || (((second - best) > 2.f * E) && fabsf(best) > 1.0e-30f);
         const bool chg = valid && certain && (bi != old);
         // Candidates that change cluster: lanes 0..31 (one per candidate) fix counts
         // and flags; then the wave takes the movers eight at a time, lanes over
@@ -701,7 +699,9 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
         tile_scores<DS, MT>(Bh, Bm, cn, aop, mtiles, lane, best, second, bi);
         bi = bi < K ? bi : 0;
         const float E = kappa * (xn + cnmax);
-        const bool certain = (K == 1) || ((second - best) > 2.f * E);
+        // (a best score next to zero may have lost its position bits to a flush of
+        // subnormal numbers: that candidate goes to the exact pass)
+        const bool certain = (K == 1) || (((second - best) > 2.f * E) && fabsf(best) > 1.0e-30f);
         const bool chg = valid && certain;
         const unsigned long long cmask = __ballot(chg && h == 0);
         if (cmask) {

@@ -246,20 +246,6 @@ __global__ void __launch_bounds__(kThreads) big_renew(BigArgs a) {
 // decides whether the nearest centroid is certain, and writes the proposal.
 constexpr int kGroupTiles = 4;     // candidate tiles staged in LDS at a time
 
-// Plain v_min_f32 / v_max_f32.  (fminf would first quiet a signalling NaN with one
-// more instruction per operand, because the compiler cannot see that scores
-// with rewritten low bits are ordinary numbers.)
-__device__ __forceinline__ float vmin(float x, float y) {
-    float r;
-    asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
-    return r;
-}
-__device__ __forceinline__ float vmax(float x, float y) {
-    float r;
-    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
-    return r;
-}
-
 template <int DS>
 __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -319,9 +305,7 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
         }
     }
     const float cnmax = __uint_as_float(a.cnmax_bits[(a.it & 1) * a.G + g]);
-    // error bound of a score: the matrix-core products, plus the position bits
-    // (|score| <= 2 (|x|^2 + max |c|^2), moved by less than 2^-18 of itself)
-    const float kappa = mfma_kappa(DS) + 7.62939453125e-06f;
+    const float kappa = mfma_kappa(DS);    // matrix-core products and position bits
     const bf16x8* sp = a.split + (size_t)tb * kTileUnits;
 
     // copy of a group of tiles: global -> registers (early) -> LDS (when the

@@ -59,9 +59,26 @@ __device__ __forceinline__ void merge_best(float& b1, float& s1, int& i1, float 
     b1 = take ? b2 : b1;
 }
 
-// error bound factor of the matrix-core scores, see the scorer's comment
+// error bound factor of the matrix-core scores, see the scorer's comment; the last
+// term covers the position bits written into a score (|score| <= 2 (|x|^2 + max |c|^2),
+// moved by less than 2^-18 of itself)
 __device__ __forceinline__ float mfma_kappa(int DS) {
-    return 3.1f * 1.52587890625e-05f + (float)(3 * 16 * DS + 4) * 2.384185791015625e-07f;
+    return 3.1f * 1.52587890625e-05f + (float)(3 * 16 * DS + 4) * 2.384185791015625e-07f +
+           7.62939453125e-06f;
+}
+
+// Plain v_min_f32 / v_max_f32.  (fminf would first quiet a signalling NaN with one
+// more instruction per operand, because the compiler cannot see that scores
+// with rewritten low bits are ordinary numbers.)
+__device__ __forceinline__ float vmin(float x, float y) {
+    float r;
+    asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
+    return r;
+}
+__device__ __forceinline__ float vmax(float x, float y) {
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
+    return r;
 }
 
 }  // namespace kb
