@@ -391,18 +391,24 @@ __device__ __forceinline__ void tile_scores(const bf16x8 (&Bh)[DS], const bf16x8
             acc[1][4 * g4 + 0] = c4.x; acc[1][4 * g4 + 1] = c4.y;
             acc[1][4 * g4 + 2] = c4.z; acc[1][4 * g4 + 3] = c4.w;
         }
+        // the first tile of centroids is finished before the second one is started, so
+        // that the vector unit can take its minimum while the matrix cores work on
+        // the second
 #pragma unroll
         for (int s = 0; s < DS; ++s) {
             // centroid operands of this K-step, straight from LDS (operand order)
             const bf16x8 a0h = aop[((0 * DS + s) * 2 + 0) * 64 + lane];
             const bf16x8 a0m = aop[((0 * DS + s) * 2 + 1) * 64 + lane];
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bh[s], acc[0], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bm[s], acc[0], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0m, Bh[s], acc[0], 0, 0, 0);
+        }
+#pragma unroll
+        for (int s = 0; s < DS; ++s) {
             const bf16x8 a1h = aop[((1 * DS + s) * 2 + 0) * 64 + lane];
             const bf16x8 a1m = aop[((1 * DS + s) * 2 + 1) * 64 + lane];
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bh[s], acc[0], 0, 0, 0);
             acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, Bh[s], acc[1], 0, 0, 0);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, Bm[s], acc[0], 0, 0, 0);
             acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, Bm[s], acc[1], 0, 0, 0);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0m, Bh[s], acc[0], 0, 0, 0);
             acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1m, Bh[s], acc[1], 0, 0, 0);
         }
     } else {
@@ -428,12 +434,21 @@ __device__ __forceinline__ void tile_scores(const bf16x8 (&Bh)[DS], const bf16x8
     float cb[2] = {kBig * 8.f, kBig * 8.f}, cs[2] = {kBig * 8.f, kBig * 8.f};
     if (two) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
+        for (int t = 0; t < 2; ++t) {
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
+            for (int r = 0; r < 16; ++r) {
                 const float v = __uint_as_float((__float_as_uint(acc[t][r]) & 0xffffffe0u) | (unsigned)(16 * t + r));
                 cs[t] = __builtin_amdgcn_fmed3f(cb[t], cs[t], v);
                 cb[t] = vmin(cb[t], v);
+            }
+            if (t == 0) {
+                // one matrix instruction of the second tile to five vector instructions of
+                // the first tile's minimum
+#pragma unroll
+                for (int q = 0; q < 3 * DS; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+                }
             }
         }
     } else {
