@@ -43,6 +43,11 @@ WsLayout ws_layout(const kb_batch& b) {
         w.samp_key = off; off += align256(8 * 2 * ranges);
         w.samp_idx = off; off += align256(4 * 2 * ranges);
     }
+    {
+        const size_t ranges = seed_ranges(b);
+        w.seed_key = off; off += align256(8 * 4 * ranges);
+        w.seed_idx = off; off += align256(4 * 4 * ranges);
+    }
     w.total = off;
     return w;
 }
@@ -302,8 +307,9 @@ static kb_status do_seed(const kb_batch* batch, const float* X, float* cent, int
     hipStream_t st = (hipStream_t)stream;
     hipError_t e = launch_order(*batch, order, (int32_t*)(base + w.tile_off), nullptr, st);
     if (e != hipSuccess) return KB_EDEVICE;
-    return dev(launch_seed(*batch, X, cent, pick, (double*)(base + w.geo_d2), order, dsquared, seed,
-                           draw0, st));
+    return dev(launch_seed(*batch, X, cent, pick, (double*)(base + w.geo_d2),
+                           (double*)(base + w.seed_key), (int32_t*)(base + w.seed_idx), order,
+                           dsquared, seed, draw0, st));
 }
 
 kb_status kb_seed_farthest(const kb_batch* batch, const float* X, float* cent, int32_t* pick,

@@ -256,6 +256,21 @@ __device__ __forceinline__ void score_valu(const ClusterArgs& a, const float* __
 // scorer reads them with conflict-free 16-byte loads.  Only rows whose membership
 // changed are touched (`init`: every row, nothing renewed; rows >= K get zero
 // operands).  Returns this thread's view of max_j |c_j|^2.
+// fp32 rounding of the correctly rounded fp64 quotient t / c, from one reciprocal
+// rc = 1 / c shared by a row's features.  t * rc lies within 2^-52 (relative) of
+// t / c, and so does the rounded quotient; the two round to the same fp32 unless
+// an fp32 rounding boundary - a 1 followed by 28 zeros in the low 29 mantissa
+// bits - lies within 2^-51 (at most 4 units of the last place) of t * rc.  Then,
+// and for results near the subnormal fp32 range where the boundaries sit
+// elsewhere, the quotient itself is formed.
+__device__ __forceinline__ float mean_f32(double t, double c, double rc) {
+    const double q = t * rc;
+    const unsigned low = (unsigned)__double_as_longlong(q) & 0x1fffffffu;
+    const unsigned off = low - 0x10000000u + 8u;
+    if (off <= 16u || (fabs(q) < 0x1p-100 && t != 0.0)) return (float)(t / c);
+    return (float)q;
+}
+
 template <int DS, bool OPERANDS>
 __device__ __forceinline__ float renew_rows(float* cent, float* cn, bf16x8* aop, const long long* sums,
                                             const int* cnt, int* dirty, float* delta, int K, int D,
@@ -276,10 +291,11 @@ __device__ __forceinline__ float renew_rows(float* cent, float* cn, bf16x8* aop,
         double mv = 0.0;
         if (renew && infeat) {
             float* vp = &v.x;
+            const double cd = (double)c, rc = 1.0 / cd;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 if (d0 + i < D) {
-                    const float cnew = (float)(((double)sums[(size_t)j * SP + d0 + i] * inv) / (double)c);
+                    const float cnew = mean_f32((double)sums[(size_t)j * SP + d0 + i] * inv, cd, rc);
                     const double df = (double)cnew - (double)vp[i];
                     mv += df * df;
                     vp[i] = cnew;
@@ -291,7 +307,10 @@ __device__ __forceinline__ float renew_rows(float* cent, float* cn, bf16x8* aop,
         if (!init) {
             mv = row_sum_d(mv);
             if (real && l16 == 0) {
-                delta[j] = renew ? (float)sqrt(mv) * 1.0000005f : 0.f;
+                // rounded up: the fp32 square root is within 2^-23 of the true one
+                delta[j] = !renew ? 0.f
+                           : mv < 1.0e-30 ? (float)sqrt(mv) * 1.0000005f
+                                          : sqrtf((float)mv) * 1.0000005f;
                 dirty[j] = 0;
             }
         }

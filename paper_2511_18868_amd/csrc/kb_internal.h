@@ -45,6 +45,9 @@ struct WsLayout {
     size_t dia_bsum;   // int64 [2 * (Ksum / 4096 + 1)] block sums of the two prefix sums
     size_t samp_key;   // double [2*ranges]  partial best keys of searches that cross range borders
     size_t samp_idx;   // int32  [2*ranges]  their candidates
+    size_t seed_key;   // double [4*ranges]  seeding of long searches: best key of every range, two
+                       //                    slots, two alternating sets
+    size_t seed_idx;   // int32  [4*ranges]  and its row
     size_t total;
 };
 WsLayout ws_layout(const kb_batch& b);
@@ -144,9 +147,11 @@ struct DiameterCall {
 };
 hipError_t launch_diameter(const kb_batch& b, const DiameterCall& c, hipStream_t st);
 
+// number of candidate ranges of the launch-per-centroid seeding (sizes skey / sidx: 4 per range)
+size_t seed_ranges(const kb_batch& b);
 hipError_t launch_seed(const kb_batch& b, const float* X, float* cent, int32_t* pick, double* mind,
-                       const int32_t* order, int dsquared, uint64_t seed, uint64_t draw0,
-                       hipStream_t st);
+                       double* skey, int32_t* sidx, const int32_t* order, int dsquared,
+                       uint64_t seed, uint64_t draw0, hipStream_t st);
 
 hipError_t launch_strategy_mask(const kb_batch& b, int R, const float* h, const int32_t* target,
                                 const int32_t* rep, float theta_sat, uint8_t* M, int32_t* nvalid,

@@ -321,3 +321,31 @@ def test_cluster_diameter(kb, case):
     d.cluster_diameter()
     _sync()
     np.testing.assert_array_equal(d.host("diam").view(np.uint32), first.view(np.uint32))
+
+
+@pytest.mark.parametrize("D", [12, 7, 64])
+def test_seeds_of_mixed_search_lengths(kb, D):
+    # short searches (one workgroup each, rows in registers, the longer ones partly
+    # streamed) next to long ones (one launch per centroid) in one batch, the long
+    # ones ending and beginning inside the same candidate range
+    b = synth.config5(G=14, nmin=64, nmax=12000, D=D, S=3, seed=5)
+    ng = np.diff(b.seg_off)
+    assert (ng > 4096).sum() >= 3 and (ng <= 4096).sum() >= 3
+    assert ng[0] > 4096 and ng[1] > 4096 and b.seg_off[1] % 1024 != 0
+    d = kb.DeviceBatch(b)
+    d.cent2.fill_(-3.0)
+    d.rep.fill_(-7)
+    d.seed_farthest()
+    _sync()
+    want = oracle.seed_farthest(b.seg_off, b.koff, b.X)
+    np.testing.assert_array_equal(d.host("rep"), want.pick)
+    np.testing.assert_array_equal(d.host("cent2").view(np.uint32), want.cent.view(np.uint32))
+    d.cent2.fill_(-3.0)
+    d.rep.fill_(-7)
+    d.seed_dsquared(11, 5)
+    _sync()
+    want = oracle.seed_dsquared(b.seg_off, b.koff, b.X, 11, 5)
+    ok = np.repeat(want.near == 0, np.diff(b.koff))
+    assert ok.mean() > 0.9
+    np.testing.assert_array_equal(d.host("rep")[ok], want.pick[ok])
+    np.testing.assert_array_equal(d.host("cent2")[ok].view(np.uint32), want.cent[ok].view(np.uint32))
