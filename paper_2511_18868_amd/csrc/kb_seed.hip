@@ -38,6 +38,13 @@ constexpr int kRange = 1024;       // its rows per workgroup (at most kBigRows, 
                                    // it, one that begins inside)
 constexpr int kBigThreads = 256;
 constexpr int kNone = 0x7fffffff;
+// rows a workgroup keeps in LDS after the registers are full: padded to 16 DS + 4
+// words (16-byte reads of consecutive rows fall into different banks), at most
+// two per thread, within 155 KB
+constexpr int lds_stride(int DS) { return 16 * DS + 4; }
+constexpr int lds_rows(int DS) {
+    return 158720 / (4 * lds_stride(DS)) < 2 * kThreads ? 158720 / (4 * lds_stride(DS)) : 2 * kThreads;
+}
 
 struct SeedArgs {
     int G, D, Ksum;
@@ -71,6 +78,8 @@ __device__ __forceinline__ double add_sq(double acc, float x, double c) {
 template <int DS, int R, bool DSQ>
 __global__ void __launch_bounds__(kThreads) seed_farthest_kernel(SeedArgs a) {
     constexpr int Q = 4 * DS;
+    constexpr int RS = lds_stride(DS), LROWS = lds_rows(DS), LV = (LROWS + kThreads - 1) / kThreads;
+    extern __shared__ __align__(16) float lx[];        // [LROWS][RS]
     __shared__ __align__(16) float c[16 * DS];
     __shared__ double redv[kWaves];
     __shared__ int redi[kWaves];
@@ -147,6 +156,33 @@ __global__ void __launch_bounds__(kThreads) seed_farthest_kernel(SeedArgs a) {
         mk[u] = INFINITY;
     }
 
+    // the next LROWS rows go to LDS, row R * 512 + tid + 512 v to thread tid
+    double ml[LV];
+#pragma unroll
+    for (int v = 0; v < LV; ++v) {
+        const int sl = tid + v * kThreads, k = R * kThreads + sl;
+        ml[v] = INFINITY;
+        if (sl < LROWS && k < ng) {
+            const float* row = Xg + (size_t)k * D;
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const int d = 4 * q;
+                float4 x4 = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (d < D) {
+                    if (vec) {
+                        x4 = *reinterpret_cast<const float4*>(row + d);
+                    } else {
+                        x4.x = row[d];
+                        if (d + 1 < D) x4.y = row[d + 1];
+                        if (d + 2 < D) x4.z = row[d + 2];
+                        if (d + 3 < D) x4.w = row[d + 3];
+                    }
+                }
+                *reinterpret_cast<float4*>(lx + (size_t)sl * RS + d) = x4;
+            }
+        }
+    }
+
     int chosen = 0;
     if constexpr (DSQ) {
         // first centroid: a uniform draw, i.e. the largest variate of draw number draw0
@@ -175,7 +211,9 @@ __global__ void __launch_bounds__(kThreads) seed_farthest_kernel(SeedArgs a) {
                 }
             }
         } else if (tid < 16 * DS) {
-            c[tid] = tid < D ? Xg[(size_t)chosen * D + tid] : 0.f;
+            c[tid] = chosen < R * kThreads + LROWS ? lx[(size_t)(chosen - R * kThreads) * RS + tid]
+                     : tid < D                     ? Xg[(size_t)chosen * D + tid]
+                                                   : 0.f;
             if (tid == 0 && a.pick) a.pick[k0 + j] = n0 + chosen;
         }
         __syncthreads();
@@ -217,9 +255,40 @@ __global__ void __launch_bounds__(kThreads) seed_farthest_kernel(SeedArgs a) {
                 }
             }
         }
-        // rows beyond the registers' share
+        // rows in LDS
+        if ((tid & ~63) + R * kThreads < ng) {
+            double acc[LV];
+#pragma unroll
+            for (int v = 0; v < LV; ++v) acc[v] = 0.0;
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                if (4 * q < D) {
+                    const float4 cv = *reinterpret_cast<const float4*>(c + 4 * q);
+                    const double cx = (double)cv.x, cy = (double)cv.y, cz = (double)cv.z, cw = (double)cv.w;
+#pragma unroll
+                    for (int v = 0; v < LV; ++v) {
+                        // (a slot beyond the search's rows is read all the same: inside the array)
+                        const int sl = tid + v * kThreads < LROWS ? tid + v * kThreads : tid;
+                        const float4 x4 = *reinterpret_cast<const float4*>(lx + (size_t)sl * RS + 4 * q);
+                        acc[v] = add_sq(acc[v], x4.x, cx);
+                        acc[v] = add_sq(acc[v], x4.y, cy);
+                        acc[v] = add_sq(acc[v], x4.z, cz);
+                        acc[v] = add_sq(acc[v], x4.w, cw);
+                    }
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < LV; ++v) {
+                const int sl = tid + v * kThreads, k = R * kThreads + sl;
+                if (sl < LROWS && k < ng) {
+                    ml[v] = ml[v] < acc[v] ? ml[v] : acc[v];
+                    offer(ml[v], k, need_key, drawn, far, arg);
+                }
+            }
+        }
+        // rows beyond the registers' and the LDS's share
         constexpr int U = 2;      // rows in flight per thread
-        for (int kb = tid + R * kThreads; kb < ng; kb += U * kThreads) {
+        for (int kb = tid + R * kThreads + LROWS; kb < ng; kb += U * kThreads) {
             double acc[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) acc[u] = 0.0;
@@ -452,14 +521,19 @@ hipError_t launch_seed(const kb_batch& b, const float* X, float* cent, int32_t* 
     a.X = X; a.cent = cent; a.pick = pick; a.mind = mind; a.order = order;
     a.skey = skey; a.sidx = sidx; a.nranges = (int)seed_ranges(b);
     const dim3 grid((unsigned)b.G), block(kThreads);
-    auto go = [&](auto far, auto dsq) {
-        if (dsquared) hipLaunchKernelGGL(dsq, grid, block, 0, st, a);
-        else hipLaunchKernelGGL(far, grid, block, 0, st, a);
+    hipError_t err = hipSuccess;
+    auto go = [&](auto far, auto dsq, int DS) {
+        const size_t lds = (size_t)4 * lds_stride(DS) * lds_rows(DS);
+        auto kern = dsquared ? dsq : far;
+        err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (err == hipSuccess) hipLaunchKernelGGL(kern, grid, block, lds, st, a);
     };
-    if (b.D <= 16) go(seed_farthest_kernel<1, 8, false>, seed_farthest_kernel<1, 8, true>);
-    else if (b.D <= 32) go(seed_farthest_kernel<2, 6, false>, seed_farthest_kernel<2, 6, true>);
-    else if (b.D <= 48) go(seed_farthest_kernel<3, 4, false>, seed_farthest_kernel<3, 4, true>);
-    else go(seed_farthest_kernel<4, 3, false>, seed_farthest_kernel<4, 3, true>);
+    if (b.D <= 16) go(seed_farthest_kernel<1, 8, false>, seed_farthest_kernel<1, 8, true>, 1);
+    else if (b.D <= 32) go(seed_farthest_kernel<2, 6, false>, seed_farthest_kernel<2, 6, true>, 2);
+    else if (b.D <= 48) go(seed_farthest_kernel<3, 4, false>, seed_farthest_kernel<3, 4, true>, 3);
+    else go(seed_farthest_kernel<4, 3, false>, seed_farthest_kernel<4, 3, true>, 4);
+    if (err != hipSuccess) return err;
     if (b.Nmax > kBigRows) {
         const dim3 bgrid((unsigned)a.nranges), bblock(kBigThreads);
         int launches = 0;
