@@ -153,12 +153,16 @@ def main():
         loop["update_stats"] = timed(lambda: kb.kb_update_stats(
             d.batch, d.params, d.sel, d.ksel, drw, dok, d.visits, d.rsum, d.Ncs, d.mu, d.t), reps)[0]
         loop["cluster_diameter"] = timed(d.cluster_diameter, 3)[0]
-        # optional farthest-point seeding: K_g passes over the rows of every search
+        # optional farthest-point seeding: K_g dependent passes over the rows of every
+        # search, which stay on chip
         loop["seed_farthest"] = timed(d.seed_farthest, 3)[0]
         loop["seed_dsquared"] = timed(lambda: d.seed_dsquared(20251118, 0), 3)[0]
         loop = {k: round(v, 4) for k, v in loop.items()}
         nk_rows = float(np.sum(np.diff(b.seg_off).astype(np.float64) * np.diff(b.koff)))
-        loop["seed_farthest_GBs"] = round(nk_rows * (4 * b.D + 16) / (loop["seed_farthest"] * 1e-3) / 1e9, 1)
+        # four fp64-rate vector instructions (widen, subtract, multiply, add) per feature,
+        # row and pass against 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
+        loop["seed_farthest_fp64_frac"] = round(
+            nk_rows * 4 * b.D / (loop["seed_farthest"] * 1e-3) / (256 * 4 * 16 * 2.4e9), 3)
         # representatives: every feature row and assignment read once
         loop["cluster_geometry_GBs"] = round(
             b.N * (4 * b.D + 4) / (loop["cluster_geometry"] * 1e-3) / 1e9, 1)
