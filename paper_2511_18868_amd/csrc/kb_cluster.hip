@@ -547,9 +547,11 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
             const int ti = wid + kWaves * (i0 + lane);
             act = __ballot(lane < nb && !(thr[ti] > drift));
         }
-        bf16x8 Bh[DS], Bm[DS];
-        float xn;
-        int old;
+        // two sets of operand registers take turns (the tile being scored, the tile
+        // requested for the next turn), so nothing is copied between turns
+        bf16x8 BhA[DS], BmA[DS], BhB[DS], BmB[DS];
+        float xnA, xnB;
+        int oldA, oldB;
         int cur = -1;
         if (act) {
             cur = __ffsll((long long)act) - 1;
@@ -557,17 +559,18 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
         }
         {
             const int t0 = wid + kWaves * (i0 + (cur >= 0 ? cur : 0));
-            load_tile(t0 < ntiles ? t0 : ntiles - 1, Bh, Bm, xn, old);
+            load_tile(t0 < ntiles ? t0 : ntiles - 1, BhA, BmA, xnA, oldA);
         }
-        while (cur >= 0) {
+        // scores tile `cur` from (Bh, Bm, xn, old), requests the next active tile into
+        // (Bh2, Bm2, xn2, old2) and returns its number (-1: none)
+        auto turn = [&](int cur, const bf16x8 (&Bh)[DS], const bf16x8 (&Bm)[DS], float xn, int old,
+                        bf16x8 (&Bh2)[DS], bf16x8 (&Bm2)[DS], float& xn2, int& old2)
+                        __attribute__((always_inline)) -> int {
         const int tile = wid + kWaves * (i0 + cur);
         const int p = tile * 32 + m;
         const bool valid = p < ng;
         // request the next tile before scoring this one (the same tile again when
         // there is no next one)
-        bf16x8 Bh2[DS], Bm2[DS];
-        float xn2;
-        int old2;
         int nxt = -1;
         if (act) {
             nxt = __ffsll((long long)act) - 1;
@@ -640,11 +643,12 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
             const float sl = half_wave_min_f((valid && certain) ? slack_of(best, second, xn, E) : INFINITY);
             if (lane == 0) thr[tile] = tile_limit(drift, sl);
         }
-#pragma unroll
-        for (int s = 0; s < DS; ++s) { Bh[s] = Bh2[s]; Bm[s] = Bm2[s]; }
-        xn = xn2;
-        old = old2;
-        cur = nxt;
+        return nxt;
+        };
+        while (cur >= 0) {
+            cur = turn(cur, BhA, BmA, xnA, oldA, BhB, BmB, xnB, oldB);
+            if (cur < 0) break;
+            cur = turn(cur, BhB, BmB, xnB, oldB, BhA, BmA, xnA, oldA);
         }
     }
     return any;   // bit 0: some candidate moved, bit 1: some candidate needs the exact pass
@@ -676,6 +680,15 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
         const int p = tile * 32 + m;
         const bool valid = p < ng;
         const float* xr = Xg + (size_t)(valid ? p : 0) * D;
+        if (D == 16 * DS && tile * 32 + 32 <= ng) {
+            // (uniform) a whole tile of rows without padding: nothing to guard
+#pragma unroll
+            for (int s = 0; s < DS; ++s) {
+                r[s][0] = *reinterpret_cast<const float4*>(xr + 16 * s + 8 * h);
+                r[s][1] = *reinterpret_cast<const float4*>(xr + 16 * s + 8 * h + 4);
+            }
+            return;
+        }
 #pragma unroll
         for (int s = 0; s < DS; ++s) {
             const int d0 = 16 * s + 8 * h;
@@ -741,12 +754,20 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
         if (cmask) {
             any |= 1;
             if (chg) {
+                long long* srow = sums + (size_t)bi * SP + 8 * h;
+                if (D == 16 * DS) {         // (uniform) no feature is padding
 #pragma unroll
-                for (int s = 0; s < DS; ++s) {
+                    for (int s = 0; s < DS; ++s) {
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const int d = 16 * s + 8 * h + i;
-                        if (d < D) lds_add(&sums[(size_t)bi * SP + d], to_fixed(xv[s][i], fsh));
+                        for (int i = 0; i < 8; ++i) lds_add(srow + 16 * s + i, to_fixed(xv[s][i], fsh));
+                    }
+                } else {
+#pragma unroll
+                    for (int s = 0; s < DS; ++s) {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            if (16 * s + 8 * h + i < D) lds_add(srow + 16 * s + i, to_fixed(xv[s][i], fsh));
+                        }
                     }
                 }
                 if (h == 0) {

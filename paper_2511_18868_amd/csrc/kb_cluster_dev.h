@@ -10,20 +10,24 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kFlagBit = (int)0x80000000u;
 constexpr float kBig = 1.0e30f;    // score of a centroid row that does not exist
 
-// Fixed-point image of one feature value: x * 2^sh cut to a 64-bit integer
-// (toward zero, so the image of -x is minus the image of x), from fsh = sh - 32.
-// Only exact fp32 steps are used: |x| * 2^fsh (a power-of-two scaling; < 2^31 by
-// the choice of sh) is cut into its integer part, which becomes the high word,
-// and its fraction, whose first 32 bits become the low word.  The same value
-// results every time a feature is added to or taken out of a sum.
+// Fixed-point image of one feature value: x * 2^sh as a 64-bit integer, from
+// fsh = sh - 32.  t = x * 2^fsh (a power-of-two scaling; below 2^31 in size by the
+// choice of sh) is cut into its floor, which becomes the (signed) high word, and
+// the rest in [0, 1], whose first 32 bits become the low word - six vector
+// instructions.  The rest is exact for t >= 0 and for t <= -1; for -1 < t < 0 it
+// is 1 + t rounded to fp32, off by at most 2^-25 (of a high-word unit, i.e. 2^-25
+// of the 2^-fsh that already lies 30 - log2(N_g) bits below max |x|), and a rest
+// that rounds to 1 leaves the saturating conversion at 2^32 - 1.  What matters
+// is that the same value results every time a feature is added to or taken out
+// of a sum.
 __device__ __forceinline__ long long to_fixed(float x, int fsh) {
-    const float t = ldexpf(fabsf(x), fsh);
+    const float t = ldexpf(x, fsh);
     const float hi = floorf(t);
-    const float lo = ldexpf(t - hi, 32);          // t - hi is exact and in [0, 1)
-    const unsigned ihi = (unsigned)hi;
-    const unsigned ilo = (unsigned)lo;           // truncates
-    const long long mag = (long long)(((unsigned long long)ihi << 32) | ilo);
-    return x < 0.f ? -mag : mag;
+    const float lo = ldexpf(t - hi, 32);
+    const int ihi = (int)hi;
+    unsigned ilo;
+    asm("v_cvt_u32_f32 %0, %1" : "=v"(ilo) : "v"(lo));      // truncates; 2^32 becomes 2^32 - 1
+    return (long long)(((unsigned long long)(unsigned)ihi << 32) | ilo);
 }
 
 // Shift of the fixed-point grid for a search: |x| < 2^e and N_g < 2^bits give
@@ -39,13 +43,20 @@ __device__ __forceinline__ int fixed_shift(float amax, int ng) {
     return 62 - e - (32 - __clz(ng));
 }
 
-// v = hi + mid + rest with hi = bf16(v), mid = bf16(v - hi), round to nearest even
+// v = hi + mid + rest with hi = bf16(v), mid = bf16(v - hi), round to nearest even;
+// two features per conversion instruction
 __device__ __forceinline__ void split8(const float (&v)[8], bf16x8& hi, bf16x8& mid) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const __bf16 h = (__bf16)v[i];
-        hi[i] = h;
-        mid[i] = (__bf16)(v[i] - (float)h);
+    for (int p = 0; p < 4; ++p) {
+        const f32x2 x = {v[2 * p], v[2 * p + 1]};
+        const bf16x2 h = __builtin_convertvector(x, bf16x2);
+        const unsigned hb = __builtin_bit_cast(unsigned, h);
+        const f32x2 r = {x.x - __uint_as_float(hb << 16), x.y - __uint_as_float(hb & 0xffff0000u)};
+        const bf16x2 m = __builtin_convertvector(r, bf16x2);
+        hi[2 * p] = h.x; hi[2 * p + 1] = h.y;
+        mid[2 * p] = m.x; mid[2 * p + 1] = m.y;
     }
 }
 
