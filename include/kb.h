@@ -266,8 +266,11 @@ kb_status kb_cluster_diameter(const kb_batch *batch, const float *X,
  * the definition; lowest k on ties).  The cover's largest radius is within a
  * factor two of the smallest possible one (the covering radius of Theorem 1's
  * approximation term).  cent [Ksum,D] out (exact copies of the chosen rows),
- * pick [Ksum] out: their global candidate indices (may be NULL).  K_g passes over
- * the rows of each search. */
+ * pick [Ksum] out: their global candidate indices (may be NULL).  K_g dependent
+ * passes over the rows of each search: searches of up to 4096 rows are read once
+ * and kept on chip by one workgroup each; a batch with longer searches (Nmax >
+ * 4096) enqueues Kmax further launches that advance all of those by one centroid
+ * each. */
 kb_status kb_seed_farthest(const kb_batch *batch, const float *X, float *cent,
                            int32_t *pick, void *ws, size_t ws_bytes,
                            void *stream);
