@@ -713,11 +713,9 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
     float am = 0.f;
     double sq = 0.0;          // sum of x^2 over this lane's features, exact products
     int any = 0;
-    float4 cur[DS][2], nxt[DS][2];
-    if (wid < ntiles) load_rows(wid, cur);
+    float4 cur[DS][2];
     for (int tile = wid; tile < ntiles; tile += kWaves) {
-        const bool more = tile + kWaves < ntiles;
-        if (more) load_rows(tile + kWaves, nxt);
+        load_rows(tile, cur);
         const int p = tile * 32 + m;
         const bool valid = p < ng;
         float xv[DS][8];
@@ -790,10 +788,6 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
         if (a.use_bounds) {
             const float sl = half_wave_min_f((valid && certain) ? slack_of(best, second, xn, E) : INFINITY);
             if (lane == 0) thr[tile] = tile_limit(0.f, sl);
-        }
-        if (more) {
-#pragma unroll
-            for (int s = 0; s < DS; ++s) { cur[s][0] = nxt[s][0]; cur[s][1] = nxt[s][1]; }
         }
     }
     am_out = am;
