@@ -13,20 +13,19 @@ constexpr float kBig = 1.0e30f;    // score of a centroid row that does not exis
 // Fixed-point image of one feature value: x * 2^sh as a 64-bit integer, from
 // fsh = sh - 32.  t = x * 2^fsh (a power-of-two scaling; below 2^31 in size by the
 // choice of sh) is cut into its floor, which becomes the (signed) high word, and
-// the rest in [0, 1], whose first 32 bits become the low word - six vector
-// instructions.  The rest is exact for t >= 0 and for t <= -1; for -1 < t < 0 it
-// is 1 + t rounded to fp32, off by at most 2^-25 (of a high-word unit, i.e. 2^-25
-// of the 2^-fsh that already lies 30 - log2(N_g) bits below max |x|), and a rest
-// that rounds to 1 leaves the saturating conversion at 2^32 - 1.  What matters
-// is that the same value results every time a feature is added to or taken out
-// of a sum.
+// its fractional part t - floor(t) (the hardware's fract, which stays below 1),
+// whose first 32 bits become the low word - five vector instructions.  The
+// fractional part is exact for t >= 0 and for t <= -1; for -1 < t < 0 it is 1 + t
+// rounded to fp32, off by at most 2^-25 (of a high-word unit, i.e. 2^-25 of the
+// 2^-fsh that already lies 30 - log2(N_g) bits below max |x|).  What matters is
+// that the same value results every time a feature is added to or taken out of
+// a sum.
 __device__ __forceinline__ long long to_fixed(float x, int fsh) {
     const float t = ldexpf(x, fsh);
-    const float hi = floorf(t);
-    const float lo = ldexpf(t - hi, 32);
-    const int ihi = (int)hi;
-    unsigned ilo;
-    asm("v_cvt_u32_f32 %0, %1" : "=v"(ilo) : "v"(lo));      // truncates; 2^32 becomes 2^32 - 1
+    int ihi;
+    asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(ihi) : "v"(t));          // floor and conversion in one
+    const float lo = ldexpf(__builtin_amdgcn_fractf(t), 32);      // below 2^32
+    const unsigned ilo = (unsigned)lo;                            // truncates
     return (long long)(((unsigned long long)(unsigned)ihi << 32) | ilo);
 }
 
