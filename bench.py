@@ -33,12 +33,13 @@ def measured_traffic(config):
     changed since they were taken (or the workload is not config 5)."""
     import hashlib
     path = os.path.join(ROOT, "profiles", "traffic_config5.json")
-    src = os.path.join(ROOT, "paper_2511_18868_amd", "csrc", "kb_cluster.hip")
     if not os.path.exists(path) or config != 5:
         return None
     rec = json.load(open(path))
-    h = hashlib.sha256(open(src, "rb").read()).hexdigest()
-    return rec["bytes_per_launch"] if rec.get("kb_cluster_hip_sha256") == h else None
+    h = hashlib.sha256()
+    for name in ("kb_cluster.hip", "kb_cluster_dev.h"):      # the kernel and its device helpers
+        h.update(open(os.path.join(ROOT, "paper_2511_18868_amd", "csrc", name), "rb").read())
+    return rec["bytes_per_launch"] if rec.get("kernel_source_sha256") == h.hexdigest() else None
 
 
 def main():
