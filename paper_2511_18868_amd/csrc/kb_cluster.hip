@@ -547,6 +547,10 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
             const int ti = wid + kWaves * (i0 + lane);
             act = __ballot(lane < nb && !(thr[ti] > drift));
         }
+        // (told to the compiler as the wave-uniform value it is: the tile numbers and
+        // addresses derived from it are then scalar work)
+        act = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(act >> 32)) << 32) |
+              (unsigned)__builtin_amdgcn_readfirstlane((int)act);
         // two sets of operand registers take turns (the tile being scored, the tile
         // requested for the next turn), so nothing is copied between turns
         bf16x8 BhA[DS], BmA[DS], BhB[DS], BmB[DS];
