@@ -514,7 +514,7 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
                                           int fsh, long long* sums, int* cnt,
                                           int* nflag, int* flist, const bf16x8* aop, int* dirty,
                                           float* thr, float drift) {
-    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
     const int m = lane & 31, h = lane >> 5;
     const int mtiles = (K + 31) >> 5;
     const float kappa = mfma_kappa(DS);
@@ -672,7 +672,7 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
                                            long long* sums, int* cnt, int* nflag, int* flist,
                                            const bf16x8* aop, int* dirty, float* thr,
                                            float& am_out, double& sq_out) {
-    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
     const int m = lane & 31, h = lane >> 5;
     const int mtiles = (K + 31) >> 5;
     const float kappa = mfma_kappa(DS);
@@ -805,7 +805,7 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
 // and add; the wave then reduces to the minimum, lowest index on ties.
 __device__ __forceinline__ void refine(const ClusterArgs& a, const float* __restrict__ Xg, int n0,
                                        int ng, int K, int D, int DP, const float* cent) {
-    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
     for (int base = wid * kWave; base < ng; base += kThreads) {
         const int p = base + lane;
         const int v = p < ng ? a.a_new[(size_t)n0 + p] : 0;
@@ -863,7 +863,7 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
                                              int SP, const float* cent, int fsh,
                                              long long* sums, int* cnt, int* dirty, float* thr,
                                              float drift) {
-    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
     const int lc = lane < D ? lane : 0;
     const float eps = 2.f * (float)(D + 2) * 5.9604644775390625e-08f;
     int any = 0;
@@ -984,7 +984,7 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
 __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restrict__ Xg, int n0,
                                       int ng, int K, int D, int SP, bool first, int fsh,
                                       long long* sums, int* cnt, int* dirty) {
-    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
     int any = 0;
     for (int base = wid * kWave; base < ng; base += kThreads) {
         const int p = base + lane;
