@@ -133,6 +133,7 @@ static kb_status do_cluster(const kb_batch* b, const float* X, const float* cent
     c.cent_out = cent; c.counts = counts; c.objective = objective;
     c.a_new = (int32_t*)(base + w.a_new); c.order = order;
     c.tile_off = (const int32_t*)(base + w.tile_off); c.xn = (float*)(base + w.xn);
+    c.lim = (float*)(base + w.geo_d2);      // (the representative pass uses this array at other times)
     c.split = (void*)(base + w.split); c.max_tiles = (int64_t)w.max_tiles;
     if (w.use_big) return dev(launch_cluster_big(*b, c, w.big, base, st));
     return dev(launch_cluster(*b, c, st));

@@ -59,11 +59,13 @@ struct ClusterArgs {
     bf16x8* split;
     int64_t max_tiles;
     int use_bounds;
+    float* lim;        // [N] limit of every candidate: drift at its last scoring + its slack
 };
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kFlagCap = 256;      // LDS list of candidates waiting for the exact pass
+constexpr int kQueue = 128;        // per wave: candidates waiting to be scored (at most 31 + 64 at a time)
 
 // Cross-lane steps inside rows of 16 lanes (data-parallel primitives: no LDS
 // traffic): lanes 1,0,3,2 and 2,3,0,1 of every four, then mirrors inside every
@@ -273,7 +275,7 @@ __device__ __forceinline__ float mean_f32(double t, double c, double rc) {
 
 template <int DS, bool OPERANDS>
 __device__ __forceinline__ float renew_rows(float* cent, float* cn, bf16x8* aop, const long long* sums,
-                                            const int* cnt, int* dirty, float* delta, int K, int D,
+                                            const int* cnt, unsigned char* dirty, float* delta, int K, int D,
                                             int SP, double inv, bool init, bool need_scores) {
     constexpr int DP = 16 * DS + 4;
     const int tid = threadIdx.x, l16 = tid & 15, d0 = 4 * (tid & 15);
@@ -512,7 +514,7 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
                                           int n0, int ng, int K, int D, int DP, int SP,
                                           const float* cent, const float* cn, float cnmax,
                                           int fsh, long long* sums, int* cnt,
-                                          int* nflag, int* flist, const bf16x8* aop, int* dirty,
+                                          int* nflag, unsigned short* flist, const bf16x8* aop, unsigned char* dirty,
                                           float* thr, float drift) {
     const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
     const int m = lane & 31, h = lane >> 5;
@@ -637,7 +639,7 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
             a.a_new[(size_t)n0 + p] = certain ? bi : (bi | kFlagBit);
             if (!certain) {
                 const int pos = atomicAdd(nflag, 1);
-                if (pos < kFlagCap) flist[pos] = p;
+                if (pos < kFlagCap) flist[pos] = (unsigned short)p;     // (N_g <= 65536 on this path)
             }
         }
         if (__any(valid && !certain)) any |= 2;
@@ -658,6 +660,162 @@ __device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __r
     return any;   // bit 0: some candidate moved, bit 1: some candidate needs the exact pass
 }
 
+// The same step with the candidates that have to be scored packed into dense
+// tiles.  Every candidate carries its own limit (drift at scoring time + slack)
+// in `lim`; a tile's number in `thr` is the smallest limit of its candidates.  A
+// wave walks its tiles whose number the drift has reached, two at a time (one
+// per half-wave), reads their candidates' limits, and appends those the drift has
+// reached to a small queue in LDS; whenever 32 are waiting they are scored as one
+// tile of the matrix instruction, each lane fetching the operands of its own
+// candidate from the split copy.  A tile in which a third of the candidates are
+// at risk thus costs a third of a scoring instead of a whole one.
+template <int DS, int MT>
+__device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* __restrict__ Xg,
+                                            const bf16x8* __restrict__ sp,
+                                            int n0, int ng, int K, int D, int DP, int SP,
+                                            const float* cent, const float* cn, float cnmax,
+                                            int fsh, long long* sums, int* cnt,
+                                            int* nflag, unsigned short* flist, const bf16x8* aop, unsigned char* dirty,
+                                            float* thr, float* __restrict__ lim,
+                                            unsigned short* queue, float drift) {
+    const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
+    const int m = lane & 31, h = lane >> 5;
+    const int mtiles = (K + 31) >> 5;
+    const float kappa = mfma_kappa(DS);
+    const int ntiles = (ng + 31) >> 5;
+    const int ntw = ntiles > wid ? (ntiles - wid + kWaves - 1) / kWaves : 0;   // tiles of this wave
+    unsigned short* q = queue + wid * kQueue;
+    unsigned head = 0, tail = 0;       // (uniform) the queue holds entries head .. tail - 1, modulo kQueue
+    int any = 0;
+
+    // scores the first `count` (<= 32) candidates of the queue
+    auto chunk = [&](int count) __attribute__((always_inline)) {
+        const bool valid = m < count;
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");      // the other lanes' queue entries
+        const int p = q[(head + (valid ? m : 0)) & (kQueue - 1)];
+        bf16x8 Bh[DS], Bm[DS];
+        {
+            const bf16x8* tp = sp + (size_t)(p >> 5) * (DS * 2 * 64) + (p & 31) + 32 * h;
+#pragma unroll
+            for (int s = 0; s < DS; ++s) {
+                Bh[s] = tp[(2 * s) * 64];
+                Bm[s] = tp[(2 * s + 1) * 64];
+            }
+        }
+        const float xn = a.xn[(size_t)n0 + p];
+        int old = a.assign[(size_t)n0 + p];
+        old = (valid && old >= 0 && old < K) ? old : -1;
+
+        float best, second;
+        int bi;
+        tile_scores<DS, MT>(Bh, Bm, cn, aop, mtiles, lane, best, second, bi);
+        bi = bi < K ? bi : 0;
+        const float E = kappa * (xn + cnmax);
+        // (a best score next to zero may have lost its position bits to a flush of
+        // subnormal numbers: that candidate goes to the exact pass)
+        const bool certain = (K == 1) || (((second - best) > 2.f * E) && fabsf(best) > 1.0e-30f);
+        const bool chg = valid && certain && (bi != old);
+        unsigned rem = (unsigned)__ballot(chg && h == 0);
+        if (rem) {
+            any |= 1;
+            if (chg && h == 0) {
+                atomicAdd(&cnt[bi], 1);
+                dirty[bi] = 1;
+                if (old >= 0) { atomicSub(&cnt[old], 1); dirty[old] = 1; }
+                a.assign[(size_t)n0 + p] = bi;
+            }
+            const int lc = lane < D ? lane : 0;
+            while (rem) {
+                constexpr int MV = 8;
+                int mb[MV];
+                float xq[MV];
+#pragma unroll
+                for (int u = 0; u < MV; ++u) {
+                    mb[u] = rem ? __ffs((int)rem) - 1 : -1;
+                    rem &= rem - 1;
+                }
+                // unconditional loads (an unused slot reads the first mover's row again)
+#pragma unroll
+                for (int u = 0; u < MV; ++u)
+                    xq[u] = Xg[(size_t)__shfl(p, mb[u] >= 0 ? mb[u] : mb[0]) * D + lc];
+#pragma unroll
+                for (int u = 0; u < MV; ++u) {
+                    if (mb[u] >= 0) {                       // uniform over the wave
+                        const int nb2 = __shfl(bi, mb[u]);
+                        const int ob2 = __shfl(old, mb[u]);
+                        if (lane < D) {
+                            const long long qf = to_fixed(xq[u], fsh);
+                            lds_add(&sums[(size_t)nb2 * SP + lane], qf);
+                            if (ob2 >= 0) lds_add(&sums[(size_t)ob2 * SP + lane], -qf);
+                        }
+                    }
+                }
+            }
+        }
+        if (valid && h == 0) {
+            a.a_new[(size_t)n0 + p] = certain ? bi : (bi | kFlagBit);
+            if (!certain) {
+                const int pos = atomicAdd(nflag, 1);
+                if (pos < kFlagCap) flist[pos] = (unsigned short)p;     // (N_g <= 65536 on this path)
+            } else if (a.use_bounds) {
+                // (the exact pass sets the limit of the candidates it decides)
+                const float L = tile_limit(drift, slack_of(best, second, xn, E));
+                lim[p] = L;
+                atomicMin(reinterpret_cast<unsigned*>(&thr[p >> 5]), __float_as_uint(L));
+            }
+        }
+        if (__any(valid && !certain)) any |= 2;
+    };
+
+    for (int i0 = 0; i0 < ntw; i0 += 64) {
+        const int nb = ntw - i0 < 64 ? ntw - i0 : 64;
+        unsigned long long act = nb == 64 ? ~0ull : ((1ull << nb) - 1ull);
+        if (a.use_bounds) {
+            const int ti = wid + kWaves * (i0 + lane);
+            act = __ballot(lane < nb && !(thr[ti] > drift));
+        }
+        act = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(act >> 32)) << 32) |
+              (unsigned)__builtin_amdgcn_readfirstlane((int)act);
+        while (act) {
+            // the next two tiles to look at: one for each half-wave
+            const int c0 = __ffsll((long long)act) - 1;
+            act &= act - 1;
+            int c1 = -1;
+            if (act) { c1 = __ffsll((long long)act) - 1; act &= act - 1; }
+            const int myc = h ? c1 : c0;
+            const int tl = wid + kWaves * (i0 + (myc >= 0 ? myc : c0));
+            const int p = tl * 32 + m;
+            const bool in = myc >= 0 && p < ng;
+            bool active = in;
+            if (a.use_bounds) {
+                const float lv = lim[in ? p : 0];
+                active = in && !(lv > drift);
+                // what the tile's number becomes: the smallest limit among the candidates
+                // that stay as they are (the scored ones lower it again)
+                float keep = (in && !active) ? lv : INFINITY;
+                keep = row_min_f(keep);
+                const float k0 = vmin(lane_f(keep, 0), lane_f(keep, 16));
+                const float k1 = vmin(lane_f(keep, 32), lane_f(keep, 48));
+                if (lane == 0) thr[wid + kWaves * (i0 + c0)] = k0;
+                if (lane == 32 && c1 >= 0) thr[wid + kWaves * (i0 + c1)] = k1;
+            }
+            const unsigned long long mask = __ballot(active);
+            if (active) {
+                const unsigned rank = __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
+                                          __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
+                q[(tail + rank) & (kQueue - 1)] = (unsigned short)p;
+            }
+            tail += (unsigned)__popcll(mask);
+            while (tail - head >= 32u) {
+                chunk(32);
+                head += 32u;
+            }
+        }
+    }
+    if (tail != head) chunk((int)(tail - head));
+    return any;   // bit 0: some candidate moved, bit 1: some candidate needs the exact pass
+}
+
 // First step of a call on the matrix-core path.  One pass over the fp32 rows
 // does everything the later steps get from the workspace: the rows are split
 // into bf16 (hi, mid) operands (written to the workspace for the steps that
@@ -669,9 +827,9 @@ template <int DS, int MT>
 __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __restrict__ Xg,
                                            bf16x8* __restrict__ spw, int n0, int ng, int K, int D,
                                            int SP, const float* cn, float cnmax, int fsh,
-                                           long long* sums, int* cnt, int* nflag, int* flist,
-                                           const bf16x8* aop, int* dirty, float* thr,
-                                           float& am_out, double& sq_out) {
+                                           long long* sums, int* cnt, int* nflag, unsigned short* flist,
+                                           const bf16x8* aop, unsigned char* dirty, float* thr,
+                                           float* __restrict__ lim, float& am_out, double& sq_out) {
     const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
     const int m = lane & 31, h = lane >> 5;
     const int mtiles = (K + 31) >> 5;
@@ -785,12 +943,14 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
                 // left to the exact pass: no cluster yet
                 a.assign[(size_t)n0 + p] = -1;
                 const int pos = atomicAdd(nflag, 1);
-                if (pos < kFlagCap) flist[pos] = p;
+                if (pos < kFlagCap) flist[pos] = (unsigned short)p;     // (N_g <= 65536 on this path)
             }
         }
         if (__any(valid && !certain)) any |= 2;
         if (a.use_bounds) {
-            const float sl = half_wave_min_f((valid && certain) ? slack_of(best, second, xn, E) : INFINITY);
+            const float own = (valid && certain) ? slack_of(best, second, xn, E) : INFINITY;
+            if (valid && certain && h == 0) lim[p] = tile_limit(0.f, own);
+            const float sl = half_wave_min_f(own);
             if (lane == 0) thr[tile] = tile_limit(0.f, sl);
         }
     }
@@ -859,10 +1019,10 @@ __device__ __forceinline__ void refine(const ClusterArgs& a, const float* __rest
 // lowest index attaining the minimum wins.  Then, if the nearest centroid differs
 // from the recorded cluster, the row moves between the running sums.
 __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* __restrict__ Xg,
-                                             int n0, int n, const int* flist, int K, int D, int DP,
+                                             int n0, int n, const unsigned short* flist, int K, int D, int DP,
                                              int SP, const float* cent, int fsh,
-                                             long long* sums, int* cnt, int* dirty, float* thr,
-                                             float drift) {
+                                             long long* sums, int* cnt, unsigned char* dirty, float* thr,
+                                             float* __restrict__ lim, float drift) {
     const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
     const int lc = lane < D ? lane : 0;
     const float eps = 2.f * (float)(D + 2) * 5.9604644775390625e-08f;
@@ -954,7 +1114,9 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
             // the slack is the difference of the bounds, rounded down; limits are
             // non-negative floats, which order like their bit patterns
             const float sl = fmaxf((lbd - ub) * 0.9999995f, 0.f);
-            atomicMin(reinterpret_cast<unsigned*>(&thr[p >> 5]), __float_as_uint(tile_limit(drift, sl)));
+            const float L = tile_limit(drift, sl);
+            lim[p] = L;
+            atomicMin(reinterpret_cast<unsigned*>(&thr[p >> 5]), __float_as_uint(L));
         }
         bj = bj < K ? bj : 0;
         old = (old >= 0 && old < K) ? old : -1;
@@ -983,7 +1145,7 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
 // wave saw any change.
 __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restrict__ Xg, int n0,
                                       int ng, int K, int D, int SP, bool first, int fsh,
-                                      long long* sums, int* cnt, int* dirty) {
+                                      long long* sums, int* cnt, unsigned char* dirty) {
     const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
     int any = 0;
     for (int base = wid * kWave; base < ng; base += kThreads) {
@@ -1023,7 +1185,7 @@ __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restr
 
 // LDS layout shared by the kernel and the host-side size computation.
 struct Lds {
-    size_t sums, cent, cn, cnt, dirty, delta, flist, aop, thr, total;
+    size_t sums, cent, cn, cnt, dirty, delta, flist, aop, thr, queue, total;
 };
 __host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP, int Nmax) {
     const int SP = D | 1;   // odd row stride: clusters spread over the LDS banks
@@ -1034,14 +1196,16 @@ __host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP, int Nmax) {
     l.cent = off; off += (size_t)Kmax * DP * 4;
     l.cn = off;   off += (size_t)((Kmax + 31) & ~31) * 4;   // padded to whole centroid tiles
     l.cnt = off;  off += (size_t)Kmax * 4;
-    l.dirty = off; off += (size_t)Kmax * 4;         // "membership changed" flags
+    l.dirty = off; off += ((size_t)Kmax + 15) & ~(size_t)15;   // "membership changed" flags, one byte each
     l.delta = off; off += (size_t)Kmax * 4;         // how far each centroid moved in the last renewal
-    l.flist = off; off += (size_t)kFlagCap * 4;
+    l.flist = off; off += (size_t)kFlagCap * 2;          // 16-bit candidate numbers
     off = (off + 15) & ~(size_t)15;
     // centroid operands of the matrix-core scorer (only when Kmax <= 64)
     l.aop = off;  if (Kmax <= 64) off += (size_t)((Kmax + 31) / 32) * ((DP - 4) / 16) * 2 * 64 * 16;
     // one drift limit per tile of 32 candidates
     l.thr = off; if (Kmax <= 64) off += ((((size_t)Nmax + 31) / 32) * 4 + 15) & ~(size_t)15;
+    // per wave: the candidates waiting to be scored
+    l.queue = off; if (Kmax <= 64) off += (size_t)kWaves * kQueue * 2;
     l.total = off;
     return l;
 }
@@ -1073,10 +1237,12 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     float* cent = reinterpret_cast<float*>(smem + L.cent);           // [Kmax][DP]
     float* cn = reinterpret_cast<float*>(smem + L.cn);               // [Kmax]
     int* cnt = reinterpret_cast<int*>(smem + L.cnt);                 // [Kmax]
-    int* flist = reinterpret_cast<int*>(smem + L.flist);             // [kFlagCap]
-    int* dirty = reinterpret_cast<int*>(smem + L.dirty);             // [Kmax]
+    unsigned short* flist = reinterpret_cast<unsigned short*>(smem + L.flist);   // [kFlagCap]
+    unsigned char* dirty = reinterpret_cast<unsigned char*>(smem + L.dirty);             // [Kmax]
     float* delta = reinterpret_cast<float*>(smem + L.delta);         // [Kmax]
     float* thr = reinterpret_cast<float*>(smem + L.thr);             // [tiles]
+    unsigned short* queue = reinterpret_cast<unsigned short*>(smem + L.queue);   // [kWaves][kQueue]
+    float* lim = a.lim + n0;                                         // [N_g], global
     int* nflag = reinterpret_cast<int*>(smem + 64);                  // behind the two reduction slots
     bf16x8* aop = reinterpret_cast<bf16x8*>(smem + L.aop);
 
@@ -1179,14 +1345,14 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
                 drift = (drift + (d1 + d2) * 1.0000005f) * 1.0000005f;
             }
         }
-        int* dw = dirty;        // rows touched in this step, for the renewal at its end
+        unsigned char* dw = dirty;        // rows touched in this step, for the renewal at its end
 
         int st;
         if constexpr (MT > 0) {
             if (first) {
                 float am_seen;
                 st = score_first<DS, MT>(a, Xg, spw, n0, ng, K, D, SP, cn, cm, fsh, sums, cnt, nflag,
-                                         flist, aop, dw, thr, am_seen, tsq);
+                                         flist, aop, dw, thr, lim, am_seen, tsq);
                 am_seen = block_max_f(am_seen, red, phase);
                 tsq = block_sum_d(tsq, red, phase);
                 const int sh_true = fixed_shift(am_seen, ng);
@@ -1211,8 +1377,8 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
                     __syncthreads();
                 }
             } else
-            st = score_mfma<DS, MT>(a, Xg, sp, n0, ng, K, D, DP, SP, cent, cn, cm, fsh, sums, cnt,
-                                    nflag, flist, aop, dw, thr, drift);
+            st = score_packed<DS, MT>(a, Xg, sp, n0, ng, K, D, DP, SP, cent, cn, cm, fsh, sums, cnt,
+                                      nflag, flist, aop, dw, thr, lim, queue, drift);
         } else {
             score_valu<4 * DS>(a, Xg, n0, ng, K, D, DP, cent, cn, cm);
             st = 2;
@@ -1223,12 +1389,14 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
             const int nf = MT > 0 ? *nflag : kFlagCap + 1;
             if (nf <= kFlagCap) {
                 moved = refine_listed(a, Xg, n0, nf, flist, K, D, DP, SP, cent, fsh, sums, cnt, dw,
-                                      thr, drift);
+                                      thr, lim, drift);
             } else {
                 // the list overflowed (or the vector-ALU scorer ran): scan every candidate;
                 // no slack is known for the refined ones, so every tile is scored next time
-                if (MT > 0 && a.use_bounds)
+                if (MT > 0 && a.use_bounds) {
                     for (int t = tid; t < ((ng + 31) >> 5); t += kThreads) thr[t] = 0.f;
+                    for (int q = tid; q < ng; q += kThreads) lim[q] = 0.f;
+                }
                 refine(a, Xg, n0, ng, K, D, DP, cent);
                 __syncthreads();
                 // after the matrix-core scorer only refined candidates are left to move,
@@ -1350,6 +1518,7 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     a.tile_off = c.tile_off; a.xn = c.xn; a.split = reinterpret_cast<bf16x8*>(c.split);
     a.max_tiles = c.max_tiles;
     a.use_bounds = g_scorer != 2;
+    a.lim = c.lim;
 
     const int ds = (b.D + 15) / 16;   // 1..4 K-steps of 16 features
     a.Nmax = b.Nmax;

@@ -75,6 +75,7 @@ struct ClusterCall {
     float* xn;
     void* split;
     int64_t max_tiles;
+    float* lim;               // float [N] scratch of the fused kernel (every candidate's drift limit)
 };
 hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t st);
 hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const BigWs& w, char* ws,
