@@ -508,160 +508,8 @@ __device__ __forceinline__ void tile_scores(const bf16x8 (&Bh)[DS], const bf16x8
     }
 }
 
-template <int DS, int MT>
-__device__ __forceinline__ int score_mfma(const ClusterArgs& a, const float* __restrict__ Xg,
-                                          const bf16x8* __restrict__ sp,
-                                          int n0, int ng, int K, int D, int DP, int SP,
-                                          const float* cent, const float* cn, float cnmax,
-                                          int fsh, long long* sums, int* cnt,
-                                          int* nflag, unsigned short* flist, const bf16x8* aop, unsigned char* dirty,
-                                          float* thr, float drift) {
-    const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
-    const int m = lane & 31, h = lane >> 5;
-    const int mtiles = (K + 31) >> 5;
-    const float kappa = mfma_kappa(DS);
-
-    auto load_tile = [&](int tile, bf16x8 (&bh)[DS], bf16x8 (&bm)[DS], float& xnv, int& oldv) {
-        const bf16x8* tp = sp + (size_t)tile * (DS * 2 * 64) + lane;
-#pragma unroll
-        for (int s = 0; s < DS; ++s) {
-            bh[s] = tp[(2 * s) * 64];
-            bm[s] = tp[(2 * s + 1) * 64];
-        }
-        // no branch around any of these loads (rows past the end read the last row):
-        // the number of loads in flight is then known at compile time, and waiting
-        // for one tile does not also wait for the tile requested after it
-        const int p = tile * 32 + m;
-        const int pc = p < ng ? p : ng - 1;
-        xnv = a.xn[(size_t)n0 + pc];
-        oldv = a.assign[(size_t)n0 + pc];
-    };
-
-    const int ntiles = (ng + 31) >> 5;
-    const int ntw = ntiles > wid ? (ntiles - wid + kWaves - 1) / kWaves : 0;   // tiles of this wave
-
-    int any = 0;
-    for (int i0 = 0; i0 < ntw; i0 += 64) {
-        const int nb = ntw - i0 < 64 ? ntw - i0 : 64;
-        unsigned long long act = nb == 64 ? ~0ull : ((1ull << nb) - 1ull);
-        if (a.use_bounds) {
-            // tiles whose slack the centroids' drift has not used up keep their clusters
-            const int ti = wid + kWaves * (i0 + lane);
-            act = __ballot(lane < nb && !(thr[ti] > drift));
-        }
-        // (told to the compiler as the wave-uniform value it is: the tile numbers and
-        // addresses derived from it are then scalar work)
-        act = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(act >> 32)) << 32) |
-              (unsigned)__builtin_amdgcn_readfirstlane((int)act);
-        // two sets of operand registers take turns (the tile being scored, the tile
-        // requested for the next turn), so nothing is copied between turns
-        bf16x8 BhA[DS], BmA[DS], BhB[DS], BmB[DS];
-        float xnA, xnB;
-        int oldA, oldB;
-        int cur = -1;
-        if (act) {
-            cur = __ffsll((long long)act) - 1;
-            act &= act - 1;
-        }
-        {
-            const int t0 = wid + kWaves * (i0 + (cur >= 0 ? cur : 0));
-            load_tile(t0 < ntiles ? t0 : ntiles - 1, BhA, BmA, xnA, oldA);
-        }
-        // scores tile `cur` from (Bh, Bm, xn, old), requests the next active tile into
-        // (Bh2, Bm2, xn2, old2) and returns its number (-1: none)
-        auto turn = [&](int cur, const bf16x8 (&Bh)[DS], const bf16x8 (&Bm)[DS], float xn, int old,
-                        bf16x8 (&Bh2)[DS], bf16x8 (&Bm2)[DS], float& xn2, int& old2)
-                        __attribute__((always_inline)) -> int {
-        const int tile = wid + kWaves * (i0 + cur);
-        const int p = tile * 32 + m;
-        const bool valid = p < ng;
-        // request the next tile before scoring this one (the same tile again when
-        // there is no next one)
-        int nxt = -1;
-        if (act) {
-            nxt = __ffsll((long long)act) - 1;
-            act &= act - 1;
-        }
-        load_tile(nxt >= 0 ? wid + kWaves * (i0 + nxt) : tile, Bh2, Bm2, xn2, old2);
-        old = (valid && old >= 0 && old < K) ? old : -1;
-
-        float best, second;
-        int bi;
-        tile_scores<DS, MT>(Bh, Bm, cn, aop, mtiles, lane, best, second, bi);
-        bi = bi < K ? bi : 0;
-        const float E = kappa * (xn + cnmax);
-        // (a best score next to zero may have lost its position bits to a flush of
-        // subnormal numbers: that candidate goes to the exact pass)
-        const bool certain = (K == 1) || (((second - best) > 2.f * E) && fabsf(best) > 1.0e-30f);
-        const bool chg = valid && certain && (bi != old);
-        // Candidates that change cluster: lanes 0..31 (one per candidate) fix counts
-        // and flags; then the wave takes the movers eight at a time, lanes over
-        // features: the fp32 rows are read again (all loads first), converted to
-        // fixed point and moved between the sums.
-        unsigned rem = (unsigned)__ballot(chg && h == 0);
-        if (rem) {
-            any |= 1;
-            if (chg && h == 0) {
-                atomicAdd(&cnt[bi], 1);
-                dirty[bi] = 1;
-                if (old >= 0) { atomicSub(&cnt[old], 1); dirty[old] = 1; }
-                a.assign[(size_t)n0 + p] = bi;
-            }
-            const int lc = lane < D ? lane : 0;
-            while (rem) {
-                constexpr int MV = 8;
-                int mb[MV];
-                float xq[MV];
-#pragma unroll
-                for (int q = 0; q < MV; ++q) {
-                    mb[q] = rem ? __ffs((int)rem) - 1 : -1;
-                    rem &= rem - 1;
-                }
-                // unconditional loads (an unused slot reads the first mover's row again)
-#pragma unroll
-                for (int q = 0; q < MV; ++q)
-                    xq[q] = Xg[(size_t)(tile * 32 + (mb[q] >= 0 ? mb[q] : mb[0])) * D + lc];
-#pragma unroll
-                for (int q = 0; q < MV; ++q) {
-                    if (mb[q] >= 0) {                       // uniform over the wave
-                        const int nb2 = __shfl(bi, mb[q]);
-                        const int ob2 = __shfl(old, mb[q]);
-                        if (lane < D) {
-                            const long long qf = to_fixed(xq[q], fsh);
-                            lds_add(&sums[(size_t)nb2 * SP + lane], qf);
-                            if (ob2 >= 0) lds_add(&sums[(size_t)ob2 * SP + lane], -qf);
-                        }
-                    }
-                }
-            }
-        }
-        if (valid && h == 0) {
-            a.a_new[(size_t)n0 + p] = certain ? bi : (bi | kFlagBit);
-            if (!certain) {
-                const int pos = atomicAdd(nflag, 1);
-                if (pos < kFlagCap) flist[pos] = (unsigned short)p;     // (N_g <= 65536 on this path)
-            }
-        }
-        if (__any(valid && !certain)) any |= 2;
-        if (a.use_bounds) {
-            // the exact pass lowers the limit for the candidates it decides
-            // both half-waves hold the same 32 candidates
-            const float sl = half_wave_min_f((valid && certain) ? slack_of(best, second, xn, E) : INFINITY);
-            if (lane == 0) thr[tile] = tile_limit(drift, sl);
-        }
-        return nxt;
-        };
-        while (cur >= 0) {
-            cur = turn(cur, BhA, BmA, xnA, oldA, BhB, BmB, xnB, oldB);
-            if (cur < 0) break;
-            cur = turn(cur, BhB, BmB, xnB, oldB, BhA, BmA, xnA, oldA);
-        }
-    }
-    return any;   // bit 0: some candidate moved, bit 1: some candidate needs the exact pass
-}
-
-// The same step with the candidates that have to be scored packed into dense
-// tiles.  Every candidate carries its own limit (drift at scoring time + slack)
+// A later step on the matrix-core path, with the candidates that have to be
+// scored packed into dense tiles.  Every candidate carries its own limit (drift at scoring time + slack)
 // in `lim`; a tile's number in `thr` is the smallest limit of its candidates.  A
 // wave walks its tiles whose number the drift has reached, two at a time (one
 // per half-wave), reads their candidates' limits, and appends those the drift has
