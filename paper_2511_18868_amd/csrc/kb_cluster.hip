@@ -624,19 +624,32 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
         }
         act = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(act >> 32)) << 32) |
               (unsigned)__builtin_amdgcn_readfirstlane((int)act);
-        while (act) {
-            // the next two tiles to look at: one for each half-wave
-            const int c0 = __ffsll((long long)act) - 1;
+        // the next two tiles to look at, one for each half-wave, and this lane's
+        // candidate in them; its limit is requested one pair ahead
+        // (no branch around the request: with none left it reads the first limit again)
+        auto take_pair = [&](bool& have, int& c0, int& c1, int& p, bool& in, float& lv) {
+            have = act != 0;
+            c0 = have ? __ffsll((long long)act) - 1 : 0;
             act &= act - 1;
-            int c1 = -1;
-            if (act) { c1 = __ffsll((long long)act) - 1; act &= act - 1; }
+            c1 = act ? __ffsll((long long)act) - 1 : -1;
+            act &= act - 1;
             const int myc = h ? c1 : c0;
             const int tl = wid + kWaves * (i0 + (myc >= 0 ? myc : c0));
-            const int p = tl * 32 + m;
-            const bool in = myc >= 0 && p < ng;
+            p = tl * 32 + m;
+            in = have && myc >= 0 && p < ng;
+            lv = lim[in ? p : 0];
+        };
+        bool have, in;
+        int c0, c1, p;
+        float lv;
+        take_pair(have, c0, c1, p, in, lv);
+        while (have) {
+            bool haven, inn;
+            int c0n, c1n, pn;
+            float lvn;
+            take_pair(haven, c0n, c1n, pn, inn, lvn);
             bool active = in;
             if (a.use_bounds) {
-                const float lv = lim[in ? p : 0];
                 active = in && !(lv > drift);
                 // what the tile's number becomes: the smallest limit among the candidates
                 // that stay as they are (the scored ones lower it again)
@@ -658,6 +671,7 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
                 chunk(32);
                 head += 32u;
             }
+            c0 = c0n; c1 = c1n; p = pn; in = inn; lv = lvn; have = haven;
         }
     }
     if (tail != head) chunk((int)(tail - head));
