@@ -8,10 +8,12 @@
 //
 // One step:
 //
-//   bounds     (default mode, once few candidates still move) every candidate
-//              carries an upper bound on the distance to its centroid and a
-//              lower bound on the distance to all others; a tile of 32
-//              candidates that provably keeps its clusters is not scored.
+//   bounds     (default mode) every scored candidate leaves a limit: the
+//              centroids' cumulative drift at that time plus the gap between
+//              the distance to its centroid and to the nearest other one.
+//              While the drift stays below the limit the candidate provably
+//              keeps its cluster and is not scored; the others are packed
+//              into dense tiles of 32.
 //   A  score   fast scores s_j = |c_j|^2 - 2 x.c_j for every centroid, the best
 //              and second-best per candidate, and a proved error bound E.
 //              If second - best > 2E the winner is certain; otherwise the
@@ -246,10 +248,10 @@ __device__ __forceinline__ void score_valu(const ClusterArgs& a, const float* __
 // a wave walks over tiles of 32 candidates.  Candidates the scorer is certain
 // about and whose cluster changed are moved between the fixed-point sums right
 // here (their fp32 row is read again; rare after the first steps).
-// The feature rows are split once per call (presplit) into a workspace laid out
-// in operand order - [tile][K-step][hi|mid][lane] x 16 bytes - so a step streams
-// them back with fully coalesced 1 KB loads and no conversion work, and the next
-// tile's operands are requested before the current tile is scored.
+// The feature rows are split once per call (in the first step) into a workspace
+// laid out in operand order - [tile][K-step][hi|mid][lane] x 16 bytes - so a later
+// step fetches a candidate's operands as 16-byte pieces with no conversion work
+// (whole tiles: fully coalesced 1 KB loads).
 // Everything that follows a change of a centroid, 16 lanes per row (lane l owns
 // features 4l .. 4l+3): the new centroid (fixed-point sum / 2^shift) / count in
 // fp64, rounded once to fp32; how far it moved (rounded up); |c_j|^2 in fp64; and
