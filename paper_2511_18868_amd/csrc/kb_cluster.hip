@@ -882,6 +882,7 @@ __device__ __forceinline__ void refine(const ClusterArgs& a, const float* __rest
 // summed over the features in index order with separate multiply and add - and the
 // lowest index attaining the minimum wins.  Then, if the nearest centroid differs
 // from the recorded cluster, the row moves between the running sums.
+template <int DS>
 __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* __restrict__ Xg,
                                              int n0, int n, const unsigned short* flist, int K, int D, int DP,
                                              int SP, const float* cent, int fsh,
@@ -914,14 +915,19 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
             const int j = j0 + lane;
             const float* cr = cent + (size_t)(j < K ? j : 0) * DP;
             float acc0 = 0.f, acc1 = 0.f;
-            for (int d = 0; d < D; d += 4) {
-                const float4 cv = *reinterpret_cast<const float4*>(cr + d);
-                const float e0 = __shfl(xv, d) - cv.x, e1 = __shfl(xv, d + 1) - cv.y;
-                const float e2 = __shfl(xv, d + 2) - cv.z, e3 = __shfl(xv, d + 3) - cv.w;
-                acc0 = fmaf(e0, e0, acc0);
-                acc1 = fmaf(e1, e1, acc1);
-                acc0 = fmaf(e2, e2, acc0);
-                acc1 = fmaf(e3, e3, acc1);
+            // (feature numbers known at compile time: the row's values are read out of
+            // their lanes into scalar registers, no cross-lane traffic through LDS)
+#pragma unroll
+            for (int d = 0; d < 16 * DS; d += 4) {
+                if (d < D) {
+                    const float4 cv = *reinterpret_cast<const float4*>(cr + d);
+                    const float e0 = lane_f(xv, d) - cv.x, e1 = lane_f(xv, d + 1) - cv.y;
+                    const float e2 = lane_f(xv, d + 2) - cv.z, e3 = lane_f(xv, d + 3) - cv.w;
+                    acc0 = fmaf(e0, e0, acc0);
+                    acc1 = fmaf(e1, e1, acc1);
+                    acc0 = fmaf(e2, e2, acc0);
+                    acc1 = fmaf(e3, e3, acc1);
+                }
             }
             const float acc = acc0 + acc1;
             if (j < K) {
@@ -944,16 +950,19 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
                 const int j = j0 + lane;
                 const float* cr = cent + (size_t)(j < K ? j : 0) * DP;
                 double acc = 0.0;
-                for (int d = 0; d < D; d += 4) {
-                    const float4 cv = *reinterpret_cast<const float4*>(cr + d);
-                    double diff = __dsub_rn((double)__shfl(xv, d), (double)cv.x);
-                    acc = __dadd_rn(acc, __dmul_rn(diff, diff));
-                    diff = __dsub_rn((double)__shfl(xv, d + 1), (double)cv.y);
-                    acc = __dadd_rn(acc, __dmul_rn(diff, diff));
-                    diff = __dsub_rn((double)__shfl(xv, d + 2), (double)cv.z);
-                    acc = __dadd_rn(acc, __dmul_rn(diff, diff));
-                    diff = __dsub_rn((double)__shfl(xv, d + 3), (double)cv.w);
-                    acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+#pragma unroll
+                for (int d = 0; d < 16 * DS; d += 4) {
+                    if (d < D) {
+                        const float4 cv = *reinterpret_cast<const float4*>(cr + d);
+                        double diff = __dsub_rn((double)lane_f(xv, d), (double)cv.x);
+                        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                        diff = __dsub_rn((double)lane_f(xv, d + 1), (double)cv.y);
+                        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                        diff = __dsub_rn((double)lane_f(xv, d + 2), (double)cv.z);
+                        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                        diff = __dsub_rn((double)lane_f(xv, d + 3), (double)cv.w);
+                        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                    }
                 }
                 if (j < K) {
                     if (acc < bd) { sd = bd; bd = acc; bj = j; }
@@ -1252,7 +1261,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
             int moved;
             const int nf = MT > 0 ? *nflag : kFlagCap + 1;
             if (nf <= kFlagCap) {
-                moved = refine_listed(a, Xg, n0, nf, flist, K, D, DP, SP, cent, fsh, sums, cnt, dw,
+                moved = refine_listed<DS>(a, Xg, n0, nf, flist, K, D, DP, SP, cent, fsh, sums, cnt, dw,
                                       thr, lim, drift);
             } else {
                 // the list overflowed (or the vector-ALU scorer ran): scan every candidate;
