@@ -635,8 +635,8 @@ __global__ void __launch_bounds__(kThreads) big_exact(BigArgs a) {
 #pragma unroll
             for (int d = 0; d < KB_MAX_D; d += 2) {
                 if (d < D4) {
-                    const float e0 = __shfl(xv, d) - c[d];
-                    const float e1 = __shfl(xv, d + 1) - c[d + 1];
+                    const float e0 = lane_value(xv, d) - c[d];
+                    const float e1 = lane_value(xv, d + 1) - c[d + 1];
                     acc0 = fmaf(e0, e0, acc0);
                     acc1 = fmaf(e1, e1, acc1);
                 }
@@ -658,7 +658,7 @@ __global__ void __launch_bounds__(kThreads) big_exact(BigArgs a) {
 #pragma unroll
             for (int d = 0; d < KB_MAX_D; ++d) {
                 if (d < D4) {
-                    const double diff = __dsub_rn((double)__shfl(xv, d), (double)c[d]);
+                    const double diff = __dsub_rn((double)lane_value(xv, d), (double)c[d]);
                     acc = __dadd_rn(acc, __dmul_rn(diff, diff));
                 }
             }

@@ -42,6 +42,12 @@ __device__ __forceinline__ int fixed_shift(float amax, int ng) {
     return 62 - e - (32 - __clz(ng));
 }
 
+// the value lane l holds, l the same in every lane (a scalar-register read, no
+// cross-lane traffic through LDS)
+__device__ __forceinline__ float lane_value(float v, int l) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
+}
+
 // v = hi + mid + rest with hi = bf16(v), mid = bf16(v - hi), round to nearest even;
 // two features per conversion instruction
 __device__ __forceinline__ void split8(const float (&v)[8], bf16x8& hi, bf16x8& mid) {
