@@ -587,12 +587,12 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
                 // unconditional loads (an unused slot reads the first mover's row again)
 #pragma unroll
                 for (int u = 0; u < MV; ++u)
-                    xq[u] = Xg[(size_t)__shfl(p, mb[u] >= 0 ? mb[u] : mb[0]) * D + lc];
+                    xq[u] = Xg[(size_t)__builtin_amdgcn_readlane(p, mb[u] >= 0 ? mb[u] : mb[0]) * D + lc];
 #pragma unroll
                 for (int u = 0; u < MV; ++u) {
                     if (mb[u] >= 0) {                       // uniform over the wave
-                        const int nb2 = __shfl(bi, mb[u]);
-                        const int ob2 = __shfl(old, mb[u]);
+                        const int nb2 = __builtin_amdgcn_readlane(bi, mb[u]);
+                        const int ob2 = __builtin_amdgcn_readlane(old, mb[u]);
                         if (lane < D) {
                             const long long qf = to_fixed(xq[u], fsh);
                             lds_add(&sums[(size_t)nb2 * SP + lane], qf);
