@@ -45,6 +45,8 @@ SMALL = {
     "paper": lambda: synth.paper_shape(),
     "ragged": lambda: synth.config5(G=17, nmin=64, nmax=700, D=20, S=6, seed=99),
     "lateoutliers": _late_outliers,
+    # the longest search the one-workgroup path takes: candidate numbers up to 2^16 - 1
+    "long1wg": lambda: synth.config2(N=65536, D=16, K=24, S=4, iters=6, seed=11),
     # shapes that take the multi-workgroup clustering path (more than 64 clusters,
     # or a search of more than 65536 candidates)
     "cfg4s": lambda: synth.config4(N=8192, K=256, ncentres=256),
@@ -432,3 +434,30 @@ def test_many_tiny_searches(kb):
     _sync()
     assert_rel_close(d.host("diam"), oracle.cluster_diameter(b.seg_off, b.koff, b.X, d.host("assign")),
                      what="diameter")
+
+
+def test_persistent_exact_ties_overflow_the_exact_list(kb, scorer):
+    # A configuration that Lloyd steps leave unchanged and in which 400 candidates lie
+    # exactly halfway between the two centroids in every step: rows at -2 (400), -1 (150)
+    # and 0 (400) make cluster 0 with mean exactly -1, rows at +1 (250) cluster 1.  The
+    # rows at 0 tie (lowest index wins), which is more than the 256 entries of the exact
+    # pass's list, so every step takes the scan over all candidates, and the later steps
+    # start from limits that were reset.
+    rng = np.random.default_rng(3)
+    x = np.concatenate([np.full(400, -2.0), np.full(150, -1.0), np.zeros(400), np.full(250, 1.0)])
+    rng.shuffle(x)
+    b = synth.config1(N=len(x), D=3, K=2)
+    b.X[:] = 0
+    b.X[:, 1] = x
+    cin = np.array([[0, -1, 0], [0, 1, 0]], np.float32)
+    import torch
+    for iters in (1, 2, 5):
+        d = kb.DeviceBatch(b, iters=iters)
+        d.cluster(cent_init=torch.from_numpy(cin).to(d.device))
+        _sync()
+        ora = oracle.cluster(b.seg_off, b.koff, b.X, iters, cent_init=cin)
+        want = (x > 0.5).astype(np.int32)
+        np.testing.assert_array_equal(ora.assign, want)
+        np.testing.assert_array_equal(d.host("assign"), want)
+        np.testing.assert_array_equal(d.host("counts"), [950, 250])
+        np.testing.assert_array_equal(d.host("cent"), cin)
