@@ -67,6 +67,7 @@ struct ClusterArgs {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kFlagCap = 256;      // LDS list of candidates waiting for the exact pass
+constexpr int kMoverBatch = 8;     // movers whose rows are requested together
 constexpr int kQueue = 128;        // per wave: candidates waiting to be scored (at most 31 + 64 at a time)
 
 // Cross-lane steps inside rows of 16 lanes (data-parallel primitives: no LDS
@@ -538,6 +539,36 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
     unsigned head = 0, tail = 0;       // (uniform) the queue holds entries head .. tail - 1, modulo kQueue
     int any = 0;
 
+    // Candidates that change cluster are moved between the fixed-point sums eight at
+    // a time, lanes over features: their fp32 rows are read again (all requests
+    // first), converted and moved.  An entry: candidate | new cluster << 16 |
+    // (old cluster + 1) << 23.
+    unsigned pend = 0;
+    int ph = 0, pt = 0;                // (uniform) entries ph .. pt - 1 wait, in lanes (index & 63)
+    const int lc = lane < D ? lane : 0;
+    auto drain = [&](int n) __attribute__((always_inline)) {
+        unsigned e[kMoverBatch];
+        float xq[kMoverBatch];
+#pragma unroll
+        for (int u = 0; u < kMoverBatch; ++u)
+            e[u] = (unsigned)__builtin_amdgcn_readlane((int)pend, (ph + (u < n ? u : 0)) & 63);
+#pragma unroll
+        for (int u = 0; u < kMoverBatch; ++u) xq[u] = Xg[(size_t)(e[u] & 0xffffu) * D + lc];
+#pragma unroll
+        for (int u = 0; u < kMoverBatch; ++u) {
+            if (u < n) {                                   // uniform over the wave
+                const int nb2 = (int)((e[u] >> 16) & 0x7fu);
+                const int ob2 = (int)(e[u] >> 23) - 1;
+                if (lane < D) {
+                    const long long qf = to_fixed(xq[u], fsh);
+                    lds_add(&sums[(size_t)nb2 * SP + lane], qf);
+                    if (ob2 >= 0) lds_add(&sums[(size_t)ob2 * SP + lane], -qf);
+                }
+            }
+        }
+        ph += n;
+    };
+
     // scores the first `count` (<= 32) candidates of the queue
     auto chunk = [&](int count) __attribute__((always_inline)) {
         const bool valid = m < count;
@@ -574,33 +605,17 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
                 if (old >= 0) { atomicSub(&cnt[old], 1); dirty[old] = 1; }
                 a.assign[(size_t)n0 + p] = bi;
             }
-            const int lc = lane < D ? lane : 0;
+            // the movers wait in a register queue (one entry per lane of `pend`) until
+            // eight of them can fetch their rows together
+            const unsigned info = (unsigned)p | ((unsigned)bi << 16) | ((unsigned)(old + 1) << 23);
             while (rem) {
-                constexpr int MV = 8;
-                int mb[MV];
-                float xq[MV];
-#pragma unroll
-                for (int u = 0; u < MV; ++u) {
-                    mb[u] = rem ? __ffs((int)rem) - 1 : -1;
-                    rem &= rem - 1;
-                }
-                // unconditional loads (an unused slot reads the first mover's row again)
-#pragma unroll
-                for (int u = 0; u < MV; ++u)
-                    xq[u] = Xg[(size_t)__builtin_amdgcn_readlane(p, mb[u] >= 0 ? mb[u] : mb[0]) * D + lc];
-#pragma unroll
-                for (int u = 0; u < MV; ++u) {
-                    if (mb[u] >= 0) {                       // uniform over the wave
-                        const int nb2 = __builtin_amdgcn_readlane(bi, mb[u]);
-                        const int ob2 = __builtin_amdgcn_readlane(old, mb[u]);
-                        if (lane < D) {
-                            const long long qf = to_fixed(xq[u], fsh);
-                            lds_add(&sums[(size_t)nb2 * SP + lane], qf);
-                            if (ob2 >= 0) lds_add(&sums[(size_t)ob2 * SP + lane], -qf);
-                        }
-                    }
-                }
+                const int mb = __ffs((int)rem) - 1;
+                rem &= rem - 1;
+                const unsigned e = (unsigned)__builtin_amdgcn_readlane((int)info, mb);
+                pend = lane == (pt & 63) ? e : pend;
+                ++pt;
             }
+            while (pt - ph >= kMoverBatch) drain(kMoverBatch);
         }
         if (valid && h == 0) {
             a.a_new[(size_t)n0 + p] = certain ? bi : (bi | kFlagBit);
@@ -677,6 +692,7 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
         }
     }
     if (tail != head) chunk((int)(tail - head));
+    if (pt != ph) drain(pt - ph);
     return any;   // bit 0: some candidate moved, bit 1: some candidate needs the exact pass
 }
 
