@@ -334,9 +334,10 @@ const char *kb_status_str(kb_status status);
  * (doubtful candidates are re-evaluated exactly in every mode); only speed
  * differs.
  *   0 (default)  matrix cores (bf16 x 3 split products) whenever Kmax <= 64, plus
- *                distance bounds: a tile of 32 candidates whose nearest centroid
- *                provably cannot have changed since the last step (triangle
- *                inequality on how far the centroids moved) is not scored again;
+ *                distance bounds: a candidate whose nearest centroid provably
+ *                cannot have changed since it was last scored (triangle
+ *                inequality on how far the centroids moved) is not scored again,
+ *                the others are packed into dense tiles;
  *   1            fp32 vector-ALU scores, every candidate scored in every step;
  *   2            matrix cores, every candidate scored in every step.
  * This is the one piece of process-wide state in the library; not thread-safe
