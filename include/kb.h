@@ -38,8 +38,8 @@
  *
  * Pointers.  Unless a comment says "host", every pointer is a DEVICE pointer to
  * memory the caller allocated and keeps owning.  The library allocates nothing
- * and keeps no state between calls (the benchmarking switch kb_set_scorer
- * aside); all scratch comes from the caller's workspace `ws` (device,
+ * and keeps no state between calls; all scratch comes from the caller's
+ * workspace `ws` (device,
  * >= kb_workspace_bytes(), 256-byte aligned, contents undefined before and
  * after a call).  The workspace holds, besides small tables, a bf16 copy of the
  * features, |x|^2, a proposal and an fp64 distance per candidate: about
@@ -107,7 +107,28 @@ typedef struct {
     float prior_n;    /* pseudo-visits added to every cluster arm (Alg. 1 starts at 1), >= 0 */
     float prior_mu;   /* mean reward of the pseudo-visits (Alg. 1 starts at 0.5) */
     int32_t iters;    /* Lloyd steps for kb_cluster / kb_round, >= 0 (>= 1 for kb_round) */
+    int32_t scorer;   /* how kb_cluster / kb_round form the fast distance scores of a Lloyd
+                       * step: one of KB_SCORER_*; 0 is the default.  Every mode gives
+                       * identical results (doubtful candidates are re-evaluated exactly in
+                       * every mode); only speed differs.  kb_cluster_step always runs the
+                       * default. */
 } kb_params;
+
+/* kb_params::scorer */
+enum {
+    /* bf16 x 3 split products on the matrix cores.  Searches on the one-workgroup
+     * path (K_g <= 64 and N_g <= 65536 for the whole batch) also keep distance
+     * bounds: a candidate whose nearest centroid provably cannot have changed
+     * since it was last scored (triangle inequality on how far the centroids
+     * moved) is not scored again, the others are packed into dense tiles. */
+    KB_SCORER_DEFAULT = 0,
+    /* fp32 fused multiply-adds on the vector ALU, every candidate scored in every
+     * step: the reference the matrix-core scorers are measured against. */
+    KB_SCORER_VECTOR_ALU = 1,
+    /* matrix cores, every candidate scored in every step (no distance bounds; on
+     * the multi-workgroup path this is what the default does as well). */
+    KB_SCORER_MATRIX_EVERY = 2
+};
 
 /* Inputs and outputs of kb_round: the union of the arguments of the three
  * stages, with the same meaning and layout as in their own entry points. */
@@ -329,20 +350,6 @@ kb_status kb_update_stats(const kb_batch *batch, const kb_params *params,
 
 /* Static, never NULL. */
 const char *kb_status_str(kb_status status);
-
-/* Benchmarking switch for the Lloyd step.  All modes give identical results
- * (doubtful candidates are re-evaluated exactly in every mode); only speed
- * differs.
- *   0 (default)  matrix cores (bf16 x 3 split products) whenever Kmax <= 64, plus
- *                distance bounds: a candidate whose nearest centroid provably
- *                cannot have changed since it was last scored (triangle
- *                inequality on how far the centroids moved) is not scored again,
- *                the others are packed into dense tiles;
- *   1            fp32 vector-ALU scores, every candidate scored in every step;
- *   2            matrix cores, every candidate scored in every step.
- * This is the one piece of process-wide state in the library; not thread-safe
- * against concurrent calls.  Returns KB_OK or KB_EINVAL. */
-int kb_set_scorer(int mode);
 
 /* Library version, "major.minor". Static. */
 const char *kb_version(void);

@@ -31,7 +31,8 @@ class kb_batch(ctypes.Structure):
 class kb_params(ctypes.Structure):
     _fields_ = [("peak_flops", ctypes.c_float), ("peak_bw", ctypes.c_float),
                 ("c", ctypes.c_float), ("prior_n", ctypes.c_float),
-                ("prior_mu", ctypes.c_float), ("iters", ctypes.c_int32)]
+                ("prior_mu", ctypes.c_float), ("iters", ctypes.c_int32),
+                ("scorer", ctypes.c_int32)]
 
 
 class kb_round_io(ctypes.Structure):
@@ -93,8 +94,6 @@ def lib() -> ctypes.CDLL:
         L.kb_status_str.restype = ctypes.c_char_p
         L.kb_status_str.argtypes = [ctypes.c_int]
         L.kb_version.restype = ctypes.c_char_p
-        L.kb_set_scorer.restype = ctypes.c_int
-        L.kb_set_scorer.argtypes = [ctypes.c_int]
         _lib = L
     return _lib
 
@@ -127,9 +126,12 @@ def make_batch(G, D, S, N, Kmax, Ksum, Nmax, seg_off, koff) -> kb_batch:
     return kb_batch(G, D, S, N, Kmax, Ksum, Nmax, _ptr(seg_off), _ptr(koff))
 
 
+KB_SCORER_DEFAULT, KB_SCORER_VECTOR_ALU, KB_SCORER_MATRIX_EVERY = range(3)
+
+
 def make_params(peak_flops=2.5e15, peak_bw=8e12, c=2.0, prior_n=0.0, prior_mu=0.5,
-                iters=1) -> kb_params:
-    return kb_params(peak_flops, peak_bw, c, prior_n, prior_mu, iters)
+                iters=1, scorer=KB_SCORER_DEFAULT) -> kb_params:
+    return kb_params(peak_flops, peak_bw, c, prior_n, prior_mu, iters, scorer)
 
 
 def kb_workspace_bytes(batch: kb_batch, params: Optional[kb_params] = None) -> int:
@@ -236,10 +238,6 @@ def kb_cluster_diameter(batch, X, assign, diam, ws, ws_bytes, stream=None, check
     return _check(s, "kb_cluster_diameter", check)
 
 
-def kb_set_scorer(mode: int) -> int:
-    return int(lib().kb_set_scorer(int(mode)))
-
-
 def kb_version() -> str:
     return lib().kb_version().decode()
 
@@ -252,7 +250,7 @@ class DeviceBatch:
     GPU and allocates every output and the workspace.  Holds the kb_batch /
     kb_params / kb_round_io structs that point into those tensors."""
 
-    def __init__(self, b, device="cuda:0", iters=None):
+    def __init__(self, b, device="cuda:0", iters=None, scorer=KB_SCORER_DEFAULT):
         import numpy as np
         import torch
         self.torch = torch
@@ -290,7 +288,7 @@ class DeviceBatch:
         self.nvalid = z((G,), torch.int32)
         self.batch = make_batch(G, D, S, N, b.Kmax, Ksum, b.Nmax, self.seg_off, self.koff)
         self.params = make_params(b.peak_flops, b.peak_bw, b.c, b.prior_n, b.prior_mu,
-                                  b.iters if iters is None else iters)
+                                  b.iters if iters is None else iters, scorer)
         self.ws_bytes = kb_workspace_bytes(self.batch, self.params)
         self.ws = z((max(self.ws_bytes, 256),), torch.uint8)
         self.io = kb_round_io(*[_ptr(x) for x in (
@@ -307,6 +305,14 @@ class DeviceBatch:
         return kb_cluster_step(self.batch, self.X, cent_in,
                                self.assign, self.cent if cent_out is None else cent_out,
                                self.counts, self.objective, self.ws, self.ws_bytes, **kw)
+
+    def cluster_one(self, cent_in, **kw):
+        """One Lloyd step through kb_cluster (iters = 1, cent_init = cent_in), which
+        unlike kb_cluster_step honours params.scorer."""
+        p = kb_params.from_buffer_copy(self.params)
+        p.iters = 1
+        return kb_cluster(self.batch, p, self.X, cent_in, self.assign, self.cent, self.counts,
+                          self.objective, self.ws, self.ws_bytes, **kw)
 
     def cluster(self, cent_init=None, **kw):
         return kb_cluster(self.batch, self.params, self.X, cent_init, self.assign, self.cent,

@@ -118,8 +118,9 @@ static kb_status check_cluster(const kb_batch* b, const float* X, const float* c
 }
 
 static kb_status do_cluster(const kb_batch* b, const float* X, const float* cent_init,
-                            int32_t iters, int32_t* assign, float* cent, int32_t* counts,
-                            float* objective, void* ws, hipStream_t st) {
+                            int32_t iters, int scorer, int32_t* assign, float* cent,
+                            int32_t* counts, float* objective, void* ws, hipStream_t st) {
+    if (scorer < KB_SCORER_DEFAULT || scorer > KB_SCORER_MATRIX_EVERY) return KB_EINVAL;
     kb_status s = check_cluster(b, X, cent_init, iters, assign, cent, counts, objective);
     if (s != KB_OK) return s;
     WsLayout w = ws_layout(*b);
@@ -135,6 +136,7 @@ static kb_status do_cluster(const kb_batch* b, const float* X, const float* cent
     c.tile_off = (const int32_t*)(base + w.tile_off); c.xn = (float*)(base + w.xn);
     c.lim = (float*)(base + w.geo_d2);      // (the representative pass uses this array at other times)
     c.split = (void*)(base + w.split); c.max_tiles = (int64_t)w.max_tiles;
+    c.scorer = scorer;
     if (w.use_big) return dev(launch_cluster_big(*b, c, w.big, base, st));
     return dev(launch_cluster(*b, c, st));
 }
@@ -206,7 +208,7 @@ kb_status kb_cluster_step(const kb_batch* batch, const float* X, const float* ce
     if (!cent_in) return KB_EINVAL;
     s = check_ws(batch, ws, ws_bytes);
     if (s != KB_OK) return s;
-    return do_cluster(batch, X, cent_in, 1, assign, cent_out, counts, objective, ws,
+    return do_cluster(batch, X, cent_in, 1, KB_SCORER_DEFAULT, assign, cent_out, counts, objective, ws,
                       (hipStream_t)stream);
 }
 
@@ -218,7 +220,8 @@ kb_status kb_cluster(const kb_batch* batch, const kb_params* params, const float
     if (!params) return KB_EINVAL;
     s = check_ws(batch, ws, ws_bytes);
     if (s != KB_OK) return s;
-    return do_cluster(batch, X, cent_init, params->iters, assign, cent, counts, objective, ws,
+    return do_cluster(batch, X, cent_init, params->iters, params->scorer, assign, cent, counts,
+                      objective, ws,
                       (hipStream_t)stream);
 }
 
@@ -393,6 +396,7 @@ kb_status kb_round(const kb_batch* batch, const kb_params* params, const kb_roun
     if (s != KB_OK) return s;
     if (!params || !io) return KB_EINVAL;
     if (params->iters < 1) return KB_EINVAL;
+    if (params->scorer < KB_SCORER_DEFAULT || params->scorer > KB_SCORER_MATRIX_EVERY) return KB_EINVAL;
     if (!io->bound) return KB_EINVAL;
     s = check_ws(batch, ws, ws_bytes);
     if (s != KB_OK) return s;
@@ -408,8 +412,8 @@ kb_status kb_round(const kb_batch* batch, const kb_params* params, const kb_roun
     hipStream_t st = (hipStream_t)stream;
     s = do_prune(batch, params, io->flops, io->bytes, io->incumbent, io->bound, io->alive, st);
     if (s != KB_OK) return s;
-    s = do_cluster(batch, io->X, nullptr, params->iters, io->assign, io->cent, io->counts,
-                   io->objective, ws, st);
+    s = do_cluster(batch, io->X, nullptr, params->iters, params->scorer, io->assign, io->cent,
+                   io->counts, io->objective, ws, st);
     if (s != KB_OK) return s;
     return do_ucb(batch, params, io->assign, io->alive, io->bound, io->visits, io->rsum, io->t,
                   io->Ncs, io->mu, io->ucb, io->sel, ws, true, st);
@@ -426,12 +430,6 @@ const char* kb_status_str(kb_status status) {
     return "KB_E?: unknown status";
 }
 
-const char* kb_version(void) { return "0.3"; }
-
-int kb_set_scorer(int mode) {
-    if (mode < 0 || mode > 2) return KB_EINVAL;
-    set_scorer(mode);
-    return KB_OK;
-}
+const char* kb_version(void) { return "0.4"; }
 
 }  // extern "C"

@@ -1166,6 +1166,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     for (int idx = tid; idx < K * SP; idx += kThreads) sums[idx] = 0;
     for (int j = tid; j < K; j += kThreads) { cnt[j] = 0; dirty[j] = 0; delta[j] = 0.f; }
     for (int j = K + tid; j < ((a.Kmax + 31) & ~31); j += kThreads) cn[j] = kBig;
+    if (tid == 0) *nflag = 0;
     __syncthreads();
 
     if (a.iters == 0) {
@@ -1223,7 +1224,6 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     bool first = true;
     float drift = 0.f;          // cumulative (largest + second largest) centroid move, rounded up
     for (int it = 0; it < a.iters; ++it) {
-        if (tid == 0) *nflag = 0;
         if constexpr (MT > 0) {
             if (a.use_bounds && it > 0) {
                 const int lane = tid & 63;
@@ -1293,6 +1293,9 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
                 moved = update(a, Xg, n0, ng, K, D, SP, first && MT == 0, fsh, sums, cnt, dw);
             }
             st |= block_or_i(moved, red, phase);
+            // every thread has read the counter before that barrier, and the barriers of
+            // the renewal below separate this reset from the next step's additions
+            if (tid == 0) *nflag = 0;
         }
         const int changed = st & 1;
         first = false;
@@ -1386,11 +1389,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
 
 constexpr size_t kMaxLds = 160 * 1024;
 
-int g_scorer = 0;   // 0 = matrix cores + distance bounds, 1 = vector ALU, 2 = matrix cores, every tile scored
-
 }  // namespace
-
-void set_scorer(int mode) { g_scorer = mode; }
 
 bool cluster_supported(const kb_batch& b) {
     const int kmax = b.Kmax > 0 ? b.Kmax : 1;
@@ -1406,7 +1405,7 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     a.counts = c.counts; a.objective = c.objective; a.a_new = c.a_new; a.order = c.order;
     a.tile_off = c.tile_off; a.xn = c.xn; a.split = reinterpret_cast<bf16x8*>(c.split);
     a.max_tiles = c.max_tiles;
-    a.use_bounds = g_scorer != 2;
+    a.use_bounds = c.scorer != 2;
     a.lim = c.lim;
 
     const int ds = (b.D + 15) / 16;   // 1..4 K-steps of 16 features
@@ -1414,7 +1413,7 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     const size_t lds = lds_layout(a.Kmax, b.D, 16 * ds + 4, b.Nmax).total;
     if (lds > kMaxLds) return hipErrorInvalidValue;
     int mt = a.Kmax <= 32 ? 1 : (a.Kmax <= 64 ? 2 : 0);
-    if (g_scorer == 1) mt = 0;
+    if (c.scorer == 1) mt = 0;
     const dim3 grid((unsigned)b.G), block(kThreads);
 #define KB_LAUNCH(DS_, MT_)                                                                     \
     do {                                                                                        \

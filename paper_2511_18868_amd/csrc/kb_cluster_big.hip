@@ -529,6 +529,101 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
     }
 }
 
+// The same step of the path with fp32 fused multiply-adds on the vector ALU
+// (scorer mode 1): the reference the matrix-core scorer is measured against.
+// One workgroup per chunk of kTilesPerChunk tiles; the search's centroids are
+// staged in LDS (every lane of a wave reads the same centroid entry, which LDS
+// broadcasts), a thread holds one candidate's row in registers at a time.  The
+// dot product is a chain of fused multiply-adds in two interleaved parts and
+// s_j = fma(-2, dot, |c_j|^2); with u = 2^-24,
+//   |s' - s| <= (D + 3) u (1 + o(1)) (|x|^2 + max_j |c_j|^2),
+// and kappa = (D + 4) u leaves room for the rounding of |x|^2, of E itself and of
+// the gap.  A candidate whose two best scores are not 2E apart goes to the full
+// exact pass.
+template <int DS>
+__global__ void __launch_bounds__(kThreads, 2) big_score_valu(BigArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int DP = 16 * DS;
+    const int tid = threadIdx.x;
+    const int c = blockIdx.x;
+    if (c >= a.chunk_off[a.G]) return;
+    const int g = upper_search(a.chunk_off, a.G, c);
+    int n0, ng, k0, K;
+    search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+    if (K > a.Kpad) K = a.Kpad;
+    if (ng <= 0 || K <= 0) return;
+    const int p0 = (c - a.chunk_off[g]) * kTilesPerChunk * 32;
+    const int p1 = p0 + kTilesPerChunk * 32 < ng ? p0 + kTilesPerChunk * 32 : ng;
+    if (p0 >= p1) return;
+    const int D = a.D;
+
+    float* cent = reinterpret_cast<float*>(smem);                   // [Kpad][DP], rows zero-padded
+    float* cn = cent + (size_t)a.Kpad * DP;                          // [Kpad]
+    int* lflag = reinterpret_cast<int*>(cn + a.Kpad);                // [kTilesPerChunk * 32]
+    int* lcount = lflag + kTilesPerChunk * 32;                       // [2]: count, base in the global list
+    if (tid == 0) lcount[0] = 0;
+    for (int idx = tid; idx < K * DP; idx += kThreads) {
+        const int j = idx / DP, d = idx - j * DP;
+        cent[idx] = d < D ? a.cent[(size_t)(k0 + j) * D + d] : 0.f;
+    }
+    for (int j = tid; j < K; j += kThreads) cn[j] = a.cnpad[(size_t)g * a.Kpad + j];
+    __syncthreads();
+
+    const float cnmax = __uint_as_float(a.cnmax_bits[(a.it & 1) * a.G + g]);
+    const float kappa = (float)(D + 4) * 5.9604644775390625e-08f;
+    const bool vec = (D & 3) == 0;
+    for (int p = p0 + tid; p < p1; p += kThreads) {
+        float x[DP];
+        const float* xr = a.X + (size_t)(n0 + p) * D;
+        if (vec) {
+#pragma unroll
+            for (int q = 0; q < DP / 4; ++q) {
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (4 * q < D) v = reinterpret_cast<const float4*>(xr)[q];
+                x[4 * q] = v.x; x[4 * q + 1] = v.y; x[4 * q + 2] = v.z; x[4 * q + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int d = 0; d < DP; ++d) x[d] = d < D ? xr[d] : 0.f;
+        }
+        float xn = 0.f;
+#pragma unroll
+        for (int d = 0; d < DP; ++d) xn = fmaf(x[d], x[d], xn);
+        float best = INFINITY, second = INFINITY;
+        int bi = 0;
+        for (int j = 0; j < K; ++j) {
+            const float4* cr = reinterpret_cast<const float4*>(cent + (size_t)j * DP);
+            float d0 = 0.f, d1 = 0.f;
+#pragma unroll
+            for (int q = 0; q < DP / 4; ++q) {
+                const float4 cv = cr[q];
+                d0 = fmaf(x[4 * q], cv.x, d0);
+                d1 = fmaf(x[4 * q + 1], cv.y, d1);
+                d0 = fmaf(x[4 * q + 2], cv.z, d0);
+                d1 = fmaf(x[4 * q + 3], cv.w, d1);
+            }
+            const float sc = fmaf(-2.f, d0 + d1, cn[j]);
+            const bool lt = sc < best;
+            second = lt ? best : fminf(second, sc);
+            bi = lt ? j : bi;
+            best = lt ? sc : best;
+        }
+        const float E = kappa * (xn + cnmax);
+        const bool certain = (K == 1) || ((second - best) > 2.f * E);
+        a.next[(size_t)n0 + p] = bi;
+        if (!certain) lflag[atomicAdd(&lcount[0], 1)] = n0 + p;      // at most one entry per candidate of the chunk
+    }
+    __syncthreads();
+    const int nl = lcount[0];
+    if (nl > 0) {
+        if (tid == 0) lcount[1] = atomicAdd(&a.nflag[0], nl);
+        __syncthreads();
+        const int64_t pos0 = lcount[1];
+        for (int i = tid; i < nl; i += kThreads)
+            if (pos0 + i < a.N) a.flist[pos0 + i] = lflag[i];
+    }
+}
+
 // Short exact pass: a doubtful candidate whose possible nearest centroids are
 // all named (at most eight) needs the exact distance to those only.  Eight
 // threads per candidate, one per named centroid; each forms its squared distance
@@ -947,7 +1042,10 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
     const unsigned chunk_blocks = (unsigned)w.max_chunks;
     const size_t lds = (size_t)kGroupTiles * ds * 2 * 64 * 16 + (size_t)4 * kGroupTiles * 64 * 8 +
                        (size_t)kTilesPerChunk * 32 * (16 + 4) + 16;
-    if (lds > 160 * 1024) return hipErrorInvalidValue;
+    // the vector-ALU scorer stages a search's centroids in LDS instead
+    const size_t lds_valu = (size_t)w.kpad * (16 * ds + 1) * 4 + (size_t)kTilesPerChunk * 32 * 4 + 16;
+    if (lds > 160 * 1024 || lds_valu > 160 * 1024) return hipErrorInvalidValue;
+    const bool valu = c.scorer == KB_SCORER_VECTOR_ALU;
     const dim3 upd_grid((unsigned)((b.N + kUpdateRange - 1) / kUpdateRange),
                         (unsigned)((a.Kmax + kRowsPerGroup - 1) / kRowsPerGroup));
 
@@ -955,6 +1053,9 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
     do {                                                                                         \
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(big_score<DS_>),        \
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+        if (e != hipSuccess) return e;                                                           \
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(big_score_valu<DS_>),              \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_valu);      \
         if (e != hipSuccess) return e;                                                           \
         if (tile_blocks) hipLaunchKernelGGL(big_presplit<DS_>, dim3(tile_blocks), dim3(kThreads), 0, st, a); \
         for (int it = 0; it < c.iters; ++it) {                                                   \
@@ -964,7 +1065,11 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
             a.next = mine ? c.assign : other;                                                    \
             a.prev = mine ? other : c.assign;                                                    \
             hipLaunchKernelGGL(big_renew<DS_>, dim3(row_blocks), dim3(kThreads), 0, st, a);      \
-            hipLaunchKernelGGL(big_score<DS_>, dim3(chunk_blocks), dim3(kThreads), lds, st, a);  \
+            if (valu)                                                                            \
+                hipLaunchKernelGGL(big_score_valu<DS_>, dim3(chunk_blocks), dim3(kThreads),      \
+                                   lds_valu, st, a);                                             \
+            else                                                                                 \
+                hipLaunchKernelGGL(big_score<DS_>, dim3(chunk_blocks), dim3(kThreads), lds, st, a); \
             hipLaunchKernelGGL(big_exact_few, dim3(512), dim3(kThreads), 0, st, a);              \
             hipLaunchKernelGGL(big_exact, dim3(1024), dim3(kThreads), 0, st, a);                 \
             hipLaunchKernelGGL(big_update, upd_grid, dim3(kThreads), 0, st, a);                  \

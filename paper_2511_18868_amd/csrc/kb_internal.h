@@ -76,12 +76,12 @@ struct ClusterCall {
     void* split;
     int64_t max_tiles;
     float* lim;               // float [N] scratch of the fused kernel (every candidate's drift limit)
+    int scorer;               // kb_params::scorer: 0 default, 1 vector ALU only, 2 matrix cores without bounds
 };
 hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t st);
 hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const BigWs& w, char* ws,
                               hipStream_t st);
 bool cluster_supported(const kb_batch& b);   // shape fits the compiled clustering kernels
-void set_scorer(int mode);                   // 0 default, 1 vector ALU only, 2 matrix cores without bounds
 
 struct UcbCall {
     const int32_t* assign;

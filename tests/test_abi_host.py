@@ -26,14 +26,14 @@ def test_exports_every_declared_symbol(L):
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(kb_[a-z_]+)\s*\(", hdr))
     assert {"kb_prune", "kb_cluster_step", "kb_cluster", "kb_ucb_select", "kb_round",
-            "kb_workspace_bytes", "kb_status_str", "kb_version", "kb_set_scorer", "kb_sample"} <= names
+            "kb_workspace_bytes", "kb_status_str", "kb_version", "kb_sample"} <= names
     for n in names:
         assert hasattr(L, n), n
 
 
 def test_struct_layout_matches_header():
     assert ctypes.sizeof(kb.kb_batch) == 56
-    assert ctypes.sizeof(kb.kb_params) == 24
+    assert ctypes.sizeof(kb.kb_params) == 28 and kb.kb_params.scorer.offset == 24
     assert ctypes.sizeof(kb.kb_round_io) == 17 * 8
     assert kb.kb_batch.N.offset == 16 and kb.kb_batch.seg_off.offset == 40
 
@@ -196,11 +196,18 @@ def test_loop_entry_points_argument_errors(L):
                                   FAKE, FAKE, FAKE, big, stream=0, check=False) == kb.KB_EINVAL
 
 
-def test_scorer_switch(L):
-    assert kb.kb_set_scorer(1) == kb.KB_OK
-    assert kb.kb_set_scorer(2) == kb.KB_OK
-    assert kb.kb_set_scorer(0) == kb.KB_OK
-    assert kb.kb_set_scorer(7) == kb.KB_EINVAL
+def test_scorer_mode_is_validated(L):
+    """The scorer mode travels in kb_params (the library keeps no state); a value
+    outside KB_SCORER_* is rejected before anything is enqueued."""
+    assert not hasattr(L, "kb_set_scorer")
+    b = _batch()
+    big = 1 << 20
+    io = kb.kb_round_io(*([FAKE] * 17))
+    for bad in (-1, 3, 7):
+        p = kb.make_params(iters=2, scorer=bad)
+        assert kb.kb_cluster(b, p, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, big, stream=0,
+                             check=False) == kb.KB_EINVAL
+        assert kb.kb_round(b, p, io, FAKE, big, stream=0, check=False) == kb.KB_EINVAL
 
 
 def test_missing_library_fails_loudly(monkeypatch):

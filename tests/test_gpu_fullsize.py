@@ -2,9 +2,8 @@
 launch configuration bench.py times (kb_round on the whole batch).
 
 Configurations 1 and 2 are already full size in test_gpu_parity.py.  3 and 5
-are compared with the oracle element by element.  For 4 (one search of 2^20
-candidates, 256 clusters) the oracle is evaluated on sampled candidates and
-clusters, and properties that hold at any size are checked on everything."""
+are compared with the oracle element by element, and so is 4 (one search of
+2^20 candidates, 256 clusters), step by step over its ten Lloyd steps."""
 import numpy as np
 import pytest
 
@@ -22,7 +21,6 @@ def kb():
         pytest.skip("no GPU")
     from paper_2511_18868_amd import binding
     binding.lib()
-    binding.kb_set_scorer(0)
     return binding
 
 
@@ -130,46 +128,61 @@ def test_config5_full(kb):
     _full_round_vs_oracle(kb, synth.config5(), "config5")
 
 
+def _oracle_assign_sliced(b, cent, parts=64):
+    """The oracle's nearest centroid for every candidate of a one-search batch.  The
+    rows are handed over as `parts` slices with a copy of the centroids each, which
+    the oracle's loop over searches spreads over the host threads."""
+    assert b.G == 1
+    K = int(b.koff[1])
+    seg = np.linspace(0, b.N, parts + 1).astype(np.int32)
+    ko = (np.arange(parts + 1) * K).astype(np.int32)
+    return oracle.assign(seg, ko, b.X, np.tile(cent, (parts, 1)))
+
+
 def test_config4_full(kb):
+    """One search of 2^20 candidates, 256 clusters, 10 Lloyd steps: every step is
+    compared with the oracle on EVERY candidate.  Both sides start each step from the
+    same centroids (the device's); where the oracle flags a near-tie the device's
+    choice is adopted, everything else must be equal."""
     import torch
     b = synth.config4()
     d = kb.DeviceBatch(b)
-    X64 = None
-    rng = np.random.default_rng(0)
-    sample = np.sort(rng.choice(b.N, size=4096, replace=False))
-    sub_seg = np.array([0, len(sample)], np.int32)
-
-    def check_step(assign, cent_in, cent_out, counts, objective, what):
-        # sampled candidates: the oracle's nearest centroid
-        a_s, _, flag = oracle.assign(sub_seg, b.koff, b.X[sample], cent_in)
-        okm = flag == 0
-        np.testing.assert_array_equal(assign[sample][okm], a_s[okm], err_msg=what)
-        assert okm.mean() > 0.99
-        # everything: sizes, centroid = mean of members, objective by definition
-        np.testing.assert_array_equal(counts, np.bincount(assign, minlength=b.Ksum))
-        upd, cnt2 = oracle.update(b.seg_off, b.koff, b.X, cent_in, assign)
-        assert_cent_close(cent_out, upd, what)
-        diff = b.X.astype(np.float64) - cent_in.astype(np.float64)[assign]
-        J = float(np.einsum("ij,ij->", diff, diff))
-        assert_rel_close(objective, np.array([J]), what=what + " objective")
-
-    # one step from random centroids
-    cin = synth.random_centroids(b, 3)
-    d.cluster_step(torch.from_numpy(cin).to(d.device))
-    _sync()
-    check_step(d.host("assign"), cin, d.host("cent"), d.host("counts"), d.host("objective"),
-               "config4 step")
-    # the full round; its clustering is checked against the 9-step centroids
-    d9 = kb.DeviceBatch(b, iters=b.iters - 1)
-    d9.cluster()
+    cur = b.X[:b.Ksum].copy()                      # init = first K rows
+    prevJ = np.inf
+    nflag_total = 0
+    for it in range(b.iters):
+        d.cluster_step(torch.from_numpy(cur).to(d.device))
+        _sync()
+        got = {k: d.host(k).copy() for k in ("assign", "cent", "counts", "objective")}
+        a_o, mind2, flag = _oracle_assign_sliced(b, cur)
+        diff = got["assign"] != a_o
+        assert not (diff & (flag == 0)).any(), \
+            f"step {it}: {(diff & (flag == 0)).sum()} unflagged assignments differ"
+        nflag_total += int(flag.sum())
+        adopted = np.where(flag != 0, got["assign"], a_o)
+        # flagged candidates: the device's choice is one of the two nearly equal nearest
+        for k in np.where(diff)[0]:
+            dk = ((b.X[k].astype(np.float64) - cur[got["assign"][k]].astype(np.float64)) ** 2).sum()
+            assert dk <= mind2[k] * (1 + 2e-6)
+        np.testing.assert_array_equal(got["counts"], np.bincount(adopted, minlength=b.Ksum))
+        upd, _ = oracle.update(b.seg_off, b.koff, b.X, cur, adopted)
+        assert_cent_close(got["cent"], upd, f"config4 step {it}")
+        assert_rel_close(got["objective"], np.array([mind2.sum()]), what=f"config4 step {it} objective")
+        assert got["objective"][0] <= prevJ * (1 + 1e-6)
+        prevJ = float(got["objective"][0])
+        print(f"[config4] step {it}: {b.N} assignments compared, {int(flag.sum())} flagged by the "
+              f"oracle, {int(diff.sum())} of those resolved differently", flush=True)
+        cur = got["cent"]
+    assert nflag_total < 1e-4 * b.N * b.iters
+    last = got
+    # the fused call and the full round give the bytes of the iterated steps
     d.round()
     _sync()
+    for k, v in last.items():
+        np.testing.assert_array_equal(d.host(k).view(np.uint8), v.view(np.uint8), err_msg=k)
     bound, alive = oracle.prune(b.seg_off, b.flops, b.bytes_, b.peak_flops, b.peak_bw, b.incumbent)
     np.testing.assert_array_equal(d.host("bound").view(np.uint32), bound.view(np.uint32))
     np.testing.assert_array_equal(d.host("alive"), alive)
-    check_step(d.host("assign"), d9.host("cent"), d.host("cent"), d.host("counts"),
-               d.host("objective"), "config4 last step")
-    assert d.host("objective")[0] <= d9.host("objective")[0] * (1 + 1e-6)
     u = oracle.ucb_select(b.seg_off, b.koff, b.S, d.host("assign"), alive, bound, b.visits, b.rsum,
                           b.t, b.c)
     np.testing.assert_array_equal(d.host("Ncs"), u.Ncs)
@@ -183,4 +196,11 @@ def test_config4_full(kb):
     _sync()
     for k, v in first.items():
         np.testing.assert_array_equal(d.host(k).view(np.uint8), v.view(np.uint8), err_msg=k)
+    # the fp32 vector-ALU scorer reaches the same bytes
+    dv = kb.DeviceBatch(b, scorer=kb.KB_SCORER_VECTOR_ALU)
+    dv.cluster()
+    _sync()
+    for k in ("assign", "cent", "counts", "objective"):
+        np.testing.assert_array_equal(dv.host(k).view(np.uint8), first[k].view(np.uint8), err_msg=k)
+    del dv
     _loop_steps_vs_oracle(kb, b, d, "config4")

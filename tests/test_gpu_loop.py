@@ -21,7 +21,6 @@ def kb():
         pytest.skip("no GPU")
     from paper_2511_18868_amd import binding
     binding.lib()
-    binding.kb_set_scorer(0)
     return binding
 
 

@@ -56,11 +56,19 @@ SMALL = {
 
 
 @pytest.fixture(scope="module", params=[0, 1, 2], ids=["bounds", "vectoralu", "matrixcore"])
-def scorer(kb, request):
-    """Every mode of the Lloyd step must give the same results."""
-    assert kb.kb_set_scorer(request.param) == 0
-    yield request.param
-    kb.kb_set_scorer(0)
+def scorer(request):
+    """kb_params.scorer: every mode of the Lloyd step must give the same results."""
+    return request.param
+
+
+def _multi_workgroup(b):
+    return b.Kmax > 64 or b.Nmax > 65536
+
+
+def _skip_repeat(b, scorer):
+    if scorer == 2 and _multi_workgroup(b):
+        pytest.skip("the multi-workgroup path scores every tile in the default mode already: "
+                    "mode 2 is the same code path as mode 0 there")
 
 
 @pytest.fixture(scope="module", params=list(SMALL))
@@ -98,19 +106,23 @@ def test_prune_extremes_and_null_bound(kb):
 
 # ---------------------------------------------------------- cluster step
 
-def _gpu_step(d, cent_in_np):
+def _gpu_step(d, cent_in_np, scorer=0):
     import torch
     cin = torch.from_numpy(np.ascontiguousarray(cent_in_np)).to(d.device)
-    d.cluster_step(cin)
+    if scorer == 0:
+        d.cluster_step(cin)
+    else:
+        d.cluster_one(cin)      # kb_cluster, iters = 1: the entry that takes the scorer mode
     _sync()
     return {k: d.host(k) for k in ("assign", "cent", "counts", "objective")}
 
 
 def test_cluster_step_strict(kb, case, scorer):
     name, b = case
-    d = kb.DeviceBatch(b)
+    _skip_repeat(b, scorer)
+    d = kb.DeviceBatch(b, scorer=scorer)
     cin = synth.random_centroids(b, 1)
-    got = _gpu_step(d, cin)
+    got = _gpu_step(d, cin, scorer)
     ora = oracle.cluster_step(b.seg_off, b.koff, b.X, cin)
     ndiff = compare_step(b, got, ora, name)
     assert ndiff == 0, f"{name}: {ndiff} flagged candidates resolved differently"
@@ -119,12 +131,13 @@ def test_cluster_step_strict(kb, case, scorer):
 
 def test_cluster_lockstep_trajectory(kb, case, scorer):
     name, b = case
-    d = kb.DeviceBatch(b)
+    _skip_repeat(b, scorer)
+    d = kb.DeviceBatch(b, scorer=scorer)
     cur = np.concatenate([b.X[b.seg_off[g]:b.seg_off[g] + (b.koff[g + 1] - b.koff[g])]
                           for g in range(b.G)])
     prevJ = np.full(b.G, np.inf)
     for it in range(min(b.iters, 12)):
-        got = _gpu_step(d, cur)
+        got = _gpu_step(d, cur, scorer)
         ora = oracle.cluster_step(b.seg_off, b.koff, b.X, cur)
         compare_step(b, got, ora, f"{name} step {it}")
         assert np.all(got["objective"] <= prevJ * (1 + 1e-5))     # non-increasing
@@ -134,7 +147,8 @@ def test_cluster_lockstep_trajectory(kb, case, scorer):
 
 def test_cluster_fused_matches_oracle(kb, case, scorer):
     name, b = case
-    d = kb.DeviceBatch(b)
+    _skip_repeat(b, scorer)
+    d = kb.DeviceBatch(b, scorer=scorer)
     d.cluster()
     _sync()
     ora = oracle.cluster(b.seg_off, b.koff, b.X, b.iters)
@@ -165,7 +179,7 @@ def test_cluster_fused_matches_oracle(kb, case, scorer):
 def test_cluster_fused_equals_iterated_steps_and_is_deterministic(kb, scorer):
     import torch
     b = synth.config5(G=40, seed=3)
-    d = kb.DeviceBatch(b, iters=6)
+    d = kb.DeviceBatch(b, iters=6, scorer=scorer)
     d.cluster()
     _sync()
     first = {k: d.host(k).copy() for k in ("assign", "cent", "counts", "objective")}
@@ -177,7 +191,7 @@ def test_cluster_fused_equals_iterated_steps_and_is_deterministic(kb, scorer):
     cur = np.concatenate([b.X[b.seg_off[g]:b.seg_off[g] + (b.koff[g + 1] - b.koff[g])]
                           for g in range(b.G)])
     for it in range(6):
-        got = _gpu_step(d, cur)
+        got = _gpu_step(d, cur, scorer)
         cur = got["cent"]
     for k in first:
         np.testing.assert_array_equal(got[k].view(np.uint32), first[k].view(np.uint32), err_msg=k)
@@ -187,7 +201,7 @@ def test_cluster_edge_cases(kb, scorer):
     import torch
     # iters = 0: only the initial centroids come out
     b = synth.config1(N=64, D=4, K=4)
-    d = kb.DeviceBatch(b, iters=0)
+    d = kb.DeviceBatch(b, iters=0, scorer=scorer)
     d.assign.fill_(-5)
     d.cluster()
     _sync()
@@ -195,14 +209,14 @@ def test_cluster_edge_cases(kb, scorer):
     assert (d.host("assign") == -5).all()
     # K = N: identity, zero objective; K = 1: column means
     b = synth.config1(N=40, D=6, K=40)
-    d = kb.DeviceBatch(b, iters=3)
+    d = kb.DeviceBatch(b, iters=3, scorer=scorer)
     d.cluster()
     _sync()
     np.testing.assert_array_equal(d.host("assign"), np.arange(40))
     assert d.host("objective")[0] == 0.0
     np.testing.assert_array_equal(d.host("cent"), b.X)
     b = synth.config2(N=500, D=12, K=1)
-    d = kb.DeviceBatch(b, iters=2)
+    d = kb.DeviceBatch(b, iters=2, scorer=scorer)
     d.cluster()
     _sync()
     assert_cent_close(d.host("cent")[0], b.X.astype(np.float64).mean(0))
@@ -210,7 +224,7 @@ def test_cluster_edge_cases(kb, scorer):
     # duplicate first rows: cluster 1 is empty after the first step and keeps its centroid
     b = synth.config1(N=64, D=4, K=4)
     b.X[1] = b.X[0]
-    d = kb.DeviceBatch(b, iters=1)
+    d = kb.DeviceBatch(b, iters=1, scorer=scorer)
     d.cluster()
     _sync()
     ora = oracle.cluster(b.seg_off, b.koff, b.X, 1)
@@ -221,8 +235,8 @@ def test_cluster_edge_cases(kb, scorer):
     b = synth.config1(N=64, D=2, K=3)
     b.X[:] = np.random.default_rng(0).integers(-3, 4, size=(64, 2)).astype(np.float32)
     cin = np.array([[0, 0], [2, 0], [0, 2]], np.float32)
-    d = kb.DeviceBatch(b)
-    got = _gpu_step(d, cin)
+    d = kb.DeviceBatch(b, scorer=scorer)
+    got = _gpu_step(d, cin, scorer)
     ora = oracle.cluster_step(b.seg_off, b.koff, b.X, cin)
     assert ora.flag.sum() > 5
     np.testing.assert_array_equal(got["assign"], ora.assign)
@@ -240,7 +254,7 @@ def test_empty_searches(kb, scorer):
     b.G = len(ng2)
     b.incumbent = np.insert(b.incumbent, ins, 1.0).astype(np.float32)
     b.t = np.insert(b.t, ins, 1).astype(np.int64)
-    d = kb.DeviceBatch(b)
+    d = kb.DeviceBatch(b, scorer=scorer)
     d.objective.fill_(-1.0)
     d.round()
     _sync()
@@ -338,7 +352,8 @@ def test_ucb_real_valued_rewards(kb):
 
 def test_round_matches_oracle_and_composition(kb, case, scorer):
     name, b = case
-    d = kb.DeviceBatch(b)
+    _skip_repeat(b, scorer)
+    d = kb.DeviceBatch(b, scorer=scorer)
     d.round()
     _sync()
     keys = ("bound", "alive", "assign", "cent", "counts", "objective", "Ncs", "mu", "ucb", "sel")
@@ -364,7 +379,7 @@ def test_round_matches_oracle_and_composition(kb, case, scorer):
         assert m[ks - b.seg_off[g]]
         assert got["bound"][ks] == got["bound"][sl][m].min()
     # composition: the three calls made separately give the same bytes
-    d2 = kb.DeviceBatch(b)
+    d2 = kb.DeviceBatch(b, scorer=scorer)
     d2.prune(); d2.cluster(); d2.ucb_select()
     _sync()
     for k in keys:
@@ -452,7 +467,7 @@ def test_persistent_exact_ties_overflow_the_exact_list(kb, scorer):
     cin = np.array([[0, -1, 0], [0, 1, 0]], np.float32)
     import torch
     for iters in (1, 2, 5):
-        d = kb.DeviceBatch(b, iters=iters)
+        d = kb.DeviceBatch(b, iters=iters, scorer=scorer)
         d.cluster(cent_init=torch.from_numpy(cin).to(d.device))
         _sync()
         ora = oracle.cluster(b.seg_off, b.koff, b.X, iters, cent_init=cin)

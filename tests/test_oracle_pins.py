@@ -274,10 +274,11 @@ def test_tie_breaks_lowest_index():
 
 def test_near_tie_flag_threshold():
     # 1-D: centroids at 0 and 2; x = 1 + e has d1 = (1+e)^2, d2 = (1-e)^2,
-    # relative gap ~ 4e.  e = 1e-8 flags, e = 1e-3 does not.
+    # relative gap ~ 4e.  e = 0 (an exact tie) flags, e = 1e-3 does not.  (Where the
+    # threshold lies in between is pinned in test_oracle_pins_flags.py.)
     seg, ko = _one(2, 2)
     cin = np.array([[0.0], [2.0]], np.float32)
-    x = np.array([[1.0 + 2.0 ** -24 * 0 + 1e-3], [1.0]], np.float32)
+    x = np.array([[1.0 + 1e-3], [1.0]], np.float32)
     r = oracle.cluster_step(seg, ko, x, cin)
     np.testing.assert_array_equal(r.flag, [0, 1])
     np.testing.assert_array_equal(r.assign, [1, 0])
