@@ -38,8 +38,8 @@
  *
  * Pointers.  Unless a comment says "host", every pointer is a DEVICE pointer to
  * memory the caller allocated and keeps owning.  The library allocates nothing
- * and keeps no state between calls; all scratch comes from the caller's
- * workspace `ws` (device,
+ * and keeps no state between calls (kb_ucb_select_static aside, which says what
+ * it keeps); all scratch comes from the caller's workspace `ws` (device,
  * >= kb_workspace_bytes(), 256-byte aligned, contents undefined before and
  * after a call).  The workspace holds, besides small tables, a bf16 copy of the
  * features, |x|^2, a proposal and an fp64 distance per candidate: about
@@ -217,6 +217,30 @@ kb_status kb_ucb_select(const kb_batch *batch, const kb_params *params,
 kb_status kb_round(const kb_batch *batch, const kb_params *params,
                    const kb_round_io *io, void *ws, size_t ws_bytes,
                    void *stream);
+
+/* kb_ucb_select for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same inputs, outputs, results and errors as kb_ucb_select,
+ * without ws: the scratch (the scheduling order of the searches and, for
+ * searches of more than 16384 candidates, the partial cluster-arm tables) lives
+ * in a static device array of 2.9 MB inside the library, one copy per GPU, held
+ * until the process ends.  The call allocates and frees nothing.  Limits
+ * (KB_EUNSUPPORTED beyond): G <= KB_STATIC_MAX_G; and when Nmax > 16384 also
+ * Ksum <= KB_STATIC_MAX_KSUM and Ksum * S <= KB_STATIC_MAX_KS.  The scratch
+ * belongs to the device that is current when the call is made, which must be
+ * the device of `stream`.  All calls on one GPU share it and it keeps the last
+ * call's contents (every call rewrites what it reads): two calls that overlap on
+ * one GPU - different streams or host threads - race; calls on one stream are
+ * ordered and safe.  The address of the array is looked up on the first call on
+ * each device and kept for the life of the process. */
+#define KB_STATIC_MAX_G 65536
+#define KB_STATIC_MAX_KSUM 65536
+#define KB_STATIC_MAX_KS 131072
+kb_status kb_ucb_select_static(const kb_batch *batch, const kb_params *params,
+                               const int32_t *assign, const uint8_t *alive,
+                               const float *bound, const int32_t *visits,
+                               const float *rsum, const int64_t *t, int32_t *Ncs,
+                               float *mu, float *ucb, int32_t *sel, void *stream);
 
 /* Parameters of the in-cluster draw. */
 typedef struct {

@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.kb_cluster.argtypes = [pb, pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.kb_ucb_select.restype = ctypes.c_int
         L.kb_ucb_select.argtypes = [pb, pp] + [vp] * 10 + [vp, sz, vp]
+        L.kb_ucb_select_static.restype = ctypes.c_int
+        L.kb_ucb_select_static.argtypes = [pb, pp] + [vp] * 10 + [vp]
         L.kb_round.restype = ctypes.c_int
         L.kb_round.argtypes = [pb, pp, ctypes.POINTER(kb_round_io), vp, sz, vp]
         L.kb_sample.restype = ctypes.c_int
@@ -167,6 +169,14 @@ def kb_ucb_select(batch, params, assign, alive, bound, visits, rsum, t, Ncs, mu,
                             _ptr(bound), _ptr(visits), _ptr(rsum), _ptr(t), _ptr(Ncs), _ptr(mu),
                             _ptr(ucb), _ptr(sel), _ptr(ws), ws_bytes, _stream(stream))
     return _check(s, "kb_ucb_select", check)
+
+
+def kb_ucb_select_static(batch, params, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel,
+                         stream=None, check=True):
+    s = lib().kb_ucb_select_static(ctypes.byref(batch), ctypes.byref(params), _ptr(assign),
+                                   _ptr(alive), _ptr(bound), _ptr(visits), _ptr(rsum), _ptr(t),
+                                   _ptr(Ncs), _ptr(mu), _ptr(ucb), _ptr(sel), _stream(stream))
+    return _check(s, "kb_ucb_select_static", check)
 
 
 def kb_round(batch, params, io: kb_round_io, ws, ws_bytes, stream=None, check=True):

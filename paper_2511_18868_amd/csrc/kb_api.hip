@@ -1,6 +1,7 @@
 // C-ABI entry points: host-side validation, workspace layout and dispatch.
 // Nothing here synchronises with the device or allocates memory.
 #include "kb_internal.h"
+#include <mutex>
 
 namespace kb {
 
@@ -154,31 +155,87 @@ static kb_status check_ucb(const kb_batch* b, const kb_params* p, const int32_t*
     return KB_OK;
 }
 
+// device scratch of the selection step
+struct UcbScratch {
+    int32_t* order;                 // [G]
+    int32_t* tile_off;              // [G + 1] (written by the ordering kernel, not read here)
+    unsigned* gN;                   // tables of the chunked path, NULL: one workgroup per search
+    unsigned long long* gR;
+    unsigned* gnalive;
+    unsigned long long* gkmin;
+};
+
+static UcbScratch ucb_scratch_in_ws(const kb_batch* b, void* ws) {
+    const WsLayout w = ws_layout(*b);
+    char* base = (char*)ws;
+    UcbScratch u;
+    u.order = (int32_t*)(base + w.order);
+    u.tile_off = (int32_t*)(base + w.tile_off);
+    u.gN = nullptr; u.gR = nullptr; u.gnalive = nullptr; u.gkmin = nullptr;
+    if (w.ucb_chunked) {
+        u.gN = (unsigned*)(base + w.ucb_N); u.gR = (unsigned long long*)(base + w.ucb_R);
+        u.gnalive = (unsigned*)(base + w.ucb_nalive); u.gkmin = (unsigned long long*)(base + w.ucb_kmin);
+    }
+    return u;
+}
+
 static kb_status do_ucb(const kb_batch* b, const kb_params* p, const int32_t* assign,
                         const uint8_t* alive, const float* bound, const int32_t* visits,
                         const float* rsum, const int64_t* t, int32_t* Ncs, float* mu,
-                        float* ucb, int32_t* sel, void* ws, bool have_order, hipStream_t st,
-                        const uint8_t* M = nullptr, bool optional_mask_inputs = false) {
+                        float* ucb, int32_t* sel, const UcbScratch& u, bool have_order,
+                        hipStream_t st, const uint8_t* M = nullptr,
+                        bool optional_mask_inputs = false) {
     kb_status s = check_ucb(b, p, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel,
                             optional_mask_inputs);
     if (s != KB_OK) return s;
-    WsLayout w = ws_layout(*b);
-    char* base = (char*)ws;
-    int32_t* order = (int32_t*)(base + w.order);
     if (!have_order) {
-        hipError_t e = launch_order(*b, order, (int32_t*)(base + w.tile_off), nullptr, st);
+        hipError_t e = launch_order(*b, u.order, u.tile_off, nullptr, st);
         if (e != hipSuccess) return KB_EDEVICE;
     }
     UcbCall c;
     c.assign = assign; c.alive = alive; c.bound = bound; c.M = M; c.visits = visits; c.rsum = rsum;
     c.t = t; c.c = p->c; c.prior_n = p->prior_n; c.prior_mu = p->prior_mu;
-    c.Ncs = Ncs; c.mu = mu; c.ucb = ucb; c.sel = sel; c.order = order;
-    c.gN = nullptr; c.gR = nullptr; c.gnalive = nullptr; c.gkmin = nullptr;
-    if (w.ucb_chunked) {
-        c.gN = (unsigned*)(base + w.ucb_N); c.gR = (unsigned long long*)(base + w.ucb_R);
-        c.gnalive = (unsigned*)(base + w.ucb_nalive); c.gkmin = (unsigned long long*)(base + w.ucb_kmin);
-    }
+    c.Ncs = Ncs; c.mu = mu; c.ucb = ucb; c.sel = sel; c.order = u.order;
+    c.gN = u.gN; c.gR = u.gR; c.gnalive = u.gnalive; c.gkmin = u.gkmin;
     return dev(launch_ucb(*b, c, st));
+}
+
+// ---- selection step without a caller workspace ---------------------------------
+// The scratch of kb_ucb_select_static: a file-scope device array, one copy per GPU
+// the library runs on, held until the process ends.  Layout (all blocks 256-byte
+// aligned): order [G], tile_off [G + 1], then the tables of the chunked path gR
+// [Ksum * S] (8 bytes), gkmin [Ksum] (8), gN [Ksum * S] (4), gnalive [Ksum] (4).
+constexpr size_t kStaticOrder = 0;
+constexpr size_t kStaticTileOff = kStaticOrder + 4 * (size_t)KB_STATIC_MAX_G;
+constexpr size_t kStaticR = kStaticTileOff + 4 * ((size_t)KB_STATIC_MAX_G + 64);
+constexpr size_t kStaticKmin = kStaticR + 8 * (size_t)KB_STATIC_MAX_KS;
+constexpr size_t kStaticN = kStaticKmin + 8 * (size_t)KB_STATIC_MAX_KSUM;
+constexpr size_t kStaticNalive = kStaticN + 4 * (size_t)KB_STATIC_MAX_KS;
+constexpr size_t kStaticBytes = kStaticNalive + 4 * (size_t)KB_STATIC_MAX_KSUM;
+static_assert(kStaticTileOff % 256 == 0 && kStaticR % 256 == 0 && kStaticKmin % 256 == 0 &&
+              kStaticN % 256 == 0 && kStaticNalive % 256 == 0, "blocks stay 256-byte aligned");
+
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+// Device address of `scratch` on the current device.  In host code the array's
+// name is only a handle for the runtime, not an address a kernel can use, so the
+// address is looked up once per device (every GPU has its own copy at its own
+// address) and kept.
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static unsigned char* g_scratch_ptr[kMaxDevices];     // zero-initialised: not looked up yet
+
+static kb_status static_scratch(unsigned char** out) {
+    int devno = -1;
+    if (hipGetDevice(&devno) != hipSuccess || devno < 0 || devno >= kMaxDevices) return KB_EDEVICE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[devno]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return KB_EDEVICE;
+        g_scratch_ptr[devno] = (unsigned char*)p;
+    }
+    *out = g_scratch_ptr[devno];
+    return KB_OK;
 }
 
 }  // namespace kb
@@ -233,8 +290,8 @@ kb_status kb_ucb_select(const kb_batch* batch, const kb_params* params, const in
     if (s != KB_OK) return s;
     s = check_ws(batch, ws, ws_bytes);
     if (s != KB_OK) return s;
-    return do_ucb(batch, params, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel, ws,
-                  false, (hipStream_t)stream);
+    return do_ucb(batch, params, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel,
+                  ucb_scratch_in_ws(batch, ws), false, (hipStream_t)stream);
 }
 
 kb_status kb_ucb_select_masked(const kb_batch* batch, const kb_params* params,
@@ -246,8 +303,39 @@ kb_status kb_ucb_select_masked(const kb_batch* batch, const kb_params* params,
     if (s != KB_OK) return s;
     s = check_ws(batch, ws, ws_bytes);
     if (s != KB_OK) return s;
-    return do_ucb(batch, params, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel, ws,
-                  false, (hipStream_t)stream, M, true);
+    return do_ucb(batch, params, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel,
+                  ucb_scratch_in_ws(batch, ws), false, (hipStream_t)stream, M, true);
+}
+
+kb_status kb_ucb_select_static(const kb_batch* batch, const kb_params* params,
+                               const int32_t* assign, const uint8_t* alive, const float* bound,
+                               const int32_t* visits, const float* rsum, const int64_t* t,
+                               int32_t* Ncs, float* mu, float* ucb, int32_t* sel, void* stream) {
+    kb_status s = check_batch(batch);
+    if (s != KB_OK) return s;
+    // sizes beyond the static scratch
+    const bool chunked = batch->Nmax > 16384;
+    if (batch->G > KB_STATIC_MAX_G) return KB_EUNSUPPORTED;
+    if (chunked && (batch->Ksum > KB_STATIC_MAX_KSUM ||
+                    (int64_t)batch->Ksum * batch->S > KB_STATIC_MAX_KS))
+        return KB_EUNSUPPORTED;
+    s = check_ucb(batch, params, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel);
+    if (s != KB_OK) return s;
+    unsigned char* base = nullptr;
+    s = static_scratch(&base);
+    if (s != KB_OK) return s;
+    UcbScratch u;
+    u.order = (int32_t*)(base + kStaticOrder);
+    u.tile_off = (int32_t*)(base + kStaticTileOff);
+    u.gN = nullptr; u.gR = nullptr; u.gnalive = nullptr; u.gkmin = nullptr;
+    if (chunked) {
+        u.gR = (unsigned long long*)(base + kStaticR);
+        u.gkmin = (unsigned long long*)(base + kStaticKmin);
+        u.gN = (unsigned*)(base + kStaticN);
+        u.gnalive = (unsigned*)(base + kStaticNalive);
+    }
+    return do_ucb(batch, params, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel, u, false,
+                  (hipStream_t)stream);
 }
 
 kb_status kb_cluster_geometry(const kb_batch* batch, const float* X, const float* cent,
@@ -416,7 +504,7 @@ kb_status kb_round(const kb_batch* batch, const kb_params* params, const kb_roun
                    io->counts, io->objective, ws, st);
     if (s != KB_OK) return s;
     return do_ucb(batch, params, io->assign, io->alive, io->bound, io->visits, io->rsum, io->t,
-                  io->Ncs, io->mu, io->ucb, io->sel, ws, true, st);
+                  io->Ncs, io->mu, io->ucb, io->sel, ucb_scratch_in_ws(batch, ws), true, st);
 }
 
 const char* kb_status_str(kb_status status) {

@@ -126,6 +126,21 @@ def test_ucb_and_round_argument_errors(L):
     assert kb.kb_round(b, p, io, FAKE, 16, stream=0, check=False) == kb.KB_EWORKSPACE
 
 
+def test_static_selection_rejects_sizes_beyond_its_scratch(L):
+    p = kb.make_params(iters=2)
+    args = [FAKE] * 10
+    assert kb.kb_ucb_select_static(_batch(G=65537, N=1 << 20, Ksum=65537 * 2), p, *args, stream=0,
+                                   check=False) == kb.KB_EUNSUPPORTED
+    # searches longer than 16384 candidates also need their cluster-arm tables to fit
+    assert kb.kb_ucb_select_static(_batch(N=1 << 22, Nmax=20000, Kmax=64, Ksum=70000), p, *args,
+                                   stream=0, check=False) == kb.KB_EUNSUPPORTED
+    assert kb.kb_ucb_select_static(_batch(N=1 << 22, Nmax=20000, Kmax=64, Ksum=40000, S=4), p, *args,
+                                   stream=0, check=False) == kb.KB_EUNSUPPORTED
+    bad = list(args)
+    bad[0] = None
+    assert kb.kb_ucb_select_static(_batch(), p, *bad, stream=0, check=False) == kb.KB_EINVAL
+
+
 def test_sample_argument_errors(L):
     b = _batch()
     big = 1 << 20
