@@ -168,6 +168,16 @@ def main():
         loop["cluster_diameter"] = timed(d.cluster_diameter, 3)[0]
         loop["seed_farthest"] = timed(d.seed_farthest, 3)[0]
         loop["seed_dsquared"] = timed(lambda: d.seed_dsquared(20251118, 0), 3)[0]
+        # ten whole iterations of Alg. 1 in one call (re-clustering in the first, warm start)
+        T = 10
+        fb = [synth.feedback(b, seed=r) for r in range(T)]
+        drw10 = up(np.stack([f[0] for f in fb]))
+        dok10 = up(np.stack([f[1] for f in fb]))
+        sl = torch.zeros((T, b.G, 3), dtype=torch.int32, device=d.device)
+        kl = torch.zeros((T, b.G), dtype=torch.int32, device=d.device)
+        ipar = kb.kb_iterate_params(T, 10, 0, 1, R, theta, sp)
+        loop["iterate_10_rounds"] = timed(lambda: d.iterate(ipar, dh, dtg, drw10, dok10, sl, kl), 3)[0]
+        del drw10, dok10, sl, kl
         loop = {k: round(v, 4) for k, v in loop.items()}
         nk_rows = float(np.sum(np.diff(b.seg_off).astype(np.float64) * np.diff(b.koff)))
         # four fp64-rate vector instructions (widen, subtract, multiply, add) per feature,

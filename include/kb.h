@@ -26,6 +26,9 @@
  *                    cluster representatives, the mask in the paper's own form,
  *                    selection under that mask, the draw with the paper's
  *                    potential, and the statistics update.
+ *   kb_iterate       several whole iterations of Alg. 1 (re-clustering every tau
+ *                    iterations where |P| >= 2K, mask, selection, draw, update)
+ *                    in one call, rewards supplied up front.
  *   kb_sample        the draw of k_t inside the chosen cluster with probability
  *                    proportional to exp(headroom) (Sec. 3.4), reproducible from
  *                    (seed, draw).
@@ -371,6 +374,65 @@ kb_status kb_update_stats(const kb_batch *batch, const kb_params *params,
                           const float *reward, const uint8_t *ok,
                           int32_t *visits, float *rsum, int32_t *Ncs, float *mu,
                           int64_t *t, void *stream);
+
+/* Several iterations of Alg. 1 in one call, enqueued on the stream without any
+ * host round trip: what is left of an iteration once generation, verification
+ * and timing of the new kernel are taken out - their results, the reward r and
+ * the verified flag of every round, are supplied up front.  Round r = 0 ..
+ * rounds-1, iteration number it = t0 + r:
+ *   if tau_recluster > 0 and it % tau_recluster == 0   ("if t mod tau = 0")
+ *       kb_cluster (params->iters steps, params->scorer) on every search with
+ *       N_g >= 2 K_g ("and |P| >= 2K"; the others keep their clustering), from
+ *       the first K_g rows or - warm_start != 0 - from the current centroids;
+ *       kb_cluster_geometry -> rep, radius; kb_strategy_mask -> M, nvalid
+ *   kb_ucb_select_masked (alive as given, bound = NULL) -> Ncs, mu, ucb, sel_log[r]
+ *       (the cluster-arm statistics are re-aggregated from visits / rsum, so they
+ *       follow a re-clustering)
+ *   kb_sample_signature, draw number sample.draw + r       -> ksel_log[r]
+ *   kb_update_stats with reward[r], ok[r]                  -> visits, rsum, Ncs, mu, t
+ * The frontier is fixed during the call (new kernels are appended by the caller
+ * between calls).  assign, cent, counts, objective, rep, radius, M and nvalid are
+ * in-out: they must hold a valid state on entry wherever the first round does not
+ * rebuild them (no re-clustering in round 0, or searches with N_g < 2 K_g).
+ * Validation and errors as in the calls it is made of; rounds >= 1, t0 >= 0. */
+typedef struct {
+    int32_t rounds;         /* T, number of iterations to run */
+    int32_t tau_recluster;  /* re-cluster every this many iterations (the paper: 10); <= 0: never */
+    int64_t t0;             /* iteration number of the first round (host copy) */
+    int32_t warm_start;     /* 0: Lloyd from the first K_g rows; else from the current centroids */
+    int32_t R;              /* resources in the hardware signature h */
+    float theta_sat;        /* saturation threshold of Eq. 5 (the paper: 0.75 of peak) */
+    kb_sample_params sample; /* seed, draw number of the first round, temperature */
+} kb_iterate_params;
+
+typedef struct {
+    const float *X;         /* [N, D] */
+    const float *h;         /* [N, R] hardware signature of every candidate */
+    const int32_t *target;  /* [S] resource each strategy works on, in [0, R) */
+    const uint8_t *alive;   /* [N] or NULL (every candidate alive) */
+    const float *reward;    /* [rounds, G] reward of round r in search g, in [0, 1] */
+    const uint8_t *ok;      /* [rounds, G] 1 = the kernel generated in round r verified */
+    int32_t *visits;        /* [N, S] in-out */
+    float *rsum;            /* [N, S] in-out */
+    int64_t *t;             /* [G]    in-out */
+    int32_t *assign;        /* [N]    in-out */
+    float *cent;            /* [Ksum, D] in-out */
+    int32_t *counts;        /* [Ksum] in-out */
+    float *objective;       /* [G]    in-out */
+    int32_t *rep;           /* [Ksum] in-out */
+    float *radius;          /* [Ksum] in-out */
+    uint8_t *M;             /* [Ksum, S] in-out */
+    int32_t *nvalid;        /* [G]    in-out */
+    int32_t *Ncs;           /* [Ksum, S] out: tables after the last round's update */
+    float *mu;              /* [Ksum, S] out */
+    float *ucb;             /* [Ksum, S] out: scores of the last round */
+    int32_t *sel_log;       /* [rounds, G, 3] out: (I_t, S_t, lowest-index alive member of I_t) */
+    int32_t *ksel_log;      /* [rounds, G] out: the sampled k_t */
+} kb_iterate_io;
+
+kb_status kb_iterate(const kb_batch *batch, const kb_params *params,
+                     const kb_iterate_params *ip, const kb_iterate_io *io,
+                     void *ws, size_t ws_bytes, void *stream);
 
 /* Static, never NULL. */
 const char *kb_status_str(kb_status status);

@@ -385,3 +385,65 @@ def round_(b, iters=None):
                   _p(out.Ncs), _p(out.mu), _p(out.ucb), _p(out.sel), _p(out.dirty),
                   _p(out.near))
     return out
+
+
+def iterate(seg_off, koff, S, X, h, target, theta_sat, alive, reward, ok, visits, rsum, t,
+            assign_, cent, counts, objective, rep, M, rounds, tau_recluster, t0, warm_start,
+            iters, c, prior_n, prior_mu, seed, draw0, temperature=1.0):
+    """Several iterations of Alg. 1 composed from the functions above, in the
+    order the algorithm states them.  Round r, iteration number it = t0 + r:
+      if tau_recluster > 0 and it % tau_recluster == 0: K-Means (`iters` Lloyd steps,
+        from the first K_g rows or, warm_start, from the current centroids) on
+        every search with N_g >= 2 K_g - the others keep their clustering - then the
+        representatives k_c and the mask of Eq. 5 from their signatures;
+      cluster-arm statistics re-aggregated from the per-candidate history, masked
+        UCB argmax (Eq. 6); draw of k_t with theta_sat - h; statistics update.
+    Returns the per-round logs (sel, ksel and the union of the near-tie flags that
+    make a search's later rounds incomparable) and the final state."""
+    seg_off = _c(seg_off, np.int32)
+    koff = _c(koff, np.int32)
+    G = len(seg_off) - 1
+    visits = np.array(visits, dtype=np.int32, copy=True)
+    rsum = np.array(rsum, dtype=np.float32, copy=True)
+    t = np.array(t, dtype=np.int64, copy=True)
+    assign_ = np.array(assign_, dtype=np.int32, copy=True)
+    cent = np.array(cent, dtype=np.float32, copy=True)
+    counts = np.array(counts, dtype=np.int32, copy=True)
+    objective = np.array(objective, dtype=np.float64, copy=True)
+    rep = np.array(rep, dtype=np.int32, copy=True)
+    M = np.array(M, dtype=np.uint8, copy=True)
+    ng = np.diff(seg_off)
+    kg = np.diff(koff)
+    sel_log = np.zeros((rounds, G, 3), np.int32)
+    ksel_log = np.zeros((rounds, G), np.int32)
+    doubt = np.zeros((rounds, G), np.uint8)     # a near-tie seen in this round (any stage)
+    Ncs = mu = ucb = None
+    for r in range(rounds):
+        it = t0 + r
+        if tau_recluster > 0 and it % tau_recluster == 0:
+            cl = cluster(seg_off, koff, X, iters, cent_init=cent if warm_start else None)
+            go = (ng >= 2 * kg) & (ng > 0)
+            gp = np.repeat(go, ng)
+            gk = np.repeat(go, kg)
+            assign_[gp] = cl.assign[gp]
+            cent[gk] = cl.cent[gk]
+            counts[gk] = cl.counts[gk]
+            objective[go] = cl.objective[go]
+            doubt[r] |= (cl.dirty != 0) & go
+            geo = cluster_geometry(seg_off, koff, X, cent, assign_)
+            rep = geo.rep
+            M = strategy_mask(koff, S, h, target, rep, theta_sat).M
+        u = ucb_select(seg_off, koff, S, assign_, alive, None, visits, rsum, t, c, prior_n,
+                       prior_mu, M=M)
+        s = sample_signature(seg_off, assign_, alive, h, target, theta_sat, u.sel, seed, draw0 + r,
+                             temperature)
+        doubt[r] |= (u.near != 0) | (s.near != 0)
+        sel_log[r] = u.sel
+        ksel_log[r] = s.ksel
+        up = update_stats(koff, S, u.sel, s.ksel, reward[r], ok[r], prior_n, visits, rsum,
+                          u.Ncs.astype(np.int32), u.mu.astype(np.float32), t)
+        visits, rsum, t = up.visits, up.rsum, up.t
+        Ncs, mu, ucb = up.Ncs, up.mu, u.ucb
+    return SimpleNamespace(sel_log=sel_log, ksel_log=ksel_log, doubt=doubt, visits=visits,
+                           rsum=rsum, t=t, assign=assign_, cent=cent, counts=counts,
+                           objective=objective, rep=rep, M=M, Ncs=Ncs, mu=mu, ucb=ucb)

@@ -45,6 +45,19 @@ class kb_sample_params(ctypes.Structure):
     _fields_ = [("seed", ctypes.c_uint64), ("draw", ctypes.c_uint64), ("tau", ctypes.c_float)]
 
 
+class kb_iterate_params(ctypes.Structure):
+    _fields_ = [("rounds", ctypes.c_int32), ("tau_recluster", ctypes.c_int32),
+                ("t0", ctypes.c_int64), ("warm_start", ctypes.c_int32), ("R", ctypes.c_int32),
+                ("theta_sat", ctypes.c_float), ("sample", kb_sample_params)]
+
+
+class kb_iterate_io(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in (
+        "X", "h", "target", "alive", "reward", "ok", "visits", "rsum", "t", "assign", "cent",
+        "counts", "objective", "rep", "radius", "M", "nvalid", "Ncs", "mu", "ucb", "sel_log",
+        "ksel_log")]
+
+
 _lib = None
 
 
@@ -71,6 +84,9 @@ def lib() -> ctypes.CDLL:
         L.kb_ucb_select.argtypes = [pb, pp] + [vp] * 10 + [vp, sz, vp]
         L.kb_ucb_select_static.restype = ctypes.c_int
         L.kb_ucb_select_static.argtypes = [pb, pp] + [vp] * 10 + [vp]
+        L.kb_iterate.restype = ctypes.c_int
+        L.kb_iterate.argtypes = [pb, pp, ctypes.POINTER(kb_iterate_params),
+                                 ctypes.POINTER(kb_iterate_io), vp, sz, vp]
         L.kb_round.restype = ctypes.c_int
         L.kb_round.argtypes = [pb, pp, ctypes.POINTER(kb_round_io), vp, sz, vp]
         L.kb_sample.restype = ctypes.c_int
@@ -183,6 +199,13 @@ def kb_round(batch, params, io: kb_round_io, ws, ws_bytes, stream=None, check=Tr
     s = lib().kb_round(ctypes.byref(batch), ctypes.byref(params), ctypes.byref(io), _ptr(ws),
                        ws_bytes, _stream(stream))
     return _check(s, "kb_round", check)
+
+
+def kb_iterate(batch, params, ip: kb_iterate_params, io: kb_iterate_io, ws, ws_bytes, stream=None,
+               check=True):
+    s = lib().kb_iterate(ctypes.byref(batch), ctypes.byref(params), ctypes.byref(ip),
+                         ctypes.byref(io), _ptr(ws), ws_bytes, _stream(stream))
+    return _check(s, "kb_iterate", check)
 
 
 def kb_sample(batch, sp: kb_sample_params, assign, alive, bound, incumbent, sel, ksel, ws,
@@ -357,6 +380,16 @@ class DeviceBatch:
 
     def round(self, **kw):
         return kb_round(self.batch, self.params, self.io, self.ws, self.ws_bytes, **kw)
+
+    def iterate(self, ip: kb_iterate_params, h, target, reward, ok, sel_log, ksel_log, alive=None,
+                **kw):
+        """kb_iterate on the buffers held here (h, target, reward, ok, the logs: device
+        tensors of the caller)."""
+        io = kb_iterate_io(*[_ptr(x) for x in (
+            self.X, h, target, alive, reward, ok, self.visits, self.rsum, self.t, self.assign,
+            self.cent, self.counts, self.objective, self.rep, self.radius, self.M, self.nvalid,
+            self.Ncs, self.mu, self.ucb, sel_log, ksel_log)])
+        return kb_iterate(self.batch, self.params, ip, io, self.ws, self.ws_bytes, **kw)
 
     def host(self, name):
         return getattr(self, name).cpu().numpy()

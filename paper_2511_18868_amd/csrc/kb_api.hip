@@ -120,9 +120,13 @@ static kb_status check_cluster(const kb_batch* b, const float* X, const float* c
 
 static kb_status do_cluster(const kb_batch* b, const float* X, const float* cent_init,
                             int32_t iters, int scorer, int32_t* assign, float* cent,
-                            int32_t* counts, float* objective, void* ws, hipStream_t st) {
+                            int32_t* counts, float* objective, void* ws, hipStream_t st,
+                            bool reclustering = false) {
     if (scorer < KB_SCORER_DEFAULT || scorer > KB_SCORER_MATRIX_EVERY) return KB_EINVAL;
-    kb_status s = check_cluster(b, X, cent_init, iters, assign, cent, counts, objective);
+    // (a re-clustering may continue from the centroids it overwrites: every kernel
+    // reads a search's initial centroids before it writes that search's new ones)
+    kb_status s = check_cluster(b, X, reclustering ? nullptr : cent_init, iters, assign, cent,
+                                counts, objective);
     if (s != KB_OK) return s;
     WsLayout w = ws_layout(*b);
     char* base = (char*)ws;
@@ -138,6 +142,7 @@ static kb_status do_cluster(const kb_batch* b, const float* X, const float* cent
     c.lim = (float*)(base + w.geo_d2);      // (the representative pass uses this array at other times)
     c.split = (void*)(base + w.split); c.max_tiles = (int64_t)w.max_tiles;
     c.scorer = scorer;
+    c.guard = reclustering ? 1 : 0;
     if (w.use_big) return dev(launch_cluster_big(*b, c, w.big, base, st));
     return dev(launch_cluster(*b, c, st));
 }
@@ -505,6 +510,87 @@ kb_status kb_round(const kb_batch* batch, const kb_params* params, const kb_roun
     if (s != KB_OK) return s;
     return do_ucb(batch, params, io->assign, io->alive, io->bound, io->visits, io->rsum, io->t,
                   io->Ncs, io->mu, io->ucb, io->sel, ucb_scratch_in_ws(batch, ws), true, st);
+}
+
+kb_status kb_iterate(const kb_batch* batch, const kb_params* params, const kb_iterate_params* ip,
+                     const kb_iterate_io* io, void* ws, size_t ws_bytes, void* stream) {
+    kb_status s = check_batch(batch);
+    if (s != KB_OK) return s;
+    if (!params || !ip || !io) return KB_EINVAL;
+    if (ip->rounds < 1 || ip->t0 < 0 || ip->R <= 0) return KB_EINVAL;
+    if (!(ip->theta_sat == ip->theta_sat)) return KB_EINVAL;
+    if (!(ip->sample.tau > 0.0f) || !(ip->sample.tau < INFINITY)) return KB_EINVAL;
+    if (!io->X || !io->h || !io->target || !io->reward || !io->ok || !io->visits || !io->rsum ||
+        !io->t || !io->assign || !io->cent || !io->counts || !io->objective || !io->rep ||
+        !io->radius || !io->M || !io->nvalid || !io->Ncs || !io->mu || !io->ucb || !io->sel_log ||
+        !io->ksel_log)
+        return KB_EINVAL;
+    if (!aligned(io->X, 16) || !aligned(io->cent, 16)) return KB_EINVAL;
+    const bool recluster = ip->tau_recluster > 0;
+    if (recluster && params->iters < 1) return KB_EINVAL;
+    if (params->scorer < KB_SCORER_DEFAULT || params->scorer > KB_SCORER_MATRIX_EVERY) return KB_EINVAL;
+    s = check_ws(batch, ws, ws_bytes);
+    if (s != KB_OK) return s;
+    // validate every stage before enqueueing anything
+    s = check_ucb(batch, params, io->assign, io->alive, nullptr, io->visits, io->rsum, io->t, io->Ncs,
+                  io->mu, io->ucb, io->sel_log, true);
+    if (s != KB_OK) return s;
+    if (recluster) {
+        s = check_cluster(batch, io->X, nullptr, params->iters, io->assign, io->cent, io->counts,
+                          io->objective);
+        if (s != KB_OK) return s;
+        if (geometry_lds_bytes(batch->Kmax > 0 ? batch->Kmax : 1, batch->D) > 160 * 1024)
+            return KB_EUNSUPPORTED;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    const WsLayout w = ws_layout(*batch);
+    char* base = (char*)ws;
+    const size_t G = (size_t)batch->G;
+    bool have_order = false;        // the scheduling order in ws, computed by the first stage that needs it
+    for (int32_t r = 0; r < ip->rounds; ++r) {
+        const bool now = recluster && ((ip->t0 + r) % ip->tau_recluster) == 0;
+        if (now) {
+            // K-Means on the frontier wherever |P| >= 2K, then the cluster representatives
+            // and the mask their hardware signatures give (Alg. 1; Eq. 5)
+            s = do_cluster(batch, io->X, ip->warm_start ? io->cent : nullptr, params->iters,
+                           params->scorer, io->assign, io->cent, io->counts, io->objective, ws, st,
+                           true);
+            if (s != KB_OK) return s;
+            have_order = true;
+            GeoCall gc;
+            gc.X = io->X; gc.cent = io->cent; gc.assign = io->assign; gc.rep = io->rep;
+            gc.radius = io->radius; gc.d2 = (double*)(base + w.geo_d2);
+            gc.gmin = (unsigned long long*)(base + w.geo_min);
+            gc.gmax = (unsigned long long*)(base + w.geo_max);
+            if (launch_geometry(*batch, gc, st) != hipSuccess) return KB_EDEVICE;
+            if (launch_strategy_mask(*batch, ip->R, io->h, io->target, io->rep, ip->theta_sat, io->M,
+                                     io->nvalid, st) != hipSuccess)
+                return KB_EDEVICE;
+        }
+        int32_t* sel = io->sel_log + (size_t)r * G * 3;
+        int32_t* ksel = io->ksel_log + (size_t)r * G;
+        // the cluster-arm tables are rebuilt from the per-candidate history, so they
+        // follow every re-clustering; masked UCB argmax (Eq. 6)
+        s = do_ucb(batch, params, io->assign, io->alive, nullptr, io->visits, io->rsum, io->t,
+                   io->Ncs, io->mu, io->ucb, sel, ucb_scratch_in_ws(batch, ws), have_order, st, io->M,
+                   true);
+        if (s != KB_OK) return s;
+        have_order = true;
+        // draw of k_t with the potential theta_sat - h (Sec. 3.4)
+        SampleCall sc;
+        sc.assign = io->assign; sc.alive = io->alive; sc.bound = nullptr; sc.incumbent = nullptr;
+        sc.sel = sel; sc.h = io->h; sc.target = io->target; sc.R = ip->R; sc.theta_sat = ip->theta_sat;
+        sc.seed = ip->sample.seed; sc.draw = ip->sample.draw + (uint64_t)r; sc.tau = ip->sample.tau;
+        sc.ksel = ksel;
+        sc.slot_key = (double*)(base + w.samp_key); sc.slot_idx = (int32_t*)(base + w.samp_idx);
+        if (launch_sample(*batch, sc, st) != hipSuccess) return KB_EDEVICE;
+        // reward of the generated kernel -> statistics (Alg. 1, last lines)
+        if (launch_update_stats(*batch, params->prior_n, sel, ksel, io->reward + (size_t)r * G,
+                                io->ok + (size_t)r * G, io->visits, io->rsum, io->Ncs, io->mu, io->t,
+                                st) != hipSuccess)
+            return KB_EDEVICE;
+    }
+    return KB_OK;
 }
 
 const char* kb_status_str(kb_status status) {

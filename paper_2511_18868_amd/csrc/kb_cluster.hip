@@ -61,6 +61,7 @@ struct ClusterArgs {
     bf16x8* split;
     int64_t max_tiles;
     int use_bounds;
+    int guard;         // leave searches with N_g < 2 K_g as they are (re-clustering rule of Alg. 1)
     float* lim;        // [N] limit of every candidate: drift at its last scoring + its slack
 };
 
@@ -1119,6 +1120,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
         if (tid == 0 && a.iters > 0 && a.objective) a.objective[g] = 0.f;
         return;
     }
+    if (a.guard && ng < 2 * K) return;      // too few candidates to re-cluster: nothing is touched
 
     const Lds L = lds_layout(a.Kmax, D, DP, a.Nmax);
     double* red = reinterpret_cast<double*>(smem);
@@ -1406,6 +1408,7 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     a.tile_off = c.tile_off; a.xn = c.xn; a.split = reinterpret_cast<bf16x8*>(c.split);
     a.max_tiles = c.max_tiles;
     a.use_bounds = c.scorer != 2;
+    a.guard = c.guard;
     a.lim = c.lim;
 
     const int ds = (b.D + 15) / 16;   // 1..4 K-steps of 16 features

@@ -36,6 +36,7 @@ constexpr int kWaves = kThreads / kWave;
 
 struct BigArgs {
     int G, D, Ksum, Kmax, Kpad, it, final_pass;
+    int guard;              // 1: searches with N_g < 2 K_g are left as they are
     int64_t N, max_tiles;
     const int32_t* seg_off;
     const int32_t* koff;
@@ -87,20 +88,31 @@ __global__ void __launch_bounds__(kThreads) big_init(BigArgs a) {
     for (int64_t idx = t0; idx < (int64_t)a.Ksum * D; idx += stride) {
         const int r = (int)(idx / D), d = (int)(idx - (int64_t)r * D);
         float v;
-        if (a.cent_init) {
+        a.sums[idx] = 0;
+        if (a.cent_init && !a.guard) {
             v = a.cent_init[idx];
         } else {
             const int g = upper_search(a.koff, a.G, r);
             int n0, ng, k0, K;
             search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+            if (a.guard && ng < 2 * K) continue;
             const int j = r - k0;
-            v = ng > 0 ? a.X[(size_t)(n0 + (j < ng ? j : ng - 1)) * D + d] : 0.f;
+            v = a.cent_init ? a.cent_init[idx]
+                            : (ng > 0 ? a.X[(size_t)(n0 + (j < ng ? j : ng - 1)) * D + d] : 0.f);
         }
         a.cent[idx] = v;
-        a.sums[idx] = 0;
     }
     if (a.it < 0) return;   // iters == 0: only the initial centroids
-    for (int64_t r = t0; r < a.Ksum; r += stride) { a.counts[r] = 0; a.dirty[r] = 0; }
+    for (int64_t r = t0; r < a.Ksum; r += stride) {
+        a.dirty[r] = 0;
+        if (a.guard) {
+            const int g = upper_search(a.koff, a.G, r);
+            int n0, ng, k0, K;
+            search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+            if (ng < 2 * K) continue;
+        }
+        a.counts[r] = 0;
+    }
     for (int64_t g = t0; g < a.G; g += stride) {
         a.amax_bits[g] = 0u;
         a.cnmax_bits[g] = 0u;
@@ -174,6 +186,8 @@ __global__ void __launch_bounds__(kThreads) big_renew(BigArgs a) {
     int n0, ng, k0, K;
     search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
     if (K > a.Kpad) K = a.Kpad;
+    if (r == 0 && lane == 0) { a.nflag[0] = 0; a.nflag[1] = 0; }
+    if (a.guard && ng < 2 * K) return;
     const int D = a.D;
     const int mt = j >> 5, lane_row = j & 31;
     __bf16* ap = reinterpret_cast<__bf16*>(a.aop + (size_t)g * (a.Kpad / 32) * (DS * 2 * 64));
@@ -221,7 +235,6 @@ __global__ void __launch_bounds__(kThreads) big_renew(BigArgs a) {
         a.dirty[row] = 0;
         atomicMax(&a.cnmax_bits[(a.it & 1) * a.G + g], __float_as_uint(f));
         if (j == 0) a.cnmax_bits[((a.it + 1) & 1) * a.G + g] = 0u;
-        if (r == 0) { a.nflag[0] = 0; a.nflag[1] = 0; }
     }
 }
 
@@ -258,6 +271,7 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
     search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
     if (K > a.Kpad) K = a.Kpad;
     if (ng <= 0 || K <= 0) return;
+    if (a.guard && ng < 2 * K) return;
     const int ntiles = (ng + 31) >> 5;
     const int t0 = (c - a.chunk_off[g]) * kTilesPerChunk;
     const int t1 = t0 + kTilesPerChunk < ntiles ? t0 + kTilesPerChunk : ntiles;
@@ -552,6 +566,7 @@ __global__ void __launch_bounds__(kThreads, 2) big_score_valu(BigArgs a) {
     search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
     if (K > a.Kpad) K = a.Kpad;
     if (ng <= 0 || K <= 0) return;
+    if (a.guard && ng < 2 * K) return;
     const int p0 = (c - a.chunk_off[g]) * kTilesPerChunk * 32;
     const int p1 = p0 + kTilesPerChunk * 32 < ng ? p0 + kTilesPerChunk * 32 : ng;
     if (p0 >= p1) return;
@@ -812,6 +827,7 @@ __global__ void __launch_bounds__(kThreads) big_update(BigArgs a) {
         search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
         if (n0 >= r1) break;
         if (jg0 >= K || ng <= 0) continue;
+        if (a.guard && ng < 2 * K) continue;
         const int64_t q0 = r0 > n0 ? r0 : n0;
         const int64_t q1 = r1 < (int64_t)n0 + ng ? r1 : (int64_t)n0 + ng;
         if (q0 >= q1) continue;
@@ -965,6 +981,11 @@ __global__ void __launch_bounds__(kThreads) big_objsum(BigArgs a) {
     __shared__ double red[kWaves];
     const int g = blockIdx.x, tid = threadIdx.x;
     if (g >= a.G) return;
+    if (a.guard) {
+        int n0, ng, k0, K;
+        search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+        if (ng > 0 && ng < 2 * K) return;        // (uniform over the workgroup) objective left as it is
+    }
     double J = 0.0;
     for (int c = a.chunk_off[g] + tid; c < a.chunk_off[g + 1]; c += kThreads) J += a.partJ[c];
     J = wave_sum_d(J);
@@ -1008,7 +1029,7 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
                               hipStream_t st) {
     BigArgs a;
     a.G = b.G; a.D = b.D; a.Ksum = b.Ksum; a.Kmax = b.Kmax > 0 ? b.Kmax : 1; a.Kpad = w.kpad;
-    a.it = 0; a.final_pass = 0; a.N = b.N; a.max_tiles = c.max_tiles;
+    a.it = 0; a.final_pass = 0; a.guard = c.guard; a.N = b.N; a.max_tiles = c.max_tiles;
     a.seg_off = b.seg_off; a.koff = b.koff; a.X = c.X; a.cent_init = c.cent_init;
     a.assign = c.assign; a.cent = c.cent_out; a.counts = c.counts; a.objective = c.objective;
     a.tile_off = c.tile_off; a.chunk_off = reinterpret_cast<const int32_t*>(ws + w.chunk_off);

@@ -76,6 +76,7 @@ struct ClusterCall {
     void* split;
     int64_t max_tiles;
     float* lim;               // float [N] scratch of the fused kernel (every candidate's drift limit)
+    int guard;                // 1: searches with N_g < 2 K_g keep their clustering untouched
     int scorer;               // kb_params::scorer: 0 default, 1 vector ALU only, 2 matrix cores without bounds
 };
 hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t st);
