@@ -717,6 +717,9 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
     const float kappa = mfma_kappa(DS);
     const bool vec = (D & 3) == 0;
     const int ntiles = (ng + 31) >> 5;
+    // the split copy, |x|^2 and the limits serve the steps that follow: a call of one
+    // step (kb_cluster_step) stores none of them
+    const bool later = a.iters > 1;
 
     // this lane's 8 features of every 16-feature step of row `tile * 32 + m`
     auto load_rows = [&](int tile, float4 (&r)[DS][2]) {
@@ -770,8 +773,10 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
             xv[s][0] = cur[s][0].x; xv[s][1] = cur[s][0].y; xv[s][2] = cur[s][0].z; xv[s][3] = cur[s][0].w;
             xv[s][4] = cur[s][1].x; xv[s][5] = cur[s][1].y; xv[s][6] = cur[s][1].z; xv[s][7] = cur[s][1].w;
             split8(xv[s], Bh[s], Bm[s]);
-            tp[(2 * s) * 64] = Bh[s];
-            tp[(2 * s + 1) * 64] = Bm[s];
+            if (later) {
+                tp[(2 * s) * 64] = Bh[s];
+                tp[(2 * s + 1) * 64] = Bm[s];
+            }
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 xn = fmaf(xv[s][i], xv[s][i], xn);
@@ -780,7 +785,7 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
             }
         }
         xn += __shfl_xor(xn, 32);
-        if (valid && h == 0) a.xn[(size_t)n0 + p] = xn;
+        if (later && valid && h == 0) a.xn[(size_t)n0 + p] = xn;
 
         float best, second;
         int bi;
@@ -828,7 +833,7 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
             }
         }
         if (__any(valid && !certain)) any |= 2;
-        if (a.use_bounds) {
+        if (a.use_bounds && later) {
             const float own = (valid && certain) ? slack_of(best, second, xn, E) : INFINITY;
             if (valid && certain && h == 0) lim[p] = tile_limit(0.f, own);
             const float sl = half_wave_min_f(own);

@@ -63,6 +63,8 @@ struct BigArgs {
     int32_t* flist;         // [N] global candidate indices
     int4* few;              // [N] (candidate, count, contenders 0..3, contenders 4..7 as bytes)
     double* partJ;          // [chunks]
+    double* tsq_part;       // [tiles] sum of x^2 over the rows of every tile (exact products, fp64 sums)
+    int* needfull;          // [G] 1: the objective of this search has to be summed member by member
 };
 
 // largest g with off[g] <= v (off non-decreasing, off[0] = 0, v < off[G])
@@ -139,6 +141,7 @@ __global__ void __launch_bounds__(kThreads) big_presplit(BigArgs a) {
     const float* xr = a.X + (size_t)(n0 + (valid ? p : 0)) * D;
     bf16x8* tp = a.split + (size_t)gt * (DS * 2 * 64) + lane;
     float xnp = 0.f, am = 0.f;
+    double sq = 0.0;
 #pragma unroll
     for (int s = 0; s < DS; ++s) {
         const int d0 = 16 * s + 8 * h;
@@ -161,10 +164,13 @@ __global__ void __launch_bounds__(kThreads) big_presplit(BigArgs a) {
         for (int i = 0; i < 8; ++i) {
             xnp = fmaf(x[i], x[i], xnp);
             am = fmaxf(am, fabsf(x[i]));
+            sq = fma((double)x[i], (double)x[i], sq);
         }
     }
     xnp += __shfl_xor(xnp, 32);
     if (valid && h == 0) a.xn[(size_t)n0 + p] = xnp;
+    sq = wave_sum_d(sq);                      // fixed order: the same bits in every run
+    if (lane == 0) a.tsq_part[gt] = sq;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) am = fmaxf(am, __shfl_xor(am, o));
     // non-negative floats order like their bit patterns; most waves find a value
@@ -915,6 +921,80 @@ __global__ void __launch_bounds__(kThreads) big_update(BigArgs a) {
     }
 }
 
+// Objective of the last step without a pass over the rows.  With S_j the exact
+// (fixed-point) sum and n_j the size of cluster j after the step's update, and c_j
+// the centroids that entered it,
+//   sum_k |x_k - c_a(k)|^2 = sum_k |x_k|^2 - sum_j c_j . (2 S_j - n_j c_j),
+// everything in fp64 and in a fixed order.  The subtraction cancels; when less than
+// 1e-7 of the first term is left (tight clusters far from the origin) the search is
+// marked and the two kernels below sum its members one by one instead.
+// One workgroup per search.
+constexpr int kObjThreads = 1024;
+__global__ void __launch_bounds__(kObjThreads) big_objfast(BigArgs a) {
+    constexpr int W = kObjThreads / kWave, U = 8;
+    __shared__ double red[2][W];
+    const int g = blockIdx.x, tid = threadIdx.x;
+    if (g >= a.G) return;
+    int n0, ng, k0, K;
+    search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+    if (tid == 0) a.needfull[g] = 0;
+    if (ng <= 0 || K <= 0) {
+        if (tid == 0) a.objective[g] = 0.f;
+        return;
+    }
+    if (a.guard && ng < 2 * K) return;
+    const int D = a.D;
+    const int ntiles = (ng + 31) >> 5;
+    const int64_t tb = a.tile_off[g];
+    if (tb + ntiles > a.max_tiles) return;
+    // (U independent loads per thread and round: a search is one workgroup, so the
+    // latency of its loads has to be covered inside it)
+    double tsq = 0.0;
+    for (int t0 = tid; t0 < ntiles; t0 += kObjThreads * U) {
+        double v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + u * kObjThreads;
+            v[u] = t < ntiles ? a.tsq_part[tb + t] : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) tsq += v[u];
+    }
+    const int sh = fixed_shift(__uint_as_float(a.amax_bits[g]), ng);
+    const double inv = ldexp(1.0, -sh);
+    double part = 0.0;
+    const int KD = K * D;
+    for (int i0 = tid; i0 < KD; i0 += kObjThreads * U) {
+        float cj[U];
+        long long Sj[U];
+        int nj[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = i0 + u * kObjThreads;
+            const bool in = i < KD;
+            cj[u] = in ? a.cent[(size_t)k0 * D + i] : 0.f;
+            Sj[u] = in ? a.sums[(size_t)k0 * D + i] : 0;
+            nj[u] = in ? a.counts[k0 + i / D] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const double c = (double)cj[u];
+            part += c * (2.0 * ((double)Sj[u] * inv) - (double)nj[u] * c);
+        }
+    }
+    tsq = wave_sum_d(tsq);
+    part = wave_sum_d(part);
+    if ((tid & 63) == 0) { red[0][tid >> 6] = tsq; red[1][tid >> 6] = part; }
+    __syncthreads();
+    if (tid == 0) {
+        double T = red[0][0], P = red[1][0];
+        for (int w = 1; w < W; ++w) { T += red[0][w]; P += red[1][w]; }
+        const double J = T - P;
+        if (J >= 1.0e-7 * T) a.objective[g] = (float)J;
+        else a.needfull[g] = 1;
+    }
+}
+
 // Per-chunk partial objective: 16 lanes per candidate (features l, l + 16, ...),
 // four candidates in flight per group, per-lane fp64 partial sums in a fixed
 // candidate order, fixed-order reduction.
@@ -924,6 +1004,7 @@ __global__ void __launch_bounds__(kThreads) big_objective(BigArgs a) {
     const int c = blockIdx.x;
     if (c >= a.chunk_off[a.G]) return;
     const int g = upper_search(a.chunk_off, a.G, c);
+    if (!a.needfull[g]) return;          // (uniform) the fast form was accurate enough
     int n0, ng, k0, K;
     search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
     const int D = a.D;
@@ -981,6 +1062,7 @@ __global__ void __launch_bounds__(kThreads) big_objsum(BigArgs a) {
     __shared__ double red[kWaves];
     const int g = blockIdx.x, tid = threadIdx.x;
     if (g >= a.G) return;
+    if (!a.needfull[g]) return;
     if (a.guard) {
         int n0, ng, k0, K;
         search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
@@ -1021,6 +1103,8 @@ BigWs big_ws_layout(const kb_batch& b, size_t base) {
     w.few = off;       off += al256(sizeof(int4) * (size_t)(b.N > 0 ? b.N : 1));
     w.partJ = off;     off += al256(sizeof(double) * w.max_chunks);
     w.prop = off;      off += al256(sizeof(int32_t) * (size_t)(b.N > 0 ? b.N : 1));
+    w.tsq = off;       off += al256(sizeof(double) * ((size_t)(b.N / 32) + (size_t)b.G));
+    w.needfull = off;  off += al256(sizeof(int) * (size_t)b.G);
     w.end = off;
     return w;
 }
@@ -1047,6 +1131,8 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
     int32_t* const other = reinterpret_cast<int32_t*>(ws + w.prop);
     a.prev = other; a.next = c.assign;
     a.partJ = reinterpret_cast<double*>(ws + w.partJ);
+    a.tsq_part = reinterpret_cast<double*>(ws + w.tsq);
+    a.needfull = reinterpret_cast<int*>(ws + w.needfull);
 
     const int ds = (b.D + 15) / 16;
     const size_t init_items = (size_t)(b.N > (int64_t)b.Ksum * b.D ? b.N : (int64_t)b.Ksum * b.D);
@@ -1095,6 +1181,7 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
             hipLaunchKernelGGL(big_exact, dim3(1024), dim3(kThreads), 0, st, a);                 \
             hipLaunchKernelGGL(big_update, upd_grid, dim3(kThreads), 0, st, a);                  \
         }                                                                                        \
+        hipLaunchKernelGGL(big_objfast, dim3((unsigned)b.G), dim3(kObjThreads), 0, st, a);       \
         hipLaunchKernelGGL(big_objective, dim3(chunk_blocks), dim3(kThreads), 0, st, a);         \
         hipLaunchKernelGGL(big_objsum, dim3((unsigned)b.G), dim3(kThreads), 0, st, a);           \
         a.final_pass = 1;                                                                        \

@@ -17,7 +17,7 @@ constexpr int kTilesPerChunk = 32;   // tiles of 32 candidates per workgroup of 
 struct BigWs {
     int kpad;            // Kmax rounded up to whole centroid tiles of 32
     size_t max_chunks;   // upper bound of the number of tile chunks (grid size)
-    size_t chunk_off, sums, cnpad, centT, aop, dirty, amax, cnmax, nflag, few, partJ, prop, end;
+    size_t chunk_off, sums, cnpad, centT, aop, dirty, amax, cnmax, nflag, few, partJ, prop, tsq, needfull, end;
 };
 BigWs big_ws_layout(const kb_batch& b, size_t base);
 // searches with more than 64 clusters or more than 65536 candidates take the

@@ -243,6 +243,39 @@ def test_cluster_edge_cases(kb, scorer):
     np.testing.assert_array_equal(got["counts"], ora.counts)
 
 
+@pytest.mark.parametrize("path", ["one_workgroup", "multi_workgroup"])
+def test_objective_of_tight_clusters_far_from_the_origin(kb, path):
+    """sum |x|^2 - sum_j c_j.(2 S_j - n_j c_j) cancels to nothing here (the clusters are
+    4000 times narrower than their distance from the origin): the objective has to
+    come from the member-by-member sum."""
+    if path == "one_workgroup":
+        b = synth.config5(G=6, nmin=300, nmax=900, seed=61)
+    else:
+        b = synth.config5(G=3, nmin=1500, nmax=3000, kcap=128, D=40, S=4, iters=6, seed=62)
+    b.X[:] = (200.0 + 0.05 * b.X.astype(np.float64)).astype(np.float32)
+    d = kb.DeviceBatch(b)
+    d.cluster()
+    _sync()
+    ora = oracle.cluster(b.seg_off, b.koff, b.X, b.iters)
+    tsq = np.add.reduceat((b.X.astype(np.float64) ** 2).sum(1), b.seg_off[:-1])
+    assert (ora.objective < 1e-7 * tsq).all()
+    clean = ora.dirty == 0
+    assert clean.any()
+    cp = clean[search_of(b.seg_off)]
+    np.testing.assert_array_equal(d.host("assign")[cp], ora.assign[cp])
+    assert_rel_close(d.host("objective")[clean], ora.objective[clean], what=path + " objective")
+    # searches with near-ties: still the objective of the assignment they ended with
+    a, c9 = d.host("assign"), None
+    d9 = kb.DeviceBatch(b, iters=b.iters - 1)
+    d9.cluster()
+    _sync()
+    cin = d9.host("cent")
+    sid = search_of(b.seg_off)
+    diff = b.X.astype(np.float64) - cin.astype(np.float64)[b.koff[:-1][sid] + a]
+    J = np.add.reduceat((diff ** 2).sum(1), b.seg_off[:-1])
+    assert_rel_close(d.host("objective"), J, what=path + " objective of the final assignment")
+
+
 def test_empty_searches(kb, scorer):
     b = synth.config5(G=12, nmin=64, nmax=200, seed=8)
     # splice in empty searches (N_g = 0, K_g = 0) at the front, middle and end
