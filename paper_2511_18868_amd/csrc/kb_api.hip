@@ -70,7 +70,7 @@ static kb_status check_batch(const kb_batch* b) {
 
 static kb_status check_cluster_shape(const kb_batch* b) {
     if (b->D > KB_MAX_D || b->Kmax > KB_MAX_K) return KB_EUNSUPPORTED;
-    if (!cluster_uses_big(*b) && !cluster_supported(*b)) return KB_EUNSUPPORTED;
+    if (!cluster_supported(*b)) return KB_EUNSUPPORTED;
     return KB_OK;
 }
 
@@ -143,8 +143,16 @@ static kb_status do_cluster(const kb_batch* b, const float* X, const float* cent
     c.split = (void*)(base + w.split); c.max_tiles = (int64_t)w.max_tiles;
     c.scorer = scorer;
     c.guard = reclustering ? 1 : 0;
-    if (w.use_big) return dev(launch_cluster_big(*b, c, w.big, base, st));
-    return dev(launch_cluster(*b, c, st));
+    c.mixed = 0;
+    if (!w.use_big) return dev(launch_cluster(*b, c, st));
+    // some search needs the multi-workgroup kernels; with more than one search in the
+    // batch the others may not, and go to the one-workgroup kernel in the same call
+    c.mixed = b->G > 1 ? 1 : 0;
+    if (c.mixed) {
+        hipError_t e = launch_cluster(*b, c, st);
+        if (e != hipSuccess) return KB_EDEVICE;
+    }
+    return dev(launch_cluster_big(*b, c, w.big, base, st));
 }
 
 static kb_status check_ucb(const kb_batch* b, const kb_params* p, const int32_t* assign,

@@ -62,6 +62,7 @@ struct ClusterArgs {
     int64_t max_tiles;
     int use_bounds;
     int guard;         // leave searches with N_g < 2 K_g as they are (re-clustering rule of Alg. 1)
+    int mixed;         // leave searches of the multi-workgroup path (K_g > 64 or N_g > 65536) alone
     float* lim;        // [N] limit of every candidate: drift at its last scoring + its slack
 };
 
@@ -1119,7 +1120,9 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     g = clampi(g, 0, a.G - 1);
     int n0, ng, k0, K;
     search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+    if (a.mixed && search_is_big(ng, K)) return;      // the multi-workgroup kernels take this search
     if (K > a.Kmax) K = a.Kmax;   // LDS is sized from the host copy of Kmax
+    if (ng > a.Nmax) ng = a.Nmax; // (and of Nmax; a consistent batch never gets here)
     if (MT > 0 && K > 32 * MT) K = 32 * MT;
     if (ng <= 0 || K <= 0) {
         if (tid == 0 && a.iters > 0 && a.objective) a.objective[g] = 0.f;
@@ -1398,15 +1401,18 @@ constexpr size_t kMaxLds = 160 * 1024;
 
 }  // namespace
 
+// sizes the one-workgroup kernel is laid out for: the largest search it will take
+static int one_wg_kmax(const kb_batch& b) { return b.Kmax > kOneWgMaxK ? kOneWgMaxK : (b.Kmax > 0 ? b.Kmax : 1); }
+static int one_wg_nmax(const kb_batch& b) { return b.Nmax > kOneWgMaxN ? kOneWgMaxN : b.Nmax; }
+
 bool cluster_supported(const kb_batch& b) {
-    const int kmax = b.Kmax > 0 ? b.Kmax : 1;
     const int ds = (b.D + 15) / 16;
-    return lds_layout(kmax, b.D, 16 * ds + 4, b.Nmax).total <= kMaxLds;
+    return lds_layout(one_wg_kmax(b), b.D, 16 * ds + 4, one_wg_nmax(b)).total <= kMaxLds;
 }
 
 hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t st) {
     ClusterArgs a;
-    a.G = b.G; a.D = b.D; a.Ksum = b.Ksum; a.Kmax = b.Kmax > 0 ? b.Kmax : 1; a.N = b.N;
+    a.G = b.G; a.D = b.D; a.Ksum = b.Ksum; a.Kmax = one_wg_kmax(b); a.N = b.N;
     a.seg_off = b.seg_off; a.koff = b.koff; a.X = c.X; a.cent_init = c.cent_init;
     a.iters = c.iters; a.early_exit = 0; a.assign = c.assign; a.cent_out = c.cent_out;
     a.counts = c.counts; a.objective = c.objective; a.a_new = c.a_new; a.order = c.order;
@@ -1414,11 +1420,12 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     a.max_tiles = c.max_tiles;
     a.use_bounds = c.scorer != 2;
     a.guard = c.guard;
+    a.mixed = c.mixed;
     a.lim = c.lim;
 
     const int ds = (b.D + 15) / 16;   // 1..4 K-steps of 16 features
-    a.Nmax = b.Nmax;
-    const size_t lds = lds_layout(a.Kmax, b.D, 16 * ds + 4, b.Nmax).total;
+    a.Nmax = one_wg_nmax(b);
+    const size_t lds = lds_layout(a.Kmax, b.D, 16 * ds + 4, a.Nmax).total;
     if (lds > kMaxLds) return hipErrorInvalidValue;
     int mt = a.Kmax <= 32 ? 1 : (a.Kmax <= 64 ? 2 : 0);
     if (c.scorer == 1) mt = 0;

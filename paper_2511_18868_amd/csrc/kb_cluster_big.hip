@@ -37,6 +37,7 @@ constexpr int kWaves = kThreads / kWave;
 struct BigArgs {
     int G, D, Ksum, Kmax, Kpad, it, final_pass;
     int guard;              // 1: searches with N_g < 2 K_g are left as they are
+    int mixed;              // 1: searches of the one-workgroup path (K_g <= 64, N_g <= 65536) are left to it
     int64_t N, max_tiles;
     const int32_t* seg_off;
     const int32_t* koff;
@@ -67,6 +68,11 @@ struct BigArgs {
     int* needfull;          // [G] 1: the objective of this search has to be summed member by member
 };
 
+// searches this launch sequence leaves untouched
+__device__ __forceinline__ bool skipped(const BigArgs& a, int ng, int K) {
+    return (a.guard && ng < 2 * K) || (a.mixed && !search_is_big(ng, K));
+}
+
 // largest g with off[g] <= v (off non-decreasing, off[0] = 0, v < off[G])
 __device__ __forceinline__ int upper_search(const int32_t* off, int G, int64_t v) {
     int lo = 0, hi = G;
@@ -91,13 +97,13 @@ __global__ void __launch_bounds__(kThreads) big_init(BigArgs a) {
         const int r = (int)(idx / D), d = (int)(idx - (int64_t)r * D);
         float v;
         a.sums[idx] = 0;
-        if (a.cent_init && !a.guard) {
+        if (a.cent_init && !a.guard && !a.mixed) {
             v = a.cent_init[idx];
         } else {
             const int g = upper_search(a.koff, a.G, r);
             int n0, ng, k0, K;
             search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
-            if (a.guard && ng < 2 * K) continue;
+            if (skipped(a, ng, K)) continue;
             const int j = r - k0;
             v = a.cent_init ? a.cent_init[idx]
                             : (ng > 0 ? a.X[(size_t)(n0 + (j < ng ? j : ng - 1)) * D + d] : 0.f);
@@ -107,11 +113,11 @@ __global__ void __launch_bounds__(kThreads) big_init(BigArgs a) {
     if (a.it < 0) return;   // iters == 0: only the initial centroids
     for (int64_t r = t0; r < a.Ksum; r += stride) {
         a.dirty[r] = 0;
-        if (a.guard) {
+        if (a.guard || a.mixed) {
             const int g = upper_search(a.koff, a.G, r);
             int n0, ng, k0, K;
             search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
-            if (ng < 2 * K) continue;
+            if (skipped(a, ng, K)) continue;
         }
         a.counts[r] = 0;
     }
@@ -134,6 +140,7 @@ __global__ void __launch_bounds__(kThreads) big_presplit(BigArgs a) {
     search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
     const int tile = (int)(gt - a.tile_off[g]);
     if (tile * 32 >= ng) return;
+    if (a.mixed && !search_is_big(ng, K)) return;      // (the one-workgroup kernel splits its own rows)
     const int D = a.D;
     const bool vec = (D & 3) == 0;
     const int p = tile * 32 + m;
@@ -193,7 +200,7 @@ __global__ void __launch_bounds__(kThreads) big_renew(BigArgs a) {
     search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
     if (K > a.Kpad) K = a.Kpad;
     if (r == 0 && lane == 0) { a.nflag[0] = 0; a.nflag[1] = 0; }
-    if (a.guard && ng < 2 * K) return;
+    if (skipped(a, ng, K)) return;
     const int D = a.D;
     const int mt = j >> 5, lane_row = j & 31;
     __bf16* ap = reinterpret_cast<__bf16*>(a.aop + (size_t)g * (a.Kpad / 32) * (DS * 2 * 64));
@@ -277,7 +284,7 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
     search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
     if (K > a.Kpad) K = a.Kpad;
     if (ng <= 0 || K <= 0) return;
-    if (a.guard && ng < 2 * K) return;
+    if (skipped(a, ng, K)) return;
     const int ntiles = (ng + 31) >> 5;
     const int t0 = (c - a.chunk_off[g]) * kTilesPerChunk;
     const int t1 = t0 + kTilesPerChunk < ntiles ? t0 + kTilesPerChunk : ntiles;
@@ -572,7 +579,7 @@ __global__ void __launch_bounds__(kThreads, 2) big_score_valu(BigArgs a) {
     search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
     if (K > a.Kpad) K = a.Kpad;
     if (ng <= 0 || K <= 0) return;
-    if (a.guard && ng < 2 * K) return;
+    if (skipped(a, ng, K)) return;
     const int p0 = (c - a.chunk_off[g]) * kTilesPerChunk * 32;
     const int p1 = p0 + kTilesPerChunk * 32 < ng ? p0 + kTilesPerChunk * 32 : ng;
     if (p0 >= p1) return;
@@ -833,7 +840,7 @@ __global__ void __launch_bounds__(kThreads) big_update(BigArgs a) {
         search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
         if (n0 >= r1) break;
         if (jg0 >= K || ng <= 0) continue;
-        if (a.guard && ng < 2 * K) continue;
+        if (skipped(a, ng, K)) continue;
         const int64_t q0 = r0 > n0 ? r0 : n0;
         const int64_t q1 = r1 < (int64_t)n0 + ng ? r1 : (int64_t)n0 + ng;
         if (q0 >= q1) continue;
@@ -942,7 +949,7 @@ __global__ void __launch_bounds__(kObjThreads) big_objfast(BigArgs a) {
         if (tid == 0) a.objective[g] = 0.f;
         return;
     }
-    if (a.guard && ng < 2 * K) return;
+    if (skipped(a, ng, K)) return;
     const int D = a.D;
     const int ntiles = (ng + 31) >> 5;
     const int64_t tb = a.tile_off[g];
@@ -1063,10 +1070,10 @@ __global__ void __launch_bounds__(kThreads) big_objsum(BigArgs a) {
     const int g = blockIdx.x, tid = threadIdx.x;
     if (g >= a.G) return;
     if (!a.needfull[g]) return;
-    if (a.guard) {
+    if (a.guard || a.mixed) {
         int n0, ng, k0, K;
         search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
-        if (ng > 0 && ng < 2 * K) return;        // (uniform over the workgroup) objective left as it is
+        if (ng > 0 && skipped(a, ng, K)) return;   // (uniform over the workgroup) objective left as it is
     }
     double J = 0.0;
     for (int c = a.chunk_off[g] + tid; c < a.chunk_off[g + 1]; c += kThreads) J += a.partJ[c];
@@ -1113,7 +1120,7 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
                               hipStream_t st) {
     BigArgs a;
     a.G = b.G; a.D = b.D; a.Ksum = b.Ksum; a.Kmax = b.Kmax > 0 ? b.Kmax : 1; a.Kpad = w.kpad;
-    a.it = 0; a.final_pass = 0; a.guard = c.guard; a.N = b.N; a.max_tiles = c.max_tiles;
+    a.it = 0; a.final_pass = 0; a.guard = c.guard; a.mixed = c.mixed; a.N = b.N; a.max_tiles = c.max_tiles;
     a.seg_off = b.seg_off; a.koff = b.koff; a.X = c.X; a.cent_init = c.cent_init;
     a.assign = c.assign; a.cent = c.cent_out; a.counts = c.counts; a.objective = c.objective;
     a.tile_off = c.tile_off; a.chunk_off = reinterpret_cast<const int32_t*>(ws + w.chunk_off);

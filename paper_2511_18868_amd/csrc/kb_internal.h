@@ -20,9 +20,15 @@ struct BigWs {
     size_t chunk_off, sums, cnpad, centT, aop, dirty, amax, cnmax, nflag, few, partJ, prop, tsq, needfull, end;
 };
 BigWs big_ws_layout(const kb_batch& b, size_t base);
-// searches with more than 64 clusters or more than 65536 candidates take the
-// multi-workgroup path
-inline bool cluster_uses_big(const kb_batch& b) { return b.Kmax > 64 || b.Nmax > 65536; }
+// Searches with more than 64 clusters or more than 65536 candidates take the
+// multi-workgroup path, the others the one-workgroup kernel.  The host sees only
+// the largest K_g and N_g of a batch: when those say that the batch holds such a
+// search, both paths are enqueued and each leaves the other's searches alone
+// (decided on the device from every search's own K_g and N_g).
+constexpr int kOneWgMaxK = 64;
+constexpr int kOneWgMaxN = 65536;
+inline bool cluster_uses_big(const kb_batch& b) { return b.Kmax > kOneWgMaxK || b.Nmax > kOneWgMaxN; }
+__host__ __device__ inline bool search_is_big(int ng, int K) { return K > kOneWgMaxK || ng > kOneWgMaxN; }
 
 struct WsLayout {
     size_t a_new;   // int32 [N]     proposed assignment of the current step (bit 31: needs exact re-evaluation)
@@ -77,6 +83,7 @@ struct ClusterCall {
     int64_t max_tiles;
     float* lim;               // float [N] scratch of the fused kernel (every candidate's drift limit)
     int guard;                // 1: searches with N_g < 2 K_g keep their clustering untouched
+    int mixed;                // 1: the batch may hold searches of both paths; each kernel skips the other's
     int scorer;               // kb_params::scorer: 0 default, 1 vector ALU only, 2 matrix cores without bounds
 };
 hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t st);

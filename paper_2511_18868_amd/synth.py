@@ -70,6 +70,19 @@ class Batch:
         return int(np.max(np.diff(self.seg_off))) if self.G else 0
 
 
+def concat(a: Batch, b: Batch, name: str = "concat") -> Batch:
+    """The searches of `a` followed by those of `b` as one batch (same D and S)."""
+    assert a.D == b.D and a.S == b.S
+    cat = np.concatenate
+    return Batch(name=name, G=a.G + b.G, D=a.D, S=a.S, iters=a.iters,
+                 seg_off=cat([a.seg_off, a.seg_off[-1] + b.seg_off[1:]]).astype(np.int32),
+                 koff=cat([a.koff, a.koff[-1] + b.koff[1:]]).astype(np.int32),
+                 X=cat([a.X, b.X]), flops=cat([a.flops, b.flops]), bytes_=cat([a.bytes_, b.bytes_]),
+                 incumbent=cat([a.incumbent, b.incumbent]), visits=cat([a.visits, b.visits]),
+                 rsum=cat([a.rsum, b.rsum]), t=cat([a.t, b.t]), peak_flops=a.peak_flops,
+                 peak_bw=a.peak_bw, c=a.c, prior_n=a.prior_n, prior_mu=a.prior_mu)
+
+
 def _zscore(a: np.ndarray) -> np.ndarray:
     """Per-feature z-score over the rows, population std, zero variance -> 0."""
     mu = a.mean(axis=0)

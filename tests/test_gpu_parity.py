@@ -37,6 +37,23 @@ def _late_outliers():
     return b
 
 
+def _mixed_k():
+    """Searches of both clustering paths in one batch: five with up to 128 clusters in the
+    middle of 300 ordinary ones."""
+    kw = dict(D=40, S=4, iters=8)
+    a = synth.config5(G=180, nmin=64, nmax=900, seed=78, **kw)
+    big = synth.config5(G=5, nmin=1500, nmax=5000, kcap=128, seed=77, **kw)
+    c = synth.config5(G=120, nmin=64, nmax=2000, seed=79, **kw)
+    return synth.concat(synth.concat(a, big), c, "mixedK")
+
+
+def _mixed_n():
+    """One search of 70001 candidates (too long for one workgroup) among 60 short ones."""
+    a = synth.config5(G=60, nmin=64, nmax=700, D=16, S=4, iters=6, seed=80)
+    big = synth.config2(N=70001, D=16, K=8, S=4, iters=6, seed=5)
+    return synth.concat(a, big, "mixedN")
+
+
 SMALL = {
     "cfg1": lambda: synth.config1(),
     "cfg2": lambda: synth.config2(),
@@ -52,6 +69,9 @@ SMALL = {
     "cfg4s": lambda: synth.config4(N=8192, K=256, ncentres=256),
     "bigmulti": lambda: synth.config5(G=5, nmin=1500, nmax=5000, kcap=128, D=40, S=4, iters=8, seed=77),
     "bigN": lambda: synth.config2(N=70001, D=16, K=8, S=4, iters=6, seed=5),
+    # both paths in one call, every search on the path its own size asks for
+    "mixedK": _mixed_k,
+    "mixedN": _mixed_n,
 }
 
 
@@ -61,12 +81,14 @@ def scorer(request):
     return request.param
 
 
-def _multi_workgroup(b):
-    return b.Kmax > 64 or b.Nmax > 65536
+def _multi_workgroup_only(b):
+    """Every search of the batch takes the multi-workgroup clustering path."""
+    ng, kg = np.diff(b.seg_off), np.diff(b.koff)
+    return bool(((kg > 64) | (ng > 65536)).all())
 
 
 def _skip_repeat(b, scorer):
-    if scorer == 2 and _multi_workgroup(b):
+    if scorer == 2 and _multi_workgroup_only(b):
         pytest.skip("the multi-workgroup path scores every tile in the default mode already: "
                     "mode 2 is the same code path as mode 0 there")
 
@@ -274,6 +296,27 @@ def test_objective_of_tight_clusters_far_from_the_origin(kb, path):
     diff = b.X.astype(np.float64) - cin.astype(np.float64)[b.koff[:-1][sid] + a]
     J = np.add.reduceat((diff ** 2).sum(1), b.seg_off[:-1])
     assert_rel_close(d.host("objective"), J, what=path + " objective of the final assignment")
+
+
+def test_mixed_batch_equals_the_two_paths_run_apart(kb):
+    """A batch that holds searches of both clustering paths gives, search by search,
+    the bytes the searches give in batches of their own kind."""
+    kw = dict(D=40, S=4, iters=5)
+    small = synth.config5(G=40, nmin=64, nmax=900, seed=81, **kw)
+    big = synth.config5(G=3, nmin=1500, nmax=4000, kcap=128, seed=82, **kw)
+    both = synth.concat(small, big)
+    out = {}
+    for name, b in (("small", small), ("big", big), ("both", both)):
+        d = kb.DeviceBatch(b)
+        d.round()
+        _sync()
+        out[name] = {k: d.host(k).copy() for k in ("assign", "cent", "counts", "objective", "Ncs", "sel")}
+    for k in ("assign", "cent", "counts", "objective", "Ncs"):
+        want = np.concatenate([out["small"][k], out["big"][k]])
+        np.testing.assert_array_equal(out["both"][k].view(np.uint8), want.view(np.uint8), err_msg=k)
+    sel_big = out["big"]["sel"].copy()
+    sel_big[:, 2] += small.N                       # k* is a global candidate index
+    np.testing.assert_array_equal(out["both"]["sel"], np.concatenate([out["small"]["sel"], sel_big]))
 
 
 def test_empty_searches(kb, scorer):
