@@ -38,11 +38,14 @@ struct UcbArgs {
     unsigned* gnalive;          // [Ksum]
     unsigned long long* gkmin;  // [Ksum]
     int64_t Nll;
+    int mixed;                  // 1: searches of up to kUcbLong candidates go to ucb_kernel, longer ones to the
+                                //    range kernels, in the same call
 };
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr double kRewardInv = 1.0 / 1073741824.0;
+constexpr int kUcbLong = 16384;     // searches longer than this are cut into candidate ranges
 
 // Monotone map from float to uint32 (a < b  <=>  key(a) < key(b)), so an
 // integer atomic min orders bounds of any sign.
@@ -219,6 +222,7 @@ __global__ void __launch_bounds__(kThreads) ucb_kernel(UcbArgs a) {
         if (tid < 3) a.sel[(size_t)g * 3 + tid] = -1;
         return;
     }
+    if (a.mixed && ng > kUcbLong) return;     // the range kernels take this search
     const int KS = K * S;
 
     double* redv = reinterpret_cast<double*>(smem);                                      // [kWaves]
@@ -273,6 +277,7 @@ __global__ void __launch_bounds__(kThreads) ucb_partial(UcbArgs a) {
         if (K > a.Kmax) K = a.Kmax;
         if (n0 >= r1) break;
         if (ng <= 0 || K <= 0) continue;
+        if (a.mixed && ng <= kUcbLong) continue;     // one workgroup takes this search whole
         const int64_t q0 = r0 > n0 ? r0 : n0;
         const int64_t q1 = r1 < (int64_t)n0 + ng ? r1 : (int64_t)n0 + ng;
         if (q0 >= q1) continue;
@@ -303,6 +308,7 @@ __global__ void __launch_bounds__(kThreads) ucb_final(UcbArgs a) {
     int n0, ng, k0, K;
     search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
     if (K > a.Kmax) K = a.Kmax;
+    if (a.mixed && ng <= kUcbLong) return;       // (uniform) done by ucb_kernel, empty searches included
     if (ng <= 0 || K <= 0) {
         if (threadIdx.x < 3) a.sel[(size_t)g * 3 + threadIdx.x] = -1;
         return;
@@ -323,11 +329,20 @@ hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st) {
     const size_t lds = 64 + (size_t)a.Kmax * b.S * 12 + (size_t)a.Kmax * 12;
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     a.gN = c.gN; a.gR = c.gR; a.gnalive = c.gnalive; a.gkmin = c.gkmin; a.Nll = b.N;
+    a.mixed = 0;
     if (c.gN) {
-        // long searches: candidate ranges -> partial tables -> global tables -> scores
+        // long searches: candidate ranges -> partial tables -> global tables -> scores;
+        // in a batch of several searches the short ones get a workgroup each as usual
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ucb_partial),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
+        if (b.G > 1) {
+            a.mixed = 1;
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(ucb_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(ucb_kernel, dim3((unsigned)b.G), dim3(kThreads), lds, st, a);
+        }
         const size_t items = (size_t)b.Ksum * b.S;
         unsigned zb = (unsigned)((items + kThreads - 1) / kThreads);
         if (zb > 4096u) zb = 4096u;
