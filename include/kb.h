@@ -62,6 +62,15 @@
  * only ever used after clamping to [0, N] / [0, Ksum], so a violated
  * precondition gives wrong numbers but no out-of-bounds access.
  *
+ * Scale of the features.  The centroid sums are exact 64-bit fixed-point sums on
+ * ONE grid per search, 2^-37 of the search's largest |x| or finer (2^-45 for a
+ * search of 4096 candidates): a centroid coordinate is the fp32 rounding of the
+ * exact mean up to that absolute step.  Features are expected to be
+ * commensurately scaled, as the normalised phi of Sec. 3.2 is.  A feature column
+ * whose values lie more than a factor 2^13 below the largest |x| of its search
+ * starts to lose low-order bits of an fp32 centroid (beyond 2^20 below, its
+ * centroids are off by more than 1e-5 relative); no error is reported.
+ *
  * Limits of the compiled kernels (KB_EUNSUPPORTED beyond):
  *   1 <= D <= 64, 1 <= S, Kmax <= 256, Kmax*S <= 8192, N < 2^31,
  *   and G <= 1048576.

@@ -271,6 +271,8 @@ __global__ void __launch_bounds__(kThreads) big_renew(BigArgs a) {
 // per-group results of a tile meet in LDS and one wave per tile merges them,
 // decides whether the nearest centroid is certain, and writes the proposal.
 constexpr int kGroupTiles = 4;     // candidate tiles staged in LDS at a time
+constexpr int kListCap = 512;      // doubtful candidates of a chunk collected in LDS per list; further ones
+                                   // are appended to the global lists one by one
 
 template <int DS>
 __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
@@ -304,9 +306,9 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
     // doubtful candidates of this chunk: those with at most one possible nearest
     // centroid per lane part go to `lfew` with the list of those centroids, the
     // others to `lflag` for the full exact pass
-    int4* lfew = reinterpret_cast<int4*>(res + 4 * kGroupTiles * 64);   // [kTilesPerChunk * 32]
-    int* lflag = reinterpret_cast<int*>(lfew + kTilesPerChunk * 32);    // [kTilesPerChunk * 32]
-    int* lcount = lflag + kTilesPerChunk * 32;      // [4]: counts, bases in the global lists
+    int4* lfew = reinterpret_cast<int4*>(res + 4 * kGroupTiles * 64);   // [kListCap]
+    int* lflag = reinterpret_cast<int*>(lfew + kListCap);               // [kListCap]
+    int* lcount = lflag + kListCap;                 // [4]: counts, bases in the global lists
     if (tid < 2) lcount[tid] = 0;
 
     // this wave's centroid operands and |c|^2, resident for the whole chunk
@@ -527,23 +529,38 @@ __global__ void __launch_bounds__(kThreads, 2) big_score(BigArgs a) {
                     int e = 0;
                     if (lane == 0) e = atomicAdd(&lcount[1], 1);
                     e = __shfl(e, 0);
+                    int4* rec = lfew + e;
+                    if (e >= kListCap) {                    // (uniform) the LDS list is full
+                        long long pos = 0;
+                        if (lane == 0) pos = atomicAdd(&a.nflag[1], 1);
+                        pos = __shfl(pos, 0);
+                        rec = a.few + (pos < a.N ? pos : 0);
+                        if (pos >= a.N) continue;           // (cannot happen: one record per candidate at most)
+                    }
                     if (is) {
                         const int rank = __popcll(cm & ((1ull << q) - 1ull));
-                        reinterpret_cast<unsigned char*>(lfew)[e * 16 + 8 + rank] = (unsigned char)idx;
+                        reinterpret_cast<unsigned char*>(rec)[8 + rank] = (unsigned char)idx;
                     }
                     if (lane == 0) {
-                        int* hdr = reinterpret_cast<int*>(lfew + e);
+                        int* hdr = reinterpret_cast<int*>(rec);
                         hdr[0] = pcand;
                         hdr[1] = __popcll(cm);
                     }
                 } else if (lane == 0) {
-                    lflag[atomicAdd(&lcount[0], 1)] = pcand;
+                    const int e = atomicAdd(&lcount[0], 1);
+                    if (e < kListCap) {
+                        lflag[e] = pcand;
+                    } else {
+                        const long long pos = atomicAdd(&a.nflag[0], 1);
+                        if (pos < a.N) a.flist[pos] = pcand;
+                    }
                 }
             }
         }
     }
     __syncthreads();
-    const int nl = lcount[0], nf = lcount[1];
+    const int nl = lcount[0] < kListCap ? lcount[0] : kListCap;
+    const int nf = lcount[1] < kListCap ? lcount[1] : kListCap;
     if (nl > 0 || nf > 0) {
         if (tid == 0 && nl > 0) lcount[2] = atomicAdd(&a.nflag[0], nl);
         if (tid == 1 && nf > 0) lcount[3] = atomicAdd(&a.nflag[1], nf);
@@ -658,13 +675,13 @@ __global__ void __launch_bounds__(kThreads, 2) big_score_valu(BigArgs a) {
 // exactly as the plain definition does - fp64, direct differences, summed over the
 // features in index order with separate multiply and add - and the eight reduce
 // to the minimum, lowest centroid index on ties.
-__global__ void __launch_bounds__(kThreads) big_exact_few(BigArgs a) {
+__device__ __forceinline__ void exact_few(const BigArgs& a, int block, int nblocks) {
     int64_t n = a.nflag[1];
     if (n > a.N) n = a.N;
     const int D = a.D;
-    const int64_t stride = (int64_t)gridDim.x * (kThreads / 8);
+    const int64_t stride = (int64_t)nblocks * (kThreads / 8);
     const int slot = threadIdx.x & 7;
-    for (int64_t i = (int64_t)blockIdx.x * (kThreads / 8) + (threadIdx.x >> 3); i < n; i += stride) {
+    for (int64_t i = (int64_t)block * (kThreads / 8) + (threadIdx.x >> 3); i < n; i += stride) {
         const int4 rec = a.few[i];
         const int pg = rec.x;
         double dist = INFINITY;
@@ -709,7 +726,7 @@ __global__ void __launch_bounds__(kThreads) big_exact_few(BigArgs a) {
 // distance within a factor 1 + 3e-5 of the smallest - every true minimiser is
 // among them - are evaluated exactly: fp64 direct differences summed over the
 // features in index order with separate multiply and add, lowest index on ties.
-__global__ void __launch_bounds__(kThreads) big_exact(BigArgs a) {
+__device__ __forceinline__ void exact_full(const BigArgs& a, int block, int nblocks) {
     static_assert(KB_MAX_K <= kThreads, "one lane per centroid");
     __shared__ float redm[kWaves];
     __shared__ double redd[kWaves];
@@ -728,15 +745,15 @@ __global__ void __launch_bounds__(kThreads) big_exact(BigArgs a) {
         return (v >= 0 && v < a.N) ? v : -1;
     };
     auto row_at = [&](int pgv) { return (pgv >= 0 && lane < D) ? a.X[(size_t)pgv * D + lane] : 0.f; };
-    int pg_cur = index_at(blockIdx.x);
-    int pg_nxt = index_at((int64_t)blockIdx.x + gridDim.x);
+    int pg_cur = index_at(block);
+    int pg_nxt = index_at((int64_t)block + nblocks);
     float xv_cur = row_at(pg_cur);
-    for (int64_t i = blockIdx.x; i < n; i += gridDim.x) {
+    for (int64_t i = block; i < n; i += nblocks) {
         // everything up to the barriers is uniform over the workgroup
         const int pg = pg_cur;
         const float xv = xv_cur;
         pg_cur = pg_nxt;
-        pg_nxt = index_at(i + 2 * (int64_t)gridDim.x);
+        pg_nxt = index_at(i + 2 * (int64_t)nblocks);
         xv_cur = row_at(pg_cur);
         if (pg < 0) continue;
         const int g = upper_search(a.seg_off, a.G, pg);
@@ -805,6 +822,14 @@ __global__ void __launch_bounds__(kThreads) big_exact(BigArgs a) {
     }
 }
 
+// Both exact passes in one launch: the first kFewBlocks workgroups take the short
+// pass, the others the full one (their lists are disjoint, so they do not meet).
+constexpr int kFewBlocks = 512, kFullBlocks = 1024;
+__global__ void __launch_bounds__(kThreads) big_exact(BigArgs a) {
+    if (blockIdx.x < kFewBlocks) exact_few(a, (int)blockIdx.x, kFewBlocks);       // (uniform over the workgroup)
+    else exact_full(a, (int)blockIdx.x - kFewBlocks, kFullBlocks);
+}
+
 // Move the candidates whose proposal differs from their previous cluster.  A
 // workgroup owns a group of kRowsPerGroup clusters of one search and a range of
 // its candidates.  It works through the range in batches: the (previous,
@@ -813,8 +838,8 @@ __global__ void __launch_bounds__(kThreads) big_exact(BigArgs a) {
 // l, l + 16, ...) convert it to fixed point and add or subtract it in LDS
 // (integer atomics), with the next row already requested.  The partial sums go
 // to the global fixed-point sums once, at the end.
-constexpr int kRowsPerGroup = 16;
-constexpr int kUpdateRange = 16384;   // candidates per workgroup
+constexpr int kRowsPerGroup = 32;
+constexpr int kUpdateRange = 8192;    // candidates per workgroup
 constexpr int kUpdateBatch = 4096;    // candidates scanned per list
 __global__ void __launch_bounds__(kThreads) big_update(BigArgs a) {
     __shared__ long long lsum[kRowsPerGroup * KB_MAX_D];
@@ -1155,7 +1180,7 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
     const unsigned row_blocks = (unsigned)(((size_t)b.G * w.kpad + kWaves - 1) / kWaves);
     const unsigned chunk_blocks = (unsigned)w.max_chunks;
     const size_t lds = (size_t)kGroupTiles * ds * 2 * 64 * 16 + (size_t)4 * kGroupTiles * 64 * 8 +
-                       (size_t)kTilesPerChunk * 32 * (16 + 4) + 16;
+                       (size_t)kListCap * (16 + 4) + 16;
     // the vector-ALU scorer stages a search's centroids in LDS instead
     const size_t lds_valu = (size_t)w.kpad * (16 * ds + 1) * 4 + (size_t)kTilesPerChunk * 32 * 4 + 16;
     if (lds > 160 * 1024 || lds_valu > 160 * 1024) return hipErrorInvalidValue;
@@ -1184,8 +1209,7 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
                                    lds_valu, st, a);                                             \
             else                                                                                 \
                 hipLaunchKernelGGL(big_score<DS_>, dim3(chunk_blocks), dim3(kThreads), lds, st, a); \
-            hipLaunchKernelGGL(big_exact_few, dim3(512), dim3(kThreads), 0, st, a);              \
-            hipLaunchKernelGGL(big_exact, dim3(1024), dim3(kThreads), 0, st, a);                 \
+            hipLaunchKernelGGL(big_exact, dim3(kFewBlocks + kFullBlocks), dim3(kThreads), 0, st, a); \
             hipLaunchKernelGGL(big_update, upd_grid, dim3(kThreads), 0, st, a);                  \
         }                                                                                        \
         hipLaunchKernelGGL(big_objfast, dim3((unsigned)b.G), dim3(kObjThreads), 0, st, a);       \

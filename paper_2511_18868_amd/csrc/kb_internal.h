@@ -10,7 +10,7 @@ namespace kb {
 constexpr int kWave = 64;
 constexpr int kGeoRange = 2048;      // candidates per workgroup of the representative / radius pass
 constexpr int kSampleRange = 4096;   // candidates per workgroup of the in-cluster draw
-constexpr int kTilesPerChunk = 32;   // tiles of 32 candidates per workgroup of the multi-workgroup clustering path
+constexpr int kTilesPerChunk = 64;   // tiles of 32 candidates per workgroup of the multi-workgroup clustering path
 
 // ---- workspace layout (all offsets 256-byte aligned) ------------------------
 // extra buffers of the multi-workgroup clustering path

@@ -29,6 +29,11 @@ def _sync():
     torch.cuda.synchronize()
 
 
+# searches the oracle excludes as near-ties at full size (seeded inputs, deterministic
+# oracle: exact counts; none of the selections is a near-tie)
+NEAR_TIE_SEARCHES = {"config3": 3, "config5": 56}
+
+
 def _full_round_vs_oracle(kb, b, name):
     d = kb.DeviceBatch(b)
     d.round()
@@ -60,7 +65,7 @@ def _full_round_vs_oracle(kb, b, name):
     print(f"[{name}] {b.G} searches: {int(clean.sum())} compared bit-exactly, {int((~clean).sum())} "
           f"excluded as near-tie (of which {same} match anyway), {int((ora.near != 0).sum())} "
           f"selections excluded as near-tie", flush=True)
-    assert clean.mean() > 0.9
+    assert (~clean).sum() <= NEAR_TIE_SEARCHES[name] and (ora.near == 0).all()
     _loop_steps_vs_oracle(kb, b, d, name, ora, ok)
 
 

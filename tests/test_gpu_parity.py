@@ -75,6 +75,13 @@ SMALL = {
 }
 
 
+# Searches of each case the oracle excludes from the bit-exact comparison of a whole
+# kb_cluster call because it saw a near-tie in one of the Lloyd steps.  The inputs
+# are seeded and the oracle is deterministic, so these are exact counts: an
+# exclusion set that grows fails the test.
+NEAR_TIE_SEARCHES = {"cfg3s": 1, "cfg5s": 4, "lateoutliers": 1}
+
+
 @pytest.fixture(scope="module", params=[0, 1, 2], ids=["bounds", "vectoralu", "matrixcore"])
 def scorer(request):
     """kb_params.scorer: every mode of the Lloyd step must give the same results."""
@@ -177,7 +184,8 @@ def test_cluster_fused_matches_oracle(kb, case, scorer):
     got = {k: d.host(k) for k in ("assign", "cent", "counts", "objective")}
     sid = search_of(b.seg_off)
     clean = ora.dirty == 0
-    assert clean.mean() > 0.8, f"{name}: only {clean.mean():.2%} searches free of near-ties"
+    assert (~clean).sum() <= NEAR_TIE_SEARCHES.get(name, 0), \
+        f"{name}: {(~clean).sum()} searches excluded as near-ties"
     cp = clean[sid]
     np.testing.assert_array_equal(got["assign"][cp], ora.assign[cp])
     ck = np.repeat(clean, np.diff(b.koff))
@@ -319,6 +327,50 @@ def test_mixed_batch_equals_the_two_paths_run_apart(kb):
     np.testing.assert_array_equal(out["both"]["sel"], np.concatenate([out["small"]["sel"], sel_big]))
 
 
+def test_features_of_different_magnitude(kb):
+    """One fixed-point grid per search serves every feature: columns a few thousand
+    times smaller than the largest one still give centroids good to fp32 rounding
+    (the documented range; kb.h says where it ends)."""
+    b = synth.config5(G=8, nmin=200, nmax=900, seed=91)
+    scale = np.ones(b.D)
+    scale[3], scale[7], scale[20] = 2.0 ** -10, 2.0 ** -12, 2.0 ** -6
+    b.X[:] = (b.X.astype(np.float64) * scale).astype(np.float32)
+    d = kb.DeviceBatch(b, iters=6)
+    d.cluster()
+    _sync()
+    ora = oracle.cluster(b.seg_off, b.koff, b.X, 6)
+    ck = np.repeat(ora.dirty == 0, np.diff(b.koff))
+    assert ck.any()
+    got, want = d.host("cent")[ck].astype(np.float64), ora.cent[ck].astype(np.float64)
+    for col in (3, 7, 20, 0):
+        big = np.abs(want[:, col]) > 1e-3 * scale[col]          # (away from zero: pure relative error)
+        rel = np.abs(got[big, col] - want[big, col]) / np.abs(want[big, col])
+        assert rel.max() < 2e-7, (col, rel.max())
+
+
+def test_many_exact_ties_on_the_multi_workgroup_path(kb):
+    """Integer coordinates on a small grid and 80 clusters seeded from the rows: most
+    candidates tie exactly between duplicate centroids, far more per chunk than the
+    scorer's on-chip lists of doubtful candidates hold, so the lists overflow into the
+    global ones.  Exact ties go to the lowest index on both sides and means of integers
+    round identically, so every assignment must be equal, flagged or not."""
+    rng = np.random.default_rng(12)
+    b = synth.config2(N=6000, D=2, K=80, S=4, iters=3, seed=13)
+    b.X[:] = rng.integers(-5, 6, size=b.X.shape).astype(np.float32)
+    d = kb.DeviceBatch(b)
+    d.cluster()
+    _sync()
+    ora = oracle.cluster(b.seg_off, b.koff, b.X, b.iters)
+    np.testing.assert_array_equal(d.host("assign"), ora.assign)
+    np.testing.assert_array_equal(d.host("counts"), ora.counts)
+    np.testing.assert_array_equal(d.host("cent").view(np.uint32), ora.cent.view(np.uint32))
+    cin = synth.random_centroids(b, 2)
+    got = _gpu_step(d, cin)
+    one = oracle.cluster_step(b.seg_off, b.koff, b.X, cin)
+    assert one.flag.sum() > 1000
+    np.testing.assert_array_equal(got["assign"], one.assign)
+
+
 def test_empty_searches(kb, scorer):
     b = synth.config5(G=12, nmin=64, nmax=200, seed=8)
     # splice in empty searches (N_g = 0, K_g = 0) at the front, middle and end
@@ -366,7 +418,7 @@ def test_ucb_select(kb, case):
     assert_rel_close(d.host("ucb"), ora.ucb, what=name + " ucb")
     ok = ora.near == 0
     np.testing.assert_array_equal(d.host("sel")[ok], ora.sel[ok])
-    assert ok.mean() > 0.9
+    assert ok.all(), f"{name}: {(~ok).sum()} selections excluded as near-ties"   # (none in these cases)
 
 
 def test_ucb_special_cases(kb):
@@ -513,7 +565,7 @@ def test_many_tiny_searches(kb):
     assert_cent_close(d.host("cent")[ck], ora.cent[ck], "tiny")
     ok = clean & (ora.near == 0)
     np.testing.assert_array_equal(d.host("sel")[ok], ora.sel[ok])
-    assert clean.mean() > 0.95
+    assert clean.all() and ok.all()          # (the oracle flags nothing in this batch)
     s = oracle.sample(b.seg_off, d.host("assign"), d.host("alive"), d.host("bound"), b.incumbent,
                       d.host("sel"), 9, 1, 1.0)
     fine = s.near == 0
