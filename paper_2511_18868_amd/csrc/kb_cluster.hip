@@ -3,8 +3,9 @@
 // of its Lloyd steps, so the search's rows stay in L2 / Infinity Cache between
 // steps and the centroids never leave LDS.
 //
-// Once per call the feature rows are split into bf16 (hi, mid) pieces in the
-// matrix cores' operand order (workspace), together with |x|^2.
+// Once per call (in its first step) the feature rows are split into bf16 (hi, mid)
+// pieces, candidate by candidate, into a workspace copy the later steps score from;
+// |x|^2, the cluster and the drift limit of every candidate share a second array.
 //
 // One step:
 //
@@ -63,7 +64,8 @@ struct ClusterArgs {
     int use_bounds;
     int guard;         // leave searches with N_g < 2 K_g as they are (re-clustering rule of Alg. 1)
     int mixed;         // leave searches of the multi-workgroup path (K_g > 64 or N_g > 65536) alone
-    float* lim;        // [N] limit of every candidate: drift at its last scoring + its slack
+    float2* lim;       // [N] state of every candidate: .x its drift limit (drift at its last scoring + its
+                       //     slack) with its cluster + 1 in the 7 lowest bits, .y its |x|^2
 };
 
 constexpr int kThreads = 256;
@@ -252,9 +254,13 @@ __device__ __forceinline__ void score_valu(const ClusterArgs& a, const float* __
 // about and whose cluster changed are moved between the fixed-point sums right
 // here (their fp32 row is read again; rare after the first steps).
 // The feature rows are split once per call (in the first step) into a workspace
-// laid out in operand order - [tile][K-step][hi|mid][lane] x 16 bytes - so a later
-// step fetches a candidate's operands as 16-byte pieces with no conversion work
-// (whole tiles: fully coalesced 1 KB loads).
+// copy laid out candidate by candidate - [candidate][K-step][half][hi|mid] x 16
+// bytes, the 64 * DS bytes of a candidate contiguous - so a later step fetches a
+// candidate's operands as 16-byte pieces with no conversion work, and a packed
+// tile of candidates from all over the search moves the bytes of those candidates
+// only (with the pieces of 32 neighbours interleaved, as the matrix cores read
+// them, a tile in which a few candidates are at risk still pulled in most of its
+// cache lines: 9.2 GB of HBM traffic on the largest benchmark against 7.1 GB).
 // Everything that follows a change of a centroid, 16 lanes per row (lane l owns
 // features 4l .. 4l+3): the new centroid (fixed-point sum / 2^shift) / count in
 // fp64, rounded once to fp32; how far it moved (rounded up); |c_j|^2 in fp64; and
@@ -387,6 +393,16 @@ __device__ __forceinline__ float half_wave_min_f(float v) {
 __device__ __forceinline__ float tile_limit(float drift, float slack) {
     return (drift + slack) * 0.9999995f;
 }
+// A candidate's limit shares its word with the candidate's cluster: cluster + 1 in the 7
+// lowest mantissa bits (0: none yet), which rounds the non-negative limit down by less
+// than 2^-16 of itself.  The wave that finds a tile at risk reads the tile's words in one
+// coalesced piece; the lane that scores a candidate then finds cluster and |x|^2 next
+// to a limit that is already in the caches, instead of two gathers of their own.
+__device__ __forceinline__ float pack_limit(float L, int cluster) {
+    return __uint_as_float((__float_as_uint(L) & ~127u) | (unsigned)(cluster + 1));
+}
+__device__ __forceinline__ float limit_of(float v) { return __uint_as_float(__float_as_uint(v) & ~127u); }
+__device__ __forceinline__ int cluster_of(float v) { return (int)(__float_as_uint(v) & 127u) - 1; }
 
 // Scores of one tile of 32 candidates (operands Bh, Bm) against the K <= 64
 // centroids: best score, second best and the row of the best, the same in both
@@ -529,7 +545,7 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
                                             const float* cent, const float* cn, float cnmax,
                                             int fsh, long long* sums, int* cnt,
                                             int* nflag, unsigned short* flist, const bf16x8* aop, unsigned char* dirty,
-                                            float* thr, float* __restrict__ lim,
+                                            float* thr, float2* __restrict__ lim,
                                             unsigned short* queue, float drift) {
     const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
     const int m = lane & 31, h = lane >> 5;
@@ -578,15 +594,18 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
         const int p = q[(head + (valid ? m : 0)) & (kQueue - 1)];
         bf16x8 Bh[DS], Bm[DS];
         {
-            const bf16x8* tp = sp + (size_t)(p >> 5) * (DS * 2 * 64) + (p & 31) + 32 * h;
+            // (candidate-major copy: the 64 * DS bytes of a candidate are contiguous, so a
+            // packed chunk fetches the bytes of its own candidates and no one else's)
+            const bf16x8* tp = sp + (size_t)p * (DS * 4) + 2 * h;
 #pragma unroll
             for (int s = 0; s < DS; ++s) {
-                Bh[s] = tp[(2 * s) * 64];
-                Bm[s] = tp[(2 * s + 1) * 64];
+                Bh[s] = tp[4 * s];
+                Bm[s] = tp[4 * s + 1];
             }
         }
-        const float xn = a.xn[(size_t)n0 + p];
-        int old = a.assign[(size_t)n0 + p];
+        const float2 state = lim[p];
+        const float xn = state.y;
+        int old = cluster_of(state.x);
         old = (valid && old >= 0 && old < K) ? old : -1;
 
         float best, second;
@@ -620,15 +639,15 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
             while (pt - ph >= kMoverBatch) drain(kMoverBatch);
         }
         if (valid && h == 0) {
-            a.a_new[(size_t)n0 + p] = certain ? bi : (bi | kFlagBit);
             if (!certain) {
+                // (the exact pass sets cluster and limit of the candidates it decides)
+                a.a_new[(size_t)n0 + p] = bi | kFlagBit;
                 const int pos = atomicAdd(nflag, 1);
                 if (pos < kFlagCap) flist[pos] = (unsigned short)p;     // (N_g <= 65536 on this path)
-            } else if (a.use_bounds) {
-                // (the exact pass sets the limit of the candidates it decides)
-                const float L = tile_limit(drift, slack_of(best, second, xn, E));
-                lim[p] = L;
-                atomicMin(reinterpret_cast<unsigned*>(&thr[p >> 5]), __float_as_uint(L));
+            } else {
+                const float L = a.use_bounds ? limit_of(tile_limit(drift, slack_of(best, second, xn, E))) : 0.f;
+                lim[p].x = pack_limit(L, bi);
+                if (a.use_bounds) atomicMin(reinterpret_cast<unsigned*>(&thr[p >> 5]), __float_as_uint(L));
             }
         }
         if (__any(valid && !certain)) any |= 2;
@@ -656,7 +675,7 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
             const int tl = wid + kWaves * (i0 + (myc >= 0 ? myc : c0));
             p = tl * 32 + m;
             in = have && myc >= 0 && p < ng;
-            lv = lim[in ? p : 0];
+            lv = limit_of(lim[in ? p : 0].x);
         };
         bool have, in;
         int c0, c1, p;
@@ -711,7 +730,7 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
                                            int SP, const float* cn, float cnmax, int fsh,
                                            long long* sums, int* cnt, int* nflag, unsigned short* flist,
                                            const bf16x8* aop, unsigned char* dirty, float* thr,
-                                           float* __restrict__ lim, float& am_out, double& sq_out) {
+                                           float2* __restrict__ lim, float& am_out, double& sq_out) {
     const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
     const int m = lane & 31, h = lane >> 5;
     const int mtiles = (K + 31) >> 5;
@@ -768,15 +787,15 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
         float xv[DS][8];
         bf16x8 Bh[DS], Bm[DS];
         float xn = 0.f;
-        bf16x8* tp = spw + (size_t)tile * (DS * 2 * 64) + lane;
+        bf16x8* tp = spw + (size_t)p * (DS * 4) + 2 * h;
 #pragma unroll
         for (int s = 0; s < DS; ++s) {
             xv[s][0] = cur[s][0].x; xv[s][1] = cur[s][0].y; xv[s][2] = cur[s][0].z; xv[s][3] = cur[s][0].w;
             xv[s][4] = cur[s][1].x; xv[s][5] = cur[s][1].y; xv[s][6] = cur[s][1].z; xv[s][7] = cur[s][1].w;
             split8(xv[s], Bh[s], Bm[s]);
             if (later) {
-                tp[(2 * s) * 64] = Bh[s];
-                tp[(2 * s + 1) * 64] = Bm[s];
+                tp[4 * s] = Bh[s];
+                tp[4 * s + 1] = Bm[s];
             }
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -786,7 +805,6 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
             }
         }
         xn += __shfl_xor(xn, 32);
-        if (later && valid && h == 0) a.xn[(size_t)n0 + p] = xn;
 
         float best, second;
         int bi;
@@ -834,11 +852,17 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
             }
         }
         if (__any(valid && !certain)) any |= 2;
-        if (a.use_bounds && later) {
-            const float own = (valid && certain) ? slack_of(best, second, xn, E) : INFINITY;
-            if (valid && certain && h == 0) lim[p] = tile_limit(0.f, own);
-            const float sl = half_wave_min_f(own);
-            if (lane == 0) thr[tile] = tile_limit(0.f, sl);
+        if (later) {
+            // state of the candidate for the later steps (no cluster yet for the ones left
+            // to the exact pass, which then sets it)
+            const float own = (valid && certain && a.use_bounds) ? slack_of(best, second, xn, E) : INFINITY;
+            if (valid && h == 0)
+                lim[p] = make_float2(certain ? pack_limit(a.use_bounds ? tile_limit(0.f, own) : 0.f, bi)
+                                             : pack_limit(0.f, -1), xn);
+            if (a.use_bounds) {
+                const float sl = half_wave_min_f(own);
+                if (lane == 0) thr[tile] = limit_of(tile_limit(0.f, sl));
+            }
         }
     }
     am_out = am;
@@ -851,7 +875,7 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
 // lane sums (x_d - c_d)^2 over d in index order in fp64 with separate multiply
 // and add; the wave then reduces to the minimum, lowest index on ties.
 __device__ __forceinline__ void refine(const ClusterArgs& a, const float* __restrict__ Xg, int n0,
-                                       int ng, int K, int D, int DP, const float* cent) {
+                                       int ng, int K, int D, int DP, const float* cent, bool mark) {
     const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
     for (int base = wid * kWave; base < ng; base += kThreads) {
         const int p = base + lane;
@@ -890,7 +914,8 @@ __device__ __forceinline__ void refine(const ClusterArgs& a, const float* __rest
                 const int oj = __shfl_xor(bj, o);
                 if (od < bd || (od == bd && oj < bj)) { bd = od; bj = oj; }
             }
-            if (lane == 0) a.a_new[(size_t)n0 + base + b] = bj < K ? bj : 0;
+            // (mark: only the entries decided here are fresh, and `update` must tell them apart)
+            if (lane == 0) a.a_new[(size_t)n0 + base + b] = (bj < K ? bj : 0) | (mark ? kRefinedBit : 0);
         }
     }
 }
@@ -910,7 +935,7 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
                                              int n0, int n, const unsigned short* flist, int K, int D, int DP,
                                              int SP, const float* cent, int fsh,
                                              long long* sums, int* cnt, unsigned char* dirty, float* thr,
-                                             float* __restrict__ lim, float drift) {
+                                             float2* __restrict__ lim, float drift) {
     const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
     const int lc = lane < D ? lane : 0;
     const float eps = 2.f * (float)(D + 2) * 5.9604644775390625e-08f;
@@ -1006,15 +1031,16 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
             ub = (float)sqrt(bd) * 1.0000005f;
             lbd = (float)sqrt(sd) * 0.9999995f;
         }
-        if (a.use_bounds && lane == 0) {
+        bj = bj < K ? bj : 0;
+        if (lane == 0) {
             // the slack is the difference of the bounds, rounded down; limits are
             // non-negative floats, which order like their bit patterns
             const float sl = fmaxf((lbd - ub) * 0.9999995f, 0.f);
-            const float L = tile_limit(drift, sl);
-            lim[p] = L;
-            atomicMin(reinterpret_cast<unsigned*>(&thr[p >> 5]), __float_as_uint(L));
+            const float L = a.use_bounds ? limit_of(tile_limit(drift, sl)) : 0.f;
+            lim[p].x = pack_limit(L, bj);
+            if (a.use_bounds) atomicMin(reinterpret_cast<unsigned*>(&thr[p >> 5]), __float_as_uint(L));
+            a.a_new[(size_t)n0 + p] = bj;          // no longer waiting for the exact pass
         }
-        bj = bj < K ? bj : 0;
         old = (old >= 0 && old < K) ? old : -1;
         if (bj != old) {
             any = 1;
@@ -1041,7 +1067,7 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
 // wave saw any change.
 __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restrict__ Xg, int n0,
                                       int ng, int K, int D, int SP, bool first, int fsh,
-                                      long long* sums, int* cnt, unsigned char* dirty) {
+                                      long long* sums, int* cnt, unsigned char* dirty, bool marked) {
     const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
     int any = 0;
     for (int base = wid * kWave; base < ng; base += kThreads) {
@@ -1050,10 +1076,17 @@ __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restr
         bool chg = false;
         if (p < ng) {
             na = a.a_new[(size_t)n0 + p];
+            // (after the matrix-core scorer only the entries the scan has just decided count;
+            // the others may date from earlier steps)
+            const bool fresh = !marked || (na >= 0 && (na & kRefinedBit));
+            if (marked && fresh) {
+                na &= ~kRefinedBit;
+                a.a_new[(size_t)n0 + p] = na;
+            }
             na = (na >= 0 && na < K) ? na : 0;
             oa = first ? -1 : a.assign[(size_t)n0 + p];
             oa = (oa >= 0 && oa < K) ? oa : -1;
-            chg = na != oa;
+            chg = fresh && na != oa;
             if (chg) a.assign[(size_t)n0 + p] = na;
         }
         unsigned long long mask = __ballot(chg);
@@ -1141,7 +1174,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     float* delta = reinterpret_cast<float*>(smem + L.delta);         // [Kmax]
     float* thr = reinterpret_cast<float*>(smem + L.thr);             // [tiles]
     unsigned short* queue = reinterpret_cast<unsigned short*>(smem + L.queue);   // [kWaves][kQueue]
-    float* lim = a.lim + n0;                                         // [N_g], global
+    float2* lim = a.lim + n0;                                        // [N_g], global
     int* nflag = reinterpret_cast<int*>(smem + 64);                  // behind the two reduction slots
     bf16x8* aop = reinterpret_cast<bf16x8*>(smem + L.aop);
 
@@ -1292,15 +1325,21 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
             } else {
                 // the list overflowed (or the vector-ALU scorer ran): scan every candidate;
                 // no slack is known for the refined ones, so every tile is scored next time
-                if (MT > 0 && a.use_bounds) {
-                    for (int t = tid; t < ((ng + 31) >> 5); t += kThreads) thr[t] = 0.f;
-                    for (int q = tid; q < ng; q += kThreads) lim[q] = 0.f;
-                }
-                refine(a, Xg, n0, ng, K, D, DP, cent);
+                refine(a, Xg, n0, ng, K, D, DP, cent, MT > 0);
                 __syncthreads();
                 // after the matrix-core scorer only refined candidates are left to move,
                 // and it has already recorded an assignment for every other candidate
-                moved = update(a, Xg, n0, ng, K, D, SP, first && MT == 0, fsh, sums, cnt, dw);
+                moved = update(a, Xg, n0, ng, K, D, SP, first && MT == 0, fsh, sums, cnt, dw, MT > 0);
+                if (MT > 0 && a.iters > 1) {
+                    // every candidate's state: its cluster as it stands now, limit 0
+                    __syncthreads();
+                    for (int q = tid; q < ng; q += kThreads) {
+                        const int c = a.assign[(size_t)n0 + q];
+                        lim[q].x = pack_limit(0.f, (c >= 0 && c < K) ? c : -1);
+                    }
+                    if (a.use_bounds)
+                        for (int t = tid; t < ((ng + 31) >> 5); t += kThreads) thr[t] = 0.f;
+                }
             }
             st |= block_or_i(moved, red, phase);
             // every thread has read the counter before that barrier, and the barriers of
@@ -1421,7 +1460,7 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     a.use_bounds = c.scorer != 2;
     a.guard = c.guard;
     a.mixed = c.mixed;
-    a.lim = c.lim;
+    a.lim = reinterpret_cast<float2*>(c.lim);
 
     const int ds = (b.D + 15) / 16;   // 1..4 K-steps of 16 features
     a.Nmax = one_wg_nmax(b);

@@ -8,6 +8,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kFlagBit = (int)0x80000000u;
+constexpr int kRefinedBit = 0x40000000;     // proposal decided by the scan over all candidates, not yet applied
 constexpr float kBig = 1.0e30f;    // score of a centroid row that does not exist
 
 // Fixed-point image of one feature value: x * 2^sh as a 64-bit integer, from

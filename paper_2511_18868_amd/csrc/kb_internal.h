@@ -35,9 +35,11 @@ struct WsLayout {
     size_t order;   // int32 [G]     searches sorted by decreasing work, for longest-first scheduling
     size_t misc;    // int32 [128]   histogram / cursors of the ordering kernel
     size_t tile_off;// int32 [G+1]   prefix sum of ceil(N_g / 32): first 32-candidate tile of each search
-    size_t xn;      // float [N]     |x_k|^2 of every candidate
-    size_t split;   // bf16          feature rows split into bf16 (hi, mid) pieces, in matrix-core
-                    //               operand order: [tile][16-feature step][hi|mid][lane][8]
+    size_t xn;      // float [N]     |x_k|^2 of every candidate (multi-workgroup path)
+    size_t split;   // bf16          feature rows split into bf16 (hi, mid) pieces, 4 * Dpad bytes per
+                    //               candidate: [candidate][16-feature step][half][hi|mid][8] on the
+                    //               one-workgroup path, [tile][16-feature step][hi|mid][lane][8] (the
+                    //               matrix cores' operand order) on the multi-workgroup path
     size_t max_tiles;   // capacity of `split` in tiles (not an offset)
     bool use_big;
     BigWs big;
@@ -81,7 +83,7 @@ struct ClusterCall {
     float* xn;
     void* split;
     int64_t max_tiles;
-    float* lim;               // float [N] scratch of the fused kernel (every candidate's drift limit)
+    float* lim;               // float2 [N] scratch of the fused kernel (every candidate's drift limit | cluster, |x|^2)
     int guard;                // 1: searches with N_g < 2 K_g keep their clustering untouched
     int mixed;                // 1: the batch may hold searches of both paths; each kernel skips the other's
     int scorer;               // kb_params::scorer: 0 default, 1 vector ALU only, 2 matrix cores without bounds
