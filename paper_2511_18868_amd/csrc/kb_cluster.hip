@@ -261,8 +261,7 @@ __device__ __forceinline__ void score_valu(const ClusterArgs& a, const float* __
 // only (with the pieces of 32 neighbours interleaved, as the matrix cores read
 // them, a tile in which a few candidates are at risk still pulled in most of its
 // cache lines: 9.2 GB of HBM traffic on the largest benchmark against 7.1 GB).
-// Everything that follows a change of a centroid, 16 lanes per row (lane l owns
-// features 4l .. 4l+3): the new centroid (fixed-point sum / 2^shift) / count in
+// Everything that follows a change of a centroid, four lanes per row: the new centroid (fixed-point sum / 2^shift) / count in
 // fp64, rounded once to fp32; how far it moved (rounded up); |c_j|^2 in fp64; and
 // the matrix cores' operands -2 c_j split into bf16 (hi, mid), stored in LDS in
 // operand order [tile of 32 rows][16-feature step][hi|mid][lane] x 16 bytes so the
@@ -284,42 +283,59 @@ __device__ __forceinline__ float mean_f32(double t, double c, double rc) {
     return (float)q;
 }
 
+// (Four lanes per row, lane q owning the 4-feature chunks q, q + 4, ...: all 64 rows of a
+// search are renewed in one pass, so a step pays this dependent chain - reciprocal,
+// means, fp64 sums across the four lanes, square root, operand conversion - once and
+// not once per group of sixteen rows.)
+__device__ __forceinline__ double quad_sum_d(double v) {
+    v += dpp_d<0xB1>(v);
+    v += dpp_d<0x4E>(v);
+    return v;
+}
+
 template <int DS, bool OPERANDS>
 __device__ __forceinline__ float renew_rows(float* cent, float* cn, bf16x8* aop, const long long* sums,
                                             const int* cnt, unsigned char* dirty, float* delta, int K, int D,
                                             int SP, double inv, bool init, bool need_scores) {
     constexpr int DP = 16 * DS + 4;
-    const int tid = threadIdx.x, l16 = tid & 15, d0 = 4 * (tid & 15);
-    const bool infeat = d0 < 16 * DS;                 // this lane's features exist in the padded row
+    const int tid = threadIdx.x, q = tid & 3;
     const int rows = init && OPERANDS ? ((K + 31) & ~31) : K;
     float cm = 0.f;
-    for (int j0 = 0; j0 < rows; j0 += kThreads / 16) {
-        const int j = j0 + (tid >> 4);
+    for (int j0 = 0; j0 < rows; j0 += kThreads / 4) {
+        const int j = j0 + (tid >> 2);
         const bool real = j < K;
         const int c = real ? cnt[j] : 0;
         const bool renew = !init && real && c > 0 && dirty[j] != 0;
         const bool fresh = renew || (init && j < rows);
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (real && infeat) v = *reinterpret_cast<const float4*>(cent + (size_t)j * DP + d0);
+        float4 v[DS];
+#pragma unroll
+        for (int i = 0; i < DS; ++i) {
+            v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (real) v[i] = *reinterpret_cast<const float4*>(cent + (size_t)j * DP + 4 * (q + 4 * i));
+        }
         double mv = 0.0;
-        if (renew && infeat) {
-            float* vp = &v.x;
+        if (renew) {
             const double cd = (double)c, rc = 1.0 / cd;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (d0 + i < D) {
-                    const float cnew = mean_f32((double)sums[(size_t)j * SP + d0 + i] * inv, cd, rc);
-                    const double df = (double)cnew - (double)vp[i];
-                    mv += df * df;
-                    vp[i] = cnew;
+            for (int i = 0; i < DS; ++i) {
+                const int d0 = 4 * (q + 4 * i);
+                float* vp = &v[i].x;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (d0 + e < D) {
+                        const float cnew = mean_f32((double)sums[(size_t)j * SP + d0 + e] * inv, cd, rc);
+                        const double df = (double)cnew - (double)vp[e];
+                        mv += df * df;
+                        vp[e] = cnew;
+                    }
                 }
+                *reinterpret_cast<float4*>(cent + (size_t)j * DP + d0) = v[i];
             }
-            *reinterpret_cast<float4*>(cent + (size_t)j * DP + d0) = v;
         }
-        // uniform over the 16 lanes of a row from here on
+        // uniform over the four lanes of a row from here on
         if (!init) {
-            mv = row_sum_d(mv);
-            if (real && l16 == 0) {
+            mv = quad_sum_d(mv);
+            if (real && q == 0) {
                 // rounded up: the fp32 square root is within 2^-23 of the true one
                 delta[j] = !renew ? 0.f
                            : mv < 1.0e-30 ? (float)sqrt(mv) * 1.0000005f
@@ -330,28 +346,34 @@ __device__ __forceinline__ float renew_rows(float* cent, float* cn, bf16x8* aop,
         float f = 0.f;
         if (need_scores) {
             if (fresh) {
-                double sq = (double)v.x * (double)v.x + (double)v.y * (double)v.y +
-                            (double)v.z * (double)v.z + (double)v.w * (double)v.w;
-                sq = row_sum_d(sq);
+                double sq = 0.0;
+#pragma unroll
+                for (int i = 0; i < DS; ++i)
+                    sq += (double)v[i].x * (double)v[i].x + (double)v[i].y * (double)v[i].y +
+                          (double)v[i].z * (double)v[i].z + (double)v[i].w * (double)v[i].w;
+                sq = quad_sum_d(sq);
                 f = (float)sq;
-                if (real && l16 == 0) cn[j] = f;
+                if (real && q == 0) cn[j] = f;
                 if constexpr (OPERANDS) {
-                    if (infeat) {
-                        // features d0 .. d0+3 are half of the 8-feature piece d0 / 8
-                        typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-                        const float w[4] = {-2.f * v.x, -2.f * v.y, -2.f * v.z, -2.f * v.w};
+                    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+                    const int mt = j >> 5;
+#pragma unroll
+                    for (int i = 0; i < DS; ++i) {
+                        // chunk ch holds features 4 ch .. 4 ch + 3: half of the 8-feature piece ch / 2
+                        const int ch = q + 4 * i;
+                        const float w[4] = {-2.f * v[i].x, -2.f * v[i].y, -2.f * v[i].z, -2.f * v[i].w};
                         bf16x4 hi, mid;
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const __bf16 hb = (__bf16)w[i];
-                            hi[i] = hb;
-                            mid[i] = (__bf16)(w[i] - (float)hb);
+                        for (int e = 0; e < 4; ++e) {
+                            const __bf16 hb = (__bf16)w[e];
+                            hi[e] = hb;
+                            mid[e] = (__bf16)(w[e] - (float)hb);
                         }
-                        const int piece = l16 >> 1, st = piece >> 1, hh = piece & 1;
-                        const int mt = j >> 5, ln = (j & 31) + 32 * hh;
-                        bf16x4* e = reinterpret_cast<bf16x4*>(aop + ((mt * DS + st) * 2 + 0) * 64 + ln) + (l16 & 1);
-                        e[0] = hi;
-                        e[64 * 2] = mid;            // the mid block follows 64 entries of 16 bytes later
+                        const int piece = ch >> 1, st = piece >> 1, hh = piece & 1;
+                        const int ln = (j & 31) + 32 * hh;
+                        bf16x4* e2 = reinterpret_cast<bf16x4*>(aop + ((mt * DS + st) * 2 + 0) * 64 + ln) + (ch & 1);
+                        e2[0] = hi;
+                        e2[64 * 2] = mid;           // the mid block follows 64 entries of 16 bytes later
                     }
                 }
             } else if (real) {
