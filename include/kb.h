@@ -44,10 +44,12 @@
  * and keeps no state between calls (kb_ucb_select_static aside, which says what
  * it keeps); all scratch comes from the caller's workspace `ws` (device,
  * >= kb_workspace_bytes(), 256-byte aligned, contents undefined before and
- * after a call).  The workspace holds, besides small tables, a bf16 copy of the
- * features, |x|^2, a proposal and an fp64 distance per candidate: about
- * (4*Dpad + 16) * N bytes with Dpad = D rounded up to 16.  Two calls may run concurrently only on
- * different workspaces.
+ * after a call).  The workspace holds, besides small tables, a proposal and an
+ * 8-byte entry (drift limit, cluster, |x|^2; at other times an fp64 distance) per
+ * candidate: about 12 * N bytes; a batch with a search of more than 64 clusters
+ * or 65536 candidates adds a bf16 copy of the features and per-candidate lists,
+ * about (4*Dpad + 28) * N bytes more with Dpad = D rounded up to 16.  Two calls
+ * may run concurrently only on different workspaces.
  * Arrays are dense, row-major, with no padding.  X, cent*, flops, bytes, bound,
  * visits and rsum must be 16-byte aligned.
  *

@@ -14,13 +14,18 @@ WsLayout ws_layout(const kb_batch& b) {
     w.order = off;  off += align256(sizeof(int32_t) * (size_t)b.G);
     w.misc = off;   off += align256(sizeof(int32_t) * 128);
     w.tile_off = off; off += align256(sizeof(int32_t) * ((size_t)b.G + 1));
-    w.xn = off;     off += align256(sizeof(float) * (size_t)(b.N > 0 ? b.N : 1));
     // every search rounds its candidates up to whole tiles of 32
     w.max_tiles = (size_t)(b.N / 32) + (size_t)b.G;
-    const size_t steps = (size_t)(b.D + 15) / 16;
-    w.split = off;  off += align256(w.max_tiles * steps * 2 * 64 * 16);
     w.use_big = cluster_uses_big(b);
-    if (w.use_big) { w.big = big_ws_layout(b, off); off = w.big.end; }
+    w.xn = w.split = off;
+    if (w.use_big) {
+        // only the multi-workgroup clustering path keeps |x|^2 and a bf16 copy of the features
+        const size_t steps = (size_t)(b.D + 15) / 16;
+        w.xn = off;     off += align256(sizeof(float) * (size_t)(b.N > 0 ? b.N : 1));
+        w.split = off;  off += align256(w.max_tiles * steps * 2 * 64 * 16);
+        w.big = big_ws_layout(b, off);
+        off = w.big.end;
+    }
     w.ucb_chunked = b.Nmax > 16384;
     w.ucb_R = w.ucb_N = w.ucb_kmin = w.ucb_nalive = 0;
     if (w.ucb_chunked) {

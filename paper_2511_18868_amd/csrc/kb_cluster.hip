@@ -3,9 +3,9 @@
 // of its Lloyd steps, so the search's rows stay in L2 / Infinity Cache between
 // steps and the centroids never leave LDS.
 //
-// Once per call (in its first step) the feature rows are split into bf16 (hi, mid)
-// pieces, candidate by candidate, into a workspace copy the later steps score from;
-// |x|^2, the cluster and the drift limit of every candidate share a second array.
+// Every scoring splits the fp32 feature rows it fetches into bf16 (hi, mid) pieces
+// on the fly; |x|^2, the cluster and the drift limit of every candidate share one
+// workspace array of 8 bytes per candidate.
 //
 // One step:
 //
@@ -20,7 +20,8 @@
 //              If second - best > 2E the winner is certain; otherwise the
 //              candidate is listed for exact re-evaluation.  Two scorers:
 //              matrix cores (bf16 x 3 split products, fp32 accumulate) for
-//              K <= 64, a vector-ALU fp32 FMA chain otherwise.
+//              K <= 64 and D a multiple of 4, a vector-ALU fp32 FMA chain
+//              otherwise.
 //   R  refine  listed candidates get their squared distances in fp64, direct
 //              difference form, summed over the features in index order with
 //              separate multiply and add - exactly the plain definition - and
@@ -57,10 +58,6 @@ struct ClusterArgs {
     float* objective;
     int32_t* a_new;
     const int32_t* order;
-    const int32_t* tile_off;
-    float* xn;
-    bf16x8* split;
-    int64_t max_tiles;
     int use_bounds;
     int guard;         // leave searches with N_g < 2 K_g as they are (re-clustering rule of Alg. 1)
     int mixed;         // leave searches of the multi-workgroup path (K_g > 64 or N_g > 65536) alone
@@ -253,14 +250,13 @@ __device__ __forceinline__ void score_valu(const ClusterArgs& a, const float* __
 // a wave walks over tiles of 32 candidates.  Candidates the scorer is certain
 // about and whose cluster changed are moved between the fixed-point sums right
 // here (their fp32 row is read again; rare after the first steps).
-// The feature rows are split once per call (in the first step) into a workspace
-// copy laid out candidate by candidate - [candidate][K-step][half][hi|mid] x 16
-// bytes, the 64 * DS bytes of a candidate contiguous - so a later step fetches a
-// candidate's operands as 16-byte pieces with no conversion work, and a packed
-// tile of candidates from all over the search moves the bytes of those candidates
-// only (with the pieces of 32 neighbours interleaved, as the matrix cores read
-// them, a tile in which a few candidates are at risk still pulled in most of its
-// cache lines: 9.2 GB of HBM traffic on the largest benchmark against 7.1 GB).
+// No bf16 copy of the features is kept: a later step fetches a candidate's fp32 row
+// again (its D * 4 bytes are contiguous, so a packed tile of candidates from all over
+// the search moves the bytes of those candidates only) and splits it in registers.
+// An operand-ordered copy - the pieces of 32 neighbours interleaved, as the matrix
+// cores read them - made a tile in which a few candidates are at risk pull in most of
+// its cache lines (9.2 GB of HBM traffic on the largest benchmark against 7.1 GB for a
+// candidate-major copy), and writing any copy costs more than converting again.
 // Everything that follows a change of a centroid, four lanes per row: the new centroid (fixed-point sum / 2^shift) / count in
 // fp64, rounded once to fp32; how far it moved (rounded up); |c_j|^2 in fp64; and
 // the matrix cores' operands -2 c_j split into bf16 (hi, mid), stored in LDS in
@@ -557,12 +553,12 @@ __device__ __forceinline__ void tile_scores(const bf16x8 (&Bh)[DS], const bf16x8
 // wave walks its tiles whose number the drift has reached, two at a time (one
 // per half-wave), reads their candidates' limits, and appends those the drift has
 // reached to a small queue in LDS; whenever 32 are waiting they are scored as one
-// tile of the matrix instruction, each lane fetching the operands of its own
-// candidate from the split copy.  A tile in which a third of the candidates are
-// at risk thus costs a third of a scoring instead of a whole one.
+// tile of the matrix instruction, each lane fetching its own candidate's fp32 row
+// (16-byte pieces; D is a multiple of 4 here) and splitting it into the bf16
+// operands in registers.  A tile in which a third of the candidates are at risk
+// thus costs a third of a scoring instead of a whole one.
 template <int DS, int MT>
 __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* __restrict__ Xg,
-                                            const bf16x8* __restrict__ sp,
                                             int n0, int ng, int K, int D, int DP, int SP,
                                             const float* cent, const float* cn, float cnmax,
                                             int fsh, long long* sums, int* cnt,
@@ -616,13 +612,24 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
         const int p = q[(head + (valid ? m : 0)) & (kQueue - 1)];
         bf16x8 Bh[DS], Bm[DS];
         {
-            // (candidate-major copy: the 64 * DS bytes of a candidate are contiguous, so a
-            // packed chunk fetches the bytes of its own candidates and no one else's)
-            const bf16x8* tp = sp + (size_t)p * (DS * 4) + 2 * h;
+            // The operands are split from the candidate's fp32 row as it is fetched (all
+            // requests first): a row is contiguous, so a packed chunk moves the bytes of
+            // its own candidates only, and no bf16 copy of the features has to be written
+            // and kept (it cost more HBM traffic than the conversions cost issue slots).
+            const float* xr = Xg + (size_t)p * D;
+            float4 r0[DS], r1[DS];
 #pragma unroll
             for (int s = 0; s < DS; ++s) {
-                Bh[s] = tp[4 * s];
-                Bm[s] = tp[4 * s + 1];
+                const int d0 = 16 * s + 8 * h;
+                r0[s] = make_float4(0.f, 0.f, 0.f, 0.f);
+                r1[s] = r0[s];
+                if (d0 < D) r0[s] = *reinterpret_cast<const float4*>(xr + d0);
+                if (d0 + 4 < D) r1[s] = *reinterpret_cast<const float4*>(xr + d0 + 4);
+            }
+#pragma unroll
+            for (int s = 0; s < DS; ++s) {
+                const float xv[8] = {r0[s].x, r0[s].y, r0[s].z, r0[s].w, r1[s].x, r1[s].y, r1[s].z, r1[s].w};
+                split8(xv, Bh[s], Bm[s]);
             }
         }
         const float2 state = lim[p];
@@ -739,16 +746,15 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
     return any;   // bit 0: some candidate moved, bit 1: some candidate needs the exact pass
 }
 
-// First step of a call on the matrix-core path.  One pass over the fp32 rows
-// does everything the later steps get from the workspace: the rows are split
-// into bf16 (hi, mid) operands (written to the workspace for the steps that
-// follow, with |x|^2), scored from the registers that hold them, and - every
-// candidate joins a cluster in the first step - added to the fixed-point sums
-// from the same registers.  Returns max |x| over the rows this thread saw in
+// First step of a call on the matrix-core path.  One pass over the fp32 rows:
+// they are split into bf16 (hi, mid) operands, scored from the registers that
+// hold them, and - every candidate joins a cluster in the first step - added to
+// the fixed-point sums from the same registers; |x|^2 and the drift limit of every
+// candidate go to the workspace for the steps that follow.  Returns max |x| over the rows this thread saw in
 // `am_out`, which the caller checks against the estimate the scale was taken from.
 template <int DS, int MT>
 __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __restrict__ Xg,
-                                           bf16x8* __restrict__ spw, int n0, int ng, int K, int D,
+                                           int n0, int ng, int K, int D,
                                            int SP, const float* cn, float cnmax, int fsh,
                                            long long* sums, int* cnt, int* nflag, unsigned short* flist,
                                            const bf16x8* aop, unsigned char* dirty, float* thr,
@@ -757,13 +763,13 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
     const int m = lane & 31, h = lane >> 5;
     const int mtiles = (K + 31) >> 5;
     const float kappa = mfma_kappa(DS);
-    const bool vec = (D & 3) == 0;
     const int ntiles = (ng + 31) >> 5;
-    // the split copy, |x|^2 and the limits serve the steps that follow: a call of one
-    // step (kb_cluster_step) stores none of them
+    // |x|^2 and the limits serve the steps that follow: a call of one step
+    // (kb_cluster_step) stores none of them
     const bool later = a.iters > 1;
 
-    // this lane's 8 features of every 16-feature step of row `tile * 32 + m`
+    // this lane's 8 features of every 16-feature step of row `tile * 32 + m`, in
+    // 16-byte pieces (D is a multiple of 4 here)
     auto load_rows = [&](int tile, float4 (&r)[DS][2]) {
         const int p = tile * 32 + m;
         const bool valid = p < ng;
@@ -782,19 +788,8 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
             const int d0 = 16 * s + 8 * h;
             r[s][0] = make_float4(0.f, 0.f, 0.f, 0.f);
             r[s][1] = r[s][0];
-            if (vec) {
-                if (valid && d0 < D) r[s][0] = *reinterpret_cast<const float4*>(xr + d0);
-                if (valid && d0 + 4 < D) r[s][1] = *reinterpret_cast<const float4*>(xr + d0 + 4);
-            } else if (valid) {
-                if (d0 + 0 < D) r[s][0].x = xr[d0 + 0];
-                if (d0 + 1 < D) r[s][0].y = xr[d0 + 1];
-                if (d0 + 2 < D) r[s][0].z = xr[d0 + 2];
-                if (d0 + 3 < D) r[s][0].w = xr[d0 + 3];
-                if (d0 + 4 < D) r[s][1].x = xr[d0 + 4];
-                if (d0 + 5 < D) r[s][1].y = xr[d0 + 5];
-                if (d0 + 6 < D) r[s][1].z = xr[d0 + 6];
-                if (d0 + 7 < D) r[s][1].w = xr[d0 + 7];
-            }
+            if (valid && d0 < D) r[s][0] = *reinterpret_cast<const float4*>(xr + d0);
+            if (valid && d0 + 4 < D) r[s][1] = *reinterpret_cast<const float4*>(xr + d0 + 4);
         }
     };
 
@@ -809,16 +804,11 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
         float xv[DS][8];
         bf16x8 Bh[DS], Bm[DS];
         float xn = 0.f;
-        bf16x8* tp = spw + (size_t)p * (DS * 4) + 2 * h;
 #pragma unroll
         for (int s = 0; s < DS; ++s) {
             xv[s][0] = cur[s][0].x; xv[s][1] = cur[s][0].y; xv[s][2] = cur[s][0].z; xv[s][3] = cur[s][0].w;
             xv[s][4] = cur[s][1].x; xv[s][5] = cur[s][1].y; xv[s][6] = cur[s][1].z; xv[s][7] = cur[s][1].w;
             split8(xv[s], Bh[s], Bm[s]);
-            if (later) {
-                tp[4 * s] = Bh[s];
-                tp[4 * s + 1] = Bm[s];
-            }
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 xn = fmaf(xv[s][i], xv[s][i], xn);
@@ -1203,21 +1193,16 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     const float* Xg = a.X + (size_t)n0 * D;
 
     // requested together with the initial centroids so that the latencies overlap:
-    // the search's place in the split workspace, and (matrix-core path) the largest
-    // |x| among the first rows, from which the fixed-point scale is estimated
-    int64_t tb = 0;
+    // (matrix-core path) the largest |x| among the first rows, from which the
+    // fixed-point scale is estimated
     float am = 0.f;
     if constexpr (MT > 0) {
-        tb = a.tile_off[g];
+        // (D is a multiple of 4 on this path: rows are 16-byte aligned)
         const int srows = ng < 64 ? ng : 64;
-        if ((D & 3) == 0) {
-            const int quads = srows * (D >> 2);
-            for (int i = tid; i < quads; i += kThreads) {
-                const float4 v = reinterpret_cast<const float4*>(Xg)[i];
-                am = fmaxf(fmaxf(am, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
-            }
-        } else {
-            for (int i = tid; i < srows * D; i += kThreads) am = fmaxf(am, fabsf(Xg[i]));
+        const int quads = srows * (D >> 2);
+        for (int i = tid; i < quads; i += kThreads) {
+            const float4 v = reinterpret_cast<const float4*>(Xg)[i];
+            am = fmaxf(fmaxf(am, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
         }
     }
     for (int idx = tid; idx < K * DP; idx += kThreads) {
@@ -1249,12 +1234,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     // the true maximum, and in the rare case that the estimate's exponent class
     // was too small the sums are rebuilt with the right scale.
     double tsq = 0.0;           // sum of x^2 over the search (exact products, fp64 sums), for the objective
-    bf16x8* spw = nullptr;
-    if constexpr (MT > 0) {
-        const int ntiles = (ng + 31) >> 5;
-        if (tb < 0 || tb + ntiles > a.max_tiles) return;   // inconsistent offsets: touch nothing
-        spw = a.split + (size_t)tb * (DS * 2 * 64);
-    } else {
+    if constexpr (MT == 0) {
         const size_t total = (size_t)ng * D;
         if ((D & 3) == 0) {
             const size_t quads = total >> 2;
@@ -1274,7 +1254,6 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
             }
         }
     }
-    const bf16x8* sp = spw;
     int phase = 0;
     am = block_max_f(am, red, phase);
     if constexpr (MT == 0) tsq = block_sum_d(tsq, red, phase);
@@ -1305,7 +1284,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
         if constexpr (MT > 0) {
             if (first) {
                 float am_seen;
-                st = score_first<DS, MT>(a, Xg, spw, n0, ng, K, D, SP, cn, cm, fsh, sums, cnt, nflag,
+                st = score_first<DS, MT>(a, Xg, n0, ng, K, D, SP, cn, cm, fsh, sums, cnt, nflag,
                                          flist, aop, dw, thr, lim, am_seen, tsq);
                 am_seen = block_max_f(am_seen, red, phase);
                 tsq = block_sum_d(tsq, red, phase);
@@ -1331,7 +1310,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
                     __syncthreads();
                 }
             } else
-            st = score_packed<DS, MT>(a, Xg, sp, n0, ng, K, D, DP, SP, cent, cn, cm, fsh, sums, cnt,
+            st = score_packed<DS, MT>(a, Xg, n0, ng, K, D, DP, SP, cent, cn, cm, fsh, sums, cnt,
                                       nflag, flist, aop, dw, thr, lim, queue, drift);
         } else {
             score_valu<4 * DS>(a, Xg, n0, ng, K, D, DP, cent, cn, cm);
@@ -1477,8 +1456,6 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     a.seg_off = b.seg_off; a.koff = b.koff; a.X = c.X; a.cent_init = c.cent_init;
     a.iters = c.iters; a.early_exit = 0; a.assign = c.assign; a.cent_out = c.cent_out;
     a.counts = c.counts; a.objective = c.objective; a.a_new = c.a_new; a.order = c.order;
-    a.tile_off = c.tile_off; a.xn = c.xn; a.split = reinterpret_cast<bf16x8*>(c.split);
-    a.max_tiles = c.max_tiles;
     a.use_bounds = c.scorer != 2;
     a.guard = c.guard;
     a.mixed = c.mixed;
@@ -1490,6 +1467,9 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     if (lds > kMaxLds) return hipErrorInvalidValue;
     int mt = a.Kmax <= 32 ? 1 : (a.Kmax <= 64 ? 2 : 0);
     if (c.scorer == 1) mt = 0;
+    // (the matrix-core kernels fetch rows in 16-byte pieces: feature counts that are not
+    // a multiple of 4 take the vector-ALU kernels, whose results are the same)
+    if ((b.D & 3) != 0) mt = 0;
     const dim3 grid((unsigned)b.G), block(kThreads);
 #define KB_LAUNCH(DS_, MT_)                                                                     \
     do {                                                                                        \
