@@ -213,6 +213,14 @@ def main():
         "model_bytes_every_step": model_bytes,
         "model_GBs": round(model_bytes / (cl_mean * 1e-3) / 1e9, 1),
     }
+    # scorer mode 2 is the streaming Lloyd iteration of the byte model: every candidate
+    # is read in every step
+    if rec and rec.get("bytes_per_launch_every_candidate") and "matrix_cores_every_candidate" in modes:
+        t2, ms2 = rec["bytes_per_launch_every_candidate"], modes["matrix_cores_every_candidate"]
+        roofline["every_candidate_mode"] = {
+            "ms": ms2, "traffic": t2, "achieved": round(t2 / (ms2 * 1e-3) / 1e9, 1),
+            "frac": round(t2 / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "frac_of_measured_copy_rate": round(t2 / (ms2 * 1e-3) / 1e9 / copy_GBs, 4)}
     # distance contraction: 2*N_g*K_g*D flops per step; the matrix-core scorer issues
     # three bf16 products per term
     nk = float(np.sum(np.diff(b.seg_off).astype(np.float64) * np.diff(b.koff)))
