@@ -136,9 +136,13 @@ static kb_status do_cluster(const kb_batch* b, const float* X, const float* cent
     WsLayout w = ws_layout(*b);
     char* base = (char*)ws;
     int32_t* order = (int32_t*)(base + w.order);
-    hipError_t e = launch_order(*b, order, (int32_t*)(base + w.tile_off),
-                                w.use_big ? (int32_t*)(base + w.big.chunk_off) : nullptr, st);
-    if (e != hipSuccess) return KB_EDEVICE;
+    // (a lone search on the one-workgroup path needs neither a scheduling order nor
+    // tile offsets: one launch less)
+    if (b->G > 1 || w.use_big) {
+        hipError_t e = launch_order(*b, order, (int32_t*)(base + w.tile_off),
+                                    w.use_big ? (int32_t*)(base + w.big.chunk_off) : nullptr, st);
+        if (e != hipSuccess) return KB_EDEVICE;
+    }
     ClusterCall c;
     c.X = X; c.cent_init = cent_init; c.iters = iters; c.assign = assign;
     c.cent_out = cent; c.counts = counts; c.objective = objective;
@@ -206,7 +210,7 @@ static kb_status do_ucb(const kb_batch* b, const kb_params* p, const int32_t* as
     kb_status s = check_ucb(b, p, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel,
                             optional_mask_inputs);
     if (s != KB_OK) return s;
-    if (!have_order) {
+    if (!have_order && b->G > 1) {
         hipError_t e = launch_order(*b, u.order, u.tile_off, nullptr, st);
         if (e != hipSuccess) return KB_EDEVICE;
     }

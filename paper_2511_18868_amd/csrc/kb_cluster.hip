@@ -65,8 +65,12 @@ struct ClusterArgs {
                        //     slack) with its cluster + 1 in the 7 lowest bits, .y its |x|^2
 };
 
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / kWave;
+// Threads per workgroup (a template parameter NT of the kernel and of the device
+// functions that stride by it): 256, three workgroups per compute unit, is the
+// shape of large batches; a batch with fewer searches than compute units runs 768,
+// so that a lone search still fills the unit it is on.
+constexpr int kThreadsNarrow = 256, kThreadsWide = 768;
+constexpr int kWideMaxG = 256;     // most searches of a batch that takes the wide shape
 constexpr int kFlagCap = 256;      // LDS list of candidates waiting for the exact pass
 constexpr int kMoverBatch = 8;     // movers whose rows are requested together
 constexpr int kQueue = 128;        // per wave: candidates waiting to be scored (at most 31 + 64 at a time)
@@ -131,40 +135,43 @@ __device__ __forceinline__ double wave_sum_d(double v) {
     return (lane_d(v, 0) + lane_d(v, 16)) + (lane_d(v, 32) + lane_d(v, 48));
 }
 
-// Block-wide reductions over kThreads threads.  `red` is LDS scratch of
-// 2 * kWaves doubles used as two alternating slots (`phase` counts the calls,
+// Block-wide reductions over the NW waves of a workgroup.  `red` is LDS scratch of
+// 2 * NW doubles used as two alternating slots (`phase` counts the calls,
 // identically in every thread), so one barrier per reduction is enough: a slot
 // is rewritten only after another reduction's barrier has passed.  Every thread
 // gets the result; per-wave values are combined in a fixed order.
+template <int NW>
 __device__ __forceinline__ float block_max_f(float v, double* red, int& phase) {
-    float* slot = reinterpret_cast<float*>(red + (phase++ & 1) * kWaves);
+    float* slot = reinterpret_cast<float*>(red + (phase++ & 1) * NW);
     v = wave_max_f(v);
     if ((threadIdx.x & 63) == 0) slot[threadIdx.x >> 6] = v;
     __syncthreads();
     float r = slot[0];
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) r = fmaxf(r, slot[w]);
+    for (int w = 1; w < NW; ++w) r = fmaxf(r, slot[w]);
     return r;
 }
+template <int NW>
 __device__ __forceinline__ double block_sum_d(double v, double* red, int& phase) {
-    double* slot = red + (phase++ & 1) * kWaves;
+    double* slot = red + (phase++ & 1) * NW;
     v = wave_sum_d(v);
     if ((threadIdx.x & 63) == 0) slot[threadIdx.x >> 6] = v;
     __syncthreads();
     double r = slot[0];
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) r += slot[w];
+    for (int w = 1; w < NW; ++w) r += slot[w];
     return r;
 }
 // bitwise OR of the two low bits of v over the block
+template <int NW>
 __device__ __forceinline__ int block_or_i(int v, double* red, int& phase) {
-    int* slot = reinterpret_cast<int*>(red + (phase++ & 1) * kWaves);
+    int* slot = reinterpret_cast<int*>(red + (phase++ & 1) * NW);
     v = (__any(v & 1) ? 1 : 0) | (__any(v & 2) ? 2 : 0);
     if ((threadIdx.x & 63) == 0) slot[threadIdx.x >> 6] = v;
     __syncthreads();
     int r = 0;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) r |= slot[w];
+    for (int w = 0; w < NW; ++w) r |= slot[w];
     return r;
 }
 
@@ -180,13 +187,13 @@ __device__ __forceinline__ void lds_add(long long* p, long long q) {
 // (2 gamma_D |x||c| <= gamma_D (|x|^2+|c|^2) for the dot, u(|c|^2 + 2|x||c|) for
 // the final rounding, u |c|^2 for the rounded norm).  kappa = (D + 4) u leaves
 // room for the rounding of |x|^2, of E itself and of the gap.
-template <int DV4>
+template <int DV4, int NT>
 __device__ __forceinline__ void score_valu(const ClusterArgs& a, const float* __restrict__ Xg,
                                            int n0, int ng, int K, int D, int DP,
                                            const float* cent, const float* cn, float cnmax) {
     const float kappa = (float)(D + 4) * 5.9604644775390625e-08f;
     const bool vec = (D & 3) == 0;
-    for (int p = threadIdx.x; p < ng; p += kThreads) {
+    for (int p = threadIdx.x; p < ng; p += NT) {
         float x[4 * DV4];
         const float* xr = Xg + (size_t)p * D;
         if (vec) {
@@ -289,7 +296,7 @@ __device__ __forceinline__ double quad_sum_d(double v) {
     return v;
 }
 
-template <int DS, bool OPERANDS>
+template <int DS, bool OPERANDS, int NT>
 __device__ __forceinline__ float renew_rows(float* cent, float* cn, bf16x8* aop, const long long* sums,
                                             const int* cnt, unsigned char* dirty, float* delta, int K, int D,
                                             int SP, double inv, bool init, bool need_scores) {
@@ -297,7 +304,7 @@ __device__ __forceinline__ float renew_rows(float* cent, float* cn, bf16x8* aop,
     const int tid = threadIdx.x, q = tid & 3;
     const int rows = init && OPERANDS ? ((K + 31) & ~31) : K;
     float cm = 0.f;
-    for (int j0 = 0; j0 < rows; j0 += kThreads / 4) {
+    for (int j0 = 0; j0 < rows; j0 += NT / 4) {
         const int j = j0 + (tid >> 2);
         const bool real = j < K;
         const int c = real ? cnt[j] : 0;
@@ -557,7 +564,7 @@ __device__ __forceinline__ void tile_scores(const bf16x8 (&Bh)[DS], const bf16x8
 // (16-byte pieces; D is a multiple of 4 here) and splitting it into the bf16
 // operands in registers.  A tile in which a third of the candidates are at risk
 // thus costs a third of a scoring instead of a whole one.
-template <int DS, int MT>
+template <int DS, int MT, int NT>
 __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* __restrict__ Xg,
                                             int n0, int ng, int K, int D, int DP, int SP,
                                             const float* cent, const float* cn, float cnmax,
@@ -569,6 +576,7 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
     const int m = lane & 31, h = lane >> 5;
     const int mtiles = (K + 31) >> 5;
     const float kappa = mfma_kappa(DS);
+    constexpr int kWaves = NT / kWave;
     const int ntiles = (ng + 31) >> 5;
     const int ntw = ntiles > wid ? (ntiles - wid + kWaves - 1) / kWaves : 0;   // tiles of this wave
     unsigned short* q = queue + wid * kQueue;
@@ -752,7 +760,7 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
 // the fixed-point sums from the same registers; |x|^2 and the drift limit of every
 // candidate go to the workspace for the steps that follow.  Returns max |x| over the rows this thread saw in
 // `am_out`, which the caller checks against the estimate the scale was taken from.
-template <int DS, int MT>
+template <int DS, int MT, int NT>
 __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __restrict__ Xg,
                                            int n0, int ng, int K, int D,
                                            int SP, const float* cn, float cnmax, int fsh,
@@ -763,6 +771,7 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
     const int m = lane & 31, h = lane >> 5;
     const int mtiles = (K + 31) >> 5;
     const float kappa = mfma_kappa(DS);
+    constexpr int kWaves = NT / kWave;
     const int ntiles = (ng + 31) >> 5;
     // |x|^2 and the limits serve the steps that follow: a call of one step
     // (kb_cluster_step) stores none of them
@@ -886,10 +895,11 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
 // Exact nearest centroid of the marked candidates: lanes take centroids, each
 // lane sums (x_d - c_d)^2 over d in index order in fp64 with separate multiply
 // and add; the wave then reduces to the minimum, lowest index on ties.
+template <int NT>
 __device__ __forceinline__ void refine(const ClusterArgs& a, const float* __restrict__ Xg, int n0,
                                        int ng, int K, int D, int DP, const float* cent, bool mark) {
     const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
-    for (int base = wid * kWave; base < ng; base += kThreads) {
+    for (int base = wid * kWave; base < ng; base += NT) {
         const int p = base + lane;
         const int v = p < ng ? a.a_new[(size_t)n0 + p] : 0;
         unsigned long long mask = __ballot(v < 0);
@@ -942,7 +952,7 @@ __device__ __forceinline__ void refine(const ClusterArgs& a, const float* __rest
 // summed over the features in index order with separate multiply and add - and the
 // lowest index attaining the minimum wins.  Then, if the nearest centroid differs
 // from the recorded cluster, the row moves between the running sums.
-template <int DS>
+template <int DS, int NT>
 __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* __restrict__ Xg,
                                              int n0, int n, const unsigned short* flist, int K, int D, int DP,
                                              int SP, const float* cent, int fsh,
@@ -956,13 +966,13 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
     int p_n = flist[wid];
     float xv_n = Xg[(size_t)p_n * D + lc];
     int old_n = a.assign[(size_t)n0 + p_n];
-    for (int i = wid; i < n; i += kWaves) {
+    for (int i = wid; i < n; i += NT / kWave) {
         const int p = p_n;
         const float xv = lane < D ? xv_n : 0.f;
         int old = old_n;
         {
             // no branch around the loads (the last candidate requests its own row again)
-            const int i2 = i + kWaves < n ? i + kWaves : i;
+            const int i2 = i + NT / kWave < n ? i + NT / kWave : i;
             p_n = flist[i2];
             xv_n = Xg[(size_t)p_n * D + lc];
             old_n = a.assign[(size_t)n0 + p_n];
@@ -1077,12 +1087,13 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
 // lanes take features, one candidate at a time, so the atomics of one
 // instruction hit consecutive LDS addresses.  Returns whether this thread's
 // wave saw any change.
+template <int NT>
 __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restrict__ Xg, int n0,
                                       int ng, int K, int D, int SP, bool first, int fsh,
                                       long long* sums, int* cnt, unsigned char* dirty, bool marked) {
     const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
     int any = 0;
-    for (int base = wid * kWave; base < ng; base += kThreads) {
+    for (int base = wid * kWave; base < ng; base += NT) {
         const int p = base + lane;
         int na = 0, oa = -1;
         bool chg = false;
@@ -1128,10 +1139,11 @@ __device__ __forceinline__ int update(const ClusterArgs& a, const float* __restr
 struct Lds {
     size_t sums, cent, cn, cnt, dirty, delta, flist, aop, thr, queue, total;
 };
-__host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP, int Nmax) {
+__host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP, int Nmax, int waves) {
     const int SP = D | 1;   // odd row stride: clusters spread over the LDS banks
     Lds l;
-    size_t off = 128;                                   // reduction scratch
+    // reduction scratch: two slots of one double per wave, then the count of listed candidates
+    size_t off = (size_t)waves * 16 + 64;
     l.sums = off; off += (size_t)Kmax * SP * 8;
     off = (off + 15) & ~(size_t)15;
     l.cent = off; off += (size_t)Kmax * DP * 4;
@@ -1146,15 +1158,16 @@ __host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP, int Nmax) {
     // one drift limit per tile of 32 candidates
     l.thr = off; if (Kmax <= 64) off += ((((size_t)Nmax + 31) / 32) * 4 + 15) & ~(size_t)15;
     // per wave: the candidates waiting to be scored
-    l.queue = off; if (Kmax <= 64) off += (size_t)kWaves * kQueue * 2;
+    l.queue = off; if (Kmax <= 64) off += (size_t)waves * kQueue * 2;
     l.total = off;
     return l;
 }
 
 // DS = feature K-steps of 16 (D <= 16*DS); MT = centroid tiles of 32 held in
 // registers by the matrix-core scorer, MT = 0 selects the vector-ALU scorer.
-template <int DS, int MT>
-__global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs a) {
+template <int DS, int MT, int NT>
+__global__ void __launch_bounds__(NT, NT == kThreadsNarrow ? 3 : 1) cluster_fused_kernel(ClusterArgs a) {
+    constexpr int kThreads = NT, kWaves = NT / kWave;
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
     const int D = a.D;
@@ -1175,7 +1188,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     }
     if (a.guard && ng < 2 * K) return;      // too few candidates to re-cluster: nothing is touched
 
-    const Lds L = lds_layout(a.Kmax, D, DP, a.Nmax);
+    const Lds L = lds_layout(a.Kmax, D, DP, a.Nmax, kWaves);
     double* red = reinterpret_cast<double*>(smem);
     long long* sums = reinterpret_cast<long long*>(smem + L.sums);   // [Kmax][SP]
     float* cent = reinterpret_cast<float*>(smem + L.cent);           // [Kmax][DP]
@@ -1187,7 +1200,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
     float* thr = reinterpret_cast<float*>(smem + L.thr);             // [tiles]
     unsigned short* queue = reinterpret_cast<unsigned short*>(smem + L.queue);   // [kWaves][kQueue]
     float2* lim = a.lim + n0;                                        // [N_g], global
-    int* nflag = reinterpret_cast<int*>(smem + 64);                  // behind the two reduction slots
+    int* nflag = reinterpret_cast<int*>(smem + kWaves * 16);         // behind the two reduction slots
     bf16x8* aop = reinterpret_cast<bf16x8*>(smem + L.aop);
 
     const float* Xg = a.X + (size_t)n0 * D;
@@ -1255,15 +1268,15 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
         }
     }
     int phase = 0;
-    am = block_max_f(am, red, phase);
-    if constexpr (MT == 0) tsq = block_sum_d(tsq, red, phase);
+    am = block_max_f<kWaves>(am, red, phase);
+    if constexpr (MT == 0) tsq = block_sum_d<kWaves>(tsq, red, phase);
     int sh = fixed_shift(am, ng);
     int fsh = sh - 32;          // what to_fixed takes
     double inv = ldexp(1.0, -sh);
 
     // |c_j|^2, their maximum and the matrix-core operands of the initial centroids
-    float cm = renew_rows<DS, (MT > 0)>(cent, cn, aop, sums, cnt, dirty, delta, K, D, SP, inv, true, true);
-    cm = block_max_f(cm, red, phase);
+    float cm = renew_rows<DS, (MT > 0), NT>(cent, cn, aop, sums, cnt, dirty, delta, K, D, SP, inv, true, true);
+    cm = block_max_f<kWaves>(cm, red, phase);
 
     bool first = true;
     float drift = 0.f;          // cumulative (largest + second largest) centroid move, rounded up
@@ -1284,10 +1297,10 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
         if constexpr (MT > 0) {
             if (first) {
                 float am_seen;
-                st = score_first<DS, MT>(a, Xg, n0, ng, K, D, SP, cn, cm, fsh, sums, cnt, nflag,
+                st = score_first<DS, MT, NT>(a, Xg, n0, ng, K, D, SP, cn, cm, fsh, sums, cnt, nflag,
                                          flist, aop, dw, thr, lim, am_seen, tsq);
-                am_seen = block_max_f(am_seen, red, phase);
-                tsq = block_sum_d(tsq, red, phase);
+                am_seen = block_max_f<kWaves>(am_seen, red, phase);
+                tsq = block_sum_d<kWaves>(tsq, red, phase);
                 const int sh_true = fixed_shift(am_seen, ng);
                 if (sh_true != sh) {
                     // the rows beyond the estimate's sample were larger: rebuild the
@@ -1310,27 +1323,27 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
                     __syncthreads();
                 }
             } else
-            st = score_packed<DS, MT>(a, Xg, n0, ng, K, D, DP, SP, cent, cn, cm, fsh, sums, cnt,
+            st = score_packed<DS, MT, NT>(a, Xg, n0, ng, K, D, DP, SP, cent, cn, cm, fsh, sums, cnt,
                                       nflag, flist, aop, dw, thr, lim, queue, drift);
         } else {
-            score_valu<4 * DS>(a, Xg, n0, ng, K, D, DP, cent, cn, cm);
+            score_valu<4 * DS, NT>(a, Xg, n0, ng, K, D, DP, cent, cn, cm);
             st = 2;
         }
-        st = block_or_i(st, red, phase);
+        st = block_or_i<kWaves>(st, red, phase);
         if (st & 2) {
             int moved;
             const int nf = MT > 0 ? *nflag : kFlagCap + 1;
             if (nf <= kFlagCap) {
-                moved = refine_listed<DS>(a, Xg, n0, nf, flist, K, D, DP, SP, cent, fsh, sums, cnt, dw,
+                moved = refine_listed<DS, NT>(a, Xg, n0, nf, flist, K, D, DP, SP, cent, fsh, sums, cnt, dw,
                                       thr, lim, drift);
             } else {
                 // the list overflowed (or the vector-ALU scorer ran): scan every candidate;
                 // no slack is known for the refined ones, so every tile is scored next time
-                refine(a, Xg, n0, ng, K, D, DP, cent, MT > 0);
+                refine<NT>(a, Xg, n0, ng, K, D, DP, cent, MT > 0);
                 __syncthreads();
                 // after the matrix-core scorer only refined candidates are left to move,
                 // and it has already recorded an assignment for every other candidate
-                moved = update(a, Xg, n0, ng, K, D, SP, first && MT == 0, fsh, sums, cnt, dw, MT > 0);
+                moved = update<NT>(a, Xg, n0, ng, K, D, SP, first && MT == 0, fsh, sums, cnt, dw, MT > 0);
                 if (MT > 0 && a.iters > 1) {
                     // every candidate's state: its cluster as it stands now, limit 0
                     __syncthreads();
@@ -1342,7 +1355,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
                         for (int t = tid; t < ((ng + 31) >> 5); t += kThreads) thr[t] = 0.f;
                 }
             }
-            st |= block_or_i(moved, red, phase);
+            st |= block_or_i<kWaves>(moved, red, phase);
             // every thread has read the counter before that barrier, and the barriers of
             // the renewal below separate this reset from the next step's additions
             if (tid == 0) *nflag = 0;
@@ -1369,7 +1382,7 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
                     }
                 }
             }
-            part = block_sum_d(part, red, phase);
+            part = block_sum_d<kWaves>(part, red, phase);
             const double Jfast = tsq - part;
             if (Jfast >= 1.0e-7 * tsq) {
                 if (tid == 0) a.objective[g] = (float)Jfast;
@@ -1420,13 +1433,13 @@ __global__ void __launch_bounds__(kThreads, 3) cluster_fused_kernel(ClusterArgs 
                     }
                 }
             }
-            acc = block_sum_d(acc, red, phase);
+            acc = block_sum_d<kWaves>(acc, red, phase);
             if (tid == 0) a.objective[g] = (float)acc;
             }
         }
         // new centroids, and what the next step needs from them
-        cm = renew_rows<DS, (MT > 0)>(cent, cn, aop, sums, cnt, dirty, delta, K, D, SP, inv, false, !last);
-        cm = block_max_f(cm, red, phase);
+        cm = renew_rows<DS, (MT > 0), NT>(cent, cn, aop, sums, cnt, dirty, delta, K, D, SP, inv, false, !last);
+        cm = block_max_f<kWaves>(cm, red, phase);
         if (last) break;
     }
 
@@ -1447,7 +1460,7 @@ static int one_wg_nmax(const kb_batch& b) { return b.Nmax > kOneWgMaxN ? kOneWgM
 
 bool cluster_supported(const kb_batch& b) {
     const int ds = (b.D + 15) / 16;
-    return lds_layout(one_wg_kmax(b), b.D, 16 * ds + 4, one_wg_nmax(b)).total <= kMaxLds;
+    return lds_layout(one_wg_kmax(b), b.D, 16 * ds + 4, one_wg_nmax(b), kThreadsNarrow / kWave).total <= kMaxLds;
 }
 
 hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t st) {
@@ -1455,7 +1468,8 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     a.G = b.G; a.D = b.D; a.Ksum = b.Ksum; a.Kmax = one_wg_kmax(b); a.N = b.N;
     a.seg_off = b.seg_off; a.koff = b.koff; a.X = c.X; a.cent_init = c.cent_init;
     a.iters = c.iters; a.early_exit = 0; a.assign = c.assign; a.cent_out = c.cent_out;
-    a.counts = c.counts; a.objective = c.objective; a.a_new = c.a_new; a.order = c.order;
+    a.counts = c.counts; a.objective = c.objective; a.a_new = c.a_new;
+    a.order = b.G > 1 ? c.order : nullptr;       // (one search: the order is the identity and was not computed)
     a.use_bounds = c.scorer != 2;
     a.guard = c.guard;
     a.mixed = c.mixed;
@@ -1463,21 +1477,30 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
 
     const int ds = (b.D + 15) / 16;   // 1..4 K-steps of 16 features
     a.Nmax = one_wg_nmax(b);
-    const size_t lds = lds_layout(a.Kmax, b.D, 16 * ds + 4, a.Nmax).total;
+    // few searches: every workgroup has a compute unit to itself and takes the wide shape
+    const size_t lds_wide = lds_layout(a.Kmax, b.D, 16 * ds + 4, a.Nmax, kThreadsWide / kWave).total;
+    const bool wide = b.G <= kWideMaxG && lds_wide <= kMaxLds;
+    const size_t lds = wide ? lds_wide
+                            : lds_layout(a.Kmax, b.D, 16 * ds + 4, a.Nmax, kThreadsNarrow / kWave).total;
     if (lds > kMaxLds) return hipErrorInvalidValue;
     int mt = a.Kmax <= 32 ? 1 : (a.Kmax <= 64 ? 2 : 0);
     if (c.scorer == 1) mt = 0;
     // (the matrix-core kernels fetch rows in 16-byte pieces: feature counts that are not
     // a multiple of 4 take the vector-ALU kernels, whose results are the same)
     if ((b.D & 3) != 0) mt = 0;
-    const dim3 grid((unsigned)b.G), block(kThreads);
-#define KB_LAUNCH(DS_, MT_)                                                                     \
+    const dim3 grid((unsigned)b.G), block(wide ? kThreadsWide : kThreadsNarrow);
+#define KB_LAUNCH_NT(DS_, MT_, NT_)                                                             \
     do {                                                                                        \
         hipError_t e = hipFuncSetAttribute(                                                     \
-            reinterpret_cast<const void*>(cluster_fused_kernel<DS_, MT_>),                      \
+            reinterpret_cast<const void*>(cluster_fused_kernel<DS_, MT_, NT_>),                 \
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                              \
         if (e != hipSuccess) return e;                                                          \
-        hipLaunchKernelGGL((cluster_fused_kernel<DS_, MT_>), grid, block, lds, st, a);          \
+        hipLaunchKernelGGL((cluster_fused_kernel<DS_, MT_, NT_>), grid, block, lds, st, a);     \
+    } while (0)
+#define KB_LAUNCH(DS_, MT_)                                                                     \
+    do {                                                                                        \
+        if (wide) KB_LAUNCH_NT(DS_, MT_, kThreadsWide);                                         \
+        else KB_LAUNCH_NT(DS_, MT_, kThreadsNarrow);                                            \
     } while (0)
 #define KB_LAUNCH_DS(DS_)                                                                       \
     do {                                                                                        \
@@ -1493,6 +1516,7 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     }
 #undef KB_LAUNCH_DS
 #undef KB_LAUNCH
+#undef KB_LAUNCH_NT
     return hipGetLastError();
 }
 

@@ -325,7 +325,8 @@ hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st) {
     a.seg_off = b.seg_off; a.koff = b.koff; a.assign = c.assign; a.alive = c.alive;
     a.bound = c.bound; a.M = c.M; a.visits = c.visits; a.rsum = c.rsum; a.t = c.t; a.c = c.c;
     a.prior_n = c.prior_n; a.prior_mu = c.prior_mu; a.Ncs = c.Ncs; a.mu = c.mu; a.ucb = c.ucb;
-    a.sel = c.sel; a.order = c.order;
+    a.sel = c.sel;
+    a.order = b.G > 1 ? c.order : nullptr;       // (one search: the order is the identity and was not computed)
     const size_t lds = 64 + (size_t)a.Kmax * b.S * 12 + (size_t)a.Kmax * 12;
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     a.gN = c.gN; a.gR = c.gR; a.gnalive = c.gnalive; a.gkmin = c.gkmin; a.Nll = b.N;
