@@ -330,6 +330,26 @@ def test_mixed_batch_equals_the_two_paths_run_apart(kb):
     np.testing.assert_array_equal(out["both"]["sel"], np.concatenate([out["small"]["sel"], sel_big]))
 
 
+def test_workgroup_shapes_agree(kb, scorer):
+    """The one-workgroup Lloyd kernel runs 768 threads per search in a batch of up to
+    256 searches and 256 threads in a larger one: the same searches give the same
+    bytes either way (the fixed-point sums do not depend on how the rows are spread
+    over the waves)."""
+    kw = dict(D=32, S=4, iters=7)
+    few = synth.config5(G=60, nmin=64, nmax=2000, seed=83, **kw)
+    filler = synth.config5(G=240, nmin=64, nmax=120, seed=84, **kw)
+    many = synth.concat(few, filler)
+    assert few.G <= 256 < many.G
+    out = []
+    for b in (few, many):
+        d = kb.DeviceBatch(b, scorer=scorer)
+        d.cluster()
+        _sync()
+        out.append({k: d.host(k).copy() for k in ("assign", "cent", "counts", "objective")})
+    for k, n in (("assign", few.N), ("cent", few.Ksum), ("counts", few.Ksum), ("objective", few.G)):
+        np.testing.assert_array_equal(out[0][k].view(np.uint8), out[1][k][:n].view(np.uint8), err_msg=k)
+
+
 def test_features_of_different_magnitude(kb):
     """One fixed-point grid per search serves every feature: columns a few thousand
     times smaller than the largest one still give centroids good to fp32 rounding
