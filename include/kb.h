@@ -46,7 +46,8 @@
  * >= kb_workspace_bytes(), 256-byte aligned, contents undefined before and
  * after a call).  The workspace holds, besides small tables, a proposal and an
  * 8-byte entry (drift limit, cluster, |x|^2; at other times an fp64 distance) per
- * candidate: about 12 * N bytes; a batch with a search of more than 64 clusters
+ * candidate and 12 bytes per cluster arm (integer statistics tables of the
+ * selection step): about 12 * N + 12 * Ksum * S bytes; a batch with a search of more than 64 clusters
  * or 65536 candidates adds a bf16 copy of the features and per-candidate lists,
  * about (4*Dpad + 28) * N bytes more with Dpad = D rounded up to 16.  Two calls
  * may run concurrently only on different workspaces.
@@ -397,8 +398,11 @@ kb_status kb_update_stats(const kb_batch *batch, const kb_params *params,
  *       the first K_g rows or - warm_start != 0 - from the current centroids;
  *       kb_cluster_geometry -> rep, radius; kb_strategy_mask -> M, nvalid
  *   kb_ucb_select_masked (alive as given, bound = NULL) -> Ncs, mu, ucb, sel_log[r]
- *       (the cluster-arm statistics are re-aggregated from visits / rsum, so they
- *       follow a re-clustering)
+ *       (the cluster-arm statistics are those an aggregation of visits / rsum over the
+ *       alive members of every cluster gives, so they follow a re-clustering: they
+ *       are aggregated in the first round and after every re-clustering, kept as
+ *       integer tables in the workspace and advanced by the update step in between,
+ *       which gives the same bits as aggregating again)
  *   kb_sample_signature, draw number sample.draw + r       -> ksel_log[r]
  *   kb_update_stats with reward[r], ok[r]                  -> visits, rsum, Ncs, mu, t
  * The frontier is fixed during the call (new kernels are appended by the caller

@@ -26,9 +26,11 @@ WsLayout ws_layout(const kb_batch& b) {
         w.big = big_ws_layout(b, off);
         off = w.big.end;
     }
+    // cluster-arm tables of the selection step in global memory: searches of more than
+    // 16384 candidates are aggregated there, and kb_iterate carries them from round to
+    // round
     w.ucb_chunked = b.Nmax > 16384;
-    w.ucb_R = w.ucb_N = w.ucb_kmin = w.ucb_nalive = 0;
-    if (w.ucb_chunked) {
+    {
         const size_t ks = (size_t)(b.Ksum > 0 ? b.Ksum : 1) * b.S, k = (size_t)(b.Ksum > 0 ? b.Ksum : 1);
         w.ucb_R = off;      off += align256(8 * ks);
         w.ucb_kmin = off;   off += align256(8 * k);
@@ -181,10 +183,11 @@ static kb_status check_ucb(const kb_batch* b, const kb_params* p, const int32_t*
 struct UcbScratch {
     int32_t* order;                 // [G]
     int32_t* tile_off;              // [G + 1] (written by the ordering kernel, not read here)
-    unsigned* gN;                   // tables of the chunked path, NULL: one workgroup per search
-    unsigned long long* gR;
+    unsigned* gN;                   // cluster-arm tables in global memory (NULL: none; then no search
+    unsigned long long* gR;         // may be longer than 16384 candidates)
     unsigned* gnalive;
     unsigned long long* gkmin;
+    bool chunked;                   // the batch has a search that is aggregated in those tables
 };
 
 static UcbScratch ucb_scratch_in_ws(const kb_batch* b, void* ws) {
@@ -193,11 +196,9 @@ static UcbScratch ucb_scratch_in_ws(const kb_batch* b, void* ws) {
     UcbScratch u;
     u.order = (int32_t*)(base + w.order);
     u.tile_off = (int32_t*)(base + w.tile_off);
-    u.gN = nullptr; u.gR = nullptr; u.gnalive = nullptr; u.gkmin = nullptr;
-    if (w.ucb_chunked) {
-        u.gN = (unsigned*)(base + w.ucb_N); u.gR = (unsigned long long*)(base + w.ucb_R);
-        u.gnalive = (unsigned*)(base + w.ucb_nalive); u.gkmin = (unsigned long long*)(base + w.ucb_kmin);
-    }
+    u.gN = (unsigned*)(base + w.ucb_N); u.gR = (unsigned long long*)(base + w.ucb_R);
+    u.gnalive = (unsigned*)(base + w.ucb_nalive); u.gkmin = (unsigned long long*)(base + w.ucb_kmin);
+    u.chunked = w.ucb_chunked;
     return u;
 }
 
@@ -206,7 +207,9 @@ static kb_status do_ucb(const kb_batch* b, const kb_params* p, const int32_t* as
                         const float* rsum, const int64_t* t, int32_t* Ncs, float* mu,
                         float* ucb, int32_t* sel, const UcbScratch& u, bool have_order,
                         hipStream_t st, const uint8_t* M = nullptr,
-                        bool optional_mask_inputs = false) {
+                        bool optional_mask_inputs = false, int tables = 0) {
+    // tables: 0 = plain call; 1 = aggregate and leave every search's tables in u's global
+    // arrays; 2 = no aggregation, scores and selection from those arrays as they stand
     kb_status s = check_ucb(b, p, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel,
                             optional_mask_inputs);
     if (s != KB_OK) return s;
@@ -219,6 +222,8 @@ static kb_status do_ucb(const kb_batch* b, const kb_params* p, const int32_t* as
     c.t = t; c.c = p->c; c.prior_n = p->prior_n; c.prior_mu = p->prior_mu;
     c.Ncs = Ncs; c.mu = mu; c.ucb = ucb; c.sel = sel; c.order = u.order;
     c.gN = u.gN; c.gR = u.gR; c.gnalive = u.gnalive; c.gkmin = u.gkmin;
+    c.chunked = u.chunked ? 1 : 0;
+    c.keep_tables = tables == 1; c.from_tables = tables == 2;
     return dev(launch_ucb(*b, c, st));
 }
 
@@ -310,6 +315,9 @@ kb_status kb_ucb_select(const kb_batch* batch, const kb_params* params, const in
                         int32_t* sel, void* ws, size_t ws_bytes, void* stream) {
     kb_status s = check_batch(batch);
     if (s != KB_OK) return s;
+    // (arguments and shape limits before the workspace, whose size depends on the shape)
+    s = check_ucb(batch, params, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel);
+    if (s != KB_OK) return s;
     s = check_ws(batch, ws, ws_bytes);
     if (s != KB_OK) return s;
     return do_ucb(batch, params, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel,
@@ -322,6 +330,8 @@ kb_status kb_ucb_select_masked(const kb_batch* batch, const kb_params* params,
                                const int64_t* t, int32_t* Ncs, float* mu, float* ucb, int32_t* sel,
                                void* ws, size_t ws_bytes, void* stream) {
     kb_status s = check_batch(batch);
+    if (s != KB_OK) return s;
+    s = check_ucb(batch, params, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel, true);
     if (s != KB_OK) return s;
     s = check_ws(batch, ws, ws_bytes);
     if (s != KB_OK) return s;
@@ -350,6 +360,7 @@ kb_status kb_ucb_select_static(const kb_batch* batch, const kb_params* params,
     u.order = (int32_t*)(base + kStaticOrder);
     u.tile_off = (int32_t*)(base + kStaticTileOff);
     u.gN = nullptr; u.gR = nullptr; u.gnalive = nullptr; u.gkmin = nullptr;
+    u.chunked = chunked;
     if (chunked) {
         u.gR = (unsigned long long*)(base + kStaticR);
         u.gkmin = (unsigned long long*)(base + kStaticKmin);
@@ -564,6 +575,14 @@ kb_status kb_iterate(const kb_batch* batch, const kb_params* params, const kb_it
     char* base = (char*)ws;
     const size_t G = (size_t)batch->G;
     bool have_order = false;        // the scheduling order in ws, computed by the first stage that needs it
+    // The cluster-arm tables (visit counts and fixed-point reward sums of the alive
+    // members of every cluster) are aggregated from the per-candidate history in the
+    // first round and after every re-clustering, kept in the workspace, and advanced by
+    // the update step in between: integer tables, so the carried ones equal a fresh
+    // aggregation bit for bit and a round without re-clustering reads K_g*S entries per
+    // search instead of N_g*S.
+    const UcbScratch us = ucb_scratch_in_ws(batch, ws);
+    bool tables_valid = false;
     for (int32_t r = 0; r < ip->rounds; ++r) {
         const bool now = recluster && ((ip->t0 + r) % ip->tau_recluster) == 0;
         if (now) {
@@ -574,6 +593,7 @@ kb_status kb_iterate(const kb_batch* batch, const kb_params* params, const kb_it
                            true);
             if (s != KB_OK) return s;
             have_order = true;
+            tables_valid = false;
             GeoCall gc;
             gc.X = io->X; gc.cent = io->cent; gc.assign = io->assign; gc.rep = io->rep;
             gc.radius = io->radius; gc.d2 = (double*)(base + w.geo_d2);
@@ -589,10 +609,11 @@ kb_status kb_iterate(const kb_batch* batch, const kb_params* params, const kb_it
         // the cluster-arm tables are rebuilt from the per-candidate history, so they
         // follow every re-clustering; masked UCB argmax (Eq. 6)
         s = do_ucb(batch, params, io->assign, io->alive, nullptr, io->visits, io->rsum, io->t,
-                   io->Ncs, io->mu, io->ucb, sel, ucb_scratch_in_ws(batch, ws), have_order, st, io->M,
-                   true);
+                   io->Ncs, io->mu, io->ucb, sel, us, have_order, st, io->M, true,
+                   tables_valid ? 2 : 1);
         if (s != KB_OK) return s;
         have_order = true;
+        tables_valid = true;
         // draw of k_t with the potential theta_sat - h (Sec. 3.4)
         SampleCall sc;
         sc.assign = io->assign; sc.alive = io->alive; sc.bound = nullptr; sc.incumbent = nullptr;
@@ -604,7 +625,7 @@ kb_status kb_iterate(const kb_batch* batch, const kb_params* params, const kb_it
         // reward of the generated kernel -> statistics (Alg. 1, last lines)
         if (launch_update_stats(*batch, params->prior_n, sel, ksel, io->reward + (size_t)r * G,
                                 io->ok + (size_t)r * G, io->visits, io->rsum, io->Ncs, io->mu, io->t,
-                                st) != hipSuccess)
+                                st, io->assign, io->alive, us.gN, us.gR) != hipSuccess)
             return KB_EDEVICE;
     }
     return KB_OK;
@@ -621,6 +642,6 @@ const char* kb_status_str(kb_status status) {
     return "KB_E?: unknown status";
 }
 
-const char* kb_version(void) { return "0.4"; }
+const char* kb_version(void) { return "0.5"; }
 
 }  // extern "C"

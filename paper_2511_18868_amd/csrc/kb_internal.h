@@ -107,11 +107,17 @@ struct UcbCall {
     float* ucb;
     int32_t* sel;
     const int32_t* order;
-    // global tables of the chunked path (NULL: one workgroup per search)
+    // cluster-arm tables in global memory: visit counts, reward sums in 2^-30 fixed
+    // point, alive members and best member per cluster.  Searches of more than 16384
+    // candidates are aggregated there (chunked != 0 says the batch has such a
+    // search; the tables must then be given); the others only when keep_tables asks
+    // for a copy of their LDS tables.  from_tables: no aggregation at all, scores
+    // and selection come from the tables as they stand.
     unsigned* gN;
     unsigned long long* gR;
     unsigned* gnalive;
     unsigned long long* gkmin;
+    int chunked, keep_tables, from_tables;
 };
 hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st);
 
@@ -167,12 +173,25 @@ hipError_t launch_seed(const kb_batch& b, const float* X, float* cent, int32_t* 
 hipError_t launch_strategy_mask(const kb_batch& b, int R, const float* h, const int32_t* target,
                                 const int32_t* rep, float theta_sat, uint8_t* M, int32_t* nvalid,
                                 hipStream_t st);
+// gN / gR != NULL: the cluster-arm tables of UcbCall are advanced too (they then equal
+// what an aggregation of the updated history under `assign` / `alive` would give).
 hipError_t launch_update_stats(const kb_batch& b, float prior_n, const int32_t* sel,
                                const int32_t* ksel, const float* reward, const uint8_t* ok,
                                int32_t* visits, float* rsum, int32_t* Ncs, float* mu, int64_t* t,
-                               hipStream_t st);
+                               hipStream_t st, const int32_t* assign = nullptr,
+                               const uint8_t* alive = nullptr, unsigned* gN = nullptr,
+                               unsigned long long* gR = nullptr);
 
 // ---- device helpers ----------------------------------------------------------
+// Reward sum in 2^-30 fixed point, rounded to nearest (ties to even), with exact
+// fp32 steps only: the integer part of r and its fraction are converted apart.
+// r is non-negative and below 2^31 (a reward sum never exceeds its visit count).
+__device__ __forceinline__ unsigned long long reward_fixed(float r) {
+    const float hi = floorf(r);
+    const float lo = rintf(ldexpf(r - hi, 30));       // r - hi is exact, in [0, 1)
+    return ((unsigned long long)(unsigned)hi << 30) + (unsigned)lo;
+}
+
 __device__ __forceinline__ int clampi(int v, int lo, int hi) {
     return v < lo ? lo : (v > hi ? hi : v);
 }

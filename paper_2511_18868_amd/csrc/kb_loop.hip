@@ -47,7 +47,9 @@ update_stats_kernel(int G, int S, int Ksum, int64_t N, const int32_t* __restrict
                     const int32_t* __restrict__ ksel, const float* __restrict__ reward,
                     const uint8_t* __restrict__ ok, double prior_n, int32_t* __restrict__ visits,
                     float* __restrict__ rsum, int32_t* __restrict__ Ncs, float* __restrict__ mu,
-                    int64_t* __restrict__ t) {
+                    int64_t* __restrict__ t, const int32_t* __restrict__ assign,
+                    const uint8_t* __restrict__ alive, unsigned* __restrict__ gN,
+                    unsigned long long* __restrict__ gR) {
     const int g = blockIdx.x * kThreads + threadIdx.x;
     if (g >= G) return;
     t[g] += 1;
@@ -63,7 +65,18 @@ update_stats_kernel(int G, int S, int Ksum, int64_t N, const int32_t* __restrict
     mu[arm] = (float)(m + (r - m) / ((double)nn + prior_n));
     const size_t cell = (size_t)k * S + s;
     visits[cell] += 1;
-    rsum[cell] = (float)((double)rsum[cell] + r);
+    const float r_old = rsum[cell];
+    const float r_new = (float)((double)r_old + r);
+    rsum[cell] = r_new;
+    if (gN && (!alive || alive[k])) {
+        // the tables an aggregation over the alive candidates would now give: one more
+        // visit and the change of this cell's fixed-point image, in the candidate's cluster
+        int j = assign[k];
+        j = (j >= 0 && j < K) ? j : 0;
+        const size_t tarm = ((size_t)k0 + j) * S + s;
+        gN[tarm] += 1u;
+        gR[tarm] += reward_fixed(r_new) - reward_fixed(r_old);
+    }
 }
 
 }  // namespace
@@ -80,10 +93,12 @@ hipError_t launch_strategy_mask(const kb_batch& b, int R, const float* h, const 
 hipError_t launch_update_stats(const kb_batch& b, float prior_n, const int32_t* sel,
                                const int32_t* ksel, const float* reward, const uint8_t* ok,
                                int32_t* visits, float* rsum, int32_t* Ncs, float* mu, int64_t* t,
-                               hipStream_t st) {
+                               hipStream_t st, const int32_t* assign, const uint8_t* alive,
+                               unsigned* gN, unsigned long long* gR) {
+    if (gN && (!gR || !assign)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(update_stats_kernel, dim3((unsigned)((b.G + kThreads - 1) / kThreads)),
                        dim3(kThreads), 0, st, b.G, b.S, b.Ksum, b.N, b.seg_off, b.koff, sel, ksel,
-                       reward, ok, (double)prior_n, visits, rsum, Ncs, mu, t);
+                       reward, ok, (double)prior_n, visits, rsum, Ncs, mu, t, assign, alive, gN, gR);
     return hipGetLastError();
 }
 

@@ -40,6 +40,7 @@ struct UcbArgs {
     int64_t Nll;
     int mixed;                  // 1: searches of up to kUcbLong candidates go to ucb_kernel, longer ones to the
                                 //    range kernels, in the same call
+    int keep;                   // 1: ucb_kernel leaves a copy of its LDS tables in the global ones
 };
 
 constexpr int kThreads = 256;
@@ -52,15 +53,6 @@ constexpr int kUcbLong = 16384;     // searches longer than this are cut into ca
 __device__ __forceinline__ unsigned ordered_bits(float f) {
     const unsigned u = __float_as_uint(f);
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-// Reward sum in 2^-30 fixed point, rounded to nearest (ties to even), with exact
-// fp32 steps only: the integer part of r and its fraction are converted apart.
-// r is non-negative and below 2^31 (a reward sum never exceeds its visit count).
-__device__ __forceinline__ unsigned long long reward_fixed(float r) {
-    const float hi = floorf(r);
-    const float lo = rintf(ldexpf(r - hi, 30));       // r - hi is exact, in [0, 1)
-    return ((unsigned long long)(unsigned)hi << 30) + (unsigned)lo;
 }
 
 // Scatter the visits / reward sums of the alive candidates [q0, q1) of a search
@@ -239,6 +231,14 @@ __global__ void __launch_bounds__(kThreads) ucb_kernel(UcbArgs a) {
     ucb_accumulate(a, n0, K, 0, ng, Ncnt, R, nalive, kmin);
     __syncthreads();
 
+    if (a.keep) {
+        // (a search is owned by this workgroup: plain stores)
+        for (int i = tid; i < KS; i += kThreads) {
+            a.gN[(size_t)k0 * S + i] = Ncnt[i];
+            a.gR[(size_t)k0 * S + i] = R[i];
+        }
+        for (int i = tid; i < K; i += kThreads) { a.gnalive[k0 + i] = nalive[i]; a.gkmin[k0 + i] = kmin[i]; }
+    }
     ucb_finish(a, g, n0, k0, K, Ncnt, R, nalive, kmin, redv, redi);
 }
 
@@ -331,12 +331,26 @@ hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st) {
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     a.gN = c.gN; a.gR = c.gR; a.gnalive = c.gnalive; a.gkmin = c.gkmin; a.Nll = b.N;
     a.mixed = 0;
-    if (c.gN) {
+    a.keep = 0;
+    if (c.from_tables) {
+        if (!c.gN) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(ucb_final, dim3((unsigned)b.G), dim3(kThreads), 0, st, a);
+        return hipGetLastError();
+    }
+    if (c.keep_tables && !c.gN) return hipErrorInvalidValue;
+    a.keep = c.keep_tables ? 1 : 0;
+    if (c.chunked) {
+        if (!c.gN) return hipErrorInvalidValue;
         // long searches: candidate ranges -> partial tables -> global tables -> scores;
         // in a batch of several searches the short ones get a workgroup each as usual
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ucb_partial),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
+        const size_t items = (size_t)b.Ksum * b.S;
+        unsigned zb = (unsigned)((items + kThreads - 1) / kThreads);
+        if (zb > 4096u) zb = 4096u;
+        if (zb == 0) zb = 1;
+        hipLaunchKernelGGL(ucb_zero, dim3(zb), dim3(kThreads), 0, st, a);
         if (b.G > 1) {
             a.mixed = 1;
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(ucb_kernel),
@@ -344,11 +358,6 @@ hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st) {
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(ucb_kernel, dim3((unsigned)b.G), dim3(kThreads), lds, st, a);
         }
-        const size_t items = (size_t)b.Ksum * b.S;
-        unsigned zb = (unsigned)((items + kThreads - 1) / kThreads);
-        if (zb > 4096u) zb = 4096u;
-        if (zb == 0) zb = 1;
-        hipLaunchKernelGGL(ucb_zero, dim3(zb), dim3(kThreads), 0, st, a);
         const unsigned ranges = (unsigned)((b.N + kUcbRange - 1) / kUcbRange);
         if (ranges) hipLaunchKernelGGL(ucb_partial, dim3(ranges), dim3(kThreads), lds, st, a);
         hipLaunchKernelGGL(ucb_final, dim3((unsigned)b.G), dim3(kThreads), 0, st, a);

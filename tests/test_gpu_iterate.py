@@ -31,6 +31,14 @@ def _guarded():
     return b
 
 
+def _with_long_search():
+    """A search of 20000 candidates (its cluster-arm tables are aggregated over candidate
+    ranges) after 30 short ones."""
+    a = synth.config5(G=30, nmin=64, nmax=500, D=16, S=4, iters=2, seed=54)
+    big = synth.config2(N=20000, D=16, K=8, S=4, iters=2, seed=6)
+    return synth.concat(a, big, "longsearch")
+
+
 CASES = {
     # name: (batch, rounds, tau, t0, warm_start, Lloyd steps per re-clustering)
     "paper": (lambda: synth.paper_shape(), 25, 10, 0, 0, 5),
@@ -39,6 +47,9 @@ CASES = {
     "multiworkgroup": (lambda: synth.config5(G=4, nmin=1500, nmax=4000, kcap=128, D=40, S=4, iters=3,
                                              seed=52), 7, 3, 0, 1, 2),
     "never": (lambda: synth.config3(G=16), 12, 0, 5, 0, 1),
+    "longsearch": (_with_long_search, 14, 6, 0, 1, 2),
+    # with a mask of alive candidates (every third one pruned)
+    "pruned": (lambda: synth.config5(G=24, nmin=64, nmax=400, S=8, seed=55), 22, 8, 1, 1, 2),
 }
 
 
@@ -67,10 +78,13 @@ def test_iterate_matches_the_composed_oracle(kb, name):
     sel_log = torch.full((T, b.G, 3), -7, dtype=torch.int32, device=d.device)
     ksel_log = torch.full((T, b.G), -7, dtype=torch.int32, device=d.device)
     ip = kb.kb_iterate_params(T, tau, t0, warm, R, theta, kb.kb_sample_params(seed, draw0, temp))
-    d.iterate(ip, dh, dtg, drw, dok, sel_log, ksel_log)
+    alive = None
+    if name == "pruned":
+        alive = (np.arange(b.N) % 3 != 1).astype(np.uint8)
+    d.iterate(ip, dh, dtg, drw, dok, sel_log, ksel_log, alive=None if alive is None else up(alive))
     torch.cuda.synchronize()
 
-    o = oracle.iterate(b.seg_off, b.koff, b.S, b.X, h, target, theta, None, rw, ok, b.visits, b.rsum,
+    o = oracle.iterate(b.seg_off, b.koff, b.S, b.X, h, target, theta, alive, rw, ok, b.visits, b.rsum,
                        b.t, cl.assign, cl.cent, cl.counts, cl.objective, geo.rep, M0, T, tau, t0, warm,
                        iters, b.c, b.prior_n, b.prior_mu, seed, draw0, temp)
     gs, gk = sel_log.cpu().numpy(), ksel_log.cpu().numpy()
