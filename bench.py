@@ -271,9 +271,19 @@ def main():
             n = 50 if c <= 3 else 20
             r_mean, r_med = timed(dc.round, n)
             c_mean, _ = timed(dc.cluster, n)
+            # the same round recorded once into a HIP graph and replayed (the library only
+            # enqueues kernels, so a call can be captured)
+            side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                dc.round()
+            graph.replay()
+            torch.cuda.synchronize()
+            _, g_med = timed(graph.replay, n)
             e = {"N": bc.N, "G": bc.G, "D": bc.D, "Kmax": bc.Kmax, "S": bc.S, "iters": bc.iters,
                  "round_ms": round(r_med, 4), "cluster_ms": round(c_mean, 4),
+                 "round_ms_graph_replay": round(g_med, 4),
                  "traces_per_s": round(bc.N / (r_med * 1e-3), 1)}
+            del graph
             sb = lloyd_step_bytes(bc)
             if c in (1, 2):
                 # one search on one workgroup: launch and barrier latency, not bandwidth
