@@ -963,19 +963,27 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
     const float eps = 2.f * (float)(D + 2) * 5.9604644775390625e-08f;
     int any = 0;
     if (wid >= n) return 0;
+    constexpr int W = NT / kWave;
+    // the rows of this wave's next two candidates are always in flight (a row is one
+    // register: lanes over features), so a step's few candidates cost one trip to
+    // memory and not one each
     int p_n = flist[wid];
     float xv_n = Xg[(size_t)p_n * D + lc];
     int old_n = a.assign[(size_t)n0 + p_n];
-    for (int i = wid; i < n; i += NT / kWave) {
+    int p_m = flist[wid + W < n ? wid + W : wid];
+    float xv_m = Xg[(size_t)p_m * D + lc];
+    int old_m = a.assign[(size_t)n0 + p_m];
+    for (int i = wid; i < n; i += W) {
         const int p = p_n;
         const float xv = lane < D ? xv_n : 0.f;
         int old = old_n;
+        p_n = p_m; xv_n = xv_m; old_n = old_m;
         {
-            // no branch around the loads (the last candidate requests its own row again)
-            const int i2 = i + NT / kWave < n ? i + NT / kWave : i;
-            p_n = flist[i2];
-            xv_n = Xg[(size_t)p_n * D + lc];
-            old_n = a.assign[(size_t)n0 + p_n];
+            // no branch around the loads (the last candidates request their own row again)
+            const int i2 = i + 2 * W < n ? i + 2 * W : i;
+            p_m = flist[i2];
+            xv_m = Xg[(size_t)p_m * D + lc];
+            old_m = a.assign[(size_t)n0 + p_m];
         }
         // rows are zero-padded to a multiple of 4 features (and xv is 0 beyond D), so
         // whole float4 chunks can be summed: the extra terms are +0.0
