@@ -10,11 +10,12 @@
 // One step:
 //
 //   bounds     (default mode) every scored candidate leaves a limit: the
-//              centroids' cumulative drift at that time plus the gap between
-//              the distance to its centroid and to the nearest other one.
-//              While the drift stays below the limit the candidate provably
-//              keeps its cluster and is not scored; the others are packed
-//              into dense tiles of 32.
+//              cumulative drift of its cluster (its centroid's moves plus the
+//              largest move of another centroid) at that time plus the gap
+//              between the distance to its centroid and to the nearest other
+//              one.  While that drift stays below the limit the candidate
+//              provably keeps its cluster and is not scored; the others are
+//              packed into dense tiles of 32.
 //   A  score   fast scores s_j = |c_j|^2 - 2 x.c_j for every centroid, the best
 //              and second-best per candidate, and a proved error bound E.
 //              If second - best > 2E the winner is certain; otherwise the
@@ -389,24 +390,30 @@ __device__ __forceinline__ float renew_rows(float* cent, float* cn, bf16x8* aop,
 }
 
 // Distance bounds.  When a candidate is scored, ub >= distance to its nearest
-// centroid and lb <= distance to every other centroid are known; its slack is
-// lb - ub.  If afterwards the centroids move, the nearest centroid b gets at most
-// sum delta_b closer/farther and any other centroid j at most sum delta_j, and
-// delta_b + delta_j never exceeds the two largest moves of a step.  So while
-//     slack > sum over the steps since scoring of (largest + second largest move)
-// the candidate's nearest centroid is unchanged and strictly nearest.  A tile of
-// 32 candidates keeps one number in LDS: (cumulative drift when it was scored) +
-// (smallest slack in the tile), rounded down; the cumulative drift is rounded up
-// at every step.  A tile whose number still exceeds the drift is not scored, and
-// not even fetched.  No per-candidate bound is stored anywhere.
+// centroid b and lb <= distance to every other centroid are known; its slack is
+// lb - ub.  If afterwards the centroids move, b gets at most sum delta_b farther
+// and any other centroid at most sum (largest move of a centroid other than b)
+// closer.  So while
+//     slack > T_b = sum over the steps since scoring of
+//                   (delta_b + largest move of another centroid)
+// the candidate's nearest centroid is unchanged and strictly nearest.  Two clocks
+// are kept, both rounded up at every step: the drift of every cluster, T_j, and
+// the drift of the search, sum of (largest + second largest move), which no T_j
+// outruns.  A candidate's limit is T_b at its scoring + its slack, rounded down,
+// and is tested against T_b; a tile of 32 candidates keeps one number in LDS in
+// the search's clock - the smallest of (drift + what a candidate has left) - so a
+// tile whose number still exceeds the drift is not scored, not fetched and its
+// limits not even read.
 __device__ __forceinline__ float slack_of(float best, float second, float xn, float E) {
     // A >= d_best^2 and B <= d_other^2 (room for the rounding of |x|^2 included), and
-    // sqrt(B) - sqrt(A) = (B - A) / (sqrt(B) + sqrt(A)) >= (B - A) / (2 sqrt(B)):
-    // one reciprocal square root (good to an ulp), the result rounded down
+    // sqrt(B) - sqrt(A) = (B - A) / (sqrt(B) + sqrt(A)): two square roots and a
+    // reciprocal, each good to an ulp, the result rounded down by far more than their
+    // errors add up to.  (The cheaper (B - A) / (2 sqrt(B)) is a lower bound too, but up
+    // to half as large: 3 % more candidates were scored with it.)
     const float Eb = E + 4.0e-6f * xn;
     const float A = fmaxf(best + xn + Eb, 0.f);
     const float B = second + xn - Eb;
-    const float sl = (B - A) * 0.5f * __builtin_amdgcn_rsqf(B) * 0.999999f;
+    const float sl = (B - A) * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(B) + __builtin_amdgcn_sqrtf(A)) * 0.999998f;
     return B > A ? sl : 0.f;
 }
 // minimum over lanes 0..31, delivered to every lane of the wave
@@ -571,7 +578,7 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
                                             int fsh, long long* sums, int* cnt,
                                             int* nflag, unsigned short* flist, const bf16x8* aop, unsigned char* dirty,
                                             float* thr, float2* __restrict__ lim,
-                                            unsigned short* queue, float drift) {
+                                            unsigned short* queue, float drift, float T) {
     const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
     const int m = lane & 31, h = lane >> 5;
     const int mtiles = (K + 31) >> 5;
@@ -675,6 +682,9 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
             }
             while (pt - ph >= kMoverBatch) drain(kMoverBatch);
         }
+        // the candidate's limit counts in its own cluster's drift, the tile's number in
+        // the search's (which grows at least as fast)
+        const float Tb = __shfl(T, bi);
         if (valid && h == 0) {
             if (!certain) {
                 // (the exact pass sets cluster and limit of the candidates it decides)
@@ -682,9 +692,10 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
                 const int pos = atomicAdd(nflag, 1);
                 if (pos < kFlagCap) flist[pos] = (unsigned short)p;     // (N_g <= 65536 on this path)
             } else {
-                const float L = a.use_bounds ? limit_of(tile_limit(drift, slack_of(best, second, xn, E))) : 0.f;
-                lim[p].x = pack_limit(L, bi);
-                if (a.use_bounds) atomicMin(reinterpret_cast<unsigned*>(&thr[p >> 5]), __float_as_uint(L));
+                const float sl = slack_of(best, second, xn, E);
+                lim[p].x = pack_limit(a.use_bounds ? tile_limit(Tb, sl) : 0.f, bi);
+                if (a.use_bounds)
+                    atomicMin(reinterpret_cast<unsigned*>(&thr[p >> 5]), __float_as_uint(tile_limit(drift, sl)));
             }
         }
         if (__any(valid && !certain)) any |= 2;
@@ -702,7 +713,7 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
         // the next two tiles to look at, one for each half-wave, and this lane's
         // candidate in them; its limit is requested one pair ahead
         // (no branch around the request: with none left it reads the first limit again)
-        auto take_pair = [&](bool& have, int& c0, int& c1, int& p, bool& in, float& lv) {
+        auto take_pair = [&](bool& have, int& c0, int& c1, int& p, bool& in, float& lv) {   // lv: the raw state word
             have = act != 0;
             c0 = have ? __ffsll((long long)act) - 1 : 0;
             act &= act - 1;
@@ -712,7 +723,7 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
             const int tl = wid + kWaves * (i0 + (myc >= 0 ? myc : c0));
             p = tl * 32 + m;
             in = have && myc >= 0 && p < ng;
-            lv = limit_of(lim[in ? p : 0].x);
+            lv = lim[in ? p : 0].x;
         };
         bool have, in;
         int c0, c1, p;
@@ -725,10 +736,16 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
             take_pair(haven, c0n, c1n, pn, inn, lvn);
             bool active = in;
             if (a.use_bounds) {
-                active = in && !(lv > drift);
-                // what the tile's number becomes: the smallest limit among the candidates
-                // that stay as they are (the scored ones lower it again)
-                float keep = (in && !active) ? lv : INFINITY;
+                // at risk once the drift of the candidate's own cluster has reached its limit
+                const int cl = cluster_of(lv);
+                const float Ta = __shfl(T, cl < 0 ? 0 : cl);
+                const float lc = limit_of(lv);
+                active = in && !(lc > Ta);
+                // what the tile's number becomes: the smallest of the limits of the
+                // candidates that stay as they are, each restated in the search's drift
+                // (drift now + what the candidate has left, rounded down; the scored ones
+                // lower the number again)
+                float keep = (in && !active) ? tile_limit(drift, (lc - Ta) * 0.9999995f) : INFINITY;
                 keep = row_min_f(keep);
                 const float k0 = vmin(lane_f(keep, 0), lane_f(keep, 16));
                 const float k1 = vmin(lane_f(keep, 32), lane_f(keep, 48));
@@ -957,7 +974,7 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
                                              int n0, int n, const unsigned short* flist, int K, int D, int DP,
                                              int SP, const float* cent, int fsh,
                                              long long* sums, int* cnt, unsigned char* dirty, float* thr,
-                                             float2* __restrict__ lim, float drift) {
+                                             float2* __restrict__ lim, float drift, float T) {
     const int lane = threadIdx.x & 63, wid = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform)
     const int lc = lane < D ? lane : 0;
     const float eps = 2.f * (float)(D + 2) * 5.9604644775390625e-08f;
@@ -1062,13 +1079,14 @@ __device__ __forceinline__ int refine_listed(const ClusterArgs& a, const float* 
             lbd = (float)sqrt(sd) * 0.9999995f;
         }
         bj = bj < K ? bj : 0;
+        const float Tb = __shfl(T, bj);
         if (lane == 0) {
             // the slack is the difference of the bounds, rounded down; limits are
             // non-negative floats, which order like their bit patterns
             const float sl = fmaxf((lbd - ub) * 0.9999995f, 0.f);
-            const float L = a.use_bounds ? limit_of(tile_limit(drift, sl)) : 0.f;
-            lim[p].x = pack_limit(L, bj);
-            if (a.use_bounds) atomicMin(reinterpret_cast<unsigned*>(&thr[p >> 5]), __float_as_uint(L));
+            lim[p].x = pack_limit(a.use_bounds ? tile_limit(Tb, sl) : 0.f, bj);
+            if (a.use_bounds)
+                atomicMin(reinterpret_cast<unsigned*>(&thr[p >> 5]), __float_as_uint(tile_limit(drift, sl)));
             a.a_new[(size_t)n0 + p] = bj;          // no longer waiting for the exact pass
         }
         old = (old >= 0 && old < K) ? old : -1;
@@ -1288,6 +1306,7 @@ __global__ void __launch_bounds__(NT, NT == kThreadsNarrow ? 3 : 1) cluster_fuse
 
     bool first = true;
     float drift = 0.f;          // cumulative (largest + second largest) centroid move, rounded up
+    float Tc = 0.f;             // lane j: cumulative (move of centroid j + largest move of another), rounded up
     for (int it = 0; it < a.iters; ++it) {
         if constexpr (MT > 0) {
             if (a.use_bounds && it > 0) {
@@ -1297,6 +1316,7 @@ __global__ void __launch_bounds__(NT, NT == kThreadsNarrow ? 3 : 1) cluster_fuse
                 const int jm = __ffsll((long long)__ballot(dj == d1)) - 1;
                 const float d2 = wave_max_f(lane == jm ? 0.f : dj);
                 drift = (drift + (d1 + d2) * 1.0000005f) * 1.0000005f;
+                Tc = (Tc + (dj + (lane == jm ? d2 : d1)) * 1.0000005f) * 1.0000005f;
             }
         }
         unsigned char* dw = dirty;        // rows touched in this step, for the renewal at its end
@@ -1332,7 +1352,7 @@ __global__ void __launch_bounds__(NT, NT == kThreadsNarrow ? 3 : 1) cluster_fuse
                 }
             } else
             st = score_packed<DS, MT, NT>(a, Xg, n0, ng, K, D, DP, SP, cent, cn, cm, fsh, sums, cnt,
-                                      nflag, flist, aop, dw, thr, lim, queue, drift);
+                                      nflag, flist, aop, dw, thr, lim, queue, drift, Tc);
         } else {
             score_valu<4 * DS, NT>(a, Xg, n0, ng, K, D, DP, cent, cn, cm);
             st = 2;
@@ -1343,7 +1363,7 @@ __global__ void __launch_bounds__(NT, NT == kThreadsNarrow ? 3 : 1) cluster_fuse
             const int nf = MT > 0 ? *nflag : kFlagCap + 1;
             if (nf <= kFlagCap) {
                 moved = refine_listed<DS, NT>(a, Xg, n0, nf, flist, K, D, DP, SP, cent, fsh, sums, cnt, dw,
-                                      thr, lim, drift);
+                                      thr, lim, drift, Tc);
             } else {
                 // the list overflowed (or the vector-ALU scorer ran): scan every candidate;
                 // no slack is known for the refined ones, so every tile is scored next time
