@@ -1507,7 +1507,9 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     a.Nmax = one_wg_nmax(b);
     // few searches: every workgroup has a compute unit to itself and takes the wide shape
     const size_t lds_wide = lds_layout(a.Kmax, b.D, 16 * ds + 4, a.Nmax, kThreadsWide / kWave).total;
-    const bool wide = b.G <= kWideMaxG && lds_wide <= kMaxLds;
+    // ... and so does a batch of long searches only (2048 candidates or more on average):
+    // measured 13-20 % faster than three of them sharing a compute unit
+    const bool wide = (b.G <= kWideMaxG || b.N >= (int64_t)2048 * b.G) && lds_wide <= kMaxLds;
     const size_t lds = wide ? lds_wide
                             : lds_layout(a.Kmax, b.D, 16 * ds + 4, a.Nmax, kThreadsNarrow / kWave).total;
     if (lds > kMaxLds) return hipErrorInvalidValue;

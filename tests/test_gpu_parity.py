@@ -64,6 +64,8 @@ SMALL = {
     # more searches than compute units: the one-workgroup kernel takes its 256-thread
     # shape (batches of up to 256 searches run 768 threads per search)
     "manysmall": lambda: synth.config5(G=300, nmin=64, nmax=260, D=16, S=4, iters=8, seed=123),
+    # more searches than compute units, all of them long: the 768-thread shape again
+    "manylong": lambda: synth.config5(G=258, nmin=2048, nmax=2100, D=8, S=4, iters=3, seed=321),
     "lateoutliers": _late_outliers,
     # the longest search the one-workgroup path takes: candidate numbers up to 2^16 - 1
     "long1wg": lambda: synth.config2(N=65536, D=16, K=24, S=4, iters=6, seed=11),
