@@ -77,3 +77,39 @@ def test_round_over_shapes(kb, D, scorer, many):
     assert got["counts"].sum() == b.N
     kg = np.diff(b.koff)[search_of(b.seg_off)]
     assert ((got["assign"] >= 0) & (got["assign"] < kg)).all()
+
+
+# cluster counts of the multi-workgroup path: one to four centroid groups of 64, whole
+# and partly filled
+BIG_KS = (65, 100, 128, 129, 192, 193, 255, 256)
+
+
+def _big_batch(D, seed):
+    rng = np.random.default_rng(seed)
+    b = None
+    for i, K in enumerate(BIG_KS):
+        n = int(rng.integers(4 * K + 1, 12 * K))
+        one = synth.config2(seed=seed * 100 + i, N=n, D=D, K=K, S=4, iters=4)
+        b = one if b is None else synth.concat(b, one, f"sweepbigD{D}")
+    return b
+
+
+@pytest.mark.parametrize("D", [4, 6, 20, 36, 48, 64])
+@pytest.mark.parametrize("scorer", [0, 1], ids=["matrixcore", "vectoralu"])
+def test_multi_workgroup_clustering_over_shapes(kb, D, scorer):
+    import torch
+    b = _big_batch(D, seed=2000 + D)
+    d = kb.DeviceBatch(b, scorer=scorer)
+    d.cluster()
+    torch.cuda.synchronize()
+    ora = oracle.cluster(b.seg_off, b.koff, b.X, b.iters)
+    got = {k: d.host(k) for k in ("assign", "cent", "counts", "objective")}
+    clean = ora.dirty == 0
+    assert clean.sum() >= b.G - 3, f"D={D}: only {clean.sum()} of {b.G} searches without a near-tie"
+    cp = clean[search_of(b.seg_off)]
+    ck = np.repeat(clean, np.diff(b.koff))
+    np.testing.assert_array_equal(got["assign"][cp], ora.assign[cp])
+    np.testing.assert_array_equal(got["counts"][ck], ora.counts[ck])
+    assert_cent_close(got["cent"][ck], ora.cent[ck], f"D={D}")
+    assert_rel_close(got["objective"][clean], ora.objective[clean], what=f"D={D} objective")
+    assert got["counts"].sum() == b.N
