@@ -314,6 +314,17 @@ def main():
             cfgs[f"config{c}"] = e
             del dc, bc
             torch.cuda.empty_cache()
+        # the scale the paper itself runs: 183 searches of 12-41 candidates, 5 features,
+        # K = 3, |S| = 6, ten Lloyd steps
+        bp = synth.paper_scale()
+        dp = kb.DeviceBatch(bp, device=dev)
+        for _ in range(3):
+            dp.round()
+        torch.cuda.synchronize()
+        _, p_med = timed(dp.round, 50)
+        cfgs["paper_scale"] = {"N": bp.N, "G": bp.G, "D": bp.D, "Kmax": bp.Kmax, "S": bp.S,
+                               "iters": bp.iters, "round_us": round(p_med * 1e3, 1), "bound": "latency"}
+        del dp, bp
         out["configs"] = cfgs
 
     if not args.no_cpu_baseline:

@@ -207,11 +207,11 @@ def config4(seed: Optional[int] = None, N=1 << 20, D=64, K=256, S=4, iters=10,
 
 
 def config5(seed: Optional[int] = None, G=4096, nmin=64, nmax=4096, D=48, S=32,
-            iters=20, kcap=64) -> Batch:
+            iters=20, kcap=64, kdiv=16) -> Batch:
     rng = np.random.default_rng(BASE_SEED + 5 if seed is None else seed)
     ng = np.rint(np.exp(rng.uniform(math.log(nmin), math.log(nmax), size=G)))
     ng = np.clip(ng, nmin, nmax).astype(np.int64)
-    kg = np.minimum(kcap, ng // 16).astype(np.int64)
+    kg = np.minimum(kcap, ng // kdiv).astype(np.int64)
     kg = np.maximum(kg, 1)
     seg_off = np.concatenate([[0], np.cumsum(ng)])
     koff = np.concatenate([[0], np.cumsum(kg)])
@@ -225,6 +225,16 @@ def config5(seed: Optional[int] = None, G=4096, nmin=64, nmax=4096, D=48, S=32,
         X[seg_off[g]:seg_off[g + 1]] = _features_gauss(
             r, int(ng[g]), D, k, sigma=sigma, weights=w)
     return _finish("config5", rng, seg_off, koff, X, D, S, iters)
+
+
+def paper_scale(seed: int = 11, G=183) -> Batch:
+    """A batch at the scale the paper itself runs (Sec. 3.6 and its experimental
+    setup: 183 benchmark kernels, one search each, a frontier that grows by one kernel
+    per iteration up to T = 40, K = 3 clusters, |S| = 6 strategies, a handful of
+    profiler features)."""
+    b = config5(seed=seed, G=G, nmin=12, nmax=41, D=5, S=6, iters=10, kcap=3, kdiv=4)
+    b.name = "paper_scale"
+    return b
 
 
 def paper_shape(seed: int = 7, N=21, D=5, K=3, S=6, iters=10) -> Batch:

@@ -60,6 +60,8 @@ SMALL = {
     "cfg3s": lambda: synth.config3(G=48),
     "cfg5s": lambda: synth.config5(G=96),
     "paper": lambda: synth.paper_shape(),
+    # 183 searches of 12 to 41 candidates, 5 features, 3 clusters, 6 strategies
+    "paperscale": lambda: synth.paper_scale(),
     "ragged": lambda: synth.config5(G=17, nmin=64, nmax=700, D=20, S=6, seed=99),
     # more searches than compute units: the one-workgroup kernel takes its 256-thread
     # shape (batches of up to 256 searches run 768 threads per search)
