@@ -135,10 +135,9 @@ enum {
      * path (K_g <= 64 and N_g <= 65536; chosen search by search) also keep distance
      * bounds: a candidate whose nearest centroid provably cannot have changed
      * since it was last scored (triangle inequality on how far the centroids
-     * moved) is not scored again, the others are packed into dense tiles.  On
-     * that path the matrix cores need D to be a multiple of 4 (rows are fetched
-     * in 16-byte pieces); batches with another D run the vector-ALU kernels in
-     * every mode: same results, several times slower. */
+     * moved) is not scored again, the others are packed into dense tiles.  Rows
+     * are fetched in 16-byte pieces when D is a multiple of 4 and feature by
+     * feature otherwise (about a third slower). */
     KB_SCORER_DEFAULT = 0,
     /* fp32 fused multiply-adds on the vector ALU, every candidate scored in every
      * step: the reference the matrix-core scorers are measured against. */

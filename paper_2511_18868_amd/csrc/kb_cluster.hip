@@ -21,8 +21,7 @@
 //              If second - best > 2E the winner is certain; otherwise the
 //              candidate is listed for exact re-evaluation.  Two scorers:
 //              matrix cores (bf16 x 3 split products, fp32 accumulate) for
-//              K <= 64 and D a multiple of 4, a vector-ALU fp32 FMA chain
-//              otherwise.
+//              K <= 64, a vector-ALU fp32 FMA chain otherwise.
 //   R  refine  listed candidates get their squared distances in fp64, direct
 //              difference form, summed over the features in index order with
 //              separate multiply and add - exactly the plain definition - and
@@ -568,10 +567,10 @@ __device__ __forceinline__ void tile_scores(const bf16x8 (&Bh)[DS], const bf16x8
 // per half-wave), reads their candidates' limits, and appends those the drift has
 // reached to a small queue in LDS; whenever 32 are waiting they are scored as one
 // tile of the matrix instruction, each lane fetching its own candidate's fp32 row
-// (16-byte pieces; D is a multiple of 4 here) and splitting it into the bf16
+// (in 16-byte pieces when D is a multiple of 4) and splitting it into the bf16
 // operands in registers.  A tile in which a third of the candidates are at risk
 // thus costs a third of a scoring instead of a whole one.
-template <int DS, int MT, int NT>
+template <int DS, int MT, int NT, bool VEC>
 __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* __restrict__ Xg,
                                             int n0, int ng, int K, int D, int DP, int SP,
                                             const float* cent, const float* cn, float cnmax,
@@ -638,8 +637,19 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
                 const int d0 = 16 * s + 8 * h;
                 r0[s] = make_float4(0.f, 0.f, 0.f, 0.f);
                 r1[s] = r0[s];
-                if (d0 < D) r0[s] = *reinterpret_cast<const float4*>(xr + d0);
-                if (d0 + 4 < D) r1[s] = *reinterpret_cast<const float4*>(xr + d0 + 4);
+                if constexpr (VEC) {
+                    if (d0 < D) r0[s] = *reinterpret_cast<const float4*>(xr + d0);
+                    if (d0 + 4 < D) r1[s] = *reinterpret_cast<const float4*>(xr + d0 + 4);
+                } else {
+                    if (d0 + 0 < D) r0[s].x = xr[d0 + 0];
+                    if (d0 + 1 < D) r0[s].y = xr[d0 + 1];
+                    if (d0 + 2 < D) r0[s].z = xr[d0 + 2];
+                    if (d0 + 3 < D) r0[s].w = xr[d0 + 3];
+                    if (d0 + 4 < D) r1[s].x = xr[d0 + 4];
+                    if (d0 + 5 < D) r1[s].y = xr[d0 + 5];
+                    if (d0 + 6 < D) r1[s].z = xr[d0 + 6];
+                    if (d0 + 7 < D) r1[s].w = xr[d0 + 7];
+                }
             }
 #pragma unroll
             for (int s = 0; s < DS; ++s) {
@@ -777,7 +787,7 @@ __device__ __forceinline__ int score_packed(const ClusterArgs& a, const float* _
 // the fixed-point sums from the same registers; |x|^2 and the drift limit of every
 // candidate go to the workspace for the steps that follow.  Returns max |x| over the rows this thread saw in
 // `am_out`, which the caller checks against the estimate the scale was taken from.
-template <int DS, int MT, int NT>
+template <int DS, int MT, int NT, bool VEC>
 __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __restrict__ Xg,
                                            int n0, int ng, int K, int D,
                                            int SP, const float* cn, float cnmax, int fsh,
@@ -794,13 +804,12 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
     // (kb_cluster_step) stores none of them
     const bool later = a.iters > 1;
 
-    // this lane's 8 features of every 16-feature step of row `tile * 32 + m`, in
-    // 16-byte pieces (D is a multiple of 4 here)
+    // this lane's 8 features of every 16-feature step of row `tile * 32 + m`
     auto load_rows = [&](int tile, float4 (&r)[DS][2]) {
         const int p = tile * 32 + m;
         const bool valid = p < ng;
         const float* xr = Xg + (size_t)(valid ? p : 0) * D;
-        if (D == 16 * DS && tile * 32 + 32 <= ng) {
+        if (VEC && D == 16 * DS && tile * 32 + 32 <= ng) {
             // (uniform) a whole tile of rows without padding: nothing to guard
 #pragma unroll
             for (int s = 0; s < DS; ++s) {
@@ -814,8 +823,19 @@ __device__ __forceinline__ int score_first(const ClusterArgs& a, const float* __
             const int d0 = 16 * s + 8 * h;
             r[s][0] = make_float4(0.f, 0.f, 0.f, 0.f);
             r[s][1] = r[s][0];
-            if (valid && d0 < D) r[s][0] = *reinterpret_cast<const float4*>(xr + d0);
-            if (valid && d0 + 4 < D) r[s][1] = *reinterpret_cast<const float4*>(xr + d0 + 4);
+            if constexpr (VEC) {
+                if (valid && d0 < D) r[s][0] = *reinterpret_cast<const float4*>(xr + d0);
+                if (valid && d0 + 4 < D) r[s][1] = *reinterpret_cast<const float4*>(xr + d0 + 4);
+            } else if (valid) {
+                if (d0 + 0 < D) r[s][0].x = xr[d0 + 0];
+                if (d0 + 1 < D) r[s][0].y = xr[d0 + 1];
+                if (d0 + 2 < D) r[s][0].z = xr[d0 + 2];
+                if (d0 + 3 < D) r[s][0].w = xr[d0 + 3];
+                if (d0 + 4 < D) r[s][1].x = xr[d0 + 4];
+                if (d0 + 5 < D) r[s][1].y = xr[d0 + 5];
+                if (d0 + 6 < D) r[s][1].z = xr[d0 + 6];
+                if (d0 + 7 < D) r[s][1].w = xr[d0 + 7];
+            }
         }
     };
 
@@ -1191,7 +1211,9 @@ __host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP, int Nmax, int
 
 // DS = feature K-steps of 16 (D <= 16*DS); MT = centroid tiles of 32 held in
 // registers by the matrix-core scorer, MT = 0 selects the vector-ALU scorer.
-template <int DS, int MT, int NT>
+// VEC: D is a multiple of 4, so the matrix-core scorers fetch rows in 16-byte pieces;
+// otherwise (a compile-time choice, so the loops hold one form only) feature by feature.
+template <int DS, int MT, int NT, bool VEC = true>
 __global__ void __launch_bounds__(NT, NT == kThreadsNarrow ? 3 : 1) cluster_fused_kernel(ClusterArgs a) {
     constexpr int kThreads = NT, kWaves = NT / kWave;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -1236,12 +1258,15 @@ __global__ void __launch_bounds__(NT, NT == kThreadsNarrow ? 3 : 1) cluster_fuse
     // fixed-point scale is estimated
     float am = 0.f;
     if constexpr (MT > 0) {
-        // (D is a multiple of 4 on this path: rows are 16-byte aligned)
         const int srows = ng < 64 ? ng : 64;
-        const int quads = srows * (D >> 2);
-        for (int i = tid; i < quads; i += kThreads) {
-            const float4 v = reinterpret_cast<const float4*>(Xg)[i];
-            am = fmaxf(fmaxf(am, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+        if constexpr (VEC) {
+            const int quads = srows * (D >> 2);
+            for (int i = tid; i < quads; i += kThreads) {
+                const float4 v = reinterpret_cast<const float4*>(Xg)[i];
+                am = fmaxf(fmaxf(am, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+            }
+        } else {
+            for (int i = tid; i < srows * D; i += kThreads) am = fmaxf(am, fabsf(Xg[i]));
         }
     }
     for (int idx = tid; idx < K * DP; idx += kThreads) {
@@ -1325,7 +1350,7 @@ __global__ void __launch_bounds__(NT, NT == kThreadsNarrow ? 3 : 1) cluster_fuse
         if constexpr (MT > 0) {
             if (first) {
                 float am_seen;
-                st = score_first<DS, MT, NT>(a, Xg, n0, ng, K, D, SP, cn, cm, fsh, sums, cnt, nflag,
+                st = score_first<DS, MT, NT, VEC>(a, Xg, n0, ng, K, D, SP, cn, cm, fsh, sums, cnt, nflag,
                                          flist, aop, dw, thr, lim, am_seen, tsq);
                 am_seen = block_max_f<kWaves>(am_seen, red, phase);
                 tsq = block_sum_d<kWaves>(tsq, red, phase);
@@ -1351,7 +1376,7 @@ __global__ void __launch_bounds__(NT, NT == kThreadsNarrow ? 3 : 1) cluster_fuse
                     __syncthreads();
                 }
             } else
-            st = score_packed<DS, MT, NT>(a, Xg, n0, ng, K, D, DP, SP, cent, cn, cm, fsh, sums, cnt,
+            st = score_packed<DS, MT, NT, VEC>(a, Xg, n0, ng, K, D, DP, SP, cent, cn, cm, fsh, sums, cnt,
                                       nflag, flist, aop, dw, thr, lim, queue, drift, Tc);
         } else {
             score_valu<4 * DS, NT>(a, Xg, n0, ng, K, D, DP, cent, cn, cm);
@@ -1505,20 +1530,21 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
 
     const int ds = (b.D + 15) / 16;   // 1..4 K-steps of 16 features
     a.Nmax = one_wg_nmax(b);
+    int mt = a.Kmax <= 32 ? 1 : (a.Kmax <= 64 ? 2 : 0);
+    if (c.scorer == 1) mt = 0;
+    // the matrix-core kernels fetch rows in 16-byte pieces when D is a multiple of 4 and
+    // feature by feature otherwise (own instantiations, in the 256-thread shape only)
+    const bool vec = (b.D & 3) == 0;
     // few searches: every workgroup has a compute unit to itself and takes the wide shape
     const size_t lds_wide = lds_layout(a.Kmax, b.D, 16 * ds + 4, a.Nmax, kThreadsWide / kWave).total;
     // ... and so does a batch of long searches only (2048 candidates or more on average):
     // measured 13-20 % faster than three of them sharing a compute unit
-    const bool wide = (b.G <= kWideMaxG || b.N >= (int64_t)2048 * b.G) && lds_wide <= kMaxLds;
+    const bool wide = (vec || mt == 0) && (b.G <= kWideMaxG || b.N >= (int64_t)2048 * b.G) && lds_wide <= kMaxLds;
     const size_t lds = wide ? lds_wide
                             : lds_layout(a.Kmax, b.D, 16 * ds + 4, a.Nmax, kThreadsNarrow / kWave).total;
     if (lds > kMaxLds) return hipErrorInvalidValue;
-    int mt = a.Kmax <= 32 ? 1 : (a.Kmax <= 64 ? 2 : 0);
-    if (c.scorer == 1) mt = 0;
-    // (the matrix-core kernels fetch rows in 16-byte pieces: feature counts that are not
-    // a multiple of 4 take the vector-ALU kernels, whose results are the same)
-    if ((b.D & 3) != 0) mt = 0;
     const dim3 grid((unsigned)b.G), block(wide ? kThreadsWide : kThreadsNarrow);
+#define KB_NARROW_SCALAR kThreadsNarrow, false
 #define KB_LAUNCH_NT(DS_, MT_, NT_)                                                             \
     do {                                                                                        \
         hipError_t e = hipFuncSetAttribute(                                                     \
@@ -1527,16 +1553,22 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
         if (e != hipSuccess) return e;                                                          \
         hipLaunchKernelGGL((cluster_fused_kernel<DS_, MT_, NT_>), grid, block, lds, st, a);     \
     } while (0)
-#define KB_LAUNCH(DS_, MT_)                                                                     \
+#define KB_LAUNCH_MATRIX(DS_, MT_)                                                              \
     do {                                                                                        \
         if (wide) KB_LAUNCH_NT(DS_, MT_, kThreadsWide);                                         \
-        else KB_LAUNCH_NT(DS_, MT_, kThreadsNarrow);                                            \
+        else if (vec) KB_LAUNCH_NT(DS_, MT_, kThreadsNarrow);                                   \
+        else KB_LAUNCH_NT(DS_, MT_, KB_NARROW_SCALAR);                                          \
+    } while (0)
+#define KB_LAUNCH_VECTOR_ALU(DS_)                                                               \
+    do {                                                                                        \
+        if (wide) KB_LAUNCH_NT(DS_, 0, kThreadsWide);                                           \
+        else KB_LAUNCH_NT(DS_, 0, kThreadsNarrow);                                              \
     } while (0)
 #define KB_LAUNCH_DS(DS_)                                                                       \
     do {                                                                                        \
-        if (mt == 1) KB_LAUNCH(DS_, 1);                                                         \
-        else if (mt == 2) KB_LAUNCH(DS_, 2);                                                    \
-        else KB_LAUNCH(DS_, 0);                                                                 \
+        if (mt == 1) KB_LAUNCH_MATRIX(DS_, 1);                                                  \
+        else if (mt == 2) KB_LAUNCH_MATRIX(DS_, 2);                                             \
+        else KB_LAUNCH_VECTOR_ALU(DS_);                                                         \
     } while (0)
     switch (ds) {
         case 1: KB_LAUNCH_DS(1); break;
@@ -1545,8 +1577,10 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
         default: KB_LAUNCH_DS(4); break;
     }
 #undef KB_LAUNCH_DS
-#undef KB_LAUNCH
+#undef KB_LAUNCH_VECTOR_ALU
+#undef KB_LAUNCH_MATRIX
 #undef KB_LAUNCH_NT
+#undef KB_NARROW_SCALAR
     return hipGetLastError();
 }
 

@@ -44,7 +44,7 @@ def _batch(D, S, seed, many=False):
 
 
 # feature counts: one to four 16-feature steps, with and without padding; 6 and 17
-# are not multiples of 4 and take the vector-ALU kernels
+# are not multiples of 4: rows are then fetched feature by feature
 @pytest.mark.parametrize("D", [4, 6, 8, 12, 16, 17, 20, 28, 32, 36, 44, 48, 52, 60, 64])
 @pytest.mark.parametrize("scorer", [0, 2], ids=["bounds", "matrixcore"])
 @pytest.mark.parametrize("many", [False, True], ids=["few", "many"])
