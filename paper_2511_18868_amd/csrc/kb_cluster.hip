@@ -60,7 +60,8 @@ struct ClusterArgs {
     const int32_t* order;
     int use_bounds;
     int guard;         // leave searches with N_g < 2 K_g as they are (re-clustering rule of Alg. 1)
-    int mixed;         // leave searches of the multi-workgroup path (K_g > 64 or N_g > 65536) alone
+    int mixed;         // leave searches of the multi-workgroup path (K_g > 64 or N_g > limit_n) alone
+    int limit_n;       // most candidates of a search this kernel takes in this batch
     float2* lim;       // [N] state of every candidate: .x its drift limit (drift at its last scoring + its
                        //     slack) with its cluster + 1 in the 7 lowest bits, .y its |x|^2
 };
@@ -1226,7 +1227,7 @@ __global__ void __launch_bounds__(NT, NT == kThreadsNarrow ? 3 : 1) cluster_fuse
     g = clampi(g, 0, a.G - 1);
     int n0, ng, k0, K;
     search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
-    if (a.mixed && search_is_big(ng, K)) return;      // the multi-workgroup kernels take this search
+    if (a.mixed && search_is_big(ng, K, a.limit_n)) return;      // the multi-workgroup kernels take this search
     if (K > a.Kmax) K = a.Kmax;   // LDS is sized from the host copy of Kmax
     if (ng > a.Nmax) ng = a.Nmax; // (and of Nmax; a consistent batch never gets here)
     if (MT > 0 && K > 32 * MT) K = 32 * MT;
@@ -1509,7 +1510,7 @@ constexpr size_t kMaxLds = 160 * 1024;
 
 // sizes the one-workgroup kernel is laid out for: the largest search it will take
 static int one_wg_kmax(const kb_batch& b) { return b.Kmax > kOneWgMaxK ? kOneWgMaxK : (b.Kmax > 0 ? b.Kmax : 1); }
-static int one_wg_nmax(const kb_batch& b) { return b.Nmax > kOneWgMaxN ? kOneWgMaxN : b.Nmax; }
+static int one_wg_nmax(const kb_batch& b) { return b.Nmax > one_wg_limit_n(b) ? one_wg_limit_n(b) : b.Nmax; }
 
 bool cluster_supported(const kb_batch& b) {
     const int ds = (b.D + 15) / 16;
@@ -1526,6 +1527,7 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     a.use_bounds = c.scorer != 2;
     a.guard = c.guard;
     a.mixed = c.mixed;
+    a.limit_n = one_wg_limit_n(b);
     a.lim = reinterpret_cast<float2*>(c.lim);
 
     const int ds = (b.D + 15) / 16;   // 1..4 K-steps of 16 features

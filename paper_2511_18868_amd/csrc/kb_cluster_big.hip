@@ -37,6 +37,7 @@ constexpr int kWaves = kThreads / kWave;
 struct BigArgs {
     int G, D, Ksum, Kmax, Kpad, it, final_pass;
     int guard;              // 1: searches with N_g < 2 K_g are left as they are
+    int limit_n;            // searches of up to this many candidates (and 64 clusters) are the one-workgroup kernel's
     int mixed;              // 1: searches of the one-workgroup path (K_g <= 64, N_g <= 65536) are left to it
     int64_t N, max_tiles;
     const int32_t* seg_off;
@@ -70,7 +71,7 @@ struct BigArgs {
 
 // searches this launch sequence leaves untouched
 __device__ __forceinline__ bool skipped(const BigArgs& a, int ng, int K) {
-    return (a.guard && ng < 2 * K) || (a.mixed && !search_is_big(ng, K));
+    return (a.guard && ng < 2 * K) || (a.mixed && !search_is_big(ng, K, a.limit_n));
 }
 
 // largest g with off[g] <= v (off non-decreasing, off[0] = 0, v < off[G])
@@ -140,7 +141,7 @@ __global__ void __launch_bounds__(kThreads) big_presplit(BigArgs a) {
     search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
     const int tile = (int)(gt - a.tile_off[g]);
     if (tile * 32 >= ng) return;
-    if (a.mixed && !search_is_big(ng, K)) return;      // (the one-workgroup kernel splits its own rows)
+    if (a.mixed && !search_is_big(ng, K, a.limit_n)) return;      // (the one-workgroup kernel splits its own rows)
     const int D = a.D;
     const bool vec = (D & 3) == 0;
     const int p = tile * 32 + m;
@@ -1145,7 +1146,7 @@ hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const Big
                               hipStream_t st) {
     BigArgs a;
     a.G = b.G; a.D = b.D; a.Ksum = b.Ksum; a.Kmax = b.Kmax > 0 ? b.Kmax : 1; a.Kpad = w.kpad;
-    a.it = 0; a.final_pass = 0; a.guard = c.guard; a.mixed = c.mixed; a.N = b.N; a.max_tiles = c.max_tiles;
+    a.it = 0; a.final_pass = 0; a.guard = c.guard; a.mixed = c.mixed; a.limit_n = one_wg_limit_n(b); a.N = b.N; a.max_tiles = c.max_tiles;
     a.seg_off = b.seg_off; a.koff = b.koff; a.X = c.X; a.cent_init = c.cent_init;
     a.assign = c.assign; a.cent = c.cent_out; a.counts = c.counts; a.objective = c.objective;
     a.tile_off = c.tile_off; a.chunk_off = reinterpret_cast<const int32_t*>(ws + w.chunk_off);

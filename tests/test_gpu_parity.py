@@ -70,7 +70,14 @@ SMALL = {
     "manylong": lambda: synth.config5(G=258, nmin=2048, nmax=2100, D=8, S=4, iters=3, seed=321),
     "lateoutliers": _late_outliers,
     # the longest search the one-workgroup path takes: candidate numbers up to 2^16 - 1
-    "long1wg": lambda: synth.config2(N=65536, D=16, K=24, S=4, iters=6, seed=11),
+    # (in a batch of more than 32 searches; with fewer, a search this long is spread over
+    # many workgroups)
+    "long1wg": lambda: synth.concat(synth.config2(N=65536, D=16, K=24, S=4, iters=6, seed=11),
+                                    synth.config5(G=40, nmin=20, nmax=90, D=16, S=4, iters=6, seed=12), "long1wg"),
+    # few searches, two of them long: those take the multi-workgroup path although they
+    # have no more than 64 clusters, the short ones the one-workgroup kernel
+    "fewlong": lambda: synth.concat(synth.config5(G=2, nmin=30000, nmax=30100, D=16, S=4, iters=5, seed=13),
+                                    synth.config5(G=6, nmin=300, nmax=900, D=16, S=4, iters=5, seed=14), "fewlong"),
     # shapes that take the multi-workgroup clustering path (more than 64 clusters,
     # or a search of more than 65536 candidates)
     "cfg4s": lambda: synth.config4(N=8192, K=256, ncentres=256),
@@ -86,7 +93,7 @@ SMALL = {
 # kb_cluster call because it saw a near-tie in one of the Lloyd steps.  The inputs
 # are seeded and the oracle is deterministic, so these are exact counts: an
 # exclusion set that grows fails the test.
-NEAR_TIE_SEARCHES = {"cfg3s": 1, "cfg5s": 4, "lateoutliers": 1}
+NEAR_TIE_SEARCHES = {"cfg3s": 1, "cfg5s": 4, "lateoutliers": 1, "fewlong": 3}
 
 
 @pytest.fixture(scope="module", params=[0, 1, 2], ids=["bounds", "vectoralu", "matrixcore"])
