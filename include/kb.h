@@ -136,7 +136,9 @@ enum {
      * chosen search by search) also keep distance
      * bounds: a candidate whose nearest centroid provably cannot have changed
      * since it was last scored (triangle inequality on how far the centroids
-     * moved) is not scored again, the others are packed into dense tiles.  Rows
+     * moved) is not scored again, the others are packed into dense tiles.  (A
+     * batch of searches of at most 64 candidates and 16 clusters runs one wave per
+     * search with exact fp32 / fp64 distances instead: same results.)  Rows
      * are fetched in 16-byte pieces when D is a multiple of 4 and feature by
      * feature otherwise (about a third slower). */
     KB_SCORER_DEFAULT = 0,

@@ -5,7 +5,8 @@
 //
 // Every scoring splits the fp32 feature rows it fetches into bf16 (hi, mid) pieces
 // on the fly; |x|^2, the cluster and the drift limit of every candidate share one
-// workspace array of 8 bytes per candidate.
+// workspace array of 8 bytes per candidate.  (Batches of very short searches run
+// one wave per search instead: cluster_wave_kernel at the end of this file.)
 //
 // One step:
 //
@@ -300,9 +301,12 @@ __device__ __forceinline__ double quad_sum_d(double v) {
 template <int DS, bool OPERANDS, int NT>
 __device__ __forceinline__ float renew_rows(float* cent, float* cn, bf16x8* aop, const long long* sums,
                                             const int* cnt, unsigned char* dirty, float* delta, int K, int D,
-                                            int SP, double inv, bool init, bool need_scores) {
+                                            int SP, double inv, bool init, bool need_scores,
+                                            int tid_in = -1) {
     constexpr int DP = 16 * DS + 4;
-    const int tid = threadIdx.x, q = tid & 3;
+    // (the caller's number among the NT threads that share the rows: the thread number in
+    // the workgroup unless a single wave works on rows of its own)
+    const int tid = tid_in >= 0 ? tid_in : (int)threadIdx.x, q = tid & 3;
     const int rows = init && OPERANDS ? ((K + 31) & ~31) : K;
     float cm = 0.f;
     for (int j0 = 0; j0 < rows; j0 += NT / 4) {
@@ -1504,6 +1508,247 @@ __global__ void __launch_bounds__(NT, NT == kThreadsNarrow ? 3 : 1) cluster_fuse
     for (int j = tid; j < K; j += kThreads) a.counts[k0 + j] = cnt[j];
 }
 
+// ---- very short searches: one wave per search --------------------------------------
+// A search of at most 64 candidates and 16 clusters - the size of a search in the
+// paper's own runs (Sec. 3.6: a frontier of a few dozen kernels, K = 3) - is one
+// wave's work: lane l keeps candidate l's row in registers for the whole call, the
+// search's centroids and fixed-point sums sit in the wave's own piece of LDS, and
+// since nothing is shared with another wave no step needs a workgroup barrier or a
+// block-wide reduction (what a step of a short search mostly consists of in the
+// kernel above).  Four searches per workgroup.
+//
+// A step: every lane decides its candidate exactly - fp32 direct-difference distances
+// (relative error <= (D + 2) 2^-24, sums of non-negative terms); if the two smallest
+// are further apart than twice that bound allows, the smallest is the unique nearest
+// centroid; otherwise fp64, summed over the features in index order with separate
+// multiply and add (the plain definition), lowest index on ties - and moves its row
+// between the fixed-point sums if the cluster changed.  Between scorings a lane
+// keeps an upper bound on the distance to its centroid and a lower bound on the
+// distance to any other; the first grows by its centroid's move, the second shrinks
+// by the largest move of another centroid, and while the first stays below the second
+// the candidate is not scored.  Centroids from the sums exactly as in the kernel
+// above (same grid, same rounding), so both give the same bytes.
+constexpr int kWaveMaxN = 64, kWaveMaxK = 16;
+
+struct WaveLds {
+    size_t sums, cent, cnt, delta, dirty, total;
+};
+__host__ __device__ inline WaveLds wave_lds_layout(int Kmax, int D, int DP) {
+    const int SP = D | 1;
+    WaveLds l;
+    size_t off = 0;
+    l.sums = off;  off += (size_t)Kmax * SP * 8;
+    off = (off + 15) & ~(size_t)15;
+    l.cent = off;  off += (size_t)Kmax * DP * 4;
+    l.cnt = off;   off += (size_t)Kmax * 4;
+    l.delta = off; off += (size_t)Kmax * 4;
+    l.dirty = off; off += ((size_t)Kmax + 15) & ~(size_t)15;
+    l.total = (off + 15) & ~(size_t)15;
+    return l;
+}
+
+template <int DS>
+__global__ void __launch_bounds__(256) cluster_wave_kernel(ClusterArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int DP = 16 * DS + 4;
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = (int)blockIdx.x * 4 + wv;
+    if (g >= a.G) return;                 // (a whole wave leaves: nothing in this kernel waits for another wave)
+    const int D = a.D, SP = D | 1;
+    int n0, ng, k0, K;
+    search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+    if (K > a.Kmax) K = a.Kmax;
+    if (ng > kWaveMaxN) ng = kWaveMaxN;   // (the host launches this kernel only for such batches)
+    if (ng <= 0 || K <= 0) {
+        if (lane == 0 && a.iters > 0 && a.objective) a.objective[g] = 0.f;
+        return;
+    }
+    if (a.guard && ng < 2 * K) return;
+
+    const WaveLds L = wave_lds_layout(a.Kmax, D, DP);
+    unsigned char* base = smem + (size_t)wv * L.total;
+    long long* sums = reinterpret_cast<long long*>(base + L.sums);      // [Kmax][SP]
+    float* cent = reinterpret_cast<float*>(base + L.cent);              // [Kmax][DP]
+    int* cnt = reinterpret_cast<int*>(base + L.cnt);                    // [Kmax]
+    float* delta = reinterpret_cast<float*>(base + L.delta);            // [Kmax]
+    unsigned char* dirty = base + L.dirty;                              // [Kmax]
+    const float* Xg = a.X + (size_t)n0 * D;
+    const bool valid = lane < ng;
+
+    // this lane's row, zero-padded to 16 * DS features (a lane without a candidate holds zeros)
+    float x[16 * DS];
+#pragma unroll
+    for (int d = 0; d < 16 * DS; ++d) x[d] = 0.f;
+    if (valid) {
+        const float* xr = Xg + (size_t)lane * D;
+        if ((D & 3) == 0) {
+#pragma unroll
+            for (int c = 0; c < 4 * DS; ++c) {
+                if (4 * c < D) {
+                    const float4 v = reinterpret_cast<const float4*>(xr)[c];
+                    x[4 * c] = v.x; x[4 * c + 1] = v.y; x[4 * c + 2] = v.z; x[4 * c + 3] = v.w;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int d = 0; d < 16 * DS; ++d) if (d < D) x[d] = xr[d];
+        }
+    }
+    float am = 0.f;
+    double tsq = 0.0;
+#pragma unroll
+    for (int d = 0; d < 16 * DS; ++d) {
+        am = fmaxf(am, fabsf(x[d]));
+        tsq = fma((double)x[d], (double)x[d], tsq);
+    }
+    am = wave_max_f(am);
+    tsq = wave_sum_d(tsq);
+
+    for (int idx = lane; idx < K * DP; idx += kWave) {
+        const int j = idx / DP, d = idx - j * DP;
+        float v = 0.f;
+        if (d < D)
+            v = a.cent_init ? a.cent_init[(size_t)(k0 + j) * D + d]
+                            : Xg[(size_t)(j < ng ? j : ng - 1) * D + d];
+        cent[idx] = v;
+    }
+    for (int idx = lane; idx < K * SP; idx += kWave) sums[idx] = 0;
+    if (lane < K) { cnt[lane] = 0; dirty[lane] = 0; delta[lane] = 0.f; }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+
+    if (a.iters == 0) {
+        for (int idx = lane; idx < K * D; idx += kWave) {
+            const int j = idx / D, d = idx - j * D;
+            a.cent_out[(size_t)(k0 + j) * D + d] = cent[(size_t)j * DP + d];
+        }
+        return;
+    }
+    const int sh = fixed_shift(am, ng);
+    const int fsh = sh - 32;
+    const double inv = ldexp(1.0, -sh);
+    const float eps = 2.f * (float)(D + 2) * 5.9604644775390625e-08f;
+
+    int mine = -1;
+    float ub = 0.f, lb = 0.f;
+    for (int it = 0; it < a.iters; ++it) {
+        bool need = valid;
+        if (it > 0) {
+            const float dj = lane < K ? delta[lane] : 0.f;       // K <= 16 here
+            const float d1 = wave_max_f(dj);
+            const int jm = __ffsll((long long)__ballot(dj == d1)) - 1;
+            const float d2 = wave_max_f(lane == jm ? 0.f : dj);
+            if (valid) {
+                ub = (ub + delta[mine]) * 1.0000005f;                           // rounded up
+                const float t = lb - (mine == jm ? d2 : d1) * 1.0000005f;
+                lb = t - fabsf(t) * 1.0e-6f;                                    // rounded down
+                need = !(a.use_bounds && ub < lb);
+            }
+        }
+        int moved = 0;
+        if (need) {
+            float b32 = INFINITY, s32 = INFINITY;
+            int bj = 0;
+            for (int j = 0; j < K; ++j) {
+                const float4* cr = reinterpret_cast<const float4*>(cent + (size_t)j * DP);   // (one address for all lanes)
+                float acc0 = 0.f, acc1 = 0.f;
+                // rows and centroids are zero-padded to 16 * DS features: the extra terms are +0.0
+#pragma unroll
+                for (int c = 0; c < 4 * DS; ++c) {
+                    const float4 cv = cr[c];
+                    const float e0 = x[4 * c] - cv.x, e1 = x[4 * c + 1] - cv.y;
+                    const float e2 = x[4 * c + 2] - cv.z, e3 = x[4 * c + 3] - cv.w;
+                    acc0 = fmaf(e0, e0, acc0);
+                    acc1 = fmaf(e1, e1, acc1);
+                    acc0 = fmaf(e2, e2, acc0);
+                    acc1 = fmaf(e3, e3, acc1);
+                }
+                const float acc = acc0 + acc1;
+                if (acc < b32) { s32 = b32; b32 = acc; bj = j; }
+                else if (acc < s32) s32 = acc;
+            }
+            if (s32 * (1.f - eps) > b32 * (1.f + eps) + 1.0e-35f) {
+                ub = sqrtf(b32 * (1.f + eps)) * 1.0000005f;
+                lb = sqrtf(s32 * (1.f - eps)) * 0.9999995f;
+            } else {
+                double bd = INFINITY, sd = INFINITY;
+                bj = 0;
+                for (int j = 0; j < K; ++j) {
+                    const float* cr = cent + (size_t)j * DP;
+                    double acc = 0.0;
+#pragma unroll
+                    for (int d = 0; d < 16 * DS; ++d) {
+                        const double diff = __dsub_rn((double)x[d], (double)cr[d]);
+                        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                    }
+                    if (acc < bd) { sd = bd; bd = acc; bj = j; }
+                    else if (acc < sd) sd = acc;
+                }
+                ub = (float)sqrt(bd) * 1.0000005f;
+                lb = (float)sqrt(sd) * 0.9999995f;
+            }
+            if (bj != mine) {
+#pragma unroll
+                for (int d = 0; d < 16 * DS; ++d) {
+                    if (d < D) {
+                        const long long q = to_fixed(x[d], fsh);
+                        lds_add(&sums[(size_t)bj * SP + d], q);
+                        if (mine >= 0) lds_add(&sums[(size_t)mine * SP + d], -q);
+                    }
+                }
+                atomicAdd(&cnt[bj], 1);
+                dirty[bj] = 1;
+                if (mine >= 0) { atomicSub(&cnt[mine], 1); dirty[mine] = 1; }
+                a.assign[(size_t)n0 + lane] = bj;
+                mine = bj;
+                moved = 1;
+            }
+        }
+        const bool changed = __any(moved) != 0;
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+
+        const bool last = (it == a.iters - 1) || (a.early_exit && !changed);
+        if (last) {
+            // objective relative to the centroids that entered this step, from the exact sums
+            // (see the kernel above); member by member when the subtraction cancels
+            double part = 0.0;
+            for (int idx = lane; idx < K * D; idx += kWave) {
+                const int j = idx / D, d = idx - j * D;
+                const double cj = (double)cent[(size_t)j * DP + d];
+                const double Sj = (double)sums[(size_t)j * SP + d] * inv;
+                part += cj * (2.0 * Sj - (double)cnt[j] * cj);
+            }
+            part = wave_sum_d(part);
+            double J = tsq - part;
+            if (!(J >= 1.0e-7 * tsq)) {
+                double acc = 0.0;
+                if (valid) {
+                    const float4* cr = reinterpret_cast<const float4*>(cent + (size_t)mine * DP);
+#pragma unroll
+                    for (int c = 0; c < 4 * DS; ++c) {
+                        const float4 cv = cr[c];
+                        const float e0 = x[4 * c] - cv.x, e1 = x[4 * c + 1] - cv.y;
+                        const float e2 = x[4 * c + 2] - cv.z, e3 = x[4 * c + 3] - cv.w;
+                        acc += (double)fmaf(e0, e0, fmaf(e1, e1, fmaf(e2, e2, e3 * e3)));
+                    }
+                }
+                J = wave_sum_d(acc);
+            }
+            if (lane == 0) a.objective[g] = (float)J;
+        }
+        // new centroids (a wave of its own: the cross-lane steps of the renewal stay inside it)
+        renew_rows<DS, false, kWave>(cent, nullptr, nullptr, sums, cnt, dirty, delta, K, D, SP, inv, false, false, lane);
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        if (last) break;
+    }
+
+    for (int idx = lane; idx < K * D; idx += kWave) {
+        const int j = idx / D, d = idx - j * D;
+        a.cent_out[(size_t)(k0 + j) * D + d] = cent[(size_t)j * DP + d];
+    }
+    if (lane < K) a.counts[k0 + lane] = cnt[lane];
+}
+
 constexpr size_t kMaxLds = 160 * 1024;
 
 }  // namespace
@@ -1545,6 +1790,27 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     const size_t lds = wide ? lds_wide
                             : lds_layout(a.Kmax, b.D, 16 * ds + 4, a.Nmax, kThreadsNarrow / kWave).total;
     if (lds > kMaxLds) return hipErrorInvalidValue;
+    // a batch of very short searches, in the library's default mode: one wave per search
+    if (c.scorer == KB_SCORER_DEFAULT && !c.mixed && b.Nmax <= kWaveMaxN && a.Kmax <= kWaveMaxK) {
+        const size_t wlds = 4 * wave_lds_layout(a.Kmax, b.D, 16 * ds + 4).total;
+        if (wlds > kMaxLds) return hipErrorInvalidValue;
+        const dim3 wgrid((unsigned)((b.G + 3) / 4)), wblock(256);
+#define KB_LAUNCH_WAVE(DS_)                                                                     \
+    do {                                                                                        \
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(cluster_wave_kernel<DS_>), \
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)wlds); \
+        if (e != hipSuccess) return e;                                                          \
+        hipLaunchKernelGGL((cluster_wave_kernel<DS_>), wgrid, wblock, wlds, st, a);             \
+    } while (0)
+        switch (ds) {
+            case 1: KB_LAUNCH_WAVE(1); break;
+            case 2: KB_LAUNCH_WAVE(2); break;
+            case 3: KB_LAUNCH_WAVE(3); break;
+            default: KB_LAUNCH_WAVE(4); break;
+        }
+#undef KB_LAUNCH_WAVE
+        return hipGetLastError();
+    }
     const dim3 grid((unsigned)b.G), block(wide ? kThreadsWide : kThreadsNarrow);
 #define KB_NARROW_SCALAR kThreadsNarrow, false
 #define KB_LAUNCH_NT(DS_, MT_, NT_)                                                             \

@@ -361,6 +361,25 @@ def test_workgroup_shapes_agree(kb, scorer):
         np.testing.assert_array_equal(out[0][k].view(np.uint8), out[1][k][:n].view(np.uint8), err_msg=k)
 
 
+def test_wave_per_search_kernel_equals_the_workgroup_kernel(kb):
+    """Searches of at most 64 candidates and 16 clusters run one wave per search in the
+    default mode; modes 1 and 2 send them through the one-workgroup kernels.  Same
+    assignments and counts, and - same fixed-point grid, same rounding - the same
+    centroid bytes."""
+    for b in (synth.paper_scale(), synth.config5(G=700, nmin=1, nmax=64, D=12, S=4, iters=7, kcap=16, kdiv=4,
+                                                 seed=17)):
+        out = []
+        for mode in (0, 2, 1):
+            d = kb.DeviceBatch(b, scorer=mode)
+            d.cluster()
+            _sync()
+            out.append({k: d.host(k).copy() for k in ("assign", "cent", "counts", "objective")})
+        for other in out[1:]:
+            for k in ("assign", "cent", "counts"):
+                np.testing.assert_array_equal(out[0][k].view(np.uint8), other[k].view(np.uint8), err_msg=k)
+            assert_rel_close(out[0]["objective"], other["objective"], what="objective")
+
+
 def test_features_of_different_magnitude(kb):
     """One fixed-point grid per search serves every feature: columns a few thousand
     times smaller than the largest one still give centroids good to fp32 rounding
