@@ -138,7 +138,8 @@ enum {
      * since it was last scored (triangle inequality on how far the centroids
      * moved) is not scored again, the others are packed into dense tiles.  (A
      * batch of searches of at most 64 candidates and 16 clusters runs one wave per
-     * search with exact fp32 / fp64 distances instead: same results.)  Rows
+     * search with exact fp32 / fp64 distances instead, and a search stops at its
+     * first step without a move, after which nothing could change: same results.)  Rows
      * are fetched in 16-byte pieces when D is a multiple of 4 and feature by
      * feature otherwise (about a third slower). */
     KB_SCORER_DEFAULT = 0,
@@ -233,7 +234,10 @@ kb_status kb_ucb_select(const kb_batch *batch, const kb_params *params,
 /* kb_prune, then kb_cluster on ALL candidates (pruned ones are clustered too:
  * the frontier is partitioned first and masked afterwards, Alg. 1), then
  * kb_ucb_select with the mask, bounds and assignment just computed.
- * Requires params->iters >= 1. */
+ * Requires params->iters >= 1.  Same outputs, byte for byte, as the three calls
+ * one after the other; a batch of searches of at most 64 candidates and 16
+ * clusters each takes, in the default scorer mode, a single launch in which one
+ * wave carries a search through all three stages. */
 kb_status kb_round(const kb_batch *batch, const kb_params *params,
                    const kb_round_io *io, void *ws, size_t ws_bytes,
                    void *stream);

@@ -128,7 +128,7 @@ static kb_status check_cluster(const kb_batch* b, const float* X, const float* c
 static kb_status do_cluster(const kb_batch* b, const float* X, const float* cent_init,
                             int32_t iters, int scorer, int32_t* assign, float* cent,
                             int32_t* counts, float* objective, void* ws, hipStream_t st,
-                            bool reclustering = false) {
+                            bool reclustering = false, bool* ordered = nullptr) {
     if (scorer < KB_SCORER_DEFAULT || scorer > KB_SCORER_MATRIX_EVERY) return KB_EINVAL;
     // (a re-clustering may continue from the centroids it overwrites: every kernel
     // reads a search's initial centroids before it writes that search's new ones)
@@ -139,8 +139,10 @@ static kb_status do_cluster(const kb_batch* b, const float* X, const float* cent
     char* base = (char*)ws;
     int32_t* order = (int32_t*)(base + w.order);
     // (a lone search on the one-workgroup path needs neither a scheduling order nor
-    // tile offsets: one launch less)
-    if (b->G > 1 || w.use_big) {
+    // tile offsets, and neither does a batch that runs one wave per search: one launch less)
+    const bool need_order = (b->G > 1 && !cluster_wave_per_search(*b, scorer)) || w.use_big;
+    if (ordered) *ordered = need_order;
+    if (need_order) {
         hipError_t e = launch_order(*b, order, (int32_t*)(base + w.tile_off),
                                     w.use_big ? (int32_t*)(base + w.big.chunk_off) : nullptr, st);
         if (e != hipSuccess) return KB_EDEVICE;
@@ -531,6 +533,18 @@ kb_status kb_round(const kb_batch* batch, const kb_params* params, const kb_roun
                   io->Ncs, io->mu, io->ucb, io->sel);
     if (s != KB_OK) return s;
     hipStream_t st = (hipStream_t)stream;
+    if (batch->G > 0 && round_in_one_launch(*batch, params->scorer)) {
+        // very short searches only: the three stages of every search in one wave, one launch
+        ClusterCall c{};
+        c.X = io->X; c.iters = params->iters; c.assign = io->assign; c.cent_out = io->cent;
+        c.counts = io->counts; c.objective = io->objective; c.scorer = params->scorer;
+        UcbCall u{};
+        u.assign = io->assign; u.alive = io->alive; u.bound = io->bound; u.visits = io->visits;
+        u.rsum = io->rsum; u.t = io->t; u.c = params->c; u.prior_n = params->prior_n;
+        u.prior_mu = params->prior_mu; u.Ncs = io->Ncs; u.mu = io->mu; u.ucb = io->ucb; u.sel = io->sel;
+        return dev(launch_round_wave(*batch, c, u, io->flops, io->bytes, io->incumbent,
+                                     params->peak_flops, params->peak_bw, io->bound, io->alive, st));
+    }
     s = do_prune(batch, params, io->flops, io->bytes, io->incumbent, io->bound, io->alive, st);
     if (s != KB_OK) return s;
     s = do_cluster(batch, io->X, nullptr, params->iters, params->scorer, io->assign, io->cent,
@@ -575,6 +589,7 @@ kb_status kb_iterate(const kb_batch* batch, const kb_params* params, const kb_it
     char* base = (char*)ws;
     const size_t G = (size_t)batch->G;
     bool have_order = false;        // the scheduling order in ws, computed by the first stage that needs it
+    bool ordered = false;
     // The cluster-arm tables (visit counts and fixed-point reward sums of the alive
     // members of every cluster) are aggregated from the per-candidate history in the
     // first round and after every re-clustering, kept in the workspace, and advanced by
@@ -590,9 +605,9 @@ kb_status kb_iterate(const kb_batch* batch, const kb_params* params, const kb_it
             // and the mask their hardware signatures give (Alg. 1; Eq. 5)
             s = do_cluster(batch, io->X, ip->warm_start ? io->cent : nullptr, params->iters,
                            params->scorer, io->assign, io->cent, io->counts, io->objective, ws, st,
-                           true);
+                           true, &ordered);
             if (s != KB_OK) return s;
-            have_order = true;
+            have_order = have_order || ordered;
             tables_valid = false;
             GeoCall gc;
             gc.X = io->X; gc.cent = io->cent; gc.assign = io->assign; gc.rep = io->rep;

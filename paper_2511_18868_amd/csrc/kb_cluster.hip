@@ -39,6 +39,7 @@
 // New centroid = (fixed-point sum / 2^shift) / count in fp64, rounded once to
 // fp32; an empty cluster keeps its centroid.
 #include "kb_cluster_dev.h"
+#include "kb_ucb_dev.h"
 
 namespace kb {
 
@@ -1531,9 +1532,10 @@ __global__ void __launch_bounds__(NT, NT == kThreadsNarrow ? 3 : 1) cluster_fuse
 constexpr int kWaveMaxN = 64, kWaveMaxK = 16;
 
 struct WaveLds {
-    size_t sums, cent, cnt, delta, dirty, total;
+    size_t sums, cent, cnt, delta, dirty, armR, armkmin, armN, armalive, total;
 };
-__host__ __device__ inline WaveLds wave_lds_layout(int Kmax, int D, int DP) {
+// S > 0: with the cluster-arm tables of the selection step (the whole-round kernel)
+__host__ __device__ inline WaveLds wave_lds_layout(int Kmax, int D, int DP, int S = 0) {
     const int SP = D | 1;
     WaveLds l;
     size_t off = 0;
@@ -1543,13 +1545,35 @@ __host__ __device__ inline WaveLds wave_lds_layout(int Kmax, int D, int DP) {
     l.cnt = off;   off += (size_t)Kmax * 4;
     l.delta = off; off += (size_t)Kmax * 4;
     l.dirty = off; off += ((size_t)Kmax + 15) & ~(size_t)15;
+    off = (off + 15) & ~(size_t)15;
+    l.armR = off;     off += (size_t)Kmax * S * 8;
+    l.armkmin = off;  off += S > 0 ? (size_t)Kmax * 8 : 0;
+    l.armN = off;     off += (size_t)Kmax * S * 4;
+    l.armalive = off; off += S > 0 ? (size_t)Kmax * 4 : 0;
     l.total = (off + 15) & ~(size_t)15;
     return l;
 }
 
-template <int DS>
-__global__ void __launch_bounds__(256) cluster_wave_kernel(ClusterArgs a) {
-    extern __shared__ __align__(16) unsigned char smem[];
+// What the whole-round kernel needs beyond the clustering arguments: the pruning
+// step's inputs and outputs (Eq. 2 and the mask of Eq. 5) and the selection call.
+struct WaveRound {
+    const float* flops;
+    const float* bytes;
+    const float* incumbent;
+    float peak_flops, peak_bw;
+    float* bound;
+    uint8_t* alive;
+    UcbArgs u;
+};
+
+// ROUND: the whole round of the search in this one wave - the roofline bound and the
+// mask of every candidate first (the same correctly rounded divisions and strict
+// compare as the pruning kernel), the clustering, then the cluster-arm statistics
+// from the lanes' own clusters (integer LDS atomics, as in the selection kernel, so
+// the same tables), scores and selection.  (The host takes this path with a.iters >= 1
+// and a.guard = 0.)
+template <int DS, bool ROUND>
+__device__ __forceinline__ void wave_search(const ClusterArgs& a, const WaveRound* rd, unsigned char* smem) {
     constexpr int DP = 16 * DS + 4;
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -1560,13 +1584,28 @@ __global__ void __launch_bounds__(256) cluster_wave_kernel(ClusterArgs a) {
     search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
     if (K > a.Kmax) K = a.Kmax;
     if (ng > kWaveMaxN) ng = kWaveMaxN;   // (the host launches this kernel only for such batches)
+    bool live = true;                     // this lane's candidate passed the pruning step
+    float rbound = 0.f;
+    if constexpr (ROUND) {
+        if (lane < ng) {
+            const float t_compute = rd->flops[(size_t)n0 + lane] / rd->peak_flops;
+            const float t_memory = rd->bytes[(size_t)n0 + lane] / rd->peak_bw;
+            rbound = t_compute > t_memory ? t_compute : t_memory;
+            live = rbound < rd->incumbent[g];
+            rd->bound[(size_t)n0 + lane] = rbound;
+            rd->alive[(size_t)n0 + lane] = live ? 1 : 0;
+        }
+    }
     if (ng <= 0 || K <= 0) {
         if (lane == 0 && a.iters > 0 && a.objective) a.objective[g] = 0.f;
+        if constexpr (ROUND) {
+            if (lane < 3) rd->u.sel[(size_t)g * 3 + lane] = -1;
+        }
         return;
     }
     if (a.guard && ng < 2 * K) return;
 
-    const WaveLds L = wave_lds_layout(a.Kmax, D, DP);
+    const WaveLds L = wave_lds_layout(a.Kmax, D, DP, ROUND ? rd->u.S : 0);
     unsigned char* base = smem + (size_t)wv * L.total;
     long long* sums = reinterpret_cast<long long*>(base + L.sums);      // [Kmax][SP]
     float* cent = reinterpret_cast<float*>(base + L.cent);              // [Kmax][DP]
@@ -1747,6 +1786,56 @@ __global__ void __launch_bounds__(256) cluster_wave_kernel(ClusterArgs a) {
         a.cent_out[(size_t)(k0 + j) * D + d] = cent[(size_t)j * DP + d];
     }
     if (lane < K) a.counts[k0 + lane] = cnt[lane];
+
+    if constexpr (ROUND) {
+        const UcbArgs& u = rd->u;
+        const int S = u.S, KS = K * S;
+        unsigned long long* R = reinterpret_cast<unsigned long long*>(base + L.armR);        // [Kmax*S]
+        unsigned long long* kmin = reinterpret_cast<unsigned long long*>(base + L.armkmin);  // [Kmax]
+        unsigned* Ncnt = reinterpret_cast<unsigned*>(base + L.armN);                         // [Kmax*S]
+        unsigned* nalive = reinterpret_cast<unsigned*>(base + L.armalive);                   // [Kmax]
+        for (int i = lane; i < KS; i += kWave) { R[i] = 0ull; Ncnt[i] = 0u; }
+        if (lane < K) { kmin[lane] = ~0ull; nalive[lane] = 0u; }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        if (valid && live) {
+            const int j = mine >= 0 ? mine : 0;       // (iters >= 1: every candidate has a cluster)
+            const int32_t* vis = u.visits + ((size_t)n0 + lane) * S;
+            const float* rs = u.rsum + ((size_t)n0 + lane) * S;
+            unsigned* nc = Ncnt + (size_t)j * S;
+            unsigned long long* rr = R + (size_t)j * S;
+            if ((S & 3) == 0) {
+                for (int s = 0; s < S; s += 4) {
+                    const int4 v = *reinterpret_cast<const int4*>(vis + s);
+                    const float4 r = *reinterpret_cast<const float4*>(rs + s);
+                    atomicAdd(nc + s + 0, (unsigned)v.x); atomicAdd(nc + s + 1, (unsigned)v.y);
+                    atomicAdd(nc + s + 2, (unsigned)v.z); atomicAdd(nc + s + 3, (unsigned)v.w);
+                    atomicAdd(rr + s + 0, reward_fixed(r.x)); atomicAdd(rr + s + 1, reward_fixed(r.y));
+                    atomicAdd(rr + s + 2, reward_fixed(r.z)); atomicAdd(rr + s + 3, reward_fixed(r.w));
+                }
+            } else {
+                for (int s = 0; s < S; ++s) {
+                    atomicAdd(nc + s, (unsigned)vis[s]);
+                    atomicAdd(rr + s, reward_fixed(rs[s]));
+                }
+            }
+            atomicAdd(&nalive[j], 1u);
+            atomicMin(&kmin[j], ((unsigned long long)ordered_bits(rbound) << 32) | (unsigned)lane);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        ucb_finish<kWave>(u, g, n0, k0, K, Ncnt, R, nalive, kmin, nullptr, nullptr, lane);
+    }
+}
+
+template <int DS>
+__global__ void __launch_bounds__(256) cluster_wave_kernel(ClusterArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    wave_search<DS, false>(a, nullptr, smem);
+}
+
+template <int DS>
+__global__ void __launch_bounds__(256) round_wave_kernel(ClusterArgs a, WaveRound rd) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    wave_search<DS, true>(a, &rd, smem);
 }
 
 constexpr size_t kMaxLds = 160 * 1024;
@@ -1762,7 +1851,7 @@ bool cluster_supported(const kb_batch& b) {
     return lds_layout(one_wg_kmax(b), b.D, 16 * ds + 4, one_wg_nmax(b), kThreadsNarrow / kWave).total <= kMaxLds;
 }
 
-hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t st) {
+static ClusterArgs cluster_args(const kb_batch& b, const ClusterCall& c) {
     ClusterArgs a;
     a.G = b.G; a.D = b.D; a.Ksum = b.Ksum; a.Kmax = one_wg_kmax(b); a.N = b.N;
     a.seg_off = b.seg_off; a.koff = b.koff; a.X = c.X; a.cent_init = c.cent_init;
@@ -1774,9 +1863,81 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
     a.mixed = c.mixed;
     a.limit_n = one_wg_limit_n(b);
     a.lim = reinterpret_cast<float2*>(c.lim);
-
-    const int ds = (b.D + 15) / 16;   // 1..4 K-steps of 16 features
     a.Nmax = one_wg_nmax(b);
+    return a;
+}
+
+bool cluster_wave_per_search(const kb_batch& b, int scorer) {
+    return scorer == KB_SCORER_DEFAULT && b.Nmax <= kWaveMaxN && b.Kmax <= kWaveMaxK;
+}
+static bool wave_per_search(const kb_batch& b, const ClusterCall& c) {
+    return !c.mixed && cluster_wave_per_search(b, c.scorer);
+}
+
+// One wave per search, four searches per workgroup; rd: the whole round, else the
+// clustering step only.
+static hipError_t launch_wave(const kb_batch& b, const ClusterArgs& a_in, const WaveRound* rd, hipStream_t st) {
+    // A search stops at its first step without a move: such a step leaves sums, sizes
+    // and centroids as they were, so every later step would repeat it and every output
+    // is the same bytes as after the full count of steps.
+    ClusterArgs a = a_in;
+    a.early_exit = 1;
+    const int ds = (b.D + 15) / 16;
+    const size_t wlds = 4 * wave_lds_layout(a.Kmax, b.D, 16 * ds + 4, rd ? b.S : 0).total;
+    if (wlds > kMaxLds) return hipErrorInvalidValue;
+    const dim3 wgrid((unsigned)((b.G + 3) / 4)), wblock(256);
+#define KB_LAUNCH_WAVE(DS_)                                                                     \
+    do {                                                                                        \
+        if (rd) {                                                                               \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(round_wave_kernel<DS_>), \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)wlds); \
+            if (e != hipSuccess) return e;                                                      \
+            hipLaunchKernelGGL((round_wave_kernel<DS_>), wgrid, wblock, wlds, st, a, *rd);      \
+        } else {                                                                                \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(cluster_wave_kernel<DS_>), \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)wlds); \
+            if (e != hipSuccess) return e;                                                      \
+            hipLaunchKernelGGL((cluster_wave_kernel<DS_>), wgrid, wblock, wlds, st, a);         \
+        }                                                                                       \
+    } while (0)
+    switch (ds) {
+        case 1: KB_LAUNCH_WAVE(1); break;
+        case 2: KB_LAUNCH_WAVE(2); break;
+        case 3: KB_LAUNCH_WAVE(3); break;
+        default: KB_LAUNCH_WAVE(4); break;
+    }
+#undef KB_LAUNCH_WAVE
+    return hipGetLastError();
+}
+
+// A batch of searches of at most 64 candidates and 16 clusters each, in the default
+// mode: the whole round (Sec. 3.5: prune, cluster, select) is one launch, a wave per
+// search.  (The selection tables share the wave's piece of LDS; strategy counts that
+// would leave fewer than two workgroups per compute unit take the three-stage path.)
+bool round_in_one_launch(const kb_batch& b, int scorer) {
+    if (scorer != KB_SCORER_DEFAULT || b.Nmax > kWaveMaxN || b.Kmax > kWaveMaxK) return false;
+    const int ds = (b.D + 15) / 16;
+    const int kmax = b.Kmax > 0 ? b.Kmax : 1;
+    return 4 * wave_lds_layout(kmax, b.D, 16 * ds + 4, b.S).total <= 64 * 1024;
+}
+
+hipError_t launch_round_wave(const kb_batch& b, const ClusterCall& c, const UcbCall& uc,
+                             const float* flops, const float* bytes, const float* incumbent,
+                             float peak_flops, float peak_bw, float* bound, uint8_t* alive,
+                             hipStream_t st) {
+    if (!round_in_one_launch(b, c.scorer) || c.mixed || c.guard || c.iters < 1 || c.cent_init)
+        return hipErrorInvalidValue;
+    const ClusterArgs a = cluster_args(b, c);
+    WaveRound rd;
+    rd.flops = flops; rd.bytes = bytes; rd.incumbent = incumbent;
+    rd.peak_flops = peak_flops; rd.peak_bw = peak_bw; rd.bound = bound; rd.alive = alive;
+    rd.u = make_ucb_args(b, uc);
+    return launch_wave(b, a, &rd, st);
+}
+
+hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t st) {
+    const ClusterArgs a = cluster_args(b, c);
+    const int ds = (b.D + 15) / 16;   // 1..4 K-steps of 16 features
     int mt = a.Kmax <= 32 ? 1 : (a.Kmax <= 64 ? 2 : 0);
     if (c.scorer == 1) mt = 0;
     // the matrix-core kernels fetch rows in 16-byte pieces when D is a multiple of 4 and
@@ -1791,26 +1952,7 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
                             : lds_layout(a.Kmax, b.D, 16 * ds + 4, a.Nmax, kThreadsNarrow / kWave).total;
     if (lds > kMaxLds) return hipErrorInvalidValue;
     // a batch of very short searches, in the library's default mode: one wave per search
-    if (c.scorer == KB_SCORER_DEFAULT && !c.mixed && b.Nmax <= kWaveMaxN && a.Kmax <= kWaveMaxK) {
-        const size_t wlds = 4 * wave_lds_layout(a.Kmax, b.D, 16 * ds + 4).total;
-        if (wlds > kMaxLds) return hipErrorInvalidValue;
-        const dim3 wgrid((unsigned)((b.G + 3) / 4)), wblock(256);
-#define KB_LAUNCH_WAVE(DS_)                                                                     \
-    do {                                                                                        \
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(cluster_wave_kernel<DS_>), \
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)wlds); \
-        if (e != hipSuccess) return e;                                                          \
-        hipLaunchKernelGGL((cluster_wave_kernel<DS_>), wgrid, wblock, wlds, st, a);             \
-    } while (0)
-        switch (ds) {
-            case 1: KB_LAUNCH_WAVE(1); break;
-            case 2: KB_LAUNCH_WAVE(2); break;
-            case 3: KB_LAUNCH_WAVE(3); break;
-            default: KB_LAUNCH_WAVE(4); break;
-        }
-#undef KB_LAUNCH_WAVE
-        return hipGetLastError();
-    }
+    if (wave_per_search(b, c)) return launch_wave(b, a, nullptr, st);
     const dim3 grid((unsigned)b.G), block(wide ? kThreadsWide : kThreadsNarrow);
 #define KB_NARROW_SCALAR kThreadsNarrow, false
 #define KB_LAUNCH_NT(DS_, MT_, NT_)                                                             \

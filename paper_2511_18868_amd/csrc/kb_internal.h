@@ -103,6 +103,7 @@ hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t s
 hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const BigWs& w, char* ws,
                               hipStream_t st);
 bool cluster_supported(const kb_batch& b);   // shape fits the compiled clustering kernels
+bool cluster_wave_per_search(const kb_batch& b, int scorer);   // the batch runs one wave per search (no scheduling order needed)
 
 struct UcbCall {
     const int32_t* assign;
@@ -131,6 +132,15 @@ struct UcbCall {
     int chunked, keep_tables, from_tables;
 };
 hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st);
+
+// The whole round of a batch of very short searches in one launch (one wave per
+// search): true if batch and mode allow it; the launch itself takes the three
+// stages' arguments (no initial centroids, iters >= 1, no workspace arrays).
+bool round_in_one_launch(const kb_batch& b, int scorer);
+hipError_t launch_round_wave(const kb_batch& b, const ClusterCall& c, const UcbCall& uc,
+                             const float* flops, const float* bytes, const float* incumbent,
+                             float peak_flops, float peak_bw, float* bound, uint8_t* alive,
+                             hipStream_t st);
 
 struct SampleCall {
     const int32_t* assign;

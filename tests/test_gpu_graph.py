@@ -29,6 +29,8 @@ CASES = {
     "manysmall": lambda: synth.config5(G=300, nmin=64, nmax=260, D=16, S=4, iters=6, seed=123),
     # the multi-workgroup launch sequence (four launches per Lloyd step)
     "cfg4s": lambda: synth.config4(N=8192, K=256, ncentres=256, iters=4),
+    # very short searches: the whole round is one launch, a wave per search
+    "paperscale": lambda: synth.paper_scale(),
 }
 
 

@@ -380,6 +380,34 @@ def test_wave_per_search_kernel_equals_the_workgroup_kernel(kb):
             assert_rel_close(out[0]["objective"], other["objective"], what="objective")
 
 
+def test_round_in_one_launch_equals_the_three_stages(kb):
+    """A batch of searches of at most 64 candidates and 16 clusters takes its whole
+    round in one launch (a wave per search) in the default mode; the three entry points
+    called one after the other run the pruning, clustering and selection kernels.  Every
+    output must be the same bytes: the divisions and the compare of the pruning step, the
+    clustering and the integer cluster-arm tables do not depend on the kernel that runs
+    them.  Feature counts with and without 16-byte rows, strategy counts with and without
+    16-byte rows, empty searches and searches shorter than their cluster count."""
+    batches = [synth.paper_scale()]
+    for D, S, seed in ((12, 4, 17), (6, 3, 18), (50, 8, 19), (33, 5, 20)):
+        b = synth.config5(G=500, nmin=1, nmax=64, D=D, S=S, iters=7, kcap=16, kdiv=4, seed=seed)
+        batches.append(b)
+    outs = ("bound", "alive", "assign", "cent", "counts", "objective", "Ncs", "mu", "ucb", "sel")
+    for b in batches:
+        one = kb.DeviceBatch(b)
+        one.round()
+        _sync()
+        three = kb.DeviceBatch(b)
+        three.prune()
+        three.cluster()
+        three.ucb_select()
+        _sync()
+        for k in outs:
+            np.testing.assert_array_equal(one.host(k).view(np.uint8), three.host(k).view(np.uint8),
+                                          err_msg=f"{b.name}: {k}")
+        assert 0 < one.host("alive").sum() < b.N          # (the mask prunes)
+
+
 def test_features_of_different_magnitude(kb):
     """One fixed-point grid per search serves every feature: columns a few thousand
     times smaller than the largest one still give centroids good to fp32 rounding
