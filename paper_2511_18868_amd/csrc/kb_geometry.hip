@@ -43,6 +43,8 @@ struct GeoArgs {
     double* d2;                    // [N]
     unsigned long long* gmin;      // [Ksum]
     unsigned long long* gmax;      // [Ksum]
+    int mixed;                     // 1: searches of at most kShortSearch candidates go to geo_wave, longer
+                                   //    ones to the range kernels, in the same call
 };
 
 __global__ void __launch_bounds__(kThreads) geo_init(GeoArgs a) {
@@ -88,6 +90,7 @@ __global__ void __launch_bounds__(kThreads) geo_dist(GeoArgs a) {
         if (K > a.Kmax) K = a.Kmax;
         if (n0 >= r1) break;
         if (ng <= 0 || K <= 0) continue;
+        if (a.mixed && ng <= kShortSearch) continue;      // (uniform) a wave of geo_wave takes this search
         const int q0 = r0 > n0 ? (int)r0 : n0;
         const int q1 = r1 < (int64_t)n0 + ng ? (int)r1 : n0 + ng;
         if (q0 >= q1) continue;
@@ -209,6 +212,7 @@ __global__ void __launch_bounds__(kThreads) geo_rep(GeoArgs a) {
         if (K > a.Kmax) K = a.Kmax;
         if (n0 >= r1) break;
         if (ng <= 0 || K <= 0) continue;
+        if (a.mixed && ng <= kShortSearch) continue;
         const int q0 = r0 > n0 ? (int)r0 : n0;
         const int q1 = r1 < (int64_t)n0 + ng ? (int)r1 : n0 + ng;
         for (int p = q0 + tid; p < q1; p += kThreads) {
@@ -227,6 +231,82 @@ __global__ void __launch_bounds__(kThreads) geo_final(GeoArgs a) {
     a.radius[i] = (float)sqrt(__longlong_as_double((long long)a.gmax[i]));
 }
 
+// Batches of short searches: one wave per search, four searches per workgroup, the
+// whole pass in one launch.  (A workgroup of the range kernels above walks the
+// searches of its range one after the other with barriers around each; with a few
+// dozen candidates per search that is hundreds of searches in a row.)  Same distances
+// - the same fp64 operations in the same order - and the same exact comparisons, so
+// the same representatives and radii.  Any search length is handled (the distances
+// wait in d2 between the two sweeps); short ones are what it is launched for.
+template <int VEC>
+__global__ void __launch_bounds__(kThreads) geo_wave(GeoArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = (int)blockIdx.x * (kThreads / kWave) + wv;
+    if (g >= a.G) return;                 // (a whole wave leaves: no wave waits for another in this kernel)
+    const int D = a.D;
+    int n0, ng, k0, K;
+    search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+    if (K > a.Kmax) K = a.Kmax;
+    if (K <= 0) return;
+    if (a.mixed && ng > kShortSearch) return;         // the range kernels take this search
+    unsigned long long* lmin = reinterpret_cast<unsigned long long*>(smem) + (size_t)wv * 2 * a.Kmax;   // [Kmax]
+    unsigned long long* lmax = lmin + a.Kmax;                                                            // [Kmax]
+    int* lrep = reinterpret_cast<int*>(smem + (size_t)(kThreads / kWave) * 16 * a.Kmax) + (size_t)wv * a.Kmax;   // [Kmax]
+    for (int j = lane; j < K; j += kWave) { lmin[j] = ~0ull; lmax[j] = 0ull; lrep[j] = kNone; }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    for (int p = n0 + lane; p < n0 + ng; p += kWave) {
+        int j = a.assign[p];
+        j = (j >= 0 && j < K) ? j : 0;
+        const float* xrow = a.X + (size_t)p * D;
+        const float* crow = a.cent + (size_t)(k0 + j) * D;
+        double acc = 0.0;
+        if constexpr (VEC == 4) {
+            for (int d = 0; d < D; d += 4) {
+                const float4 xv = *reinterpret_cast<const float4*>(xrow + d);
+                const float4 cv = *reinterpret_cast<const float4*>(crow + d);
+                double diff = __dsub_rn((double)xv.x, (double)cv.x);
+                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                diff = __dsub_rn((double)xv.y, (double)cv.y);
+                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                diff = __dsub_rn((double)xv.z, (double)cv.z);
+                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                diff = __dsub_rn((double)xv.w, (double)cv.w);
+                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+            }
+        } else {
+            for (int d = 0; d < D; ++d) {
+                const double diff = __dsub_rn((double)xrow[d], (double)crow[d]);
+                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+            }
+        }
+        a.d2[p] = acc;
+        const unsigned long long bits = (unsigned long long)__double_as_longlong(acc);
+        atomicMin(&lmin[j], bits);
+        atomicMax(&lmax[j], bits);
+    }
+    // (a lane reads back only the distances it wrote itself)
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    for (int p = n0 + lane; p < n0 + ng; p += kWave) {
+        int j = a.assign[p];
+        j = (j >= 0 && j < K) ? j : 0;
+        const unsigned long long bits = (unsigned long long)__double_as_longlong(a.d2[p]);
+        if (bits == lmin[j]) atomicMin(&lrep[j], p);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    for (int j = lane; j < K; j += kWave) {
+        if (a.mixed) {
+            // geo_final finishes every cluster of the batch from the global tables
+            a.rep[k0 + j] = lrep[j];
+            a.gmax[k0 + j] = lmax[j];
+        } else {
+            a.rep[k0 + j] = lrep[j] == kNone ? -1 : lrep[j];
+            a.radius[k0 + j] = (float)sqrt(__longlong_as_double((long long)lmax[j]));
+        }
+    }
+}
+
 }  // namespace
 
 size_t geometry_lds_bytes(int Kmax, int D) {
@@ -239,8 +319,24 @@ hipError_t launch_geometry(const kb_batch& b, const GeoCall& c, hipStream_t st) 
     a.seg_off = b.seg_off; a.koff = b.koff; a.X = c.X; a.cent = c.cent; a.assign = c.assign;
     a.rep = c.rep; a.radius = c.radius; a.d2 = c.d2; a.gmin = c.gmin; a.gmax = c.gmax;
     if (b.Ksum <= 0) return hipSuccess;
+    // a batch of short searches only: a wave per search, one launch; a batch of several
+    // searches with longer ones among them: the wave kernel after the tables are
+    // initialised, then the range kernels, each skipping the other's searches
+    a.mixed = b.Nmax > kShortSearch && b.G > 1;
+    const size_t wlds = (size_t)(kThreads / kWave) * 20 * a.Kmax;
+    const dim3 wgrid((unsigned)((b.G + kThreads / kWave - 1) / (kThreads / kWave)));
+    if (wlds > 64 * 1024) return hipErrorInvalidValue;
+    if (b.Nmax <= kShortSearch && b.G > 0) {
+        if ((b.D & 3) == 0) hipLaunchKernelGGL(geo_wave<4>, wgrid, dim3(kThreads), wlds, st, a);
+        else hipLaunchKernelGGL(geo_wave<1>, wgrid, dim3(kThreads), wlds, st, a);
+        return hipGetLastError();
+    }
     const unsigned kblocks = (unsigned)((b.Ksum + kThreads - 1) / kThreads);
     hipLaunchKernelGGL(geo_init, dim3(kblocks), dim3(kThreads), 0, st, a);
+    if (a.mixed) {
+        if ((b.D & 3) == 0) hipLaunchKernelGGL(geo_wave<4>, wgrid, dim3(kThreads), wlds, st, a);
+        else hipLaunchKernelGGL(geo_wave<1>, wgrid, dim3(kThreads), wlds, st, a);
+    }
     const unsigned ranges = (unsigned)((b.N + kGeoRange - 1) / kGeoRange);
     if (ranges) {
         const size_t lds = geometry_lds_bytes(a.Kmax, b.D);

@@ -46,6 +46,8 @@ struct SampleArgs {
     int32_t* ksel;             // [G]
     double* slot_key;          // [2 * ranges]  left slot of range r at 2r, right slot at 2r+1
     int32_t* slot_idx;         // [2 * ranges]
+    int mixed;                 // 1: searches of at most kShortSearch candidates go to sample_wave, longer
+                               //    ones to the range kernels, in the same call
 };
 
 // (key, index) pairs ordered by larger key, then lower index; index kNone = empty
@@ -86,6 +88,7 @@ __global__ void __launch_bounds__(kThreads) sample_range(SampleArgs a) {
         search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
         if (n0 >= r1) break;
         if (ng <= 0) continue;
+        if (a.mixed && ng <= kShortSearch) continue;      // (uniform) a wave of sample_wave takes this search
         const int n1 = n0 + ng;
         const int q0 = r0 > n0 ? (int)r0 : n0;
         const int q1 = r1 < n1 ? (int)r1 : n1;
@@ -153,6 +156,7 @@ __global__ void __launch_bounds__(kThreads) sample_final(SampleArgs a) {
     int n0, ng, k0, K;
     search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
     if (ng <= 0) { a.ksel[g] = -1; return; }
+    if (a.mixed && ng <= kShortSearch) return;
     const int rf = n0 / kSampleRange, rl = (n0 + ng - 1) / kSampleRange;
     if (rf == rl) return;
     double bk = a.slot_key[2 * (size_t)rf + 1];
@@ -163,6 +167,49 @@ __global__ void __launch_bounds__(kThreads) sample_final(SampleArgs a) {
         if (better(ok, oi, bk, bi)) { bk = ok; bi = oi; }
     }
     a.ksel[g] = bi == kNone ? -1 : bi;
+}
+
+// Batches of short searches: one wave per search, four searches per workgroup, one
+// launch.  (A workgroup of sample_range walks the searches of its range one after
+// the other, a barrier per search; with a few dozen candidates per search that is
+// hundreds of searches in a row.)  Same keys, same exact comparison, so the same draw.
+__global__ void __launch_bounds__(kThreads) sample_wave(SampleArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int g = (int)blockIdx.x * kWaves + (int)(threadIdx.x >> 6);
+    if (g >= a.G) return;
+    int n0, ng, k0, K;
+    search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+    if (ng <= 0) {
+        if (lane == 0) a.ksel[g] = -1;
+        return;
+    }
+    if (a.mixed && ng > kShortSearch) return;         // the range kernels take this search
+    const int I = a.sel[(size_t)g * 3];
+    double bk = 0.0;
+    int bi = kNone;
+    if (I >= 0) {
+        double pot_scale = 1.0;
+        int tcol = 0;
+        if (a.mode == 0) {
+            pot_scale = (double)a.incumbent[g];
+        } else {
+            const int s = clampi(a.sel[(size_t)g * 3 + 1], 0, a.S - 1);
+            tcol = clampi(a.target[s], 0, a.R - 1);
+        }
+        for (int p = n0 + lane; p < n0 + ng; p += kWave) {
+            if (a.assign[p] != I) continue;
+            if (a.alive && !a.alive[p]) continue;
+            const double key = sample_key(a, p, pot_scale, tcol);
+            if (better(key, p, bk, bi)) { bk = key; bi = p; }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const double ok = __shfl_xor(bk, o);
+            const int oi = __shfl_xor(bi, o);
+            if (better(ok, oi, bk, bi)) { bk = ok; bi = oi; }
+        }
+    }
+    if (lane == 0) a.ksel[g] = bi == kNone ? -1 : bi;
 }
 
 }  // namespace
@@ -177,6 +224,13 @@ hipError_t launch_sample(const kb_batch& b, const SampleCall& c, hipStream_t st)
     a.draw_lo = (unsigned)c.draw; a.draw_hi = (unsigned)(c.draw >> 32);
     a.tau = (double)c.tau;
     a.ksel = c.ksel; a.slot_key = c.slot_key; a.slot_idx = c.slot_idx;
+    // a batch of short searches only: a wave per search, one launch; a batch of several
+    // searches with longer ones among them: both kernels, each skipping the other's searches
+    a.mixed = b.Nmax > kShortSearch && b.G > 1;
+    if ((b.Nmax <= kShortSearch || a.mixed) && b.G > 0) {
+        hipLaunchKernelGGL(sample_wave, dim3((unsigned)((b.G + kWaves - 1) / kWaves)), dim3(kThreads), 0, st, a);
+        if (!a.mixed) return hipGetLastError();
+    }
     const unsigned ranges = (unsigned)((b.N + kSampleRange - 1) / kSampleRange);
     if (ranges) hipLaunchKernelGGL(sample_range, dim3(ranges), dim3(kThreads), 0, st, a);
     hipLaunchKernelGGL(sample_final, dim3((unsigned)((b.G + kThreads - 1) / kThreads)),

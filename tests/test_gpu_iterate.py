@@ -50,6 +50,9 @@ CASES = {
     "longsearch": (_with_long_search, 14, 6, 0, 1, 2),
     # with a mask of alive candidates (every third one pruned)
     "pruned": (lambda: synth.config5(G=24, nmin=64, nmax=400, S=8, seed=55), 22, 8, 1, 1, 2),
+    # short searches only: clustering, representatives and draw run a wave per search
+    "paperscale": (lambda: synth.paper_scale(), 24, 6, 0, 1, 4),
+    "short": (lambda: synth.config5(G=120, nmin=8, nmax=256, D=12, S=4, kcap=16, kdiv=4, seed=78), 18, 5, 1, 0, 3),
 }
 
 

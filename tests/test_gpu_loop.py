@@ -58,6 +58,10 @@ CASES = {
     "empty": _with_empty_searches,
     "cfg4s": lambda: synth.config4(N=8192, K=256, ncentres=256),  # largest LDS footprint
     "bigN": lambda: synth.config2(N=70001, D=16, K=8, S=4, iters=2, seed=5),
+    # batches of short searches (at most 256 candidates each): a wave per search in the
+    # representative pass and the draw
+    "paperscale": lambda: synth.paper_scale(),
+    "short": lambda: synth.config5(G=300, nmin=1, nmax=256, D=12, S=4, iters=3, kcap=16, kdiv=4, seed=77),
 }
 
 

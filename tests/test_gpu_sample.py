@@ -48,6 +48,9 @@ CASES = {
     "paper": lambda: synth.paper_shape(),
     "empty": _with_empty_searches,
     "bigN": lambda: synth.config2(N=70001, D=16, K=8, S=4, iters=2, seed=5),   # one search over 18 ranges
+    # batches of short searches (at most 256 candidates each): a wave per search
+    "paperscale": lambda: synth.paper_scale(),
+    "short": lambda: synth.config5(G=300, nmin=1, nmax=256, D=12, S=4, iters=3, kcap=16, kdiv=4, seed=77),
 }
 
 DRAWS = [(20251118, 0, 1.0), (20251118, 1, 1.0), (7, 2 ** 40 + 3, 0.25), (2 ** 63 + 11, 5, 8.0)]
