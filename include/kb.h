@@ -132,7 +132,8 @@ typedef struct {
 /* kb_params::scorer */
 enum {
     /* bf16 x 3 split products on the matrix cores.  Searches on the one-workgroup
-     * path (K_g <= 64 and N_g <= 65536 - 24576 in a batch of at most 32 searches -,
+     * path (K_g <= 64 and N_g <= 65536 - 24576 in a batch of at most 32 searches
+     * or 786432 candidates -,
      * chosen search by search) also keep distance
      * bounds: a candidate whose nearest centroid provably cannot have changed
      * since it was last scored (triangle inequality on how far the centroids

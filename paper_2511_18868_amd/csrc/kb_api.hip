@@ -215,7 +215,7 @@ static kb_status do_ucb(const kb_batch* b, const kb_params* p, const int32_t* as
     kb_status s = check_ucb(b, p, assign, alive, bound, visits, rsum, t, Ncs, mu, ucb, sel,
                             optional_mask_inputs);
     if (s != KB_OK) return s;
-    if (!have_order && b->G > 1) {
+    if (!have_order && b->G > 1 && !ucb_wave_per_search(*b)) {
         hipError_t e = launch_order(*b, u.order, u.tile_off, nullptr, st);
         if (e != hipSuccess) return KB_EDEVICE;
     }

@@ -1789,7 +1789,7 @@ __device__ __forceinline__ void wave_search(const ClusterArgs& a, const WaveRoun
 
     if constexpr (ROUND) {
         const UcbArgs& u = rd->u;
-        const int S = u.S, KS = K * S;
+        const int KS = K * u.S;
         unsigned long long* R = reinterpret_cast<unsigned long long*>(base + L.armR);        // [Kmax*S]
         unsigned long long* kmin = reinterpret_cast<unsigned long long*>(base + L.armkmin);  // [Kmax]
         unsigned* Ncnt = reinterpret_cast<unsigned*>(base + L.armN);                         // [Kmax*S]
@@ -1797,30 +1797,8 @@ __device__ __forceinline__ void wave_search(const ClusterArgs& a, const WaveRoun
         for (int i = lane; i < KS; i += kWave) { R[i] = 0ull; Ncnt[i] = 0u; }
         if (lane < K) { kmin[lane] = ~0ull; nalive[lane] = 0u; }
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-        if (valid && live) {
-            const int j = mine >= 0 ? mine : 0;       // (iters >= 1: every candidate has a cluster)
-            const int32_t* vis = u.visits + ((size_t)n0 + lane) * S;
-            const float* rs = u.rsum + ((size_t)n0 + lane) * S;
-            unsigned* nc = Ncnt + (size_t)j * S;
-            unsigned long long* rr = R + (size_t)j * S;
-            if ((S & 3) == 0) {
-                for (int s = 0; s < S; s += 4) {
-                    const int4 v = *reinterpret_cast<const int4*>(vis + s);
-                    const float4 r = *reinterpret_cast<const float4*>(rs + s);
-                    atomicAdd(nc + s + 0, (unsigned)v.x); atomicAdd(nc + s + 1, (unsigned)v.y);
-                    atomicAdd(nc + s + 2, (unsigned)v.z); atomicAdd(nc + s + 3, (unsigned)v.w);
-                    atomicAdd(rr + s + 0, reward_fixed(r.x)); atomicAdd(rr + s + 1, reward_fixed(r.y));
-                    atomicAdd(rr + s + 2, reward_fixed(r.z)); atomicAdd(rr + s + 3, reward_fixed(r.w));
-                }
-            } else {
-                for (int s = 0; s < S; ++s) {
-                    atomicAdd(nc + s, (unsigned)vis[s]);
-                    atomicAdd(rr + s, reward_fixed(rs[s]));
-                }
-            }
-            atomicAdd(&nalive[j], 1u);
-            atomicMin(&kmin[j], ((unsigned long long)ordered_bits(rbound) << 32) | (unsigned)lane);
-        }
+        if (valid && live)        // (iters >= 1: every candidate has a cluster)
+            ucb_add_candidate(u, (size_t)n0 + lane, lane, mine >= 0 ? mine : 0, rbound, Ncnt, R, nalive, kmin);
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
         ucb_finish<kWave>(u, g, n0, k0, K, Ncnt, R, nalive, kmin, nullptr, nullptr, lane);
     }

@@ -861,7 +861,10 @@ __global__ void __launch_bounds__(kThreads) big_update(BigArgs a) {
     const bool first = a.it == 0;
     // a range may span several searches: handle them one after the other
     int g = upper_search(a.seg_off, a.G, r0);
-    for (; g < a.G; ++g) {
+    const auto mine = [&](int n0, int ng, int k0, int K) {
+        return n0 >= r1 || (ng > 0 && jg0 < K && !skipped(a, ng, K));
+    };
+    for (; (g = next_search(a.seg_off, a.koff, g, a.G, a.N, a.Ksum, mine)) < a.G; ++g) {
         int n0, ng, k0, K;
         search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
         if (n0 >= r1) break;

@@ -29,6 +29,9 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kRange = 4096;     // candidates per workgroup of the histogram / scatter walks
+constexpr int kDiaShort = 64;    // searches of at most this many candidates: all pairs by one wave (dia_wave);
+                                 // beyond, a lane's loop over the later members gets long (a search of 256
+                                 // candidates took 0.34 ms that way against 0.03 ms through the tiles)
 
 struct DiaArgs {
     int G, D, Ksum, Kmax;
@@ -44,6 +47,8 @@ struct DiaArgs {
     long long* bsum;      // [2 * blocks of the prefix sum] (members, tiles) per block
     unsigned* dmax;       // [Ksum] bits of the largest squared distance (aliases diam)
     int32_t* perm;        // [N]
+    int mixed;            // 1: searches of at most kDiaShort candidates go to dia_wave, longer ones
+                          //    through the grouping and the pair tiles, in the same call
 };
 
 __global__ void __launch_bounds__(kThreads) dia_zero(DiaArgs a) {
@@ -65,12 +70,17 @@ __global__ void __launch_bounds__(kThreads) dia_walk(DiaArgs a) {
         const int mid = (lo + hi) >> 1;
         if ((int64_t)a.seg_off[mid] <= r0) lo = mid; else hi = mid;
     }
-    for (int g = lo; g < a.G; ++g) {
+    const auto mine = [&](int n0, int ng, int k0, int K) {
+        return n0 >= r1 || (ng > 0 && K > 0 && !(a.mixed && ng <= kDiaShort));
+    };
+    for (int g = lo; (g = next_search(a.seg_off, a.koff, g, a.G, a.N, a.Ksum, mine)) < a.G; ++g) {
         int n0, ng, k0, K;
         search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
         if (K > KB_MAX_K) K = KB_MAX_K;
         if (n0 >= r1) break;
         if (ng <= 0 || K <= 0) continue;
+        if (a.mixed && ng <= kDiaShort) continue;         // (uniform) a wave of dia_wave takes this search:
+                                                          // its clusters keep size 0 here and get no tiles
         const int q0 = r0 > n0 ? (int)r0 : n0;
         const int q1 = r1 < (int64_t)n0 + ng ? (int)r1 : n0 + ng;
         if (q0 >= q1) continue;
@@ -360,6 +370,66 @@ __global__ void __launch_bounds__(kThreads) dia_pairs(DiaArgs a) {
     }
 }
 
+// Short searches: one wave per search, four searches per workgroup.  (The walks above
+// take the searches of a range one after the other with barriers around each, and the
+// grouping, the prefix sums and the tile numbering are seven launches: 0.34 ms for 183
+// searches of a few dozen candidates.)  Lane l takes candidates l, l + 64, ... and
+// compares each with the later members of its cluster; a pair's squared distance is
+// the same chain of fused multiply-adds over the features in index order as in the
+// tiles above, so the maxima are the same bits.
+__global__ void __launch_bounds__(kThreads) dia_wave(DiaArgs a) {
+    extern __shared__ unsigned wmax[];
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = (int)blockIdx.x * kWaves + wv;
+    if (g >= a.G) return;                 // (a whole wave leaves: no wave waits for another in this kernel)
+    const int D = a.D;
+    int n0, ng, k0, K;
+    search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+    if (K > a.Kmax) K = a.Kmax;
+    if (K <= 0) return;
+    if (a.mixed && ng > kDiaShort) return;            // the tile kernels take this search
+    unsigned* lmax = wmax + (size_t)wv * a.Kmax;      // [Kmax] bits of the largest squared distance
+    for (int j = lane; j < K; j += kWave) lmax[j] = 0u;
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    const bool vec = (D & 3) == 0;
+    for (int p = lane; p < ng; p += kWave) {
+        int jp = a.assign[(size_t)n0 + p];
+        jp = (jp >= 0 && jp < K) ? jp : 0;
+        const float* xp = a.X + ((size_t)n0 + p) * D;
+        float far = 0.f;
+        for (int q = p + 1; q < ng; ++q) {
+            int jq = a.assign[(size_t)n0 + q];
+            jq = (jq >= 0 && jq < K) ? jq : 0;
+            if (jq != jp) continue;
+            const float* xq = a.X + ((size_t)n0 + q) * D;
+            float acc = 0.f;
+            if (vec) {
+                for (int d = 0; d < D; d += 4) {
+                    const float4 u = *reinterpret_cast<const float4*>(xp + d);
+                    const float4 v = *reinterpret_cast<const float4*>(xq + d);
+                    float e = u.x - v.x; acc = fmaf(e, e, acc);
+                    e = u.y - v.y; acc = fmaf(e, e, acc);
+                    e = u.z - v.z; acc = fmaf(e, e, acc);
+                    e = u.w - v.w; acc = fmaf(e, e, acc);
+                }
+            } else {
+                for (int d = 0; d < D; ++d) {
+                    const float e = xp[d] - xq[d];
+                    acc = fmaf(e, e, acc);
+                }
+            }
+            far = fmaxf(far, acc);
+        }
+        if (far > 0.f) atomicMax(&lmax[jp], __float_as_uint(far));
+    }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    for (int j = lane; j < K; j += kWave) {
+        if (a.mixed) a.dmax[k0 + j] = lmax[j];        // dia_final takes the root of every cluster
+        else a.diam[k0 + j] = sqrtf(__uint_as_float(lmax[j]));
+    }
+}
+
 __global__ void __launch_bounds__(kThreads) dia_final(DiaArgs a) {
     const int i = blockIdx.x * kThreads + threadIdx.x;
     if (i < a.Ksum) a.diam[i] = sqrtf(__uint_as_float(a.dmax[i]));
@@ -370,12 +440,23 @@ __global__ void __launch_bounds__(kThreads) dia_final(DiaArgs a) {
 hipError_t launch_diameter(const kb_batch& b, const DiameterCall& c, hipStream_t st) {
     if (b.Ksum <= 0) return hipSuccess;
     DiaArgs a;
-    a.G = b.G; a.D = b.D; a.Ksum = b.Ksum; a.Kmax = b.Kmax; a.N = b.N;
+    a.G = b.G; a.D = b.D; a.Ksum = b.Ksum; a.Kmax = b.Kmax > 0 ? b.Kmax : 1; a.N = b.N;
     a.seg_off = b.seg_off; a.koff = b.koff; a.X = c.X; a.assign = c.assign; a.diam = c.diam;
     a.cnt = c.cnt; a.off = c.off; a.toff = c.toff; a.bsum = c.bsum; a.dmax = reinterpret_cast<unsigned*>(c.diam); a.perm = c.perm;
     const unsigned kblocks = (unsigned)((b.Ksum + kThreads - 1) / kThreads);
     const unsigned ranges = (unsigned)((b.N + kRange - 1) / kRange);
+    // a batch of short searches only: a wave per search, one launch; a batch of several
+    // searches with longer ones among them: the wave kernel after the maxima are zeroed,
+    // then the grouping and the tiles, which leave the short searches out
+    a.mixed = b.Nmax > kDiaShort && b.G > 1;
+    const size_t wlds = (size_t)kWaves * 4 * (b.Kmax > 0 ? b.Kmax : 1);
+    const dim3 wgrid((unsigned)((b.G + kWaves - 1) / kWaves));
+    if (b.Nmax <= kDiaShort && b.G > 0) {
+        hipLaunchKernelGGL(dia_wave, wgrid, dim3(kThreads), wlds, st, a);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(dia_zero, dim3(kblocks), dim3(kThreads), 0, st, a);
+    if (a.mixed) hipLaunchKernelGGL(dia_wave, wgrid, dim3(kThreads), wlds, st, a);
     if (ranges) hipLaunchKernelGGL(dia_walk<false>, dim3(ranges), dim3(kThreads), 0, st, a);
     const int nscan = (b.Ksum + kScanBlock - 1) / kScanBlock;
     hipLaunchKernelGGL(dia_bsum, dim3((unsigned)nscan), dim3(kThreads), 0, st, a);

@@ -84,7 +84,10 @@ __global__ void __launch_bounds__(kThreads) geo_dist(GeoArgs a) {
         const int mid = (lo + hi) >> 1;
         if ((int64_t)a.seg_off[mid] <= r0) lo = mid; else hi = mid;
     }
-    for (int g = lo; g < a.G; ++g) {
+    const auto mine = [&](int n0, int ng, int k0, int K) {
+        return n0 >= r1 || (ng > 0 && K > 0 && !(a.mixed && ng <= kShortSearch));
+    };
+    for (int g = lo; (g = next_search(a.seg_off, a.koff, g, a.G, a.N, a.Ksum, mine)) < a.G; ++g) {
         int n0, ng, k0, K;
         search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
         if (K > a.Kmax) K = a.Kmax;
@@ -206,7 +209,10 @@ __global__ void __launch_bounds__(kThreads) geo_rep(GeoArgs a) {
         const int mid = (lo + hi) >> 1;
         if ((int64_t)a.seg_off[mid] <= r0) lo = mid; else hi = mid;
     }
-    for (int g = lo; g < a.G; ++g) {
+    const auto mine = [&](int n0, int ng, int k0, int K) {
+        return n0 >= r1 || (ng > 0 && K > 0 && !(a.mixed && ng <= kShortSearch));
+    };
+    for (int g = lo; (g = next_search(a.seg_off, a.koff, g, a.G, a.N, a.Ksum, mine)) < a.G; ++g) {
         int n0, ng, k0, K;
         search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
         if (K > a.Kmax) K = a.Kmax;

@@ -33,11 +33,16 @@ constexpr int kOneWgMaxN = 65536;
 // by staying on one compute unit: there the multi-workgroup path takes over earlier
 // (measured: a lone search of 32768 candidates 1.47 against 1.16 ms, eight of 30000 6.1
 // against 1.7 ms; 32 searches of 16000 are as fast either way).
+// The same holds for a few long searches among many short ones, which are done long
+// before the long ones (2000 searches of 12-41 candidates and one of 30000: 1.67 ms,
+// all of it the long one on its compute unit).  The host does not see the lengths, but
+// a batch of at most 32 * 24576 candidates cannot hold more than 32 searches beyond 24576.
 constexpr int kFewSearches = 32;
 constexpr int kFewSearchesMaxN = 24576;
 // most candidates of a search that the one-workgroup Lloyd kernel takes in this batch
 inline int one_wg_limit_n(const kb_batch& b) {
-    return (b.G <= kFewSearches && b.Nmax > kFewSearchesMaxN) ? kFewSearchesMaxN : kOneWgMaxN;
+    const bool few_long = b.G <= kFewSearches || b.N <= (int64_t)kFewSearches * kFewSearchesMaxN;
+    return (few_long && b.Nmax > kFewSearchesMaxN) ? kFewSearchesMaxN : kOneWgMaxN;
 }
 inline bool cluster_uses_big(const kb_batch& b) { return b.Kmax > kOneWgMaxK || b.Nmax > one_wg_limit_n(b); }
 // (limit_n: one_wg_limit_n of the batch)
@@ -134,6 +139,7 @@ struct UcbCall {
     int chunked, keep_tables, from_tables;
 };
 hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st);
+bool ucb_wave_per_search(const kb_batch& b);   // a plain or table-keeping selection call runs one wave per search (no scheduling order needed)
 
 // The whole round of a batch of very short searches in one launch (one wave per
 // search): true if batch and mode allow it; the launch itself takes the three
@@ -229,6 +235,32 @@ __device__ __forceinline__ void search_bounds(const int32_t* seg_off, const int3
     int c = clampi(koff[g], 0, Ksum);
     int d = clampi(koff[g + 1], c, Ksum);
     n0 = a; ng = b - a; k0 = c; K = d - c;
+}
+
+// The first search g' >= g whose bounds satisfy take(n0, ng, k0, K), or G.  For kernels
+// whose workgroups walk the searches of a candidate range but handle only some of them
+// (a batch of a few long searches among thousands of short ones: a walk that looks at
+// one search at a time spends 0.25 us of dependent loads on every search it skips).
+// The 64 lanes of a wave test 64 searches at once; every wave of a workgroup gets the
+// same answer on its own, so no barrier is involved.  `take` must also hold for the
+// first search beyond the range, where the walk ends.
+template <class F>
+__device__ __forceinline__ int next_search(const int32_t* seg_off, const int32_t* koff, int g, int G,
+                                           int64_t N, int Ksum, F take) {
+    const int lane = threadIdx.x & 63;
+    while (g < G) {
+        const int gi = g + lane;
+        bool hit = false;
+        if (gi < G) {
+            int n0, ng, k0, K;
+            search_bounds(seg_off, koff, gi, N, Ksum, n0, ng, k0, K);
+            hit = take(n0, ng, k0, K);
+        }
+        const unsigned long long m = __ballot(hit);
+        if (m) return g + __ffsll((long long)m) - 1;
+        g += 64;
+    }
+    return G;
 }
 
 }  // namespace kb

@@ -148,6 +148,50 @@ __global__ void __launch_bounds__(kThreads) ucb_kernel(UcbArgs a) {
 }
 
 
+// ---- short searches: a wave per search, four searches per workgroup, no barrier.
+// A lane owns a candidate and adds its two rows to the wave's own tables; the same
+// integer tables as above, so the same scores and the same selection.
+__global__ void __launch_bounds__(kThreads) ucb_wave(UcbArgs a, int per) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = (int)blockIdx.x * kWaves + wv;
+    if (g >= a.G) return;                 // (a whole wave leaves: no wave waits for another in this kernel)
+    const int S = a.S;
+    int n0, ng, k0, K;
+    search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
+    if (K > a.Kmax) K = a.Kmax;
+    if (ng <= 0 || K <= 0) {
+        if (lane < 3) a.sel[(size_t)g * 3 + lane] = -1;
+        return;
+    }
+    const int KS = K * S;
+    unsigned char* base = smem + (size_t)wv * per;
+    unsigned long long* R = reinterpret_cast<unsigned long long*>(base);                 // [Kmax*S]
+    unsigned long long* kmin = R + (size_t)a.Kmax * S;                                   // [Kmax]
+    unsigned* Ncnt = reinterpret_cast<unsigned*>(kmin + a.Kmax);                         // [Kmax*S]
+    unsigned* nalive = Ncnt + (size_t)a.Kmax * S;                                        // [Kmax]
+    for (int i = lane; i < KS; i += kWave) { R[i] = 0ull; Ncnt[i] = 0u; }
+    for (int i = lane; i < K; i += kWave) { kmin[i] = ~0ull; nalive[i] = 0u; }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    for (int p = lane; p < ng; p += kWave) {
+        if (a.alive && !a.alive[(size_t)n0 + p]) continue;
+        int j = a.assign[(size_t)n0 + p];
+        j = (j >= 0 && j < K) ? j : 0;
+        ucb_add_candidate(a, (size_t)n0 + p, p, j, a.bound ? a.bound[(size_t)n0 + p] : 0.f, Ncnt, R, nalive, kmin);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    if (a.keep) {
+        for (int i = lane; i < KS; i += kWave) {
+            a.gN[(size_t)k0 * S + i] = Ncnt[i];
+            a.gR[(size_t)k0 * S + i] = R[i];
+        }
+        for (int i = lane; i < K; i += kWave) { a.gnalive[k0 + i] = nalive[i]; a.gkmin[k0 + i] = kmin[i]; }
+    }
+    ucb_finish<kWave>(a, g, n0, k0, K, Ncnt, R, nalive, kmin, nullptr, nullptr, lane);
+}
+
+
 // ---- searches too long for one workgroup: partial tables per candidate range,
 // ---- merged in global memory with integer atomics (still order-independent)
 constexpr int kUcbRange = 8192;
@@ -176,7 +220,10 @@ __global__ void __launch_bounds__(kThreads) ucb_partial(UcbArgs a) {
         const int mid = (lo + hi) >> 1;
         if ((int64_t)a.seg_off[mid] <= r0) lo = mid; else hi = mid;
     }
-    for (int g = lo; g < a.G; ++g) {
+    const auto mine = [&](int n0, int ng, int k0, int K) {
+        return n0 >= r1 || (ng > 0 && K > 0 && !(a.mixed && ng <= kUcbLong));
+    };
+    for (int g = lo; (g = next_search(a.seg_off, a.koff, g, a.G, a.N, a.Ksum, mine)) < a.G; ++g) {
         int n0, ng, k0, K;
         search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
         if (K > a.Kmax) K = a.Kmax;
@@ -224,6 +271,16 @@ __global__ void __launch_bounds__(kThreads) ucb_final(UcbArgs a) {
 
 }  // namespace
 
+// bytes of one search's tables in ucb_wave
+static int wave_table_bytes(const kb_batch& b) {
+    const size_t kmax = b.Kmax > 0 ? b.Kmax : 1;
+    return (int)(((kmax * b.S * 12 + kmax * 12) + 15) & ~(size_t)15);
+}
+
+bool ucb_wave_per_search(const kb_batch& b) {
+    return b.G > 0 && b.Nmax <= kShortSearch && (size_t)wave_table_bytes(b) * kWaves <= 64 * 1024;
+}
+
 hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st) {
     UcbArgs a = make_ucb_args(b, c);
     const size_t lds = 64 + (size_t)a.Kmax * b.S * 12 + (size_t)a.Kmax * 12;
@@ -257,6 +314,14 @@ hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st) {
         const unsigned ranges = (unsigned)((b.N + kUcbRange - 1) / kUcbRange);
         if (ranges) hipLaunchKernelGGL(ucb_partial, dim3(ranges), dim3(kThreads), lds, st, a);
         hipLaunchKernelGGL(ucb_final, dim3((unsigned)b.G), dim3(kThreads), 0, st, a);
+        return hipGetLastError();
+    }
+    // a batch of short searches only: a wave per search (if four searches' tables fit the
+    // 64 KB of LDS a kernel gets without asking); needs no scheduling order
+    if (ucb_wave_per_search(b)) {
+        const int per = wave_table_bytes(b);
+        hipLaunchKernelGGL(ucb_wave, dim3((unsigned)((b.G + kWaves - 1) / kWaves)), dim3(kThreads),
+                           (size_t)per * kWaves, st, a, per);
         return hipGetLastError();
     }
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ucb_kernel),

@@ -42,6 +42,37 @@ __device__ __forceinline__ unsigned ordered_bits(float f) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// One alive candidate's visits and reward sums (row `row` of the two arrays) into the
+// tables of its cluster j; p is its index inside the search and bd its roofline bound
+// (the member with the smallest bound, lowest index on ties, is the cluster's k*).
+// For the kernels in which a lane owns a whole candidate.
+__device__ __forceinline__ void ucb_add_candidate(const UcbArgs& a, size_t row, int p, int j, float bd,
+                                                  unsigned* Ncnt, unsigned long long* R,
+                                                  unsigned* nalive, unsigned long long* kmin) {
+    const int S = a.S;
+    const int32_t* vis = a.visits + row * S;
+    const float* rs = a.rsum + row * S;
+    unsigned* nc = Ncnt + (size_t)j * S;
+    unsigned long long* rr = R + (size_t)j * S;
+    if ((S & 3) == 0) {
+        for (int s = 0; s < S; s += 4) {
+            const int4 v = *reinterpret_cast<const int4*>(vis + s);
+            const float4 r = *reinterpret_cast<const float4*>(rs + s);
+            atomicAdd(nc + s + 0, (unsigned)v.x); atomicAdd(nc + s + 1, (unsigned)v.y);
+            atomicAdd(nc + s + 2, (unsigned)v.z); atomicAdd(nc + s + 3, (unsigned)v.w);
+            atomicAdd(rr + s + 0, reward_fixed(r.x)); atomicAdd(rr + s + 1, reward_fixed(r.y));
+            atomicAdd(rr + s + 2, reward_fixed(r.z)); atomicAdd(rr + s + 3, reward_fixed(r.w));
+        }
+    } else {
+        for (int s = 0; s < S; ++s) {
+            atomicAdd(nc + s, (unsigned)vis[s]);
+            atomicAdd(rr + s, reward_fixed(rs[s]));
+        }
+    }
+    atomicAdd(&nalive[j], 1u);
+    atomicMin(&kmin[j], ((unsigned long long)ordered_bits(bd) << 32) | (unsigned)p);
+}
+
 // Scores, outputs and selection of one search from its accumulated tables
 // (which may live in LDS or in global memory).  Called by a whole workgroup of NT
 // threads, or, with NT = 64, by one wave on its own (tid = the lane; redv and redi

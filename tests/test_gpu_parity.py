@@ -70,10 +70,17 @@ SMALL = {
     "manylong": lambda: synth.config5(G=258, nmin=2048, nmax=2100, D=8, S=4, iters=3, seed=321),
     "lateoutliers": _late_outliers,
     # the longest search the one-workgroup path takes: candidate numbers up to 2^16 - 1
-    # (in a batch of more than 32 searches; with fewer, a search this long is spread over
-    # many workgroups)
+    # (in a batch of more than 32 searches and more than 32 * 24576 candidates; in a
+    # smaller batch a search this long is spread over many workgroups)
     "long1wg": lambda: synth.concat(synth.config2(N=65536, D=16, K=24, S=4, iters=6, seed=11),
-                                    synth.config5(G=40, nmin=20, nmax=90, D=16, S=4, iters=6, seed=12), "long1wg"),
+                                    synth.config5(G=330, nmin=2000, nmax=2600, D=16, S=4, iters=6, kcap=16,
+                                                  seed=12), "long1wg"),
+    # one long search behind 300 of the paper's size: the long one takes the multi-workgroup
+    # kernels and the range kernels of the selection, whose workgroups skip the short
+    # searches of their candidate ranges 64 at a time
+    "tinylong": lambda: synth.concat(synth.config5(G=300, nmin=12, nmax=41, D=5, S=6, iters=6, kcap=3, kdiv=4,
+                                                   seed=21),
+                                     synth.config2(N=30000, D=5, K=3, S=6, iters=6, seed=22), "tinylong"),
     # few searches, two of them long: those take the multi-workgroup path although they
     # have no more than 64 clusters, the short ones the one-workgroup kernel
     "fewlong": lambda: synth.concat(synth.config5(G=2, nmin=30000, nmax=30100, D=16, S=4, iters=5, seed=13),
@@ -93,7 +100,7 @@ SMALL = {
 # kb_cluster call because it saw a near-tie in one of the Lloyd steps.  The inputs
 # are seeded and the oracle is deterministic, so these are exact counts: an
 # exclusion set that grows fails the test.
-NEAR_TIE_SEARCHES = {"cfg3s": 1, "cfg5s": 4, "lateoutliers": 1, "fewlong": 3}
+NEAR_TIE_SEARCHES = {"cfg3s": 1, "cfg5s": 4, "lateoutliers": 1, "fewlong": 3, "long1wg": 4}
 
 
 @pytest.fixture(scope="module", params=[0, 1, 2], ids=["bounds", "vectoralu", "matrixcore"])

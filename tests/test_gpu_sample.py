@@ -51,6 +51,11 @@ CASES = {
     # batches of short searches (at most 256 candidates each): a wave per search
     "paperscale": lambda: synth.paper_scale(),
     "short": lambda: synth.config5(G=300, nmin=1, nmax=256, D=12, S=4, iters=3, kcap=16, kdiv=4, seed=77),
+    # a longer search behind 300 of the paper's size: waves for the short ones, the range
+    # kernels - which skip the short searches of their ranges 64 at a time - for the long one
+    "tinylong": lambda: synth.concat(synth.config5(G=300, nmin=12, nmax=41, D=5, S=6, iters=3, kcap=3, kdiv=4,
+                                                   seed=21),
+                                     synth.config2(N=9000, D=5, K=3, S=6, iters=3, seed=22), "tinylong"),
 }
 
 DRAWS = [(20251118, 0, 1.0), (20251118, 1, 1.0), (7, 2 ** 40 + 3, 0.25), (2 ** 63 + 11, 5, 8.0)]
