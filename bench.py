@@ -324,6 +324,20 @@ def main():
         _, p_med = timed(dp.round, 50)
         cfgs["paper_scale"] = {"N": bp.N, "G": bp.G, "D": bp.D, "Kmax": bp.Kmax, "S": bp.S,
                                "iters": bp.iters, "round_us": round(p_med * 1e3, 1), "bound": "latency"}
+        # twenty whole iterations of Alg. 1 in one call, re-clustering every tenth
+        Rp, Tp = 3, 20
+        hp, tgp, thp = synth.signatures(bp, Rp)
+        fbp = [synth.feedback(bp, seed=r) for r in range(Tp)]
+        upp = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        dhp, dtp = upp(hp), upp(tgp)
+        drp, dop = upp(np.stack([f[0] for f in fbp])), upp(np.stack([f[1] for f in fbp]))
+        slp = torch.zeros((Tp, bp.G, 3), dtype=torch.int32, device=dev)
+        klp = torch.zeros((Tp, bp.G), dtype=torch.int32, device=dev)
+        ipp = kb.kb_iterate_params(Tp, 10, 0, 1, Rp, thp, kb.kb_sample_params(20251118, 1, 1.0))
+        itp = lambda: dp.iterate(ipp, dhp, dtp, drp, dop, slp, klp)
+        itp()
+        torch.cuda.synchronize()
+        cfgs["paper_scale"]["iteration_us"] = round(timed(itp, 10)[1] * 1e3 / Tp, 1)
         del dp, bp
         out["configs"] = cfgs
 
