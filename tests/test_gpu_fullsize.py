@@ -31,7 +31,7 @@ def _sync():
 
 # searches the oracle excludes as near-ties at full size (seeded inputs, deterministic
 # oracle: exact counts; none of the selections is a near-tie)
-NEAR_TIE_SEARCHES = {"config3": 3, "config5": 56}
+NEAR_TIE_SEARCHES = {"config3": 3, "config5": 56, "manytiny": 0}
 
 
 def _full_round_vs_oracle(kb, b, name):
@@ -131,6 +131,12 @@ def test_config3_full(kb):
 
 def test_config5_full(kb):
     _full_round_vs_oracle(kb, synth.config5(), "config5")
+
+
+def test_many_tiny_searches_full(kb):
+    """20000 searches of 1 to 40 candidates: every stage runs its wave-per-search kernel,
+    at a grid of 5000 workgroups."""
+    _full_round_vs_oracle(kb, synth.config5(G=20000, nmin=1, nmax=40, D=8, S=4, iters=4, seed=15), "manytiny")
 
 
 def _oracle_assign_sliced(b, cent, parts=64):
