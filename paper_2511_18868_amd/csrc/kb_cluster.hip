@@ -1219,8 +1219,16 @@ __host__ __device__ inline Lds lds_layout(int Kmax, int D, int DP, int Nmax, int
 // registers by the matrix-core scorer, MT = 0 selects the vector-ALU scorer.
 // VEC: D is a multiple of 4, so the matrix-core scorers fetch rows in 16-byte pieces;
 // otherwise (a compile-time choice, so the loops hold one form only) feature by feature.
+// Workgroups per compute unit in the 256-thread shape: three, and four (128 registers,
+// a few of them spilled) where at most 32 clusters and 48 features leave room for it -
+// batches of many short searches gain 10-17 % from the fourth resident search
+// (measured; five cost more in spills than they gain, and with two centroid tiles in
+// registers four were 4 % slower).
+constexpr int narrow_workgroups_per_cu(int DS, int MT) { return (MT == 1 && DS <= 3) ? 4 : 3; }
+
 template <int DS, int MT, int NT, bool VEC = true>
-__global__ void __launch_bounds__(NT, NT == kThreadsNarrow ? 3 : 1) cluster_fused_kernel(ClusterArgs a) {
+__global__ void __launch_bounds__(NT, NT == kThreadsNarrow ? narrow_workgroups_per_cu(DS, MT) : 1)
+cluster_fused_kernel(ClusterArgs a) {
     constexpr int kThreads = NT, kWaves = NT / kWave;
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
