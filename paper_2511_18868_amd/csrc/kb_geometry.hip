@@ -59,8 +59,8 @@ __global__ void __launch_bounds__(kThreads) geo_dist(GeoArgs a) {
     const int tid = threadIdx.x;
     // row stride of the transposed tile: D + 4 words keeps 16-byte pieces aligned and
     // spreads consecutive rows over the banks (conflict-free 16-byte reads whenever
-    // D/4 is even); D + 1 for the scalar path
-    const int D = a.D, DP = VEC == 4 ? D + 4 : D + 1;
+    // D/4 is even); the next odd number for the scalar path
+    const int D = a.D, DP = VEC == 4 ? D + 4 : (D | 1);
     unsigned long long* lmin = reinterpret_cast<unsigned long long*>(smem);          // [Kmax]
     unsigned long long* lmax = lmin + a.Kmax;                                         // [Kmax]
     float* lc = reinterpret_cast<float*>(lmax + a.Kmax);                              // [Kmax * D]
@@ -129,10 +129,33 @@ __global__ void __launch_bounds__(kThreads) geo_dist(GeoArgs a) {
                 }
             }
         };
-        fetch(q0);
+        if constexpr (VEC == 4) fetch(q0);
         for (int tb = q0; tb < q1; tb += kThreads) {
             const int cnt = q1 - tb < kThreads ? q1 - tb : kThreads;
             const int total = cnt * D / VEC;
+            if constexpr (VEC == 1) {
+                // feature by feature: straight from memory into the transposed tile, eight
+                // values in flight per thread (holding a whole tile's 64 values per thread
+                // for the next round, as the 16-byte form does, leaves room for one
+                // workgroup per compute unit only)
+                const float* src = a.X + (size_t)tb * D;
+                int row = row0, col = col0;
+                for (int i0 = 0; i0 < npieces; i0 += 8) {
+                    float v[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int idx = tid + (i0 + u) * kThreads;
+                        v[u] = (i0 + u < npieces && idx < total) ? src[idx] : 0.f;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int idx = tid + (i0 + u) * kThreads;
+                        if (i0 + u < npieces && idx < total) lx[row * DP + col] = v[u];
+                        row += qd; col += rd;
+                        if (col >= D) { col -= D; row += 1; }
+                    }
+                }
+            } else
             // registers -> LDS, one row per candidate
             {
                 int row = row0, col = col0;
@@ -155,7 +178,9 @@ __global__ void __launch_bounds__(kThreads) geo_dist(GeoArgs a) {
             int j = p < q1 ? a.assign[p] : 0;
             j = (j >= 0 && j < K) ? j : 0;
             __syncthreads();
-            if (tb + kThreads < q1) fetch(tb + kThreads);
+            if constexpr (VEC == 4) {
+                if (tb + kThreads < q1) fetch(tb + kThreads);
+            }
             if (tid < cnt) {
                 const float* xrow = lx + tid * DP;
                 const float* crow = lc + (size_t)j * D;
@@ -177,7 +202,20 @@ __global__ void __launch_bounds__(kThreads) geo_dist(GeoArgs a) {
                         acc = __dadd_rn(acc, __dmul_rn(diff, diff));
                     }
                 } else {
-                    for (int d = 0; d < D; ++d) {
+                    // eight features' values requested before the first is used; the sum
+                    // itself stays in index order
+                    int d = 0;
+                    for (; d + 8 <= D; d += 8) {
+                        float xv[8], cv[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) { xv[u] = xrow[d + u]; cv[u] = crow[d + u]; }
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const double diff = __dsub_rn((double)xv[u], (double)cv[u]);
+                            acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+                        }
+                    }
+                    for (; d < D; ++d) {
                         const double diff = __dsub_rn((double)xrow[d], (double)crow[d]);
                         acc = __dadd_rn(acc, __dmul_rn(diff, diff));
                     }
