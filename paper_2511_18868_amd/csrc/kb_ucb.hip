@@ -22,89 +22,99 @@ constexpr int kUcbLong = 16384;     // searches longer than this are cut into ca
 
 // Scatter the visits / reward sums of the alive candidates [q0, q1) of a search
 // (indices local to the search) into K x S tables keyed by cluster.
-__device__ __forceinline__ void ucb_accumulate(const UcbArgs& a, int n0, int K, int q0, int q1,
-                                               unsigned* Ncnt, unsigned long long* R,
-                                               unsigned* nalive, unsigned long long* kmin) {
+//
+// A candidate's two rows are cut into pieces of E values - 16 bytes when S is a
+// multiple of 4, 8 bytes when it is even, single values otherwise (the rows start at
+// multiples of 4 S bytes, so that is the alignment they have) - and T threads, the
+// next power of two at or above the number of pieces, share a candidate: the
+// thread-to-piece mapping is fixed, so no index arithmetic per step (with S = 6, the
+// paper's own count, a loop over single values that divides every index by S ran at a
+// quarter of the rate of S = 8).  Four candidates per thread are in flight: mask and
+// cluster first, then the rows of the alive ones, then the atomics.
+// EXACT: the pieces of a row are a power of two in number, one per thread of its group
+// (no idle threads and no loop over pieces).
+template <int E, bool EXACT>
+__device__ __forceinline__ void ucb_accumulate_pieces(const UcbArgs& a, int n0, int K, int q0, int q1,
+                                                      unsigned* Ncnt, unsigned long long* R,
+                                                      unsigned* nalive, unsigned long long* kmin) {
     const int tid = threadIdx.x;
     const int S = a.S;
-    const int ng = q1 - q0;
-    const int32_t* vis = a.visits + ((size_t)n0 + q0) * S;
-    const float* rs = a.rsum + ((size_t)n0 + q0) * S;
-    if ((S & 3) == 0 && (kThreads % (S >> 2)) == 0) {
-        // S/4 threads per candidate, each owning one 16-byte piece of its two rows;
-        // the thread-to-piece mapping is fixed, so no index arithmetic per step.  Four
-        // candidates per thread are in flight: mask and cluster first, then the rows
-        // of the alive ones, then the atomics.
-        const int S4 = S >> 2;
-        const int rpp = kThreads / S4;            // candidates per pass of the workgroup
-        const int sq = tid % S4, row = tid / S4;
-        const int s0 = sq * 4;
-        constexpr int U = 4;
-        for (int pb = q0 + row; pb < q1; pb += rpp * U) {
-            bool al[U];
-            int jj[U];
-            float bd[U];
-            int4 v[U];
-            float4 r[U];
+    const int pieces = S / E;
+    int T = 1;
+    while (T < pieces && T < kThreads) T <<= 1;
+    const int rpp = kThreads / T;             // candidates per pass of the workgroup
+    const int sq = tid & (T - 1), row = tid / T;
+    constexpr int U = 4;
+    for (int pb = q0 + row; pb < q1; pb += rpp * U) {
+        bool al[U];
+        int jj[U];
+        float bd[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int p = pb + u * rpp;
+            const int pc = p < q1 ? p : q1 - 1;
+            al[u] = (a.alive ? a.alive[(size_t)n0 + pc] != 0 : true) && p < q1;
+            jj[u] = a.assign[(size_t)n0 + pc];
+            bd[u] = a.bound ? a.bound[(size_t)n0 + pc] : 0.f;
+        }
+        const auto piece = [&](int c) {
+            int v[U][E];
+            float r[U][E];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int p = pb + u * rpp;
-                const int pc = p < q1 ? p : q1 - 1;
-                al[u] = (a.alive ? a.alive[(size_t)n0 + pc] != 0 : true) && p < q1;
-                jj[u] = a.assign[(size_t)n0 + pc];
-                bd[u] = a.bound ? a.bound[(size_t)n0 + pc] : 0.f;
-            }
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int p = pb + u * rpp;
-                v[u] = make_int4(0, 0, 0, 0);
-                r[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int e = 0; e < E; ++e) { v[u][e] = 0; r[u][e] = 0.f; }
                 if (al[u]) {
-                    v[u] = reinterpret_cast<const int4*>(a.visits)[((size_t)n0 + p) * S4 + sq];
-                    r[u] = reinterpret_cast<const float4*>(a.rsum)[((size_t)n0 + p) * S4 + sq];
+                    const size_t at = ((size_t)n0 + p) * pieces + c;
+                    if constexpr (E == 4) {
+                        const int4 vv = reinterpret_cast<const int4*>(a.visits)[at];
+                        const float4 rv = reinterpret_cast<const float4*>(a.rsum)[at];
+                        v[u][0] = vv.x; v[u][1] = vv.y; v[u][2] = vv.z; v[u][3] = vv.w;
+                        r[u][0] = rv.x; r[u][1] = rv.y; r[u][2] = rv.z; r[u][3] = rv.w;
+                    } else if constexpr (E == 2) {
+                        const int2 vv = reinterpret_cast<const int2*>(a.visits)[at];
+                        const float2 rv = reinterpret_cast<const float2*>(a.rsum)[at];
+                        v[u][0] = vv.x; v[u][1] = vv.y;
+                        r[u][0] = rv.x; r[u][1] = rv.y;
+                    } else {
+                        v[u][0] = a.visits[at];
+                        r[u][0] = a.rsum[at];
+                    }
                 }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (!al[u]) continue;
-                const int p = pb + u * rpp;
                 const int j = (jj[u] >= 0 && jj[u] < K) ? jj[u] : 0;
-                unsigned* nc = Ncnt + (size_t)j * S + s0;
-                unsigned long long* rr = R + (size_t)j * S + s0;
-                atomicAdd(nc + 0, (unsigned)v[u].x); atomicAdd(nc + 1, (unsigned)v[u].y);
-                atomicAdd(nc + 2, (unsigned)v[u].z); atomicAdd(nc + 3, (unsigned)v[u].w);
-                atomicAdd(rr + 0, reward_fixed(r[u].x));
-                atomicAdd(rr + 1, reward_fixed(r[u].y));
-                atomicAdd(rr + 2, reward_fixed(r[u].z));
-                atomicAdd(rr + 3, reward_fixed(r[u].w));
-                if (sq == 0) {
+                unsigned* nc = Ncnt + (size_t)j * S + c * E;
+                unsigned long long* rr = R + (size_t)j * S + c * E;
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    atomicAdd(nc + e, (unsigned)v[u][e]);
+                    atomicAdd(rr + e, reward_fixed(r[u][e]));
+                }
+                if (c == 0) {         // the thread with a row's first piece also counts the candidate
                     atomicAdd(&nalive[j], 1u);
                     const unsigned long long key =
-                        ((unsigned long long)ordered_bits(bd[u]) << 32) | (unsigned)p;
+                        ((unsigned long long)ordered_bits(bd[u]) << 32) | (unsigned)(pb + u * rpp);
                     atomicMin(&kmin[j], key);
                 }
             }
-        }
-    } else {
-        const size_t total = (size_t)ng * S;
-        for (size_t q = tid; q < total; q += kThreads) {
-            const int pl = (int)(q / S), p = q0 + pl;
-            const int s = (int)(q - (size_t)pl * S);
-            if (a.alive && !a.alive[(size_t)n0 + p]) continue;
-            int j = a.assign[(size_t)n0 + p];
-            j = (j >= 0 && j < K) ? j : 0;
-            atomicAdd(&Ncnt[(size_t)j * S + s], (unsigned)vis[q]);
-            atomicAdd(&R[(size_t)j * S + s], reward_fixed(rs[q]));
-            if (s == 0) {
-                atomicAdd(&nalive[j], 1u);
-                const unsigned long long key =
-                    ((unsigned long long)ordered_bits(a.bound ? a.bound[(size_t)n0 + p] : 0.f) << 32) | (unsigned)p;
-                atomicMin(&kmin[j], key);
-            }
+        };
+        if constexpr (EXACT) {
+            piece(sq);
+        } else {
+            for (int c = sq; c < pieces; c += T) piece(c);     // (one round unless a row has more than 256 pieces)
         }
     }
 }
 
+
+// E, EXACT: how the rows are cut (ucb_accumulate_pieces); instantiations of their own,
+// so that each form has the registers it needs and no more (in one kernel the forms for
+// odd strategy counts raised the count from 64 to 99 and halved the resident waves of all)
+template <int E, bool EXACT>
 __global__ void __launch_bounds__(kThreads) ucb_kernel(UcbArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
@@ -133,7 +143,7 @@ __global__ void __launch_bounds__(kThreads) ucb_kernel(UcbArgs a) {
     for (int i = tid; i < K; i += kThreads) { kmin[i] = ~0ull; nalive[i] = 0u; }
     __syncthreads();
 
-    ucb_accumulate(a, n0, K, 0, ng, Ncnt, R, nalive, kmin);
+    ucb_accumulate_pieces<E, EXACT>(a, n0, K, 0, ng, Ncnt, R, nalive, kmin);
     __syncthreads();
 
     if (a.keep) {
@@ -203,6 +213,7 @@ __global__ void __launch_bounds__(kThreads) ucb_zero(UcbArgs a) {
     for (int64_t i = t0; i < a.Ksum; i += stride) { a.gnalive[i] = 0u; a.gkmin[i] = ~0ull; }
 }
 
+template <int E, bool EXACT>
 __global__ void __launch_bounds__(kThreads) ucb_partial(UcbArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
@@ -237,7 +248,7 @@ __global__ void __launch_bounds__(kThreads) ucb_partial(UcbArgs a) {
         for (int i = tid; i < KS; i += kThreads) { R[i] = 0ull; Ncnt[i] = 0u; }
         for (int i = tid; i < K; i += kThreads) { kmin[i] = ~0ull; nalive[i] = 0u; }
         __syncthreads();
-        ucb_accumulate(a, n0, K, (int)(q0 - n0), (int)(q1 - n0), Ncnt, R, nalive, kmin);
+        ucb_accumulate_pieces<E, EXACT>(a, n0, K, (int)(q0 - n0), (int)(q1 - n0), Ncnt, R, nalive, kmin);
         __syncthreads();
         for (int i = tid; i < KS; i += kThreads) {
             if (Ncnt[i]) atomicAdd(&a.gN[(size_t)k0 * S + i], Ncnt[i]);
@@ -281,6 +292,52 @@ bool ucb_wave_per_search(const kb_batch& b) {
     return b.G > 0 && b.Nmax <= kShortSearch && (size_t)wave_table_bytes(b) * kWaves <= 64 * 1024;
 }
 
+namespace {
+
+// the aggregation kernels in the form that fits the strategy count (see ucb_accumulate_pieces)
+template <int E, bool EXACT>
+hipError_t launch_search_kernel(const UcbArgs& a, size_t lds, hipStream_t st) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ucb_kernel<E, EXACT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((ucb_kernel<E, EXACT>), dim3((unsigned)a.G), dim3(kThreads), lds, st, a);
+    return hipGetLastError();
+}
+template <int E, bool EXACT>
+hipError_t launch_range_kernel(const UcbArgs& a, unsigned ranges, size_t lds, hipStream_t st) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ucb_partial<E, EXACT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((ucb_partial<E, EXACT>), dim3(ranges), dim3(kThreads), lds, st, a);
+    return hipGetLastError();
+}
+// form 0: 16-byte pieces, a power of two of them per row; 1: 16-byte pieces; 2: 8-byte; 3: single values
+int row_form(int S) {
+    if ((S & 3) == 0) {
+        const int pieces = S >> 2;
+        return ((pieces & (pieces - 1)) == 0 && pieces <= kThreads) ? 0 : 1;
+    }
+    return (S & 1) == 0 ? 2 : 3;
+}
+hipError_t launch_search_kernel(const UcbArgs& a, size_t lds, hipStream_t st) {
+    switch (row_form(a.S)) {
+        case 0: return launch_search_kernel<4, true>(a, lds, st);
+        case 1: return launch_search_kernel<4, false>(a, lds, st);
+        case 2: return launch_search_kernel<2, false>(a, lds, st);
+        default: return launch_search_kernel<1, false>(a, lds, st);
+    }
+}
+hipError_t launch_range_kernel(const UcbArgs& a, unsigned ranges, size_t lds, hipStream_t st) {
+    switch (row_form(a.S)) {
+        case 0: return launch_range_kernel<4, true>(a, ranges, lds, st);
+        case 1: return launch_range_kernel<4, false>(a, ranges, lds, st);
+        case 2: return launch_range_kernel<2, false>(a, ranges, lds, st);
+        default: return launch_range_kernel<1, false>(a, ranges, lds, st);
+    }
+}
+
+}  // namespace
+
 hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st) {
     UcbArgs a = make_ucb_args(b, c);
     const size_t lds = 64 + (size_t)a.Kmax * b.S * 12 + (size_t)a.Kmax * 12;
@@ -296,9 +353,6 @@ hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st) {
         if (!c.gN) return hipErrorInvalidValue;
         // long searches: candidate ranges -> partial tables -> global tables -> scores;
         // in a batch of several searches the short ones get a workgroup each as usual
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ucb_partial),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
         const size_t items = (size_t)b.Ksum * b.S;
         unsigned zb = (unsigned)((items + kThreads - 1) / kThreads);
         if (zb > 4096u) zb = 4096u;
@@ -306,13 +360,14 @@ hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st) {
         hipLaunchKernelGGL(ucb_zero, dim3(zb), dim3(kThreads), 0, st, a);
         if (b.G > 1) {
             a.mixed = 1;
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(ucb_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            const hipError_t e = launch_search_kernel(a, lds, st);
             if (e != hipSuccess) return e;
-            hipLaunchKernelGGL(ucb_kernel, dim3((unsigned)b.G), dim3(kThreads), lds, st, a);
         }
         const unsigned ranges = (unsigned)((b.N + kUcbRange - 1) / kUcbRange);
-        if (ranges) hipLaunchKernelGGL(ucb_partial, dim3(ranges), dim3(kThreads), lds, st, a);
+        if (ranges) {
+            const hipError_t e = launch_range_kernel(a, ranges, lds, st);
+            if (e != hipSuccess) return e;
+        }
         hipLaunchKernelGGL(ucb_final, dim3((unsigned)b.G), dim3(kThreads), 0, st, a);
         return hipGetLastError();
     }
@@ -324,11 +379,7 @@ hipError_t launch_ucb(const kb_batch& b, const UcbCall& c, hipStream_t st) {
                            (size_t)per * kWaves, st, a, per);
         return hipGetLastError();
     }
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ucb_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(ucb_kernel, dim3((unsigned)b.G), dim3(kThreads), lds, st, a);
-    return hipGetLastError();
+    return launch_search_kernel(a, lds, st);
 }
 
 }  // namespace kb
