@@ -113,3 +113,34 @@ def test_multi_workgroup_clustering_over_shapes(kb, D, scorer):
     assert_cent_close(got["cent"][ck], ora.cent[ck], f"D={D}")
     assert_rel_close(got["objective"][clean], ora.objective[clean], what=f"D={D} objective")
     assert got["counts"].sum() == b.N
+
+
+# strategy counts of every row form of the selection kernels: 16-byte pieces in a power
+# of two per row (4, 8), 16-byte pieces otherwise (12, 20, 24), 8-byte pieces (2, 6, 10),
+# single values (1, 5, 7)
+@pytest.mark.parametrize("S", [1, 2, 4, 5, 6, 7, 8, 10, 12, 20, 24])
+def test_selection_over_strategy_counts(kb, S):
+    """The selection step against the oracle for each S: 40 searches of 64-3000 candidates
+    (one workgroup each), one of 20000 behind them (candidate ranges and global tables), and
+    the same 40 alone shortened to at most 200 candidates (a wave each)."""
+    import torch
+    short = synth.config5(G=40, nmin=20, nmax=200, D=8, S=S, iters=2, seed=300 + S)
+    mid = synth.config5(G=40, nmin=64, nmax=3000, D=8, S=S, iters=2, seed=400 + S)
+    both = synth.concat(mid, synth.config2(N=20000, D=8, K=6, S=S, iters=2, seed=500 + S), f"S{S}")
+    for b in (short, mid, both):
+        bound, alive = oracle.prune(b.seg_off, b.flops, b.bytes_, b.peak_flops, b.peak_bw, b.incumbent)
+        cl = oracle.cluster(b.seg_off, b.koff, b.X, 2)
+        d = kb.DeviceBatch(b)
+        d.assign.copy_(torch.from_numpy(cl.assign))
+        d.alive.copy_(torch.from_numpy(alive))
+        d.bound.copy_(torch.from_numpy(bound))
+        d.ucb_select()
+        torch.cuda.synchronize()
+        ora = oracle.ucb_select(b.seg_off, b.koff, b.S, cl.assign, alive, bound, b.visits, b.rsum,
+                                b.t, b.c, b.prior_n, b.prior_mu)
+        np.testing.assert_array_equal(d.host("Ncs"), ora.Ncs, err_msg=f"S={S} {b.name}")
+        assert_rel_close(d.host("mu"), ora.mu, what=f"S={S} mu")
+        assert_rel_close(d.host("ucb"), ora.ucb, what=f"S={S} ucb")
+        ok = ora.near == 0
+        assert ok.sum() >= b.G - 2
+        np.testing.assert_array_equal(d.host("sel")[ok], ora.sel[ok], err_msg=f"S={S} {b.name}")
