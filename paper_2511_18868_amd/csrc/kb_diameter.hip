@@ -445,10 +445,11 @@ hipError_t launch_diameter(const kb_batch& b, const DiameterCall& c, hipStream_t
     a.cnt = c.cnt; a.off = c.off; a.toff = c.toff; a.bsum = c.bsum; a.dmax = reinterpret_cast<unsigned*>(c.diam); a.perm = c.perm;
     const unsigned kblocks = (unsigned)((b.Ksum + kThreads - 1) / kThreads);
     const unsigned ranges = (unsigned)((b.N + kRange - 1) / kRange);
-    // a batch of short searches only: a wave per search, one launch; a batch of several
-    // searches with longer ones among them: the wave kernel after the maxima are zeroed,
-    // then the grouping and the tiles, which leave the short searches out
-    a.mixed = b.Nmax > kDiaShort && b.G > 1;
+    // a batch of short searches only: a wave per search, one launch; a batch of mostly
+    // short searches (256 candidates or fewer on average) with longer ones among them: the
+    // wave kernel after the maxima are zeroed, then the grouping and the tiles, which leave
+    // the short searches out
+    a.mixed = b.Nmax > kDiaShort && b.G > 1 && b.N <= (int64_t)kShortSearch * b.G;
     const size_t wlds = (size_t)kWaves * 4 * (b.Kmax > 0 ? b.Kmax : 1);
     const dim3 wgrid((unsigned)((b.G + kWaves - 1) / kWaves));
     if (b.Nmax <= kDiaShort && b.G > 0) {

@@ -363,10 +363,12 @@ hipError_t launch_geometry(const kb_batch& b, const GeoCall& c, hipStream_t st) 
     a.seg_off = b.seg_off; a.koff = b.koff; a.X = c.X; a.cent = c.cent; a.assign = c.assign;
     a.rep = c.rep; a.radius = c.radius; a.d2 = c.d2; a.gmin = c.gmin; a.gmax = c.gmax;
     if (b.Ksum <= 0) return hipSuccess;
-    // a batch of short searches only: a wave per search, one launch; a batch of several
-    // searches with longer ones among them: the wave kernel after the tables are
-    // initialised, then the range kernels, each skipping the other's searches
-    a.mixed = b.Nmax > kShortSearch && b.G > 1;
+    // a batch of short searches only: a wave per search, one launch; a batch of mostly
+    // short searches (256 candidates or fewer on average) with longer ones among them: the
+    // wave kernel after the tables are initialised, then the range kernels, each skipping
+    // the other's searches.  (Where short searches are the exception the range kernels
+    // take them in passing: on the largest benchmark the extra launch cost more than it saved.)
+    a.mixed = b.Nmax > kShortSearch && b.G > 1 && b.N <= (int64_t)kShortSearch * b.G;
     const size_t wlds = (size_t)(kThreads / kWave) * 20 * a.Kmax;
     const dim3 wgrid((unsigned)((b.G + kThreads / kWave - 1) / (kThreads / kWave)));
     if (wlds > 64 * 1024) return hipErrorInvalidValue;
