@@ -140,6 +140,14 @@ def main():
             run()
             torch.cuda.synchronize()
             modes[name] = round(timed(run, max(3, reps // 2))[0], 4)
+        # ... and the default mode with kb_params.stop_early: searches stop at their first
+        # step without a move (same outputs; not the timed round, which runs every step)
+        ds = kb.make_params(b.peak_flops, b.peak_bw, b.c, b.prior_n, b.prior_mu, b.iters, args.scorer, 1)
+        run = lambda: kb.kb_cluster(d.batch, ds, d.X, None, d.assign, d.cent, d.counts,
+                                    d.objective, d.ws, d.ws_bytes)
+        run()
+        torch.cuda.synchronize()
+        modes["default_stop_early"] = round(timed(run, max(3, reps // 2))[0], 4)
         d.cluster()
 
     # the remaining device-side steps of an iteration of Alg. 1 (not part of the
@@ -271,6 +279,13 @@ def main():
             n = 50 if c <= 3 else 20
             r_mean, r_med = timed(dc.round, n)
             c_mean, _ = timed(dc.cluster, n)
+            dcs = kb.make_params(bc.peak_flops, bc.peak_bw, bc.c, bc.prior_n, bc.prior_mu, bc.iters, 0, 1)
+            stop_run = lambda: kb.kb_cluster(dc.batch, dcs, dc.X, None, dc.assign, dc.cent, dc.counts,
+                                             dc.objective, dc.ws, dc.ws_bytes)
+            stop_run()
+            torch.cuda.synchronize()
+            cs_mean, _ = timed(stop_run, n)
+            dc.cluster()
             # the same round recorded once into a HIP graph and replayed (the library only
             # enqueues kernels, so a call can be captured)
             side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
@@ -281,6 +296,7 @@ def main():
             _, g_med = timed(graph.replay, n)
             e = {"N": bc.N, "G": bc.G, "D": bc.D, "Kmax": bc.Kmax, "S": bc.S, "iters": bc.iters,
                  "round_ms": round(r_med, 4), "cluster_ms": round(c_mean, 4),
+                 "cluster_ms_stop_early": round(cs_mean, 4),
                  "round_ms_graph_replay": round(g_med, 4),
                  "traces_per_s": round(bc.N / (r_med * 1e-3), 1)}
             del graph

@@ -127,6 +127,14 @@ typedef struct {
                        * identical results (doubtful candidates are re-evaluated exactly in
                        * every mode); only speed differs.  kb_cluster_step always runs the
                        * default. */
+    int32_t stop_early; /* 0: every search runs all `iters` Lloyd steps.  1: a search stops at
+                       * its first step in which no candidate changes cluster - such a step
+                       * leaves sums, sizes and centroids as they were, so every later step
+                       * would repeat it and all outputs are the same bytes as with 0.
+                       * Honoured by the kernels that keep a search in one workgroup;
+                       * searches on the multi-workgroup path run all steps either way.
+                       * (Searches of at most 64 candidates and 16 clusters that run one
+                       * wave each always stop there.) */
 } kb_params;
 
 /* kb_params::scorer */

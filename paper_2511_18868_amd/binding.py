@@ -32,7 +32,7 @@ class kb_params(ctypes.Structure):
     _fields_ = [("peak_flops", ctypes.c_float), ("peak_bw", ctypes.c_float),
                 ("c", ctypes.c_float), ("prior_n", ctypes.c_float),
                 ("prior_mu", ctypes.c_float), ("iters", ctypes.c_int32),
-                ("scorer", ctypes.c_int32)]
+                ("scorer", ctypes.c_int32), ("stop_early", ctypes.c_int32)]
 
 
 class kb_round_io(ctypes.Structure):
@@ -148,8 +148,8 @@ KB_SCORER_DEFAULT, KB_SCORER_VECTOR_ALU, KB_SCORER_MATRIX_EVERY = range(3)
 
 
 def make_params(peak_flops=2.5e15, peak_bw=8e12, c=2.0, prior_n=0.0, prior_mu=0.5,
-                iters=1, scorer=KB_SCORER_DEFAULT) -> kb_params:
-    return kb_params(peak_flops, peak_bw, c, prior_n, prior_mu, iters, scorer)
+                iters=1, scorer=KB_SCORER_DEFAULT, stop_early=0) -> kb_params:
+    return kb_params(peak_flops, peak_bw, c, prior_n, prior_mu, iters, scorer, stop_early)
 
 
 def kb_workspace_bytes(batch: kb_batch, params: Optional[kb_params] = None) -> int:
@@ -283,7 +283,7 @@ class DeviceBatch:
     GPU and allocates every output and the workspace.  Holds the kb_batch /
     kb_params / kb_round_io structs that point into those tensors."""
 
-    def __init__(self, b, device="cuda:0", iters=None, scorer=KB_SCORER_DEFAULT):
+    def __init__(self, b, device="cuda:0", iters=None, scorer=KB_SCORER_DEFAULT, stop_early=0):
         import numpy as np
         import torch
         self.torch = torch
@@ -321,7 +321,7 @@ class DeviceBatch:
         self.nvalid = z((G,), torch.int32)
         self.batch = make_batch(G, D, S, N, b.Kmax, Ksum, b.Nmax, self.seg_off, self.koff)
         self.params = make_params(b.peak_flops, b.peak_bw, b.c, b.prior_n, b.prior_mu,
-                                  b.iters if iters is None else iters, scorer)
+                                  b.iters if iters is None else iters, scorer, stop_early)
         self.ws_bytes = kb_workspace_bytes(self.batch, self.params)
         self.ws = z((max(self.ws_bytes, 256),), torch.uint8)
         self.io = kb_round_io(*[_ptr(x) for x in (

@@ -126,10 +126,11 @@ static kb_status check_cluster(const kb_batch* b, const float* X, const float* c
 }
 
 static kb_status do_cluster(const kb_batch* b, const float* X, const float* cent_init,
-                            int32_t iters, int scorer, int32_t* assign, float* cent,
+                            int32_t iters, int scorer, int stop_early, int32_t* assign, float* cent,
                             int32_t* counts, float* objective, void* ws, hipStream_t st,
                             bool reclustering = false, bool* ordered = nullptr) {
     if (scorer < KB_SCORER_DEFAULT || scorer > KB_SCORER_MATRIX_EVERY) return KB_EINVAL;
+    if (stop_early != 0 && stop_early != 1) return KB_EINVAL;
     // (a re-clustering may continue from the centroids it overwrites: every kernel
     // reads a search's initial centroids before it writes that search's new ones)
     kb_status s = check_cluster(b, X, reclustering ? nullptr : cent_init, iters, assign, cent,
@@ -155,6 +156,7 @@ static kb_status do_cluster(const kb_batch* b, const float* X, const float* cent
     c.lim = (float*)(base + w.geo_d2);      // (the representative pass uses this array at other times)
     c.split = (void*)(base + w.split); c.max_tiles = (int64_t)w.max_tiles;
     c.scorer = scorer;
+    c.stop_early = stop_early;
     c.guard = reclustering ? 1 : 0;
     c.mixed = 0;
     if (!w.use_big) return dev(launch_cluster(*b, c, st));
@@ -294,7 +296,7 @@ kb_status kb_cluster_step(const kb_batch* batch, const float* X, const float* ce
     if (!cent_in) return KB_EINVAL;
     s = check_ws(batch, ws, ws_bytes);
     if (s != KB_OK) return s;
-    return do_cluster(batch, X, cent_in, 1, KB_SCORER_DEFAULT, assign, cent_out, counts, objective, ws,
+    return do_cluster(batch, X, cent_in, 1, KB_SCORER_DEFAULT, 0, assign, cent_out, counts, objective, ws,
                       (hipStream_t)stream);
 }
 
@@ -306,7 +308,7 @@ kb_status kb_cluster(const kb_batch* batch, const kb_params* params, const float
     if (!params) return KB_EINVAL;
     s = check_ws(batch, ws, ws_bytes);
     if (s != KB_OK) return s;
-    return do_cluster(batch, X, cent_init, params->iters, params->scorer, assign, cent, counts,
+    return do_cluster(batch, X, cent_init, params->iters, params->scorer, params->stop_early, assign, cent, counts,
                       objective, ws,
                       (hipStream_t)stream);
 }
@@ -520,6 +522,7 @@ kb_status kb_round(const kb_batch* batch, const kb_params* params, const kb_roun
     if (!params || !io) return KB_EINVAL;
     if (params->iters < 1) return KB_EINVAL;
     if (params->scorer < KB_SCORER_DEFAULT || params->scorer > KB_SCORER_MATRIX_EVERY) return KB_EINVAL;
+    if (params->stop_early != 0 && params->stop_early != 1) return KB_EINVAL;
     if (!io->bound) return KB_EINVAL;
     s = check_ws(batch, ws, ws_bytes);
     if (s != KB_OK) return s;
@@ -547,7 +550,7 @@ kb_status kb_round(const kb_batch* batch, const kb_params* params, const kb_roun
     }
     s = do_prune(batch, params, io->flops, io->bytes, io->incumbent, io->bound, io->alive, st);
     if (s != KB_OK) return s;
-    s = do_cluster(batch, io->X, nullptr, params->iters, params->scorer, io->assign, io->cent,
+    s = do_cluster(batch, io->X, nullptr, params->iters, params->scorer, params->stop_early, io->assign, io->cent,
                    io->counts, io->objective, ws, st);
     if (s != KB_OK) return s;
     return do_ucb(batch, params, io->assign, io->alive, io->bound, io->visits, io->rsum, io->t,
@@ -571,6 +574,7 @@ kb_status kb_iterate(const kb_batch* batch, const kb_params* params, const kb_it
     const bool recluster = ip->tau_recluster > 0;
     if (recluster && params->iters < 1) return KB_EINVAL;
     if (params->scorer < KB_SCORER_DEFAULT || params->scorer > KB_SCORER_MATRIX_EVERY) return KB_EINVAL;
+    if (params->stop_early != 0 && params->stop_early != 1) return KB_EINVAL;
     s = check_ws(batch, ws, ws_bytes);
     if (s != KB_OK) return s;
     // validate every stage before enqueueing anything
@@ -604,7 +608,7 @@ kb_status kb_iterate(const kb_batch* batch, const kb_params* params, const kb_it
             // K-Means on the frontier wherever |P| >= 2K, then the cluster representatives
             // and the mask their hardware signatures give (Alg. 1; Eq. 5)
             s = do_cluster(batch, io->X, ip->warm_start ? io->cent : nullptr, params->iters,
-                           params->scorer, io->assign, io->cent, io->counts, io->objective, ws, st,
+                           params->scorer, params->stop_early, io->assign, io->cent, io->counts, io->objective, ws, st,
                            true, &ordered);
             if (s != KB_OK) return s;
             have_order = have_order || ordered;
@@ -657,6 +661,6 @@ const char* kb_status_str(kb_status status) {
     return "KB_E?: unknown status";
 }
 
-const char* kb_version(void) { return "0.5"; }
+const char* kb_version(void) { return "0.6"; }
 
 }  // extern "C"

@@ -1841,7 +1841,7 @@ static ClusterArgs cluster_args(const kb_batch& b, const ClusterCall& c) {
     ClusterArgs a;
     a.G = b.G; a.D = b.D; a.Ksum = b.Ksum; a.Kmax = one_wg_kmax(b); a.N = b.N;
     a.seg_off = b.seg_off; a.koff = b.koff; a.X = c.X; a.cent_init = c.cent_init;
-    a.iters = c.iters; a.early_exit = 0; a.assign = c.assign; a.cent_out = c.cent_out;
+    a.iters = c.iters; a.early_exit = c.stop_early ? 1 : 0; a.assign = c.assign; a.cent_out = c.cent_out;
     a.counts = c.counts; a.objective = c.objective; a.a_new = c.a_new;
     a.order = b.G > 1 ? c.order : nullptr;       // (one search: the order is the identity and was not computed)
     a.use_bounds = c.scorer != 2;

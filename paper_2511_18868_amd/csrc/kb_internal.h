@@ -105,6 +105,7 @@ struct ClusterCall {
     int guard;                // 1: searches with N_g < 2 K_g keep their clustering untouched
     int mixed;                // 1: the batch may hold searches of both paths; each kernel skips the other's
     int scorer;               // kb_params::scorer: 0 default, 1 vector ALU only, 2 matrix cores without bounds
+    int stop_early;           // kb_params::stop_early (one-workgroup kernels only)
 };
 hipError_t launch_cluster(const kb_batch& b, const ClusterCall& c, hipStream_t st);
 hipError_t launch_cluster_big(const kb_batch& b, const ClusterCall& c, const BigWs& w, char* ws,

@@ -33,7 +33,8 @@ def test_exports_every_declared_symbol(L):
 
 def test_struct_layout_matches_header():
     assert ctypes.sizeof(kb.kb_batch) == 56
-    assert ctypes.sizeof(kb.kb_params) == 28 and kb.kb_params.scorer.offset == 24
+    assert ctypes.sizeof(kb.kb_params) == 32 and kb.kb_params.scorer.offset == 24
+    assert kb.kb_params.stop_early.offset == 28
     assert ctypes.sizeof(kb.kb_round_io) == 17 * 8
     assert kb.kb_batch.N.offset == 16 and kb.kb_batch.seg_off.offset == 40
 
@@ -94,6 +95,9 @@ def test_cluster_argument_errors(L):
                          check=False) == kb.KB_EINVAL
     assert kb.kb_cluster(b, kb.make_params(iters=-1), FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE,
                          big, stream=0, check=False) == kb.KB_EINVAL
+    # stop_early is 0 or 1
+    assert kb.kb_cluster(b, kb.make_params(iters=3, stop_early=2), FAKE, None, FAKE, FAKE, FAKE, FAKE,
+                         FAKE, big, stream=0, check=False) == kb.KB_EINVAL
     assert kb.kb_cluster(b, p, FAKE, 0x2000, FAKE, 0x2000 + 16, FAKE, FAKE, FAKE, big, stream=0,
                          check=False) == kb.KB_EINVAL
     assert kb.kb_cluster_step(b, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, big, stream=0,

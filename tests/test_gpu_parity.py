@@ -415,6 +415,28 @@ def test_round_in_one_launch_equals_the_three_stages(kb):
         assert 0 < one.host("alive").sum() < b.N          # (the mask prunes)
 
 
+def test_stopping_at_the_fixed_point_changes_nothing(kb, scorer):
+    """kb_params.stop_early: a search stops at its first Lloyd step without a move.  Such a
+    step leaves sums, sizes and centroids as they were, so the outputs must be the same
+    bytes as after all `iters` steps - on searches that converge long before (short ones,
+    60 steps) and on searches that do not, in every scorer mode and in both workgroup
+    shapes; the multi-workgroup path runs all steps either way."""
+    cases = [synth.config5(G=40, nmin=64, nmax=400, D=16, S=4, iters=60, seed=31),            # 768 threads
+             synth.config5(G=300, nmin=64, nmax=1500, D=32, S=4, iters=25, seed=32),          # 256 threads
+             synth.config1(),
+             synth.config5(G=3, nmin=1500, nmax=3000, kcap=128, D=40, S=4, iters=4, seed=33)]  # multi-workgroup
+    for b in cases:
+        out = []
+        for stop in (0, 1):
+            d = kb.DeviceBatch(b, scorer=scorer, stop_early=stop)
+            d.round()
+            _sync()
+            out.append({k: d.host(k).copy() for k in ("assign", "cent", "counts", "objective", "sel", "ucb")})
+        for k in out[0]:
+            np.testing.assert_array_equal(out[0][k].view(np.uint8), out[1][k].view(np.uint8),
+                                          err_msg=f"{b.name}: {k}")
+
+
 def test_features_of_different_magnitude(kb):
     """One fixed-point grid per search serves every feature: columns a few thousand
     times smaller than the largest one still give centroids good to fp32 rounding
