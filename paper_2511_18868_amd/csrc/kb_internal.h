@@ -11,7 +11,7 @@ constexpr int kWave = 64;
 constexpr int kGeoRange = 2048;      // candidates per workgroup of the representative / radius pass
 constexpr int kSampleRange = 4096;   // candidates per workgroup of the in-cluster draw
 constexpr int kShortSearch = 256;    // a batch whose longest search has at most this many candidates runs
-                                     // the representative pass and the draw one wave per search
+                                     // the selection and the representative pass one wave per search
 constexpr int kTilesPerChunk = 64;   // tiles of 32 candidates per workgroup of the multi-workgroup clustering path
 
 // ---- workspace layout (all offsets 256-byte aligned) ------------------------

@@ -25,6 +25,18 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kNone = 0x7fffffff;
+// Searches of at most short_n candidates are drawn by one wave each (sample_wave).  In a
+// batch of many searches (1024 candidates or fewer on average, so that a range of the
+// range kernels holds several) that is 4096: a lane then walks up to 64 candidates,
+// reading 4 bytes of each and a little more of the chosen cluster's members.  Measured:
+// 1024 searches of 512 candidates 36 -> 12 us, the largest benchmark (64-4096) 41 -> 23
+// us against the range kernels; at 16384 a batch of 64 searches of that length went 27 ->
+// 198 us.  In a batch of few long searches a wave per search is the slower way (8
+// searches of 4000: 27 -> 44 us) and the limit stays at kShortSearch.
+constexpr int kSampleShortMany = 4096;
+static int sample_short(const kb_batch& b) {
+    return b.N <= (int64_t)1024 * b.G ? kSampleShortMany : kShortSearch;
+}
 
 struct SampleArgs {
     int G, Ksum;
@@ -46,7 +58,8 @@ struct SampleArgs {
     int32_t* ksel;             // [G]
     double* slot_key;          // [2 * ranges]  left slot of range r at 2r, right slot at 2r+1
     int32_t* slot_idx;         // [2 * ranges]
-    int mixed;                 // 1: searches of at most kShortSearch candidates go to sample_wave, longer
+    int short_n;               // sample_short() of the batch
+    int mixed;                 // 1: searches of at most short_n candidates go to sample_wave, longer
                                //    ones to the range kernels, in the same call
 };
 
@@ -84,14 +97,14 @@ __global__ void __launch_bounds__(kThreads) sample_range(SampleArgs a) {
         if ((int64_t)a.seg_off[mid] <= r0) lo = mid; else hi = mid;
     }
     const auto mine = [&](int n0, int ng, int k0, int K) {
-        return n0 >= r1 || (ng > 0 && !(a.mixed && ng <= kShortSearch));
+        return n0 >= r1 || (ng > 0 && !(a.mixed && ng <= a.short_n));
     };
     for (int g = lo; (g = next_search(a.seg_off, a.koff, g, a.G, a.N, a.Ksum, mine)) < a.G; ++g) {
         int n0, ng, k0, K;
         search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
         if (n0 >= r1) break;
         if (ng <= 0) continue;
-        if (a.mixed && ng <= kShortSearch) continue;      // (uniform) a wave of sample_wave takes this search
+        if (a.mixed && ng <= a.short_n) continue;      // (uniform) a wave of sample_wave takes this search
         const int n1 = n0 + ng;
         const int q0 = r0 > n0 ? (int)r0 : n0;
         const int q1 = r1 < n1 ? (int)r1 : n1;
@@ -159,7 +172,7 @@ __global__ void __launch_bounds__(kThreads) sample_final(SampleArgs a) {
     int n0, ng, k0, K;
     search_bounds(a.seg_off, a.koff, g, a.N, a.Ksum, n0, ng, k0, K);
     if (ng <= 0) { a.ksel[g] = -1; return; }
-    if (a.mixed && ng <= kShortSearch) return;
+    if (a.mixed && ng <= a.short_n) return;
     const int rf = n0 / kSampleRange, rl = (n0 + ng - 1) / kSampleRange;
     if (rf == rl) return;
     double bk = a.slot_key[2 * (size_t)rf + 1];
@@ -186,7 +199,7 @@ __global__ void __launch_bounds__(kThreads) sample_wave(SampleArgs a) {
         if (lane == 0) a.ksel[g] = -1;
         return;
     }
-    if (a.mixed && ng > kShortSearch) return;         // the range kernels take this search
+    if (a.mixed && ng > a.short_n) return;         // the range kernels take this search
     const int I = a.sel[(size_t)g * 3];
     double bk = 0.0;
     int bi = kNone;
@@ -229,11 +242,10 @@ hipError_t launch_sample(const kb_batch& b, const SampleCall& c, hipStream_t st)
     a.ksel = c.ksel; a.slot_key = c.slot_key; a.slot_idx = c.slot_idx;
     // a batch of short searches only: a wave per search, one launch; a batch of several
     // searches with longer ones among them: both kernels, each skipping the other's searches
-    // (also where short searches are the exception: on the largest benchmark, a third of
-    // whose searches are short, the two launches took 45 us against 60 us for the range
-    // kernels alone)
-    a.mixed = b.Nmax > kShortSearch && b.G > 1;
-    if ((b.Nmax <= kShortSearch || a.mixed) && b.G > 0) {
+    // (an empty launch of the other kernel costs a few microseconds)
+    a.short_n = sample_short(b);
+    a.mixed = b.Nmax > a.short_n && b.G > 1;
+    if ((b.Nmax <= a.short_n || a.mixed) && b.G > 0) {
         hipLaunchKernelGGL(sample_wave, dim3((unsigned)((b.G + kWaves - 1) / kWaves)), dim3(kThreads), 0, st, a);
         if (!a.mixed) return hipGetLastError();
     }
