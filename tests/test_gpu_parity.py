@@ -85,6 +85,12 @@ SMALL = {
     # have no more than 64 clusters, the short ones the one-workgroup kernel
     "fewlong": lambda: synth.concat(synth.config5(G=2, nmin=30000, nmax=30100, D=16, S=4, iters=5, seed=13),
                                     synth.config5(G=6, nmin=300, nmax=900, D=16, S=4, iters=5, seed=14), "fewlong"),
+    # mostly searches of the paper's size with twenty longer ones among them (up to 300
+    # candidates and 24 clusters): the whole batch takes the one-workgroup kernel
+    "tinymix": lambda: synth.concat(
+        synth.concat(synth.config5(G=200, nmin=12, nmax=41, D=12, S=4, iters=8, kcap=3, kdiv=4, seed=41),
+                     synth.config5(G=20, nmin=70, nmax=300, D=12, S=4, iters=8, kcap=24, kdiv=6, seed=42)),
+        synth.config5(G=200, nmin=1, nmax=64, D=12, S=4, iters=8, kcap=16, kdiv=4, seed=43), "tinymix"),
     # shapes that take the multi-workgroup clustering path (more than 64 clusters,
     # or a search of more than 65536 candidates)
     "cfg4s": lambda: synth.config4(N=8192, K=256, ncentres=256),
